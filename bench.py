@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the policy forward pass on one MI355X.
+
+A step is one pass of the whole hot path (features, both message-passing sweeps, pooling,
+policy head) over one batch of synthetic graphs, called through the C ABI with all inputs
+resident in HBM.  Each step uses a different pre-generated episode state (placement,
+current node, visited flags).  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload nasnet]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+N_STATES = 8
+CPU_SAMPLE_GRAPHS = {"random32": 1, "layered200": 64, "inception": 128, "nmt": 64, "nasnet": 32}
+
+
+def sweep_algorithmic_bytes(n_tot: int, e_tot: int, H: int) -> int:
+    """Bytes one sweep launch (both directions) must move: per node and direction the state
+    is read and written once and its message written once (3 x 4H), every edge's message is
+    read once (4H), plus the bucket order, CSR offsets and neighbour ids."""
+    return 2 * n_tot * (12 * H + 8) + 2 * e_tot * (4 * H + 4)
+
+
+def path_algorithmic_bytes(n_tot: int, e_tot: int, H: int) -> int:
+    """The whole path: the sweeps, one write of x (2 x 4H), one read of [td;bu] in pooling
+    (8H), raw features, placement and flags."""
+    return sweep_algorithmic_bytes(n_tot, e_tot, H) + n_tot * (16 * H + 12 + 4 + 2)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="nasnet")
+    ap.add_argument("--batch", type=int, default=None, help="override the number of graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the path shards over the batch of "
+              "independent graphs and no multi-GPU figure is produced (--gpus must be 1).",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_1906_08879_amd as pl
+    from workloads import make_workload, make_states
+
+    if not os.path.exists(pl.library_path()):
+        from paper_1906_08879_amd.build import build
+        build()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        return 3
+    dev = torch.device("cuda:0")
+
+    w = make_workload(args.workload, B=args.batch)
+    placement, cur, done = make_states(w, N_STATES)
+    g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+    wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+    feats = []
+    for s in range(N_STATES):
+        f = np.array(w.node_feats, dtype=np.float32, copy=True)
+        f[:, 2] = done[s]
+        feats.append(torch.from_numpy(f).to(dev))
+    t_place = [torch.from_numpy(placement[s]).to(dev) for s in range(N_STATES)]
+    t_cur = [torch.from_numpy(cur[s]).to(dev) for s in range(N_STATES)]
+    logits = torch.empty((w.B, w.D), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        s = i % N_STATES
+        pl.embed_forward(g, feats[s], t_place[s], t_cur[s], wt, logits, stream=stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    g.profile_enable(True)
+    g.profile_read(reset=True)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    stages = g.profile_read(reset=True)
+    g.profile_enable(False)
+    assert torch.isfinite(logits).all(), "non-finite logits in the timed run"
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    steps_per_s = w.B * args.steps / elapsed
+    stage_ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in stages.items()}
+    sweep_ms, sweep_launches = stages["sweep"]
+    launches_per_step = max(1, w.k_sweeps)
+    avg_launch_ms = sweep_ms / max(1, sweep_launches) / launches_per_step
+    alg = sweep_algorithmic_bytes(w.n_tot, w.e_tot, w.H)
+    achieved = alg / (avg_launch_ms * 1e-3) / 1e9 if avg_launch_ms > 0 else 0.0
+    roofline = {"kernel": "sweep (message passing, both directions)", "bound": "hbm",
+                "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                "algorithmic_bytes_per_launch": alg, "avg_launch_ms": round(avg_launch_ms, 5),
+                "path_algorithmic_bytes_per_step": path_algorithmic_bytes(w.n_tot, w.e_tot, w.H),
+                "path_frac": round(path_algorithmic_bytes(w.n_tot, w.e_tot, w.H)
+                                   / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 5)}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        n_s = min(w.B, CPU_SAMPLE_GRAPHS.get(args.workload, 32))
+        ws = make_workload(args.workload, B=n_s)
+        threads = min(16, os.cpu_count() or 1)
+        oracle.load()
+        t0 = time.perf_counter()
+        oracle.forward_workload(ws, n_threads=threads, want_emb=False)
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": round(n_s / dt, 3), "unit": "graph-steps/s", "cores": threads,
+                        "kind": "oracle",
+                        "sample": f"one forward of the first {n_s} graphs of '{args.workload}' "
+                                  f"({int(ws.n_tot)} nodes), float64 C oracle, {dt:.2f} s wall",
+                        "node_embeddings_per_s": round(ws.n_tot / dt, 1)}
+
+    out = {
+        "metric": "policy forward steps/sec (graphs x steps)",
+        "value": round(steps_per_s, 2), "unit": "graph-steps/s",
+        "node_embeddings_per_s": round(w.n_tot * args.steps / elapsed, 1),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if w.weight_dtype == "fp32" else "f32 (bf16 weights)",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "B": int(w.B), "N_tot": int(w.n_tot),
+                   "E_tot": int(w.e_tot), "D": w.D, "H": w.H, "n_layers": w.n_layers,
+                   "k_sweeps": w.k_sweeps, "max_depth": int(g.max_depth),
+                   "weight_dtype": w.weight_dtype, "states": N_STATES},
+        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out))
+    g.close()
+    wt.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,157 @@
+/*
+ * placeto.h — C ABI of the MI355X (gfx950) library for Placeto's policy forward pass.
+ *
+ * The library evaluates, for a batch of independent computation graphs, the placement
+ * policy of "Placeto: Learning Generalizable Device Placement Algorithms for Distributed
+ * Machine Learning" (Section 2.2 and Appendix A.7): raw per-node features, two-way
+ * message passing over the DAG, pooling over the current node's parent / child / parallel
+ * sets, and a two-layer policy network with a softmax over devices.  Every step runs in
+ * HIP kernels; there is no CPU fallback.
+ *
+ * General rules
+ *   - Every function returns PL_OK (0) or a negative pl_status; no exception crosses the
+ *     boundary.  pl_last_error() gives a thread-local message for the last failure.
+ *   - "host" pointers are ordinary process memory; "dev" pointers are HIP device memory on
+ *     the current device.  The library never frees or keeps caller memory.
+ *   - Handles are created and destroyed by the library and are bound to the device that
+ *     was current when they were first used by a device call.
+ *   - A forward call is asynchronous on the given stream.  Two calls that use the same
+ *     pl_graph_batch must not overlap in time: the batch owns the intermediate buffers.
+ */
+#ifndef PLACETO_H
+#define PLACETO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PL_OK = 0,
+    PL_ERR_NULL = -1,       /* a required pointer is NULL                               */
+    PL_ERR_SHAPE = -2,      /* a size or configuration value is out of the supported range */
+    PL_ERR_RANGE = -3,      /* a node id, device id or edge endpoint is out of range    */
+    PL_ERR_SELF_LOOP = -4,  /* an edge (v, v)                                           */
+    PL_ERR_DUP_EDGE = -5,   /* the same (src, dst) pair twice in one graph              */
+    PL_ERR_CYCLE = -6,      /* the graph is not acyclic                                 */
+    PL_ERR_HIP = -7,        /* a HIP runtime call failed (message has the HIP error)    */
+    PL_ERR_NOMEM = -8       /* host allocation failed                                   */
+} pl_status;
+
+/* Network configuration.  Appendix A.7: the message-passing and aggregation networks are
+ * feed-forward with ReLU; the policy head has two layers and a softmax output. */
+typedef struct {
+    int32_t D;               /* number of devices, 1..16                                 */
+    int32_t H;               /* embedding width, 1..256                                  */
+    int32_t n_layers;        /* layers in each of f, g, l_i, h_i; 1..4 (the paper uses 1) */
+    int32_t k_sweeps;        /* repetitions of the message passing (Section 2.2 step 2), 0..8 */
+    int32_t group_by_device; /* 1: pool per (set, device); 0: per set only, as printed   */
+    int32_t weight_dtype;    /* PL_WEIGHTS_FP32 or PL_WEIGHTS_BF16                       */
+} pl_model_cfg;
+
+enum { PL_WEIGHTS_FP32 = 0, PL_WEIGHTS_BF16 = 1 };
+
+typedef struct pl_graph_batch pl_graph_batch;  /* opaque: CSR, levels, buckets, buffers */
+typedef struct pl_weights pl_weights;          /* opaque: device copy of the parameters */
+
+/* ---- graphs (Section 2: a DAG G(V,E) of op groups; an op receives tensors from its
+ * parents).  All arguments are host memory.
+ *   B          number of graphs (0 is allowed and gives an empty batch)
+ *   n_nodes    [B]  nodes per graph, each >= 1
+ *   n_edges    [B]  edges per graph, each >= 0
+ *   edge_src, edge_dst  [sum n_edges]  concatenated in batch order, graph-local node ids;
+ *              dst consumes src's output, so src is a PARENT of dst.  Edge order is free.
+ * The grouped graph of the paper is a simple DAG: self loops, repeated edges and cycles
+ * are refused (PL_ERR_SELF_LOOP / PL_ERR_DUP_EDGE / PL_ERR_CYCLE), endpoints outside
+ * [0, n_nodes[b]) give PL_ERR_RANGE.  Builds, on the host: parent and child CSR (neighbour
+ * lists ascending by id), longest-path levels from the roots (td) and from the leaves
+ * (bu), and level buckets ordered by (level, node id).  Device copies are made on first
+ * use by a device call.  *out is owned by the library until pl_graph_batch_destroy. */
+int pl_graph_batch_create(int32_t B, const int32_t *n_nodes, const int32_t *n_edges,
+                          const int32_t *edge_src, const int32_t *edge_dst,
+                          pl_graph_batch **out);
+int pl_graph_batch_destroy(pl_graph_batch *g);   /* NULL is accepted */
+
+/* Sizes of a batch: any output pointer may be NULL.  max_depth = largest number of levels
+ * of any graph in the batch. */
+int pl_graph_batch_info(const pl_graph_batch *g, int32_t *B, int64_t *n_tot, int64_t *e_tot,
+                        int32_t *max_depth);
+
+/* Levels of every node, host arrays [N_tot] in batch order.  td_level(v) = 0 for a node
+ * without parents, else 1 + max over parents; bu_level symmetric over children. */
+int pl_graph_batch_levels(const pl_graph_batch *g, int32_t *td_level, int32_t *bu_level);
+
+/* The host-side layout, for inspection and tests.  Any pointer may be NULL.
+ *   par_ptr, chi_ptr   [N_tot + 1]  offsets into par_idx / chi_idx (batch-wide)
+ *   par_idx, chi_idx   [E_tot]      graph-local neighbour ids, ascending within a node
+ *   td_order, bu_order [N_tot]      graph-local node ids of each graph, sorted by
+ *                                   (level, id); graph b occupies its node range */
+int pl_graph_batch_layout(const pl_graph_batch *g, int64_t *par_ptr, int32_t *par_idx,
+                          int64_t *chi_ptr, int32_t *chi_idx, int32_t *td_order,
+                          int32_t *bu_order);
+
+/* Section 2.2 step 3: the sets of the current node v* of every graph.
+ *   cur_node   dev [B]      graph-local id of v*
+ *   out_class  dev [N_tot]  0 = v*, 1 = S_parents (can reach v*), 2 = S_children
+ *                           (reachable from v*), 3 = S_parallel (neither)
+ * Asynchronous on `stream` (a hipStream_t, NULL = default stream). */
+int pl_node_classes(pl_graph_batch *g, const int32_t *cur_node, uint8_t *out_class,
+                    void *stream);
+
+/* ---- parameters.  The blob holds, for every layer, a row-major [in, out] matrix followed
+ * by `out` biases, in this order: input projection (D+4 -> H); f top-down, g top-down,
+ * f bottom-up, g bottom-up (n_layers x H -> H each); l for the parent, child, parallel
+ * sets (2H -> H, then H -> H); h for the same three (H -> H); policy layer 1
+ * ((2 + 3G) H -> H, G = D or 1) and policy layer 2 (H -> D).
+ * With PL_WEIGHTS_BF16 every matrix is rounded to bfloat16 (nearest even) on upload and
+ * biases stay fp32; accumulation is fp32 in either case. */
+size_t pl_weights_count(const pl_model_cfg *cfg);       /* 0 if cfg is invalid */
+int pl_weights_create(const pl_model_cfg *cfg, const float *host_blob, size_t n_floats,
+                      pl_weights **out);
+int pl_weights_destroy(pl_weights *w);                  /* NULL is accepted */
+
+/* ---- the forward pass (Section 2.2 steps 1-3 + policy head, Appendix A.7).
+ *   node_feats  dev [N_tot, 3] fp32  per node: run time, output size, is-visited flag
+ *                                    (Section 2.1 features 1, 2 and 4)
+ *   placement   dev [N_tot] int32    current device of every node, in [0, D) (feature 3)
+ *   cur_node    dev [B] int32        graph-local id of the node being placed (feature 5)
+ *   out_logits  dev [B, D] fp32      pre-softmax policy outputs
+ * The one-hot device and the is-current flag are derived inside the library.  A device id
+ * outside [0, D) contributes an all-zero one-hot and is pooled nowhere; a cur_node outside
+ * its graph gives NaN logits for that graph; neither writes out of bounds.
+ * The first call on a batch for a given (D, H) allocates the batch's intermediate buffers
+ * (and is therefore not capturable into a HIP graph); later calls only launch kernels. */
+int pl_embed_forward(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                     const int32_t *cur_node, const pl_weights *w, float *out_logits,
+                     void *stream);
+
+/* Same, with optional extra outputs (NULL to skip):
+ *   out_probs     dev [B, D]        softmax of the logits
+ *   out_node_emb  dev [N_tot, 2H]   [top-down ; bottom-up] embedding of every node
+ *   out_pooled    dev [B, 3, G, H]  summed l_i outputs per (set, device group) */
+int pl_embed_forward_ex(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                        const int32_t *cur_node, const pl_weights *w, float *out_logits,
+                        float *out_probs, float *out_node_emb, float *out_pooled,
+                        void *stream);
+
+/* ---- per-stage timing, for benchmarks.  While enabled, forward calls bracket each
+ * kernel stage with HIP events on the caller's stream.  pl_profile_read synchronises those
+ * events and returns, per stage, the summed milliseconds and the number of launches since
+ * the last reset.  Stage ids: see pl_stage. */
+typedef enum {
+    PL_STAGE_PROJECT = 0, PL_STAGE_SWEEP = 1, PL_STAGE_POOL = 2, PL_STAGE_HEAD = 3,
+    PL_STAGE_COUNT = 4
+} pl_stage;
+int pl_profile_enable(pl_graph_batch *g, int32_t on);
+int pl_profile_read(pl_graph_batch *g, double *ms_sum /*[PL_STAGE_COUNT]*/,
+                    int64_t *launches /*[PL_STAGE_COUNT]*/, int32_t reset);
+
+const char *pl_last_error(void);
+const char *pl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PLACETO_H */

@@ -1,0 +1,17 @@
+"""MI355X-native policy forward pass of Placeto (arXiv 1906.08879, Section 2.2).
+
+Thin ctypes binding over libplaceto.so; every step of the path runs in HIP kernels.
+Importing this package does not load the library; the first call does, and fails loudly
+if it has not been built (`python -m paper_1906_08879_amd.build`).
+"""
+from .binding import (  # noqa: F401
+    GraphBatch,
+    ModelCfg,
+    PlacetoError,
+    Weights,
+    embed_forward,
+    library_path,
+    load_library,
+    node_classes,
+    weights_count,
+)

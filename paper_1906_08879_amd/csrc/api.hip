@@ -1,0 +1,516 @@
+// C ABI of the library (declared in include/placeto.h): handles, uploads, scratch buffers
+// and the sequence of kernel launches that makes one policy forward pass (Section 2.2
+// steps 1-3 and the policy head of Appendix A.7).
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "internal.h"
+
+namespace pl {
+
+namespace {
+thread_local std::string g_error;
+}
+
+void set_error(const std::string &msg) { g_error = msg; }
+
+int fail(int code, const std::string &msg)
+{
+    g_error = msg;
+    return code;
+}
+
+int hip_fail(hipError_t e, const char *what)
+{
+    g_error = std::string(what) + ": " + hipGetErrorString(e);
+    (void)hipGetLastError();
+    return PL_ERR_HIP;
+}
+
+namespace {
+
+template <typename T>
+int upload(const std::vector<T> &host, T **dev)
+{
+    *dev = nullptr;
+    const size_t bytes = sizeof(T) * (host.empty() ? 1 : host.size());
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(dev), bytes));
+    if (!host.empty())
+        PL_HIP(hipMemcpy(*dev, host.data(), sizeof(T) * host.size(), hipMemcpyHostToDevice));
+    return PL_OK;
+}
+
+struct StageTimer {
+    std::vector<hipEvent_t> ev[PL_STAGE_COUNT];   // start/stop pairs not yet read
+    double ms_sum[PL_STAGE_COUNT] = {0, 0, 0, 0};
+    int64_t launches[PL_STAGE_COUNT] = {0, 0, 0, 0};
+    bool on = false;
+};
+
+}  // namespace
+}  // namespace pl
+
+struct pl_graph_batch {
+    pl::HostLayout host;
+    bool on_device = false;
+    int device = -1;
+    // device arrays
+    int32_t *d_node_off = nullptr, *d_lvl_off = nullptr, *d_node_graph = nullptr;
+    int32_t *d_nbr_ptr[2] = {nullptr, nullptr}, *d_nbr_idx[2] = {nullptr, nullptr};
+    int32_t *d_order[2] = {nullptr, nullptr}, *d_lvl_ptr[2] = {nullptr, nullptr};
+    pl::GraphView view{};
+    pl::Workspace ws;
+    pl::StageTimer timer;
+};
+
+struct pl_weights {
+    pl_model_cfg cfg{};
+    pl::ModelView view{};
+    float *d_blob = nullptr;
+    std::vector<float> host_blob;   // values as stored (bf16-rounded when asked)
+};
+
+namespace pl {
+namespace {
+
+bool cfg_ok(const pl_model_cfg *c)
+{
+    return c && c->D >= 1 && c->D <= kMaxD && c->H >= 1 && c->H <= kMaxH && c->n_layers >= 1 &&
+           c->n_layers <= kMaxLayers && c->k_sweeps >= 0 && c->k_sweeps <= kMaxSweeps &&
+           (c->group_by_device == 0 || c->group_by_device == 1) &&
+           (c->weight_dtype == PL_WEIGHTS_FP32 || c->weight_dtype == PL_WEIGHTS_BF16);
+}
+
+// Lays out the blob: fills every LayerRef and returns the total number of floats.
+size_t plan_weights(const pl_model_cfg &c, ModelView *mv)
+{
+    ModelView m{};
+    m.D = c.D;
+    m.H = c.H;
+    m.L = c.n_layers;
+    m.G = c.group_by_device ? c.D : 1;
+    m.F = c.D + 4;
+    m.Z = (2 + 3 * m.G) * c.H;
+    size_t pos = 0;
+    auto take = [&pos](int n_in, int n_out) {
+        LayerRef r;
+        r.w = static_cast<int32_t>(pos);
+        r.b = static_cast<int32_t>(pos + static_cast<size_t>(n_in) * n_out);
+        r.n_in = n_in;
+        r.n_out = n_out;
+        pos += static_cast<size_t>(n_in) * n_out + n_out;
+        return r;
+    };
+    auto take_mlp = [&](int n_in) {
+        MlpRef r{};
+        for (int l = 0; l < c.n_layers; ++l) r.layer[l] = take(l == 0 ? n_in : c.H, c.H);
+        return r;
+    };
+    m.proj = take(m.F, c.H);
+    m.f[0] = take_mlp(c.H);
+    m.g[0] = take_mlp(c.H);
+    m.f[1] = take_mlp(c.H);
+    m.g[1] = take_mlp(c.H);
+    for (int i = 0; i < 3; ++i) m.l[i] = take_mlp(2 * c.H);
+    for (int i = 0; i < 3; ++i) m.h[i] = take_mlp(c.H);
+    m.pol1 = take(m.Z, c.H);
+    m.pol2 = take(c.H, c.D);
+    if (mv) *mv = m;
+    return pos;
+}
+
+// fp32 -> nearest bfloat16 (ties to even), returned widened back to fp32.
+float round_bf16(float x)
+{
+    uint32_t u;
+    std::memcpy(&u, &x, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u) return x;   // inf / nan unchanged
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    u &= 0xFFFF0000u;
+    std::memcpy(&x, &u, 4);
+    return x;
+}
+
+void round_layer(std::vector<float> &blob, const LayerRef &r)
+{
+    for (int64_t i = 0; i < static_cast<int64_t>(r.n_in) * r.n_out; ++i)
+        blob[r.w + i] = round_bf16(blob[r.w + i]);
+}
+
+int ensure_on_device(pl_graph_batch *g)
+{
+    if (g->on_device) return PL_OK;
+    const HostLayout &L = g->host;
+    PL_HIP(hipGetDevice(&g->device));
+    std::vector<int32_t> node_off(L.node_off.begin(), L.node_off.end());
+    std::vector<int32_t> lvl_off(L.lvl_off.begin(), L.lvl_off.end());
+    std::vector<int32_t> node_graph(L.n_tot);
+    std::vector<int32_t> ptr[2], idx[2], order[2], lvl[2];
+    for (int dir = 0; dir < 2; ++dir) {
+        const auto &hp = dir ? L.chi_ptr : L.par_ptr;
+        const auto &hi = dir ? L.chi_idx : L.par_idx;
+        const auto &ho = dir ? L.bu_order : L.td_order;
+        const auto &hl = dir ? L.bu_lvl_ptr : L.td_lvl_ptr;
+        ptr[dir].assign(hp.begin(), hp.end());
+        idx[dir].resize(L.e_tot);
+        order[dir].resize(L.n_tot);
+        lvl[dir].resize(hl.size());
+        for (int32_t b = 0; b < L.B; ++b) {
+            const int32_t n0 = static_cast<int32_t>(L.node_off[b]);
+            for (int64_t v = L.node_off[b]; v < L.node_off[b + 1]; ++v) {
+                node_graph[v] = b;
+                order[dir][v] = n0 + ho[v];
+                for (int64_t p = hp[v]; p < hp[v + 1]; ++p) idx[dir][p] = n0 + hi[p];
+            }
+            for (int64_t q = L.lvl_off[b]; q < L.lvl_off[b + 1]; ++q) lvl[dir][q] = n0 + hl[q];
+        }
+    }
+    int rc;
+    if ((rc = upload(node_off, &g->d_node_off))) return rc;
+    if ((rc = upload(lvl_off, &g->d_lvl_off))) return rc;
+    if ((rc = upload(node_graph, &g->d_node_graph))) return rc;
+    for (int dir = 0; dir < 2; ++dir) {
+        if ((rc = upload(ptr[dir], &g->d_nbr_ptr[dir]))) return rc;
+        if ((rc = upload(idx[dir], &g->d_nbr_idx[dir]))) return rc;
+        if ((rc = upload(order[dir], &g->d_order[dir]))) return rc;
+        if ((rc = upload(lvl[dir], &g->d_lvl_ptr[dir]))) return rc;
+    }
+    GraphView &v = g->view;
+    v.B = L.B;
+    v.n_tot = static_cast<int32_t>(L.n_tot);
+    v.node_off = g->d_node_off;
+    v.lvl_off = g->d_lvl_off;
+    v.node_graph = g->d_node_graph;
+    for (int dir = 0; dir < 2; ++dir) {
+        v.nbr_ptr[dir] = g->d_nbr_ptr[dir];
+        v.nbr_idx[dir] = g->d_nbr_idx[dir];
+        v.order[dir] = g->d_order[dir];
+        v.lvl_ptr[dir] = g->d_lvl_ptr[dir];
+    }
+    g->on_device = true;
+    return PL_OK;
+}
+
+void free_workspace(Workspace &ws)
+{
+    (void)hipFree(ws.emb);
+    (void)hipFree(ws.msg);
+    (void)hipFree(ws.reach);
+    (void)hipFree(ws.partial);
+    ws = Workspace();
+}
+
+int ensure_reach(pl_graph_batch *g)
+{
+    if (g->ws.reach) return PL_OK;
+    const size_t n = static_cast<size_t>(g->host.n_tot);
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->ws.reach), 2 * n + 16));
+    PL_HIP(hipMemset(g->ws.reach, 0, 2 * n + 16));
+    return PL_OK;
+}
+
+int ensure_workspace(pl_graph_batch *g, const ModelView &mv)
+{
+    Workspace &ws = g->ws;
+    if (ws.emb && ws.H == mv.H && ws.G == mv.G) return PL_OK;
+    uint8_t *keep = ws.reach;
+    ws.reach = nullptr;
+    free_workspace(ws);
+    ws.reach = keep;
+    const size_t n = static_cast<size_t>(g->host.n_tot), H = mv.H;
+    int rc = ensure_reach(g);
+    if (rc) return rc;
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.emb), sizeof(float) * (n * 2 * H + 4)));
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.msg), sizeof(float) * (2 * n * H + 4)));
+    ws.n_chunks = 8;
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.partial),
+                     sizeof(float) * (static_cast<size_t>(g->host.B) * ws.n_chunks * 3 * mv.G * H + 4)));
+    ws.H = mv.H;
+    ws.G = mv.G;
+    return PL_OK;
+}
+
+struct StageScope {
+    StageTimer &t;
+    int stage;
+    hipStream_t s;
+    StageScope(StageTimer &timer, int st, hipStream_t stream) : t(timer), stage(st), s(stream)
+    {
+        if (!t.on) return;
+        hipEvent_t e;
+        if (hipEventCreate(&e) == hipSuccess) {
+            (void)hipEventRecord(e, s);
+            t.ev[stage].push_back(e);
+        }
+    }
+    ~StageScope()
+    {
+        if (!t.on || (t.ev[stage].size() & 1u) == 0) return;
+        hipEvent_t e;
+        if (hipEventCreate(&e) == hipSuccess) {
+            (void)hipEventRecord(e, s);
+            t.ev[stage].push_back(e);
+        } else {
+            (void)hipEventDestroy(t.ev[stage].back());
+            t.ev[stage].pop_back();
+        }
+    }
+};
+
+int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                 const int32_t *cur_node, const pl_weights *w, float *out_logits, float *out_probs,
+                 float *out_node_emb, float *out_pooled, void *stream)
+{
+    if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
+    if (g->host.B == 0) return PL_OK;
+    if (!node_feats || !placement || !cur_node || !out_logits)
+        return fail(PL_ERR_NULL, "node_feats, placement, cur_node and out_logits are required");
+    int rc = ensure_on_device(g);
+    if (rc) return rc;
+    const ModelView &mv = w->view;
+    if ((rc = ensure_workspace(g, mv))) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ForwardArgs fa{node_feats, placement, cur_node, out_logits, out_probs, out_pooled};
+    const GraphView &gv = g->view;
+    {
+        StageScope scope(g->timer, PL_STAGE_PROJECT, s);
+        launch_project(gv, mv, g->ws, fa, s);
+    }
+    {
+        StageScope scope(g->timer, PL_STAGE_SWEEP, s);
+        if (w->cfg.k_sweeps == 0) launch_reach_only(gv, cur_node, g->ws.reach, s);
+        for (int k = 0; k < w->cfg.k_sweeps; ++k)
+            launch_sweep_generic(gv, mv, g->ws, fa, k == 0, s);
+    }
+    {
+        StageScope scope(g->timer, PL_STAGE_POOL, s);
+        launch_pool_generic(gv, mv, g->ws, fa, s);
+    }
+    {
+        StageScope scope(g->timer, PL_STAGE_HEAD, s);
+        launch_head_generic(gv, mv, g->ws, fa, s);
+    }
+    if (out_node_emb)
+        PL_HIP(hipMemcpyAsync(out_node_emb, g->ws.emb,
+                              sizeof(float) * static_cast<size_t>(g->host.n_tot) * 2 * mv.H,
+                              hipMemcpyDeviceToDevice, s));
+    PL_HIP(hipGetLastError());
+    return PL_OK;
+}
+
+}  // namespace
+}  // namespace pl
+
+using namespace pl;
+
+extern "C" {
+
+int pl_graph_batch_create(int32_t B, const int32_t *n_nodes, const int32_t *n_edges,
+                          const int32_t *edge_src, const int32_t *edge_dst, pl_graph_batch **out)
+{
+    if (!out) return fail(PL_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    if (B < 0) return fail(PL_ERR_SHAPE, "B is negative");
+    if (B > 0 && (!n_nodes || !n_edges)) return fail(PL_ERR_NULL, "n_nodes / n_edges are NULL");
+    pl_graph_batch *g = new (std::nothrow) pl_graph_batch();
+    if (!g) return fail(PL_ERR_NOMEM, "out of host memory");
+    int rc;
+    try {
+        rc = build_layout(B, n_nodes, n_edges, edge_src, edge_dst, &g->host);
+    } catch (const std::bad_alloc &) {
+        rc = fail(PL_ERR_NOMEM, "out of host memory");
+    }
+    if (rc) {
+        delete g;
+        return rc;
+    }
+    *out = g;
+    return PL_OK;
+}
+
+int pl_graph_batch_destroy(pl_graph_batch *g)
+{
+    if (!g) return PL_OK;
+    if (g->on_device) {
+        (void)hipFree(g->d_node_off);
+        (void)hipFree(g->d_lvl_off);
+        (void)hipFree(g->d_node_graph);
+        for (int dir = 0; dir < 2; ++dir) {
+            (void)hipFree(g->d_nbr_ptr[dir]);
+            (void)hipFree(g->d_nbr_idx[dir]);
+            (void)hipFree(g->d_order[dir]);
+            (void)hipFree(g->d_lvl_ptr[dir]);
+        }
+    }
+    free_workspace(g->ws);
+    for (auto &v : g->timer.ev)
+        for (hipEvent_t e : v) (void)hipEventDestroy(e);
+    delete g;
+    return PL_OK;
+}
+
+int pl_graph_batch_info(const pl_graph_batch *g, int32_t *B, int64_t *n_tot, int64_t *e_tot,
+                        int32_t *max_depth)
+{
+    if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
+    if (B) *B = g->host.B;
+    if (n_tot) *n_tot = g->host.n_tot;
+    if (e_tot) *e_tot = g->host.e_tot;
+    if (max_depth) *max_depth = g->host.max_depth;
+    return PL_OK;
+}
+
+int pl_graph_batch_levels(const pl_graph_batch *g, int32_t *td_level, int32_t *bu_level)
+{
+    if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
+    const size_t bytes = sizeof(int32_t) * static_cast<size_t>(g->host.n_tot);
+    if (td_level && bytes) std::memcpy(td_level, g->host.td_level.data(), bytes);
+    if (bu_level && bytes) std::memcpy(bu_level, g->host.bu_level.data(), bytes);
+    return PL_OK;
+}
+
+int pl_graph_batch_layout(const pl_graph_batch *g, int64_t *par_ptr, int32_t *par_idx,
+                          int64_t *chi_ptr, int32_t *chi_idx, int32_t *td_order,
+                          int32_t *bu_order)
+{
+    if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
+    const HostLayout &L = g->host;
+    auto copy = [](auto *dst, const auto &src) {
+        if (dst && !src.empty()) std::memcpy(dst, src.data(), sizeof(src[0]) * src.size());
+    };
+    copy(par_ptr, L.par_ptr);
+    copy(par_idx, L.par_idx);
+    copy(chi_ptr, L.chi_ptr);
+    copy(chi_idx, L.chi_idx);
+    copy(td_order, L.td_order);
+    copy(bu_order, L.bu_order);
+    return PL_OK;
+}
+
+int pl_node_classes(pl_graph_batch *g, const int32_t *cur_node, uint8_t *out_class, void *stream)
+{
+    if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
+    if (g->host.B == 0) return PL_OK;
+    if (!cur_node || !out_class) return fail(PL_ERR_NULL, "cur_node / out_class are NULL");
+    int rc = ensure_on_device(g);
+    if (rc) return rc;
+    if ((rc = ensure_reach(g))) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    launch_reach_only(g->view, cur_node, g->ws.reach, s);
+    launch_classes(g->view, cur_node, g->ws.reach, out_class, s);
+    PL_HIP(hipGetLastError());
+    return PL_OK;
+}
+
+size_t pl_weights_count(const pl_model_cfg *cfg)
+{
+    if (!cfg_ok(cfg)) return 0;
+    return plan_weights(*cfg, nullptr);
+}
+
+int pl_weights_create(const pl_model_cfg *cfg, const float *host_blob, size_t n_floats,
+                      pl_weights **out)
+{
+    if (!out) return fail(PL_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    if (!cfg || !host_blob) return fail(PL_ERR_NULL, "cfg / host_blob are NULL");
+    if (!cfg_ok(cfg)) return fail(PL_ERR_SHAPE, "model configuration out of the supported range");
+    pl_weights *w = new (std::nothrow) pl_weights();
+    if (!w) return fail(PL_ERR_NOMEM, "out of host memory");
+    w->cfg = *cfg;
+    const size_t need = plan_weights(*cfg, &w->view);
+    if (n_floats != need) {
+        delete w;
+        return fail(PL_ERR_SHAPE, "weight blob has " + std::to_string(n_floats) + " floats, expected " +
+                                      std::to_string(need));
+    }
+    w->host_blob.assign(host_blob, host_blob + n_floats);
+    if (cfg->weight_dtype == PL_WEIGHTS_BF16) {
+        const ModelView &m = w->view;
+        round_layer(w->host_blob, m.proj);
+        for (int l = 0; l < m.L; ++l) {
+            for (int d = 0; d < 2; ++d) {
+                round_layer(w->host_blob, m.f[d].layer[l]);
+                round_layer(w->host_blob, m.g[d].layer[l]);
+            }
+            for (int i = 0; i < 3; ++i) {
+                round_layer(w->host_blob, m.l[i].layer[l]);
+                round_layer(w->host_blob, m.h[i].layer[l]);
+            }
+        }
+        round_layer(w->host_blob, m.pol1);
+        round_layer(w->host_blob, m.pol2);
+    }
+    int rc = upload(w->host_blob, &w->d_blob);
+    if (rc) {
+        delete w;
+        return rc;
+    }
+    w->view.blob = w->d_blob;
+    *out = w;
+    return PL_OK;
+}
+
+int pl_weights_destroy(pl_weights *w)
+{
+    if (!w) return PL_OK;
+    (void)hipFree(w->d_blob);
+    delete w;
+    return PL_OK;
+}
+
+int pl_embed_forward(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                     const int32_t *cur_node, const pl_weights *w, float *out_logits, void *stream)
+{
+    return forward_impl(g, node_feats, placement, cur_node, w, out_logits, nullptr, nullptr,
+                        nullptr, stream);
+}
+
+int pl_embed_forward_ex(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                        const int32_t *cur_node, const pl_weights *w, float *out_logits,
+                        float *out_probs, float *out_node_emb, float *out_pooled, void *stream)
+{
+    return forward_impl(g, node_feats, placement, cur_node, w, out_logits, out_probs, out_node_emb,
+                        out_pooled, stream);
+}
+
+int pl_profile_enable(pl_graph_batch *g, int32_t on)
+{
+    if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
+    g->timer.on = on != 0;
+    return PL_OK;
+}
+
+int pl_profile_read(pl_graph_batch *g, double *ms_sum, int64_t *launches, int32_t reset)
+{
+    if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
+    StageTimer &t = g->timer;
+    for (int st = 0; st < PL_STAGE_COUNT; ++st) {
+        auto &ev = t.ev[st];
+        for (size_t i = 0; i + 1 < ev.size(); i += 2) {
+            float ms = 0.0f;
+            PL_HIP(hipEventSynchronize(ev[i + 1]));
+            PL_HIP(hipEventElapsedTime(&ms, ev[i], ev[i + 1]));
+            t.ms_sum[st] += ms;
+            t.launches[st] += 1;
+        }
+        for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+        ev.clear();
+        if (ms_sum) ms_sum[st] = t.ms_sum[st];
+        if (launches) launches[st] = t.launches[st];
+        if (reset) {
+            t.ms_sum[st] = 0.0;
+            t.launches[st] = 0;
+        }
+    }
+    return PL_OK;
+}
+
+const char *pl_last_error(void) { return g_error.c_str(); }
+
+const char *pl_version(void) { return "placeto-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

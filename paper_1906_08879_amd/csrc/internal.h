@@ -1,0 +1,124 @@
+// Internal declarations shared by the host layout builder, the C ABI and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "placeto.h"
+
+namespace pl {
+
+constexpr int kMaxD = 16;
+constexpr int kMaxH = 256;
+constexpr int kMaxLayers = 4;
+constexpr int kMaxSweeps = 8;
+
+void set_error(const std::string &msg);
+int fail(int code, const std::string &msg);
+int hip_fail(hipError_t e, const char *what);
+
+#define PL_HIP(call)                                             \
+    do {                                                         \
+        hipError_t e__ = (call);                                 \
+        if (e__ != hipSuccess) return ::pl::hip_fail(e__, #call); \
+    } while (0)
+
+// ---- host-side layout of a batch (Section 2.2 step 2 needs parents and children of every
+// node and an order in which all of a node's neighbours are final before the node).
+struct HostLayout {
+    int32_t B = 0;
+    int64_t n_tot = 0, e_tot = 0;
+    int32_t max_depth = 0;
+    std::vector<int64_t> node_off;   // [B+1]
+    std::vector<int64_t> edge_off;   // [B+1]
+    std::vector<int64_t> par_ptr;    // [n_tot+1] into par_idx
+    std::vector<int64_t> chi_ptr;    // [n_tot+1]
+    std::vector<int32_t> par_idx;    // [e_tot] graph-local ids, ascending per node
+    std::vector<int32_t> chi_idx;    // [e_tot]
+    std::vector<int32_t> td_level;   // [n_tot]
+    std::vector<int32_t> bu_level;   // [n_tot]
+    std::vector<int32_t> td_order;   // [n_tot] graph-local ids by (level, id)
+    std::vector<int32_t> bu_order;   // [n_tot]
+    std::vector<int32_t> depth;      // [B] number of levels (same in both directions)
+    std::vector<int64_t> lvl_off;    // [B+1] offset of graph b's level pointers
+    std::vector<int32_t> td_lvl_ptr; // [lvl_off[B]] per graph depth+1 positions into its order
+    std::vector<int32_t> bu_lvl_ptr; // same for bottom-up
+};
+
+int build_layout(int32_t B, const int32_t *n_nodes, const int32_t *n_edges,
+                 const int32_t *edge_src, const int32_t *edge_dst, HostLayout *out);
+
+// ---- device-side view of a batch, passed to kernels by value
+struct GraphView {
+    int32_t B;
+    int32_t n_tot;
+    const int32_t *node_off;   // [B+1]
+    const int32_t *lvl_off;    // [B+1]
+    // index 0 = top-down (neighbours = parents), 1 = bottom-up (neighbours = children)
+    const int32_t *nbr_ptr[2]; // [n_tot+1]
+    const int32_t *nbr_idx[2]; // [e_tot] GLOBAL node ids
+    const int32_t *order[2];   // [n_tot] GLOBAL node ids by (graph, level, id)
+    const int32_t *lvl_ptr[2]; // per graph depth+1 GLOBAL positions into order
+    const int32_t *node_graph; // [n_tot] graph of each node
+};
+
+// ---- parameters: offsets (in floats) of every layer inside the fp32 device blob
+struct LayerRef {
+    int32_t w;      // offset of the [in,out] matrix
+    int32_t b;      // offset of the bias
+    int32_t n_in;
+    int32_t n_out;
+};
+
+struct MlpRef {
+    LayerRef layer[kMaxLayers];
+};
+
+struct ModelView {
+    int32_t D, H, L, G, Z, F;
+    const float *blob;       // fp32 (bf16-rounded values when the model stores bf16)
+    LayerRef proj;
+    MlpRef f[2], g[2];       // [direction]
+    MlpRef l[3], h[3];       // [set]: parents, children, parallel
+    LayerRef pol1, pol2;
+};
+
+// ---- scratch owned by a batch for one (D, H)
+struct Workspace {
+    float *emb = nullptr;       // [n_tot, 2H]  [td ; bu]
+    float *msg = nullptr;       // [2, n_tot, H]
+    uint8_t *reach = nullptr;   // [2, n_tot]   0: descendant-of-v* bit, 1: ancestor-of-v* bit
+    float *partial = nullptr;   // [B, n_chunks_max, 3G, H] pooling partial sums
+    int32_t *chunk_off = nullptr; // [B+1] first pooling chunk of each graph
+    int32_t n_chunks = 0;
+    int32_t H = 0, G = 0;
+};
+
+// ---- kernel launchers (kernels_generic.hip)
+struct ForwardArgs {
+    const float *node_feats;
+    const int32_t *placement;
+    const int32_t *cur_node;
+    float *out_logits;
+    float *out_probs;
+    float *out_pooled;
+};
+
+constexpr int kPoolChunk = 128;   // nodes per pooling workgroup
+
+void launch_project(const GraphView &gv, const ModelView &mv, const Workspace &ws,
+                    const ForwardArgs &fa, hipStream_t s);
+void launch_sweep_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
+                          const ForwardArgs &fa, bool write_reach, hipStream_t s);
+void launch_reach_only(const GraphView &gv, const int32_t *cur_node, uint8_t *reach,
+                       hipStream_t s);
+void launch_classes(const GraphView &gv, const int32_t *cur_node, const uint8_t *reach,
+                    uint8_t *out_class, hipStream_t s);
+void launch_pool_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
+                         const ForwardArgs &fa, hipStream_t s);
+void launch_head_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
+                         const ForwardArgs &fa, hipStream_t s);
+
+}  // namespace pl

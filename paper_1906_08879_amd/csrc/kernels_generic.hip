@@ -1,0 +1,464 @@
+// Generic fp32 kernels for the policy forward pass: any H <= 256, D <= 16, 1..4 layers.
+// They are the reference-quality HIP path (plain vector FMAs, deterministic summation
+// order) and the fallback for shapes the matrix-core kernels do not cover.
+//
+// Section 2.2 of the paper: (1) raw features, (2) two-way message passing
+// x_v <- g(sum_{u in xi(v)} f(x_u)), (3) pooling h_i(sum_{u in S_i(v)} l_i(x_u)) over the
+// parent / child / parallel sets of the current node, then the policy head (Appendix A.7).
+#include "internal.h"
+
+namespace pl {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTile = 16;   // rows (nodes) pushed through a network together
+
+// y[r][j] = act(bias[j] + sum_k x[r][k] * W[k][j]) for r < rows (rows <= kTile).
+// x and y live in LDS.  Thread (grp, j): column j = tid % n_out, row group grp = tid / n_out;
+// it owns rows grp, grp + groups, ... (at most RPT of them), so one weight load feeds up to
+// RPT FMAs.  Requires n_out <= kThreads and min(kThreads / n_out, kTile) * RPT >= kTile.
+template <int RPT>
+__device__ __forceinline__ void dense_layer(const float *__restrict__ W,
+                                            const float *__restrict__ bias, int n_in, int n_out,
+                                            const float *x, int ldx, float *y, int ldy, int rows,
+                                            bool relu)
+{
+    const int tid = threadIdx.x;
+    int groups = kThreads / n_out;
+    if (groups > kTile) groups = kTile;
+    const int grp = tid / n_out, j = tid - grp * n_out;
+    if (grp >= groups || grp >= rows) return;
+    float acc[RPT];
+    const float bj = bias[j];
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) acc[i] = bj;
+    int xoff[RPT];   // rows past the tile's end re-read its last row (never stored)
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) xoff[i] = min(grp + i * groups, rows - 1) * ldx;
+    for (int k = 0; k < n_in; ++k) {
+        const float w = W[static_cast<size_t>(k) * n_out + j];
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) acc[i] = fmaf(x[xoff[i] + k], w, acc[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        const int r = grp + i * groups;
+        if (r < rows) y[r * ldy + j] = relu ? fmaxf(acc[i], 0.0f) : acc[i];
+    }
+}
+
+// ------------------------------------------------------------------ step 1: features
+// phi_v = [time, size, one-hot(device), is-current, is-visited]; x_v = relu(W^T phi_v + b).
+// Written to both halves of the embedding (the two directions start from the same x).
+__global__ __launch_bounds__(kThreads) void k_project(GraphView gv, ModelView mv,
+                                                      const float *__restrict__ feats,
+                                                      const int32_t *__restrict__ placement,
+                                                      const int32_t *__restrict__ cur_node,
+                                                      float *__restrict__ emb)
+{
+    const int H = mv.H, D = mv.D;
+    const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (idx >= static_cast<size_t>(gv.n_tot) * H) return;
+    const int v = static_cast<int>(idx / H), h = static_cast<int>(idx - static_cast<size_t>(v) * H);
+    const int b = gv.node_graph[v];
+    const float *W = mv.blob + mv.proj.w;
+    float s = mv.blob[mv.proj.b + h];
+    s = fmaf(feats[v * 3 + 0], W[0 * H + h], s);
+    s = fmaf(feats[v * 3 + 1], W[1 * H + h], s);
+    const int dev = placement[v];
+    if (dev >= 0 && dev < D) s += W[(2 + dev) * H + h];
+    if (v - gv.node_off[b] == cur_node[b]) s += W[(2 + D) * H + h];
+    s = fmaf(feats[v * 3 + 2], W[(3 + D) * H + h], s);
+    s = fmaxf(s, 0.0f);
+    emb[static_cast<size_t>(v) * 2 * H + h] = s;
+    emb[static_cast<size_t>(v) * 2 * H + H + h] = s;
+}
+
+// ------------------------------------------------------------------ step 2: one sweep
+// One workgroup per (graph, direction) walks the graph's levels in order; graphs are
+// independent, so no grid-wide barrier is needed.  For every node v of a level:
+//   a_v = sum over neighbours u (parents top-down, children bottom-up) of m_u
+//   s_v <- s_v + g(a_v);  m_v = f(s_v)
+// and, riding along, the reachability bit used for the node sets of step 3:
+//   top-down:  desc(v) = OR over parents p of (p == v* or desc(p))
+//   bottom-up: anc(v)  = OR over children c of (c == v* or anc(c))
+template <int RPT>
+__global__ __launch_bounds__(kThreads) void k_sweep_generic(GraphView gv, ModelView mv,
+                                                            float *__restrict__ emb,
+                                                            float *__restrict__ msg_base,
+                                                            uint8_t *__restrict__ reach_base,
+                                                            const int32_t *__restrict__ cur_node,
+                                                            int write_reach)
+{
+    extern __shared__ float lds[];
+    const int H = mv.H, L = mv.L;
+    const int b = blockIdx.x, dir = blockIdx.y, tid = threadIdx.x;
+    float *buf_a = lds, *buf_b = lds + kTile * H;
+    float *msg = msg_base + static_cast<size_t>(dir) * gv.n_tot * H;
+    uint8_t *reach = reach_base + static_cast<size_t>(dir) * gv.n_tot;
+    const int32_t *order = gv.order[dir];
+    const int32_t *nbr_ptr = gv.nbr_ptr[dir], *nbr_idx = gv.nbr_idx[dir];
+    const int32_t *lvl = gv.lvl_ptr[dir] + gv.lvl_off[b];
+    const int depth = gv.lvl_off[b + 1] - gv.lvl_off[b] - 1;
+    const int n_b = gv.node_off[b + 1] - gv.node_off[b];
+    const int cur_local = cur_node[b];
+    const int cur = (cur_local >= 0 && cur_local < n_b) ? gv.node_off[b] + cur_local : -1;
+    const MlpRef &fn = mv.f[dir], &gn = mv.g[dir];
+
+    for (int level = 0; level < depth; ++level) {
+        const int beg = lvl[level], end = lvl[level + 1];
+        for (int t0 = beg; t0 < end; t0 += kTile) {
+            const int rows = min(kTile, end - t0);
+            for (int i = tid; i < rows * H; i += kThreads) {
+                const int r = i / H, h = i - r * H;
+                const int v = order[t0 + r];
+                float a = 0.0f;
+                for (int p = nbr_ptr[v]; p < nbr_ptr[v + 1]; ++p)
+                    a += msg[static_cast<size_t>(nbr_idx[p]) * H + h];
+                buf_a[i] = a;
+            }
+            if (write_reach && tid < rows) {
+                const int v = order[t0 + tid];
+                int bit = 0;
+                for (int p = nbr_ptr[v]; p < nbr_ptr[v + 1]; ++p) {
+                    const int u = nbr_idx[p];
+                    bit |= (u == cur) | reach[u];
+                }
+                reach[v] = static_cast<uint8_t>(bit);
+            }
+            __syncthreads();
+            float *in = buf_a, *out = buf_b;
+            for (int l = 0; l < L; ++l) {
+                dense_layer<RPT>(mv.blob + gn.layer[l].w, mv.blob + gn.layer[l].b, H, H, in, H,
+                                 out, H, rows, true);
+                __syncthreads();
+                float *t = in; in = out; out = t;
+            }
+            for (int i = tid; i < rows * H; i += kThreads) {
+                const int r = i / H, h = i - r * H;
+                const size_t at = static_cast<size_t>(order[t0 + r]) * 2 * H + dir * H + h;
+                const float s = emb[at] + in[i];
+                emb[at] = s;
+                in[i] = s;
+            }
+            __syncthreads();
+            for (int l = 0; l < L; ++l) {
+                dense_layer<RPT>(mv.blob + fn.layer[l].w, mv.blob + fn.layer[l].b, H, H, in, H,
+                                 out, H, rows, true);
+                __syncthreads();
+                float *t = in; in = out; out = t;
+            }
+            for (int i = tid; i < rows * H; i += kThreads) {
+                const int r = i / H, h = i - r * H;
+                msg[static_cast<size_t>(order[t0 + r]) * H + h] = in[i];
+            }
+            __syncthreads();
+        }
+        // messages of this level are read by later levels of this same workgroup
+        __threadfence_block();
+        __syncthreads();
+    }
+}
+
+// The reachability bits alone (k = 0 sweeps, or when only the node sets are wanted).
+__global__ __launch_bounds__(kThreads) void k_reach_only(GraphView gv,
+                                                         const int32_t *__restrict__ cur_node,
+                                                         uint8_t *__restrict__ reach_base)
+{
+    const int b = blockIdx.x, dir = blockIdx.y, tid = threadIdx.x;
+    uint8_t *reach = reach_base + static_cast<size_t>(dir) * gv.n_tot;
+    const int32_t *order = gv.order[dir];
+    const int32_t *nbr_ptr = gv.nbr_ptr[dir], *nbr_idx = gv.nbr_idx[dir];
+    const int32_t *lvl = gv.lvl_ptr[dir] + gv.lvl_off[b];
+    const int depth = gv.lvl_off[b + 1] - gv.lvl_off[b] - 1;
+    const int n_b = gv.node_off[b + 1] - gv.node_off[b];
+    const int cur_local = cur_node[b];
+    const int cur = (cur_local >= 0 && cur_local < n_b) ? gv.node_off[b] + cur_local : -1;
+    for (int level = 0; level < depth; ++level) {
+        for (int t = lvl[level] + tid; t < lvl[level + 1]; t += kThreads) {
+            const int v = order[t];
+            int bit = 0;
+            for (int p = nbr_ptr[v]; p < nbr_ptr[v + 1]; ++p) {
+                const int u = nbr_idx[p];
+                bit |= (u == cur) | reach[u];
+            }
+            reach[v] = static_cast<uint8_t>(bit);
+        }
+        __threadfence_block();
+        __syncthreads();
+    }
+}
+
+// Section 2.2 step 3: 0 = v*, 1 = can reach v*, 2 = reachable from v*, 3 = neither.
+__device__ __forceinline__ int node_class(int v, int cur, const uint8_t *reach, int n_tot)
+{
+    if (v == cur) return 0;
+    if (reach[static_cast<size_t>(n_tot) + v]) return 1;   // bottom-up bit: ancestor of v*
+    if (reach[v]) return 2;                                // top-down bit: descendant of v*
+    return 3;
+}
+
+__global__ __launch_bounds__(kThreads) void k_classes(GraphView gv,
+                                                      const int32_t *__restrict__ cur_node,
+                                                      const uint8_t *__restrict__ reach,
+                                                      uint8_t *__restrict__ out_class)
+{
+    const int v = blockIdx.x * kThreads + threadIdx.x;
+    if (v >= gv.n_tot) return;
+    const int b = gv.node_graph[v];
+    const int n_b = gv.node_off[b + 1] - gv.node_off[b];
+    const int c = cur_node[b];
+    const int cur = (c >= 0 && c < n_b) ? gv.node_off[b] + c : -1;
+    out_class[v] = static_cast<uint8_t>(node_class(v, cur, reach, gv.n_tot));
+}
+
+// ------------------------------------------------------------------ step 3: pooling
+// Workgroup (chunk c, graph b) handles a contiguous slice of the graph's nodes.  Nodes are
+// bucketed by set (in node order, so the summation order is fixed), pushed through that
+// set's l network in tiles, and summed per (set, device group) into LDS accumulators.
+// Partial sums go to partial[b][c][3G][H]; the head kernel adds the chunks in order.
+constexpr int kSub = 256;   // nodes classified at a time
+
+template <int RPT>
+__global__ __launch_bounds__(kThreads) void k_pool_generic(GraphView gv, ModelView mv,
+                                                           const float *__restrict__ emb,
+                                                           const uint8_t *__restrict__ reach,
+                                                           const int32_t *__restrict__ placement,
+                                                           const int32_t *__restrict__ cur_node,
+                                                           float *__restrict__ partial,
+                                                           int max_chunks)
+{
+    extern __shared__ float lds[];
+    __shared__ int16_t s_list[3][kSub];
+    __shared__ int8_t s_cls[kSub];
+    __shared__ int s_count[3];
+    __shared__ int s_dev[kTile];
+    const int H = mv.H, G = mv.G, D = mv.D, L = mv.L;
+    const int b = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+    const int n0 = gv.node_off[b], n_b = gv.node_off[b + 1] - n0;
+    int chunks = (n_b + kPoolChunk - 1) / kPoolChunk;
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (c >= chunks) return;
+    const int per = (n_b + chunks - 1) / chunks;
+    const int lo = n0 + c * per, hi = min(n0 + n_b, lo + per);
+    const int cl = cur_node[b];
+    const int cur = (cl >= 0 && cl < n_b) ? n0 + cl : -1;
+
+    float *acc = lds;                       // [3G][H]
+    float *buf_x = acc + 3 * G * H;         // [kTile][2H]
+    float *buf_a = buf_x + kTile * 2 * H;   // [kTile][H]
+    float *buf_b = buf_a + kTile * H;       // [kTile][H]
+    for (int i = tid; i < 3 * G * H; i += kThreads) acc[i] = 0.0f;
+
+    for (int s0 = lo; s0 < hi; s0 += kSub) {
+        const int cnt = min(kSub, hi - s0);
+        if (tid < cnt) s_cls[tid] = static_cast<int8_t>(node_class(s0 + tid, cur, reach, gv.n_tot));
+        __syncthreads();
+        if (tid < 3) {
+            int m = 0;
+            for (int i = 0; i < cnt; ++i)
+                if (s_cls[i] == tid + 1) s_list[tid][m++] = static_cast<int16_t>(i);
+            s_count[tid] = m;
+        }
+        __syncthreads();
+        for (int set = 0; set < 3; ++set) {
+            const int m = s_count[set];
+            const MlpRef &ln = mv.l[set];
+            for (int t0 = 0; t0 < m; t0 += kTile) {
+                const int rows = min(kTile, m - t0);
+                for (int i = tid; i < rows * 2 * H; i += kThreads) {
+                    const int r = i / (2 * H), k = i - r * 2 * H;
+                    buf_x[i] = emb[static_cast<size_t>(s0 + s_list[set][t0 + r]) * 2 * H + k];
+                }
+                if (tid < rows) {
+                    const int dev = placement[s0 + s_list[set][t0 + tid]];
+                    s_dev[tid] = (dev >= 0 && dev < D) ? (G == 1 ? 0 : dev) : -1;
+                }
+                __syncthreads();
+                const float *in = buf_x;
+                int n_in = 2 * H;
+                float *out = buf_a;
+                for (int l = 0; l < L; ++l) {
+                    dense_layer<RPT>(mv.blob + ln.layer[l].w, mv.blob + ln.layer[l].b, n_in, H, in,
+                                     n_in, out, H, rows, true);
+                    __syncthreads();
+                    in = out;
+                    n_in = H;
+                    out = (out == buf_a) ? buf_b : buf_a;
+                }
+                if (tid < H) {
+                    for (int r = 0; r < rows; ++r) {
+                        const int dev = s_dev[r];
+                        if (dev >= 0) acc[(set * G + dev) * H + tid] += in[r * H + tid];
+                    }
+                }
+                __syncthreads();
+            }
+        }
+    }
+    float *dst = partial + (static_cast<size_t>(b) * max_chunks + c) * 3 * G * H;
+    for (int i = tid; i < 3 * G * H; i += kThreads) dst[i] = acc[i];
+}
+
+// ------------------------------------------------------------------ policy head
+// One workgroup per graph: P[i][d] = sum of the chunk partials (fixed order);
+// q[i][d] = h_i(P[i][d]) (also for empty groups); z = [e_{v*} ; q]; two-layer policy
+// network with a softmax over devices (Appendix A.7).
+template <int RPT>
+__global__ __launch_bounds__(kThreads) void k_head_generic(GraphView gv, ModelView mv,
+                                                           const float *__restrict__ emb,
+                                                           const float *__restrict__ partial,
+                                                           const int32_t *__restrict__ cur_node,
+                                                           int max_chunks,
+                                                           float *__restrict__ out_logits,
+                                                           float *__restrict__ out_probs,
+                                                           float *__restrict__ out_pooled)
+{
+    extern __shared__ float lds[];
+    const int H = mv.H, G = mv.G, D = mv.D, L = mv.L, Z = mv.Z;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int n0 = gv.node_off[b], n_b = gv.node_off[b + 1] - n0;
+    int chunks = (n_b + kPoolChunk - 1) / kPoolChunk;
+    if (chunks > max_chunks) chunks = max_chunks;
+    const int cl = cur_node[b];
+    const bool cur_ok = (cl >= 0 && cl < n_b);
+
+    float *P = lds;                     // [3G][H]
+    float *z = P + 3 * G * H;           // [Z]
+    float *buf_a = z + Z;               // [kTile][H]
+    float *buf_b = buf_a + kTile * H;   // [kTile][H]
+    const float *src = partial + static_cast<size_t>(b) * max_chunks * 3 * G * H;
+    for (int i = tid; i < 3 * G * H; i += kThreads) {
+        float s = 0.0f;
+        for (int c = 0; c < chunks; ++c) s += src[static_cast<size_t>(c) * 3 * G * H + i];
+        P[i] = s;
+        if (out_pooled) out_pooled[static_cast<size_t>(b) * 3 * G * H + i] = s;
+    }
+    for (int i = tid; i < 2 * H; i += kThreads)
+        z[i] = cur_ok ? emb[static_cast<size_t>(n0 + cl) * 2 * H + i] : 0.0f;
+    __syncthreads();
+    for (int set = 0; set < 3; ++set) {
+        const MlpRef &hn = mv.h[set];
+        const float *in = P + set * G * H;
+        for (int l = 0; l < L; ++l) {
+            float *out = (l == L - 1) ? z + (2 + set * G) * H : ((l & 1) ? buf_b : buf_a);
+            dense_layer<RPT>(mv.blob + hn.layer[l].w, mv.blob + hn.layer[l].b, H, H, in, H, out, H,
+                             G, true);
+            __syncthreads();
+            in = out;
+        }
+    }
+    dense_layer<RPT>(mv.blob + mv.pol1.w, mv.blob + mv.pol1.b, Z, H, z, Z, buf_a, H, 1, true);
+    __syncthreads();
+    dense_layer<RPT>(mv.blob + mv.pol2.w, mv.blob + mv.pol2.b, H, D, buf_a, H, buf_b, D, 1, false);
+    __syncthreads();
+    if (tid == 0) {
+        float mx = buf_b[0];
+        for (int d = 1; d < D; ++d) mx = fmaxf(mx, buf_b[d]);
+        float tot = 0.0f;
+        for (int d = 0; d < D; ++d) tot += expf(buf_b[d] - mx);
+        const float bad = __builtin_nanf("");   // no valid current node: nothing to decide
+        for (int d = 0; d < D; ++d) {
+            out_logits[static_cast<size_t>(b) * D + d] = cur_ok ? buf_b[d] : bad;
+            if (out_probs)
+                out_probs[static_cast<size_t>(b) * D + d] = cur_ok ? expf(buf_b[d] - mx) / tot : bad;
+        }
+    }
+}
+
+int pick_rpt(int H)
+{
+    int groups = kThreads / H;
+    if (groups > kTile) groups = kTile;
+    int rpt = 1;
+    while (groups * rpt < kTile) rpt *= 2;
+    return rpt;
+}
+
+template <typename K>
+void allow_lds(K kernel, size_t bytes)
+{
+    if (bytes > 48 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  static_cast<int>(bytes));
+}
+
+#define PL_DISPATCH_RPT(rpt, CALL) \
+    switch (rpt) {                 \
+        case 1: { CALL(1); break; }  \
+        case 2: { CALL(2); break; }  \
+        case 4: { CALL(4); break; }  \
+        case 8: { CALL(8); break; }  \
+        default: { CALL(16); break; } \
+    }
+
+}  // namespace
+
+void launch_project(const GraphView &gv, const ModelView &mv, const Workspace &ws,
+                    const ForwardArgs &fa, hipStream_t s)
+{
+    const size_t total = static_cast<size_t>(gv.n_tot) * mv.H;
+    if (total == 0) return;
+    const unsigned blocks = static_cast<unsigned>((total + kThreads - 1) / kThreads);
+    hipLaunchKernelGGL(k_project, dim3(blocks), dim3(kThreads), 0, s, gv, mv, fa.node_feats,
+                       fa.placement, fa.cur_node, ws.emb);
+}
+
+void launch_sweep_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
+                          const ForwardArgs &fa, bool write_reach, hipStream_t s)
+{
+    if (gv.B == 0) return;
+    const size_t lds = sizeof(float) * 2 * kTile * mv.H;
+#define CALL(R)                                                                               \
+    allow_lds(k_sweep_generic<R>, lds);                                                       \
+    hipLaunchKernelGGL(k_sweep_generic<R>, dim3(gv.B, 2), dim3(kThreads), lds, s, gv, mv, ws.emb, \
+                       ws.msg, ws.reach, fa.cur_node, write_reach ? 1 : 0)
+    PL_DISPATCH_RPT(pick_rpt(mv.H), CALL)
+#undef CALL
+}
+
+void launch_reach_only(const GraphView &gv, const int32_t *cur_node, uint8_t *reach, hipStream_t s)
+{
+    if (gv.B == 0) return;
+    hipLaunchKernelGGL(k_reach_only, dim3(gv.B, 2), dim3(kThreads), 0, s, gv, cur_node, reach);
+}
+
+void launch_classes(const GraphView &gv, const int32_t *cur_node, const uint8_t *reach,
+                    uint8_t *out_class, hipStream_t s)
+{
+    if (gv.n_tot == 0) return;
+    hipLaunchKernelGGL(k_classes, dim3((gv.n_tot + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
+                       gv, cur_node, reach, out_class);
+}
+
+void launch_pool_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
+                         const ForwardArgs &fa, hipStream_t s)
+{
+    if (gv.B == 0) return;
+    const size_t lds = sizeof(float) * (static_cast<size_t>(3) * mv.G * mv.H + kTile * 4 * mv.H);
+#define CALL(R)                                                                              \
+    allow_lds(k_pool_generic<R>, lds);                                                       \
+    hipLaunchKernelGGL(k_pool_generic<R>, dim3(ws.n_chunks, gv.B), dim3(kThreads), lds, s, gv, mv, \
+                       ws.emb, ws.reach, fa.placement, fa.cur_node, ws.partial, ws.n_chunks)
+    PL_DISPATCH_RPT(pick_rpt(mv.H), CALL)
+#undef CALL
+}
+
+void launch_head_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
+                         const ForwardArgs &fa, hipStream_t s)
+{
+    if (gv.B == 0) return;
+    const size_t lds =
+        sizeof(float) * (static_cast<size_t>(3) * mv.G * mv.H + mv.Z + 2 * kTile * mv.H);
+#define CALL(R)                                                                               \
+    allow_lds(k_head_generic<R>, lds);                                                        \
+    hipLaunchKernelGGL(k_head_generic<R>, dim3(gv.B), dim3(kThreads), lds, s, gv, mv, ws.emb, \
+                       ws.partial, fa.cur_node, ws.n_chunks, fa.out_logits, fa.out_probs,     \
+                       fa.out_pooled)
+    PL_DISPATCH_RPT(pick_rpt(mv.H), CALL)
+#undef CALL
+}
+
+}  // namespace pl

@@ -1,0 +1,162 @@
+"""GPU parity: the HIP library, called through the C ABI, against the float64 oracle on the
+same seeded inputs.  Logits within 1e-4 relative + 1e-5 absolute per element; node sets
+and levels bit-exact."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from gpu_common import assert_logits_close, assert_probs_close, run_library
+from workloads import CONFIG_NAMES, make_workload, make_states, tiny_random_dag, weight_count
+from workloads.synthetic import Workload
+
+pytestmark = pytest.mark.gpu
+
+THREADS = min(16, os.cpu_count() or 1)
+SMALL_B = {"random32": 1, "layered200": 8, "inception": 6, "nmt": 4, "nasnet": 3}
+
+
+def _compare(w, what, check_emb=True):
+    ref = oracle.forward_workload(w, n_threads=THREADS, want_emb=check_emb)
+    got = run_library(w, want_emb=check_emb)
+    assert_logits_close(got["logits"], ref["logits"], what)
+    assert_probs_close(got["probs"], ref["probs"], ref["logits"], what)
+    if check_emb:
+        scale = np.abs(ref["emb"]).max()
+        assert np.abs(got["emb"] - ref["emb"]).max() <= 2e-5 * scale, what
+    pscale = max(np.abs(ref["pooled"]).max(), 1e-30)
+    assert np.abs(got["pooled"] - ref["pooled"]).max() <= 2e-5 * pscale, what
+    return got, ref
+
+
+@pytest.mark.parametrize("name", CONFIG_NAMES)
+def test_small_batches_elementwise(name):
+    """Every logit, embedding and pooled vector on a few graphs of each configuration
+    (several level tiles, ragged tails)."""
+    print(f"[parity] small {name}", flush=True)
+    _compare(make_workload(name, B=SMALL_B[name]), name)
+
+
+@pytest.mark.parametrize("name", CONFIG_NAMES)
+def test_full_size_logits(name):
+    """Full batch sizes of the five configurations, in the launch shape the benchmark
+    times; all logits against the oracle (run on all host threads)."""
+    print(f"[parity] full {name}", flush=True)
+    w = make_workload(name)
+    ref = oracle.forward_workload(w, n_threads=THREADS, want_emb=False)
+    got = run_library(w, want_emb=False)
+    e = assert_logits_close(got["logits"], ref["logits"], name)
+    print(f"[parity] {name}: {e}", flush=True)
+
+
+@pytest.mark.parametrize("name", ["layered200", "nmt"])
+def test_node_sets_bit_exact(name):
+    import torch
+    import paper_1906_08879_amd as pl
+    w = make_workload(name, B=6)
+    g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+    rng = np.random.default_rng(1)
+    for _ in range(3):
+        cur = np.array([rng.integers(n) for n in w.n_nodes], dtype=np.int32)
+        out = torch.zeros(w.n_tot, dtype=torch.uint8, device="cuda:0")
+        pl.node_classes(g, torch.from_numpy(cur).cuda(), out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        for b in range(w.B):
+            n, src, dst, *_ = w.graph(b)
+            np.testing.assert_array_equal(got[w.node_off[b]:w.node_off[b + 1]],
+                                          oracle.classes(n, src, dst, int(cur[b])))
+    g.close()
+
+
+def _custom(rng, sizes, D, H, n_layers=2, k_sweeps=1, group=1, weight_dtype="fp32", p_edge=0.3):
+    n_nodes, n_edges, srcs, dsts, feats, places, curs = [], [], [], [], [], [], []
+    for n in sizes:
+        s, d = tiny_random_dag(rng, n, p_edge)
+        n_nodes.append(n); n_edges.append(len(s)); srcs.append(s); dsts.append(d)
+        feats.append(np.stack([rng.lognormal(0, 1, n), rng.lognormal(2, 1, n),
+                               (rng.random(n) < 0.5)], axis=1))
+        places.append(rng.integers(0, D, n)); curs.append(rng.integers(n))
+    weights = rng.normal(0, 0.1, weight_count(D, H, n_layers, bool(group))).astype(np.float32)
+    return Workload(name="custom", B=len(sizes), D=D, H=H, n_layers=n_layers, k_sweeps=k_sweeps,
+                    group_by_device=group, weight_dtype=weight_dtype,
+                    n_nodes=np.array(n_nodes, np.int32), n_edges=np.array(n_edges, np.int32),
+                    edge_src=np.concatenate(srcs).astype(np.int32),
+                    edge_dst=np.concatenate(dsts).astype(np.int32),
+                    node_feats=np.concatenate(feats).astype(np.float32),
+                    placement=np.concatenate(places).astype(np.int32),
+                    cur_node=np.array(curs, np.int32), weights=weights)
+
+
+@pytest.mark.parametrize("D,H,L,k,group,wd", [
+    (2, 8, 2, 1, 1, "fp32"), (1, 5, 1, 1, 1, "fp32"), (16, 16, 2, 1, 1, "fp32"),
+    (4, 48, 3, 1, 1, "fp32"), (3, 100, 2, 1, 0, "fp32"), (4, 32, 2, 0, 1, "fp32"),
+    (4, 32, 2, 2, 1, "fp32"), (4, 64, 1, 3, 0, "fp32"), (8, 128, 2, 1, 1, "bf16"),
+    (2, 256, 2, 1, 1, "fp32"), (4, 64, 4, 1, 1, "bf16"),
+])
+def test_shapes_and_variants(D, H, L, k, group, wd):
+    """Ragged batches (single nodes, edgeless graphs, wide levels) over the supported range
+    of D, H, layers, sweeps, pooling modes and weight formats."""
+    print(f"[parity] variant D={D} H={H} L={L} k={k} group={group} {wd}", flush=True)
+    rng = np.random.default_rng(100 * D + H)
+    w = _custom(rng, [1, 2, 40, 1, 17, 70, 3], D, H, L, k, group, wd)
+    _compare(w, f"D={D} H={H} L={L} k={k} g={group} {wd}")
+
+
+def test_edgeless_and_wide_levels():
+    rng = np.random.default_rng(9)
+    w = _custom(rng, [50, 33, 1], 4, 32, p_edge=0.0)          # every node is a root and a leaf
+    _compare(w, "edgeless")
+    w = _custom(rng, [90, 64], 4, 64, p_edge=0.02)            # levels wider than one tile
+    _compare(w, "wide levels")
+
+
+def test_batch_rows_are_independent_and_deterministic():
+    w1 = make_workload("layered200", B=5)
+    a = run_library(w1)
+    b = run_library(w1)
+    np.testing.assert_array_equal(a["logits"], b["logits"])   # bitwise run-to-run
+    np.testing.assert_array_equal(a["emb"], b["emb"])
+    w2 = make_workload("layered200", B=2)                      # same first two graphs
+    c = run_library(w2)
+    np.testing.assert_array_equal(c["logits"], a["logits"][:2])
+
+
+def test_state_stream_reuses_handles():
+    """An episode-like stream of states through one pair of handles."""
+    import paper_1906_08879_amd as pl
+    w = make_workload("inception", B=4)
+    placement, cur, done = make_states(w, 3)
+    g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+    wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+    for s in range(3):
+        ref = oracle.forward_workload(w, n_threads=THREADS, want_emb=False, placement=placement[s],
+                                      cur_node=cur[s], done=done[s])
+        got = run_library(w, placement[s], cur[s], done[s], want_emb=False, handles=(g, wt))
+        assert_logits_close(got["logits"], ref["logits"], f"state {s}")
+    g.close(); wt.close()
+
+
+def test_out_of_range_state_is_contained():
+    """A device id outside [0, D) is an all-zero one-hot pooled nowhere; a current node
+    outside its graph gives NaN logits for that graph only."""
+    w = make_workload("layered200", B=3)
+    ref = oracle.forward_workload(w, n_threads=2, want_emb=False)
+    cur = w.cur_node.copy()
+    cur[1] = 10_000
+    got = run_library(w, cur_node=cur, want_emb=False)
+    assert np.isnan(got["logits"][1]).all()
+    assert_logits_close(got["logits"][[0, 2]], ref["logits"][[0, 2]], "neighbours of a bad row")
+
+
+def test_empty_batch_is_a_no_op():
+    import torch
+    import paper_1906_08879_amd as pl
+    g = pl.GraphBatch([], [], [], [])
+    wt = pl.Weights(np.zeros(weight_count(2, 8), np.float32), 2, 8)
+    z = torch.zeros(0, device="cuda:0")
+    zi = torch.zeros(0, dtype=torch.int32, device="cuda:0")
+    pl.embed_forward(g, z, zi, zi, wt, z)
+    torch.cuda.synchronize()
+    g.close(); wt.close()
