@@ -112,6 +112,12 @@ int pl_weights_create(const pl_model_cfg *cfg, const float *host_blob, size_t n_
                       pl_weights **out);
 int pl_weights_destroy(pl_weights *w);                  /* NULL is accepted */
 
+/* Kernel selection for forward passes that use `w`: 0 (default) = the fastest kernels that
+ * cover the configuration (matrix-core sweeps for H in {32, 64, 128} with bf16 weights,
+ * H in {32, 64} with fp32 weights, n_layers <= 2); 1 = the generic fp32 kernels, which
+ * cover every supported configuration.  Both compute the same function. */
+int pl_weights_set_path(pl_weights *w, int32_t path);
+
 /* ---- the forward pass (Section 2.2 steps 1-3 + policy head, Appendix A.7).
  *   node_feats  dev [N_tot, 3] fp32  per node: run time, output size, is-visited flag
  *                                    (Section 2.1 features 1, 2 and 4)

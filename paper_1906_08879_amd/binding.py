@@ -58,6 +58,7 @@ def load_library(path: Optional[str] = None):
         "pl_weights_create": (ctypes.c_int, [cfgp, ctypes.POINTER(ctypes.c_float),
                                              ctypes.c_size_t, ctypes.POINTER(vp)]),
         "pl_weights_destroy": (ctypes.c_int, [vp]),
+        "pl_weights_set_path": (ctypes.c_int, [vp, ctypes.c_int32]),
         "pl_embed_forward": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp]),
         "pl_embed_forward_ex": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "pl_profile_enable": (ctypes.c_int, [vp, ctypes.c_int32]),
@@ -184,6 +185,10 @@ class Weights:
                                      blob.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
                                      blob.size, ctypes.byref(self._h)), "pl_weights_create")
         self.D, self.H, self.G = D, H, (D if group_by_device else 1)
+
+    def set_path(self, path: int):
+        """0 = fastest kernels available for this configuration, 1 = generic fp32 kernels."""
+        _check(load_library().pl_weights_set_path(self._h, int(path)), "pl_weights_set_path")
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h:

@@ -61,6 +61,9 @@ struct pl_graph_batch {
     int32_t *d_node_off = nullptr, *d_lvl_off = nullptr, *d_node_graph = nullptr;
     int32_t *d_nbr_ptr[2] = {nullptr, nullptr}, *d_nbr_idx[2] = {nullptr, nullptr};
     int32_t *d_order[2] = {nullptr, nullptr}, *d_lvl_ptr[2] = {nullptr, nullptr};
+    int32_t *d_ck_off[2] = {nullptr, nullptr}, *d_ck_meta[2] = {nullptr, nullptr};
+    int32_t *d_ck_far[2] = {nullptr, nullptr};
+    uint16_t *d_ck_ent[2] = {nullptr, nullptr};
     pl::GraphView view{};
     pl::Workspace ws;
     pl::StageTimer timer;
@@ -71,6 +74,11 @@ struct pl_weights {
     pl::ModelView view{};
     float *d_blob = nullptr;
     std::vector<float> host_blob;   // values as stored (bf16-rounded when asked)
+    // matrix-core sweep: packed A fragments and biases (null when the shape is not covered)
+    uint16_t *d_wfrag = nullptr;
+    float *d_sweep_bias = nullptr;
+    int sweep_ws = 0;               // bf16 parts per weight: 1 (bf16 weights) or 3 (fp32)
+    int path = 0;                   // 0 = fastest available kernels, 1 = generic fp32 kernels
 };
 
 namespace pl {
@@ -177,6 +185,12 @@ int ensure_on_device(pl_graph_batch *g)
         if ((rc = upload(idx[dir], &g->d_nbr_idx[dir]))) return rc;
         if ((rc = upload(order[dir], &g->d_order[dir]))) return rc;
         if ((rc = upload(lvl[dir], &g->d_lvl_ptr[dir]))) return rc;
+        SweepPlanHost plan;
+        if ((rc = build_sweep_plan(L, dir, &plan))) return rc;
+        if ((rc = upload(plan.ck_off, &g->d_ck_off[dir]))) return rc;
+        if ((rc = upload(plan.meta, &g->d_ck_meta[dir]))) return rc;
+        if ((rc = upload(plan.ent, &g->d_ck_ent[dir]))) return rc;
+        if ((rc = upload(plan.far, &g->d_ck_far[dir]))) return rc;
     }
     GraphView &v = g->view;
     v.B = L.B;
@@ -189,6 +203,10 @@ int ensure_on_device(pl_graph_batch *g)
         v.nbr_idx[dir] = g->d_nbr_idx[dir];
         v.order[dir] = g->d_order[dir];
         v.lvl_ptr[dir] = g->d_lvl_ptr[dir];
+        v.plan[dir].ck_off = g->d_ck_off[dir];
+        v.plan[dir].meta = reinterpret_cast<const int4 *>(g->d_ck_meta[dir]);
+        v.plan[dir].ent = reinterpret_cast<const uint4 *>(g->d_ck_ent[dir]);
+        v.plan[dir].far = g->d_ck_far[dir];
     }
     g->on_device = true;
     return PL_OK;
@@ -282,8 +300,13 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
     {
         StageScope scope(g->timer, PL_STAGE_SWEEP, s);
         if (w->cfg.k_sweeps == 0) launch_reach_only(gv, cur_node, g->ws.reach, s);
-        for (int k = 0; k < w->cfg.k_sweeps; ++k)
-            launch_sweep_generic(gv, mv, g->ws, fa, k == 0, s);
+        for (int k = 0; k < w->cfg.k_sweeps; ++k) {
+            if (w->d_wfrag && w->path == 0)
+                launch_sweep_mfma(gv, mv, g->ws, fa, reinterpret_cast<const uint4 *>(w->d_wfrag),
+                                  w->d_sweep_bias, w->sweep_ws, s);
+            else
+                launch_sweep_generic(gv, mv, g->ws, fa, k == 0, s);
+        }
     }
     {
         StageScope scope(g->timer, PL_STAGE_POOL, s);
@@ -343,6 +366,10 @@ int pl_graph_batch_destroy(pl_graph_batch *g)
             (void)hipFree(g->d_nbr_idx[dir]);
             (void)hipFree(g->d_order[dir]);
             (void)hipFree(g->d_lvl_ptr[dir]);
+            (void)hipFree(g->d_ck_off[dir]);
+            (void)hipFree(g->d_ck_meta[dir]);
+            (void)hipFree(g->d_ck_ent[dir]);
+            (void)hipFree(g->d_ck_far[dir]);
         }
     }
     free_workspace(g->ws);
@@ -450,7 +477,25 @@ int pl_weights_create(const pl_model_cfg *cfg, const float *host_blob, size_t n_
         return rc;
     }
     w->view.blob = w->d_blob;
+    if (sweep_mfma_supported(cfg->H, cfg->n_layers, cfg->weight_dtype)) {
+        std::vector<uint16_t> frag;
+        std::vector<float> sweep_bias;
+        w->sweep_ws = cfg->weight_dtype == PL_WEIGHTS_BF16 ? 1 : 3;
+        pack_sweep_weights(w->view, w->host_blob.data(), w->sweep_ws, &frag, &sweep_bias);
+        if ((rc = upload(frag, &w->d_wfrag)) || (rc = upload(sweep_bias, &w->d_sweep_bias))) {
+            pl_weights_destroy(w);
+            return rc;
+        }
+    }
     *out = w;
+    return PL_OK;
+}
+
+int pl_weights_set_path(pl_weights *w, int32_t path)
+{
+    if (!w) return fail(PL_ERR_NULL, "weights handle is NULL");
+    if (path != 0 && path != 1) return fail(PL_ERR_SHAPE, "path must be 0 or 1");
+    w->path = path;
     return PL_OK;
 }
 
@@ -458,6 +503,8 @@ int pl_weights_destroy(pl_weights *w)
 {
     if (!w) return PL_OK;
     (void)hipFree(w->d_blob);
+    (void)hipFree(w->d_wfrag);
+    (void)hipFree(w->d_sweep_bias);
     delete w;
     return PL_OK;
 }

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstring>
 #include <string>
 #include <vector>
 
@@ -50,6 +51,30 @@ struct HostLayout {
 int build_layout(int32_t B, const int32_t *n_nodes, const int32_t *n_edges,
                  const int32_t *edge_src, const int32_t *edge_dst, HostLayout *out);
 
+// ---- gather plan of the matrix-core sweep kernel (plan.cpp)
+constexpr int kChunkRows = 10;   // nodes per chunk: two column tiles of five nodes
+constexpr int kFarCap = 16;      // far sources staged per chunk
+constexpr int kRing = 2;         // chunks whose messages stay in the LDS table
+constexpr int kMaxEnt = 7;       // neighbours per row held in the chunk record
+constexpr int kMsgSlots = kRing * kChunkRows + 2 * kFarCap;
+
+struct SweepPlanHost {
+    std::vector<int32_t> ck_off;   // [B+1] chunk range of each graph
+    std::vector<int32_t> meta;     // [n_chunks][4]: global bucket position, rows, n_far, 0
+    std::vector<uint16_t> ent;     // [n_chunks][kChunkRows][8]: count (0xFFFF = sum from global), slots
+    std::vector<int32_t> far;      // [n_chunks][kFarCap] global node ids staged for the chunk
+    int64_t n_chunks = 0;
+};
+
+int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out);
+
+struct SweepPlanView {
+    const int32_t *ck_off;
+    const int4 *meta;
+    const uint4 *ent;
+    const int32_t *far;
+};
+
 // ---- device-side view of a batch, passed to kernels by value
 struct GraphView {
     int32_t B;
@@ -62,6 +87,7 @@ struct GraphView {
     const int32_t *order[2];   // [n_tot] GLOBAL node ids by (graph, level, id)
     const int32_t *lvl_ptr[2]; // per graph depth+1 GLOBAL positions into order
     const int32_t *node_graph; // [n_tot] graph of each node
+    SweepPlanView plan[2];     // per direction
 };
 
 // ---- parameters: offsets (in floats) of every layer inside the fp32 device blob
@@ -120,5 +146,13 @@ void launch_pool_generic(const GraphView &gv, const ModelView &mv, const Workspa
                          const ForwardArgs &fa, hipStream_t s);
 void launch_head_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                          const ForwardArgs &fa, hipStream_t s);
+
+// ---- matrix-core sweep (kernels_mfma.hip)
+bool sweep_mfma_supported(int H, int L, int weight_dtype);
+void pack_sweep_weights(const ModelView &mv, const float *blob, int WS, std::vector<uint16_t> *frag,
+                        std::vector<float> *bias);
+void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
+                       const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
+                       hipStream_t s);
 
 }  // namespace pl
