@@ -62,7 +62,8 @@ struct pl_graph_batch {
     int32_t *d_nbr_ptr[2] = {nullptr, nullptr}, *d_nbr_idx[2] = {nullptr, nullptr};
     int32_t *d_order[2] = {nullptr, nullptr}, *d_lvl_ptr[2] = {nullptr, nullptr};
     int32_t *d_ck_off[2] = {nullptr, nullptr}, *d_ck_meta[2] = {nullptr, nullptr};
-    int32_t *d_ck_far[2] = {nullptr, nullptr};
+    int32_t *d_ck_far[2] = {nullptr, nullptr}, *d_ck_ovf[2] = {nullptr, nullptr};
+    int32_t *d_pos[2] = {nullptr, nullptr};
     uint16_t *d_ck_ent[2] = {nullptr, nullptr};
     pl::GraphView view{};
     pl::Workspace ws;
@@ -191,6 +192,10 @@ int ensure_on_device(pl_graph_batch *g)
         if ((rc = upload(plan.meta, &g->d_ck_meta[dir]))) return rc;
         if ((rc = upload(plan.ent, &g->d_ck_ent[dir]))) return rc;
         if ((rc = upload(plan.far, &g->d_ck_far[dir]))) return rc;
+        if ((rc = upload(plan.ovf, &g->d_ck_ovf[dir]))) return rc;
+        std::vector<int32_t> pos(L.n_tot);
+        for (int64_t p = 0; p < L.n_tot; ++p) pos[order[dir][p]] = static_cast<int32_t>(p);
+        if ((rc = upload(pos, &g->d_pos[dir]))) return rc;
     }
     GraphView &v = g->view;
     v.B = L.B;
@@ -207,6 +212,8 @@ int ensure_on_device(pl_graph_batch *g)
         v.plan[dir].meta = reinterpret_cast<const int4 *>(g->d_ck_meta[dir]);
         v.plan[dir].ent = reinterpret_cast<const uint4 *>(g->d_ck_ent[dir]);
         v.plan[dir].far = g->d_ck_far[dir];
+        v.plan[dir].ovf = g->d_ck_ovf[dir];
+        v.pos[dir] = g->d_pos[dir];
     }
     g->on_device = true;
     return PL_OK;
@@ -216,6 +223,7 @@ void free_workspace(Workspace &ws)
 {
     (void)hipFree(ws.emb);
     (void)hipFree(ws.msg);
+    (void)hipFree(ws.xb);
     (void)hipFree(ws.reach);
     (void)hipFree(ws.partial);
     ws = Workspace();
@@ -243,6 +251,7 @@ int ensure_workspace(pl_graph_batch *g, const ModelView &mv)
     if (rc) return rc;
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.emb), sizeof(float) * (n * 2 * H + 4)));
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.msg), sizeof(float) * (2 * n * H + 4)));
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.xb), sizeof(float) * (2 * n * H + 4)));
     ws.n_chunks = 8;
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.partial),
                      sizeof(float) * (static_cast<size_t>(g->host.B) * ws.n_chunks * 3 * mv.G * H + 4)));
@@ -293,17 +302,18 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
     hipStream_t s = static_cast<hipStream_t>(stream);
     ForwardArgs fa{node_feats, placement, cur_node, out_logits, out_probs, out_pooled};
     const GraphView &gv = g->view;
+    const bool mfma = w->d_wfrag && w->path == 0 && w->cfg.k_sweeps > 0;
     {
         StageScope scope(g->timer, PL_STAGE_PROJECT, s);
-        launch_project(gv, mv, g->ws, fa, s);
+        launch_project(gv, mv, g->ws, fa, !mfma, mfma, s);
     }
     {
         StageScope scope(g->timer, PL_STAGE_SWEEP, s);
         if (w->cfg.k_sweeps == 0) launch_reach_only(gv, cur_node, g->ws.reach, s);
         for (int k = 0; k < w->cfg.k_sweeps; ++k) {
-            if (w->d_wfrag && w->path == 0)
+            if (mfma)
                 launch_sweep_mfma(gv, mv, g->ws, fa, reinterpret_cast<const uint4 *>(w->d_wfrag),
-                                  w->d_sweep_bias, w->sweep_ws, s);
+                                  w->d_sweep_bias, w->sweep_ws, k + 1 < w->cfg.k_sweeps, s);
             else
                 launch_sweep_generic(gv, mv, g->ws, fa, k == 0, s);
         }
@@ -370,6 +380,8 @@ int pl_graph_batch_destroy(pl_graph_batch *g)
             (void)hipFree(g->d_ck_meta[dir]);
             (void)hipFree(g->d_ck_ent[dir]);
             (void)hipFree(g->d_ck_far[dir]);
+            (void)hipFree(g->d_ck_ovf[dir]);
+            (void)hipFree(g->d_pos[dir]);
         }
     }
     free_workspace(g->ws);

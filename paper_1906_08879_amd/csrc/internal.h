@@ -60,9 +60,11 @@ constexpr int kMsgSlots = kRing * kChunkRows + 2 * kFarCap;
 
 struct SweepPlanHost {
     std::vector<int32_t> ck_off;   // [B+1] chunk range of each graph
-    std::vector<int32_t> meta;     // [n_chunks][4]: global bucket position, rows, n_far, 0
+    std::vector<int32_t> meta;     // [n_chunks][4]: global bucket position, rows, n_far, most table entries of a row
     std::vector<uint16_t> ent;     // [n_chunks][kChunkRows][8]: count (0xFFFF = sum from global), slots
     std::vector<int32_t> far;      // [n_chunks][kFarCap] global node ids staged for the chunk
+    std::vector<int32_t> ovf;      // neighbour lists of rows that do not fit their record:
+                                   // >= 0 global node id (>= 3 chunks back), < 0: -1 - table slot
     int64_t n_chunks = 0;
 };
 
@@ -73,6 +75,7 @@ struct SweepPlanView {
     const int4 *meta;
     const uint4 *ent;
     const int32_t *far;
+    const int32_t *ovf;
 };
 
 // ---- device-side view of a batch, passed to kernels by value
@@ -87,6 +90,7 @@ struct GraphView {
     const int32_t *order[2];   // [n_tot] GLOBAL node ids by (graph, level, id)
     const int32_t *lvl_ptr[2]; // per graph depth+1 GLOBAL positions into order
     const int32_t *node_graph; // [n_tot] graph of each node
+    const int32_t *pos[2];     // [n_tot] bucket position of each node (inverse of order)
     SweepPlanView plan[2];     // per direction
 };
 
@@ -115,6 +119,7 @@ struct ModelView {
 struct Workspace {
     float *emb = nullptr;       // [n_tot, 2H]  [td ; bu]
     float *msg = nullptr;       // [2, n_tot, H]
+    float *xb = nullptr;        // [2, n_tot, H]  sweep input in bucket order (matrix-core path)
     uint8_t *reach = nullptr;   // [2, n_tot]   0: descendant-of-v* bit, 1: ancestor-of-v* bit
     float *partial = nullptr;   // [B, n_chunks_max, 3G, H] pooling partial sums
     int32_t *chunk_off = nullptr; // [B+1] first pooling chunk of each graph
@@ -135,7 +140,7 @@ struct ForwardArgs {
 constexpr int kPoolChunk = 128;   // nodes per pooling workgroup
 
 void launch_project(const GraphView &gv, const ModelView &mv, const Workspace &ws,
-                    const ForwardArgs &fa, hipStream_t s);
+                    const ForwardArgs &fa, bool to_emb, bool to_xb, hipStream_t s);
 void launch_sweep_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                           const ForwardArgs &fa, bool write_reach, hipStream_t s);
 void launch_reach_only(const GraphView &gv, const int32_t *cur_node, uint8_t *reach,
@@ -153,6 +158,6 @@ void pack_sweep_weights(const ModelView &mv, const float *blob, int WS, std::vec
                         std::vector<float> *bias);
 void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                        const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
-                       hipStream_t s);
+                       bool more_sweeps, hipStream_t s);
 
 }  // namespace pl

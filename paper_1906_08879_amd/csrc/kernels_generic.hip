@@ -50,12 +50,14 @@ __device__ __forceinline__ void dense_layer(const float *__restrict__ W,
 
 // ------------------------------------------------------------------ step 1: features
 // phi_v = [time, size, one-hot(device), is-current, is-visited]; x_v = relu(W^T phi_v + b).
-// Written to both halves of the embedding (the two directions start from the same x).
+// The two directions start from the same x: it goes to both halves of the embedding
+// (node order) and/or to the per-direction bucket-ordered input of the matrix-core sweep.
 __global__ __launch_bounds__(kThreads) void k_project(GraphView gv, ModelView mv,
                                                       const float *__restrict__ feats,
                                                       const int32_t *__restrict__ placement,
                                                       const int32_t *__restrict__ cur_node,
-                                                      float *__restrict__ emb)
+                                                      float *__restrict__ emb,
+                                                      float *__restrict__ xb)
 {
     const int H = mv.H, D = mv.D;
     const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
@@ -71,8 +73,14 @@ __global__ __launch_bounds__(kThreads) void k_project(GraphView gv, ModelView mv
     if (v - gv.node_off[b] == cur_node[b]) s += W[(2 + D) * H + h];
     s = fmaf(feats[v * 3 + 2], W[(3 + D) * H + h], s);
     s = fmaxf(s, 0.0f);
-    emb[static_cast<size_t>(v) * 2 * H + h] = s;
-    emb[static_cast<size_t>(v) * 2 * H + H + h] = s;
+    if (emb) {
+        emb[static_cast<size_t>(v) * 2 * H + h] = s;
+        emb[static_cast<size_t>(v) * 2 * H + H + h] = s;
+    }
+    if (xb) {
+        xb[static_cast<size_t>(gv.pos[0][v]) * H + h] = s;
+        xb[(static_cast<size_t>(gv.n_tot) + gv.pos[1][v]) * H + h] = s;
+    }
 }
 
 // ------------------------------------------------------------------ step 2: one sweep
@@ -397,13 +405,13 @@ void allow_lds(K kernel, size_t bytes)
 }  // namespace
 
 void launch_project(const GraphView &gv, const ModelView &mv, const Workspace &ws,
-                    const ForwardArgs &fa, hipStream_t s)
+                    const ForwardArgs &fa, bool to_emb, bool to_xb, hipStream_t s)
 {
     const size_t total = static_cast<size_t>(gv.n_tot) * mv.H;
     if (total == 0) return;
     const unsigned blocks = static_cast<unsigned>((total + kThreads - 1) / kThreads);
     hipLaunchKernelGGL(k_project, dim3(blocks), dim3(kThreads), 0, s, gv, mv, fa.node_feats,
-                       fa.placement, fa.cur_node, ws.emb);
+                       fa.placement, fa.cur_node, to_emb ? ws.emb : nullptr, to_xb ? ws.xb : nullptr);
 }
 
 void launch_sweep_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,

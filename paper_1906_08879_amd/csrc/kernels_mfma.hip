@@ -14,9 +14,15 @@
 //     kernel (bf16 weights: 128 VGPRs at H = 128); only activations move through LDS.
 //   * Messages of the last two chunks stay in an LDS table; messages from older chunks are
 //     prefetched from HBM one chunk ahead into the same table, so the gather on the
-//     critical path reads LDS only.  Chunk records, node ids and the residual inputs are
-//     prefetched the same way.
-//   * Barriers between layers wait on LDS traffic only, so prefetches stay in flight.
+//     critical path reads LDS only.  Chunk records, node ids and the residual inputs (kept
+//     in bucket order, so a chunk's rows are contiguous) are prefetched the same way.
+//   * One barrier per chunk (after the first layer) completes global stores; the others
+//     order LDS traffic only, so prefetches stay in flight across them.  A message written
+//     to HBM in chunk c is therefore only read back from HBM from chunk c + 3 on; nearer
+//     consumers use the LDS table.
+//   * A single wave per SIMD runs a dependent chain, so the kernel is bound by instruction
+//     issue, not by bandwidth: the split is done by truncation (4 VALU ops per value), the
+//     column sums are single DPP adds, and the gather is spread over all 256 lanes.
 #include "internal.h"
 
 namespace pl {
@@ -24,7 +30,6 @@ namespace pl {
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int kThreads = 256;
@@ -32,45 +37,83 @@ constexpr int CH = kChunkRows, FCAP = kFarCap, RING = kRing;
 constexpr int kTileNodes = 5;                 // nodes per 16-column MFMA tile (3 columns each)
 constexpr int NT = CH / kTileNodes;           // column tiles per chunk
 
-// Workgroup barrier that waits for LDS traffic only (global prefetches stay outstanding).
+// Workgroup barrier that orders LDS traffic only: global prefetches stay outstanding.
 __device__ __forceinline__ void lds_barrier()
 {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Full workgroup barrier: also completes this wave's outstanding global stores and loads.
+__device__ __forceinline__ void full_barrier() { __syncthreads(); }
+
+// acc + (value v of lane l+N in the same row of 16 lanes, 0 past the row's end), in one VALU
+// instruction.  The s_nop covers the VALU-write -> DPP-read hazard, which the compiler
+// cannot see inside inline assembly.
 template <int N>
-__device__ __forceinline__ float row_shl(float v)   // lane l reads lane l+N of its row of 16
+__device__ __forceinline__ float add_row_shl(float acc, float v)
 {
-    return __int_as_float(
-        __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x100 + N, 0xF, 0xF, true));
+    float r;
+    if constexpr (N == 1)
+        asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %1, %2 row_shl:1 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                     : "=v"(r)
+                     : "v"(v), "v"(acc));
+    else
+        asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %1, %2 row_shl:2 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                     : "=v"(r)
+                     : "v"(v), "v"(acc));
+    return r;
 }
 
-// x = h + m + l exactly (each part a bf16), for finite x away from the subnormal range.
-__device__ __forceinline__ void split3(float x, __bf16 &h, __bf16 &m, __bf16 &l)
+// Exact three-way split of four fp32 values into bf16 parts by truncation:
+// x = hi + mid + lo with hi = top 16 bits of x, mid = top 16 bits of (x - hi),
+// lo = x - hi - mid (at most 8 significant bits left).  Returned packed, two bf16 per dword.
+struct Split4 {
+    uint2 hi, mid, lo;
+};
+
+__device__ __forceinline__ uint32_t pack_hi16(float lo_word, float hi_word)
 {
-    h = static_cast<__bf16>(x);
-    float r = x - static_cast<float>(h);
-    m = static_cast<__bf16>(r);
-    r -= static_cast<float>(m);
-    l = static_cast<__bf16>(r);
+    return __builtin_amdgcn_perm(__float_as_uint(hi_word), __float_as_uint(lo_word), 0x07060302u);
 }
 
-__device__ __forceinline__ __bf16 split_part(float x, int s)
+__device__ __forceinline__ Split4 split4(const float (&x)[4])
 {
-    __bf16 h, m, l;
-    split3(x, h, m, l);
-    return s == 0 ? h : (s == 1 ? m : l);
+    float r[4], l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        r[i] = x[i] - __uint_as_float(__float_as_uint(x[i]) & 0xFFFF0000u);
+        l[i] = r[i] - __uint_as_float(__float_as_uint(r[i]) & 0xFFFF0000u);
+    }
+    Split4 s;
+    s.hi = uint2{pack_hi16(x[0], x[1]), pack_hi16(x[2], x[3])};
+    s.mid = uint2{pack_hi16(r[0], r[1]), pack_hi16(r[2], r[3])};
+    s.lo = uint2{pack_hi16(l[0], l[1]), pack_hi16(l[2], l[3])};
+    return s;
 }
 
 struct SweepParams {
     GraphView gv;
     const uint4 *wfrag;     // packed A fragments, see pack_sweep_weights()
-    const float *bias;      // [2 dir][2 net][L][H]
-    float *emb;             // [n_tot, 2H]
+    const float *bias;      // [2 dir][2L layers][H]
+    float *emb;             // [n_tot, 2H]   output s_v in node order ([td ; bu])
+    float *xb;              // [2, n_tot, H] residual input in bucket order, per direction
     float *msg;             // [2, n_tot, H]
     uint8_t *reach;         // [2, n_tot]
     const int32_t *cur_node;
+    int write_xb;           // another sweep follows: keep xb current
 };
+
+// Reads a chunk's meta record through the constant address space, so that the wave-uniform
+// record comes in with a scalar load.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ int4 load_uniform(const int4 *p)
+{
+    const i32x4 r = *reinterpret_cast<const __attribute__((address_space(4))) i32x4 *>(
+        reinterpret_cast<uintptr_t>(p));
+    return int4{r.x, r.y, r.z, r.w};
+}
 
 template <int H, int WS, int L>
 __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
@@ -79,13 +122,16 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
     constexpr int TPW = (MT + 3) / 4;          // output tiles per wave
     constexpr int NL = 2 * L;                  // layers per chunk: g then f
     constexpr int LDA = H + 8;                 // bf16 row stride of the activation buffers
-    constexpr int TPR = H / 4;                 // float4 per message row
-    constexpr int PFN = (FCAP * TPR + kThreads - 1) / kThreads;
+    constexpr int TPR = H / 4;                 // float4 per row
+    constexpr int PFN = (FCAP * TPR + kThreads - 1) / kThreads;   // staged far float4 per thread
+    constexpr int PGN = (CH * TPR + kThreads - 1) / kThreads;     // gather items per thread
 
-    __shared__ __attribute__((aligned(16))) float msgtab[kMsgSlots * H];
+    __shared__ __attribute__((aligned(16))) float msgtab[(kMsgSlots + 1) * H];   // last row stays zero
+    __shared__ __attribute__((aligned(16))) float resbuf[2][CH * H];
     __shared__ __attribute__((aligned(16))) __bf16 actbuf[2][NT][16][LDA];
-    __shared__ uint8_t flagtab[kMsgSlots + 12];
     __shared__ __attribute__((aligned(16))) float bias_lds[NL * H];
+    __shared__ int vtab[CH + 6];                  // node ids of the chunk's rows
+    __shared__ uint8_t flagtab[kMsgSlots + 12];   // entry kMsgSlots (the zero row) stays 0
 
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -95,9 +141,10 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
 
     const GraphView &gv = P.gv;
     const SweepPlanView plan = gv.plan[dir];
-    const int32_t *__restrict__ order = gv.order[dir];
-    float *__restrict__ msg = P.msg + static_cast<size_t>(dir) * gv.n_tot * H;
-    uint8_t *__restrict__ reach = P.reach + static_cast<size_t>(dir) * gv.n_tot;
+    const int32_t *order = gv.order[dir];
+    float *msg = P.msg + static_cast<size_t>(dir) * gv.n_tot * H;
+    float *xb = P.xb + static_cast<size_t>(dir) * gv.n_tot * H;
+    uint8_t *reach = P.reach + static_cast<size_t>(dir) * gv.n_tot;
     const int n0 = gv.node_off[b], n_b = gv.node_off[b + 1] - n0;
     const int cl = P.cur_node[b];
     const int cur = (cl >= 0 && cl < n_b) ? n0 + cl : -1;
@@ -122,79 +169,103 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
                 }
         }
     for (int i = tid; i < NL * H; i += kThreads) bias_lds[i] = P.bias[static_cast<size_t>(dir) * NL * H + i];
-
-    for (int i = tid; i < kMsgSlots * H; i += kThreads) msgtab[i] = 0.0f;
+    for (int i = tid; i < (kMsgSlots + 1) * H; i += kThreads) msgtab[i] = 0.0f;
     for (int i = tid; i < 2 * NT * 16 * LDA; i += kThreads) (&actbuf[0][0][0][0])[i] = static_cast<__bf16>(0.0f);
     if (tid < kMsgSlots + 12) flagtab[tid] = 0;
 
-    // ---- software pipeline state
+    // ---- software pipeline state.  m0 describes chunk c, m1 chunk c + 1.  A gather item is
+    // (row r, float4 q) of the chunk: item i of this thread is e = tid + i * 256.
     auto clampc = [&](int c) { return c < c_end ? c : c_end - 1; };
-    int4 m0 = plan.meta[c_begin];                      // chunk c
-    int4 m1 = plan.meta[clampc(c_begin + 1)];          // chunk c + 1
-    uint4 ent0[NT];
-    int v0[NT];
-    int fid1[PFN];
+    int4 m0 = load_uniform(plan.meta + c_begin);
+    int4 m1 = load_uniform(plan.meta + clampc(c_begin + 1));
+    uint4 ent0[PGN];         // neighbour record of the item's row, chunk c
+    int vg0[PGN];            // node id of the item's row, chunk c
+    int fid1[PFN];           // far sources of chunk c + 1
 #pragma unroll
-    for (int ct = 0; ct < NT; ++ct) {
-        const int r = ct * kTileNodes + (jrow < kTileNodes ? jrow : 0);
-        ent0[ct] = plan.ent[static_cast<size_t>(c_begin) * CH + r];
-        v0[ct] = order[m0.x + (r < m0.y ? r : 0)];
+    for (int i = 0; i < PGN; ++i) {
+        const int e = tid + i * kThreads;
+        const int r = e / TPR, q = e - r * TPR;
+        const int rr = r < m0.y ? r : 0;
+        ent0[i] = plan.ent[static_cast<size_t>(c_begin) * CH + rr];
+        vg0[i] = order[m0.x + rr];
+        if (r < m0.y)                          // residual inputs of the first chunk
+            *reinterpret_cast<float4 *>(&resbuf[0][r * H + 4 * q]) =
+                *reinterpret_cast<const float4 *>(xb + static_cast<size_t>(m0.x + r) * H + 4 * q);
     }
 #pragma unroll
     for (int i = 0; i < PFN; ++i) {
         const int f = (tid + i * kThreads) / TPR;
         fid1[i] = (f < FCAP) ? plan.far[static_cast<size_t>(clampc(c_begin + 1)) * FCAP + f] : -1;
     }
-    __syncthreads();
+    full_barrier();
 
     for (int c = c_begin; c < c_end; ++c) {
         const int rows = m0.y;
         const int ntile = rows > kTileNodes ? 2 : 1;
         const bool has_next = c + 1 < c_end;
+        const int par = (c - c_begin) & 1;
 
-        // ---- A: issue every load that does not depend on this chunk's arithmetic
-        f32x4 res[TPW][NT];                              // residual inputs s_v of this chunk
+        // ---- gather: a_v = sum of neighbour messages from the LDS table, split into three
+        // bf16 parts, written as the B operand of the first layer
+        int my_bit[PGN];
 #pragma unroll
-        for (int t = 0; t < TPW; ++t)
-#pragma unroll
-            for (int ct = 0; ct < NT; ++ct) {
-                const int mt = wave * TPW + t;
-                const float4 x = *reinterpret_cast<const float4 *>(
-                    P.emb + static_cast<size_t>(v0[ct]) * 2 * H + dir * H + (mt < MT ? mt : 0) * 16 + 4 * kg);
-                res[t][ct] = f32x4{x.x, x.y, x.z, x.w};
-            }
-        float4 pf[PFN];
-        int pf_flag[PFN];
-#pragma unroll
-        for (int i = 0; i < PFN; ++i) {
+        for (int i = 0; i < PGN; ++i) {
             const int e = tid + i * kThreads;
-            const int f = e / TPR, q = e - f * TPR;
-            const bool live = has_next && f < m1.z && fid1[i] >= 0;
-            const int u = live ? fid1[i] : m0.x;         // any valid row when not live
-            pf[i] = *reinterpret_cast<const float4 *>(msg + static_cast<size_t>(u) * H + 4 * q);
-            pf_flag[i] = (live && q == 0) ? ((u == cur) | reach[u]) : 0;
-        }
-        const int4 m2 = plan.meta[clampc(c + 2)];
-        uint4 ent1[NT];
-        int v1[NT];
-        int fid2[PFN];
+            const int r = e / TPR, q = e - r * TPR;
+            my_bit[i] = 0;
+            if (r >= rows) continue;
+            const uint32_t w0 = ent0[i].x, w1 = ent0[i].y, w2 = ent0[i].z, w3 = ent0[i].w;
+            const int cnt = w0 & 0xFFFF;
+            const int slot[kMaxEnt] = {static_cast<int>(w0 >> 16), static_cast<int>(w1 & 0xFFFF),
+                                       static_cast<int>(w1 >> 16), static_cast<int>(w2 & 0xFFFF),
+                                       static_cast<int>(w2 >> 16), static_cast<int>(w3 & 0xFFFF),
+                                       static_cast<int>(w3 >> 16)};
+            float sum[4] = {0.f, 0.f, 0.f, 0.f};
+            int bit = 0;
+            if (cnt != 0xFFFF) {
 #pragma unroll
-        for (int ct = 0; ct < NT; ++ct) {
-            const int r = ct * kTileNodes + (jrow < kTileNodes ? jrow : 0);
-            ent1[ct] = plan.ent[static_cast<size_t>(clampc(c + 1)) * CH + r];
-            v1[ct] = order[m1.x + (r < m1.y ? r : 0)];
+                for (int k = 0; k < kMaxEnt; ++k) {
+                    if (k < cnt) {
+                        const float4 x = *reinterpret_cast<const float4 *>(msgtab + slot[k] * H + 4 * q);
+                        sum[0] += x.x; sum[1] += x.y; sum[2] += x.z; sum[3] += x.w;
+                        bit |= flagtab[slot[k]];
+                    }
+                }
+            } else {
+                // a row with more neighbours than its record holds: a list of table slots
+                // (recent sources) and node ids (sources at least three chunks back)
+                const int d0 = static_cast<int>(w0 >> 16) | (static_cast<int>(w1 & 0xFFFF) << 16);
+                const int d1 = d0 + (static_cast<int>(w1 >> 16) | (static_cast<int>(w2 & 0xFFFF) << 16));
+                for (int p = d0; p < d1; ++p) {
+                    const int u = plan.ovf[p];
+                    float4 x;
+                    if (u < 0) {
+                        x = *reinterpret_cast<const float4 *>(msgtab + (-1 - u) * H + 4 * q);
+                        bit |= flagtab[-1 - u];
+                    } else {
+                        x = *reinterpret_cast<const float4 *>(msg + static_cast<size_t>(u) * H + 4 * q);
+                        bit |= (u == cur) | reach[u];
+                    }
+                    sum[0] += x.x; sum[1] += x.y; sum[2] += x.z; sum[3] += x.w;
+                }
+            }
+            my_bit[i] = bit;
+            const Split4 sp = split4(sum);
+            const int ct = r >= kTileNodes ? 1 : 0;
+            __bf16 *dst = &actbuf[0][ct][3 * (r - ct * kTileNodes)][4 * q];
+            *reinterpret_cast<uint2 *>(dst) = sp.hi;
+            *reinterpret_cast<uint2 *>(dst + LDA) = sp.mid;
+            *reinterpret_cast<uint2 *>(dst + 2 * LDA) = sp.lo;
+            if (q == 0) vtab[r] = vg0[i];
         }
-#pragma unroll
-        for (int i = 0; i < PFN; ++i) {
-            const int f = (tid + i * kThreads) / TPR;
-            fid2[i] = (f < FCAP) ? plan.far[static_cast<size_t>(clampc(c + 2)) * FCAP + f] : -1;
-        }
+        lds_barrier();
 
-        // ---- layers: gather feeds the first one straight from the message table
+        float4 pf[PFN];          // far messages of chunk c + 1, in flight during the later layers
+        int pf_reach[PFN];
+        float4 pr[PGN];          // residual inputs of chunk c + 1
+        int vg1[PGN];
+        int4 m2 = m1;
         f32x4 acc[TPW][NT];
-        int my_bit[NT];
-#pragma unroll
-        for (int ct = 0; ct < NT; ++ct) my_bit[ct] = 0;
 
 #pragma unroll
         for (int n = 0; n < NL; ++n) {
@@ -206,72 +277,16 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
 #pragma unroll
             for (int ct = 0; ct < NT; ++ct) {
                 if (ct >= ntile) break;
-                const int r = ct * kTileNodes + jrow;
-                const bool live_col = jrow < kTileNodes && r < rows;
-                if (n == 0) {
-                    // gather: a_v = sum of neighbour messages, taken from the LDS table
-                    const uint32_t w0 = ent0[ct].x, w1 = ent0[ct].y, w2 = ent0[ct].z, w3 = ent0[ct].w;
-                    const int cnt_raw = w0 & 0xFFFF;
-                    const bool direct = live_col && cnt_raw == 0xFFFF;
-                    const int cnt = (live_col && !direct) ? cnt_raw : 0;
-                    const int slot[kMaxEnt] = {static_cast<int>(w0 >> 16), static_cast<int>(w1 & 0xFFFF),
-                                               static_cast<int>(w1 >> 16), static_cast<int>(w2 & 0xFFFF),
-                                               static_cast<int>(w2 >> 16), static_cast<int>(w3 & 0xFFFF),
-                                               static_cast<int>(w3 >> 16)};
-                    int bit = 0;
 #pragma unroll
-                    for (int e = 0; e < kMaxEnt; ++e)
-                        if (e < cnt) bit |= flagtab[slot[e]];
-                    const int v = v0[ct];
-                    const int d0 = direct ? gv.nbr_ptr[dir][v] : 0;
-                    const int d1 = direct ? gv.nbr_ptr[dir][v + 1] : 0;
-                    for (int p = d0; p < d1; ++p) {
-                        const int u = gv.nbr_idx[dir][p];
-                        bit |= (u == cur) | reach[u];
-                    }
-                    my_bit[ct] = bit;
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 frag =
+                        *reinterpret_cast<const bf16x8 *>(&actbuf[n & 1][ct][col][32 * ks + 8 * kg]);
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
-                        float sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    for (int t = 0; t < TPW; ++t)
 #pragma unroll
-                        for (int e = 0; e < kMaxEnt; ++e) {
-                            if (e < cnt) {
-                                const float4 *src = reinterpret_cast<const float4 *>(
-                                    msgtab + slot[e] * H + 32 * ks + 8 * kg);
-                                const float4 x0 = src[0], x1 = src[1];
-                                sum[0] += x0.x; sum[1] += x0.y; sum[2] += x0.z; sum[3] += x0.w;
-                                sum[4] += x1.x; sum[5] += x1.y; sum[6] += x1.z; sum[7] += x1.w;
-                            }
-                        }
-                        for (int p = d0; p < d1; ++p) {    // rows too wide for the chunk record
-                            const float4 *src = reinterpret_cast<const float4 *>(
-                                msg + static_cast<size_t>(gv.nbr_idx[dir][p]) * H + 32 * ks + 8 * kg);
-                            const float4 x0 = src[0], x1 = src[1];
-                            sum[0] += x0.x; sum[1] += x0.y; sum[2] += x0.z; sum[3] += x0.w;
-                            sum[4] += x1.x; sum[5] += x1.y; sum[6] += x1.z; sum[7] += x1.w;
-                        }
-                        bf16x8 frag;
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) frag[i] = split_part(sum[i], spart);
-#pragma unroll
-                        for (int t = 0; t < TPW; ++t)
-#pragma unroll
-                            for (int ws = 0; ws < WS; ++ws)
-                                acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    A[n][t][ks][ws], frag, acc[t][ct], 0, 0, 0);
-                    }
-                } else {
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
-                        const bf16x8 frag = *reinterpret_cast<const bf16x8 *>(
-                            &actbuf[(n - 1) & 1][ct][col][32 * ks + 8 * kg]);
-#pragma unroll
-                        for (int t = 0; t < TPW; ++t)
-#pragma unroll
-                            for (int ws = 0; ws < WS; ++ws)
-                                acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    A[n][t][ks][ws], frag, acc[t][ct], 0, 0, 0);
-                    }
+                        for (int ws = 0; ws < WS; ++ws)
+                            acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[n][t][ks][ws], frag,
+                                                                                 acc[t][ct], 0, 0, 0);
                 }
             }
 
@@ -285,67 +300,92 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
                     if (ct >= ntile) break;
                     const float4 bv = *reinterpret_cast<const float4 *>(bias_lds + n * H + mt * 16 + 4 * kg);
                     const float bias4[4] = {bv.x, bv.y, bv.z, bv.w};
-                    f32x4 y;
+                    float y[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const float a = acc[t][ct][i];
-                        y[i] = fmaxf(a + row_shl<1>(a) + row_shl<2>(a) + bias4[i], 0.0f);
+                        y[i] = fmaxf(add_row_shl<2>(add_row_shl<1>(a, a), a) + bias4[i], 0.0f);
                     }
                     const int r = ct * kTileNodes + jrow;
                     if (!(own && r < rows)) continue;
-                    const int v = v0[ct];
                     if (n == L - 1) {                    // end of g: residual update of s_v
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) y[i] += res[t][ct][i];
-                        *reinterpret_cast<float4 *>(P.emb + static_cast<size_t>(v) * 2 * H + dir * H +
-                                                    mt * 16 + 4 * kg) = float4{y[0], y[1], y[2], y[3]};
+                        const float4 x = *reinterpret_cast<const float4 *>(
+                            &resbuf[par][r * H + mt * 16 + 4 * kg]);
+                        y[0] += x.x; y[1] += x.y; y[2] += x.z; y[3] += x.w;
+                        const float4 out{y[0], y[1], y[2], y[3]};
+                        *reinterpret_cast<float4 *>(P.emb + static_cast<size_t>(vtab[r]) * 2 * H + dir * H +
+                                                    mt * 16 + 4 * kg) = out;
+                        if (P.write_xb)
+                            *reinterpret_cast<float4 *>(xb + static_cast<size_t>(m0.x + r) * H + mt * 16 +
+                                                        4 * kg) = out;
                     }
                     if (n == NL - 1) {                   // end of f: the message of v
                         const float4 out{y[0], y[1], y[2], y[3]};
-                        *reinterpret_cast<float4 *>(msg + static_cast<size_t>(v) * H + mt * 16 + 4 * kg) = out;
-                        *reinterpret_cast<float4 *>(msgtab + ((c - c_begin) % RING * CH + r) * H + mt * 16 +
+                        *reinterpret_cast<float4 *>(msg + static_cast<size_t>(vtab[r]) * H + mt * 16 +
                                                     4 * kg) = out;
+                        *reinterpret_cast<float4 *>(msgtab + (par * CH + r) * H + mt * 16 + 4 * kg) = out;
                     } else {
-                        bf16x4 ph, pm, pl;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            __bf16 a, b2, c2;
-                            split3(y[i], a, b2, c2);
-                            ph[i] = a;
-                            pm[i] = b2;
-                            pl[i] = c2;
-                        }
-                        __bf16 *dst = &actbuf[n & 1][ct][col][mt * 16 + 4 * kg];
-                        *reinterpret_cast<bf16x4 *>(dst) = ph;
-                        *reinterpret_cast<bf16x4 *>(dst + LDA) = pm;
-                        *reinterpret_cast<bf16x4 *>(dst + 2 * LDA) = pl;
+                        const Split4 sp = split4(y);
+                        __bf16 *dst = &actbuf[(n + 1) & 1][ct][col][mt * 16 + 4 * kg];
+                        *reinterpret_cast<uint2 *>(dst) = sp.hi;
+                        *reinterpret_cast<uint2 *>(dst + LDA) = sp.mid;
+                        *reinterpret_cast<uint2 *>(dst + 2 * LDA) = sp.lo;
                     }
                 }
             }
+
             if (n == NL - 1) {
-                // reachability bits of this chunk's nodes, then the staged far messages
-                if (wave == 0 && kg == 0 && own) {
+                // reachability bits of this chunk's nodes, then the staged data of chunk c + 1
 #pragma unroll
-                    for (int ct = 0; ct < NT; ++ct) {
-                        const int r = ct * kTileNodes + jrow;
-                        if (ct < ntile && r < rows) {
-                            reach[v0[ct]] = static_cast<uint8_t>(my_bit[ct]);
-                            flagtab[(c - c_begin) % RING * CH + r] =
-                                static_cast<uint8_t>(my_bit[ct] | (v0[ct] == cur));
-                        }
+                for (int i = 0; i < PGN; ++i) {
+                    const int e = tid + i * kThreads;
+                    const int r = e / TPR, q = e - r * TPR;
+                    if (q == 0 && r < rows) {
+                        reach[vg0[i]] = static_cast<uint8_t>(my_bit[i]);
+                        flagtab[par * CH + r] = static_cast<uint8_t>(my_bit[i] | (vg0[i] == cur));
                     }
+                    if (has_next && r < m1.y)
+                        *reinterpret_cast<float4 *>(&resbuf[par ^ 1][r * H + 4 * q]) = pr[i];
                 }
 #pragma unroll
                 for (int i = 0; i < PFN; ++i) {
                     const int e = tid + i * kThreads;
                     const int f = e / TPR, q = e - f * TPR;
                     if (has_next && f < m1.z) {
-                        const int slot = RING * CH + ((c + 1 - c_begin) & 1) * FCAP + f;
+                        const int slot = RING * CH + (par ^ 1) * FCAP + f;
                         *reinterpret_cast<float4 *>(msgtab + slot * H + 4 * q) = pf[i];
-                        if (q == 0) flagtab[slot] = static_cast<uint8_t>(pf_flag[i]);
+                        if (q == 0) flagtab[slot] = static_cast<uint8_t>(pf_reach[i] != 0);
                     }
                 }
-                __syncthreads();     // also makes this chunk's global messages visible
+                lds_barrier();
+            } else if (n == 0) {
+                // Global stores of the previous chunk are complete after this barrier; only
+                // then are the loads for the next chunk issued (they may read such stores).
+                full_barrier();
+#pragma unroll
+                for (int i = 0; i < PFN; ++i) {
+                    const int e = tid + i * kThreads;
+                    const int f = e / TPR, q = e - f * TPR;
+                    const bool live = has_next && f < m1.z && fid1[i] >= 0;
+                    const int u = live ? fid1[i] : vg0[0];       // any valid row when not live
+                    pf[i] = *reinterpret_cast<const float4 *>(msg + static_cast<size_t>(u) * H + 4 * q);
+                    pf_reach[i] = reach[u] | (u == cur ? 2 : 0);
+                }
+                m2 = load_uniform(plan.meta + clampc(c + 2));
+#pragma unroll
+                for (int i = 0; i < PGN; ++i) {
+                    const int e = tid + i * kThreads;
+                    const int r = e / TPR, q = e - r * TPR;
+                    const int rr = (r < m1.y) ? r : 0;
+                    pr[i] = *reinterpret_cast<const float4 *>(xb + static_cast<size_t>(m1.x + rr) * H + 4 * q);
+                    ent0[i] = plan.ent[static_cast<size_t>(clampc(c + 1)) * CH + rr];
+                    vg1[i] = order[m1.x + rr];
+                }
+#pragma unroll
+                for (int i = 0; i < PFN; ++i) {     // ids staged two chunks ahead of their data
+                    const int f = (tid + i * kThreads) / TPR;
+                    fid1[i] = (f < FCAP) ? plan.far[static_cast<size_t>(clampc(c + 2)) * FCAP + f] : -1;
+                }
             } else {
                 lds_barrier();
             }
@@ -354,12 +394,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
         m0 = m1;
         m1 = m2;
 #pragma unroll
-        for (int ct = 0; ct < NT; ++ct) {
-            ent0[ct] = ent1[ct];
-            v0[ct] = v1[ct];
-        }
-#pragma unroll
-        for (int i = 0; i < PFN; ++i) fid1[i] = fid2[i];
+        for (int i = 0; i < PGN; ++i) vg0[i] = vg1[i];
     }
 }
 
@@ -417,10 +452,10 @@ bool sweep_mfma_supported(int H, int L, int weight_dtype)
 
 void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                        const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
-                       hipStream_t s)
+                       bool more_sweeps, hipStream_t s)
 {
     if (gv.B == 0) return;
-    SweepParams P{gv, wfrag, bias, ws.emb, ws.msg, ws.reach, fa.cur_node};
+    SweepParams P{gv, wfrag, bias, ws.emb, ws.xb, ws.msg, ws.reach, fa.cur_node, more_sweeps ? 1 : 0};
     const dim3 grid(2 * gv.B), block(kThreads);
 #define PL_CASE(HH, WW, LL)                                                      \
     if (mv.H == HH && WS == WW && mv.L == LL) {                                  \

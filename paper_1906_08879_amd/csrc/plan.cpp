@@ -50,7 +50,7 @@ int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
         for (int32_t c = 0; c < n_chunks; ++c) {
             int32_t *meta = &P.meta[static_cast<size_t>(first + c) * 4];
             int32_t *far = &P.far[static_cast<size_t>(first + c) * kFarCap];
-            int32_t n_far = 0;
+            int32_t n_far = 0, max_ent = 0;
             const int32_t p0 = meta[0] - static_cast<int32_t>(n0);
             for (int32_t r = 0; r < meta[1]; ++r) {
                 uint16_t *ent = &P.ent[(static_cast<size_t>(first + c) * kChunkRows + r) * 8];
@@ -68,11 +68,24 @@ int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
                     }
                     direct = n_far + new_far > kFarCap;
                 }
-                if (direct) {            // the kernel sums this row straight from global memory
+                if (direct) {            // the row's list goes to the overflow array
+                    const uint32_t off = static_cast<uint32_t>(P.ovf.size());
                     ent[0] = 0xFFFF;
+                    ent[1] = static_cast<uint16_t>(off & 0xFFFF);
+                    ent[2] = static_cast<uint16_t>(off >> 16);
+                    ent[3] = static_cast<uint16_t>(deg & 0xFFFF);
+                    ent[4] = static_cast<uint16_t>(deg >> 16);
+                    for (int64_t e = e0; e < e1; ++e) {
+                        const int32_t u = idx[e];
+                        if (c - node_chunk[u] <= kRing)
+                            P.ovf.push_back(-1 - ((node_chunk[u] % kRing) * kChunkRows + node_row[u]));
+                        else
+                            P.ovf.push_back(static_cast<int32_t>(n0) + u);
+                    }
                     continue;
                 }
                 ent[0] = static_cast<uint16_t>(deg);
+                max_ent = std::max(max_ent, deg);
                 for (int64_t e = e0; e < e1; ++e) {
                     const int32_t u = idx[e];
                     int32_t slot;
@@ -88,6 +101,7 @@ int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
                 }
             }
             meta[2] = n_far;
+            meta[3] = max_ent;
         }
     }
     P.n_chunks = static_cast<int64_t>(P.meta.size() / 4);
