@@ -16,10 +16,10 @@
 //     prefetched from HBM one chunk ahead into the same table, so the gather on the
 //     critical path reads LDS only.  Chunk records, node ids and the residual inputs (kept
 //     in bucket order, so a chunk's rows are contiguous) are prefetched the same way.
-//   * One barrier per chunk (after the first layer) completes global stores; the others
-//     order LDS traffic only, so prefetches stay in flight across them.  A message written
-//     to HBM in chunk c is therefore only read back from HBM from chunk c + 3 on; nearer
-//     consumers use the LDS table.
+//   * Barriers order LDS traffic only, so global prefetches stay in flight across them.
+//     A message written to HBM in chunk c is only read back from HBM from chunk c + 3 on
+//     (nearer consumers use the LDS table); by then the store has retired, because each
+//     wave waits once per chunk for a batch of loads that it issued after that store.
 //   * A single wave per SIMD runs a dependent chain, so the kernel is bound by instruction
 //     issue, not by bandwidth: the split is done by truncation (4 VALU ops per value), the
 //     column sums are single DPP adds, and the gather is spread over all 256 lanes.
@@ -31,6 +31,7 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int CH = kChunkRows, FCAP = kFarCap, RING = kRing;
@@ -178,7 +179,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
     auto clampc = [&](int c) { return c < c_end ? c : c_end - 1; };
     int4 m0 = load_uniform(plan.meta + c_begin);
     int4 m1 = load_uniform(plan.meta + clampc(c_begin + 1));
-    uint4 ent0[PGN];         // neighbour record of the item's row, chunk c
+    u32x4 ent0[PGN];         // neighbour record of the item's row, chunk c
     int vg0[PGN];            // node id of the item's row, chunk c
     int fid1[PFN];           // far sources of chunk c + 1
 #pragma unroll
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
         const int e = tid + i * kThreads;
         const int r = e / TPR, q = e - r * TPR;
         const int rr = r < m0.y ? r : 0;
-        ent0[i] = plan.ent[static_cast<size_t>(c_begin) * CH + rr];
+        ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(c_begin) * CH + rr);
         vg0[i] = order[m0.x + rr];
         if (r < m0.y)                          // residual inputs of the first chunk
             *reinterpret_cast<float4 *>(&resbuf[0][r * H + 4 * q]) =
@@ -260,9 +261,12 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
         }
         lds_barrier();
 
-        float4 pf[PFN];          // far messages of chunk c + 1, in flight during the later layers
+        // Plain vector types on purpose: arrays of the HIP float4 class that are written in one
+        // unrolled branch and read in another are not always split into registers.
+        f32x4 pf[PFN];           // far messages of chunk c + 1, in flight during the later layers
         int pf_reach[PFN];
-        float4 pr[PGN];          // residual inputs of chunk c + 1
+        bool pf_cur[PFN];
+        f32x4 pr[PGN];           // residual inputs of chunk c + 1
         int vg1[PGN];
         int4 m2 = m1;
         f32x4 acc[TPW][NT];
@@ -335,6 +339,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
             }
 
             if (n == NL - 1) {
+                // Wait for this wave's prefetch batch whether or not a lane uses it: the stores
+                // that preceded it are then complete too (see above).
+#pragma unroll
+                for (int i = 0; i < PFN; ++i) asm volatile("" ::"v"(pf[i][0]), "v"(pf_reach[i]));
+                // An offset the compiler cannot see through, defined only here: without it the
+                // staged LDS stores below are scheduled right behind their loads, which puts
+                // the whole HBM latency back on the critical path.
+                int late = 0;
+                asm volatile("" : "+v"(late));
                 // reachability bits of this chunk's nodes, then the staged data of chunk c + 1
 #pragma unroll
                 for (int i = 0; i < PGN; ++i) {
@@ -345,7 +358,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
                         flagtab[par * CH + r] = static_cast<uint8_t>(my_bit[i] | (vg0[i] == cur));
                     }
                     if (has_next && r < m1.y)
-                        *reinterpret_cast<float4 *>(&resbuf[par ^ 1][r * H + 4 * q]) = pr[i];
+                        *reinterpret_cast<f32x4 *>(&resbuf[par ^ 1][r * H + 4 * q + late]) = pr[i];
                 }
 #pragma unroll
                 for (int i = 0; i < PFN; ++i) {
@@ -353,23 +366,32 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
                     const int f = e / TPR, q = e - f * TPR;
                     if (has_next && f < m1.z) {
                         const int slot = RING * CH + (par ^ 1) * FCAP + f;
-                        *reinterpret_cast<float4 *>(msgtab + slot * H + 4 * q) = pf[i];
-                        if (q == 0) flagtab[slot] = static_cast<uint8_t>(pf_reach[i] != 0);
+                        *reinterpret_cast<f32x4 *>(msgtab + slot * H + 4 * q + late) = pf[i];
+                        if (q == 0) flagtab[slot + late] = static_cast<uint8_t>((pf_reach[i] != 0) | pf_cur[i]);
                     }
                 }
                 lds_barrier();
             } else if (n == 0) {
-                // Global stores of the previous chunk are complete after this barrier; only
-                // then are the loads for the next chunk issued (they may read such stores).
-                full_barrier();
+                // The loads for the next chunk are issued here, one layer into the chunk.
+                // They may read messages that this workgroup stored to HBM at least two
+                // chunks ago.  Those stores are complete: vector memory operations of a wave
+                // retire in order, and every wave waited for its own previous batch of these
+                // loads (issued after those stores) before the last barrier of the previous
+                // chunk (see the end-of-chunk stage below).
+                lds_barrier();
 #pragma unroll
                 for (int i = 0; i < PFN; ++i) {
                     const int e = tid + i * kThreads;
                     const int f = e / TPR, q = e - f * TPR;
                     const bool live = has_next && f < m1.z && fid1[i] >= 0;
-                    const int u = live ? fid1[i] : vg0[0];       // any valid row when not live
-                    pf[i] = *reinterpret_cast<const float4 *>(msg + static_cast<size_t>(u) * H + 4 * q);
-                    pf_reach[i] = reach[u] | (u == cur ? 2 : 0);
+                    const int u = live ? fid1[i] : 0;
+                    // lanes without a far source read a constant row instead, so that every
+                    // wave has a load of this batch to wait for
+                    const float *src = live ? msg + static_cast<size_t>(u) * H + 4 * q : P.bias + 4 * q;
+                    const uint8_t *rsrc = live ? reach + u : reinterpret_cast<const uint8_t *>(P.bias);
+                    pf[i] = *reinterpret_cast<const f32x4 *>(src);
+                    pf_reach[i] = *rsrc;                 // combined with pf_cur at the end of the chunk
+                    pf_cur[i] = live && u == cur;
                 }
                 m2 = load_uniform(plan.meta + clampc(c + 2));
 #pragma unroll
@@ -377,8 +399,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
                     const int e = tid + i * kThreads;
                     const int r = e / TPR, q = e - r * TPR;
                     const int rr = (r < m1.y) ? r : 0;
-                    pr[i] = *reinterpret_cast<const float4 *>(xb + static_cast<size_t>(m1.x + rr) * H + 4 * q);
-                    ent0[i] = plan.ent[static_cast<size_t>(clampc(c + 1)) * CH + rr];
+                    pr[i] = *reinterpret_cast<const f32x4 *>(xb + static_cast<size_t>(m1.x + rr) * H + 4 * q);
+                    ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(clampc(c + 1)) * CH + rr);
                     vg1[i] = order[m1.x + rr];
                 }
 #pragma unroll
