@@ -78,6 +78,8 @@ struct pl_weights {
     // matrix-core sweep: packed A fragments and biases (null when the shape is not covered)
     uint16_t *d_wfrag = nullptr;
     float *d_sweep_bias = nullptr;
+    uint16_t *d_pool_frag = nullptr;
+    float *d_pool_bias = nullptr;
     int sweep_ws = 0;               // bf16 parts per weight: 1 (bf16 weights) or 3 (fp32)
     int path = 0;                   // 0 = fastest available kernels, 1 = generic fp32 kernels
 };
@@ -318,13 +320,18 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
                 launch_sweep_generic(gv, mv, g->ws, fa, k == 0, s);
         }
     }
+    const bool pool_mfma = w->d_pool_frag && w->path == 0;
     {
         StageScope scope(g->timer, PL_STAGE_POOL, s);
-        launch_pool_generic(gv, mv, g->ws, fa, s);
+        if (pool_mfma)
+            launch_pool_mfma(gv, mv, g->ws, fa, reinterpret_cast<const uint4 *>(w->d_pool_frag),
+                             w->d_pool_bias, w->sweep_ws, s);
+        else
+            launch_pool_generic(gv, mv, g->ws, fa, s);
     }
     {
         StageScope scope(g->timer, PL_STAGE_HEAD, s);
-        launch_head_generic(gv, mv, g->ws, fa, s);
+        launch_head_generic(gv, mv, g->ws, fa, pool_mfma ? kPoolSlices : g->ws.n_chunks, s);
     }
     if (out_node_emb)
         PL_HIP(hipMemcpyAsync(out_node_emb, g->ws.emb,
@@ -499,6 +506,16 @@ int pl_weights_create(const pl_model_cfg *cfg, const float *host_blob, size_t n_
             return rc;
         }
     }
+    if (pool_mfma_supported(cfg->H, cfg->n_layers, cfg->weight_dtype)) {
+        std::vector<uint16_t> frag;
+        std::vector<float> pool_bias;
+        w->sweep_ws = cfg->weight_dtype == PL_WEIGHTS_BF16 ? 1 : 3;
+        pack_pool_weights(w->view, w->host_blob.data(), w->sweep_ws, &frag, &pool_bias);
+        if ((rc = upload(frag, &w->d_pool_frag)) || (rc = upload(pool_bias, &w->d_pool_bias))) {
+            pl_weights_destroy(w);
+            return rc;
+        }
+    }
     *out = w;
     return PL_OK;
 }
@@ -517,6 +534,8 @@ int pl_weights_destroy(pl_weights *w)
     (void)hipFree(w->d_blob);
     (void)hipFree(w->d_wfrag);
     (void)hipFree(w->d_sweep_bias);
+    (void)hipFree(w->d_pool_frag);
+    (void)hipFree(w->d_pool_bias);
     delete w;
     return PL_OK;
 }

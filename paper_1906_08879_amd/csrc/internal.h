@@ -150,7 +150,16 @@ void launch_classes(const GraphView &gv, const int32_t *cur_node, const uint8_t 
 void launch_pool_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                          const ForwardArgs &fa, hipStream_t s);
 void launch_head_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
-                         const ForwardArgs &fa, hipStream_t s);
+                         const ForwardArgs &fa, int max_chunks, hipStream_t s);
+
+// ---- matrix-core pooling (kernels_pool_mfma.hip); writes ws.partial as [B, kPoolSlices, 3G, H]
+constexpr int kPoolSlices = 4;
+bool pool_mfma_supported(int H, int L, int weight_dtype);
+void pack_pool_weights(const ModelView &mv, const float *blob, int WS, std::vector<uint16_t> *frag,
+                       std::vector<float> *bias);
+void launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
+                      const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
+                      hipStream_t s);
 
 // ---- matrix-core sweep (kernels_mfma.hip)
 bool sweep_mfma_supported(int H, int L, int weight_dtype);

@@ -455,7 +455,7 @@ void launch_pool_generic(const GraphView &gv, const ModelView &mv, const Workspa
 }
 
 void launch_head_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
-                         const ForwardArgs &fa, hipStream_t s)
+                         const ForwardArgs &fa, int max_chunks, hipStream_t s)
 {
     if (gv.B == 0) return;
     const size_t lds =
@@ -463,7 +463,7 @@ void launch_head_generic(const GraphView &gv, const ModelView &mv, const Workspa
 #define CALL(R)                                                                               \
     allow_lds(k_head_generic<R>, lds);                                                        \
     hipLaunchKernelGGL(k_head_generic<R>, dim3(gv.B), dim3(kThreads), lds, s, gv, mv, ws.emb, \
-                       ws.partial, fa.cur_node, ws.n_chunks, fa.out_logits, fa.out_probs,     \
+                       ws.partial, fa.cur_node, max_chunks, fa.out_logits, fa.out_probs,      \
                        fa.out_pooled)
     PL_DISPATCH_RPT(pick_rpt(mv.H), CALL)
 #undef CALL
