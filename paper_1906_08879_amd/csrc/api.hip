@@ -228,6 +228,8 @@ void free_workspace(Workspace &ws)
     (void)hipFree(ws.xb);
     (void)hipFree(ws.reach);
     (void)hipFree(ws.partial);
+    (void)hipFree(ws.zbuf);
+    (void)hipFree(ws.hidp);
     ws = Workspace();
 }
 
@@ -257,6 +259,10 @@ int ensure_workspace(pl_graph_batch *g, const ModelView &mv)
     ws.n_chunks = 8;
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.partial),
                      sizeof(float) * (static_cast<size_t>(g->host.B) * ws.n_chunks * 3 * mv.G * H + 4)));
+    const size_t B = static_cast<size_t>(g->host.B);
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.zbuf), sizeof(float) * (B * mv.Z + 4)));
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.hidp),
+                     sizeof(float) * (static_cast<size_t>((mv.Z + 255) / 256) * B * H + 4)));
     ws.H = mv.H;
     ws.G = mv.G;
     return PL_OK;

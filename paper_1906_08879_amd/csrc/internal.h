@@ -122,6 +122,8 @@ struct Workspace {
     float *xb = nullptr;        // [2, n_tot, H]  sweep input in bucket order (matrix-core path)
     uint8_t *reach = nullptr;   // [2, n_tot]   0: descendant-of-v* bit, 1: ancestor-of-v* bit
     float *partial = nullptr;   // [B, n_chunks_max, 3G, H] pooling partial sums
+    float *zbuf = nullptr;      // [B, Z] policy inputs
+    float *hidp = nullptr;      // [ceil(Z / 256), B, H] partial products of policy layer 1
     int32_t *chunk_off = nullptr; // [B+1] first pooling chunk of each graph
     int32_t n_chunks = 0;
     int32_t H = 0, G = 0;

@@ -310,67 +310,134 @@ __global__ __launch_bounds__(kThreads) void k_pool_generic(GraphView gv, ModelVi
 }
 
 // ------------------------------------------------------------------ policy head
-// One workgroup per graph: P[i][d] = sum of the chunk partials (fixed order);
-// q[i][d] = h_i(P[i][d]) (also for empty groups); z = [e_{v*} ; q]; two-layer policy
+// Three small kernels, parallel over (graph, set), over (16 graphs, slice of Z) and over
+// graphs: q[i][d] = h_i(P[i][d]) (also for empty groups); z = [e_{v*} ; q]; two-layer policy
 // network with a softmax over devices (Appendix A.7).
+constexpr int kZSlice = 256;   // inputs of policy layer 1 handled by one workgroup
+
+// (1) workgroup (set, graph): P[set] = sum of the pooling partials in slice order, then h_set;
+// set 0 also copies the current node's own embedding into z.
 template <int RPT>
-__global__ __launch_bounds__(kThreads) void k_head_generic(GraphView gv, ModelView mv,
-                                                           const float *__restrict__ emb,
-                                                           const float *__restrict__ partial,
-                                                           const int32_t *__restrict__ cur_node,
-                                                           int max_chunks,
-                                                           float *__restrict__ out_logits,
-                                                           float *__restrict__ out_probs,
-                                                           float *__restrict__ out_pooled)
+__global__ __launch_bounds__(kThreads) void k_head_sets(GraphView gv, ModelView mv,
+                                                        const float *__restrict__ emb,
+                                                        const float *__restrict__ partial,
+                                                        const int32_t *__restrict__ cur_node,
+                                                        int max_chunks, float *__restrict__ zbuf,
+                                                        float *__restrict__ out_pooled)
 {
     extern __shared__ float lds[];
-    const int H = mv.H, G = mv.G, D = mv.D, L = mv.L, Z = mv.Z;
-    const int b = blockIdx.x, tid = threadIdx.x;
+    const int H = mv.H, G = mv.G, L = mv.L, Z = mv.Z;
+    const int set = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const int n0 = gv.node_off[b], n_b = gv.node_off[b + 1] - n0;
     int chunks = (n_b + kPoolChunk - 1) / kPoolChunk;
     if (chunks > max_chunks) chunks = max_chunks;
-    const int cl = cur_node[b];
-    const bool cur_ok = (cl >= 0 && cl < n_b);
-
-    float *P = lds;                     // [3G][H]
-    float *z = P + 3 * G * H;           // [Z]
-    float *buf_a = z + Z;               // [kTile][H]
-    float *buf_b = buf_a + kTile * H;   // [kTile][H]
-    const float *src = partial + static_cast<size_t>(b) * max_chunks * 3 * G * H;
-    for (int i = tid; i < 3 * G * H; i += kThreads) {
+    float *P = lds;                     // [G][H]
+    float *buf_a = P + kTile * H;       // [kTile][H]
+    float *buf_b = buf_a + kTile * H;
+    float *z = zbuf + static_cast<size_t>(b) * Z;
+    const float *src = partial + (static_cast<size_t>(b) * max_chunks * 3 + set) * G * H;
+    for (int i = tid; i < G * H; i += kThreads) {
         float s = 0.0f;
         for (int c = 0; c < chunks; ++c) s += src[static_cast<size_t>(c) * 3 * G * H + i];
         P[i] = s;
-        if (out_pooled) out_pooled[static_cast<size_t>(b) * 3 * G * H + i] = s;
+        if (out_pooled) out_pooled[(static_cast<size_t>(b) * 3 + set) * G * H + i] = s;
     }
-    for (int i = tid; i < 2 * H; i += kThreads)
-        z[i] = cur_ok ? emb[static_cast<size_t>(n0 + cl) * 2 * H + i] : 0.0f;
-    __syncthreads();
-    for (int set = 0; set < 3; ++set) {
-        const MlpRef &hn = mv.h[set];
-        const float *in = P + set * G * H;
-        for (int l = 0; l < L; ++l) {
-            float *out = (l == L - 1) ? z + (2 + set * G) * H : ((l & 1) ? buf_b : buf_a);
-            dense_layer<RPT>(mv.blob + hn.layer[l].w, mv.blob + hn.layer[l].b, H, H, in, H, out, H,
-                             G, true);
-            __syncthreads();
-            in = out;
-        }
+    if (set == 0) {
+        const int cl = cur_node[b];
+        const bool ok = cl >= 0 && cl < n_b;
+        for (int i = tid; i < 2 * H; i += kThreads)
+            z[i] = ok ? emb[static_cast<size_t>(n0 + cl) * 2 * H + i] : 0.0f;
     }
-    dense_layer<RPT>(mv.blob + mv.pol1.w, mv.blob + mv.pol1.b, Z, H, z, Z, buf_a, H, 1, true);
     __syncthreads();
-    dense_layer<RPT>(mv.blob + mv.pol2.w, mv.blob + mv.pol2.b, H, D, buf_a, H, buf_b, D, 1, false);
+    const MlpRef &hn = mv.h[set];
+    const float *in = P;
+    for (int l = 0; l < L; ++l) {
+        float *out = (l & 1) ? buf_b : buf_a;
+        dense_layer<RPT>(mv.blob + hn.layer[l].w, mv.blob + hn.layer[l].b, H, H, in, H, out, H, G, true);
+        __syncthreads();
+        in = out;
+    }
+    for (int i = tid; i < G * H; i += kThreads) z[(2 + set * G) * H + i] = in[i];
+}
+
+// (2) workgroup (row tile, slice): partial products of policy layer 1 for 16 graphs and one
+// slice of z: hidp[slice][b][j] = sum over k in the slice of z[b][k] W1[k][j].
+template <int RPT>
+__global__ __launch_bounds__(kThreads) void k_head_policy1(ModelView mv, int B,
+                                                           const float *__restrict__ zbuf,
+                                                           float *__restrict__ hidp)
+{
+    __shared__ float x[kTile][kZSlice];
+    const int H = mv.H, Z = mv.Z, tid = threadIdx.x;
+    const int b0 = blockIdx.x * kTile, slice = blockIdx.y;
+    const int k0 = slice * kZSlice, kn = min(kZSlice, Z - k0);
+    const int rows = min(kTile, B - b0);
+    for (int i = tid; i < rows * kZSlice; i += kThreads) {
+        const int r = i / kZSlice, k = i - r * kZSlice;
+        x[r][k] = k < kn ? zbuf[static_cast<size_t>(b0 + r) * Z + k0 + k] : 0.0f;
+    }
+    __syncthreads();
+    // same thread mapping as dense_layer, without bias and activation
+    int groups = kThreads / H;
+    if (groups > kTile) groups = kTile;
+    const int grp = tid / H, j = tid - grp * H;
+    if (grp >= groups || grp >= rows) return;
+    float acc[RPT];
+    int xoff[RPT];
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        acc[i] = 0.0f;
+        xoff[i] = min(grp + i * groups, rows - 1) * kZSlice;
+    }
+    const float *W = mv.blob + mv.pol1.w + static_cast<size_t>(k0) * H;
+    const float *xf = &x[0][0];
+    for (int k = 0; k < kn; ++k) {
+        const float w = W[static_cast<size_t>(k) * H + j];
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) acc[i] = fmaf(xf[xoff[i] + k], w, acc[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        const int r = grp + i * groups;
+        if (r < rows) hidp[(static_cast<size_t>(slice) * B + b0 + r) * H + j] = acc[i];
+    }
+}
+
+// (3) one workgroup per graph: hidden = relu(sum of the slices + bias), output layer, softmax.
+__global__ __launch_bounds__(64) void k_head_out(GraphView gv, ModelView mv,
+                                                 const float *__restrict__ hidp, int n_slices,
+                                                 const int32_t *__restrict__ cur_node,
+                                                 float *__restrict__ out_logits,
+                                                 float *__restrict__ out_probs)
+{
+    __shared__ float hid[kMaxH];
+    __shared__ float logit[kMaxD];
+    const int H = mv.H, D = mv.D, b = blockIdx.x, tid = threadIdx.x;
+    const int n_b = gv.node_off[b + 1] - gv.node_off[b];
+    const int cl = cur_node[b];
+    const bool cur_ok = cl >= 0 && cl < n_b;
+    for (int j = tid; j < H; j += 64) {
+        float s = mv.blob[mv.pol1.b + j];
+        for (int sl = 0; sl < n_slices; ++sl) s += hidp[(static_cast<size_t>(sl) * gv.B + b) * H + j];
+        hid[j] = fmaxf(s, 0.0f);
+    }
+    __syncthreads();
+    if (tid < D) {
+        const float *W = mv.blob + mv.pol2.w;
+        float s = mv.blob[mv.pol2.b + tid];
+        for (int k = 0; k < H; ++k) s = fmaf(hid[k], W[k * D + tid], s);
+        logit[tid] = s;
+    }
     __syncthreads();
     if (tid == 0) {
-        float mx = buf_b[0];
-        for (int d = 1; d < D; ++d) mx = fmaxf(mx, buf_b[d]);
+        float mx = logit[0];
+        for (int d = 1; d < D; ++d) mx = fmaxf(mx, logit[d]);
         float tot = 0.0f;
-        for (int d = 0; d < D; ++d) tot += expf(buf_b[d] - mx);
+        for (int d = 0; d < D; ++d) tot += expf(logit[d] - mx);
         const float bad = __builtin_nanf("");   // no valid current node: nothing to decide
         for (int d = 0; d < D; ++d) {
-            out_logits[static_cast<size_t>(b) * D + d] = cur_ok ? buf_b[d] : bad;
-            if (out_probs)
-                out_probs[static_cast<size_t>(b) * D + d] = cur_ok ? expf(buf_b[d] - mx) / tot : bad;
+            out_logits[static_cast<size_t>(b) * D + d] = cur_ok ? logit[d] : bad;
+            if (out_probs) out_probs[static_cast<size_t>(b) * D + d] = cur_ok ? expf(logit[d] - mx) / tot : bad;
         }
     }
 }
@@ -458,15 +525,18 @@ void launch_head_generic(const GraphView &gv, const ModelView &mv, const Workspa
                          const ForwardArgs &fa, int max_chunks, hipStream_t s)
 {
     if (gv.B == 0) return;
-    const size_t lds =
-        sizeof(float) * (static_cast<size_t>(3) * mv.G * mv.H + mv.Z + 2 * kTile * mv.H);
-#define CALL(R)                                                                               \
-    allow_lds(k_head_generic<R>, lds);                                                        \
-    hipLaunchKernelGGL(k_head_generic<R>, dim3(gv.B), dim3(kThreads), lds, s, gv, mv, ws.emb, \
-                       ws.partial, fa.cur_node, max_chunks, fa.out_logits, fa.out_probs,      \
-                       fa.out_pooled)
+    const size_t lds = sizeof(float) * 3 * kTile * mv.H;
+    const int n_slices = (mv.Z + kZSlice - 1) / kZSlice;
+    const int row_tiles = (gv.B + kTile - 1) / kTile;
+#define CALL(R)                                                                                  \
+    hipLaunchKernelGGL(k_head_sets<R>, dim3(3, gv.B), dim3(kThreads), lds, s, gv, mv, ws.emb,    \
+                       ws.partial, fa.cur_node, max_chunks, ws.zbuf, fa.out_pooled);             \
+    hipLaunchKernelGGL(k_head_policy1<R>, dim3(row_tiles, n_slices), dim3(kThreads), 0, s, mv,   \
+                       gv.B, ws.zbuf, ws.hidp)
     PL_DISPATCH_RPT(pick_rpt(mv.H), CALL)
 #undef CALL
+    hipLaunchKernelGGL(k_head_out, dim3(gv.B), dim3(64), 0, s, gv, mv, ws.hidp, n_slices, fa.cur_node,
+                       fa.out_logits, fa.out_probs);
 }
 
 }  // namespace pl
