@@ -52,7 +52,7 @@ int build_layout(int32_t B, const int32_t *n_nodes, const int32_t *n_edges,
                  const int32_t *edge_src, const int32_t *edge_dst, HostLayout *out);
 
 // ---- gather plan of the matrix-core sweep kernel (plan.cpp)
-constexpr int kChunkRows = 10;   // nodes per chunk: two column tiles of five nodes
+constexpr int kChunkRows = 8;    // nodes per chunk: two MFMA row tiles of four nodes
 constexpr int kFarCap = 16;      // far sources staged per chunk
 constexpr int kRing = 2;         // chunks whose messages stay in the LDS table
 constexpr int kMaxEnt = 7;       // neighbours per row held in the chunk record

@@ -2,16 +2,17 @@
 //   a_v = sum_{u in xi(v)} m_u,   s_v <- s_v + g(a_v),   m_v = f(s_v),
 // for H in {32, 64, 128} and one or two layers per network.
 //
-// One workgroup (4 waves) per (graph, direction) walks the graph's levels in chunks of at
-// most 10 nodes.  Design points, all specific to CDNA4:
-//   * v_mfma_f32_16x16x32_bf16 with the WEIGHTS as the A operand (16 output columns x 32 k)
-//     and the node activations as the B operand.  The fp32 activation of a node is split
-//     exactly into three bf16 values (hi, mid, lo); the three parts sit in three adjacent B
-//     columns, so one MFMA multiplies the weights with all three parts of five nodes and
-//     the three result columns are added with DPP row shifts.  This keeps fp32 accuracy at
-//     one third of the MFMA count of three separate passes.
+// One workgroup (one wave per 16 output columns, up to 8 waves) per (graph, direction)
+// walks the graph's levels in chunks of at most 8 nodes.  Design points, all specific to
+// CDNA4:
+//   * v_mfma_f32_16x16x32_bf16 with the node activations as the A operand and the WEIGHTS as
+//     the B operand.  The fp32 activation of a node is split exactly into three bf16 values
+//     (hi, mid, lo) by truncation; the three parts are three ROWS of A (a fourth row is
+//     zero), so a 16-row tile holds four nodes and the three partial products of a node land
+//     in one lane's accumulator registers, where they are added: fp32 accuracy from the bf16
+//     matrix cores without any cross-lane traffic.
 //   * The weight fragments of all layers of one direction live in registers for the whole
-//     kernel (bf16 weights: 128 VGPRs at H = 128); only activations move through LDS.
+//     kernel (bf16 weights: 64 VGPRs per wave at H = 128); only activations move through LDS.
 //   * Messages of the last two chunks stay in an LDS table; messages from older chunks are
 //     prefetched from HBM one chunk ahead into the same table, so the gather on the
 //     critical path reads LDS only.  Chunk records, node ids and the residual inputs (kept
@@ -20,9 +21,9 @@
 //     A message written to HBM in chunk c is only read back from HBM from chunk c + 3 on
 //     (nearer consumers use the LDS table); by then the store has retired, because each
 //     wave waits once per chunk for a batch of loads that it issued after that store.
-//   * A single wave per SIMD runs a dependent chain, so the kernel is bound by instruction
-//     issue, not by bandwidth: the split is done by truncation (4 VALU ops per value), the
-//     column sums are single DPP adds, and the gather is spread over all 256 lanes.
+//   * The kernel runs a dependent chain (about a thousand chunks of four layers per graph),
+//     so it is bound by instruction issue and LDS round trips, not by HBM bandwidth: the
+//     per-layer epilogue is about fifteen instructions per tile.
 #include "internal.h"
 
 namespace pl {
@@ -33,10 +34,9 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
 constexpr int CH = kChunkRows, FCAP = kFarCap, RING = kRing;
-constexpr int kTileNodes = 5;                 // nodes per 16-column MFMA tile (3 columns each)
-constexpr int NT = CH / kTileNodes;           // column tiles per chunk
+constexpr int kTileNodes = 4;                 // nodes per 16-row MFMA tile (hi, mid, lo, zero rows)
+constexpr int NT = CH / kTileNodes;           // row tiles per chunk
 
 // Workgroup barrier that orders LDS traffic only: global prefetches stay outstanding.
 __device__ __forceinline__ void lds_barrier()
@@ -46,57 +46,19 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// Full workgroup barrier: also completes this wave's outstanding global stores and loads.
-__device__ __forceinline__ void full_barrier() { __syncthreads(); }
-
-// acc + (value v of lane l+N in the same row of 16 lanes, 0 past the row's end), in one VALU
-// instruction.  The s_nop covers the VALU-write -> DPP-read hazard, which the compiler
-// cannot see inside inline assembly.
-template <int N>
-__device__ __forceinline__ float add_row_shl(float acc, float v)
-{
-    float r;
-    if constexpr (N == 1)
-        asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %1, %2 row_shl:1 row_mask:0xf bank_mask:0xf bound_ctrl:1"
-                     : "=v"(r)
-                     : "v"(v), "v"(acc));
-    else
-        asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %1, %2 row_shl:2 row_mask:0xf bank_mask:0xf bound_ctrl:1"
-                     : "=v"(r)
-                     : "v"(v), "v"(acc));
-    return r;
-}
-
-// Exact three-way split of four fp32 values into bf16 parts by truncation:
-// x = hi + mid + lo with hi = top 16 bits of x, mid = top 16 bits of (x - hi),
-// lo = x - hi - mid (at most 8 significant bits left).  Returned packed, two bf16 per dword.
-struct Split4 {
-    uint2 hi, mid, lo;
-};
-
 __device__ __forceinline__ uint32_t pack_hi16(float lo_word, float hi_word)
 {
     return __builtin_amdgcn_perm(__float_as_uint(hi_word), __float_as_uint(lo_word), 0x07060302u);
 }
 
-__device__ __forceinline__ Split4 split4(const float (&x)[4])
+__device__ __forceinline__ float trunc_bf16(float x)
 {
-    float r[4], l[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        r[i] = x[i] - __uint_as_float(__float_as_uint(x[i]) & 0xFFFF0000u);
-        l[i] = r[i] - __uint_as_float(__float_as_uint(r[i]) & 0xFFFF0000u);
-    }
-    Split4 s;
-    s.hi = uint2{pack_hi16(x[0], x[1]), pack_hi16(x[2], x[3])};
-    s.mid = uint2{pack_hi16(r[0], r[1]), pack_hi16(r[2], r[3])};
-    s.lo = uint2{pack_hi16(l[0], l[1]), pack_hi16(l[2], l[3])};
-    return s;
+    return __uint_as_float(__float_as_uint(x) & 0xFFFF0000u);
 }
 
 struct SweepParams {
     GraphView gv;
-    const uint4 *wfrag;     // packed A fragments, see pack_sweep_weights()
+    const uint4 *wfrag;     // packed weight fragments, see pack_sweep_weights()
     const float *bias;      // [2 dir][2L layers][H]
     float *emb;             // [n_tot, 2H]   output s_v in node order ([td ; bu])
     float *xb;              // [2, n_tot, H] residual input in bucket order, per direction
@@ -116,29 +78,31 @@ __device__ __forceinline__ int4 load_uniform(const int4 *p)
     return int4{r.x, r.y, r.z, r.w};
 }
 
+constexpr int sweep_waves(int H) { return H / 16 > 8 ? 8 : H / 16; }
+
 template <int H, int WS, int L>
-__global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
+__global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) void k_sweep_mfma(SweepParams P)
 {
-    constexpr int MT = H / 16, KS = H / 32;
-    constexpr int TPW = (MT + 3) / 4;          // output tiles per wave
+    constexpr int NW = sweep_waves(H);         // waves; wave w owns output column tiles w * TPW ...
+    constexpr int kThreads = 64 * NW;
+    constexpr int NTL = H / 16, KS = H / 32;
+    constexpr int TPW = NTL / NW;              // output column tiles per wave
     constexpr int NL = 2 * L;                  // layers per chunk: g then f
     constexpr int LDA = H + 8;                 // bf16 row stride of the activation buffers
     constexpr int TPR = H / 4;                 // float4 per row
     constexpr int PFN = (FCAP * TPR + kThreads - 1) / kThreads;   // staged far float4 per thread
     constexpr int PGN = (CH * TPR + kThreads - 1) / kThreads;     // gather items per thread
+    static_assert(NTL % NW == 0, "column tiles must divide over the waves");
 
     __shared__ __attribute__((aligned(16))) float msgtab[(kMsgSlots + 1) * H];   // last row stays zero
     __shared__ __attribute__((aligned(16))) float resbuf[2][CH * H];
-    __shared__ __attribute__((aligned(16))) __bf16 actbuf[2][NT][16][LDA];
-    __shared__ __attribute__((aligned(16))) float bias_lds[NL * H];
-    __shared__ int vtab[CH + 6];                  // node ids of the chunk's rows
+    __shared__ __attribute__((aligned(16))) __bf16 actbuf[2][NT * 16][LDA];
+    __shared__ int vtab[CH];                      // node ids of the chunk's rows
     __shared__ uint8_t flagtab[kMsgSlots + 12];   // entry kMsgSlots (the zero row) stays 0
 
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int col = lane & 15, kg = lane >> 4;
-    const int jrow = col / 3, spart = col - 3 * jrow;      // col 15: jrow = 5 (unused)
-    const bool own = (spart == 0) && (jrow < kTileNodes);  // lane that finishes a node's column
+    const int col = lane & 15, kg = lane >> 4;    // MFMA result: column col, node kg of a tile
 
     const GraphView &gv = P.gv;
     const SweepPlanView plan = gv.plan[dir];
@@ -151,31 +115,31 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
     const int cur = (cl >= 0 && cl < n_b) ? n0 + cl : -1;
     const int c_begin = plan.ck_off[b], c_end = plan.ck_off[b + 1];
 
-    // ---- weights of this direction into registers
-    bf16x8 A[NL][TPW][KS][WS];
+    // ---- weights of this direction into registers (B operand: lane holds column 16 nt + col)
+    bf16x8 W[NL][TPW][KS][WS];
+    float bias[NL][TPW];
 #pragma unroll
     for (int n = 0; n < NL; ++n)
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
-            const int mt = wave * TPW + t;
-            const int mtc = mt < MT ? mt : MT - 1;
+            const int nt = wave * TPW + t;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                 for (int ws = 0; ws < WS; ++ws) {
                     const size_t at =
-                        ((((static_cast<size_t>(dir) * NL + n) * MT + mtc) * KS + ks) * WS + ws) * 64 + lane;
+                        ((((static_cast<size_t>(dir) * NL + n) * NTL + nt) * KS + ks) * WS + ws) * 64 + lane;
                     const uint4 raw = P.wfrag[at];
-                    A[n][t][ks][ws] = *reinterpret_cast<const bf16x8 *>(&raw);
+                    W[n][t][ks][ws] = *reinterpret_cast<const bf16x8 *>(&raw);
                 }
+            bias[n][t] = P.bias[(static_cast<size_t>(dir) * NL + n) * H + nt * 16 + col];
         }
-    for (int i = tid; i < NL * H; i += kThreads) bias_lds[i] = P.bias[static_cast<size_t>(dir) * NL * H + i];
     for (int i = tid; i < (kMsgSlots + 1) * H; i += kThreads) msgtab[i] = 0.0f;
-    for (int i = tid; i < 2 * NT * 16 * LDA; i += kThreads) (&actbuf[0][0][0][0])[i] = static_cast<__bf16>(0.0f);
+    for (int i = tid; i < 2 * NT * 16 * LDA; i += kThreads) (&actbuf[0][0][0])[i] = static_cast<__bf16>(0.0f);
     if (tid < kMsgSlots + 12) flagtab[tid] = 0;
 
     // ---- software pipeline state.  m0 describes chunk c, m1 chunk c + 1.  A gather item is
-    // (row r, float4 q) of the chunk: item i of this thread is e = tid + i * 256.
+    // (row r, float4 q) of the chunk: item i of this thread is e = tid + i * kThreads.
     auto clampc = [&](int c) { return c < c_end ? c : c_end - 1; };
     int4 m0 = load_uniform(plan.meta + c_begin);
     int4 m1 = load_uniform(plan.meta + clampc(c_begin + 1));
@@ -190,24 +154,24 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
         ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(c_begin) * CH + rr);
         vg0[i] = order[m0.x + rr];
         if (r < m0.y)                          // residual inputs of the first chunk
-            *reinterpret_cast<float4 *>(&resbuf[0][r * H + 4 * q]) =
-                *reinterpret_cast<const float4 *>(xb + static_cast<size_t>(m0.x + r) * H + 4 * q);
+            *reinterpret_cast<f32x4 *>(&resbuf[0][r * H + 4 * q]) =
+                *reinterpret_cast<const f32x4 *>(xb + static_cast<size_t>(m0.x + r) * H + 4 * q);
     }
 #pragma unroll
     for (int i = 0; i < PFN; ++i) {
         const int f = (tid + i * kThreads) / TPR;
         fid1[i] = (f < FCAP) ? plan.far[static_cast<size_t>(clampc(c_begin + 1)) * FCAP + f] : -1;
     }
-    full_barrier();
+    __syncthreads();
 
     for (int c = c_begin; c < c_end; ++c) {
         const int rows = m0.y;
-        const int ntile = rows > kTileNodes ? 2 : 1;
+        const int ntile = (rows + kTileNodes - 1) / kTileNodes;
         const bool has_next = c + 1 < c_end;
         const int par = (c - c_begin) & 1;
 
         // ---- gather: a_v = sum of neighbour messages from the LDS table, split into three
-        // bf16 parts, written as the B operand of the first layer
+        // bf16 parts, written as three A rows of the first layer
         int my_bit[PGN];
 #pragma unroll
         for (int i = 0; i < PGN; ++i) {
@@ -251,12 +215,16 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
                 }
             }
             my_bit[i] = bit;
-            const Split4 sp = split4(sum);
-            const int ct = r >= kTileNodes ? 1 : 0;
-            __bf16 *dst = &actbuf[0][ct][3 * (r - ct * kTileNodes)][4 * q];
-            *reinterpret_cast<uint2 *>(dst) = sp.hi;
-            *reinterpret_cast<uint2 *>(dst + LDA) = sp.mid;
-            *reinterpret_cast<uint2 *>(dst + 2 * LDA) = sp.lo;
+            float rs[4], ls[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                rs[k] = sum[k] - trunc_bf16(sum[k]);
+                ls[k] = rs[k] - trunc_bf16(rs[k]);
+            }
+            __bf16 *dst = &actbuf[0][4 * r][4 * q];      // rows 4r, 4r+1, 4r+2 of the chunk's tiles
+            *reinterpret_cast<uint2 *>(dst) = uint2{pack_hi16(sum[0], sum[1]), pack_hi16(sum[2], sum[3])};
+            *reinterpret_cast<uint2 *>(dst + LDA) = uint2{pack_hi16(rs[0], rs[1]), pack_hi16(rs[2], rs[3])};
+            *reinterpret_cast<uint2 *>(dst + 2 * LDA) = uint2{pack_hi16(ls[0], ls[1]), pack_hi16(ls[2], ls[3])};
             if (q == 0) vtab[r] = vg0[i];
         }
         lds_barrier();
@@ -273,74 +241,59 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
 
 #pragma unroll
         for (int n = 0; n < NL; ++n) {
-#pragma unroll
-            for (int t = 0; t < TPW; ++t)
-#pragma unroll
-                for (int ct = 0; ct < NT; ++ct) acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-
+            // ---- rows of A from LDS (activation parts), weights from registers
 #pragma unroll
             for (int ct = 0; ct < NT; ++ct) {
-                if (ct >= ntile) break;
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (ct >= ntile) continue;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 frag =
-                        *reinterpret_cast<const bf16x8 *>(&actbuf[n & 1][ct][col][32 * ks + 8 * kg]);
+                    const bf16x8 a =
+                        *reinterpret_cast<const bf16x8 *>(&actbuf[n & 1][16 * ct + col][32 * ks + 8 * kg]);
 #pragma unroll
                     for (int t = 0; t < TPW; ++t)
 #pragma unroll
                         for (int ws = 0; ws < WS; ++ws)
-                            acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[n][t][ks][ws], frag,
+                            acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W[n][t][ks][ws],
                                                                                  acc[t][ct], 0, 0, 0);
                 }
             }
 
-            // ---- epilogue: add the three part-columns, bias, ReLU, then hand over
+            // ---- epilogue: lane (col, kg) holds, for node 4 ct + kg and output column
+            // 16 nt + col, the three partial products in acc[..][0..2]
 #pragma unroll
-            for (int t = 0; t < TPW; ++t) {
-                const int mt = wave * TPW + t;
-                if (mt >= MT) continue;
+            for (int ct = 0; ct < NT; ++ct) {
+                if (ct >= ntile) continue;
+                const int r = ct * kTileNodes + kg;
+                if (r >= rows) continue;
 #pragma unroll
-                for (int ct = 0; ct < NT; ++ct) {
-                    if (ct >= ntile) break;
-                    const float4 bv = *reinterpret_cast<const float4 *>(bias_lds + n * H + mt * 16 + 4 * kg);
-                    const float bias4[4] = {bv.x, bv.y, bv.z, bv.w};
-                    float y[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float a = acc[t][ct][i];
-                        y[i] = fmaxf(add_row_shl<2>(add_row_shl<1>(a, a), a) + bias4[i], 0.0f);
-                    }
-                    const int r = ct * kTileNodes + jrow;
-                    if (!(own && r < rows)) continue;
+                for (int t = 0; t < TPW; ++t) {
+                    const int m = (wave * TPW + t) * 16 + col;
+                    float y = fmaxf(acc[t][ct][0] + acc[t][ct][1] + acc[t][ct][2] + bias[n][t], 0.0f);
                     if (n == L - 1) {                    // end of g: residual update of s_v
-                        const float4 x = *reinterpret_cast<const float4 *>(
-                            &resbuf[par][r * H + mt * 16 + 4 * kg]);
-                        y[0] += x.x; y[1] += x.y; y[2] += x.z; y[3] += x.w;
-                        const float4 out{y[0], y[1], y[2], y[3]};
-                        *reinterpret_cast<float4 *>(P.emb + static_cast<size_t>(vtab[r]) * 2 * H + dir * H +
-                                                    mt * 16 + 4 * kg) = out;
-                        if (P.write_xb)
-                            *reinterpret_cast<float4 *>(xb + static_cast<size_t>(m0.x + r) * H + mt * 16 +
-                                                        4 * kg) = out;
+                        y += resbuf[par][r * H + m];
+                        P.emb[static_cast<size_t>(vtab[r]) * 2 * H + dir * H + m] = y;
+                        if (P.write_xb) xb[static_cast<size_t>(m0.x + r) * H + m] = y;
                     }
                     if (n == NL - 1) {                   // end of f: the message of v
-                        const float4 out{y[0], y[1], y[2], y[3]};
-                        *reinterpret_cast<float4 *>(msg + static_cast<size_t>(vtab[r]) * H + mt * 16 +
-                                                    4 * kg) = out;
-                        *reinterpret_cast<float4 *>(msgtab + (par * CH + r) * H + mt * 16 + 4 * kg) = out;
+                        msg[static_cast<size_t>(vtab[r]) * H + m] = y;
+                        msgtab[(par * CH + r) * H + m] = y;
                     } else {
-                        const Split4 sp = split4(y);
-                        __bf16 *dst = &actbuf[(n + 1) & 1][ct][col][mt * 16 + 4 * kg];
-                        *reinterpret_cast<uint2 *>(dst) = sp.hi;
-                        *reinterpret_cast<uint2 *>(dst + LDA) = sp.mid;
-                        *reinterpret_cast<uint2 *>(dst + 2 * LDA) = sp.lo;
+                        const float rr = y - trunc_bf16(y);
+                        const float ll = rr - trunc_bf16(rr);
+                        unsigned short *dst =
+                            reinterpret_cast<unsigned short *>(&actbuf[(n + 1) & 1][4 * r][m]);
+                        dst[0] = static_cast<unsigned short>(__float_as_uint(y) >> 16);
+                        dst[LDA] = static_cast<unsigned short>(__float_as_uint(rr) >> 16);
+                        dst[2 * LDA] = static_cast<unsigned short>(__float_as_uint(ll) >> 16);
                     }
                 }
             }
 
             if (n == NL - 1) {
                 // Wait for this wave's prefetch batch whether or not a lane uses it: the stores
-                // that preceded it are then complete too (see above).
+                // that preceded it are then complete too (see the note at the prefetch).
 #pragma unroll
                 for (int i = 0; i < PFN; ++i) asm volatile("" ::"v"(pf[i][0]), "v"(pf_reach[i]));
                 // An offset the compiler cannot see through, defined only here: without it the
@@ -377,7 +330,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
                 // chunks ago.  Those stores are complete: vector memory operations of a wave
                 // retire in order, and every wave waited for its own previous batch of these
                 // loads (issued after those stores) before the last barrier of the previous
-                // chunk (see the end-of-chunk stage below).
+                // chunk (see the end-of-chunk stage above).
                 lds_barrier();
 #pragma unroll
                 for (int i = 0; i < PFN; ++i) {
@@ -422,7 +375,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_sweep_mfma(SweepParams P)
 
 }  // namespace
 
-// Packs the f and g weights of both directions into MFMA A-operand fragments.
+// Packs the f and g weights of both directions into MFMA B-operand fragments.
 // Index: ((((dir * 2L + n) * MT + mt) * KS + ks) * WS + ws) * 64 + lane, n = g layers then f
 // layers; lane l holds W[32 ks + 8 (l / 16) + i][16 mt + l % 16], i = 0..7, as bf16 part ws
 // of the exact three-way split (ws = 0 only when the weights are bf16 already).
@@ -478,10 +431,10 @@ void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace
 {
     if (gv.B == 0) return;
     SweepParams P{gv, wfrag, bias, ws.emb, ws.xb, ws.msg, ws.reach, fa.cur_node, more_sweeps ? 1 : 0};
-    const dim3 grid(2 * gv.B), block(kThreads);
+    const dim3 grid(2 * gv.B);
 #define PL_CASE(HH, WW, LL)                                                      \
     if (mv.H == HH && WS == WW && mv.L == LL) {                                  \
-        hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL>), grid, block, 0, s, P);    \
+        hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL>), grid, dim3(64 * sweep_waves(HH)), 0, s, P); \
         return;                                                                  \
     }
     PL_CASE(128, 1, 2) PL_CASE(128, 1, 1)
