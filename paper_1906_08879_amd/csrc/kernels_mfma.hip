@@ -78,7 +78,7 @@ __device__ __forceinline__ int4 load_uniform(const int4 *p)
     return int4{r.x, r.y, r.z, r.w};
 }
 
-constexpr int sweep_waves(int H) { return H / 16 > 8 ? 8 : H / 16; }
+constexpr int sweep_waves(int H) { return H / 16 > 4 ? 4 : H / 16; }
 
 template <int H, int WS, int L>
 __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) void k_sweep_mfma(SweepParams P)
@@ -91,14 +91,18 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
     constexpr int LDA = H + 8;                 // bf16 row stride of the activation buffers
     constexpr int TPR = H / 4;                 // float4 per row
     constexpr int PFN = (FCAP * TPR + kThreads - 1) / kThreads;   // staged far float4 per thread
-    constexpr int PGN = (CH * TPR + kThreads - 1) / kThreads;     // gather items per thread
+    constexpr int IPR = TPR;                   // gather items per row: one per float4
+    constexpr int PGN = (CH * IPR + kThreads - 1) / kThreads;     // gather items per thread
+    constexpr int LDM = H + 4;                 // float row stride of the message table
+    constexpr int NACC = KS > 1 ? 2 : 1;       // independent accumulation chains per tile
     static_assert(NTL % NW == 0, "column tiles must divide over the waves");
 
-    __shared__ __attribute__((aligned(16))) float msgtab[(kMsgSlots + 1) * H];   // last row stays zero
+    // message table: H floats per row plus a flag column (1.0 if the node is v* or has v* among
+    // the nodes it was computed from, i.e. the reachability bit); the last row stays zero
+    __shared__ __attribute__((aligned(16))) float msgtab[(kMsgSlots + 1) * LDM];
     __shared__ __attribute__((aligned(16))) float resbuf[2][CH * H];
     __shared__ __attribute__((aligned(16))) __bf16 actbuf[2][NT * 16][LDA];
     __shared__ int vtab[CH];                      // node ids of the chunk's rows
-    __shared__ uint8_t flagtab[kMsgSlots + 12];   // entry kMsgSlots (the zero row) stays 0
 
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -134,9 +138,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                 }
             bias[n][t] = P.bias[(static_cast<size_t>(dir) * NL + n) * H + nt * 16 + col];
         }
-    for (int i = tid; i < (kMsgSlots + 1) * H; i += kThreads) msgtab[i] = 0.0f;
+    for (int i = tid; i < (kMsgSlots + 1) * LDM; i += kThreads) msgtab[i] = 0.0f;
     for (int i = tid; i < 2 * NT * 16 * LDA; i += kThreads) (&actbuf[0][0][0])[i] = static_cast<__bf16>(0.0f);
-    if (tid < kMsgSlots + 12) flagtab[tid] = 0;
 
     // ---- software pipeline state.  m0 describes chunk c, m1 chunk c + 1.  A gather item is
     // (row r, float4 q) of the chunk: item i of this thread is e = tid + i * kThreads.
@@ -149,7 +152,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
 #pragma unroll
     for (int i = 0; i < PGN; ++i) {
         const int e = tid + i * kThreads;
-        const int r = e / TPR, q = e - r * TPR;
+        const int r = e / IPR, q = e - r * IPR;
         const int rr = r < m0.y ? r : 0;
         ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(c_begin) * CH + rr);
         vg0[i] = order[m0.x + rr];
@@ -173,30 +176,32 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
         // ---- gather: a_v = sum of neighbour messages from the LDS table, split into three
         // bf16 parts, written as three A rows of the first layer
         int my_bit[PGN];
+        const int cmax = m0.w;                   // most table entries of any row of the chunk
 #pragma unroll
         for (int i = 0; i < PGN; ++i) {
             const int e = tid + i * kThreads;
-            const int r = e / TPR, q = e - r * TPR;
+            const int r = e / IPR, q = e - r * IPR;
             my_bit[i] = 0;
             if (r >= rows) continue;
             const uint32_t w0 = ent0[i].x, w1 = ent0[i].y, w2 = ent0[i].z, w3 = ent0[i].w;
-            const int cnt = w0 & 0xFFFF;
-            const int slot[kMaxEnt] = {static_cast<int>(w0 >> 16), static_cast<int>(w1 & 0xFFFF),
-                                       static_cast<int>(w1 >> 16), static_cast<int>(w2 & 0xFFFF),
-                                       static_cast<int>(w2 >> 16), static_cast<int>(w3 & 0xFFFF),
-                                       static_cast<int>(w3 >> 16)};
+            const int cnt_raw = w0 & 0xFFFF;
+            const int cnt = cnt_raw == 0xFFFF ? 0 : cnt_raw;
+            const int raw[kMaxEnt] = {static_cast<int>(w0 >> 16), static_cast<int>(w1 & 0xFFFF),
+                                      static_cast<int>(w1 >> 16), static_cast<int>(w2 & 0xFFFF),
+                                      static_cast<int>(w2 >> 16), static_cast<int>(w3 & 0xFFFF),
+                                      static_cast<int>(w3 >> 16)};
             float sum[4] = {0.f, 0.f, 0.f, 0.f};
-            int bit = 0;
-            if (cnt != 0xFFFF) {
+            float flag = 0.0f;                   // sum of the sources' flag column
 #pragma unroll
-                for (int k = 0; k < kMaxEnt; ++k) {
-                    if (k < cnt) {
-                        const float4 x = *reinterpret_cast<const float4 *>(msgtab + slot[k] * H + 4 * q);
-                        sum[0] += x.x; sum[1] += x.y; sum[2] += x.z; sum[3] += x.w;
-                        bit |= flagtab[slot[k]];
-                    }
+            for (int k = 0; k < kMaxEnt; ++k) {
+                if (k < cmax) {                  // uniform bound; short rows read the zero row
+                    const int slot = k < cnt ? raw[k] : kMsgSlots;
+                    const float4 x = *reinterpret_cast<const float4 *>(msgtab + slot * LDM + 4 * q);
+                    sum[0] += x.x; sum[1] += x.y; sum[2] += x.z; sum[3] += x.w;
+                    flag += msgtab[slot * LDM + H];
                 }
-            } else {
+            }
+            if (cnt_raw == 0xFFFF) {
                 // a row with more neighbours than its record holds: a list of table slots
                 // (recent sources) and node ids (sources at least three chunks back)
                 const int d0 = static_cast<int>(w0 >> 16) | (static_cast<int>(w1 & 0xFFFF) << 16);
@@ -205,16 +210,15 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                     const int u = plan.ovf[p];
                     float4 x;
                     if (u < 0) {
-                        x = *reinterpret_cast<const float4 *>(msgtab + (-1 - u) * H + 4 * q);
-                        bit |= flagtab[-1 - u];
+                        x = *reinterpret_cast<const float4 *>(msgtab + (-1 - u) * LDM + 4 * q);
+                        flag += msgtab[(-1 - u) * LDM + H];
                     } else {
                         x = *reinterpret_cast<const float4 *>(msg + static_cast<size_t>(u) * H + 4 * q);
-                        bit |= (u == cur) | reach[u];
+                        flag += ((u == cur) | reach[u]) ? 1.0f : 0.0f;
                     }
                     sum[0] += x.x; sum[1] += x.y; sum[2] += x.z; sum[3] += x.w;
                 }
             }
-            my_bit[i] = bit;
             float rs[4], ls[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -225,6 +229,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
             *reinterpret_cast<uint2 *>(dst) = uint2{pack_hi16(sum[0], sum[1]), pack_hi16(sum[2], sum[3])};
             *reinterpret_cast<uint2 *>(dst + LDA) = uint2{pack_hi16(rs[0], rs[1]), pack_hi16(rs[2], rs[3])};
             *reinterpret_cast<uint2 *>(dst + 2 * LDA) = uint2{pack_hi16(ls[0], ls[1]), pack_hi16(ls[2], ls[3])};
+            my_bit[i] = flag > 0.0f;             // reachability bit of the row's node
             if (q == 0) vtab[r] = vg0[i];
         }
         lds_barrier();
@@ -237,15 +242,18 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
         f32x4 pr[PGN];           // residual inputs of chunk c + 1
         int vg1[PGN];
         int4 m2 = m1;
-        f32x4 acc[TPW][NT];
+        f32x4 acc[TPW][NT][NACC];
 
 #pragma unroll
         for (int n = 0; n < NL; ++n) {
-            // ---- rows of A from LDS (activation parts), weights from registers
+            // ---- rows of A from LDS (activation parts), weights from registers; the k-steps
+            // alternate between two accumulators so that the MFMA chains are half as long
 #pragma unroll
             for (int ct = 0; ct < NT; ++ct) {
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int t = 0; t < TPW; ++t)
+#pragma unroll
+                    for (int h = 0; h < NACC; ++h) acc[t][ct][h] = f32x4{0.f, 0.f, 0.f, 0.f};
                 if (ct >= ntile) continue;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
@@ -255,8 +263,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                     for (int t = 0; t < TPW; ++t)
 #pragma unroll
                         for (int ws = 0; ws < WS; ++ws)
-                            acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W[n][t][ks][ws],
-                                                                                 acc[t][ct], 0, 0, 0);
+                            acc[t][ct][ks % NACC] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                a, W[n][t][ks][ws], acc[t][ct][ks % NACC], 0, 0, 0);
                 }
             }
 
@@ -270,7 +278,9 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
                     const int m = (wave * TPW + t) * 16 + col;
-                    float y = fmaxf(acc[t][ct][0] + acc[t][ct][1] + acc[t][ct][2] + bias[n][t], 0.0f);
+                    float y = acc[t][ct][0][0] + acc[t][ct][0][1] + acc[t][ct][0][2];
+                    if constexpr (NACC > 1) y += acc[t][ct][1][0] + acc[t][ct][1][1] + acc[t][ct][1][2];
+                    y = fmaxf(y + bias[n][t], 0.0f);
                     if (n == L - 1) {                    // end of g: residual update of s_v
                         y += resbuf[par][r * H + m];
                         P.emb[static_cast<size_t>(vtab[r]) * 2 * H + dir * H + m] = y;
@@ -278,7 +288,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                     }
                     if (n == NL - 1) {                   // end of f: the message of v
                         msg[static_cast<size_t>(vtab[r]) * H + m] = y;
-                        msgtab[(par * CH + r) * H + m] = y;
+                        msgtab[(par * CH + r) * LDM + m] = y;
                     } else {
                         const float rr = y - trunc_bf16(y);
                         const float ll = rr - trunc_bf16(rr);
@@ -305,10 +315,10 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
 #pragma unroll
                 for (int i = 0; i < PGN; ++i) {
                     const int e = tid + i * kThreads;
-                    const int r = e / TPR, q = e - r * TPR;
+                    const int r = e / IPR, q = e - r * IPR;
                     if (q == 0 && r < rows) {
                         reach[vg0[i]] = static_cast<uint8_t>(my_bit[i]);
-                        flagtab[par * CH + r] = static_cast<uint8_t>(my_bit[i] | (vg0[i] == cur));
+                        msgtab[(par * CH + r) * LDM + H] = (my_bit[i] | (vg0[i] == cur)) ? 1.0f : 0.0f;
                     }
                     if (has_next && r < m1.y)
                         *reinterpret_cast<f32x4 *>(&resbuf[par ^ 1][r * H + 4 * q + late]) = pr[i];
@@ -319,8 +329,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                     const int f = e / TPR, q = e - f * TPR;
                     if (has_next && f < m1.z) {
                         const int slot = RING * CH + (par ^ 1) * FCAP + f;
-                        *reinterpret_cast<f32x4 *>(msgtab + slot * H + 4 * q + late) = pf[i];
-                        if (q == 0) flagtab[slot + late] = static_cast<uint8_t>((pf_reach[i] != 0) | pf_cur[i]);
+                        *reinterpret_cast<f32x4 *>(msgtab + slot * LDM + 4 * q + late) = pf[i];
+                        if (q == 0) msgtab[slot * LDM + H + late] = ((pf_reach[i] != 0) | pf_cur[i]) ? 1.0f : 0.0f;
                     }
                 }
                 lds_barrier();
@@ -350,7 +360,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
 #pragma unroll
                 for (int i = 0; i < PGN; ++i) {
                     const int e = tid + i * kThreads;
-                    const int r = e / TPR, q = e - r * TPR;
+                    const int r = e / IPR, q = e - r * IPR;
                     const int rr = (r < m1.y) ? r : 0;
                     pr[i] = *reinterpret_cast<const f32x4 *>(xb + static_cast<size_t>(m1.x + rr) * H + 4 * q);
                     ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(clampc(c + 1)) * CH + rr);
