@@ -254,7 +254,9 @@ int ensure_workspace(pl_graph_batch *g, const ModelView &mv)
     int rc = ensure_reach(g);
     if (rc) return rc;
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.emb), sizeof(float) * (n * 2 * H + 4)));
-    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.msg), sizeof(float) * (2 * n * H + 4)));
+    // one spare row after both directions' messages: never written, target of dummy loads
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.msg), sizeof(float) * (2 * n * H + H + 4)));
+    PL_HIP(hipMemset(ws.msg, 0, sizeof(float) * (2 * n * H + H + 4)));
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.xb), sizeof(float) * (2 * n * H + 4)));
     ws.n_chunks = 8;
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.partial),
@@ -310,7 +312,9 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
     hipStream_t s = static_cast<hipStream_t>(stream);
     ForwardArgs fa{node_feats, placement, cur_node, out_logits, out_probs, out_pooled};
     const GraphView &gv = g->view;
-    const bool mfma = w->d_wfrag && w->path == 0 && w->cfg.k_sweeps > 0;
+    // the matrix-core sweep addresses its buffers with 32-bit offsets
+    const bool fits32 = static_cast<double>(g->host.n_tot) * 2 * mv.H * sizeof(float) < 4.0e9;
+    const bool mfma = w->d_wfrag && w->path == 0 && w->cfg.k_sweeps > 0 && fits32;
     {
         StageScope scope(g->timer, PL_STAGE_PROJECT, s);
         launch_project(gv, mv, g->ws, fa, !mfma, mfma, s);

@@ -118,6 +118,9 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
     const int cl = P.cur_node[b];
     const int cur = (cl >= 0 && cl < n_b) ? n0 + cl : -1;
     const int c_begin = plan.ck_off[b], c_end = plan.ck_off[b + 1];
+    // one row past both directions' messages (and one byte past both directions' bits) is
+    // never written: the address of dummy loads, relative to this direction's base
+    const int spare_row = (2 - dir) * gv.n_tot;
 
     // ---- weights of this direction into registers (B operand: lane holds column 16 nt + col)
     bf16x8 W[NL][TPW][KS][WS];
@@ -154,7 +157,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
         const int e = tid + i * kThreads;
         const int r = e / IPR, q = e - r * IPR;
         const int rr = r < m0.y ? r : 0;
-        ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(c_begin) * CH + rr);
+        ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(c_begin) * CH + static_cast<uint32_t>(rr));
         vg0[i] = order[m0.x + rr];
         if (r < m0.y)                          // residual inputs of the first chunk
             *reinterpret_cast<f32x4 *>(&resbuf[0][r * H + 4 * q]) =
@@ -213,7 +216,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                         x = *reinterpret_cast<const float4 *>(msgtab + (-1 - u) * LDM + 4 * q);
                         flag += msgtab[(-1 - u) * LDM + H];
                     } else {
-                        x = *reinterpret_cast<const float4 *>(msg + static_cast<size_t>(u) * H + 4 * q);
+                        x = *reinterpret_cast<const float4 *>(msg + static_cast<uint32_t>(u * H + 4 * q));
                         flag += ((u == cur) | reach[u]) ? 1.0f : 0.0f;
                     }
                     sum[0] += x.x; sum[1] += x.y; sum[2] += x.z; sum[3] += x.w;
@@ -283,11 +286,11 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                     y = fmaxf(y + bias[n][t], 0.0f);
                     if (n == L - 1) {                    // end of g: residual update of s_v
                         y += resbuf[par][r * H + m];
-                        P.emb[static_cast<size_t>(vtab[r]) * 2 * H + dir * H + m] = y;
-                        if (P.write_xb) xb[static_cast<size_t>(m0.x + r) * H + m] = y;
+                        P.emb[static_cast<uint32_t>(vtab[r] * 2 * H + dir * H + m)] = y;
+                        if (P.write_xb) xb[static_cast<uint32_t>((m0.x + r) * H + m)] = y;
                     }
                     if (n == NL - 1) {                   // end of f: the message of v
-                        msg[static_cast<size_t>(vtab[r]) * H + m] = y;
+                        msg[static_cast<uint32_t>(vtab[r] * H + m)] = y;
                         msgtab[(par * CH + r) * LDM + m] = y;
                     } else {
                         const float rr = y - trunc_bf16(y);
@@ -347,13 +350,11 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                     const int e = tid + i * kThreads;
                     const int f = e / TPR, q = e - f * TPR;
                     const bool live = has_next && f < m1.z && fid1[i] >= 0;
-                    const int u = live ? fid1[i] : 0;
-                    // lanes without a far source read a constant row instead, so that every
-                    // wave has a load of this batch to wait for
-                    const float *src = live ? msg + static_cast<size_t>(u) * H + 4 * q : P.bias + 4 * q;
-                    const uint8_t *rsrc = live ? reach + u : reinterpret_cast<const uint8_t *>(P.bias);
-                    pf[i] = *reinterpret_cast<const f32x4 *>(src);
-                    pf_reach[i] = *rsrc;                 // combined with pf_cur at the end of the chunk
+                    // lanes without a far source read a spare row that is never written, so
+                    // that every wave has a load of this batch to wait for
+                    const int u = live ? fid1[i] : spare_row;
+                    pf[i] = *reinterpret_cast<const f32x4 *>(msg + static_cast<uint32_t>(u * H + 4 * q));
+                    pf_reach[i] = reach[static_cast<uint32_t>(u)];   // combined with pf_cur at the end of the chunk
                     pf_cur[i] = live && u == cur;
                 }
                 m2 = load_uniform(plan.meta + clampc(c + 2));
@@ -362,14 +363,16 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                     const int e = tid + i * kThreads;
                     const int r = e / IPR, q = e - r * IPR;
                     const int rr = (r < m1.y) ? r : 0;
-                    pr[i] = *reinterpret_cast<const f32x4 *>(xb + static_cast<size_t>(m1.x + rr) * H + 4 * q);
-                    ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(clampc(c + 1)) * CH + rr);
-                    vg1[i] = order[m1.x + rr];
+                    pr[i] = *reinterpret_cast<const f32x4 *>(xb + static_cast<size_t>(m1.x) * H +
+                                                            static_cast<uint32_t>(rr * H + 4 * q));
+                    ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(clampc(c + 1)) * CH +
+                                                              static_cast<uint32_t>(rr));
+                    vg1[i] = (order + m1.x)[static_cast<uint32_t>(rr)];
                 }
 #pragma unroll
                 for (int i = 0; i < PFN; ++i) {     // ids staged two chunks ahead of their data
                     const int f = (tid + i * kThreads) / TPR;
-                    fid1[i] = (f < FCAP) ? plan.far[static_cast<size_t>(clampc(c + 2)) * FCAP + f] : -1;
+                    fid1[i] = (f < FCAP) ? (plan.far + static_cast<size_t>(clampc(c + 2)) * FCAP)[static_cast<uint32_t>(f)] : -1;
                 }
             } else {
                 lds_barrier();
