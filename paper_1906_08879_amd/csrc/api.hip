@@ -226,6 +226,7 @@ void free_workspace(Workspace &ws)
     (void)hipFree(ws.emb);
     (void)hipFree(ws.msg);
     (void)hipFree(ws.xb);
+    (void)hipFree(ws.featb);
     (void)hipFree(ws.reach);
     (void)hipFree(ws.partial);
     (void)hipFree(ws.zbuf);
@@ -258,6 +259,7 @@ int ensure_workspace(pl_graph_batch *g, const ModelView &mv)
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.msg), sizeof(float) * (2 * n * H + H + 4)));
     PL_HIP(hipMemset(ws.msg, 0, sizeof(float) * (2 * n * H + H + 4)));
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.xb), sizeof(float) * (2 * n * H + 4)));
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.featb), sizeof(float4) * (2 * n + 1)));
     ws.n_chunks = 8;
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.partial),
                      sizeof(float) * (static_cast<size_t>(g->host.B) * ws.n_chunks * 3 * mv.G * H + 4)));
@@ -316,8 +318,9 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
     const bool fits32 = static_cast<double>(g->host.n_tot) * 2 * mv.H * sizeof(float) < 4.0e9;
     const bool mfma = w->d_wfrag && w->path == 0 && w->cfg.k_sweeps > 0 && fits32;
     {
+        // the matrix-core sweep computes x_v itself from the raw features (first sweep)
         StageScope scope(g->timer, PL_STAGE_PROJECT, s);
-        launch_project(gv, mv, g->ws, fa, !mfma, mfma, s);
+        if (!mfma) launch_project(gv, mv, g->ws, fa, true, false, s);
     }
     {
         StageScope scope(g->timer, PL_STAGE_SWEEP, s);
@@ -325,7 +328,7 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
         for (int k = 0; k < w->cfg.k_sweeps; ++k) {
             if (mfma)
                 launch_sweep_mfma(gv, mv, g->ws, fa, reinterpret_cast<const uint4 *>(w->d_wfrag),
-                                  w->d_sweep_bias, w->sweep_ws, k + 1 < w->cfg.k_sweeps, s);
+                                  w->d_sweep_bias, w->sweep_ws, k == 0, k + 1 < w->cfg.k_sweeps, s);
             else
                 launch_sweep_generic(gv, mv, g->ws, fa, k == 0, s);
         }

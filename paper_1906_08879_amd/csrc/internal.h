@@ -120,6 +120,7 @@ struct Workspace {
     float *emb = nullptr;       // [n_tot, 2H]  [td ; bu]
     float *msg = nullptr;       // [2, n_tot, H]
     float *xb = nullptr;        // [2, n_tot, H]  sweep input in bucket order (matrix-core path)
+    float4 *featb = nullptr;    // [2, n_tot] raw features in bucket order (matrix-core path)
     uint8_t *reach = nullptr;   // [2, n_tot]   0: descendant-of-v* bit, 1: ancestor-of-v* bit
     float *partial = nullptr;   // [B, n_chunks_max, 3G, H] pooling partial sums
     float *zbuf = nullptr;      // [B, Z] policy inputs
@@ -169,6 +170,6 @@ void pack_sweep_weights(const ModelView &mv, const float *blob, int WS, std::vec
                         std::vector<float> *bias);
 void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                        const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
-                       bool more_sweeps, hipStream_t s);
+                       bool first_sweep, bool more_sweeps, hipStream_t s);
 
 }  // namespace pl

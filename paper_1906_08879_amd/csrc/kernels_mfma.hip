@@ -66,6 +66,11 @@ struct SweepParams {
     uint8_t *reach;         // [2, n_tot]
     const int32_t *cur_node;
     int write_xb;           // another sweep follows: keep xb current
+    // first sweep: the input x_v = relu(W_in^T phi_v + b_in) (Section 2.2 step 1) is computed
+    // here from the node's raw features, kept in bucket order, 16 bytes per node
+    const float4 *featb;    // [2, n_tot] {run time, output size, is-visited, bits(device | is-current << 16)}
+    const float *proj;      // [(F + 1), H]: rows of W_in, then b_in; NULL when the input comes from xb
+    int D;
 };
 
 // Reads a chunk's meta record through the constant address space, so that the wave-uniform
@@ -103,6 +108,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
     __shared__ __attribute__((aligned(16))) float resbuf[2][CH * H];
     __shared__ __attribute__((aligned(16))) __bf16 actbuf[2][NT * 16][LDA];
     __shared__ int vtab[CH];                      // node ids of the chunk's rows
+    __shared__ __attribute__((aligned(16))) float proj_lds[(kMaxD + 5) * H];   // W_in rows, then b_in
 
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -141,6 +147,34 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                 }
             bias[n][t] = P.bias[(static_cast<size_t>(dir) * NL + n) * H + nt * 16 + col];
         }
+    const bool from_feats = P.proj != nullptr;
+    const int D = P.D;
+    const float4 *featb = P.featb + static_cast<size_t>(dir) * gv.n_tot;
+    if (from_feats)
+        for (int i = tid; i < (D + 5) * H; i += kThreads) proj_lds[i] = P.proj[i];
+    // x_v[4q .. 4q+3] from a node's raw-feature record
+    auto project4 = [&](const f32x4 ft, int q) {
+        const float4 *w = reinterpret_cast<const float4 *>(proj_lds) + q;
+        const int bits = __float_as_int(ft[3]);
+        const int dev = bits & 0xFFFF;
+        const float4 bb = w[(D + 4) * (H / 4)], w0 = w[0], w1 = w[H / 4], wd = w[(3 + D) * (H / 4)];
+        f32x4 o{bb.x, bb.y, bb.z, bb.w};
+        o[0] = fmaf(ft[0], w0.x, o[0]); o[1] = fmaf(ft[0], w0.y, o[1]);
+        o[2] = fmaf(ft[0], w0.z, o[2]); o[3] = fmaf(ft[0], w0.w, o[3]);
+        o[0] = fmaf(ft[1], w1.x, o[0]); o[1] = fmaf(ft[1], w1.y, o[1]);
+        o[2] = fmaf(ft[1], w1.z, o[2]); o[3] = fmaf(ft[1], w1.w, o[3]);
+        if (dev < D) {
+            const float4 wv = w[(2 + dev) * (H / 4)];
+            o[0] += wv.x; o[1] += wv.y; o[2] += wv.z; o[3] += wv.w;
+        }
+        if (bits >> 16) {
+            const float4 wc = w[(2 + D) * (H / 4)];
+            o[0] += wc.x; o[1] += wc.y; o[2] += wc.z; o[3] += wc.w;
+        }
+        o[0] = fmaxf(fmaf(ft[2], wd.x, o[0]), 0.0f); o[1] = fmaxf(fmaf(ft[2], wd.y, o[1]), 0.0f);
+        o[2] = fmaxf(fmaf(ft[2], wd.z, o[2]), 0.0f); o[3] = fmaxf(fmaf(ft[2], wd.w, o[3]), 0.0f);
+        return o;
+    };
     for (int i = tid; i < (kMsgSlots + 1) * LDM; i += kThreads) msgtab[i] = 0.0f;
     for (int i = tid; i < 2 * NT * 16 * LDA; i += kThreads) (&actbuf[0][0][0])[i] = static_cast<__bf16>(0.0f);
 
@@ -159,14 +193,22 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
         const int rr = r < m0.y ? r : 0;
         ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(c_begin) * CH + static_cast<uint32_t>(rr));
         vg0[i] = order[m0.x + rr];
-        if (r < m0.y)                          // residual inputs of the first chunk
-            *reinterpret_cast<f32x4 *>(&resbuf[0][r * H + 4 * q]) =
-                *reinterpret_cast<const f32x4 *>(xb + static_cast<size_t>(m0.x + r) * H + 4 * q);
     }
 #pragma unroll
     for (int i = 0; i < PFN; ++i) {
         const int f = (tid + i * kThreads) / TPR;
         fid1[i] = (f < FCAP) ? plan.far[static_cast<size_t>(clampc(c_begin + 1)) * FCAP + f] : -1;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < PGN; ++i) {            // residual inputs of the first chunk
+        const int e = tid + i * kThreads;
+        const int r = e / IPR, q = e - r * IPR;
+        if (r < m0.y) {
+            const f32x4 raw = from_feats ? *reinterpret_cast<const f32x4 *>(featb + m0.x + r)
+                                         : *reinterpret_cast<const f32x4 *>(xb + static_cast<size_t>(m0.x + r) * H + 4 * q);
+            *reinterpret_cast<f32x4 *>(&resbuf[0][r * H + 4 * q]) = from_feats ? project4(raw, q) : raw;
+        }
     }
     __syncthreads();
 
@@ -324,7 +366,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                         msgtab[(par * CH + r) * LDM + H] = (my_bit[i] | (vg0[i] == cur)) ? 1.0f : 0.0f;
                     }
                     if (has_next && r < m1.y)
-                        *reinterpret_cast<f32x4 *>(&resbuf[par ^ 1][r * H + 4 * q + late]) = pr[i];
+                        *reinterpret_cast<f32x4 *>(&resbuf[par ^ 1][r * H + 4 * q + late]) =
+                            from_feats ? project4(pr[i], q) : pr[i];
                 }
 #pragma unroll
                 for (int i = 0; i < PFN; ++i) {
@@ -363,8 +406,9 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                     const int e = tid + i * kThreads;
                     const int r = e / IPR, q = e - r * IPR;
                     const int rr = (r < m1.y) ? r : 0;
-                    pr[i] = *reinterpret_cast<const f32x4 *>(xb + static_cast<size_t>(m1.x) * H +
-                                                            static_cast<uint32_t>(rr * H + 4 * q));
+                    pr[i] = from_feats ? *reinterpret_cast<const f32x4 *>(featb + m1.x + static_cast<uint32_t>(rr))
+                                       : *reinterpret_cast<const f32x4 *>(xb + static_cast<size_t>(m1.x) * H +
+                                                                          static_cast<uint32_t>(rr * H + 4 * q));
                     ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(clampc(c + 1)) * CH +
                                                               static_cast<uint32_t>(rr));
                     vg1[i] = (order + m1.x)[static_cast<uint32_t>(rr)];
@@ -384,6 +428,23 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
 #pragma unroll
         for (int i = 0; i < PGN; ++i) vg0[i] = vg1[i];
     }
+}
+
+// Raw features of every node in the bucket order of both directions (Section 2.1 features;
+// the device and the is-current flag travel as bits).
+__global__ __launch_bounds__(256) void k_bucket_feats(GraphView gv, const float *__restrict__ feats,
+                                                      const int32_t *__restrict__ placement,
+                                                      const int32_t *__restrict__ cur_node, int D,
+                                                      float4 *__restrict__ featb)
+{
+    const int v = blockIdx.x * 256 + threadIdx.x;
+    if (v >= gv.n_tot) return;
+    const int b = gv.node_graph[v];
+    const int dev = placement[v];
+    const int bits = ((dev >= 0 && dev < D) ? dev : 0xFFFF) | ((v - gv.node_off[b] == cur_node[b]) ? 0x10000 : 0);
+    const float4 rec{feats[v * 3 + 0], feats[v * 3 + 1], feats[v * 3 + 2], __int_as_float(bits)};
+    featb[gv.pos[0][v]] = rec;
+    featb[static_cast<size_t>(gv.n_tot) + gv.pos[1][v]] = rec;
 }
 
 }  // namespace
@@ -440,10 +501,14 @@ bool sweep_mfma_supported(int H, int L, int weight_dtype)
 
 void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                        const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
-                       bool more_sweeps, hipStream_t s)
+                       bool first_sweep, bool more_sweeps, hipStream_t s)
 {
     if (gv.B == 0) return;
-    SweepParams P{gv, wfrag, bias, ws.emb, ws.xb, ws.msg, ws.reach, fa.cur_node, more_sweeps ? 1 : 0};
+    SweepParams P{gv, wfrag, bias, ws.emb, ws.xb, ws.msg, ws.reach, fa.cur_node, more_sweeps ? 1 : 0,
+                  ws.featb, first_sweep ? mv.blob + mv.proj.w : nullptr, mv.D};
+    if (first_sweep)
+        hipLaunchKernelGGL(k_bucket_feats, dim3((gv.n_tot + 255) / 256), dim3(256), 0, s, gv, fa.node_feats,
+                           fa.placement, fa.cur_node, mv.D, ws.featb);
     const dim3 grid(2 * gv.B);
 #define PL_CASE(HH, WW, LL)                                                      \
     if (mv.H == HH && WS == WW && mv.L == LL) {                                  \
