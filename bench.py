@@ -38,6 +38,33 @@ def path_algorithmic_bytes(n_tot: int, e_tot: int, H: int) -> int:
     return sweep_algorithmic_bytes(n_tot, e_tot, H) + n_tot * (16 * H + 12 + 4 + 2)
 
 
+def csrc_digest() -> str:
+    """sha256 over the library's sources: ties a stored counter measurement to the kernels."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_1906_08879_amd", "csrc", "*"))):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload: str, batch: int):
+    """HBM bytes per sweep launch from the stored rocprofv3 counter summary, or None when
+    there is none for this workload or the kernels have changed since it was taken."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}_B{batch}.txt")
+    if not os.path.exists(path):
+        return None
+    rec = {}
+    for line in open(path):
+        if not line.startswith("#") and ":" in line:
+            k, v = line.split(":", 1)
+            rec[k.strip()] = v.strip()
+    if rec.get("source_sha256") != csrc_digest() or "sweep_traffic_bytes_per_launch" not in rec:
+        return None
+    return int(rec["sweep_traffic_bytes_per_launch"])
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -46,6 +73,9 @@ def main() -> int:
     ap.add_argument("--workload", default="nasnet")
     ap.add_argument("--batch", type=int, default=None, help="override the number of graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run a plain 1 GiB device copy five times and exit (reference for "
+                         "scaling the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path shards over the batch of "
@@ -55,6 +85,16 @@ def main() -> int:
 
     import numpy as np
     import torch
+    if args.copy_probe:
+        n = 1 << 28                                     # 2^28 floats = 1 GiB read, 1 GiB written
+        a = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        b = torch.empty_like(a)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe": True, "bytes_read_per_copy": 4 * n, "bytes_written_per_copy": 4 * n,
+                          "copies": 5}))
+        return 0
     import paper_1906_08879_amd as pl
     from workloads import make_workload, make_states
 
@@ -108,7 +148,8 @@ def main() -> int:
     achieved = alg / (avg_launch_ms * 1e-3) / 1e9 if avg_launch_ms > 0 else 0.0
     roofline = {"kernel": "sweep (message passing, both directions)", "bound": "hbm",
                 "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 5),
+                "traffic": measured_traffic(args.workload, int(w.B)),
                 "algorithmic_bytes_per_launch": alg, "avg_launch_ms": round(avg_launch_ms, 5),
                 "path_algorithmic_bytes_per_step": path_algorithmic_bytes(w.n_tot, w.e_tot, w.H),
                 "path_frac": round(path_algorithmic_bytes(w.n_tot, w.e_tot, w.H)

@@ -5,7 +5,7 @@ import numpy as np
 RTOL, ATOL = 1e-4, 1e-5     # fp32 logits vs the float64 oracle
 
 
-def run_library(w, placement=None, cur_node=None, done=None, want_emb=True, handles=None):
+def run_library(w, placement=None, cur_node=None, done=None, want_emb=True, handles=None, path=0):
     """One forward pass of workload `w` on cuda:0.  Returns dict of numpy arrays."""
     import torch
     import paper_1906_08879_amd as pl
@@ -14,6 +14,8 @@ def run_library(w, placement=None, cur_node=None, done=None, want_emb=True, hand
         g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
         wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device,
                         w.weight_dtype)
+        if path:
+            wt.set_path(path)
     else:
         g, wt = handles
     feats = np.array(w.node_feats, dtype=np.float32, copy=True)

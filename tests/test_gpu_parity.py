@@ -104,6 +104,21 @@ def test_shapes_and_variants(D, H, L, k, group, wd):
     _compare(w, f"D={D} H={H} L={L} k={k} g={group} {wd}")
 
 
+@pytest.mark.parametrize("name", ["layered200", "nmt", "nasnet"])
+def test_generic_kernels_on_matrix_core_shapes(name):
+    """The generic fp32 kernels (pl_weights_set_path 1) on shapes the matrix-core kernels
+    normally take: same bar against the oracle, and both paths agree closely."""
+    w = make_workload(name, B=2)
+    ref = oracle.forward_workload(w, n_threads=THREADS, want_emb=True)
+    slow = run_library(w, path=1)
+    fast = run_library(w, path=0)
+    assert_logits_close(slow["logits"], ref["logits"], name + " generic")
+    assert_logits_close(fast["logits"], ref["logits"], name + " matrix-core")
+    scale = np.abs(ref["emb"]).max()
+    assert np.abs(slow["emb"] - ref["emb"]).max() <= 2e-5 * scale
+    assert np.abs(fast["emb"] - slow["emb"]).max() <= 2e-5 * scale
+
+
 def test_edgeless_and_wide_levels():
     rng = np.random.default_rng(9)
     w = _custom(rng, [50, 33, 1], 4, 32, p_edge=0.0)          # every node is a root and a leaf
