@@ -189,7 +189,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
 #pragma unroll
     for (int i = 0; i < PGN; ++i) {
         const int e = tid + i * kThreads;
-        const int r = e / IPR, q = e - r * IPR;
+        const int r = e / IPR;
         const int rr = r < m0.y ? r : 0;
         ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(c_begin) * CH + static_cast<uint32_t>(rr));
         vg0[i] = order[m0.x + rr];

@@ -214,15 +214,18 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
         issue();          // ends with a barrier: act1 and batch_dev are visible
 
         // ---- (3) layer 1
-        const int ntile = (cnt + 3) >> 2;
         f32x4 acc[kTiles][TPW];
 #pragma unroll
-        for (int tl = 0; tl < kTiles; ++tl) {
+        for (int tl = 0; tl < kTiles; ++tl)
 #pragma unroll
             for (int t = 0; t < TPW; ++t) acc[tl][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (tl >= ntile) continue;
+        // k-steps outermost: kTiles * TPW independent accumulation chains are in flight, which
+        // hides the latency of a dependent MFMA (about three issue slots).  All four tiles are
+        // always computed; rows past the batch's end hold stale data that is never summed.
 #pragma unroll
-            for (int ks = 0; ks < KS1; ++ks) {
+        for (int ks = 0; ks < KS1; ++ks)
+#pragma unroll
+            for (int tl = 0; tl < kTiles; ++tl) {
                 const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&act1[16 * tl + col][32 * ks + 8 * kg]);
 #pragma unroll
                 for (int t = 0; t < TPW; ++t)
@@ -230,13 +233,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
                     for (int ws = 0; ws < WS; ++ws)
                         acc[tl][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W1[t][ks][ws], acc[tl][t], 0, 0, 0);
             }
-        }
         // lane (col, kg) holds, for node 4 tl + kg and output column 16 nt + col, the three
         // partial products in acc[..][0..2]
         if constexpr (L > 1) {
 #pragma unroll
             for (int tl = 0; tl < kTiles; ++tl) {
-                if (tl >= ntile) continue;
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
                     const int nt = wave * TPW + t;
@@ -253,12 +254,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
             lds_barrier();
             // ---- (4) layer 2
 #pragma unroll
-            for (int tl = 0; tl < kTiles; ++tl) {
+            for (int tl = 0; tl < kTiles; ++tl)
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) acc[tl][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (tl >= ntile) continue;
 #pragma unroll
-                for (int ks = 0; ks < KS2; ++ks) {
+            for (int ks = 0; ks < KS2; ++ks)
+#pragma unroll
+                for (int tl = 0; tl < kTiles; ++tl) {
                     const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&act2[16 * tl + col][32 * ks + 8 * kg]);
 #pragma unroll
                     for (int t = 0; t < TPW; ++t)
@@ -267,11 +269,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
                             acc[tl][t] =
                                 __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W2[t][ks][ws], acc[tl][t], 0, 0, 0);
                 }
-            }
         }
 #pragma unroll
         for (int tl = 0; tl < kTiles; ++tl) {
-            if (tl >= ntile) continue;
 #pragma unroll
             for (int t = 0; t < TPW; ++t) {
                 const int nt = wave * TPW + t;
