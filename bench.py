@@ -22,7 +22,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 N_STATES = 8
-CPU_SAMPLE_GRAPHS = {"random32": 1, "layered200": 64, "inception": 128, "nmt": 64, "nasnet": 32}
+CPU_SAMPLE_GRAPHS = {"random32": 1, "layered200": 64, "inception": 128, "nmt": 64, "nasnet": 256}
 
 
 def sweep_algorithmic_bytes(n_tot: int, e_tot: int, H: int) -> int:

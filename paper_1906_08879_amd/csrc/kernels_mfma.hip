@@ -2,7 +2,7 @@
 //   a_v = sum_{u in xi(v)} m_u,   s_v <- s_v + g(a_v),   m_v = f(s_v),
 // for H in {32, 64, 128} and one or two layers per network.
 //
-// One workgroup (one wave per 16 output columns, up to 8 waves) per (graph, direction)
+// One workgroup (one wave per 16 or 32 output columns, at most four waves) per (graph, direction)
 // walks the graph's levels in chunks of at most 8 nodes.  Design points, all specific to
 // CDNA4:
 //   * v_mfma_f32_16x16x32_bf16 with the node activations as the A operand and the WEIGHTS as
@@ -12,7 +12,7 @@
 //     in one lane's accumulator registers, where they are added: fp32 accuracy from the bf16
 //     matrix cores without any cross-lane traffic.
 //   * The weight fragments of all layers of one direction live in registers for the whole
-//     kernel (bf16 weights: 64 VGPRs per wave at H = 128); only activations move through LDS.
+//     kernel (bf16 weights: 128 VGPRs per wave at H = 128); only activations move through LDS.
 //   * Messages of the last two chunks stay in an LDS table; messages from older chunks are
 //     prefetched from HBM one chunk ahead into the same table, so the gather on the
 //     critical path reads LDS only.  Chunk records, node ids and the residual inputs (kept
