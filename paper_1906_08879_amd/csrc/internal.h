@@ -60,8 +60,10 @@ constexpr int kMsgSlots = kRing * kChunkRows + 2 * kFarCap;
 
 struct SweepPlanHost {
     std::vector<int32_t> ck_off;   // [B+1] chunk range of each graph
-    std::vector<int32_t> meta;     // [n_chunks][4]: global bucket position, rows, n_far, most table entries of a row
-    std::vector<uint16_t> ent;     // [n_chunks][kChunkRows][8]: count (0xFFFF = sum from global), slots
+    std::vector<int32_t> meta;     // [n_chunks][4]: global bucket position, rows, n_far,
+                                   // most table entries of a row | (some row uses the overflow list) << 8
+    std::vector<uint16_t> ent;     // [n_chunks][kChunkRows][8]: count (0xFFFF = overflow list), slots;
+                                   // unused entries = kMsgSlots, the table's zero row
     std::vector<int32_t> far;      // [n_chunks][kFarCap] global node ids staged for the chunk
     std::vector<int32_t> ovf;      // neighbour lists of rows that do not fit their record:
                                    // >= 0 global node id (>= 3 chunks back), < 0: -1 - table slot

@@ -24,6 +24,8 @@
 //   * The kernel runs a dependent chain (about a thousand chunks of four layers per graph),
 //     so it is bound by instruction issue and LDS round trips, not by HBM bandwidth: the
 //     per-layer epilogue is about fifteen instructions per tile.
+#include <type_traits>
+
 #include "internal.h"
 
 namespace pl {
@@ -44,11 +46,6 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-__device__ __forceinline__ uint32_t pack_hi16(float lo_word, float hi_word)
-{
-    return __builtin_amdgcn_perm(__float_as_uint(hi_word), __float_as_uint(lo_word), 0x07060302u);
 }
 
 __device__ __forceinline__ float trunc_bf16(float x)
@@ -85,34 +82,38 @@ __device__ __forceinline__ int4 load_uniform(const int4 *p)
 
 constexpr int sweep_waves(int H) { return H / 16 > 4 ? 4 : H / 16; }
 
-template <int H, int WS, int L>
-__global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) void k_sweep_mfma(SweepParams P)
+// FF: first sweep, the input x_v is computed from the raw-feature records; otherwise it is
+// read from xb.
+template <int H, int WS, int L, bool FF>
+__global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepParams P)
 {
-    constexpr int NW = sweep_waves(H);         // waves; wave w owns output column tiles w * TPW ...
+    constexpr int NW = sweep_waves(H);         // waves; wave w owns output columns [w WC, (w + 1) WC)
     constexpr int kThreads = 64 * NW;
     constexpr int NTL = H / 16, KS = H / 32;
     constexpr int TPW = NTL / NW;              // output column tiles per wave
+    constexpr int WC = 16 * TPW;               // columns owned by a wave
     constexpr int NL = 2 * L;                  // layers per chunk: g then f
     constexpr int LDA = H + 8;                 // bf16 row stride of the activation buffers
-    constexpr int TPR = H / 4;                 // float4 per row
-    constexpr int PFN = (FCAP * TPR + kThreads - 1) / kThreads;   // staged far float4 per thread
-    constexpr int IPR = TPR;                   // gather items per row: one per float4
-    constexpr int PGN = (CH * IPR + kThreads - 1) / kThreads;     // gather items per thread
-    constexpr int LDM = H + 4;                 // float row stride of the message table
+    constexpr int LDM = H + 16;                // float row stride of the message table (16 mod 64:
+                                               // four consecutive rows fall on disjoint banks)
+    constexpr int QW = WC / 4;                 // float4 per far row and wave
+    constexpr int PFN = (FCAP * QW + 63) / 64; // staged far float4 per lane
     constexpr int NACC = KS > 1 ? 2 : 1;       // independent accumulation chains per tile
+    constexpr int kZeroSlot = kMsgSlots;
     static_assert(NTL % NW == 0, "column tiles must divide over the waves");
 
-    // message table: H floats per row plus a flag column (1.0 if the node is v* or has v* among
-    // the nodes it was computed from, i.e. the reachability bit); the last row stays zero
+    // Message table: H floats per row, then one flag column PER WAVE (1.0 if the node is v* or
+    // has v* among the nodes it was computed from: the reachability bit).  A wave reads and
+    // writes only its own columns and its own flag column, so the table needs no barrier.
+    // The last row stays zero.
     __shared__ __attribute__((aligned(16))) float msgtab[(kMsgSlots + 1) * LDM];
-    __shared__ __attribute__((aligned(16))) float resbuf[2][CH * H];
     __shared__ __attribute__((aligned(16))) __bf16 actbuf[2][NT * 16][LDA];
-    __shared__ int vtab[CH];                      // node ids of the chunk's rows
-    __shared__ __attribute__((aligned(16))) float proj_lds[(kMaxD + 5) * H];   // W_in rows, then b_in
+    __shared__ float proj_dev[(kMaxD + 1) * H];   // one-hot device rows of W_in, then a zero row
 
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, kg = lane >> 4;    // MFMA result: column col, node kg of a tile
+    const int wc0 = wave * WC;
 
     const GraphView &gv = P.gv;
     const SweepPlanView plan = gv.plan[dir];
@@ -124,6 +125,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
     const int cl = P.cur_node[b];
     const int cur = (cl >= 0 && cl < n_b) ? n0 + cl : -1;
     const int c_begin = plan.ck_off[b], c_end = plan.ck_off[b + 1];
+    if (c_begin >= c_end) return;
     // one row past both directions' messages (and one byte past both directions' bits) is
     // never written: the address of dummy loads, relative to this direction's base
     const int spare_row = (2 - dir) * gv.n_tot;
@@ -147,286 +149,360 @@ __global__ __launch_bounds__(64 * sweep_waves(H), sweep_waves(H) == 8 ? 4 : 2) v
                 }
             bias[n][t] = P.bias[(static_cast<size_t>(dir) * NL + n) * H + nt * 16 + col];
         }
-    const bool from_feats = P.proj != nullptr;
+
+    // ---- input projection (Section 2.2 step 1), one output column per lane and tile:
+    // x = relu(b + time w0 + size w1 + w[2 + device] + is_current w[2 + D] + visited w[3 + D])
     const int D = P.D;
+    float pw_time[TPW], pw_size[TPW], pw_cur[TPW], pw_vis[TPW], pw_b[TPW];
+    if constexpr (FF) {
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            const int m = wc0 + 16 * t + col;
+            pw_time[t] = P.proj[m];
+            pw_size[t] = P.proj[H + m];
+            pw_cur[t] = P.proj[(2 + D) * H + m];
+            pw_vis[t] = P.proj[(3 + D) * H + m];
+            pw_b[t] = P.proj[(4 + D) * H + m];
+        }
+        for (int i = tid; i < (kMaxD + 1) * H; i += kThreads)
+            proj_dev[i] = (i < D * H) ? P.proj[2 * H + i] : 0.0f;
+    }
     const float4 *featb = P.featb + static_cast<size_t>(dir) * gv.n_tot;
-    if (from_feats)
-        for (int i = tid; i < (D + 5) * H; i += kThreads) proj_lds[i] = P.proj[i];
-    // x_v[4q .. 4q+3] from a node's raw-feature record
-    auto project4 = [&](const f32x4 ft, int q) {
-        const float4 *w = reinterpret_cast<const float4 *>(proj_lds) + q;
+    auto project = [&](const f32x4 ft, int t) {
         const int bits = __float_as_int(ft[3]);
         const int dev = bits & 0xFFFF;
-        const float4 bb = w[(D + 4) * (H / 4)], w0 = w[0], w1 = w[H / 4], wd = w[(3 + D) * (H / 4)];
-        f32x4 o{bb.x, bb.y, bb.z, bb.w};
-        o[0] = fmaf(ft[0], w0.x, o[0]); o[1] = fmaf(ft[0], w0.y, o[1]);
-        o[2] = fmaf(ft[0], w0.z, o[2]); o[3] = fmaf(ft[0], w0.w, o[3]);
-        o[0] = fmaf(ft[1], w1.x, o[0]); o[1] = fmaf(ft[1], w1.y, o[1]);
-        o[2] = fmaf(ft[1], w1.z, o[2]); o[3] = fmaf(ft[1], w1.w, o[3]);
-        if (dev < D) {
-            const float4 wv = w[(2 + dev) * (H / 4)];
-            o[0] += wv.x; o[1] += wv.y; o[2] += wv.z; o[3] += wv.w;
-        }
-        if (bits >> 16) {
-            const float4 wc = w[(2 + D) * (H / 4)];
-            o[0] += wc.x; o[1] += wc.y; o[2] += wc.z; o[3] += wc.w;
-        }
-        o[0] = fmaxf(fmaf(ft[2], wd.x, o[0]), 0.0f); o[1] = fmaxf(fmaf(ft[2], wd.y, o[1]), 0.0f);
-        o[2] = fmaxf(fmaf(ft[2], wd.z, o[2]), 0.0f); o[3] = fmaxf(fmaf(ft[2], wd.w, o[3]), 0.0f);
-        return o;
+        float o = pw_b[t];
+        o = fmaf(ft[0], pw_time[t], o);
+        o = fmaf(ft[1], pw_size[t], o);
+        o += proj_dev[(dev < D ? dev : D) * H + wc0 + 16 * t + col];
+        o += (bits >> 16) ? pw_cur[t] : 0.0f;
+        return fmaxf(fmaf(ft[2], pw_vis[t], o), 0.0f);
     };
     for (int i = tid; i < (kMsgSlots + 1) * LDM; i += kThreads) msgtab[i] = 0.0f;
     for (int i = tid; i < 2 * NT * 16 * LDA; i += kThreads) (&actbuf[0][0][0])[i] = static_cast<__bf16>(0.0f);
 
-    // ---- software pipeline state.  m0 describes chunk c, m1 chunk c + 1.  A gather item is
-    // (row r, float4 q) of the chunk: item i of this thread is e = tid + i * kThreads.
+    // Writes y, split exactly into three bf16 parts, as rows 4 r .. 4 r + 2 of an A operand.
+    auto put_parts = [&](int buf, int r, int m, float y) {
+        const float rr = y - trunc_bf16(y);
+        const float ll = rr - trunc_bf16(rr);
+        unsigned short *dst = reinterpret_cast<unsigned short *>(&actbuf[buf][4 * r][m]);
+        dst[0] = static_cast<unsigned short>(__float_as_uint(y) >> 16);
+        dst[LDA] = static_cast<unsigned short>(__float_as_uint(rr) >> 16);
+        dst[2 * LDA] = static_cast<unsigned short>(__float_as_uint(ll) >> 16);
+    };
+
+    // ---- gather of a chunk: a_v = sum of neighbour messages, for rows kg and kg + 4 and this
+    // wave's columns, from the wave's own part of the LDS table; written as A rows of the first
+    // layer.  K entries of every row record are summed (unused entries name the zero row).
+    auto gather_fixed = [&](auto kc, int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT]) {
+        constexpr int K = decltype(kc)::value;
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) {
+            bit[ct] = 0;
+            if (ct >= ntile_x) continue;
+            const u32x4 rec = ent[ct];
+            float s[TPW], fl = 0.0f;
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) s[t] = 0.0f;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const int j = k + 1;
+                const int slot = (j & 1) ? static_cast<int>(rec[j >> 1] >> 16) : static_cast<int>(rec[j >> 1] & 0xFFFF);
+                const float *row = msgtab + slot * LDM;
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) s[t] += row[wc0 + 16 * t + col];
+                fl += row[H + wave];
+            }
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) put_parts(0, 4 * ct + kg, wc0 + 16 * t + col, s[t]);
+            bit[ct] = fl > 0.0f;
+        }
+    };
+    // The same for a chunk in which some row has more neighbours than its record holds: that
+    // row sums a list of table slots (recent sources) and node ids (sources at least three
+    // chunks back, read from HBM).
+    auto gather_general = [&](int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT]) {
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) {
+            bit[ct] = 0;
+            if (ct >= ntile_x) continue;
+            const u32x4 rec = ent[ct];
+            const bool listed = (rec[0] & 0xFFFF) == 0xFFFF;
+            float s[TPW], fl = 0.0f;
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) s[t] = 0.0f;
+#pragma unroll
+            for (int k = 0; k < kMaxEnt; ++k) {
+                const int j = k + 1;
+                const int raw = (j & 1) ? static_cast<int>(rec[j >> 1] >> 16) : static_cast<int>(rec[j >> 1] & 0xFFFF);
+                const float *row = msgtab + (listed ? kZeroSlot : raw) * LDM;
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) s[t] += row[wc0 + 16 * t + col];
+                fl += row[H + wave];
+            }
+            if (listed) {
+                const int d0 = static_cast<int>(rec[0] >> 16) | (static_cast<int>(rec[1] & 0xFFFF) << 16);
+                const int d1 = d0 + (static_cast<int>(rec[1] >> 16) | (static_cast<int>(rec[2] & 0xFFFF) << 16));
+                for (int p = d0; p < d1; ++p) {
+                    const int u = plan.ovf[p];
+                    if (u < 0) {
+                        const float *row = msgtab + (-1 - u) * LDM;
+#pragma unroll
+                        for (int t = 0; t < TPW; ++t) s[t] += row[wc0 + 16 * t + col];
+                        fl += row[H + wave];
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < TPW; ++t)
+                            s[t] += msg[static_cast<uint32_t>(u * H + wc0 + 16 * t + col)];
+                        fl += ((u == cur) | reach[static_cast<uint32_t>(u)]) ? 1.0f : 0.0f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) put_parts(0, 4 * ct + kg, wc0 + 16 * t + col, s[t]);
+            bit[ct] = fl > 0.0f;
+        }
+    };
+    // w = meta.w of the chunk: most entries of a row | (a row uses the list) << 8
+    auto gather = [&](int w, int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT]) {
+        if (w <= 3)
+            gather_fixed(std::integral_constant<int, 3>{}, ntile_x, ent, bit);
+        else if (w <= kMaxEnt)
+            gather_fixed(std::integral_constant<int, kMaxEnt>{}, ntile_x, ent, bit);
+        else
+            gather_general(ntile_x, ent, bit);
+    };
+
+    // ---- software pipeline state.  m0 describes chunk c, m1 chunk c + 1.  A lane works on
+    // rows kg (tile 0) and kg + 4 (tile 1) of a chunk.
     auto clampc = [&](int c) { return c < c_end ? c : c_end - 1; };
     int4 m0 = load_uniform(plan.meta + c_begin);
     int4 m1 = load_uniform(plan.meta + clampc(c_begin + 1));
-    u32x4 ent0[PGN];         // neighbour record of the item's row, chunk c
-    int vg0[PGN];            // node id of the item's row, chunk c
+    u32x4 ent1[NT];          // neighbour records of the rows of the chunk gathered next
+    int vg0[NT], vg1[NT];    // node ids of the rows of chunk c, c + 1
+    f32x4 ft0[NT];           // raw-feature records of the rows of chunk c        (FF)
+    float x0[NT][TPW];       // residual inputs x_v of chunk c
+    float x1[NT][TPW];       // ... of chunk c + 1                                  (!FF)
+    int bit0[NT];            // reachability bits of the rows of chunk c
     int fid1[PFN];           // far sources of chunk c + 1
 #pragma unroll
-    for (int i = 0; i < PGN; ++i) {
-        const int e = tid + i * kThreads;
-        const int r = e / IPR;
+    for (int ct = 0; ct < NT; ++ct) {
+        const int r = 4 * ct + kg;
         const int rr = r < m0.y ? r : 0;
-        ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(c_begin) * CH + static_cast<uint32_t>(rr));
-        vg0[i] = order[m0.x + rr];
+        ent1[ct] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(c_begin) * CH + r);
+        vg0[ct] = order[m0.x + rr];
+        vg1[ct] = vg0[ct];
+        if constexpr (FF) {
+            ft0[ct] = *reinterpret_cast<const f32x4 *>(featb + m0.x + rr);
+        } else {
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) {
+                x0[ct][t] = xb[static_cast<size_t>(m0.x + rr) * H + wc0 + 16 * t + col];
+                x1[ct][t] = x0[ct][t];
+            }
+        }
     }
 #pragma unroll
     for (int i = 0; i < PFN; ++i) {
-        const int f = (tid + i * kThreads) / TPR;
+        const int f = (lane + 64 * i) / QW;
         fid1[i] = (f < FCAP) ? plan.far[static_cast<size_t>(clampc(c_begin + 1)) * FCAP + f] : -1;
     }
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < PGN; ++i) {            // residual inputs of the first chunk
-        const int e = tid + i * kThreads;
-        const int r = e / IPR, q = e - r * IPR;
-        if (r < m0.y) {
-            const f32x4 raw = from_feats ? *reinterpret_cast<const f32x4 *>(featb + m0.x + r)
-                                         : *reinterpret_cast<const f32x4 *>(xb + static_cast<size_t>(m0.x + r) * H + 4 * q);
-            *reinterpret_cast<f32x4 *>(&resbuf[0][r * H + 4 * q]) = from_feats ? project4(raw, q) : raw;
-        }
-    }
+    gather(m0.w, (m0.y + kTileNodes - 1) / kTileNodes, ent1, bit0);
     __syncthreads();
 
     for (int c = c_begin; c < c_end; ++c) {
         const int rows = m0.y;
-        const int ntile = (rows + kTileNodes - 1) / kTileNodes;
+        const bool two = rows > kTileNodes;      // the chunk fills a second row tile
         const bool has_next = c + 1 < c_end;
         const int par = (c - c_begin) & 1;
-
-        // ---- gather: a_v = sum of neighbour messages from the LDS table, split into three
-        // bf16 parts, written as three A rows of the first layer
-        int my_bit[PGN];
-        const int cmax = m0.w;                   // most table entries of any row of the chunk
-#pragma unroll
-        for (int i = 0; i < PGN; ++i) {
-            const int e = tid + i * kThreads;
-            const int r = e / IPR, q = e - r * IPR;
-            my_bit[i] = 0;
-            if (r >= rows) continue;
-            const uint32_t w0 = ent0[i].x, w1 = ent0[i].y, w2 = ent0[i].z, w3 = ent0[i].w;
-            const int cnt_raw = w0 & 0xFFFF;
-            const int cnt = cnt_raw == 0xFFFF ? 0 : cnt_raw;
-            const int raw[kMaxEnt] = {static_cast<int>(w0 >> 16), static_cast<int>(w1 & 0xFFFF),
-                                      static_cast<int>(w1 >> 16), static_cast<int>(w2 & 0xFFFF),
-                                      static_cast<int>(w2 >> 16), static_cast<int>(w3 & 0xFFFF),
-                                      static_cast<int>(w3 >> 16)};
-            float sum[4] = {0.f, 0.f, 0.f, 0.f};
-            float flag = 0.0f;                   // sum of the sources' flag column
-#pragma unroll
-            for (int k = 0; k < kMaxEnt; ++k) {
-                if (k < cmax) {                  // uniform bound; short rows read the zero row
-                    const int slot = k < cnt ? raw[k] : kMsgSlots;
-                    const float4 x = *reinterpret_cast<const float4 *>(msgtab + slot * LDM + 4 * q);
-                    sum[0] += x.x; sum[1] += x.y; sum[2] += x.z; sum[3] += x.w;
-                    flag += msgtab[slot * LDM + H];
-                }
-            }
-            if (cnt_raw == 0xFFFF) {
-                // a row with more neighbours than its record holds: a list of table slots
-                // (recent sources) and node ids (sources at least three chunks back)
-                const int d0 = static_cast<int>(w0 >> 16) | (static_cast<int>(w1 & 0xFFFF) << 16);
-                const int d1 = d0 + (static_cast<int>(w1 >> 16) | (static_cast<int>(w2 & 0xFFFF) << 16));
-                for (int p = d0; p < d1; ++p) {
-                    const int u = plan.ovf[p];
-                    float4 x;
-                    if (u < 0) {
-                        x = *reinterpret_cast<const float4 *>(msgtab + (-1 - u) * LDM + 4 * q);
-                        flag += msgtab[(-1 - u) * LDM + H];
-                    } else {
-                        x = *reinterpret_cast<const float4 *>(msg + static_cast<uint32_t>(u * H + 4 * q));
-                        flag += ((u == cur) | reach[u]) ? 1.0f : 0.0f;
-                    }
-                    sum[0] += x.x; sum[1] += x.y; sum[2] += x.z; sum[3] += x.w;
-                }
-            }
-            float rs[4], ls[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                rs[k] = sum[k] - trunc_bf16(sum[k]);
-                ls[k] = rs[k] - trunc_bf16(rs[k]);
-            }
-            __bf16 *dst = &actbuf[0][4 * r][4 * q];      // rows 4r, 4r+1, 4r+2 of the chunk's tiles
-            *reinterpret_cast<uint2 *>(dst) = uint2{pack_hi16(sum[0], sum[1]), pack_hi16(sum[2], sum[3])};
-            *reinterpret_cast<uint2 *>(dst + LDA) = uint2{pack_hi16(rs[0], rs[1]), pack_hi16(rs[2], rs[3])};
-            *reinterpret_cast<uint2 *>(dst + 2 * LDA) = uint2{pack_hi16(ls[0], ls[1]), pack_hi16(ls[2], ls[3])};
-            my_bit[i] = flag > 0.0f;             // reachability bit of the row's node
-            if (q == 0) vtab[r] = vg0[i];
-        }
-        lds_barrier();
 
         // Plain vector types on purpose: arrays of the HIP float4 class that are written in one
         // unrolled branch and read in another are not always split into registers.
         f32x4 pf[PFN];           // far messages of chunk c + 1, in flight during the later layers
         int pf_reach[PFN];
         bool pf_cur[PFN];
-        f32x4 pr[PGN];           // residual inputs of chunk c + 1
-        int vg1[PGN];
         int4 m2 = m1;
-        f32x4 acc[TPW][NT][NACC];
+        // Accumulators: a chunk of one row tile splits its k-steps over two chains per column
+        // tile (acc[chain][t]); a chunk of two row tiles runs one chain per (row tile, column
+        // tile) (acc[ct][t]): four independent chains either way.
+        f32x4 acc[2][TPW];
 
 #pragma unroll
         for (int n = 0; n < NL; ++n) {
-            // ---- rows of A from LDS (activation parts), weights from registers; the k-steps
-            // alternate between two accumulators so that the MFMA chains are half as long
-#pragma unroll
-            for (int ct = 0; ct < NT; ++ct) {
-#pragma unroll
-                for (int t = 0; t < TPW; ++t)
-#pragma unroll
-                    for (int h = 0; h < NACC; ++h) acc[t][ct][h] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (ct >= ntile) continue;
+            // ---- rows of A from LDS (activation parts), weights from registers
+            auto mfma_one_tile = [&]() {
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a =
-                        *reinterpret_cast<const bf16x8 *>(&actbuf[n & 1][16 * ct + col][32 * ks + 8 * kg]);
+                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&actbuf[n & 1][col][32 * ks + 8 * kg]);
 #pragma unroll
                     for (int t = 0; t < TPW; ++t)
 #pragma unroll
-                        for (int ws = 0; ws < WS; ++ws)
-                            acc[t][ct][ks % NACC] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                a, W[n][t][ks][ws], acc[t][ct][ks % NACC], 0, 0, 0);
+                        for (int ws = 0; ws < WS; ++ws) {
+                            const f32x4 c_in = (ks < NACC && ws == 0) ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[ks % NACC][t];
+                            acc[ks % NACC][t] =
+                                __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W[n][t][ks][ws], c_in, 0, 0, 0);
+                        }
+                }
+                if constexpr (NACC == 1) {
+#pragma unroll
+                    for (int t = 0; t < TPW; ++t) acc[1][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            };
+            auto mfma_two_tiles = [&]() {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                    for (int ct = 0; ct < 2; ++ct) {
+                        const bf16x8 a =
+                            *reinterpret_cast<const bf16x8 *>(&actbuf[n & 1][16 * ct + col][32 * ks + 8 * kg]);
+#pragma unroll
+                        for (int t = 0; t < TPW; ++t)
+#pragma unroll
+                            for (int ws = 0; ws < WS; ++ws) {
+                                const f32x4 c_in = (ks == 0 && ws == 0) ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[ct][t];
+                                acc[ct][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W[n][t][ks][ws], c_in, 0, 0, 0);
+                            }
+                    }
+            };
+            // ---- epilogue: lane (col, kg) holds, for node 4 ct + kg and output column
+            // wc0 + 16 t + col, the three partial products in rows 0..2 of its accumulators
+            auto epilogue = [&](int ct, bool both) {
+                const int r = ct * kTileNodes + kg;
+                const bool live = r < rows;
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) {
+                    const int m = wc0 + 16 * t + col;
+                    float y;
+                    if (both)
+                        y = acc[ct][t][0] + acc[ct][t][1] + acc[ct][t][2];
+                    else
+                        y = (acc[0][t][0] + acc[0][t][1] + acc[0][t][2]) + (acc[1][t][0] + acc[1][t][1] + acc[1][t][2]);
+                    y = fmaxf(y + bias[n][t], 0.0f);
+                    if (n == L - 1) {                    // end of g: residual update of s_v
+                        y += x0[ct][t];
+                        if (live) {
+                            P.emb[static_cast<uint32_t>(vg0[ct] * 2 * H + dir * H + m)] = y;
+                            if (P.write_xb) xb[static_cast<uint32_t>((m0.x + r) * H + m)] = y;
+                        }
+                    }
+                    if (n == NL - 1) {                   // end of f: the message of v
+                        if (live) msg[static_cast<uint32_t>(vg0[ct] * H + m)] = y;
+                        msgtab[(par * CH + r) * LDM + m] = y;
+                    } else {
+                        put_parts((n + 1) & 1, r, m, y);
+                    }
+                }
+            };
+
+            if (two)
+                mfma_two_tiles();
+            else
+                mfma_one_tile();
+
+            if (n == 0) {
+                // The inputs of this chunk's residual, then the loads for the next chunk, issued
+                // behind the first layer's matrix instructions.  The loads may read messages
+                // that this workgroup stored to HBM at least two chunks ago.  Those stores are
+                // complete: vector memory operations of a wave retire in order, and every wave
+                // waited for its own previous batch of these loads (issued after those stores)
+                // before the last barrier of the previous chunk.
+                if constexpr (FF) {
+#pragma unroll
+                    for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+                        for (int t = 0; t < TPW; ++t) x0[ct][t] = project(ft0[ct], t);
+                }
+#pragma unroll
+                for (int i = 0; i < PFN; ++i) {
+                    const int e = lane + 64 * i;
+                    const int f = e / QW, q = e - f * QW;
+                    const bool wanted = has_next && f < m1.z && fid1[i] >= 0;
+                    // lanes without a far source read a spare row that is never written, so
+                    // that every wave has a load of this batch to wait for
+                    const int u = wanted ? fid1[i] : spare_row;
+                    pf[i] = *reinterpret_cast<const f32x4 *>(msg + static_cast<uint32_t>(u * H + wc0 + 4 * q));
+                    pf_reach[i] = reach[static_cast<uint32_t>(u)];   // combined with pf_cur at the end of the chunk
+                    pf_cur[i] = wanted && u == cur;
+                }
+                m2 = load_uniform(plan.meta + clampc(c + 2));
+#pragma unroll
+                for (int ct = 0; ct < NT; ++ct) {
+                    const int r = 4 * ct + kg;
+                    const int rr = (r < m1.y) ? r : 0;
+                    ent1[ct] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(clampc(c + 1)) * CH +
+                                                               static_cast<uint32_t>(r));
+                    vg1[ct] = (order + m1.x)[static_cast<uint32_t>(rr)];
+                    if constexpr (FF) {
+                        ft0[ct] = *reinterpret_cast<const f32x4 *>(featb + m1.x + static_cast<uint32_t>(rr));
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < TPW; ++t)
+                            x1[ct][t] = (xb + static_cast<size_t>(m1.x) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < PFN; ++i) {     // ids staged two chunks ahead of their data
+                    const int f = (lane + 64 * i) / QW;
+                    fid1[i] = (f < FCAP) ? (plan.far + static_cast<size_t>(clampc(c + 2)) * FCAP)[static_cast<uint32_t>(f)] : -1;
                 }
             }
 
-            // ---- epilogue: lane (col, kg) holds, for node 4 ct + kg and output column
-            // 16 nt + col, the three partial products in acc[..][0..2]
-#pragma unroll
-            for (int ct = 0; ct < NT; ++ct) {
-                if (ct >= ntile) continue;
-                const int r = ct * kTileNodes + kg;
-                if (r >= rows) continue;
-#pragma unroll
-                for (int t = 0; t < TPW; ++t) {
-                    const int m = (wave * TPW + t) * 16 + col;
-                    float y = acc[t][ct][0][0] + acc[t][ct][0][1] + acc[t][ct][0][2];
-                    if constexpr (NACC > 1) y += acc[t][ct][1][0] + acc[t][ct][1][1] + acc[t][ct][1][2];
-                    y = fmaxf(y + bias[n][t], 0.0f);
-                    if (n == L - 1) {                    // end of g: residual update of s_v
-                        y += resbuf[par][r * H + m];
-                        P.emb[static_cast<uint32_t>(vtab[r] * 2 * H + dir * H + m)] = y;
-                        if (P.write_xb) xb[static_cast<uint32_t>((m0.x + r) * H + m)] = y;
-                    }
-                    if (n == NL - 1) {                   // end of f: the message of v
-                        msg[static_cast<uint32_t>(vtab[r] * H + m)] = y;
-                        msgtab[(par * CH + r) * LDM + m] = y;
-                    } else {
-                        const float rr = y - trunc_bf16(y);
-                        const float ll = rr - trunc_bf16(rr);
-                        unsigned short *dst =
-                            reinterpret_cast<unsigned short *>(&actbuf[(n + 1) & 1][4 * r][m]);
-                        dst[0] = static_cast<unsigned short>(__float_as_uint(y) >> 16);
-                        dst[LDA] = static_cast<unsigned short>(__float_as_uint(rr) >> 16);
-                        dst[2 * LDA] = static_cast<unsigned short>(__float_as_uint(ll) >> 16);
-                    }
-                }
+            if (two) {
+                epilogue(0, true);
+                epilogue(1, true);
+            } else {
+                epilogue(0, false);
             }
 
             if (n == NL - 1) {
+                // reachability bits of this chunk's nodes: to HBM and into the wave's flag column
+#pragma unroll
+                for (int ct = 0; ct < NT; ++ct) {
+                    const int r = ct * kTileNodes + kg;
+                    if (col == 0) {
+                        msgtab[(par * CH + r) * LDM + H + wave] = (bit0[ct] | (vg0[ct] == cur)) ? 1.0f : 0.0f;
+                        if (wave == 0 && r < rows) reach[vg0[ct]] = static_cast<uint8_t>(bit0[ct]);
+                    }
+                }
                 // Wait for this wave's prefetch batch whether or not a lane uses it: the stores
                 // that preceded it are then complete too (see the note at the prefetch).
 #pragma unroll
                 for (int i = 0; i < PFN; ++i) asm volatile("" ::"v"(pf[i][0]), "v"(pf_reach[i]));
-                // An offset the compiler cannot see through, defined only here: without it the
-                // staged LDS stores below are scheduled right behind their loads, which puts
-                // the whole HBM latency back on the critical path.
-                int late = 0;
-                asm volatile("" : "+v"(late));
-                // reachability bits of this chunk's nodes, then the staged data of chunk c + 1
+                if (has_next) {
+                    // An offset the compiler cannot see through, defined only here: without it
+                    // the staged LDS stores below are scheduled right behind their loads, which
+                    // puts the whole HBM latency back on the critical path.
+                    int late = 0;
+                    asm volatile("" : "+v"(late));
 #pragma unroll
-                for (int i = 0; i < PGN; ++i) {
-                    const int e = tid + i * kThreads;
-                    const int r = e / IPR, q = e - r * IPR;
-                    if (q == 0 && r < rows) {
-                        reach[vg0[i]] = static_cast<uint8_t>(my_bit[i]);
-                        msgtab[(par * CH + r) * LDM + H] = (my_bit[i] | (vg0[i] == cur)) ? 1.0f : 0.0f;
+                    for (int i = 0; i < PFN; ++i) {     // far messages of chunk c + 1, this wave's columns
+                        const int e = lane + 64 * i;
+                        const int f = e / QW, q = e - f * QW;
+                        if (f < m1.z) {
+                            const int slot = RING * CH + (par ^ 1) * FCAP + f;
+                            *reinterpret_cast<f32x4 *>(msgtab + slot * LDM + wc0 + 4 * q + late) = pf[i];
+                            if (q == 0) msgtab[slot * LDM + H + wave + late] = ((pf_reach[i] != 0) | pf_cur[i]) ? 1.0f : 0.0f;
+                        }
                     }
-                    if (has_next && r < m1.y)
-                        *reinterpret_cast<f32x4 *>(&resbuf[par ^ 1][r * H + 4 * q + late]) =
-                            from_feats ? project4(pr[i], q) : pr[i];
+                    // The table rows that chunk c + 1 sums were all written by this wave (its own
+                    // columns), so its gather follows without a barrier.
+                    gather(m1.w, (m1.y + kTileNodes - 1) / kTileNodes, ent1, bit0);
                 }
-#pragma unroll
-                for (int i = 0; i < PFN; ++i) {
-                    const int e = tid + i * kThreads;
-                    const int f = e / TPR, q = e - f * TPR;
-                    if (has_next && f < m1.z) {
-                        const int slot = RING * CH + (par ^ 1) * FCAP + f;
-                        *reinterpret_cast<f32x4 *>(msgtab + slot * LDM + 4 * q + late) = pf[i];
-                        if (q == 0) msgtab[slot * LDM + H + late] = ((pf_reach[i] != 0) | pf_cur[i]) ? 1.0f : 0.0f;
-                    }
-                }
-                lds_barrier();
-            } else if (n == 0) {
-                // The loads for the next chunk are issued here, one layer into the chunk.
-                // They may read messages that this workgroup stored to HBM at least two
-                // chunks ago.  Those stores are complete: vector memory operations of a wave
-                // retire in order, and every wave waited for its own previous batch of these
-                // loads (issued after those stores) before the last barrier of the previous
-                // chunk (see the end-of-chunk stage above).
-                lds_barrier();
-#pragma unroll
-                for (int i = 0; i < PFN; ++i) {
-                    const int e = tid + i * kThreads;
-                    const int f = e / TPR, q = e - f * TPR;
-                    const bool live = has_next && f < m1.z && fid1[i] >= 0;
-                    // lanes without a far source read a spare row that is never written, so
-                    // that every wave has a load of this batch to wait for
-                    const int u = live ? fid1[i] : spare_row;
-                    pf[i] = *reinterpret_cast<const f32x4 *>(msg + static_cast<uint32_t>(u * H + 4 * q));
-                    pf_reach[i] = reach[static_cast<uint32_t>(u)];   // combined with pf_cur at the end of the chunk
-                    pf_cur[i] = live && u == cur;
-                }
-                m2 = load_uniform(plan.meta + clampc(c + 2));
-#pragma unroll
-                for (int i = 0; i < PGN; ++i) {
-                    const int e = tid + i * kThreads;
-                    const int r = e / IPR, q = e - r * IPR;
-                    const int rr = (r < m1.y) ? r : 0;
-                    pr[i] = from_feats ? *reinterpret_cast<const f32x4 *>(featb + m1.x + static_cast<uint32_t>(rr))
-                                       : *reinterpret_cast<const f32x4 *>(xb + static_cast<size_t>(m1.x) * H +
-                                                                          static_cast<uint32_t>(rr * H + 4 * q));
-                    ent0[i] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(clampc(c + 1)) * CH +
-                                                              static_cast<uint32_t>(rr));
-                    vg1[i] = (order + m1.x)[static_cast<uint32_t>(rr)];
-                }
-#pragma unroll
-                for (int i = 0; i < PFN; ++i) {     // ids staged two chunks ahead of their data
-                    const int f = (tid + i * kThreads) / TPR;
-                    fid1[i] = (f < FCAP) ? (plan.far + static_cast<size_t>(clampc(c + 2)) * FCAP)[static_cast<uint32_t>(f)] : -1;
-                }
-            } else {
-                lds_barrier();
             }
+            lds_barrier();
         }
 
         m0 = m1;
         m1 = m2;
 #pragma unroll
-        for (int i = 0; i < PGN; ++i) vg0[i] = vg1[i];
+        for (int ct = 0; ct < NT; ++ct) {
+            vg0[ct] = vg1[ct];
+            if constexpr (!FF) {
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) x0[ct][t] = x1[ct][t];
+            }
+        }
     }
 }
 
@@ -512,7 +588,10 @@ void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace
     const dim3 grid(2 * gv.B);
 #define PL_CASE(HH, WW, LL)                                                      \
     if (mv.H == HH && WS == WW && mv.L == LL) {                                  \
-        hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL>), grid, dim3(64 * sweep_waves(HH)), 0, s, P); \
+        if (first_sweep)                                                         \
+            hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, true>), grid, dim3(64 * sweep_waves(HH)), 0, s, P);  \
+        else                                                                     \
+            hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, false>), grid, dim3(64 * sweep_waves(HH)), 0, s, P); \
         return;                                                                  \
     }
     PL_CASE(128, 1, 2) PL_CASE(128, 1, 1)

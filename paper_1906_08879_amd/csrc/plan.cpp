@@ -4,7 +4,9 @@
 // of at most kChunkRows nodes.  The kernel keeps the messages of the last kRing chunks in an
 // LDS table and stages messages from older chunks ("far" sources) into the same table one
 // chunk ahead.  This file turns the CSR into, per chunk: its position and row count, for
-// every row the LDS table slots of its neighbours, and the list of far sources to stage.
+// every row the LDS table slots of its neighbours (unused entries name the table's zero row,
+// slot kMsgSlots, so that a fixed number of entries can be summed without tests), and the
+// list of far sources to stage.
 #include <algorithm>
 #include <cstdint>
 #include <vector>
@@ -44,13 +46,18 @@ int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
         }
         const int32_t n_chunks = static_cast<int32_t>(P.meta.size() / 4) - first;
         P.ck_off[b + 1] = first + n_chunks;
-        P.ent.resize(static_cast<size_t>(first + n_chunks) * kChunkRows * 8, 0);
+        // every record starts as "no neighbours": count 0, all entries the table's zero row
+        {
+            const size_t old = P.ent.size();
+            P.ent.resize(static_cast<size_t>(first + n_chunks) * kChunkRows * 8, static_cast<uint16_t>(kMsgSlots));
+            for (size_t i = old; i < P.ent.size(); i += 8) P.ent[i] = 0;
+        }
         P.far.resize(static_cast<size_t>(first + n_chunks) * kFarCap, -1);
         // pass 2: neighbour slots
         for (int32_t c = 0; c < n_chunks; ++c) {
             int32_t *meta = &P.meta[static_cast<size_t>(first + c) * 4];
             int32_t *far = &P.far[static_cast<size_t>(first + c) * kFarCap];
-            int32_t n_far = 0, max_ent = 0;
+            int32_t n_far = 0, max_ent = 0, has_ovf = 0;
             const int32_t p0 = meta[0] - static_cast<int32_t>(n0);
             for (int32_t r = 0; r < meta[1]; ++r) {
                 uint16_t *ent = &P.ent[(static_cast<size_t>(first + c) * kChunkRows + r) * 8];
@@ -70,6 +77,7 @@ int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
                 }
                 if (direct) {            // the row's list goes to the overflow array
                     const uint32_t off = static_cast<uint32_t>(P.ovf.size());
+                    has_ovf = 1;
                     ent[0] = 0xFFFF;
                     ent[1] = static_cast<uint16_t>(off & 0xFFFF);
                     ent[2] = static_cast<uint16_t>(off >> 16);
@@ -101,7 +109,7 @@ int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
                 }
             }
             meta[2] = n_far;
-            meta[3] = max_ent;
+            meta[3] = max_ent | (has_ovf << 8);
         }
     }
     P.n_chunks = static_cast<int64_t>(P.meta.size() / 4);
