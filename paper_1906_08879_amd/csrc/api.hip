@@ -254,11 +254,13 @@ int ensure_workspace(pl_graph_batch *g, const ModelView &mv)
     const size_t n = static_cast<size_t>(g->host.n_tot), H = mv.H;
     int rc = ensure_reach(g);
     if (rc) return rc;
-    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.emb), sizeof(float) * (n * 2 * H + 4)));
-    // one spare row after both directions' messages: never written, target of dummy loads
-    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.msg), sizeof(float) * (2 * n * H + H + 4)));
-    PL_HIP(hipMemset(ws.msg, 0, sizeof(float) * (2 * n * H + H + 4)));
-    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.xb), sizeof(float) * (2 * n * H + 4)));
+    // Rows past the data (matrix-core sweep): emb row n, msg row 2n + 1, xb row 2n and reach
+    // byte 2n + 1 take the stores of a chunk's unused rows; msg row 2n and reach byte 2n are
+    // never written and are the target of dummy loads.
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.emb), sizeof(float) * ((n + 1) * 2 * H + 4)));
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.msg), sizeof(float) * ((2 * n + 2) * H + 4)));
+    PL_HIP(hipMemset(ws.msg, 0, sizeof(float) * ((2 * n + 2) * H + 4)));
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.xb), sizeof(float) * ((2 * n + 1) * H + 4)));
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.featb), sizeof(float4) * (2 * n + 1)));
     ws.n_chunks = 8;
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.partial),
@@ -315,7 +317,7 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
     ForwardArgs fa{node_feats, placement, cur_node, out_logits, out_probs, out_pooled};
     const GraphView &gv = g->view;
     // the matrix-core sweep addresses its buffers with 32-bit offsets
-    const bool fits32 = static_cast<double>(g->host.n_tot) * 2 * mv.H * sizeof(float) < 4.0e9;
+    const bool fits32 = (static_cast<double>(g->host.n_tot) + 2) * 2 * mv.H * sizeof(float) < 4.0e9;
     const bool mfma = w->d_wfrag && w->path == 0 && w->cfg.k_sweeps > 0 && fits32;
     {
         // the matrix-core sweep computes x_v itself from the raw features (first sweep)

@@ -62,7 +62,6 @@ struct SweepParams {
     float *msg;             // [2, n_tot, H]
     uint8_t *reach;         // [2, n_tot]
     const int32_t *cur_node;
-    int write_xb;           // another sweep follows: keep xb current
     // first sweep: the input x_v = relu(W_in^T phi_v + b_in) (Section 2.2 step 1) is computed
     // here from the node's raw features, kept in bucket order, 16 bytes per node
     const float4 *featb;    // [2, n_tot] {run time, output size, is-visited, bits(device | is-current << 16)}
@@ -83,8 +82,8 @@ __device__ __forceinline__ int4 load_uniform(const int4 *p)
 constexpr int sweep_waves(int H) { return H / 16 > 4 ? 4 : H / 16; }
 
 // FF: first sweep, the input x_v is computed from the raw-feature records; otherwise it is
-// read from xb.
-template <int H, int WS, int L, bool FF>
+// read from xb.  WX: another sweep follows, s_v is also written to xb.
+template <int H, int WS, int L, bool FF, bool WX>
 __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepParams P)
 {
     constexpr int NW = sweep_waves(H);         // waves; wave w owns output columns [w WC, (w + 1) WC)
@@ -127,8 +126,12 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     const int c_begin = plan.ck_off[b], c_end = plan.ck_off[b + 1];
     if (c_begin >= c_end) return;
     // one row past both directions' messages (and one byte past both directions' bits) is
-    // never written: the address of dummy loads, relative to this direction's base
+    // never written: the address of dummy loads, relative to this direction's base.  The row
+    // (byte) after it, and row n_tot of emb, take the stores of a chunk's unused rows: every
+    // lane stores on every chunk, so the number of stores in flight behind a load is known
+    // when the kernel is compiled and a wait for that load does not wait for the stores.
     const int spare_row = (2 - dir) * gv.n_tot;
+    const int sink_row = spare_row + 1;
 
     // ---- weights of this direction into registers (B operand: lane holds column 16 nt + col)
     bf16x8 W[NL][TPW][KS][WS];
@@ -265,8 +268,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     };
     // w = meta.w of the chunk: most entries of a row | (a row uses the list) << 8
     auto gather = [&](int w, int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT]) {
-        if (w <= 3)
-            gather_fixed(std::integral_constant<int, 3>{}, ntile_x, ent, bit);
+        if (w <= 2)
+            gather_fixed(std::integral_constant<int, 2>{}, ntile_x, ent, bit);
         else if (w <= kMaxEnt)
             gather_fixed(std::integral_constant<int, kMaxEnt>{}, ntile_x, ent, bit);
         else
@@ -309,6 +312,20 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     }
     __syncthreads();
     gather(m0.w, (m0.y + kTileNodes - 1) / kTileNodes, ent1, bit0);
+    // every load so far has returned before the loop is entered (inside the loop the compiler
+    // then never waits for more than the loads of the loop's own batch)
+#pragma unroll
+    for (int i = 0; i < PFN; ++i) asm volatile("" ::"v"(fid1[i]));
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        asm volatile("" ::"v"(vg0[ct]), "v"(vg1[ct]));
+        if constexpr (FF) {
+            asm volatile("" ::"v"(ft0[ct][0]));
+        } else {
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) asm volatile("" ::"v"(x0[ct][t]), "v"(x1[ct][t]));
+        }
+    }
     __syncthreads();
 
     for (int c = c_begin; c < c_end; ++c) {
@@ -367,27 +384,29 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             };
             // ---- epilogue: lane (col, kg) holds, for node 4 ct + kg and output column
             // wc0 + 16 t + col, the three partial products in rows 0..2 of its accumulators
-            auto epilogue = [&](int ct, bool both) {
+            // Row tile 0 is handled by code common to both kinds of chunk, so that its stores
+            // are on every path (see sink_row).
+            auto epilogue = [&](int ct) {
                 const int r = ct * kTileNodes + kg;
                 const bool live = r < rows;
+                const int v_emb = live ? vg0[ct] : gv.n_tot;
+                const int v_msg = live ? vg0[ct] : sink_row;
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
                     const int m = wc0 + 16 * t + col;
-                    float y;
-                    if (both)
-                        y = acc[ct][t][0] + acc[ct][t][1] + acc[ct][t][2];
-                    else
-                        y = (acc[0][t][0] + acc[0][t][1] + acc[0][t][2]) + (acc[1][t][0] + acc[1][t][1] + acc[1][t][2]);
+                    float y = acc[ct][t][0] + acc[ct][t][1] + acc[ct][t][2];
+                    if (ct == 0) {                       // one row tile: acc[1] is the second chain
+                        const float y1 = acc[1][t][0] + acc[1][t][1] + acc[1][t][2];
+                        y += two ? 0.0f : y1;
+                    }
                     y = fmaxf(y + bias[n][t], 0.0f);
                     if (n == L - 1) {                    // end of g: residual update of s_v
                         y += x0[ct][t];
-                        if (live) {
-                            P.emb[static_cast<uint32_t>(vg0[ct] * 2 * H + dir * H + m)] = y;
-                            if (P.write_xb) xb[static_cast<uint32_t>((m0.x + r) * H + m)] = y;
-                        }
+                        P.emb[static_cast<uint32_t>(v_emb * 2 * H + dir * H + m)] = y;
+                        if constexpr (WX) xb[static_cast<uint32_t>((live ? m0.x + r : spare_row) * H + m)] = y;
                     }
                     if (n == NL - 1) {                   // end of f: the message of v
-                        if (live) msg[static_cast<uint32_t>(vg0[ct] * H + m)] = y;
+                        msg[static_cast<uint32_t>(v_msg * H + m)] = y;
                         msgtab[(par * CH + r) * LDM + m] = y;
                     } else {
                         put_parts((n + 1) & 1, r, m, y);
@@ -407,14 +426,20 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 // complete: vector memory operations of a wave retire in order, and every wave
                 // waited for its own previous batch of these loads (issued after those stores)
                 // before the last barrier of the previous chunk.
+                // Work for a second row tile (rows 4..7) is skipped when the chunk has none, and
+                // far rows beyond the first 64 / QW only when the next chunk stages that many.
                 if constexpr (FF) {
 #pragma unroll
                     for (int ct = 0; ct < NT; ++ct)
+                        if (ct == 0 || two) {
 #pragma unroll
-                        for (int t = 0; t < TPW; ++t) x0[ct][t] = project(ft0[ct], t);
+                            for (int t = 0; t < TPW; ++t) x0[ct][t] = project(ft0[ct], t);
+                        }
                 }
+                const bool two_next = m1.y > kTileNodes;
 #pragma unroll
                 for (int i = 0; i < PFN; ++i) {
+                    if (i > 0 && m1.z <= i * (64 / QW)) continue;
                     const int e = lane + 64 * i;
                     const int f = e / QW, q = e - f * QW;
                     const bool wanted = has_next && f < m1.z && fid1[i] >= 0;
@@ -428,6 +453,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 m2 = load_uniform(plan.meta + clampc(c + 2));
 #pragma unroll
                 for (int ct = 0; ct < NT; ++ct) {
+                    if (ct > 0 && !two_next) continue;
                     const int r = 4 * ct + kg;
                     const int rr = (r < m1.y) ? r : 0;
                     ent1[ct] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(clampc(c + 1)) * CH +
@@ -448,27 +474,33 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 }
             }
 
-            if (two) {
-                epilogue(0, true);
-                epilogue(1, true);
-            } else {
-                epilogue(0, false);
-            }
+            epilogue(0);
+            if (two) epilogue(1);
 
             if (n == NL - 1) {
                 // reachability bits of this chunk's nodes: to HBM and into the wave's flag column
 #pragma unroll
                 for (int ct = 0; ct < NT; ++ct) {
                     const int r = ct * kTileNodes + kg;
-                    if (col == 0) {
-                        msgtab[(par * CH + r) * LDM + H + wave] = (bit0[ct] | (vg0[ct] == cur)) ? 1.0f : 0.0f;
-                        if (wave == 0 && r < rows) reach[vg0[ct]] = static_cast<uint8_t>(bit0[ct]);
-                    }
+                    if (col == 0) msgtab[(par * CH + r) * LDM + H + wave] = (bit0[ct] | (vg0[ct] == cur)) ? 1.0f : 0.0f;
+                    reach[static_cast<uint32_t>((wave == 0 && col == 0 && r < rows) ? vg0[ct] : sink_row)] =
+                        static_cast<uint8_t>(bit0[ct]);
                 }
                 // Wait for this wave's prefetch batch whether or not a lane uses it: the stores
                 // that preceded it are then complete too (see the note at the prefetch).
 #pragma unroll
-                for (int i = 0; i < PFN; ++i) asm volatile("" ::"v"(pf[i][0]), "v"(pf_reach[i]));
+                for (int i = 0; i < PFN; ++i) asm volatile("" ::"v"(pf[i][0]), "v"(pf_reach[i]), "v"(fid1[i]));
+                // ... and for the rest of the batch, which the next chunk then uses without waiting
+#pragma unroll
+                for (int ct = 0; ct < NT; ++ct) {
+                    asm volatile("" ::"v"(ent1[ct][0]), "v"(vg1[ct]));
+                    if constexpr (FF) {
+                        asm volatile("" ::"v"(ft0[ct][0]));
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < TPW; ++t) asm volatile("" ::"v"(x1[ct][t]));
+                    }
+                }
                 if (has_next) {
                     // An offset the compiler cannot see through, defined only here: without it
                     // the staged LDS stores below are scheduled right behind their loads, which
@@ -477,6 +509,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     asm volatile("" : "+v"(late));
 #pragma unroll
                     for (int i = 0; i < PFN; ++i) {     // far messages of chunk c + 1, this wave's columns
+                        if (m1.z <= i * (64 / QW)) continue;
                         const int e = lane + 64 * i;
                         const int f = e / QW, q = e - f * QW;
                         if (f < m1.z) {
@@ -580,7 +613,7 @@ void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace
                        bool first_sweep, bool more_sweeps, hipStream_t s)
 {
     if (gv.B == 0) return;
-    SweepParams P{gv, wfrag, bias, ws.emb, ws.xb, ws.msg, ws.reach, fa.cur_node, more_sweeps ? 1 : 0,
+    SweepParams P{gv, wfrag, bias, ws.emb, ws.xb, ws.msg, ws.reach, fa.cur_node,
                   ws.featb, first_sweep ? mv.blob + mv.proj.w : nullptr, mv.D};
     if (first_sweep)
         hipLaunchKernelGGL(k_bucket_feats, dim3((gv.n_tot + 255) / 256), dim3(256), 0, s, gv, fa.node_feats,
@@ -588,10 +621,15 @@ void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace
     const dim3 grid(2 * gv.B);
 #define PL_CASE(HH, WW, LL)                                                      \
     if (mv.H == HH && WS == WW && mv.L == LL) {                                  \
-        if (first_sweep)                                                         \
-            hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, true>), grid, dim3(64 * sweep_waves(HH)), 0, s, P);  \
+        const dim3 block(64 * sweep_waves(HH));                                  \
+        if (first_sweep && more_sweeps)                                          \
+            hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, true, true>), grid, block, 0, s, P);   \
+        else if (first_sweep)                                                    \
+            hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, true, false>), grid, block, 0, s, P);  \
+        else if (more_sweeps)                                                    \
+            hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, false, true>), grid, block, 0, s, P);  \
         else                                                                     \
-            hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, false>), grid, dim3(64 * sweep_waves(HH)), 0, s, P); \
+            hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, false, false>), grid, block, 0, s, P); \
         return;                                                                  \
     }
     PL_CASE(128, 1, 2) PL_CASE(128, 1, 1)
