@@ -101,10 +101,10 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     constexpr int kZeroSlot = kMsgSlots;
     static_assert(NTL % NW == 0, "column tiles must divide over the waves");
 
-    // Message table: H floats per row, then one flag column PER WAVE (1.0 if the node is v* or
-    // has v* among the nodes it was computed from: the reachability bit).  A wave reads and
-    // writes only its own columns and its own flag column, so the table needs no barrier.
-    // The last row stays zero.
+    // Message table: H floats per row.  Messages are ReLU outputs, so their sign bit is free:
+    // in the table it carries the reachability flag of the row's node (set if the node is v* or
+    // has v* among the nodes it was computed from); sums take |x|.  A wave reads and writes
+    // only its own columns, so the table needs no barrier.  The last row stays zero.
     __shared__ __attribute__((aligned(16))) float msgtab[(kMsgSlots + 1) * LDM];
     __shared__ __attribute__((aligned(16))) __bf16 actbuf[2][NT * 16][LDA];
     __shared__ float proj_dev[(kMaxD + 1) * H];   // one-hot device rows of W_in, then a zero row
@@ -204,21 +204,23 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             bit[ct] = 0;
             if (ct >= ntile_x) continue;
             const u32x4 rec = ent[ct];
-            float s[TPW], fl = 0.0f;
-#pragma unroll
-            for (int t = 0; t < TPW; ++t) s[t] = 0.0f;
+            float s[TPW];
+            uint32_t signs = 0;
 #pragma unroll
             for (int k = 0; k < K; ++k) {
                 const int j = k + 1;
                 const int slot = (j & 1) ? static_cast<int>(rec[j >> 1] >> 16) : static_cast<int>(rec[j >> 1] & 0xFFFF);
                 const float *row = msgtab + slot * LDM;
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) s[t] += row[wc0 + 16 * t + col];
-                fl += row[H + wave];
+                for (int t = 0; t < TPW; ++t) {
+                    const float x = row[wc0 + 16 * t + col];
+                    s[t] = k == 0 ? fabsf(x) : s[t] + fabsf(x);
+                    if (t == 0) signs |= __float_as_uint(x);
+                }
             }
 #pragma unroll
             for (int t = 0; t < TPW; ++t) put_parts(0, 4 * ct + kg, wc0 + 16 * t + col, s[t]);
-            bit[ct] = fl > 0.0f;
+            bit[ct] = static_cast<int>(signs >> 31);
         }
     };
     // The same for a chunk in which some row has more neighbours than its record holds: that
@@ -231,7 +233,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             if (ct >= ntile_x) continue;
             const u32x4 rec = ent[ct];
             const bool listed = (rec[0] & 0xFFFF) == 0xFFFF;
-            float s[TPW], fl = 0.0f;
+            float s[TPW];
+            uint32_t signs = 0;
 #pragma unroll
             for (int t = 0; t < TPW; ++t) s[t] = 0.0f;
 #pragma unroll
@@ -240,8 +243,11 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 const int raw = (j & 1) ? static_cast<int>(rec[j >> 1] >> 16) : static_cast<int>(rec[j >> 1] & 0xFFFF);
                 const float *row = msgtab + (listed ? kZeroSlot : raw) * LDM;
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) s[t] += row[wc0 + 16 * t + col];
-                fl += row[H + wave];
+                for (int t = 0; t < TPW; ++t) {
+                    const float x = row[wc0 + 16 * t + col];
+                    s[t] += fabsf(x);
+                    signs |= __float_as_uint(x);
+                }
             }
             if (listed) {
                 const int d0 = static_cast<int>(rec[0] >> 16) | (static_cast<int>(rec[1] & 0xFFFF) << 16);
@@ -251,19 +257,22 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     if (u < 0) {
                         const float *row = msgtab + (-1 - u) * LDM;
 #pragma unroll
-                        for (int t = 0; t < TPW; ++t) s[t] += row[wc0 + 16 * t + col];
-                        fl += row[H + wave];
+                        for (int t = 0; t < TPW; ++t) {
+                            const float x = row[wc0 + 16 * t + col];
+                            s[t] += fabsf(x);
+                            signs |= __float_as_uint(x);
+                        }
                     } else {
 #pragma unroll
                         for (int t = 0; t < TPW; ++t)
                             s[t] += msg[static_cast<uint32_t>(u * H + wc0 + 16 * t + col)];
-                        fl += ((u == cur) | reach[static_cast<uint32_t>(u)]) ? 1.0f : 0.0f;
+                        signs |= ((u == cur) | reach[static_cast<uint32_t>(u)]) ? 0x80000000u : 0u;
                     }
                 }
             }
 #pragma unroll
             for (int t = 0; t < TPW; ++t) put_parts(0, 4 * ct + kg, wc0 + 16 * t + col, s[t]);
-            bit[ct] = fl > 0.0f;
+            bit[ct] = static_cast<int>(signs >> 31);
         }
     };
     // w = meta.w of the chunk: most entries of a row | (a row uses the list) << 8
@@ -407,7 +416,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     }
                     if (n == NL - 1) {                   // end of f: the message of v
                         msg[static_cast<uint32_t>(v_msg * H + m)] = y;
-                        msgtab[(par * CH + r) * LDM + m] = y;
+                        const uint32_t flag = (bit0[ct] | (vg0[ct] == cur)) ? 0x80000000u : 0u;
+                        msgtab[(par * CH + r) * LDM + m] = __uint_as_float(__float_as_uint(y) | flag);
                     } else {
                         put_parts((n + 1) & 1, r, m, y);
                     }
@@ -474,15 +484,12 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 }
             }
 
-            epilogue(0);
-            if (two) epilogue(1);
-
             if (n == NL - 1) {
-                // reachability bits of this chunk's nodes: to HBM and into the wave's flag column
+                // Behind the last layer's matrix instructions: the reachability bits of this
+                // chunk's nodes go to HBM and the far messages of the next chunk into the table.
 #pragma unroll
                 for (int ct = 0; ct < NT; ++ct) {
                     const int r = ct * kTileNodes + kg;
-                    if (col == 0) msgtab[(par * CH + r) * LDM + H + wave] = (bit0[ct] | (vg0[ct] == cur)) ? 1.0f : 0.0f;
                     reach[static_cast<uint32_t>((wave == 0 && col == 0 && r < rows) ? vg0[ct] : sink_row)] =
                         static_cast<uint8_t>(bit0[ct]);
                 }
@@ -514,15 +521,22 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         const int f = e / QW, q = e - f * QW;
                         if (f < m1.z) {
                             const int slot = RING * CH + (par ^ 1) * FCAP + f;
-                            *reinterpret_cast<f32x4 *>(msgtab + slot * LDM + wc0 + 4 * q + late) = pf[i];
-                            if (q == 0) msgtab[slot * LDM + H + wave + late] = ((pf_reach[i] != 0) | pf_cur[i]) ? 1.0f : 0.0f;
+                            const uint32_t flag = ((pf_reach[i] != 0) | pf_cur[i]) ? 0x80000000u : 0u;
+                            f32x4 v;
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) v[k] = __uint_as_float(__float_as_uint(pf[i][k]) | flag);
+                            *reinterpret_cast<f32x4 *>(msgtab + slot * LDM + wc0 + 4 * q + late) = v;
                         }
                     }
-                    // The table rows that chunk c + 1 sums were all written by this wave (its own
-                    // columns), so its gather follows without a barrier.
-                    gather(m1.w, (m1.y + kTileNodes - 1) / kTileNodes, ent1, bit0);
                 }
             }
+
+            epilogue(0);
+            if (two) epilogue(1);
+
+            // The table rows that chunk c + 1 sums were all written by this wave (its own
+            // columns), so its gather follows without a barrier.
+            if (n == NL - 1 && has_next) gather(m1.w, (m1.y + kTileNodes - 1) / kTileNodes, ent1, bit0);
             lds_barrier();
         }
 
