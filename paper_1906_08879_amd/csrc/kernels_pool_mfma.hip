@@ -10,8 +10,9 @@
 //     there: no cross-lane traffic;
 //   * the weights of l_i are the B operand and stay in registers for the whole kernel;
 //   * the rows of the next batch are loaded from HBM while the current one is computed;
-//   * the per-device sums are taken by one owner thread per output column in node order,
-//     so the result is bitwise reproducible.
+//   * the per-device sums are taken in registers, by the lane that holds a node's output in
+//     its accumulators, in batch order; the four lanes of a column are added once at the end
+//     in a fixed order, so the result is bitwise reproducible.
 #include "internal.h"
 
 namespace pl {
@@ -71,8 +72,6 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
 
     __shared__ __attribute__((aligned(16))) __bf16 act1[kBatch * 4][LD1];   // parts of the input rows
     __shared__ __attribute__((aligned(16))) __bf16 act2[kBatch * 4][LD2];   // parts of layer-1 outputs
-    __shared__ __attribute__((aligned(16))) float outb[kBatch][H];          // l_i outputs of the batch
-    __shared__ float accP[2][kMaxD][H];
     __shared__ int queue[kQueue];
     __shared__ int batch_node[2][kBatch];
     __shared__ int batch_dev[2][kBatch];
@@ -138,9 +137,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
     int have = 0;             // nodes of the batch whose rows are in flight (uniform)
     int slot = 0;             // batch_node buffer of the in-flight batch
     f32x4 x[NLD];             // the in-flight rows: item e = tid + i * 256 -> (node e / QPR, float4 e % QPR)
-    float acc_reg[kMaxD];     // per-device sums of this thread's (column, half)
+    float acc_dev[kMaxD][TPW];   // per-device sums over this lane's nodes (rows kg of every tile) and columns
 #pragma unroll
-    for (int d = 0; d < kMaxD; ++d) acc_reg[d] = 0.0f;
+    for (int d = 0; d < kMaxD; ++d)
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) acc_dev[d][t] = 0.0f;
 
     // Fills the queue until it holds a full batch or the graph is exhausted.
     auto refill = [&]() {
@@ -270,49 +271,53 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
                                 __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W2[t][ks][ws], acc[tl][t], 0, 0, 0);
                 }
         }
+        // ---- (5) per-device sums in registers: lane (col, kg) adds the outputs of its own
+        // nodes (4 tl + kg) to the sum of the node's device; nodes past the end of the batch
+        // have device -1 and are never added
+        float y[kTiles][TPW];
+        int dv[kTiles];
 #pragma unroll
         for (int tl = 0; tl < kTiles; ++tl) {
+            const int node = 4 * tl + kg;
+            dv[tl] = node < cnt ? batch_dev[my_slot][node] : -1;
 #pragma unroll
             for (int t = 0; t < TPW; ++t) {
-                const int nt = wave * TPW + t;
-                if (nt >= NTL) continue;
                 const float bl = (L > 1) ? bias2[t] : bias1[t];
-                outb[4 * tl + kg][16 * nt + col] =
-                    fmaxf(acc[tl][t][0] + acc[tl][t][1] + acc[tl][t][2] + bl, 0.0f);
+                y[tl][t] = fmaxf(acc[tl][t][0] + acc[tl][t][1] + acc[tl][t][2] + bl, 0.0f);
             }
         }
-        lds_barrier();
-        // ---- (5) per-device sums in registers: thread (column, half) adds its eight nodes of
-        // the batch in order; the two halves are combined once, after the last batch
-        if (tid < 2 * H) {
-            const int half = tid >= H ? 1 : 0, c = tid - half * H;
-            float o[8];
-            int dv[8];
+        // rows past the end of the batch hold earlier, finite outputs: weight 0 removes them
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int node = 8 * half + k;
-                o[k] = outb[node][c];
-                dv[k] = node < cnt ? batch_dev[my_slot][node] : -1;
-            }
+        for (int d = 0; d < kMaxD; ++d) {
+            if (d >= G) break;
 #pragma unroll
-            for (int d = 0; d < kMaxD; ++d) {
-                if (d >= G) break;
-                float sdev = 0.0f;
+            for (int tl = 0; tl < kTiles; ++tl) {
+                const float wgt = dv[tl] == d ? 1.0f : 0.0f;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) sdev += (dv[k] == d) ? o[k] : 0.0f;
-                acc_reg[d] += sdev;
+                for (int t = 0; t < TPW; ++t) acc_dev[d][t] = fmaf(wgt, y[tl][t], acc_dev[d][t]);
             }
         }
     }
 
-    if (tid < 2 * H) {
-        const int half = tid >= H ? 1 : 0, c = tid - half * H;
+    // ---- the four lanes of a column (kg = 0..3) are added in order; the buffer of the first
+    // layer's A rows is free now and holds the partial sums
+    __syncthreads();
+    float *red = reinterpret_cast<float *>(&act1[0][0]);      // [4 kg][G][H]
+    static_assert(sizeof(act1) >= sizeof(float) * 4 * kMaxD * H, "reduction buffer must fit");
 #pragma unroll
-        for (int d = 0; d < kMaxD; ++d) accP[half][d][c] = acc_reg[d];
+    for (int t = 0; t < TPW; ++t) {
+        const int nt = wave * TPW + t;
+        if (nt >= NTL) continue;
+#pragma unroll
+        for (int d = 0; d < kMaxD; ++d) {
+            if (d >= G) break;
+            red[(kg * G + d) * H + 16 * nt + col] = acc_dev[d][t];
+        }
     }
     __syncthreads();
     float *dst = P.partial + (((static_cast<size_t>(b) * P.max_slices + slice) * 3 + set) * G) * H;
-    for (int i = tid; i < G * H; i += kThreads) dst[i] = accP[0][i / H][i % H] + accP[1][i / H][i % H];
+    for (int i = tid; i < G * H; i += kThreads)
+        dst[i] = ((red[i] + red[G * H + i]) + red[2 * G * H + i]) + red[3 * G * H + i];
 }
 
 // Appends the MFMA B-operand fragments of one layer: index ((nt * KS + ks) * WS + ws) * 64 + lane,
