@@ -171,13 +171,17 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             proj_dev[i] = (i < D * H) ? P.proj[2 * H + i] : 0.0f;
     }
     const float4 *featb = P.featb + static_cast<size_t>(dir) * gv.n_tot;
-    auto project = [&](const f32x4 ft, int t) {
+    // the device's row of W_in comes from LDS: read early (device_term), used late (project)
+    auto device_term = [&](const f32x4 ft, int t) {
+        const int dev = __float_as_int(ft[3]) & 0xFFFF;
+        return proj_dev[(dev < D ? dev : D) * H + wc0 + 16 * t + col];
+    };
+    auto project = [&](const f32x4 ft, float dev_term, int t) {
         const int bits = __float_as_int(ft[3]);
-        const int dev = bits & 0xFFFF;
         float o = pw_b[t];
         o = fmaf(ft[0], pw_time[t], o);
         o = fmaf(ft[1], pw_size[t], o);
-        o += proj_dev[(dev < D ? dev : D) * H + wc0 + 16 * t + col];
+        o += dev_term;
         o += (bits >> 16) ? pw_cur[t] : 0.0f;
         return fmaxf(fmaf(ft[2], pw_vis[t], o), 0.0f);
     };
@@ -438,15 +442,15 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 // before the last barrier of the previous chunk.
                 // Work for a second row tile (rows 4..7) is skipped when the chunk has none, and
                 // far rows beyond the first 64 / QW only when the next chunk stages that many.
+                float dterm[NT][TPW];
                 if constexpr (FF) {
 #pragma unroll
                     for (int ct = 0; ct < NT; ++ct)
                         if (ct == 0 || two) {
 #pragma unroll
-                            for (int t = 0; t < TPW; ++t) x0[ct][t] = project(ft0[ct], t);
+                            for (int t = 0; t < TPW; ++t) dterm[ct][t] = device_term(ft0[ct], t);
                         }
                 }
-                const bool two_next = m1.y > kTileNodes;
 #pragma unroll
                 for (int i = 0; i < PFN; ++i) {
                     if (i > 0 && m1.z <= i * (64 / QW)) continue;
@@ -460,6 +464,18 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     pf_reach[i] = reach[static_cast<uint32_t>(u)];   // combined with pf_cur at the end of the chunk
                     pf_cur[i] = wanted && u == cur;
                 }
+                if constexpr (FF) {
+#pragma unroll
+                    for (int ct = 0; ct < NT; ++ct)
+                        if (ct == 0 || two) {
+#pragma unroll
+                            for (int t = 0; t < TPW; ++t) x0[ct][t] = project(ft0[ct], dterm[ct][t], t);
+                        }
+                }
+            }
+            if (n == (NL > 2 ? 1 : 0)) {
+                // the rest of the batch, behind the second layer's matrix instructions
+                const bool two_next = m1.y > kTileNodes;
                 m2 = load_uniform(plan.meta + clampc(c + 2));
 #pragma unroll
                 for (int ct = 0; ct < NT; ++ct) {
