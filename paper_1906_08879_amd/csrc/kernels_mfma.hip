@@ -256,21 +256,36 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             if (listed) {
                 const int d0 = static_cast<int>(rec[0] >> 16) | (static_cast<int>(rec[1] & 0xFFFF) << 16);
                 const int d1 = d0 + (static_cast<int>(rec[1] >> 16) | (static_cast<int>(rec[2] & 0xFFFF) << 16));
-                for (int p = d0; p < d1; ++p) {
-                    const int u = plan.ovf[p];
-                    if (u < 0) {
-                        const float *row = msgtab + (-1 - u) * LDM;
+                // LB list entries at a time, every load issued before the first use: an entry
+                // is a table slot or a node id; the other source of the pair is the table's zero
+                // row or the spare (all-zero, never written) row of msg, so both are always read
+                // and added, in list order.
+                constexpr int LB = TPW > 1 ? 4 : 8;
+                for (int p = d0; p < d1; p += LB) {
+                    int u[LB];
+#pragma unroll
+                    for (int k = 0; k < LB; ++k) u[k] = p + k < d1 ? plan.ovf[p + k] : -1 - kZeroSlot;
+                    float xl[LB][TPW], xg[LB][TPW];
+                    int rg[LB];
+#pragma unroll
+                    for (int k = 0; k < LB; ++k) {
+                        const float *row = msgtab + (u[k] < 0 ? -1 - u[k] : kZeroSlot) * LDM;
+                        const int v = u[k] >= 0 ? u[k] : spare_row;
 #pragma unroll
                         for (int t = 0; t < TPW; ++t) {
-                            const float x = row[wc0 + 16 * t + col];
-                            s[t] += fabsf(x);
-                            signs |= __float_as_uint(x);
+                            xl[k][t] = row[wc0 + 16 * t + col];
+                            xg[k][t] = msg[static_cast<uint32_t>(v * H + wc0 + 16 * t + col)];
                         }
-                    } else {
+                        rg[k] = reach[static_cast<uint32_t>(v)];
+                    }
 #pragma unroll
-                        for (int t = 0; t < TPW; ++t)
-                            s[t] += msg[static_cast<uint32_t>(u * H + wc0 + 16 * t + col)];
-                        signs |= ((u == cur) | reach[static_cast<uint32_t>(u)]) ? 0x80000000u : 0u;
+                    for (int k = 0; k < LB; ++k) {
+#pragma unroll
+                        for (int t = 0; t < TPW; ++t) {
+                            s[t] += fabsf(xl[k][t]) + xg[k][t];
+                            signs |= __float_as_uint(xl[k][t]);
+                        }
+                        signs |= ((u[k] >= 0) & ((u[k] == cur) | (rg[k] != 0))) ? 0x80000000u : 0u;
                     }
                 }
             }
