@@ -36,7 +36,20 @@ __device__ __forceinline__ void dense_layer(const float *__restrict__ W,
     int xoff[RPT];   // rows past the tile's end re-read its last row (never stored)
 #pragma unroll
     for (int i = 0; i < RPT; ++i) xoff[i] = min(grp + i * groups, rows - 1) * ldx;
-    for (int k = 0; k < n_in; ++k) {
+    // weights sixteen at a time, all loads issued before the first use: the loop is bound by the
+    // latency of one batch instead of one load per step
+    constexpr int KB = 16;
+    int k = 0;
+    for (; k + KB <= n_in; k += KB) {
+        float w[KB];
+#pragma unroll
+        for (int u = 0; u < KB; ++u) w[u] = W[static_cast<size_t>(k + u) * n_out + j];
+#pragma unroll
+        for (int u = 0; u < KB; ++u)
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) acc[i] = fmaf(x[xoff[i] + k + u], w[u], acc[i]);
+    }
+    for (; k < n_in; ++k) {
         const float w = W[static_cast<size_t>(k) * n_out + j];
 #pragma unroll
         for (int i = 0; i < RPT; ++i) acc[i] = fmaf(x[xoff[i] + k], w, acc[i]);
@@ -391,7 +404,18 @@ __global__ __launch_bounds__(kThreads) void k_head_policy1(ModelView mv, int B,
     }
     const float *W = mv.blob + mv.pol1.w + static_cast<size_t>(k0) * H;
     const float *xf = &x[0][0];
-    for (int k = 0; k < kn; ++k) {
+    constexpr int KB = 16;      // weights per batch of loads, as in dense_layer
+    int k = 0;
+    for (; k + KB <= kn; k += KB) {
+        float w[KB];
+#pragma unroll
+        for (int u = 0; u < KB; ++u) w[u] = W[static_cast<size_t>(k + u) * H + j];
+#pragma unroll
+        for (int u = 0; u < KB; ++u)
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) acc[i] = fmaf(xf[xoff[i] + k + u], w[u], acc[i]);
+    }
+    for (; k < kn; ++k) {
         const float w = W[static_cast<size_t>(k) * H + j];
 #pragma unroll
         for (int i = 0; i < RPT; ++i) acc[i] = fmaf(xf[xoff[i] + k], w, acc[i]);
