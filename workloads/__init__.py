@@ -11,6 +11,7 @@ from .synthetic import (  # noqa: F401
     Workload,
     make_workload,
     make_states,
+    make_episode,
     tiny_random_dag,
     weight_layout,
     weight_count,

@@ -465,6 +465,22 @@ def make_states(w: Workload, n_states: int, seed: Optional[int] = None):
     return placement, cur, done
 
 
+def make_episode(w: Workload, n_steps: int, seed: Optional[int] = None):
+    """Inputs of an on-device episode: a visiting order per graph (a permutation of its
+    graph-local node ids, concatenated), uniform numbers in [0, 1) for the sampled actions
+    [n_steps, B] (float32), and the trivial start placement (every node on device 0).
+    """
+    seed = w.seed + 104729 if seed is None else seed
+    rng = np.random.default_rng([seed, n_steps])
+    order = np.empty(w.n_tot, dtype=np.int32)
+    for b in range(w.B):
+        n0, n1 = int(w.node_off[b]), int(w.node_off[b + 1])
+        order[n0:n1] = rng.permutation(n1 - n0).astype(np.int32)
+    uniforms = rng.random((n_steps, w.B), dtype=np.float32)
+    placement0 = np.zeros(w.n_tot, dtype=np.int32)
+    return order, uniforms, placement0
+
+
 def tiny_random_dag(rng: np.random.Generator, n: int, p_edge: float = 0.35):
     """A random DAG on n nodes with shuffled labels (for brute-force tests)."""
     order = rng.permutation(n)
