@@ -142,6 +142,38 @@ int pl_embed_forward_ex(pl_graph_batch *g, const float *node_feats, const int32_
                         float *out_probs, float *out_node_emb, float *out_pooled,
                         void *stream);
 
+/* ---- the MDP transition (Section 2.1) on the device, for every graph of the batch: an
+ * action a is drawn from softmax(logits[b]) (Appendix A.7) by inverse CDF, i.e. the first
+ * device d whose cumulative probability exceeds uniforms[b]; the current node takes device a,
+ * is marked visited, and node order[t + 1] of the graph becomes the current node (-1 after
+ * the graph's last node, at which point the graph's episode is over).
+ *   logits      dev [B, D] fp32     output of the forward pass on the state before the step
+ *   uniforms    dev [B] fp32        numbers in [0, 1), drawn by the caller
+ *   order       dev [N_tot] int32   per graph a permutation of its graph-local node ids,
+ *                                   concatenated: the visiting order of the episode
+ *   t                               index of this step in the episode (cur_node[b] is order[t])
+ *   node_feats  dev [N_tot, 3]      in/out: the visited flag (column 2) of the current node := 1
+ *   placement   dev [N_tot] int32   in/out: the current node's device := a
+ *   cur_node    dev [B] int32       in/out: := order[t + 1] or -1
+ *   out_action  dev [B] int32       a, or -1 for a graph whose episode is over (NULL to skip)
+ *   out_logp    dev [B] fp32        log softmax(logits[b])[a], 0 for such a graph (NULL to skip)
+ * A graph whose cur_node is outside the graph is left unchanged (cur_node := -1).
+ * Asynchronous on `stream`; allocates nothing once the batch is on the device. */
+int pl_episode_step(pl_graph_batch *g, int32_t D, const float *logits, const float *uniforms,
+                    const int32_t *order, int32_t t, float *node_feats, int32_t *placement,
+                    int32_t *cur_node, int32_t *out_action, float *out_logp, void *stream);
+
+/* n_steps times { forward pass, transition }, steps t0 .. t0 + n_steps - 1 of the episode,
+ * all enqueued on `stream` without any host synchronisation (Section 2.1: an episode is |V|
+ * such steps).  Arguments as above, and
+ *   uniforms     dev [n_steps, B]
+ *   logits       dev [B, D], or [n_steps, B, D] when keep_logits != 0 (every step's logits)
+ *   out_actions  dev [n_steps, B] or NULL;  out_logp  dev [n_steps, B] or NULL */
+int pl_episode_run(pl_graph_batch *g, const pl_weights *w, float *node_feats, int32_t *placement,
+                   int32_t *cur_node, const int32_t *order, const float *uniforms, int32_t t0,
+                   int32_t n_steps, float *logits, int32_t keep_logits, int32_t *out_actions,
+                   float *out_logp, void *stream);
+
 /* ---- per-stage timing, for benchmarks.  While enabled, forward calls bracket each
  * kernel stage with HIP events on the caller's stream.  pl_profile_read synchronises those
  * events and returns, per stage, the summed milliseconds and the number of launches since

@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     PlacetoError,
     Weights,
     embed_forward,
+    episode_run,
+    episode_step,
     library_path,
     load_library,
     node_classes,

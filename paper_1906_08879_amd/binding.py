@@ -61,6 +61,10 @@ def load_library(path: Optional[str] = None):
         "pl_weights_set_path": (ctypes.c_int, [vp, ctypes.c_int32]),
         "pl_embed_forward": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp]),
         "pl_embed_forward_ex": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "pl_episode_step": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, vp, ctypes.c_int32, vp, vp, vp,
+                                           vp, vp, vp]),
+        "pl_episode_run": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
+                                          vp, ctypes.c_int32, vp, vp, vp]),
         "pl_profile_enable": (ctypes.c_int, [vp, ctypes.c_int32]),
         "pl_profile_read": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_double), i64p,
                                            ctypes.c_int32]),
@@ -233,3 +237,39 @@ def embed_forward(g: GraphBatch, node_feats, placement, cur_node, w: Weights, ou
             _dev_ptr(out_pooled, torch.float32, g.B * 3 * w.G * w.H, "out_pooled"),
             _stream_ptr(stream)), "pl_embed_forward_ex")
     return out_logits
+
+
+def episode_step(g: GraphBatch, D: int, logits, uniforms, order, t: int, node_feats, placement,
+                 cur_node, out_action=None, out_logp=None, stream=None):
+    """pl_episode_step on device tensors: one MDP transition for every graph, in place."""
+    import torch
+    lib = load_library()
+    _check(lib.pl_episode_step(
+        g._h, int(D), _dev_ptr(logits, torch.float32, g.B * D, "logits"),
+        _dev_ptr(uniforms, torch.float32, g.B, "uniforms"),
+        _dev_ptr(order, torch.int32, g.n_tot, "order"), int(t),
+        _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
+        _dev_ptr(placement, torch.int32, g.n_tot, "placement"),
+        _dev_ptr(cur_node, torch.int32, g.B, "cur_node"),
+        _dev_ptr(out_action, torch.int32, g.B, "out_action"),
+        _dev_ptr(out_logp, torch.float32, g.B, "out_logp"), _stream_ptr(stream)), "pl_episode_step")
+
+
+def episode_run(g: GraphBatch, w: Weights, node_feats, placement, cur_node, order, uniforms,
+                t0: int, n_steps: int, logits, keep_logits: bool = False, out_actions=None,
+                out_logp=None, stream=None):
+    """pl_episode_run on device tensors: n_steps x (forward pass, transition), in place and
+    without host synchronisation."""
+    import torch
+    lib = load_library()
+    n_log = g.B * w.D * (n_steps if keep_logits else 1)
+    _check(lib.pl_episode_run(
+        g._h, w._h, _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
+        _dev_ptr(placement, torch.int32, g.n_tot, "placement"),
+        _dev_ptr(cur_node, torch.int32, g.B, "cur_node"),
+        _dev_ptr(order, torch.int32, g.n_tot, "order"),
+        _dev_ptr(uniforms, torch.float32, g.B * n_steps, "uniforms"), int(t0), int(n_steps),
+        _dev_ptr(logits, torch.float32, n_log, "logits"), 1 if keep_logits else 0,
+        _dev_ptr(out_actions, torch.int32, g.B * n_steps, "out_actions"),
+        _dev_ptr(out_logp, torch.float32, g.B * n_steps, "out_logp"), _stream_ptr(stream)),
+        "pl_episode_run")

@@ -570,6 +570,47 @@ int pl_embed_forward_ex(pl_graph_batch *g, const float *node_feats, const int32_
                         out_pooled, stream);
 }
 
+int pl_episode_step(pl_graph_batch *g, int32_t D, const float *logits, const float *uniforms,
+                    const int32_t *order, int32_t t, float *node_feats, int32_t *placement,
+                    int32_t *cur_node, int32_t *out_action, float *out_logp, void *stream)
+{
+    if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
+    if (D < 1 || D > kMaxD || t < 0) return fail(PL_ERR_SHAPE, "D must be in [1, 16] and t >= 0");
+    if (g->host.B == 0) return PL_OK;
+    if (!logits || !uniforms || !order || !node_feats || !placement || !cur_node)
+        return fail(PL_ERR_NULL, "a required device array is NULL");
+    int rc = ensure_on_device(g);
+    if (rc) return rc;
+    launch_episode_step(g->view, D, logits, uniforms, order, t, node_feats, placement, cur_node, out_action,
+                        out_logp, static_cast<hipStream_t>(stream));
+    PL_HIP(hipGetLastError());
+    return PL_OK;
+}
+
+int pl_episode_run(pl_graph_batch *g, const pl_weights *w, float *node_feats, int32_t *placement,
+                   int32_t *cur_node, const int32_t *order, const float *uniforms, int32_t t0,
+                   int32_t n_steps, float *logits, int32_t keep_logits, int32_t *out_actions,
+                   float *out_logp, void *stream)
+{
+    if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
+    if (t0 < 0 || n_steps < 0) return fail(PL_ERR_SHAPE, "t0 and n_steps must not be negative");
+    if (g->host.B == 0 || n_steps == 0) return PL_OK;
+    if (!logits || !uniforms || !order || !node_feats || !placement || !cur_node)
+        return fail(PL_ERR_NULL, "a required device array is NULL");
+    const size_t B = static_cast<size_t>(g->host.B), D = static_cast<size_t>(w->cfg.D);
+    for (int32_t i = 0; i < n_steps; ++i) {
+        float *l = keep_logits ? logits + static_cast<size_t>(i) * B * D : logits;
+        int rc = forward_impl(g, node_feats, placement, cur_node, w, l, nullptr, nullptr, nullptr, stream);
+        if (rc) return rc;
+        launch_episode_step(g->view, w->cfg.D, l, uniforms + static_cast<size_t>(i) * B, order, t0 + i,
+                            node_feats, placement, cur_node, out_actions ? out_actions + static_cast<size_t>(i) * B : nullptr,
+                            out_logp ? out_logp + static_cast<size_t>(i) * B : nullptr,
+                            static_cast<hipStream_t>(stream));
+    }
+    PL_HIP(hipGetLastError());
+    return PL_OK;
+}
+
 int pl_profile_enable(pl_graph_batch *g, int32_t on)
 {
     if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");

@@ -157,6 +157,11 @@ void launch_pool_generic(const GraphView &gv, const ModelView &mv, const Workspa
 void launch_head_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                          const ForwardArgs &fa, int max_chunks, hipStream_t s);
 
+// ---- MDP transition (kernels_episode.hip)
+void launch_episode_step(const GraphView &gv, int D, const float *logits, const float *uniforms,
+                         const int32_t *order, int t, float *node_feats, int32_t *placement,
+                         int32_t *cur_node, int32_t *out_action, float *out_logp, hipStream_t s);
+
 // ---- matrix-core pooling (kernels_pool_mfma.hip); writes ws.partial as [B, kPoolSlices, 3G, H]
 constexpr int kPoolSlices = 4;
 bool pool_mfma_supported(int H, int L, int weight_dtype);
