@@ -175,3 +175,61 @@ def test_empty_batch_is_a_no_op():
     pl.embed_forward(g, z, zi, zi, wt, z)
     torch.cuda.synchronize()
     g.close(); wt.close()
+
+
+@pytest.mark.parametrize("name,k,group,layers", [
+    ("nasnet", 2, 1, 2),      # two sweeps on deep graphs: every variant of the matrix-core sweep kernel
+    ("nasnet", 3, 0, 1),      # three sweeps, single-layer networks, pooling per set only
+    ("nmt", 2, 0, 2),         # long neighbour lists in every sweep
+    ("inception", 0, 1, 2),   # no message passing at all: the sets and the pooling alone
+])
+def test_architecture_variants_on_deep_graphs(name, k, group, layers):
+    """Section 2.2: the sweep may be repeated k times; Section 3.4 compares against a policy
+    without message passing; the printed pooling is per set, not per (set, device)."""
+    w = make_workload(name, B=3, k_sweeps=k, group_by_device=group, n_layers=layers)
+    _compare(w, f"{name} k={k} group={group} layers={layers}")
+
+
+def test_forward_replays_from_a_hip_graph():
+    """After the first call on a batch a forward pass only launches kernels, so it can be
+    captured once and replayed: three replays on new states, with eager work in between,
+    each equal bit for bit to the eager result on the same state."""
+    import torch
+    import paper_1906_08879_amd as pl
+    from workloads import make_states
+    dev = torch.device("cuda:0")
+    w = make_workload("layered200", B=16)
+    placement, cur, done = make_states(w, 4)
+    g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+    wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+
+    def state(s):
+        f = np.array(w.node_feats, dtype=np.float32)
+        f[:, 2] = done[s]
+        return torch.from_numpy(f).to(dev), torch.from_numpy(placement[s]).to(dev), torch.from_numpy(cur[s]).to(dev)
+
+    f_in, p_in, c_in = state(0)
+    out = torch.empty((w.B, w.D), dtype=torch.float32, device=dev)
+    eager = torch.empty_like(out)
+    pl.embed_forward(g, f_in, p_in, c_in, wt, eager)           # first call: allocates
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        pl.embed_forward(g, f_in, p_in, c_in, wt, out, stream=side)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    for s in (1, 2, 3):
+        f, p, c = state(s)
+        pl.embed_forward(g, f, p, c, wt, eager)                # eager work between the replays
+        torch.cuda.synchronize()
+        f_in.copy_(f); p_in.copy_(p); c_in.copy_(c)
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(out.cpu().numpy(), eager.cpu().numpy())
+    del graph
+    g.close()
+    wt.close()
