@@ -4,10 +4,10 @@
 //
 // One workgroup per (graph, slice of its nodes, set).  It scans its nodes in node order, queues
 // the nodes of its set, and pushes them through l_i sixteen at a time:
-//   * the fp32 embedding row of a node is split exactly into three bf16 parts (truncation),
-//     which become three ROWS of the MFMA A operand (a fourth row is zero), so the three
-//     partial products of a node land in one lane's accumulator registers and are added
-//     there: no cross-lane traffic;
+//   * the fp32 embedding row of a node is split exactly into three bf16 parts (truncation);
+//     the hi, mid and lo parts of the sixteen nodes form three 16-row MFMA A tiles, so a lane
+//     finds the three partial products of (node, column) in the same element of three
+//     accumulators and adds them there: no cross-lane traffic and no wasted rows;
 //   * the weights of l_i are the B operand and stay in registers for the whole kernel;
 //   * the rows of the next batch are loaded from HBM while the current one is computed;
 //   * the per-device sums are taken in registers, by the lane that holds a node's output in
@@ -23,8 +23,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int kThreads = 256;
-constexpr int kBatch = 16;          // nodes per batch: four MFMA row tiles of four nodes
-constexpr int kTiles = kBatch / 4;
+constexpr int kBatch = 16;          // nodes per batch: one MFMA row tile per bf16 part
 constexpr int kWindow = 256;        // nodes classified per scan step
 constexpr int kQueue = 512;         // circular queue of node ids (power of two > kWindow + kBatch)
 
@@ -70,8 +69,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
     constexpr int NLD = kBatch * QPR / kThreads; // float4 loads per thread and batch
     static_assert(kBatch * QPR % kThreads == 0, "batch rows must divide over the threads");
 
-    __shared__ __attribute__((aligned(16))) __bf16 act1[kBatch * 4][LD1];   // parts of the input rows
-    __shared__ __attribute__((aligned(16))) __bf16 act2[kBatch * 4][LD2];   // parts of layer-1 outputs
+    // [part][node][k] bf16 parts of the input rows and of the layer-1 outputs; the same memory
+    // holds the final cross-lane reduction
+    constexpr size_t kAct1 = sizeof(__bf16) * 3 * kBatch * LD1, kAct2 = sizeof(__bf16) * 3 * kBatch * LD2;
+    constexpr size_t kRed = sizeof(float) * 4 * kMaxD * H;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kAct1 + kAct2 > kRed ? kAct1 + kAct2 : kRed];
+    __bf16 (*act1)[kBatch][LD1] = reinterpret_cast<__bf16 (*)[kBatch][LD1]>(smem);
+    __bf16 (*act2)[kBatch][LD2] = reinterpret_cast<__bf16 (*)[kBatch][LD2]>(smem + kAct1);
     __shared__ int queue[kQueue];
     __shared__ int batch_node[2][kBatch];
     __shared__ int batch_dev[2][kBatch];
@@ -127,8 +131,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
             }
         }
     }
-    for (int i = tid; i < kBatch * 4 * LD1; i += kThreads) (&act1[0][0])[i] = static_cast<__bf16>(0.0f);
-    for (int i = tid; i < kBatch * 4 * LD2; i += kThreads) (&act2[0][0])[i] = static_cast<__bf16>(0.0f);
+    for (int i = tid; i < static_cast<int>((kAct1 + kAct2) / 4); i += kThreads) reinterpret_cast<uint32_t *>(smem)[i] = 0u;
     __syncthreads();
 
     int q_head = 0;           // position of the oldest queued node (uniform)
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
     int have = 0;             // nodes of the batch whose rows are in flight (uniform)
     int slot = 0;             // batch_node buffer of the in-flight batch
     f32x4 x[NLD];             // the in-flight rows: item e = tid + i * 256 -> (node e / QPR, float4 e % QPR)
-    float acc_dev[kMaxD][TPW];   // per-device sums over this lane's nodes (rows kg of every tile) and columns
+    float acc_dev[kMaxD][TPW];   // per-device sums over this lane's nodes (4 kg .. 4 kg + 3 of every batch) and columns
 #pragma unroll
     for (int d = 0; d < kMaxD; ++d)
 #pragma unroll
@@ -196,10 +199,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
                 r[k] = x[i][k] - trunc_bf16(x[i][k]);
                 l[k] = r[k] - trunc_bf16(r[k]);
             }
-            __bf16 *dst = &act1[node * 4][4 * q];
-            *reinterpret_cast<uint2 *>(dst) = uint2{pack_hi16(x[i][0], x[i][1]), pack_hi16(x[i][2], x[i][3])};
-            *reinterpret_cast<uint2 *>(dst + LD1) = uint2{pack_hi16(r[0], r[1]), pack_hi16(r[2], r[3])};
-            *reinterpret_cast<uint2 *>(dst + 2 * LD1) = uint2{pack_hi16(l[0], l[1]), pack_hi16(l[2], l[3])};
+            *reinterpret_cast<uint2 *>(&act1[0][node][4 * q]) = uint2{pack_hi16(x[i][0], x[i][1]), pack_hi16(x[i][2], x[i][3])};
+            *reinterpret_cast<uint2 *>(&act1[1][node][4 * q]) = uint2{pack_hi16(r[0], r[1]), pack_hi16(r[2], r[3])};
+            *reinterpret_cast<uint2 *>(&act1[2][node][4 * q]) = uint2{pack_hi16(l[0], l[1]), pack_hi16(l[2], l[3])};
         }
         if (tid < kBatch) {
             const int v = batch_node[my_slot][tid];
@@ -214,76 +216,73 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
         refill();
         issue();          // ends with a barrier: act1 and batch_dev are visible
 
-        // ---- (3) layer 1
-        f32x4 acc[kTiles][TPW];
+        // ---- (3) layer 1.  acc[part][t]: element i of lane (col, kg) belongs to node 4 kg + i
+        // and output column 16 nt + col.  3 * TPW independent accumulation chains are in
+        // flight, which hides the latency of a dependent MFMA.  Rows past the batch's end hold
+        // stale data that is never summed.
+        f32x4 acc[3][TPW];
 #pragma unroll
-        for (int tl = 0; tl < kTiles; ++tl)
+        for (int p = 0; p < 3; ++p)
 #pragma unroll
-            for (int t = 0; t < TPW; ++t) acc[tl][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-        // k-steps outermost: kTiles * TPW independent accumulation chains are in flight, which
-        // hides the latency of a dependent MFMA (about three issue slots).  All four tiles are
-        // always computed; rows past the batch's end hold stale data that is never summed.
+            for (int t = 0; t < TPW; ++t) acc[p][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS1; ++ks)
 #pragma unroll
-            for (int tl = 0; tl < kTiles; ++tl) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&act1[16 * tl + col][32 * ks + 8 * kg]);
+            for (int p = 0; p < 3; ++p) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&act1[p][col][32 * ks + 8 * kg]);
 #pragma unroll
                 for (int t = 0; t < TPW; ++t)
 #pragma unroll
                     for (int ws = 0; ws < WS; ++ws)
-                        acc[tl][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W1[t][ks][ws], acc[tl][t], 0, 0, 0);
+                        acc[p][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W1[t][ks][ws], acc[p][t], 0, 0, 0);
             }
-        // lane (col, kg) holds, for node 4 tl + kg and output column 16 nt + col, the three
-        // partial products in acc[..][0..2]
         if constexpr (L > 1) {
 #pragma unroll
-            for (int tl = 0; tl < kTiles; ++tl) {
+            for (int t = 0; t < TPW; ++t) {
+                const int nt = wave * TPW + t;
+                if (nt >= NTL) continue;
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) {
-                    const int nt = wave * TPW + t;
-                    if (nt >= NTL) continue;
-                    const float y = fmaxf(acc[tl][t][0] + acc[tl][t][1] + acc[tl][t][2] + bias1[t], 0.0f);
+                for (int i = 0; i < 4; ++i) {
+                    const float y = fmaxf(acc[0][t][i] + acc[1][t][i] + acc[2][t][i] + bias1[t], 0.0f);
                     const float r = y - trunc_bf16(y);
                     const float l = r - trunc_bf16(r);
-                    unsigned short *dst = reinterpret_cast<unsigned short *>(&act2[16 * tl + 4 * kg][16 * nt + col]);
-                    dst[0] = static_cast<unsigned short>(__float_as_uint(y) >> 16);
-                    dst[LD2] = static_cast<unsigned short>(__float_as_uint(r) >> 16);
-                    dst[2 * LD2] = static_cast<unsigned short>(__float_as_uint(l) >> 16);
+                    const int node = 4 * kg + i, c = 16 * nt + col;
+                    reinterpret_cast<unsigned short *>(&act2[0][node][c])[0] = static_cast<unsigned short>(__float_as_uint(y) >> 16);
+                    reinterpret_cast<unsigned short *>(&act2[1][node][c])[0] = static_cast<unsigned short>(__float_as_uint(r) >> 16);
+                    reinterpret_cast<unsigned short *>(&act2[2][node][c])[0] = static_cast<unsigned short>(__float_as_uint(l) >> 16);
                 }
             }
             lds_barrier();
             // ---- (4) layer 2
 #pragma unroll
-            for (int tl = 0; tl < kTiles; ++tl)
+            for (int p = 0; p < 3; ++p)
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) acc[tl][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int t = 0; t < TPW; ++t) acc[p][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS2; ++ks)
 #pragma unroll
-                for (int tl = 0; tl < kTiles; ++tl) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&act2[16 * tl + col][32 * ks + 8 * kg]);
+                for (int p = 0; p < 3; ++p) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&act2[p][col][32 * ks + 8 * kg]);
 #pragma unroll
                     for (int t = 0; t < TPW; ++t)
 #pragma unroll
                         for (int ws = 0; ws < WS; ++ws)
-                            acc[tl][t] =
-                                __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W2[t][ks][ws], acc[tl][t], 0, 0, 0);
+                            acc[p][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W2[t][ks][ws], acc[p][t], 0, 0, 0);
                 }
         }
         // ---- (5) per-device sums in registers: lane (col, kg) adds the outputs of its own
-        // nodes (4 tl + kg) to the sum of the node's device; nodes past the end of the batch
+        // nodes (4 kg + i) to the sum of the node's device; nodes past the end of the batch
         // have device -1 and are never added
-        float y[kTiles][TPW];
-        int dv[kTiles];
+        float y[4][TPW];
+        int dv[4];
 #pragma unroll
-        for (int tl = 0; tl < kTiles; ++tl) {
-            const int node = 4 * tl + kg;
-            dv[tl] = node < cnt ? batch_dev[my_slot][node] : -1;
+        for (int i = 0; i < 4; ++i) {
+            const int node = 4 * kg + i;
+            dv[i] = node < cnt ? batch_dev[my_slot][node] : -1;
 #pragma unroll
             for (int t = 0; t < TPW; ++t) {
                 const float bl = (L > 1) ? bias2[t] : bias1[t];
-                y[tl][t] = fmaxf(acc[tl][t][0] + acc[tl][t][1] + acc[tl][t][2] + bl, 0.0f);
+                y[i][t] = fmaxf(acc[0][t][i] + acc[1][t][i] + acc[2][t][i] + bl, 0.0f);
             }
         }
         // rows past the end of the batch hold earlier, finite outputs: weight 0 removes them
@@ -291,10 +290,10 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
         for (int d = 0; d < kMaxD; ++d) {
             if (d >= G) break;
 #pragma unroll
-            for (int tl = 0; tl < kTiles; ++tl) {
-                const float wgt = dv[tl] == d ? 1.0f : 0.0f;
+            for (int i = 0; i < 4; ++i) {
+                const float wgt = dv[i] == d ? 1.0f : 0.0f;
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) acc_dev[d][t] = fmaf(wgt, y[tl][t], acc_dev[d][t]);
+                for (int t = 0; t < TPW; ++t) acc_dev[d][t] = fmaf(wgt, y[i][t], acc_dev[d][t]);
             }
         }
     }
@@ -302,8 +301,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
     // ---- the four lanes of a column (kg = 0..3) are added in order; the buffer of the first
     // layer's A rows is free now and holds the partial sums
     __syncthreads();
-    float *red = reinterpret_cast<float *>(&act1[0][0]);      // [4 kg][G][H]
-    static_assert(sizeof(act1) >= sizeof(float) * 4 * kMaxD * H, "reduction buffer must fit");
+    float *red = reinterpret_cast<float *>(smem);             // [4 kg][G][H]
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
         const int nt = wave * TPW + t;
