@@ -13,17 +13,26 @@
 //     matrix cores without any cross-lane traffic.
 //   * The weight fragments of all layers of one direction live in registers for the whole
 //     kernel (bf16 weights: 128 VGPRs per wave at H = 128); only activations move through LDS.
-//   * Messages of the last two chunks stay in an LDS table; messages from older chunks are
-//     prefetched from HBM one chunk ahead into the same table, so the gather on the
-//     critical path reads LDS only.  Chunk records, node ids and the residual inputs (kept
-//     in bucket order, so a chunk's rows are contiguous) are prefetched the same way.
+//   * A wave owns its output columns from end to end: it writes its columns of a message into
+//     an LDS table, stages its columns of older messages (prefetched from HBM one chunk ahead)
+//     into the same table, and sums its columns for the next chunk, in the MFMA result layout
+//     (lane = node of the tile, column).  The table therefore needs no barrier; only the A
+//     rows of the next layer cross waves: one LDS barrier per layer, four per chunk.
+//   * Messages are ReLU outputs, so in the table their sign bit carries the reachability flag
+//     of Section 2.2 step 3 (the node is v* or was computed from v*): sums take |x| and OR the
+//     signs.  Row records name a fixed number of table slots (unused ones a zero row), so the
+//     common gather is branch-free.
+//   * On the first sweep the same lane computes its columns of x_v = relu(W_in^T phi_v + b)
+//     (step 1) from the node's 16-byte feature record: x never exists in HBM.
 //   * Barriers order LDS traffic only, so global prefetches stay in flight across them.
 //     A message written to HBM in chunk c is only read back from HBM from chunk c + 3 on
 //     (nearer consumers use the LDS table); by then the store has retired, because each
 //     wave waits once per chunk for a batch of loads that it issued after that store.
+//     Every global store is on every path (unused rows store to sink rows), so the number of
+//     stores behind a load is known at compile time and waiting for the load never waits for
+//     the stores.
 //   * The kernel runs a dependent chain (about a thousand chunks of four layers per graph),
-//     so it is bound by instruction issue and LDS round trips, not by HBM bandwidth: the
-//     per-layer epilogue is about fifteen instructions per tile.
+//     so it is bound by LDS round trips, MFMA latency and barriers, not by HBM bandwidth.
 #include <type_traits>
 
 #include "internal.h"

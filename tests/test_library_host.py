@@ -122,3 +122,26 @@ def test_null_and_shape_errors(lib):
                                  10, ctypes.byref(out)) == -2
     assert b"expected" in lib.pl_last_error()
     assert lib.pl_graph_batch_destroy(None) == 0 and lib.pl_weights_destroy(None) == 0
+
+
+def test_episode_entry_points_reject_bad_arguments(lib):
+    """Error paths of the MDP transition calls that need no device: NULL handles and
+    impossible sizes come back as error codes, with a message."""
+    import ctypes
+    raw = ctypes.CDLL(pl.library_path())
+    null = ctypes.c_void_p(None)
+    args_step = [null, ctypes.c_int32(4), null, null, null, ctypes.c_int32(0), null, null, null, null, null, null]
+    assert raw.pl_episode_step(*args_step) == -1                       # PL_ERR_NULL
+    g = pl.GraphBatch([2], [1], [0], [1])
+    args_step[0] = g._h
+    args_step[1] = ctypes.c_int32(99)
+    assert raw.pl_episode_step(*args_step) != 0                         # D out of range
+    args_step[1] = ctypes.c_int32(4)
+    args_step[5] = ctypes.c_int32(-1)
+    assert raw.pl_episode_step(*args_step) != 0                         # negative step
+    args_run = [g._h, null, null, null, null, null, null, ctypes.c_int32(0), ctypes.c_int32(1), null,
+                ctypes.c_int32(0), null, null, null]
+    assert raw.pl_episode_run(*args_run) == -1                          # weights handle is NULL
+    raw.pl_last_error.restype = ctypes.c_char_p
+    assert b"NULL" in raw.pl_last_error()
+    g.close()
