@@ -111,7 +111,9 @@ def main() -> int:
 
     w = make_workload(args.workload, B=args.batch)
     placement, cur, done = make_states(w, N_STATES)
+    t_build = time.perf_counter()
     g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+    layout_build_ms = 1e3 * (time.perf_counter() - t_build)     # host: CSR, levels, buckets (once per batch)
     wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
     feats = []
     for s in range(N_STATES):
@@ -156,7 +158,10 @@ def main() -> int:
                 "algorithmic_bytes_per_launch": alg, "avg_launch_ms": round(avg_launch_ms, 5),
                 "path_algorithmic_bytes_per_step": path_algorithmic_bytes(w.n_tot, w.e_tot, w.H),
                 "path_frac": round(path_algorithmic_bytes(w.n_tot, w.e_tot, w.H)
-                                   / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 5)}
+                                   / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 5),
+                # what actually bounds the sweep: one dependent step per level of the deepest graph
+                "levels": int(g.max_depth),
+                "us_per_level": round(1e3 * avg_launch_ms / max(1, int(g.max_depth)), 4)}
 
     # the same path driven as an episode (Section 2.1): forward pass + on-device transition per
     # step, enqueued without host synchronisation; reported beside the headline, not in it
@@ -209,6 +214,7 @@ def main() -> int:
                    "k_sweeps": w.k_sweeps, "max_depth": int(g.max_depth),
                    "weight_dtype": w.weight_dtype, "states": N_STATES},
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "layout_build_ms": round(layout_build_ms, 2),
         "roofline": roofline,
         "episode": episode,
         "cpu_baseline": cpu_baseline,

@@ -233,3 +233,20 @@ def test_forward_replays_from_a_hip_graph():
     del graph
     g.close()
     wt.close()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_dags_through_the_matrix_core_kernels(seed):
+    """Random DAGs of many densities through every path of the matrix-core sweep and pooling
+    kernels: short and long row records, neighbour lists, more than eight and more than
+    sixteen far sources per chunk, one and two row tiles, all three widths, both weight
+    formats, one to three sweeps."""
+    rng = np.random.default_rng(1000 + seed)
+    H = (32, 64, 128)[seed % 3]
+    wd = "bf16" if (H == 128 or seed % 2) else "fp32"
+    sizes = [int(x) for x in rng.integers(1, 140, size=6)]
+    p_edge = float(rng.choice([0.01, 0.03, 0.08, 0.2, 0.5]))
+    D = int(rng.integers(1, 9))
+    w = _custom(rng, sizes, D, H, n_layers=1 + seed % 2, k_sweeps=1 + (seed // 4) % 3, group=seed % 2,
+                weight_dtype=wd, p_edge=p_edge)
+    _compare(w, f"seed {seed}: H={H} {wd} sizes={sizes} p_edge={p_edge} D={D}")
