@@ -1,0 +1,104 @@
+"""CPU oracle for the runtime simulator of a placement (Appendix, "Simulator").
+
+TEST INFRASTRUCTURE ONLY: imported by tests/; shares no code with the HIP library.
+
+What the paper fixes: every device d has a FIFO queue of runnable operations and a FIFO
+queue of output tensors waiting to leave d; a device runs one operation at a time and its
+bus carries one tensor at a time, transfers overlap with compute; an operation is runnable on
+its device once all its parents have finished and their outputs have arrived there; an
+event-driven loop with op-done, transfer-done and wakeup events produces the timeline; the
+simulated run time is the timestamp of the last op-done event; a transfer takes
+size / bandwidth.
+
+Readings where the paper is silent:
+ * one run time per operation (the synthetic workloads have one cost per node, so all devices
+   are alike);
+ * an output tensor is sent once per destination device, however many children wait there;
+ * operations without parents are queued in ascending node id at time 0; the children of a
+   finished operation are visited in ascending node id;
+ * events are taken in order of (timestamp, creation number); after every event the free
+   devices 0..D-1 with a non-empty queue are started first, then the free buses 0..D-1
+   (these are the paper's wakeups);
+ * timestamps are float32, formed as start + cost and start + size * (1 / bandwidth) with one
+   rounding per operation: the event order is an integer decision taken in this precision
+   on both sides, so the two timelines are identical event by event;
+ * the peak-memory term of the reward is not modelled (the paper gives no formula for it).
+"""
+from __future__ import annotations
+
+from collections import deque
+
+import numpy as np
+
+F = np.float32
+
+
+def simulate(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth, trace=None):
+    """Run time of one placement of one graph.  src/dst: edges (parent, child), graph-local
+    ids.  Returns (runtime float32, n_events).  `trace`, if a list, receives
+    (kind, node, device, timestamp) per processed event."""
+    src = np.asarray(src, dtype=np.int64)
+    dst = np.asarray(dst, dtype=np.int64)
+    cost = np.asarray(cost, dtype=F)
+    out_bytes = np.asarray(out_bytes, dtype=F)
+    placement = np.asarray(placement, dtype=np.int64)
+    inv_bw = F(inv_bandwidth)
+    children = [[] for _ in range(n)]
+    pend = np.zeros(n, dtype=np.int64)
+    for u, v in sorted(zip(src.tolist(), dst.tolist())):
+        children[u].append(v)              # ascending child id
+        pend[v] += 1
+    q_op = [deque() for _ in range(D)]
+    q_tr = [deque() for _ in range(D)]
+    ev = {}                                # slot -> (time, seq, node, dest): slot d = device d, D + d = bus d
+    seq = 0
+    for v in range(n):
+        if pend[v] == 0:
+            q_op[placement[v]].append(v)
+
+    def wake(now):
+        nonlocal seq
+        for d in range(D):
+            if d not in ev and q_op[d]:
+                o = q_op[d].popleft()
+                ev[d] = (F(now + cost[o]), seq, o, -1)
+                seq += 1
+        for d in range(D):
+            if D + d not in ev and q_tr[d]:
+                o, dc = q_tr[d].popleft()
+                ev[D + d] = (F(now + F(out_bytes[o] * inv_bw)), seq, o, dc)
+                seq += 1
+
+    wake(F(0.0))
+    last = F(0.0)
+    n_events = 0
+    while ev:
+        slot = min(ev, key=lambda s: (ev[s][0], ev[s][1]))
+        now, _, o, dc = ev.pop(slot)
+        n_events += 1
+        if slot < D:                       # op-done of o on device slot
+            d = slot
+            last = now
+            if trace is not None:
+                trace.append(("op", o, d, float(now)))
+            sent = set()
+            for c in children[o]:
+                pc = int(placement[c])
+                if pc == d:
+                    pend[c] -= 1
+                    if pend[c] == 0:
+                        q_op[pc].append(c)
+                elif pc not in sent:
+                    sent.add(pc)
+                    q_tr[d].append((o, pc))
+        else:                              # transfer-done: o's output has arrived on device dc
+            if trace is not None:
+                trace.append(("tr", o, dc, float(now)))
+            for c in children[o]:
+                if int(placement[c]) == dc:
+                    pend[c] -= 1
+                    if pend[c] == 0:
+                        q_op[dc].append(c)
+        wake(now)
+    assert (pend == 0).all(), "an operation never became runnable"
+    return last, n_events
