@@ -185,6 +185,24 @@ def main() -> int:
                "graph_steps_per_s": round(w.B * ep_steps / ep_elapsed, 2),
                "what": "forward pass + sampled on-device transition per step, from the trivial placement"}
 
+    # the run-time simulator of the paper's appendix on the same batch (the reward of an episode
+    # needs one run per episode, or one per step with intermediate rewards); beside the headline
+    sim_rt = torch.empty((w.B,), dtype=torch.float32, device=dev)
+    sim_ev = torch.empty((w.B,), dtype=torch.int32, device=dev)
+    inv_bw = 5e-5
+    pl.simulate_runtime(g, w.D, feats[0], t_place[0], inv_bw, sim_rt, sim_ev, stream=stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    sim_reps = 5
+    for i in range(sim_reps):
+        pl.simulate_runtime(g, w.D, feats[0], t_place[i % N_STATES], inv_bw, sim_rt, sim_ev, stream=stream)
+    torch.cuda.synchronize()
+    sim_elapsed = (time.perf_counter() - t0) / sim_reps
+    simulator = {"ms_per_batch": round(1e3 * sim_elapsed, 4),
+                 "placements_per_s": round(w.B / sim_elapsed, 1),
+                 "events_per_s": round(float(sim_ev.sum().item()) / sim_elapsed, 1),
+                 "what": "event-driven run-time simulation of one placement per graph (one wave per graph)"}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
@@ -217,6 +235,7 @@ def main() -> int:
         "layout_build_ms": round(layout_build_ms, 2),
         "roofline": roofline,
         "episode": episode,
+        "simulator": simulator,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))

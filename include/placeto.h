@@ -174,6 +174,24 @@ int pl_episode_run(pl_graph_batch *g, const pl_weights *w, float *node_feats, in
                    int32_t n_steps, float *logits, int32_t keep_logits, int32_t *out_actions,
                    float *out_logp, void *stream);
 
+/* ---- run time of a placement from the event-driven simulator of the paper's appendix
+ * ("Simulator"), for every graph of the batch: per device a FIFO queue of runnable operations
+ * and a FIFO queue of outgoing tensors, one operation per device and one transfer per bus at a
+ * time, transfers overlapping compute; the result is the timestamp of the last op-done event.
+ * This is the run time r of the reward R(p); the peak-memory term of R(p) is not modelled.
+ *   node_feats     dev [N_tot, 3]  column 0: run time of the operation, column 1: size of its output
+ *   placement      dev [N_tot]     device of every node, in [0, D)
+ *   inv_bandwidth                  seconds per unit of output size (a transfer takes size x this)
+ *   out_runtime    dev [B] fp32    simulated run time; NaN for a graph with a device id outside [0, D)
+ *   out_events     dev [B] int32   events processed (operations + transfers), -1 for such a graph; NULL to skip
+ * Ties are broken as follows: roots are queued in ascending node id, children are visited in
+ * ascending node id, an output crosses once per destination device, events are ordered by
+ * (float32 timestamp, creation number), idle devices are started before idle buses, both in
+ * ascending index.  A graph must fit in LDS: fewer than 65535 nodes and edges and
+ * 17 n + 7 e bytes <= 160 KB, else PL_ERR_SHAPE.  Asynchronous on `stream`. */
+int pl_simulate_runtime(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
+                        float inv_bandwidth, float *out_runtime, int32_t *out_events, void *stream);
+
 /* ---- per-stage timing, for benchmarks.  While enabled, forward calls bracket each
  * kernel stage with HIP events on the caller's stream.  pl_profile_read synchronises those
  * events and returns, per stage, the summed milliseconds and the number of launches since

@@ -15,5 +15,6 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     node_classes,
+    simulate_runtime,
     weights_count,
 )

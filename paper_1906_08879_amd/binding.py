@@ -65,6 +65,7 @@ def load_library(path: Optional[str] = None):
                                            vp, vp, vp]),
         "pl_episode_run": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
                                           vp, ctypes.c_int32, vp, vp, vp]),
+        "pl_simulate_runtime": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, ctypes.c_float, vp, vp, vp]),
         "pl_profile_enable": (ctypes.c_int, [vp, ctypes.c_int32]),
         "pl_profile_read": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_double), i64p,
                                            ctypes.c_int32]),
@@ -273,3 +274,16 @@ def episode_run(g: GraphBatch, w: Weights, node_feats, placement, cur_node, orde
         _dev_ptr(out_actions, torch.int32, g.B * n_steps, "out_actions"),
         _dev_ptr(out_logp, torch.float32, g.B * n_steps, "out_logp"), _stream_ptr(stream)),
         "pl_episode_run")
+
+
+def simulate_runtime(g: GraphBatch, D: int, node_feats, placement, inv_bandwidth: float, out_runtime,
+                     out_events=None, stream=None):
+    """pl_simulate_runtime on device tensors: simulated run time of the placement of every graph."""
+    import torch
+    lib = load_library()
+    _check(lib.pl_simulate_runtime(
+        g._h, int(D), _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
+        _dev_ptr(placement, torch.int32, g.n_tot, "placement"), float(inv_bandwidth),
+        _dev_ptr(out_runtime, torch.float32, g.B, "out_runtime"),
+        _dev_ptr(out_events, torch.int32, g.B, "out_events"), _stream_ptr(stream)), "pl_simulate_runtime")
+    return out_runtime

@@ -1,6 +1,7 @@
 // C ABI of the library (declared in include/placeto.h): handles, uploads, scratch buffers
 // and the sequence of kernel launches that makes one policy forward pass (Section 2.2
 // steps 1-3 and the policy head of Appendix A.7).
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -607,6 +608,32 @@ int pl_episode_run(pl_graph_batch *g, const pl_weights *w, float *node_feats, in
                             out_logp ? out_logp + static_cast<size_t>(i) * B : nullptr,
                             static_cast<hipStream_t>(stream));
     }
+    PL_HIP(hipGetLastError());
+    return PL_OK;
+}
+
+int pl_simulate_runtime(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
+                        float inv_bandwidth, float *out_runtime, int32_t *out_events, void *stream)
+{
+    if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
+    if (D < 1 || D > kMaxD) return fail(PL_ERR_SHAPE, "D must be in [1, 16]");
+    if (!(inv_bandwidth >= 0.0f)) return fail(PL_ERR_SHAPE, "inv_bandwidth must not be negative");
+    if (g->host.B == 0) return PL_OK;
+    if (!node_feats || !placement || !out_runtime) return fail(PL_ERR_NULL, "a required device array is NULL");
+    int64_t n_max = 0, e_max = 0;
+    for (int32_t b = 0; b < g->host.B; ++b) {
+        n_max = std::max<int64_t>(n_max, g->host.node_off[b + 1] - g->host.node_off[b]);
+        e_max = std::max<int64_t>(e_max, g->host.edge_off[b + 1] - g->host.edge_off[b]);
+    }
+    // graph-local ids and queue links are 16-bit in LDS; the whole graph must fit the 160 KB of a CU
+    if (n_max >= 0xFFFF || e_max >= 0xFFFF ||
+        simulator_lds_bytes(static_cast<int>(n_max), static_cast<int>(e_max)) > 160 * 1024)
+        return fail(PL_ERR_SHAPE, "a graph is too large for the simulator (its state must fit in 160 KB of LDS)");
+    int rc = ensure_on_device(g);
+    if (rc) return rc;
+    rc = launch_simulate(g->view, D, static_cast<int>(n_max), static_cast<int>(e_max), node_feats, placement,
+                         inv_bandwidth, out_runtime, out_events, static_cast<hipStream_t>(stream));
+    if (rc) return rc;
     PL_HIP(hipGetLastError());
     return PL_OK;
 }

@@ -162,6 +162,12 @@ void launch_episode_step(const GraphView &gv, int D, const float *logits, const 
                          const int32_t *order, int t, float *node_feats, int32_t *placement,
                          int32_t *cur_node, int32_t *out_action, float *out_logp, hipStream_t s);
 
+// ---- run-time simulator of a placement (kernels_simulator.hip); n_max / e_max: largest graph
+size_t simulator_lds_bytes(int n_max, int e_max);
+int launch_simulate(const GraphView &gv, int D, int n_max, int e_max, const float *node_feats,
+                    const int32_t *placement, float inv_bw, float *out_runtime, int32_t *out_events,
+                    hipStream_t s);
+
 // ---- matrix-core pooling (kernels_pool_mfma.hip); writes ws.partial as [B, kPoolSlices, 3G, H]
 constexpr int kPoolSlices = 4;
 bool pool_mfma_supported(int H, int L, int weight_dtype);

@@ -1,0 +1,245 @@
+// Run-time simulator of a placement (Appendix, "Simulator"): per device a FIFO queue of
+// runnable operations and a FIFO queue of output tensors waiting to leave the device; a device
+// runs one operation at a time, its bus carries one tensor at a time, transfers overlap with
+// compute; an event loop over op-done and transfer-done events; the run time is the timestamp
+// of the last op-done event.
+//
+// A discrete-event simulation is one dependent chain, so a graph gets one wave, and the batch
+// of graphs (rollouts) supplies the parallelism: one workgroup of 64 lanes per graph, the whole
+// state of the graph in LDS (children lists, placement, costs, pending-input counters, queue
+// links).  There are at most 2 D events pending (one per device, one per bus): lane d owns the
+// queue and the pending event of device d, lane D + d those of bus d, in registers; the next
+// event is a wave-wide minimum over (timestamp, creation number), wake-ups of idle devices and
+// buses happen in all lanes at once.  Control flow is uniform over the wave.
+//
+// Timestamps are float32 with one rounding per operation (no fused multiply-add), and events
+// are ordered by (timestamp, creation number): the order is the same as that of a scalar
+// implementation of the same rules, event by event.
+#include "internal.h"
+
+namespace pl {
+
+namespace {
+
+struct SimLds {
+    int32_t *cptr;        // [n + 1] children offsets, graph-local
+    float *cost;          // [n]
+    float *size;          // [n]
+    uint16_t *cidx;       // [e] children, graph-local ids, ascending per node
+    uint16_t *pend;       // [n] inputs not yet available on the node's device
+    uint16_t *next_op;    // [n] link of the per-device operation queues
+    uint16_t *tr_op;      // [e] transfer records: producer
+    uint16_t *tr_next;    // [e] link of the per-bus transfer queues
+    uint8_t *place;       // [n]
+    uint8_t *tr_dst;      // [e] destination device
+};
+
+__device__ __forceinline__ SimLds carve(unsigned char *base, int n_max, int e_max)
+{
+    SimLds s;
+    unsigned char *p = base;
+    s.cptr = reinterpret_cast<int32_t *>(p);   p += sizeof(int32_t) * (n_max + 1);
+    s.cost = reinterpret_cast<float *>(p);     p += sizeof(float) * n_max;
+    s.size = reinterpret_cast<float *>(p);     p += sizeof(float) * n_max;
+    s.cidx = reinterpret_cast<uint16_t *>(p);  p += sizeof(uint16_t) * (e_max + (e_max & 1));
+    s.pend = reinterpret_cast<uint16_t *>(p);  p += sizeof(uint16_t) * (n_max + (n_max & 1));
+    s.next_op = reinterpret_cast<uint16_t *>(p); p += sizeof(uint16_t) * (n_max + (n_max & 1));
+    s.tr_op = reinterpret_cast<uint16_t *>(p); p += sizeof(uint16_t) * (e_max + (e_max & 1));
+    s.tr_next = reinterpret_cast<uint16_t *>(p); p += sizeof(uint16_t) * (e_max + (e_max & 1));
+    s.place = p;                               p += n_max;
+    s.tr_dst = p;
+    return s;
+}
+
+constexpr int kNone = 0xFFFF;    // empty link / empty queue
+
+// Minimum of an unsigned value over lanes 0..31 (two DPP rows), returned in every lane.
+__device__ __forceinline__ unsigned int row_pair_min(unsigned int v)
+{
+    const int i0 = static_cast<int>(v);
+    unsigned int o;
+    o = static_cast<unsigned int>(__builtin_amdgcn_update_dpp(i0, i0, 0xB1, 0xF, 0xF, false));     // quad_perm [1,0,3,2]
+    v = o < v ? o : v;
+    o = static_cast<unsigned int>(__builtin_amdgcn_update_dpp(static_cast<int>(v), static_cast<int>(v), 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+    v = o < v ? o : v;
+    o = static_cast<unsigned int>(__builtin_amdgcn_update_dpp(static_cast<int>(v), static_cast<int>(v), 0x141, 0xF, 0xF, false));  // row_half_mirror
+    v = o < v ? o : v;
+    o = static_cast<unsigned int>(__builtin_amdgcn_update_dpp(static_cast<int>(v), static_cast<int>(v), 0x140, 0xF, 0xF, false));  // row_mirror
+    v = o < v ? o : v;
+    const unsigned int r0 = static_cast<unsigned int>(__builtin_amdgcn_readlane(static_cast<int>(v), 0));
+    const unsigned int r1 = static_cast<unsigned int>(__builtin_amdgcn_readlane(static_cast<int>(v), 16));
+    return r0 < r1 ? r0 : r1;
+}
+
+__global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max, int e_max,
+                                                 const float *__restrict__ node_feats,
+                                                 const int32_t *__restrict__ placement, float inv_bw,
+                                                 float *__restrict__ out_runtime,
+                                                 int32_t *__restrict__ out_events)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const SimLds S = carve(lds_raw, n_max, e_max);
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int n0 = gv.node_off[b], n = gv.node_off[b + 1] - n0;
+    const int32_t *gptr = gv.nbr_ptr[1] + n0;            // children CSR (global offsets / ids)
+    const int e0 = gptr[0], e = gptr[n] - e0;
+
+    // ---- the graph's state into LDS
+    bool bad = false;                                     // a device id outside [0, D)
+    for (int v = lane; v < n; v += 64) {
+        const int d = placement[n0 + v];
+        bad |= d < 0 || d >= D;
+        S.place[v] = static_cast<uint8_t>(d);
+        S.cost[v] = node_feats[static_cast<size_t>(n0 + v) * 3 + 0];
+        S.size[v] = node_feats[static_cast<size_t>(n0 + v) * 3 + 1];
+        S.pend[v] = static_cast<uint16_t>(gv.nbr_ptr[0][n0 + v + 1] - gv.nbr_ptr[0][n0 + v]);   // number of parents
+        S.next_op[v] = kNone;
+    }
+    for (int v = lane; v <= n; v += 64) S.cptr[v] = gptr[v] - e0;
+    for (int i = lane; i < e; i += 64) S.cidx[i] = static_cast<uint16_t>(gv.nbr_idx[1][e0 + i] - n0);
+    __syncthreads();
+    if (__ballot(bad) != 0ull) {
+        if (lane == 0) {
+            out_runtime[b] = __builtin_nanf("");
+            if (out_events) out_events[b] = -1;
+        }
+        return;
+    }
+
+    // ---- lane-private queue ends and pending event (lane d: device d, lane D + d: bus d)
+    int q_head = kNone, q_tail = kNone;
+    bool active = false;
+    float ev_time = 0.0f;
+    int ev_seq = 0, ev_node = 0, ev_dst = 0;
+    int seq = 0, n_tr = 0, n_events = 0;
+    float last = 0.0f;
+
+    auto enqueue_op = [&](int dev, int v) {               // uniform arguments
+        if (lane == dev) {
+            if (q_tail == kNone) q_head = v; else S.next_op[q_tail] = static_cast<uint16_t>(v);
+            q_tail = v;
+        }
+    };
+    auto enqueue_transfer = [&](int dev, int o, int dst) {
+        const int k = n_tr++;
+        S.tr_op[k] = static_cast<uint16_t>(o);
+        S.tr_dst[k] = static_cast<uint8_t>(dst);
+        S.tr_next[k] = kNone;
+        if (lane == D + dev) {
+            if (q_tail == kNone) q_head = k; else S.tr_next[q_tail] = static_cast<uint16_t>(k);
+            q_tail = k;
+        }
+    };
+    // idle devices, then idle buses, with a non-empty queue start their next item (the wake-ups)
+    auto wake = [&](float now) {
+        const bool start = !active && q_head != kNone && lane < 2 * D;
+        const unsigned long long m = __ballot(start);
+        if (start) {
+            const int item = q_head;
+            int o, dst = -1;
+            float dur;
+            if (lane < D) {
+                o = item;
+                q_head = S.next_op[item];
+                dur = S.cost[o];
+            } else {
+                o = S.tr_op[item];
+                dst = S.tr_dst[item];
+                q_head = S.tr_next[item];
+                dur = __fmul_rn(S.size[o], inv_bw);
+            }
+            if (q_head == kNone) q_tail = kNone;
+            active = true;
+            ev_time = __fadd_rn(now, dur);
+            ev_seq = seq + __popcll(m & ((1ull << lane) - 1ull));
+            ev_node = o;
+            ev_dst = dst;
+        }
+        seq += __popcll(m);
+    };
+
+    for (int base = 0; base < n; base += 64) {            // operations without parents, ascending id
+        const int v = base + lane;
+        unsigned long long roots = __ballot(v < n && S.pend[v < n ? v : 0] == 0);
+        while (roots != 0ull) {
+            const int r = base + __ffsll(static_cast<long long>(roots)) - 1;
+            roots &= roots - 1;
+            enqueue_op(S.place[r], r);
+        }
+    }
+    wake(0.0f);
+
+    const int max_events = n + e + 8;                     // every operation and transfer ends once
+    for (int it = 0; it < max_events; ++it) {
+        // ---- next event: smallest (timestamp, creation number).  Timestamps are >= 0, so their
+        // bit patterns order like the values.  Lanes 0 .. 2 D - 1 (at most two rows of sixteen)
+        // hold the candidates: the minimum over each row comes from four DPP steps, the two
+        // rows are combined through scalar registers.
+        const unsigned int t_bits = active ? __float_as_uint(ev_time) : 0xFFFFFFFFu;
+        const unsigned int t_min = row_pair_min(t_bits);
+        if (t_min == 0xFFFFFFFFu) break;                  // nothing pending: the simulation is over
+        const unsigned int s_bits = (active && t_bits == t_min) ? static_cast<unsigned int>(ev_seq) : 0xFFFFFFFFu;
+        const unsigned int s_min = row_pair_min(s_bits);
+        const int slot = __ffsll(static_cast<long long>(__ballot(s_bits == s_min && active && t_bits == t_min))) - 1;
+        const float now = __uint_as_float(t_min);
+        const int o = __builtin_amdgcn_readlane(ev_node, slot);
+        const int dst = __builtin_amdgcn_readlane(ev_dst, slot);
+        if (lane == slot) active = false;
+        ++n_events;
+        const int c0 = S.cptr[o], c1 = S.cptr[o + 1];
+        if (slot < D) {                                   // op-done of o on device `slot`
+            last = now;
+            unsigned int sent = 0;
+            for (int i = c0; i < c1; ++i) {
+                const int c = S.cidx[i];
+                const int pc = S.place[c];
+                if (pc == slot) {
+                    const int p = S.pend[c] - 1;
+                    S.pend[c] = static_cast<uint16_t>(p);
+                    if (p == 0) enqueue_op(pc, c);
+                } else if (((sent >> pc) & 1u) == 0) {    // the output crosses once per destination
+                    sent |= 1u << pc;
+                    enqueue_transfer(slot, o, pc);
+                }
+            }
+        } else {                                          // o's output has arrived on device dst
+            for (int i = c0; i < c1; ++i) {
+                const int c = S.cidx[i];
+                if (S.place[c] == dst) {
+                    const int p = S.pend[c] - 1;
+                    S.pend[c] = static_cast<uint16_t>(p);
+                    if (p == 0) enqueue_op(dst, c);
+                }
+            }
+        }
+        wake(now);
+    }
+    if (lane == 0) {
+        out_runtime[b] = last;
+        if (out_events) out_events[b] = n_events;
+    }
+}
+
+}  // namespace
+
+size_t simulator_lds_bytes(int n_max, int e_max)
+{
+    return sizeof(int32_t) * (n_max + 1) + 2 * sizeof(float) * n_max + 3 * sizeof(uint16_t) * (e_max + (e_max & 1)) +
+           2 * sizeof(uint16_t) * (n_max + (n_max & 1)) + n_max + e_max + 16;
+}
+
+int launch_simulate(const GraphView &gv, int D, int n_max, int e_max, const float *node_feats,
+                    const int32_t *placement, float inv_bw, float *out_runtime, int32_t *out_events,
+                    hipStream_t s)
+{
+    if (gv.B == 0) return PL_OK;
+    const size_t lds = simulator_lds_bytes(n_max, e_max);
+    if (lds > 64 * 1024)
+        PL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_simulate),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+    hipLaunchKernelGGL(k_simulate, dim3(gv.B), dim3(64), lds, s, gv, D, n_max, e_max, node_feats, placement, inv_bw,
+                       out_runtime, out_events);
+    return PL_OK;
+}
+
+}  // namespace pl

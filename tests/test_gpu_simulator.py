@@ -1,0 +1,93 @@
+"""GPU parity of the placement run-time simulator against its oracle (oracle/simulator.py),
+through the C ABI.  Timestamps are float32 with the same roundings on both sides and events
+are ordered by (timestamp, creation number), so run times and event counts must be equal bit
+for bit."""
+import numpy as np
+import pytest
+
+from oracle import simulator as sim
+from workloads import make_workload, tiny_random_dag
+from workloads.synthetic import Workload
+
+pytestmark = pytest.mark.gpu
+
+
+def run_device(w, placement, inv_bw):
+    import torch
+    import paper_1906_08879_amd as pl
+    dev = torch.device("cuda:0")
+    g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+    out = torch.full((w.B,), -1.0, dtype=torch.float32, device=dev)
+    ev = torch.full((w.B,), -7, dtype=torch.int32, device=dev)
+    pl.simulate_runtime(g, w.D, torch.from_numpy(np.ascontiguousarray(w.node_feats, dtype=np.float32)).to(dev),
+                        torch.from_numpy(np.ascontiguousarray(placement, dtype=np.int32)).to(dev), inv_bw, out, ev)
+    torch.cuda.synchronize()
+    g.close()
+    return out.cpu().numpy(), ev.cpu().numpy()
+
+
+def oracle_graph(w, b, placement, inv_bw):
+    n0, n1 = int(w.node_off[b]), int(w.node_off[b + 1])
+    e0, e1 = int(w.edge_off[b]), int(w.edge_off[b + 1])
+    return sim.simulate(n1 - n0, w.edge_src[e0:e1], w.edge_dst[e0:e1], w.node_feats[n0:n1, 0],
+                        w.node_feats[n0:n1, 1], placement[n0:n1], w.D, inv_bw)
+
+
+@pytest.mark.parametrize("name,B,inv_bw", [("random32", 1, 1e-4), ("layered200", 8, 1e-4), ("inception", 4, 3e-5),
+                                           ("nmt", 3, 1e-4), ("nasnet", 3, 5e-5), ("layered200", 5, 0.0)])
+def test_run_times_and_event_counts_bit_exact(name, B, inv_bw):
+    w = make_workload(name, B=B)
+    rng = np.random.default_rng(17)
+    for trial in range(2):
+        placement = w.placement if trial == 0 else rng.integers(0, w.D, w.n_tot).astype(np.int32)
+        got_r, got_e = run_device(w, placement, inv_bw)
+        for b in range(w.B):
+            r, e = oracle_graph(w, b, placement, np.float32(inv_bw))
+            assert got_e[b] == e, (name, b, got_e[b], e)
+            assert got_r[b] == r, (name, b, got_r[b], r)
+
+
+def test_all_on_one_device_and_bad_device_ids():
+    w = make_workload("layered200", B=4)
+    placement = np.zeros(w.n_tot, dtype=np.int32)
+    placement[w.node_off[2] + 5] = w.D            # outside [0, D): that graph only
+    got_r, got_e = run_device(w, placement, 1e-4)
+    for b in range(w.B):
+        n0, n1 = int(w.node_off[b]), int(w.node_off[b + 1])
+        if b == 2:
+            assert np.isnan(got_r[b]) and got_e[b] == -1
+        else:
+            assert got_e[b] == n1 - n0           # no transfers
+            assert abs(got_r[b] - w.node_feats[n0:n1, 0].astype(np.float64).sum()) <= 1e-4 * got_r[b]
+
+
+def test_random_dags_with_ties_and_wide_fan_out():
+    # integer costs and sizes: many events share a timestamp, so the tie rules decide the order
+    rng = np.random.default_rng(3)
+    sizes = [1, 2, 30, 64, 100, 7]
+    n_nodes, n_edges, srcs, dsts, feats = [], [], [], [], []
+    for n in sizes:
+        s, d = tiny_random_dag(rng, n, 0.3)
+        n_nodes.append(n); n_edges.append(len(s)); srcs.append(s); dsts.append(d)
+        feats.append(np.stack([rng.integers(1, 4, n), rng.integers(0, 3, n), np.zeros(n)], axis=1))
+    D = 5
+    w = Workload(name="custom", B=len(sizes), D=D, H=8, n_layers=1, k_sweeps=1, group_by_device=1, weight_dtype="fp32",
+                 n_nodes=np.array(n_nodes, np.int32), n_edges=np.array(n_edges, np.int32),
+                 edge_src=np.concatenate(srcs).astype(np.int32), edge_dst=np.concatenate(dsts).astype(np.int32),
+                 node_feats=np.concatenate(feats).astype(np.float32),
+                 placement=rng.integers(0, D, sum(sizes)).astype(np.int32),
+                 cur_node=np.zeros(len(sizes), np.int32), weights=np.zeros(1, np.float32))
+    got_r, got_e = run_device(w, w.placement, 1.0)
+    for b in range(w.B):
+        r, e = oracle_graph(w, b, w.placement, np.float32(1.0))
+        assert (got_r[b], got_e[b]) == (r, e), (b, got_r[b], r, got_e[b], e)
+
+
+def test_full_batch_sampled():
+    # the benchmark's batch; three graphs are simulated by the oracle
+    w = make_workload("nasnet")
+    got_r, got_e = run_device(w, w.placement, 5e-5)
+    assert np.isfinite(got_r).all() and (got_e >= w.n_nodes).all()
+    for b in (0, 100, w.B - 1):
+        r, e = oracle_graph(w, b, w.placement, np.float32(5e-5))
+        assert (got_r[b], got_e[b]) == (r, e)
