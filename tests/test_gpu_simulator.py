@@ -61,7 +61,8 @@ def test_all_on_one_device_and_bad_device_ids():
             assert abs(got_r[b] - w.node_feats[n0:n1, 0].astype(np.float64).sum()) <= 1e-4 * got_r[b]
 
 
-def test_random_dags_with_ties_and_wide_fan_out():
+@pytest.mark.parametrize("D", [1, 5, 16])
+def test_random_dags_with_ties_and_wide_fan_out(D):
     # integer costs and sizes: many events share a timestamp, so the tie rules decide the order
     rng = np.random.default_rng(3)
     sizes = [1, 2, 30, 64, 100, 7]
@@ -70,7 +71,6 @@ def test_random_dags_with_ties_and_wide_fan_out():
         s, d = tiny_random_dag(rng, n, 0.3)
         n_nodes.append(n); n_edges.append(len(s)); srcs.append(s); dsts.append(d)
         feats.append(np.stack([rng.integers(1, 4, n), rng.integers(0, 3, n), np.zeros(n)], axis=1))
-    D = 5
     w = Workload(name="custom", B=len(sizes), D=D, H=8, n_layers=1, k_sweeps=1, group_by_device=1, weight_dtype="fp32",
                  n_nodes=np.array(n_nodes, np.int32), n_edges=np.array(n_edges, np.int32),
                  edge_src=np.concatenate(srcs).astype(np.int32), edge_dst=np.concatenate(dsts).astype(np.int32),
