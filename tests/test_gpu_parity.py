@@ -250,3 +250,23 @@ def test_random_dags_through_the_matrix_core_kernels(seed):
     w = _custom(rng, sizes, D, H, n_layers=1 + seed % 2, k_sweeps=1 + (seed // 4) % 3, group=seed % 2,
                 weight_dtype=wd, p_edge=p_edge)
     _compare(w, f"seed {seed}: H={H} {wd} sizes={sizes} p_edge={p_edge} D={D}")
+
+
+@pytest.mark.parametrize("name", ["nmt", "nasnet"])
+def test_full_size_sampled_embeddings_and_pooled_sums(name):
+    """At the benchmark's batch size: node embeddings and pooled sums of three sampled graphs
+    against the oracle run on those graphs alone (the logits of every graph are covered by
+    test_full_size_logits)."""
+    w = make_workload(name)
+    got = run_library(w, want_emb=True)
+    blob = oracle.weights_as_stored(w.weights, w.D, w.H, w.n_layers, w.group_by_device, w.weight_dtype)
+    for b in (0, w.B // 2, w.B - 1):
+        n, src, dst, feats, placement, cur = w.graph(b)
+        ref = oracle.forward_graph(n, src, dst, feats, placement, cur, blob, w.D, w.H, w.n_layers, w.k_sweeps,
+                                   w.group_by_device)
+        n0 = int(w.node_off[b])
+        scale = np.abs(ref["emb"]).max()
+        assert np.abs(got["emb"][n0:n0 + n] - ref["emb"]).max() <= 2e-5 * scale, (name, b)
+        pscale = max(np.abs(ref["pooled"]).max(), 1e-30)
+        assert np.abs(got["pooled"][b] - ref["pooled"].reshape(got["pooled"][b].shape)).max() <= 2e-5 * pscale, (name, b)
+        assert_logits_close(got["logits"][b:b + 1], ref["logits"].reshape(1, -1), f"{name} graph {b}")
