@@ -188,7 +188,7 @@ int pl_episode_run(pl_graph_batch *g, const pl_weights *w, float *node_feats, in
  * ascending node id, an output crosses once per destination device, events are ordered by
  * (float32 timestamp, creation number), idle devices are started before idle buses, both in
  * ascending index.  A graph must fit in LDS: fewer than 65535 nodes and edges and
- * 17 n + 7 e bytes <= 160 KB, else PL_ERR_SHAPE.  Asynchronous on `stream`. */
+ * 18 n + 11 e bytes <= 160 KB, else PL_ERR_SHAPE.  Asynchronous on `stream`. */
 int pl_simulate_runtime(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
                         float inv_bandwidth, float *out_runtime, int32_t *out_events, void *stream);
 

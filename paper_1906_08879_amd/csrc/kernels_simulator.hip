@@ -7,7 +7,7 @@
 // A discrete-event simulation is one dependent chain, so a graph gets one wave, and the batch
 // of graphs (rollouts) supplies the parallelism: one workgroup of 64 lanes per graph, the whole
 // state of the graph in LDS (children lists, placement, costs, pending-input counters, queue
-// links).  There are at most 2 D events pending (one per device, one per bus): lane d owns the
+// links, transfer records).  There are at most 2 D events pending (one per device, one per bus): lane d owns the
 // queue and the pending event of device d, lane D + d those of bus d, in registers; the next
 // event is a wave-wide minimum over (timestamp, creation number), wake-ups of idle devices and
 // buses happen in all lanes at once.  Control flow is uniform over the wave.
@@ -25,12 +25,12 @@ struct SimLds {
     int32_t *cptr;        // [n + 1] children offsets, graph-local
     float *cost;          // [n]
     float *size;          // [n]
+    float *tr_dur;        // [e] transfer records: duration = size of the producer's output / bandwidth
     uint16_t *cidx;       // [e] children, graph-local ids, ascending per node
-    uint16_t *pend;       // [n] inputs not yet available on the node's device
+    uint32_t *node;       // [n] device of the node (bits 0-7) | inputs not yet available on that device << 8
     uint16_t *next_op;    // [n] link of the per-device operation queues
     uint16_t *tr_op;      // [e] transfer records: producer
     uint16_t *tr_next;    // [e] link of the per-bus transfer queues
-    uint8_t *place;       // [n]
     uint8_t *tr_dst;      // [e] destination device
 };
 
@@ -41,12 +41,12 @@ __device__ __forceinline__ SimLds carve(unsigned char *base, int n_max, int e_ma
     s.cptr = reinterpret_cast<int32_t *>(p);   p += sizeof(int32_t) * (n_max + 1);
     s.cost = reinterpret_cast<float *>(p);     p += sizeof(float) * n_max;
     s.size = reinterpret_cast<float *>(p);     p += sizeof(float) * n_max;
+    s.tr_dur = reinterpret_cast<float *>(p);   p += sizeof(float) * e_max;
+    s.node = reinterpret_cast<uint32_t *>(p);  p += sizeof(uint32_t) * n_max;
     s.cidx = reinterpret_cast<uint16_t *>(p);  p += sizeof(uint16_t) * (e_max + (e_max & 1));
-    s.pend = reinterpret_cast<uint16_t *>(p);  p += sizeof(uint16_t) * (n_max + (n_max & 1));
     s.next_op = reinterpret_cast<uint16_t *>(p); p += sizeof(uint16_t) * (n_max + (n_max & 1));
     s.tr_op = reinterpret_cast<uint16_t *>(p); p += sizeof(uint16_t) * (e_max + (e_max & 1));
     s.tr_next = reinterpret_cast<uint16_t *>(p); p += sizeof(uint16_t) * (e_max + (e_max & 1));
-    s.place = p;                               p += n_max;
     s.tr_dst = p;
     return s;
 }
@@ -89,10 +89,10 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
     for (int v = lane; v < n; v += 64) {
         const int d = placement[n0 + v];
         bad |= d < 0 || d >= D;
-        S.place[v] = static_cast<uint8_t>(d);
         S.cost[v] = node_feats[static_cast<size_t>(n0 + v) * 3 + 0];
         S.size[v] = node_feats[static_cast<size_t>(n0 + v) * 3 + 1];
-        S.pend[v] = static_cast<uint16_t>(gv.nbr_ptr[0][n0 + v + 1] - gv.nbr_ptr[0][n0 + v]);   // number of parents
+        S.node[v] = (static_cast<uint32_t>(d) & 0xFFu) |
+                    (static_cast<uint32_t>(gv.nbr_ptr[0][n0 + v + 1] - gv.nbr_ptr[0][n0 + v]) << 8);   // number of parents
         S.next_op[v] = kNone;
     }
     for (int v = lane; v <= n; v += 64) S.cptr[v] = gptr[v] - e0;
@@ -120,10 +120,11 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
             q_tail = v;
         }
     };
-    auto enqueue_transfer = [&](int dev, int o, int dst) {
+    auto enqueue_transfer = [&](int dev, int o, int dst, float dur) {
         const int k = n_tr++;
         S.tr_op[k] = static_cast<uint16_t>(o);
         S.tr_dst[k] = static_cast<uint8_t>(dst);
+        S.tr_dur[k] = dur;
         S.tr_next[k] = kNone;
         if (lane == D + dev) {
             if (q_tail == kNone) q_head = k; else S.tr_next[q_tail] = static_cast<uint16_t>(k);
@@ -146,7 +147,7 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
                 o = S.tr_op[item];
                 dst = S.tr_dst[item];
                 q_head = S.tr_next[item];
-                dur = __fmul_rn(S.size[o], inv_bw);
+                dur = S.tr_dur[item];
             }
             if (q_head == kNone) q_tail = kNone;
             active = true;
@@ -160,11 +161,12 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
 
     for (int base = 0; base < n; base += 64) {            // operations without parents, ascending id
         const int v = base + lane;
-        unsigned long long roots = __ballot(v < n && S.pend[v < n ? v : 0] == 0);
+        const uint32_t word = S.node[v < n ? v : 0];
+        unsigned long long roots = __ballot(v < n && (word >> 8) == 0);
         while (roots != 0ull) {
-            const int r = base + __ffsll(static_cast<long long>(roots)) - 1;
+            const int l = __ffsll(static_cast<long long>(roots)) - 1;
             roots &= roots - 1;
-            enqueue_op(S.place[r], r);
+            enqueue_op(__builtin_amdgcn_readlane(static_cast<int>(word & 0xFFu), l), base + l);
         }
     }
     wake(0.0f);
@@ -186,29 +188,38 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
         const int dst = __builtin_amdgcn_readlane(ev_dst, slot);
         if (lane == slot) active = false;
         ++n_events;
-        const int c0 = S.cptr[o], c1 = S.cptr[o + 1];
-        if (slot < D) {                                   // op-done of o on device `slot`
-            last = now;
-            unsigned int sent = 0;
-            for (int i = c0; i < c1; ++i) {
-                const int c = S.cidx[i];
-                const int pc = S.place[c];
-                if (pc == slot) {
-                    const int p = S.pend[c] - 1;
-                    S.pend[c] = static_cast<uint16_t>(p);
-                    if (p == 0) enqueue_op(pc, c);
-                } else if (((sent >> pc) & 1u) == 0) {    // the output crosses once per destination
-                    sent |= 1u << pc;
-                    enqueue_transfer(slot, o, pc);
-                }
+        // ---- the children of o, one per lane: those on the device where o's output now is
+        // (its own device after op-done, the destination after transfer-done) have one input
+        // fewer to wait for; after op-done the others make the output cross, once per device.
+        // Queues are filled in ascending child id (= lane order), as a scalar loop would.
+        const int c0 = S.cptr[o], cnt = S.cptr[o + 1] - c0;
+        const bool op_done = slot < D;
+        const int here = op_done ? slot : dst;
+        const float dur = op_done ? __fmul_rn(S.size[o], inv_bw) : 0.0f;
+        if (op_done) last = now;
+        unsigned int sent = 0;
+        for (int base = 0; base < cnt; base += 64) {
+            const bool valid = base + lane < cnt;
+            const int c = valid ? S.cidx[c0 + base + lane] : 0;
+            const uint32_t word = S.node[c];
+            const int pc = static_cast<int>(word & 0xFFu);
+            const bool same = valid && pc == here;
+            const int p = static_cast<int>(word >> 8) - 1;
+            if (same) S.node[c] = word - 0x100u;
+            unsigned long long ready = __ballot(same && p == 0);
+            unsigned long long cross = op_done ? __ballot(valid && pc != here) : 0ull;
+            while (ready != 0ull) {
+                const int l = __ffsll(static_cast<long long>(ready)) - 1;
+                ready &= ready - 1;
+                enqueue_op(here, __builtin_amdgcn_readlane(c, l));
             }
-        } else {                                          // o's output has arrived on device dst
-            for (int i = c0; i < c1; ++i) {
-                const int c = S.cidx[i];
-                if (S.place[c] == dst) {
-                    const int p = S.pend[c] - 1;
-                    S.pend[c] = static_cast<uint16_t>(p);
-                    if (p == 0) enqueue_op(dst, c);
+            while (cross != 0ull) {
+                const int l = __ffsll(static_cast<long long>(cross)) - 1;
+                cross &= cross - 1;
+                const int pd = __builtin_amdgcn_readlane(pc, l);
+                if (((sent >> pd) & 1u) == 0) {           // the output crosses once per destination
+                    sent |= 1u << pd;
+                    enqueue_transfer(slot, o, pd, dur);
                 }
             }
         }
@@ -224,8 +235,9 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
 
 size_t simulator_lds_bytes(int n_max, int e_max)
 {
-    return sizeof(int32_t) * (n_max + 1) + 2 * sizeof(float) * n_max + 3 * sizeof(uint16_t) * (e_max + (e_max & 1)) +
-           2 * sizeof(uint16_t) * (n_max + (n_max & 1)) + n_max + e_max + 16;
+    return sizeof(int32_t) * (n_max + 1) + 2 * sizeof(float) * n_max + sizeof(float) * e_max +
+           3 * sizeof(uint16_t) * (e_max + (e_max & 1)) + sizeof(uint32_t) * n_max +
+           sizeof(uint16_t) * (n_max + (n_max & 1)) + e_max + 16;
 }
 
 int launch_simulate(const GraphView &gv, int D, int n_max, int e_max, const float *node_feats,
