@@ -159,3 +159,47 @@ def test_episode_segment_at_full_size():
         assert out["visited"][n0:int(w.node_off[b + 1])].sum() == n_steps
         np.testing.assert_array_equal(out["placement"][first], out["actions"][:, b])
         assert out["cur"][b] == order[n0 + n_steps]
+
+
+def test_episode_loop_replays_from_a_hip_graph():
+    """Sixteen steps of forward pass + transition captured once (with the reset of the state)
+    and replayed three times, with eager work in between: the actions equal the eager run's."""
+    import torch
+    import paper_1906_08879_amd as pl
+    dev = torch.device("cuda:0")
+    w = make_workload("layered200", B=12)
+    T = 16
+    order, uniforms, placement0 = make_episode(w, T)
+    eager = run_device_episode(w, T, order, uniforms, placement0)
+    g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+    wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+    f0 = np.array(w.node_feats, dtype=np.float32)
+    f0[:, 2] = 0.0
+    cur0 = np.array([order[w.node_off[b]] for b in range(w.B)], dtype=np.int32)
+    tf0, tp0, tc0, to, tu = (torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+                             for x in (f0, placement0, cur0, order, uniforms))
+    tf, tp, tc = tf0.clone(), tp0.clone(), tc0.clone()
+    logits = torch.empty((w.B, w.D), dtype=torch.float32, device=dev)
+    act = torch.empty((T, w.B), dtype=torch.int32, device=dev)
+    pl.embed_forward(g, tf, tp, tc, wt, logits)                     # first call allocates
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        tf.copy_(tf0); tp.copy_(tp0); tc.copy_(tc0)
+        pl.episode_run(g, wt, tf, tp, tc, to, tu, 0, T, logits, False, act, None, stream=side)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        act.fill_(77)
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(act.cpu().numpy(), eager["actions"])
+        np.testing.assert_array_equal(tp.cpu().numpy(), eager["placement"])
+        pl.embed_forward(g, tf0, tp0, tc0, wt, logits)              # eager work between the replays
+        torch.cuda.synchronize()
+    del graph
+    g.close()
+    wt.close()
