@@ -65,7 +65,7 @@ struct pl_graph_batch {
     int32_t *d_ck_off[2] = {nullptr, nullptr}, *d_ck_meta[2] = {nullptr, nullptr};
     int32_t *d_ck_far[2] = {nullptr, nullptr}, *d_ck_ovf[2] = {nullptr, nullptr};
     int32_t *d_pos[2] = {nullptr, nullptr};
-    uint16_t *d_ck_ent[2] = {nullptr, nullptr};
+    uint32_t *d_ck_ent[2] = {nullptr, nullptr};
     pl::GraphView view{};
     pl::Workspace ws;
     pl::StageTimer timer;

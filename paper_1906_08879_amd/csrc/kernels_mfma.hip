@@ -221,8 +221,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             uint32_t signs = 0;
 #pragma unroll
             for (int k = 0; k < K; ++k) {
-                const int j = k + 1;
-                const int slot = (j & 1) ? static_cast<int>(rec[j >> 1] >> 16) : static_cast<int>(rec[j >> 1] & 0xFFFF);
+                const int slot = static_cast<int>((rec[k / 5] >> (6 * (k % 5))) & 63u);
                 const float *row = msgtab + slot * LDM;
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
@@ -245,15 +244,14 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             bit[ct] = 0;
             if (ct >= ntile_x) continue;
             const u32x4 rec = ent[ct];
-            const bool listed = (rec[0] & 0xFFFF) == 0xFFFF;
+            const bool listed = ((rec[0] >> 30) & 1u) != 0;
             float s[TPW];
             uint32_t signs = 0;
 #pragma unroll
             for (int t = 0; t < TPW; ++t) s[t] = 0.0f;
 #pragma unroll
             for (int k = 0; k < kMaxEnt; ++k) {
-                const int j = k + 1;
-                const int raw = (j & 1) ? static_cast<int>(rec[j >> 1] >> 16) : static_cast<int>(rec[j >> 1] & 0xFFFF);
+                const int raw = static_cast<int>((rec[k / 5] >> (6 * (k % 5))) & 63u);
                 const float *row = msgtab + (listed ? kZeroSlot : raw) * LDM;
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
@@ -263,8 +261,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 }
             }
             if (listed) {
-                const int d0 = static_cast<int>(rec[0] >> 16) | (static_cast<int>(rec[1] & 0xFFFF) << 16);
-                const int d1 = d0 + (static_cast<int>(rec[1] >> 16) | (static_cast<int>(rec[2] & 0xFFFF) << 16));
+                const int d0 = static_cast<int>(rec[1]);
+                const int d1 = d0 + static_cast<int>(rec[2]);
                 // LB list entries at a time, every load issued before the first use: an entry
                 // is a table slot or a node id; the other source of the pair is the table's zero
                 // row or the spare (all-zero, never written) row of msg, so both are always read
@@ -307,6 +305,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     auto gather = [&](int w, int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT]) {
         if (w <= 2)
             gather_fixed(std::integral_constant<int, 2>{}, ntile_x, ent, bit);
+        else if (w <= 5)
+            gather_fixed(std::integral_constant<int, 5>{}, ntile_x, ent, bit);
         else if (w <= kMaxEnt)
             gather_fixed(std::integral_constant<int, kMaxEnt>{}, ntile_x, ent, bit);
         else

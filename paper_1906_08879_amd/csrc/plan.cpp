@@ -15,6 +15,8 @@
 
 namespace pl {
 
+static_assert(kMsgSlots < 64 && kMaxEnt <= 20, "table slots are stored in six bits, twenty per record");
+
 int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
 {
     SweepPlanHost &P = *out;
@@ -46,11 +48,11 @@ int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
         }
         const int32_t n_chunks = static_cast<int32_t>(P.meta.size() / 4) - first;
         P.ck_off[b + 1] = first + n_chunks;
-        // every record starts as "no neighbours": count 0, all entries the table's zero row
+        // every record starts as "no neighbours": all twenty entries the table's zero row
         {
-            const size_t old = P.ent.size();
-            P.ent.resize(static_cast<size_t>(first + n_chunks) * kChunkRows * 8, static_cast<uint16_t>(kMsgSlots));
-            for (size_t i = old; i < P.ent.size(); i += 8) P.ent[i] = 0;
+            uint32_t empty = 0;
+            for (int i = 0; i < 5; ++i) empty |= static_cast<uint32_t>(kMsgSlots) << (6 * i);
+            P.ent.resize(static_cast<size_t>(first + n_chunks) * kChunkRows * 4, empty);
         }
         P.far.resize(static_cast<size_t>(first + n_chunks) * kFarCap, -1);
         // pass 2: neighbour slots
@@ -60,7 +62,7 @@ int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
             int32_t n_far = 0, max_ent = 0, has_ovf = 0;
             const int32_t p0 = meta[0] - static_cast<int32_t>(n0);
             for (int32_t r = 0; r < meta[1]; ++r) {
-                uint16_t *ent = &P.ent[(static_cast<size_t>(first + c) * kChunkRows + r) * 8];
+                uint32_t *ent = &P.ent[(static_cast<size_t>(first + c) * kChunkRows + r) * 4];
                 const int32_t v = order[n0 + p0 + r];
                 const int64_t e0 = ptr[n0 + v], e1 = ptr[n0 + v + 1];
                 const int32_t deg = static_cast<int32_t>(e1 - e0);
@@ -78,11 +80,9 @@ int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
                 if (direct) {            // the row's list goes to the overflow array
                     const uint32_t off = static_cast<uint32_t>(P.ovf.size());
                     has_ovf = 1;
-                    ent[0] = 0xFFFF;
-                    ent[1] = static_cast<uint16_t>(off & 0xFFFF);
-                    ent[2] = static_cast<uint16_t>(off >> 16);
-                    ent[3] = static_cast<uint16_t>(deg & 0xFFFF);
-                    ent[4] = static_cast<uint16_t>(deg >> 16);
+                    ent[0] |= 1u << 30;
+                    ent[1] = off;
+                    ent[2] = static_cast<uint32_t>(deg);
                     for (int64_t e = e0; e < e1; ++e) {
                         const int32_t u = idx[e];
                         if (c - node_chunk[u] <= kRing)
@@ -92,7 +92,6 @@ int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
                     }
                     continue;
                 }
-                ent[0] = static_cast<uint16_t>(deg);
                 max_ent = std::max(max_ent, deg);
                 for (int64_t e = e0; e < e1; ++e) {
                     const int32_t u = idx[e];
@@ -105,7 +104,8 @@ int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
                         if (f == n_far) far[n_far++] = gu;
                         slot = kRing * kChunkRows + (c % 2) * kFarCap + f;
                     }
-                    ent[1 + (e - e0)] = static_cast<uint16_t>(slot);
+                    const int k = static_cast<int>(e - e0);
+                    ent[k / 5] = (ent[k / 5] & ~(63u << (6 * (k % 5)))) | (static_cast<uint32_t>(slot) << (6 * (k % 5)));
                 }
             }
             meta[2] = n_far;
