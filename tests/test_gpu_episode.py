@@ -203,3 +203,28 @@ def test_episode_loop_replays_from_a_hip_graph():
     del graph
     g.close()
     wt.close()
+
+
+def test_ragged_batch_graphs_finish_at_different_steps():
+    """Graphs of 3, 11 and 26 nodes in one batch: each episode ends after its own |V| steps and
+    is left untouched afterwards, while the others go on."""
+    from workloads import tiny_random_dag, weight_count
+    from workloads.synthetic import Workload
+    rng = np.random.default_rng(21)
+    sizes, D, H = [3, 11, 26], 3, 32
+    n_nodes, n_edges, srcs, dsts, feats = [], [], [], [], []
+    for n in sizes:
+        s, d = tiny_random_dag(rng, n, 0.3)
+        n_nodes.append(n); n_edges.append(len(s)); srcs.append(s); dsts.append(d)
+        feats.append(np.stack([rng.lognormal(0, 1, n), rng.lognormal(2, 1, n), np.zeros(n)], axis=1))
+    w = Workload(name="ragged", B=len(sizes), D=D, H=H, n_layers=2, k_sweeps=1, group_by_device=1, weight_dtype="fp32",
+                 n_nodes=np.array(n_nodes, np.int32), n_edges=np.array(n_edges, np.int32),
+                 edge_src=np.concatenate(srcs).astype(np.int32), edge_dst=np.concatenate(dsts).astype(np.int32),
+                 node_feats=np.concatenate(feats).astype(np.float32), placement=np.zeros(sum(sizes), np.int32),
+                 cur_node=np.zeros(len(sizes), np.int32),
+                 weights=rng.normal(0, 0.1, weight_count(D, H, 2, True)).astype(np.float32))
+    n_steps = max(sizes) + 1
+    order, uniforms, placement0 = make_episode(w, n_steps)
+    out = run_device_episode(w, n_steps, order, uniforms, placement0)
+    for b in range(w.B):
+        check_against_replay(w, b, n_steps, order, uniforms, placement0, out, complete=True)
