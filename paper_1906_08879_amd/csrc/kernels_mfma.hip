@@ -263,19 +263,61 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             if (listed) {
                 const int d0 = static_cast<int>(rec[1]);
                 const int d1 = d0 + static_cast<int>(rec[2]);
-                // LB list entries at a time, every load issued before the first use: an entry
-                // is a table slot or a node id; the other source of the pair is the table's zero
-                // row or the spare (all-zero, never written) row of msg, so both are always read
-                // and added, in list order.
-                constexpr int LB = TPW > 1 ? 4 : 8;
-                for (int p = d0; p < d1; p += LB) {
-                    int u[LB];
+                // The list is walked in passes of PB entries, three passes per step.  The sixteen
+                // lanes of the row's group first load the step's entries (one load each per
+                // pass, all in flight together) and hand them round with lane shuffles; then a
+                // pass issues all its loads before the first use.  An entry is a table slot or a
+                // node id; the other source of the pair is the table's zero row or the spare
+                // (all-zero, never written) row of msg, so both are always read and added, in
+                // list order.
+                constexpr int PB = 16;
+                if constexpr (TPW == 1)
+                for (int p0 = d0; p0 < d1; p0 += 3 * PB) {
+                    int idv[3];
 #pragma unroll
-                    for (int k = 0; k < LB; ++k) u[k] = p + k < d1 ? plan.ovf[p + k] : -1 - kZeroSlot;
-                    float xl[LB][TPW], xg[LB][TPW];
-                    int rg[LB];
+                    for (int q = 0; q < 3; ++q) {
+                        const int at = p0 + q * PB + (col % PB);
+                        idv[q] = (at < d1) ? plan.ovf[at] : -1 - kZeroSlot;
+                    }
 #pragma unroll
-                    for (int k = 0; k < LB; ++k) {
+                    for (int q = 0; q < 3; ++q) {
+                        if (p0 + q * PB >= d1) break;
+                        int u[PB];
+                        float xl[PB][TPW], xg[PB][TPW];
+                        int rg[PB];
+#pragma unroll
+                        for (int k = 0; k < PB; ++k) {
+                            u[k] = __shfl(idv[q], (lane & 48) + k);
+                            const float *row = msgtab + (u[k] < 0 ? -1 - u[k] : kZeroSlot) * LDM;
+                            const int v = u[k] >= 0 ? u[k] : spare_row;
+#pragma unroll
+                            for (int t = 0; t < TPW; ++t) {
+                                xl[k][t] = row[wc0 + 16 * t + col];
+                                xg[k][t] = msg[static_cast<uint32_t>(v * H + wc0 + 16 * t + col)];
+                            }
+                            rg[k] = reach[static_cast<uint32_t>(v)];
+                        }
+#pragma unroll
+                        for (int k = 0; k < PB; ++k) {
+#pragma unroll
+                            for (int t = 0; t < TPW; ++t) {
+                                s[t] += fabsf(xl[k][t]) + xg[k][t];
+                                signs |= __float_as_uint(xl[k][t]);
+                            }
+                            signs |= ((u[k] >= 0) & ((u[k] == cur) | (rg[k] != 0))) ? 0x80000000u : 0u;
+                        }
+                    }
+                }
+                // two column tiles per wave leave no registers for that: four entries at a time
+                if constexpr (TPW > 1)
+                for (int p = d0; p < d1; p += 4) {
+                    int u[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) u[k] = p + k < d1 ? plan.ovf[p + k] : -1 - kZeroSlot;
+                    float xl[4][TPW], xg[4][TPW];
+                    int rg[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
                         const float *row = msgtab + (u[k] < 0 ? -1 - u[k] : kZeroSlot) * LDM;
                         const int v = u[k] >= 0 ? u[k] : spare_row;
 #pragma unroll
@@ -286,7 +328,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         rg[k] = reach[static_cast<uint32_t>(v)];
                     }
 #pragma unroll
-                    for (int k = 0; k < LB; ++k) {
+                    for (int k = 0; k < 4; ++k) {
 #pragma unroll
                         for (int t = 0; t < TPW; ++t) {
                             s[t] += fabsf(xl[k][t]) + xg[k][t];
