@@ -174,6 +174,31 @@ int pl_episode_run(pl_graph_batch *g, const pl_weights *w, float *node_feats, in
                    int32_t n_steps, float *logits, int32_t keep_logits, int32_t *out_actions,
                    float *out_logp, void *stream);
 
+/* ---- the policy gradient of one batch of decisions (appendix "REINFORCE Algorithm", Eq. 1:
+ * theta <- theta + eta * sum_i grad_theta log pi_theta(a_i | s_i) * (sum_{i' >= i} r_i' - b_i)).
+ * For the B states given as in pl_embed_forward, with the action taken in each and one scalar
+ * per state (the caller's return-minus-baseline), computes
+ *     grad (+)= sum_b coeff[b] * d/d theta log softmax(logits_theta(s_b))[actions[b]]
+ * by a forward pass followed by a reverse pass through the policy head, the pooling, the two
+ * message-passing directions (levels in reverse order) and the input projection.
+ *   actions     dev [B] int32   device chosen for the current node, in [0, D)
+ *   coeff       dev [B] fp32    scalar multiplying the state's gradient
+ *   accumulate                  0: grad is overwritten; else the sum is added to it (the sum
+ *                               over the steps of an episode is built by successive calls)
+ *   grad        dev [pl_weights_count] fp32, laid out like the parameter blob (with
+ *                               PL_WEIGHTS_BF16 the derivative is taken at the rounded weights)
+ *   out_logits  dev [B, D] fp32 logits of the forward pass (required)
+ *   out_logp    dev [B] fp32    log pi(a_b | s_b); NULL to skip
+ * A graph whose cur_node or action is out of range adds nothing and gets out_logp = NaN.
+ * ReLU's derivative at 0 is taken as 0.  Covers k_sweeps <= 1 (PL_ERR_SHAPE otherwise).  The
+ * first call on a batch allocates the buffers of the reverse pass (about (10 n_layers + 7)
+ * x N_tot x H floats); later calls only launch kernels.  Asynchronous on `stream`; summation
+ * orders are fixed, so equal inputs give bit-equal gradients. */
+int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                       const int32_t *cur_node, const pl_weights *w, const int32_t *actions,
+                       const float *coeff, int32_t accumulate, float *grad, float *out_logits,
+                       float *out_logp, void *stream);
+
 /* ---- run time of a placement from the event-driven simulator of the paper's appendix
  * ("Simulator"), for every graph of the batch: per device a FIFO queue of runnable operations
  * and a FIFO queue of outgoing tensors, one operation per device and one transfer per bus at a

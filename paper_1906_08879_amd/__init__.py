@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     node_classes,
+    policy_gradient,
     simulate_runtime,
     weights_count,
 )

@@ -65,6 +65,7 @@ def load_library(path: Optional[str] = None):
                                            vp, vp, vp]),
         "pl_episode_run": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
                                           vp, ctypes.c_int32, vp, vp, vp]),
+        "pl_policy_gradient": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp, vp]),
         "pl_simulate_runtime": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, ctypes.c_float, vp, vp, vp]),
         "pl_profile_enable": (ctypes.c_int, [vp, ctypes.c_int32]),
         "pl_profile_read": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_double), i64p,
@@ -287,3 +288,20 @@ def simulate_runtime(g: GraphBatch, D: int, node_feats, placement, inv_bandwidth
         _dev_ptr(out_runtime, torch.float32, g.B, "out_runtime"),
         _dev_ptr(out_events, torch.int32, g.B, "out_events"), _stream_ptr(stream)), "pl_simulate_runtime")
     return out_runtime
+
+
+def policy_gradient(g: GraphBatch, node_feats, placement, cur_node, w: Weights, actions, coeff, grad,
+                    out_logits, out_logp=None, accumulate: bool = False, stream=None):
+    """pl_policy_gradient on device tensors: grad (+)= sum_b coeff[b] * d log pi(a_b | s_b) / d theta."""
+    import torch
+    lib = load_library()
+    n_par = int(lib.pl_weights_count(ctypes.byref(w.cfg)))
+    _check(lib.pl_policy_gradient(
+        g._h, _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
+        _dev_ptr(placement, torch.int32, g.n_tot, "placement"),
+        _dev_ptr(cur_node, torch.int32, g.B, "cur_node"), w._h,
+        _dev_ptr(actions, torch.int32, g.B, "actions"), _dev_ptr(coeff, torch.float32, g.B, "coeff"),
+        1 if accumulate else 0, _dev_ptr(grad, torch.float32, n_par, "grad"),
+        _dev_ptr(out_logits, torch.float32, g.B * w.D, "out_logits"),
+        _dev_ptr(out_logp, torch.float32, g.B, "out_logp"), _stream_ptr(stream)), "pl_policy_gradient")
+    return grad

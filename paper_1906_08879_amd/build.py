@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libplaceto.so")
-SOURCES = ["api.hip", "kernels_generic.hip", "kernels_mfma.hip", "kernels_pool_mfma.hip", "kernels_episode.hip", "kernels_simulator.hip", "layout.cpp", "plan.cpp"]
+SOURCES = ["api.hip", "kernels_generic.hip", "kernels_mfma.hip", "kernels_pool_mfma.hip", "kernels_episode.hip", "kernels_simulator.hip", "kernels_backward.hip", "layout.cpp", "plan.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -68,6 +68,7 @@ struct pl_graph_batch {
     uint32_t *d_ck_ent[2] = {nullptr, nullptr};
     pl::GraphView view{};
     pl::Workspace ws;
+    pl::GradWorkspace gw;
     pl::StageTimer timer;
 };
 
@@ -75,6 +76,7 @@ struct pl_weights {
     pl_model_cfg cfg{};
     pl::ModelView view{};
     float *d_blob = nullptr;
+    float *d_blob_t = nullptr;      // same offsets, every matrix transposed to [out, in] (gradient pass)
     std::vector<float> host_blob;   // values as stored (bf16-rounded when asked)
     // matrix-core sweep: packed A fragments and biases (null when the shape is not covered)
     uint16_t *d_wfrag = nullptr;
@@ -235,6 +237,15 @@ void free_workspace(Workspace &ws)
     ws = Workspace();
 }
 
+void free_grad_workspace(GradWorkspace &gw)
+{
+    float *all[] = {gw.fact, gw.gact, gw.agg, gw.dagg, gw.df, gw.dg, gw.lact, gw.dl, gw.demb, gw.dx, gw.phi,
+                    gw.pooled, gw.dP, gw.hin, gw.hact, gw.dh, gw.dz, gw.hid, gw.dpre, gw.dlogit, gw.partial};
+    for (float *p : all) (void)hipFree(p);
+    (void)hipFree(gw.cls);
+    gw = GradWorkspace();
+}
+
 int ensure_reach(pl_graph_batch *g)
 {
     if (g->ws.reach) return PL_OK;
@@ -272,6 +283,50 @@ int ensure_workspace(pl_graph_batch *g, const ModelView &mv)
                      sizeof(float) * (static_cast<size_t>((mv.Z + 255) / 256) * B * H + 4)));
     ws.H = mv.H;
     ws.G = mv.G;
+    return PL_OK;
+}
+
+int ensure_grad_workspace(pl_graph_batch *g, const ModelView &mv)
+{
+    GradWorkspace &gw = g->gw;
+    if (gw.demb && gw.H == mv.H && gw.G == mv.G && gw.L == mv.L && gw.D == mv.D) return PL_OK;
+    free_grad_workspace(gw);
+    const size_t n = static_cast<size_t>(g->host.n_tot), H = mv.H, L = mv.L, B = g->host.B;
+    const size_t NH = n * H, BG = B * mv.G;
+    auto take = [](float **p, size_t floats) {
+        return hipMalloc(reinterpret_cast<void **>(p), sizeof(float) * (floats + 4));
+    };
+    PL_HIP(take(&gw.fact, 2 * L * NH));
+    PL_HIP(take(&gw.gact, 2 * L * NH));
+    PL_HIP(take(&gw.agg, 2 * NH));
+    PL_HIP(take(&gw.dagg, 2 * NH));
+    PL_HIP(take(&gw.df, 2 * L * NH));
+    PL_HIP(take(&gw.dg, 2 * L * NH));
+    PL_HIP(take(&gw.lact, L * NH));
+    PL_HIP(take(&gw.dl, L * NH));
+    PL_HIP(take(&gw.demb, 2 * NH));
+    PL_HIP(take(&gw.dx, NH));
+    PL_HIP(take(&gw.phi, n * mv.F));
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.cls), n + 16));
+    PL_HIP(take(&gw.pooled, 3 * BG * H));
+    PL_HIP(take(&gw.dP, 3 * BG * H));
+    PL_HIP(take(&gw.hin, 3 * BG * H));
+    PL_HIP(take(&gw.hact, 3 * L * BG * H));
+    PL_HIP(take(&gw.dh, 3 * L * BG * H));
+    PL_HIP(take(&gw.dz, B * mv.Z));
+    PL_HIP(take(&gw.hid, B * H));
+    PL_HIP(take(&gw.dpre, B * H));
+    PL_HIP(take(&gw.dlogit, B * mv.D));
+    size_t part = wgrad_partial_floats(static_cast<int64_t>(n), 2 * mv.H, mv.H);
+    part = std::max(part, wgrad_partial_floats(static_cast<int64_t>(n), mv.F, mv.H));
+    part = std::max(part, wgrad_partial_floats(static_cast<int64_t>(BG), mv.H, mv.H));
+    part = std::max(part, wgrad_partial_floats(static_cast<int64_t>(B), mv.Z, mv.H));
+    part = std::max(part, wgrad_partial_floats(static_cast<int64_t>(B), mv.H, mv.D));
+    PL_HIP(take(&gw.partial, part));
+    gw.H = mv.H;
+    gw.G = mv.G;
+    gw.L = mv.L;
+    gw.D = mv.D;
     return PL_OK;
 }
 
@@ -408,6 +463,7 @@ int pl_graph_batch_destroy(pl_graph_batch *g)
         }
     }
     free_workspace(g->ws);
+    free_grad_workspace(g->gw);
     for (auto &v : g->timer.ev)
         for (hipEvent_t e : v) (void)hipEventDestroy(e);
     delete g;
@@ -512,6 +568,32 @@ int pl_weights_create(const pl_model_cfg *cfg, const float *host_blob, size_t n_
         return rc;
     }
     w->view.blob = w->d_blob;
+    {
+        std::vector<float> t(w->host_blob);
+        auto flip = [&](const LayerRef &r) {
+            for (int i = 0; i < r.n_in; ++i)
+                for (int j = 0; j < r.n_out; ++j)
+                    t[r.w + static_cast<size_t>(j) * r.n_in + i] = w->host_blob[r.w + static_cast<size_t>(i) * r.n_out + j];
+        };
+        const ModelView &m = w->view;
+        flip(m.proj);
+        for (int l = 0; l < m.L; ++l) {
+            for (int d = 0; d < 2; ++d) {
+                flip(m.f[d].layer[l]);
+                flip(m.g[d].layer[l]);
+            }
+            for (int i = 0; i < 3; ++i) {
+                flip(m.l[i].layer[l]);
+                flip(m.h[i].layer[l]);
+            }
+        }
+        flip(m.pol1);
+        flip(m.pol2);
+        if ((rc = upload(t, &w->d_blob_t))) {
+            pl_weights_destroy(w);
+            return rc;
+        }
+    }
     if (sweep_mfma_supported(cfg->H, cfg->n_layers, cfg->weight_dtype)) {
         std::vector<uint16_t> frag;
         std::vector<float> sweep_bias;
@@ -548,6 +630,7 @@ int pl_weights_destroy(pl_weights *w)
 {
     if (!w) return PL_OK;
     (void)hipFree(w->d_blob);
+    (void)hipFree(w->d_blob_t);
     (void)hipFree(w->d_wfrag);
     (void)hipFree(w->d_sweep_bias);
     (void)hipFree(w->d_pool_frag);
@@ -608,6 +691,33 @@ int pl_episode_run(pl_graph_batch *g, const pl_weights *w, float *node_feats, in
                             out_logp ? out_logp + static_cast<size_t>(i) * B : nullptr,
                             static_cast<hipStream_t>(stream));
     }
+    PL_HIP(hipGetLastError());
+    return PL_OK;
+}
+
+int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                       const int32_t *cur_node, const pl_weights *w, const int32_t *actions,
+                       const float *coeff, int32_t accumulate, float *grad, float *out_logits,
+                       float *out_logp, void *stream)
+{
+    if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
+    if (w->cfg.k_sweeps > 1)
+        return fail(PL_ERR_SHAPE, "the gradient pass covers k_sweeps <= 1 (later sweeps overwrite the states "
+                                  "that the earlier ones would need)");
+    if (g->host.B == 0) return PL_OK;
+    if (!node_feats || !placement || !cur_node || !actions || !coeff || !grad || !out_logits)
+        return fail(PL_ERR_NULL, "a required device array is NULL");
+    int rc = ensure_on_device(g);
+    if (rc) return rc;
+    const ModelView &mv = w->view;
+    if ((rc = ensure_grad_workspace(g, mv))) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rc = forward_impl(g, node_feats, placement, cur_node, w, out_logits, nullptr, nullptr, g->gw.pooled, stream);
+    if (rc) return rc;
+    if (!accumulate) launch_fill_zero(grad, plan_weights(w->cfg, nullptr), s);
+    ForwardArgs fa{node_feats, placement, cur_node, out_logits, nullptr, g->gw.pooled};
+    launch_backward_generic(g->view, mv, w->d_blob_t, g->ws, g->gw, fa, actions, coeff, w->cfg.k_sweeps,
+                            g->ws.n_chunks, grad, out_logp, s);
     PL_HIP(hipGetLastError());
     return PL_OK;
 }

@@ -179,6 +179,33 @@ void launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace 
                       const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
                       hipStream_t s);
 
+// ---- policy gradient (kernels_backward.hip): buffers owned by a batch for one (D, H, L)
+struct GradWorkspace {
+    float *fact = nullptr, *gact = nullptr;   // [2, L, n_tot, H] layer outputs of f and g
+    float *agg = nullptr, *dagg = nullptr;    // [2, n_tot, H] gathered sums and their gradients
+    float *df = nullptr, *dg = nullptr;       // [2, L, n_tot, H] layer deltas of f and g
+    float *lact = nullptr, *dl = nullptr;     // [L, n_tot, H] layer outputs / deltas of l (own set)
+    float *demb = nullptr;                    // [n_tot, 2H] gradient of the embeddings
+    float *dx = nullptr;                      // [n_tot, H] delta of the projection
+    float *phi = nullptr;                     // [n_tot, F] raw feature rows
+    uint8_t *cls = nullptr;                   // [n_tot] node set of every node
+    float *pooled = nullptr, *dP = nullptr;   // [B, 3, G, H]
+    float *hin = nullptr;                     // [3, B G, H] inputs of h per set
+    float *hact = nullptr, *dh = nullptr;     // [3, L, B G, H]
+    float *dz = nullptr;                      // [B, Z]
+    float *hid = nullptr, *dpre = nullptr;    // [B, H] policy hidden layer and its delta
+    float *dlogit = nullptr;                  // [B, D]
+    float *partial = nullptr;                 // slab sums of the weight-gradient contraction
+    int32_t H = 0, G = 0, L = 0, D = 0;
+};
+
+size_t wgrad_partial_floats(int64_t R, int I, int J);
+void launch_fill_zero(float *p, size_t n, hipStream_t s);
+void launch_backward_generic(const GraphView &gv, const ModelView &mv, const float *blob_t,
+                             const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
+                             const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
+                             float *grad, float *out_logp, hipStream_t s);
+
 // ---- matrix-core sweep (kernels_mfma.hip)
 bool sweep_mfma_supported(int H, int L, int weight_dtype);
 void pack_sweep_weights(const ModelView &mv, const float *blob, int WS, std::vector<uint16_t> *frag,

@@ -1,0 +1,813 @@
+// Reverse-mode pass of the policy network: the gradient of log pi(a | s) with respect to every
+// parameter, summed over a batch with one scalar per state.  This is the term
+// grad_theta log pi_theta(a_i | s_i) * (return - baseline) of the REINFORCE update (appendix
+// "REINFORCE Algorithm", Eq. 1) for the network of Section 2.2 / Appendix A.7.
+//
+// The forward pass leaves the node embeddings e_v = [td_v ; bu_v], the pooled sums and the
+// policy inputs in the batch's buffers.  From them:
+//   1. head:   d logits = c (one-hot(a) - pi); back through the policy layers and h_i to the
+//              pooled sums P[i][d] and to e_{v*};
+//   2. pool:   every node u of set i on device d receives dP[i][d]; back through l_i to e_u;
+//   3. sweeps: activations of f and g are recomputed for all nodes at once (they depend only
+//              on the final states), then one workgroup per (graph, direction) walks the levels
+//              in REVERSE order: a node's state gradient needs the gradients of all the sums it
+//              was gathered into, which belong to later levels;
+//   4. projection: both directions start from x_v, so its gradient is the sum of the two;
+//   5. every weight gradient is a contraction over rows (nodes, pooled groups or graphs) of
+//              layer input x layer delta, done by one kernel in slabs with a fixed summation
+//              order (no atomics).
+// All arithmetic is fp32 vector FMAs; any H <= 256, D <= 16, 1..4 layers, k <= 1 sweeps.
+#include "internal.h"
+
+namespace pl {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTile = 16;      // rows pushed through a layer together
+constexpr int kWgI = 16;       // weight-matrix rows per workgroup of the contraction kernel
+constexpr int kWgRB = 32;      // contraction rows staged at a time
+constexpr int kPoolSub = 256;  // nodes classified at a time
+
+// y[r][j] = bias[j] + sum_k x[r][k] * W[k * ldw + j] for r < rows (<= kTile), j < n_out, optional
+// ReLU.  x and y in LDS.  Thread (grp, j) owns rows grp, grp + groups, ...  Requires
+// n_out <= kThreads and min(kThreads / n_out, kTile) * RPT >= kTile.  bias may be null.
+template <int RPT>
+__device__ __forceinline__ void dense_rows(const float *__restrict__ W, int ldw,
+                                           const float *__restrict__ bias, int n_in, int n_out,
+                                           const float *x, int ldx, float *y, int ldy, int rows,
+                                           bool relu)
+{
+    const int tid = threadIdx.x;
+    int groups = kThreads / n_out;
+    if (groups > kTile) groups = kTile;
+    const int grp = tid / n_out, j = tid - grp * n_out;
+    if (grp >= groups || grp >= rows) return;
+    float acc[RPT];
+    const float bj = bias ? bias[j] : 0.0f;
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) acc[i] = bj;
+    int xoff[RPT];
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) xoff[i] = min(grp + i * groups, rows - 1) * ldx;
+    constexpr int KB = 16;
+    int k = 0;
+    for (; k + KB <= n_in; k += KB) {
+        float w[KB];
+#pragma unroll
+        for (int u = 0; u < KB; ++u) w[u] = W[static_cast<size_t>(k + u) * ldw + j];
+#pragma unroll
+        for (int u = 0; u < KB; ++u)
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) acc[i] = fmaf(x[xoff[i] + k + u], w[u], acc[i]);
+    }
+    for (; k < n_in; ++k) {
+        const float w = W[static_cast<size_t>(k) * ldw + j];
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) acc[i] = fmaf(x[xoff[i] + k], w, acc[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        const int r = grp + i * groups;
+        if (r < rows) y[r * ldy + j] = relu ? fmaxf(acc[i], 0.0f) : acc[i];
+    }
+}
+
+// Position of activation / delta array (dir, layer) inside a [2][L][n_tot][H] buffer.
+__device__ __forceinline__ size_t slab(int dir, int l, int L, int n_tot, int H)
+{
+    return (static_cast<size_t>(dir) * L + l) * static_cast<size_t>(n_tot) * H;
+}
+
+// ------------------------------------------------------------------ 1. policy head
+// One workgroup per graph: logits again from the stored partial products of policy layer 1,
+// d logits = c (one-hot(a) - softmax), back to the hidden layer and to the policy input z.
+// A graph whose current node or action is out of range gets a zero gradient and logp = NaN.
+__global__ __launch_bounds__(kThreads) void k_bw_head(GraphView gv, ModelView mv,
+                                                      const float *__restrict__ blob_t,
+                                                      const float *__restrict__ hidp, int n_slices,
+                                                      const int32_t *__restrict__ cur_node,
+                                                      const int32_t *__restrict__ actions,
+                                                      const float *__restrict__ coeff,
+                                                      float *__restrict__ hid_out,
+                                                      float *__restrict__ dpre_out,
+                                                      float *__restrict__ dlogit_out,
+                                                      float *__restrict__ dz,
+                                                      float *__restrict__ out_logp)
+{
+    __shared__ float hid[kMaxH];
+    __shared__ float dpre[kMaxH];
+    __shared__ float logit[kMaxD];
+    __shared__ float dlog[kMaxD];
+    const int H = mv.H, D = mv.D, Z = mv.Z, b = blockIdx.x, tid = threadIdx.x;
+    const int n_b = gv.node_off[b + 1] - gv.node_off[b];
+    const int cl = cur_node[b];
+    const bool cur_ok = cl >= 0 && cl < n_b;
+    for (int j = tid; j < H; j += kThreads) {
+        float s = mv.blob[mv.pol1.b + j];
+        for (int sl = 0; sl < n_slices; ++sl) s += hidp[(static_cast<size_t>(sl) * gv.B + b) * H + j];
+        hid[j] = fmaxf(s, 0.0f);
+    }
+    __syncthreads();
+    if (tid < D) {
+        const float *W = mv.blob + mv.pol2.w;
+        float s = mv.blob[mv.pol2.b + tid];
+        for (int k = 0; k < H; ++k) s = fmaf(hid[k], W[k * D + tid], s);
+        logit[tid] = s;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float mx = logit[0];
+        for (int d = 1; d < D; ++d) mx = fmaxf(mx, logit[d]);
+        float tot = 0.0f;
+        for (int d = 0; d < D; ++d) tot += expf(logit[d] - mx);
+        const int a = actions[b];
+        const bool ok = cur_ok && a >= 0 && a < D;
+        const float c = ok ? coeff[b] : 0.0f;
+        for (int d = 0; d < D; ++d) {
+            const float p = expf(logit[d] - mx) / tot;
+            dlog[d] = c * ((d == a ? 1.0f : 0.0f) - p);
+        }
+        if (out_logp) out_logp[b] = ok ? (logit[a] - mx) - logf(tot) : __builtin_nanf("");
+    }
+    __syncthreads();
+    for (int j = tid; j < H; j += kThreads) {
+        const float *W = mv.blob + mv.pol2.w + static_cast<size_t>(j) * D;
+        float s = 0.0f;
+        for (int d = 0; d < D; ++d) s = fmaf(W[d], dlog[d], s);
+        const float dp = hid[j] > 0.0f ? s : 0.0f;
+        dpre[j] = dp;
+        hid_out[static_cast<size_t>(b) * H + j] = hid[j];
+        dpre_out[static_cast<size_t>(b) * H + j] = dp;
+    }
+    if (tid < D) dlogit_out[static_cast<size_t>(b) * D + tid] = dlog[tid];
+    __syncthreads();
+    const float *W1t = blob_t + mv.pol1.w;   // [H][Z]
+    for (int k = tid; k < Z; k += kThreads) {
+        float s = 0.0f;
+        for (int j = 0; j < H; ++j) s = fmaf(W1t[static_cast<size_t>(j) * Z + k], dpre[j], s);
+        dz[static_cast<size_t>(b) * Z + k] = s;
+    }
+}
+
+// Workgroup (set, graph): q[set][d] = h_set(P[set][d]) again for the G device groups, keeping
+// every layer's output, then back from dz to dP[set][d].
+template <int RPT>
+__global__ __launch_bounds__(kThreads) void k_bw_head_sets(GraphView gv, ModelView mv,
+                                                           const float *__restrict__ blob_t,
+                                                           const float *__restrict__ pooled,
+                                                           const float *__restrict__ dz,
+                                                           float *__restrict__ hin,
+                                                           float *__restrict__ hact,
+                                                           float *__restrict__ dh,
+                                                           float *__restrict__ dP)
+{
+    extern __shared__ float lds[];
+    const int H = mv.H, G = mv.G, L = mv.L, Z = mv.Z;
+    const int set = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const size_t BG = static_cast<size_t>(gv.B) * G;
+    float *buf_p = lds, *buf_a = lds + kTile * H, *buf_b = buf_a + kTile * H;
+    const float *src = pooled + (static_cast<size_t>(b) * 3 + set) * G * H;
+    for (int i = tid; i < G * H; i += kThreads) {
+        const float v = src[i];
+        buf_p[i] = v;
+        hin[(static_cast<size_t>(set) * BG + static_cast<size_t>(b) * G) * H + i] = v;
+    }
+    __syncthreads();
+    const MlpRef &hn = mv.h[set];
+    const float *in = buf_p;
+    for (int l = 0; l < L; ++l) {
+        float *out = (l & 1) ? buf_b : buf_a;
+        dense_rows<RPT>(mv.blob + hn.layer[l].w, H, mv.blob + hn.layer[l].b, H, H, in, H, out, H, G, true);
+        __syncthreads();
+        float *dst = hact + ((static_cast<size_t>(set) * L + l) * BG + static_cast<size_t>(b) * G) * H;
+        for (int i = tid; i < G * H; i += kThreads) dst[i] = out[i];
+        in = out;
+    }
+    __threadfence_block();
+    __syncthreads();
+    // delta of the last layer: dz of this set's slots, masked by the layer's output
+    float *dcur = buf_a, *dnext = buf_b;
+    {
+        const float *act = hact + ((static_cast<size_t>(set) * L + (L - 1)) * BG + static_cast<size_t>(b) * G) * H;
+        const float *g = dz + static_cast<size_t>(b) * Z + static_cast<size_t>(2 + set * G) * H;
+        for (int i = tid; i < G * H; i += kThreads) dcur[i] = act[i] > 0.0f ? g[i] : 0.0f;
+    }
+    __syncthreads();
+    for (int l = L - 1; l >= 0; --l) {
+        float *dst = dh + ((static_cast<size_t>(set) * L + l) * BG + static_cast<size_t>(b) * G) * H;
+        for (int i = tid; i < G * H; i += kThreads) dst[i] = dcur[i];
+        dense_rows<RPT>(blob_t + hn.layer[l].w, H, nullptr, H, H, dcur, H, dnext, H, G, false);
+        __syncthreads();
+        if (l > 0) {
+            const float *act = hact + ((static_cast<size_t>(set) * L + (l - 1)) * BG + static_cast<size_t>(b) * G) * H;
+            for (int i = tid; i < G * H; i += kThreads) dnext[i] = act[i] > 0.0f ? dnext[i] : 0.0f;
+        } else {
+            float *out = dP + (static_cast<size_t>(b) * 3 + set) * G * H;
+            for (int i = tid; i < G * H; i += kThreads) out[i] = dnext[i];
+        }
+        __syncthreads();
+        float *t = dcur; dcur = dnext; dnext = t;
+    }
+}
+
+// Section 2.2 step 3: 0 = v*, 1 = can reach v*, 2 = reachable from v*, 3 = neither.
+__device__ __forceinline__ int node_class_bw(int v, int cur, const uint8_t *reach, int n_tot)
+{
+    if (v == cur) return 0;
+    if (reach[static_cast<size_t>(n_tot) + v]) return 1;
+    if (reach[v]) return 2;
+    return 3;
+}
+
+// ------------------------------------------------------------------ 2. pooling
+// Workgroup (chunk, graph) over a contiguous slice of the graph's nodes, bucketed by set as in
+// the forward pass.  A tile of nodes of one set goes forward through l_set (outputs kept in
+// lact), takes dP[set][device] as the gradient of its last output, and goes back to d e_u.
+// The current node takes its gradient from the policy input; a node with a device id outside
+// [0, D) was pooled nowhere and gets zero.
+template <int RPT>
+__global__ __launch_bounds__(kThreads) void k_bw_pool(GraphView gv, ModelView mv,
+                                                      const float *__restrict__ blob_t,
+                                                      const float *__restrict__ emb,
+                                                      const uint8_t *__restrict__ reach,
+                                                      const int32_t *__restrict__ placement,
+                                                      const int32_t *__restrict__ cur_node,
+                                                      const float *__restrict__ dP,
+                                                      const float *__restrict__ dz,
+                                                      uint8_t *__restrict__ cls_out,
+                                                      float *__restrict__ lact,
+                                                      float *__restrict__ dl,
+                                                      float *__restrict__ demb, int max_chunks)
+{
+    extern __shared__ float lds[];
+    __shared__ int16_t s_list[3][kPoolSub];
+    __shared__ int8_t s_cls[kPoolSub];
+    __shared__ int s_count[3];
+    __shared__ int s_dev[kTile];
+    __shared__ int s_node[kTile];
+    const int H = mv.H, G = mv.G, D = mv.D, L = mv.L, Z = mv.Z;
+    const int b = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+    const int n0 = gv.node_off[b], n_b = gv.node_off[b + 1] - n0;
+    int chunks = (n_b + kPoolChunk - 1) / kPoolChunk;
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (c >= chunks) return;
+    const int per = (n_b + chunks - 1) / chunks;
+    const int lo = n0 + c * per, hi = min(n0 + n_b, lo + per);
+    const int cl = cur_node[b];
+    const int cur = (cl >= 0 && cl < n_b) ? n0 + cl : -1;
+    const size_t NH = static_cast<size_t>(gv.n_tot) * H;
+
+    float *buf_x = lds;                    // [kTile][2H]
+    float *buf_a = buf_x + kTile * 2 * H;  // [kTile][H]
+    float *buf_b = buf_a + kTile * H;      // [kTile][H]
+
+    for (int s0 = lo; s0 < hi; s0 += kPoolSub) {
+        const int cnt = min(kPoolSub, hi - s0);
+        if (tid < cnt) {
+            const int k = node_class_bw(s0 + tid, cur, reach, gv.n_tot);
+            s_cls[tid] = static_cast<int8_t>(k);
+            cls_out[s0 + tid] = static_cast<uint8_t>(k);
+        }
+        __syncthreads();
+        if (tid < 3) {
+            int m = 0;
+            for (int i = 0; i < cnt; ++i)
+                if (s_cls[i] == tid + 1) s_list[tid][m++] = static_cast<int16_t>(i);
+            s_count[tid] = m;
+        }
+        // the current node: d e = first 2H entries of dz; its l rows are never used
+        if (cur >= s0 && cur < s0 + cnt)
+            for (int i = tid; i < 2 * H; i += kThreads)
+                demb[static_cast<size_t>(cur) * 2 * H + i] = dz[static_cast<size_t>(b) * Z + i];
+        __syncthreads();
+        for (int set = 0; set < 3; ++set) {
+            const int m = s_count[set];
+            const MlpRef &ln = mv.l[set];
+            for (int t0 = 0; t0 < m; t0 += kTile) {
+                const int rows = min(kTile, m - t0);
+                for (int i = tid; i < rows * 2 * H; i += kThreads) {
+                    const int r = i / (2 * H), k = i - r * 2 * H;
+                    buf_x[i] = emb[static_cast<size_t>(s0 + s_list[set][t0 + r]) * 2 * H + k];
+                }
+                if (tid < rows) {
+                    const int v = s0 + s_list[set][t0 + tid];
+                    const int dev = placement[v];
+                    s_node[tid] = v;
+                    s_dev[tid] = (dev >= 0 && dev < D) ? (G == 1 ? 0 : dev) : -1;
+                }
+                __syncthreads();
+                // forward through l_set, every layer's output kept
+                const float *in = buf_x;
+                int n_in = 2 * H;
+                float *out = buf_a;
+                for (int l = 0; l < L; ++l) {
+                    dense_rows<RPT>(mv.blob + ln.layer[l].w, H, mv.blob + ln.layer[l].b, n_in, H, in, n_in,
+                                    out, H, rows, true);
+                    __syncthreads();
+                    for (int i = tid; i < rows * H; i += kThreads) {
+                        const int r = i / H, h = i - r * H;
+                        lact[static_cast<size_t>(l) * NH + static_cast<size_t>(s_node[r]) * H + h] = out[i];
+                    }
+                    in = out;
+                    n_in = H;
+                    out = (out == buf_a) ? buf_b : buf_a;
+                }
+                // `in` holds the last layer's output; delta of the last layer into `out`
+                float *dcur = out, *dnext = const_cast<float *>(in);
+                for (int i = tid; i < rows * H; i += kThreads) {
+                    const int r = i / H, h = i - r * H;
+                    const int dev = s_dev[r];
+                    const float g = dev >= 0 ? dP[((static_cast<size_t>(b) * 3 + set) * G + dev) * H + h] : 0.0f;
+                    dcur[i] = in[i] > 0.0f ? g : 0.0f;
+                }
+                __threadfence_block();
+                __syncthreads();
+                for (int l = L - 1; l >= 0; --l) {
+                    for (int i = tid; i < rows * H; i += kThreads) {
+                        const int r = i / H, h = i - r * H;
+                        dl[static_cast<size_t>(l) * NH + static_cast<size_t>(s_node[r]) * H + h] = dcur[i];
+                    }
+                    if (l > 0) {
+                        dense_rows<RPT>(blob_t + ln.layer[l].w, H, nullptr, H, H, dcur, H, dnext, H, rows, false);
+                        __syncthreads();
+                        for (int i = tid; i < rows * H; i += kThreads) {
+                            const int r = i / H, h = i - r * H;
+                            const float a = lact[static_cast<size_t>(l - 1) * NH + static_cast<size_t>(s_node[r]) * H + h];
+                            dnext[i] = a > 0.0f ? dnext[i] : 0.0f;
+                        }
+                        __syncthreads();
+                        float *t = dcur; dcur = dnext; dnext = t;
+                    } else {
+                        // first layer: [2H, H] stored transposed as [H][2H]; the two halves of d e
+                        dense_rows<RPT>(blob_t + ln.layer[0].w, 2 * H, nullptr, H, H, dcur, H, buf_x, 2 * H, rows, false);
+                        dense_rows<RPT>(blob_t + ln.layer[0].w + H, 2 * H, nullptr, H, H, dcur, H, buf_x + H, 2 * H, rows, false);
+                        __syncthreads();
+                        for (int i = tid; i < rows * 2 * H; i += kThreads) {
+                            const int r = i / (2 * H), k = i - r * 2 * H;
+                            demb[static_cast<size_t>(s_node[r]) * 2 * H + k] = buf_x[i];
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ 3. sweeps
+// (a) f at the final state of every node: tile of 16 nodes x direction.
+template <int RPT>
+__global__ __launch_bounds__(kThreads) void k_bw_f_acts(GraphView gv, ModelView mv,
+                                                        const float *__restrict__ emb,
+                                                        float *__restrict__ fact)
+{
+    extern __shared__ float lds[];
+    const int H = mv.H, L = mv.L, tid = threadIdx.x, dir = blockIdx.y;
+    const int v0 = blockIdx.x * kTile, rows = min(kTile, gv.n_tot - v0);
+    float *buf_a = lds, *buf_b = lds + kTile * H;
+    for (int i = tid; i < rows * H; i += kThreads) {
+        const int r = i / H, h = i - r * H;
+        buf_a[i] = emb[static_cast<size_t>(v0 + r) * 2 * H + dir * H + h];
+    }
+    __syncthreads();
+    float *in = buf_a, *out = buf_b;
+    for (int l = 0; l < L; ++l) {
+        const LayerRef &ly = mv.f[dir].layer[l];
+        dense_rows<RPT>(mv.blob + ly.w, H, mv.blob + ly.b, H, H, in, H, out, H, rows, true);
+        __syncthreads();
+        float *dst = fact + slab(dir, l, L, gv.n_tot, H) + static_cast<size_t>(v0) * H;
+        for (int i = tid; i < rows * H; i += kThreads) dst[i] = out[i];
+        float *t = in; in = out; out = t;
+    }
+}
+
+// (b) the gathered sums a_v = sum of the neighbours' messages, and g at them.
+template <int RPT>
+__global__ __launch_bounds__(kThreads) void k_bw_g_acts(GraphView gv, ModelView mv,
+                                                        const float *__restrict__ fact,
+                                                        float *__restrict__ agg,
+                                                        float *__restrict__ gact)
+{
+    extern __shared__ float lds[];
+    const int H = mv.H, L = mv.L, tid = threadIdx.x, dir = blockIdx.y;
+    const int v0 = blockIdx.x * kTile, rows = min(kTile, gv.n_tot - v0);
+    float *buf_a = lds, *buf_b = lds + kTile * H;
+    const float *msg = fact + slab(dir, L - 1, L, gv.n_tot, H);
+    const int32_t *nbr_ptr = gv.nbr_ptr[dir], *nbr_idx = gv.nbr_idx[dir];
+    for (int i = tid; i < rows * H; i += kThreads) {
+        const int r = i / H, h = i - r * H;
+        const int v = v0 + r;
+        float a = 0.0f;
+        for (int p = nbr_ptr[v]; p < nbr_ptr[v + 1]; ++p) a += msg[static_cast<size_t>(nbr_idx[p]) * H + h];
+        buf_a[i] = a;
+        agg[(static_cast<size_t>(dir) * gv.n_tot + v) * H + h] = a;
+    }
+    __syncthreads();
+    float *in = buf_a, *out = buf_b;
+    for (int l = 0; l < L; ++l) {
+        const LayerRef &ly = mv.g[dir].layer[l];
+        dense_rows<RPT>(mv.blob + ly.w, H, mv.blob + ly.b, H, H, in, H, out, H, rows, true);
+        __syncthreads();
+        float *dst = gact + slab(dir, l, L, gv.n_tot, H) + static_cast<size_t>(v0) * H;
+        for (int i = tid; i < rows * H; i += kThreads) dst[i] = out[i];
+        float *t = in; in = out; out = t;
+    }
+}
+
+// (c) the dependent chain.  s_v <- s_v + g(a_v), m_v = f(s_v), a_w = sum of m over xi(w).
+// With dE/ds_v given from outside (pooling, head) in demb, for v in reverse level order:
+//   dm_v   = sum over the nodes w that gathered m_v (v's neighbours in the OTHER direction) of da_w
+//   ds_v  += f'(s_v)^T dm_v          (back through the layers of f)
+//   da_v   = g'(a_v)^T ds_v          (back through the layers of g)
+// demb becomes the gradient of the sweep's input (the residual passes ds_v through unchanged).
+template <int RPT>
+__global__ __launch_bounds__(kThreads) void k_bw_sweep_generic(GraphView gv, ModelView mv,
+                                                               const float *__restrict__ blob_t,
+                                                               const float *__restrict__ fact,
+                                                               const float *__restrict__ gact,
+                                                               float *__restrict__ demb,
+                                                               float *__restrict__ dagg_base,
+                                                               float *__restrict__ df,
+                                                               float *__restrict__ dg)
+{
+    extern __shared__ float lds[];
+    const int H = mv.H, L = mv.L;
+    const int b = blockIdx.x, dir = blockIdx.y, tid = threadIdx.x;
+    float *buf_a = lds, *buf_b = lds + kTile * H;
+    float *dagg = dagg_base + static_cast<size_t>(dir) * gv.n_tot * H;
+    const int32_t *order = gv.order[dir];
+    const int32_t *suc_ptr = gv.nbr_ptr[1 - dir], *suc_idx = gv.nbr_idx[1 - dir];
+    const int32_t *lvl = gv.lvl_ptr[dir] + gv.lvl_off[b];
+    const int depth = gv.lvl_off[b + 1] - gv.lvl_off[b] - 1;
+    const MlpRef &fn = mv.f[dir], &gn = mv.g[dir];
+
+    for (int level = depth - 1; level >= 0; --level) {
+        const int beg = lvl[level], end = lvl[level + 1];
+        for (int t0 = beg; t0 < end; t0 += kTile) {
+            const int rows = min(kTile, end - t0);
+            // dm_v, masked by the last layer of f
+            for (int i = tid; i < rows * H; i += kThreads) {
+                const int r = i / H, h = i - r * H;
+                const int v = order[t0 + r];
+                float a = 0.0f;
+                for (int p = suc_ptr[v]; p < suc_ptr[v + 1]; ++p)
+                    a += dagg[static_cast<size_t>(suc_idx[p]) * H + h];
+                const float m = fact[slab(dir, L - 1, L, gv.n_tot, H) + static_cast<size_t>(v) * H + h];
+                buf_a[i] = m > 0.0f ? a : 0.0f;
+            }
+            __syncthreads();
+            float *dcur = buf_a, *dnext = buf_b;
+            for (int l = L - 1; l >= 0; --l) {
+                for (int i = tid; i < rows * H; i += kThreads) {
+                    const int r = i / H, h = i - r * H;
+                    df[slab(dir, l, L, gv.n_tot, H) + static_cast<size_t>(order[t0 + r]) * H + h] = dcur[i];
+                }
+                dense_rows<RPT>(blob_t + fn.layer[l].w, H, nullptr, H, H, dcur, H, dnext, H, rows, false);
+                __syncthreads();
+                if (l > 0) {
+                    for (int i = tid; i < rows * H; i += kThreads) {
+                        const int r = i / H, h = i - r * H;
+                        const float a = fact[slab(dir, l - 1, L, gv.n_tot, H) + static_cast<size_t>(order[t0 + r]) * H + h];
+                        dnext[i] = a > 0.0f ? dnext[i] : 0.0f;
+                    }
+                    __syncthreads();
+                }
+                float *t = dcur; dcur = dnext; dnext = t;
+            }
+            // ds_v = outside gradient + f-path; then the delta of g's last layer
+            for (int i = tid; i < rows * H; i += kThreads) {
+                const int r = i / H, h = i - r * H;
+                const int v = order[t0 + r];
+                const size_t at = static_cast<size_t>(v) * 2 * H + dir * H + h;
+                const float ds = demb[at] + dcur[i];
+                demb[at] = ds;
+                const float u = gact[slab(dir, L - 1, L, gv.n_tot, H) + static_cast<size_t>(v) * H + h];
+                dcur[i] = u > 0.0f ? ds : 0.0f;
+            }
+            __syncthreads();
+            for (int l = L - 1; l >= 0; --l) {
+                for (int i = tid; i < rows * H; i += kThreads) {
+                    const int r = i / H, h = i - r * H;
+                    dg[slab(dir, l, L, gv.n_tot, H) + static_cast<size_t>(order[t0 + r]) * H + h] = dcur[i];
+                }
+                dense_rows<RPT>(blob_t + gn.layer[l].w, H, nullptr, H, H, dcur, H, dnext, H, rows, false);
+                __syncthreads();
+                if (l > 0) {
+                    for (int i = tid; i < rows * H; i += kThreads) {
+                        const int r = i / H, h = i - r * H;
+                        const float a = gact[slab(dir, l - 1, L, gv.n_tot, H) + static_cast<size_t>(order[t0 + r]) * H + h];
+                        dnext[i] = a > 0.0f ? dnext[i] : 0.0f;
+                    }
+                    __syncthreads();
+                }
+                float *t = dcur; dcur = dnext; dnext = t;
+            }
+            for (int i = tid; i < rows * H; i += kThreads) {
+                const int r = i / H, h = i - r * H;
+                dagg[static_cast<size_t>(order[t0 + r]) * H + h] = dcur[i];
+            }
+            __syncthreads();
+        }
+        // da of this level is read by earlier levels of this same workgroup
+        __threadfence_block();
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------ 4. projection
+// x_v = relu(W^T phi_v + b) feeds both directions: dx_v = (ds_td + ds_bu) masked by x_v > 0.
+// Also writes phi_v, the input rows of the projection's weight gradient.
+__global__ __launch_bounds__(kThreads) void k_bw_proj(GraphView gv, ModelView mv,
+                                                      const float *__restrict__ feats,
+                                                      const int32_t *__restrict__ placement,
+                                                      const int32_t *__restrict__ cur_node,
+                                                      const float *__restrict__ demb,
+                                                      float *__restrict__ dx,
+                                                      float *__restrict__ phi)
+{
+    const int H = mv.H, D = mv.D, F = mv.F;
+    const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (idx >= static_cast<size_t>(gv.n_tot) * H) return;
+    const int v = static_cast<int>(idx / H), h = static_cast<int>(idx - static_cast<size_t>(v) * H);
+    const int b = gv.node_graph[v];
+    const float *W = mv.blob + mv.proj.w;
+    float s = mv.blob[mv.proj.b + h];
+    s = fmaf(feats[v * 3 + 0], W[0 * H + h], s);
+    s = fmaf(feats[v * 3 + 1], W[1 * H + h], s);
+    const int dev = placement[v];
+    if (dev >= 0 && dev < D) s += W[(2 + dev) * H + h];
+    const bool is_cur = v - gv.node_off[b] == cur_node[b];
+    if (is_cur) s += W[(2 + D) * H + h];
+    s = fmaf(feats[v * 3 + 2], W[(3 + D) * H + h], s);
+    const float g = demb[static_cast<size_t>(v) * 2 * H + h] + demb[static_cast<size_t>(v) * 2 * H + H + h];
+    dx[idx] = s > 0.0f ? g : 0.0f;
+    if (h < F) {
+        float p;
+        if (h == 0) p = feats[v * 3 + 0];
+        else if (h == 1) p = feats[v * 3 + 1];
+        else if (h < 2 + D) p = (dev == h - 2) ? 1.0f : 0.0f;
+        else if (h == 2 + D) p = is_cur ? 1.0f : 0.0f;
+        else p = feats[v * 3 + 2];
+        phi[static_cast<size_t>(v) * F + h] = p;
+    }
+}
+
+// phi rows when H < F (more raw features than embedding columns): one thread per (node, feature).
+__global__ __launch_bounds__(kThreads) void k_bw_phi(GraphView gv, ModelView mv,
+                                                     const float *__restrict__ feats,
+                                                     const int32_t *__restrict__ placement,
+                                                     const int32_t *__restrict__ cur_node,
+                                                     float *__restrict__ phi)
+{
+    const int D = mv.D, F = mv.F;
+    const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (idx >= static_cast<size_t>(gv.n_tot) * F) return;
+    const int v = static_cast<int>(idx / F), h = static_cast<int>(idx - static_cast<size_t>(v) * F);
+    const int b = gv.node_graph[v];
+    const int dev = placement[v];
+    float p;
+    if (h == 0) p = feats[v * 3 + 0];
+    else if (h == 1) p = feats[v * 3 + 1];
+    else if (h < 2 + D) p = (dev == h - 2) ? 1.0f : 0.0f;
+    else if (h == 2 + D) p = (v - gv.node_off[b] == cur_node[b]) ? 1.0f : 0.0f;
+    else p = feats[v * 3 + 2];
+    phi[idx] = p;
+}
+
+// ------------------------------------------------------------------ 5. weight gradients
+// partial[slab][i * J + j] = sum over the slab's rows r of A[r][i] * Dl[r][j]  (i in this
+// workgroup's block of kWgI), partial[slab][I * J + j] = sum of Dl[r][j] (the bias).  Rows whose
+// class byte differs from `want` are skipped when row_cls is given.  Thread (grp, j): column j,
+// rows grp, grp + groups, ... of every staged batch; groups are added in order at the end.
+__global__ __launch_bounds__(kThreads) void k_wgrad(const float *__restrict__ A, int lda,
+                                                    const float *__restrict__ Dl, int ldd,
+                                                    const uint8_t *__restrict__ row_cls, int want,
+                                                    int R, int I, int J, int rows_per_slab,
+                                                    float *__restrict__ partial)
+{
+    __shared__ float a_s[kWgRB][kWgI];
+    __shared__ int ok_s[kWgRB];
+    __shared__ float red[kThreads * (kWgI + 1)];
+    const int tid = threadIdx.x;
+    const int i0 = blockIdx.x * kWgI, sl = blockIdx.y;
+    const int r_beg = sl * rows_per_slab, r_end = min(R, r_beg + rows_per_slab);
+    const int groups = kThreads / J;
+    const int grp = tid / J, j = tid - grp * J;
+    const bool active = grp < groups;
+    float acc[kWgI];
+#pragma unroll
+    for (int ii = 0; ii < kWgI; ++ii) acc[ii] = 0.0f;
+    float accb = 0.0f;
+    for (int r0 = r_beg; r0 < r_end; r0 += kWgRB) {
+        for (int idx = tid; idx < kWgRB * kWgI; idx += kThreads) {
+            const int rr = idx / kWgI, ii = idx - rr * kWgI;
+            const int row = r0 + rr;
+            const bool ok = row < r_end && (!row_cls || row_cls[row] == want);
+            a_s[rr][ii] = (ok && i0 + ii < I) ? A[static_cast<size_t>(row) * lda + i0 + ii] : 0.0f;
+            if (ii == 0) ok_s[rr] = ok ? 1 : 0;
+        }
+        __syncthreads();
+        if (active) {
+            for (int rr = grp; rr < kWgRB; rr += groups) {
+                if (!ok_s[rr]) continue;
+                const float d = Dl[static_cast<size_t>(r0 + rr) * ldd + j];
+#pragma unroll
+                for (int ii = 0; ii < kWgI; ++ii) acc[ii] = fmaf(a_s[rr][ii], d, acc[ii]);
+                accb += d;
+            }
+        }
+        __syncthreads();
+    }
+    if (active) {
+#pragma unroll
+        for (int ii = 0; ii < kWgI; ++ii) red[(grp * (kWgI + 1) + ii) * J + j] = acc[ii];
+        red[(grp * (kWgI + 1) + kWgI) * J + j] = accb;
+    }
+    __syncthreads();
+    if (active && grp == 0) {
+        float *dst = partial + static_cast<size_t>(sl) * (static_cast<size_t>(I) * J + J);
+        for (int ii = 0; ii <= kWgI; ++ii) {
+            float s = 0.0f;
+            for (int gq = 0; gq < groups; ++gq) s += red[(gq * (kWgI + 1) + ii) * J + j];
+            if (ii < kWgI) {
+                if (i0 + ii < I) dst[static_cast<size_t>(i0 + ii) * J + j] = s;
+            } else if (blockIdx.x == 0) {
+                dst[static_cast<size_t>(I) * J + j] = s;
+            }
+        }
+    }
+}
+
+// out[idx] += sum over slabs, in slab order.
+__global__ __launch_bounds__(kThreads) void k_wgrad_reduce(const float *__restrict__ partial, int n_slabs,
+                                                           size_t count, float *__restrict__ out)
+{
+    const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (idx >= count) return;
+    float s = 0.0f;
+    for (int sl = 0; sl < n_slabs; ++sl) s += partial[static_cast<size_t>(sl) * count + idx];
+    out[idx] += s;
+}
+
+__global__ __launch_bounds__(kThreads) void k_fill_zero(float *__restrict__ p, size_t n)
+{
+    const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (idx < n) p[idx] = 0.0f;
+}
+
+int pick_rpt_bw(int H)
+{
+    int groups = kThreads / H;
+    if (groups > kTile) groups = kTile;
+    int rpt = 1;
+    while (groups * rpt < kTile) rpt *= 2;
+    return rpt;
+}
+
+template <typename K>
+void allow_lds_bw(K kernel, size_t bytes)
+{
+    if (bytes > 48 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+}
+
+#define PL_DISPATCH_RPT(rpt, CALL) \
+    switch (rpt) {                 \
+        case 1: { CALL(1); break; }  \
+        case 2: { CALL(2); break; }  \
+        case 4: { CALL(4); break; }  \
+        case 8: { CALL(8); break; }  \
+        default: { CALL(16); break; } \
+    }
+
+int wgrad_rows_per_slab(int64_t R)
+{
+    int64_t per = (R + 383) / 384;
+    if (per < 256) per = 256;
+    return static_cast<int>((per + kWgRB - 1) / kWgRB * kWgRB);
+}
+
+}  // namespace
+
+size_t wgrad_partial_floats(int64_t R, int I, int J)
+{
+    const int per = wgrad_rows_per_slab(R);
+    const int64_t slabs = R > 0 ? (R + per - 1) / per : 0;
+    return static_cast<size_t>(slabs) * (static_cast<size_t>(I) * J + J);
+}
+
+void launch_fill_zero(float *p, size_t n, hipStream_t s)
+{
+    if (n == 0) return;
+    hipLaunchKernelGGL(k_fill_zero, dim3(static_cast<unsigned>((n + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                       s, p, n);
+}
+
+void launch_wgrad(const float *A, int lda, const float *Dl, int ldd, const uint8_t *row_cls, int want,
+                  int64_t R, const LayerRef &ly, float *partial, float *grad, hipStream_t s)
+{
+    if (R <= 0) return;
+    const int I = ly.n_in, J = ly.n_out;
+    const int per = wgrad_rows_per_slab(R);
+    const int slabs = static_cast<int>((R + per - 1) / per);
+    hipLaunchKernelGGL(k_wgrad, dim3((I + kWgI - 1) / kWgI, slabs), dim3(kThreads), 0, s, A, lda, Dl, ldd,
+                       row_cls, want, static_cast<int>(R), I, J, per, partial);
+    const size_t count = static_cast<size_t>(I) * J + J;
+    hipLaunchKernelGGL(k_wgrad_reduce, dim3(static_cast<unsigned>((count + kThreads - 1) / kThreads)),
+                       dim3(kThreads), 0, s, partial, slabs, count, grad + ly.w);
+}
+
+void launch_backward_generic(const GraphView &gv, const ModelView &mv, const float *blob_t,
+                             const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
+                             const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
+                             float *grad, float *out_logp, hipStream_t s)
+{
+    if (gv.B == 0) return;
+    const int H = mv.H, L = mv.L, G = mv.G, B = gv.B, n = gv.n_tot;
+    const int rpt = pick_rpt_bw(H);
+    const int n_slices = (mv.Z + 255) / 256;
+    const size_t NH = static_cast<size_t>(n) * H;
+    const size_t BG = static_cast<size_t>(B) * G;
+
+    // 1. head
+    hipLaunchKernelGGL(k_bw_head, dim3(B), dim3(kThreads), 0, s, gv, mv, blob_t, ws.hidp, n_slices, fa.cur_node,
+                       actions, coeff, gw.hid, gw.dpre, gw.dlogit, gw.dz, out_logp);
+    {
+        const size_t lds = sizeof(float) * 3 * kTile * H;
+#define CALL(R)                                                                                          \
+    allow_lds_bw(k_bw_head_sets<R>, lds);                                                                \
+    hipLaunchKernelGGL(k_bw_head_sets<R>, dim3(3, B), dim3(kThreads), lds, s, gv, mv, blob_t, gw.pooled, \
+                       gw.dz, gw.hin, gw.hact, gw.dh, gw.dP)
+        PL_DISPATCH_RPT(rpt, CALL)
+#undef CALL
+    }
+    // 2. pooling
+    {
+        const size_t lds = sizeof(float) * kTile * 4 * H;
+#define CALL(R)                                                                                             \
+    allow_lds_bw(k_bw_pool<R>, lds);                                                                        \
+    hipLaunchKernelGGL(k_bw_pool<R>, dim3(pool_chunks, B), dim3(kThreads), lds, s, gv, mv, blob_t, ws.emb,  \
+                       ws.reach, fa.placement, fa.cur_node, gw.dP, gw.dz, gw.cls, gw.lact, gw.dl, gw.demb, \
+                       pool_chunks)
+        PL_DISPATCH_RPT(rpt, CALL)
+#undef CALL
+    }
+    // 3. sweeps
+    if (k_sweeps > 0) {
+        const size_t lds = sizeof(float) * 2 * kTile * H;
+        const unsigned tiles = static_cast<unsigned>((n + kTile - 1) / kTile);
+#define CALL(R)                                                                                            \
+    allow_lds_bw(k_bw_f_acts<R>, lds);                                                                     \
+    allow_lds_bw(k_bw_g_acts<R>, lds);                                                                     \
+    allow_lds_bw(k_bw_sweep_generic<R>, lds);                                                              \
+    hipLaunchKernelGGL(k_bw_f_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, ws.emb, gw.fact);   \
+    hipLaunchKernelGGL(k_bw_g_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, gw.fact, gw.agg,    \
+                       gw.gact);                                                                           \
+    hipLaunchKernelGGL(k_bw_sweep_generic<R>, dim3(B, 2), dim3(kThreads), lds, s, gv, mv, blob_t, gw.fact, \
+                       gw.gact, gw.demb, gw.dagg, gw.df, gw.dg)
+        PL_DISPATCH_RPT(rpt, CALL)
+#undef CALL
+    }
+    // 4. projection
+    {
+        const size_t total = NH;
+        hipLaunchKernelGGL(k_bw_proj, dim3(static_cast<unsigned>((total + kThreads - 1) / kThreads)),
+                           dim3(kThreads), 0, s, gv, mv, fa.node_feats, fa.placement, fa.cur_node, gw.demb,
+                           gw.dx, gw.phi);
+        if (H < mv.F) {
+            const size_t tf = static_cast<size_t>(n) * mv.F;
+            hipLaunchKernelGGL(k_bw_phi, dim3(static_cast<unsigned>((tf + kThreads - 1) / kThreads)),
+                               dim3(kThreads), 0, s, gv, mv, fa.node_feats, fa.placement, fa.cur_node, gw.phi);
+        }
+    }
+    // 5. weight gradients
+    launch_wgrad(gw.phi, mv.F, gw.dx, H, nullptr, 0, n, mv.proj, gw.partial, grad, s);
+    if (k_sweeps > 0) {
+        for (int dir = 0; dir < 2; ++dir)
+            for (int l = 0; l < L; ++l) {
+                const size_t at = (static_cast<size_t>(dir) * L + l) * NH;
+                const float *fin = l == 0 ? ws.emb + dir * H : gw.fact + (static_cast<size_t>(dir) * L + l - 1) * NH;
+                launch_wgrad(fin, l == 0 ? 2 * H : H, gw.df + at, H, nullptr, 0, n, mv.f[dir].layer[l],
+                             gw.partial, grad, s);
+                const float *gin = l == 0 ? gw.agg + static_cast<size_t>(dir) * NH
+                                          : gw.gact + (static_cast<size_t>(dir) * L + l - 1) * NH;
+                launch_wgrad(gin, H, gw.dg + at, H, nullptr, 0, n, mv.g[dir].layer[l], gw.partial, grad, s);
+            }
+    }
+    for (int set = 0; set < 3; ++set)
+        for (int l = 0; l < L; ++l) {
+            const float *lin = l == 0 ? ws.emb : gw.lact + static_cast<size_t>(l - 1) * NH;
+            launch_wgrad(lin, l == 0 ? 2 * H : H, gw.dl + static_cast<size_t>(l) * NH, H, gw.cls, set + 1, n,
+                         mv.l[set].layer[l], gw.partial, grad, s);
+            const float *hin = l == 0 ? gw.hin + static_cast<size_t>(set) * BG * H
+                                      : gw.hact + (static_cast<size_t>(set) * L + l - 1) * BG * H;
+            launch_wgrad(hin, H, gw.dh + (static_cast<size_t>(set) * L + l) * BG * H, H, nullptr, 0,
+                         static_cast<int64_t>(BG), mv.h[set].layer[l], gw.partial, grad, s);
+        }
+    launch_wgrad(ws.zbuf, mv.Z, gw.dpre, H, nullptr, 0, B, mv.pol1, gw.partial, grad, s);
+    launch_wgrad(gw.hid, H, gw.dlogit, mv.D, nullptr, 0, B, mv.pol2, gw.partial, grad, s);
+}
+
+}  // namespace pl

@@ -88,3 +88,59 @@ def assert_probs_close(got, ref_probs, ref_logits, what=""):
     bound = np.minimum(1.0, 1e-6 + np.asarray(ref_probs) * growth + 1e-6 * delta)
     assert np.all(np.abs(np.asarray(got, dtype=np.float64) - ref_probs) <= bound), what
     assert np.allclose(np.asarray(got).sum(axis=-1), 1.0, atol=1e-5), what
+
+
+def custom_workload(rng, sizes, D, H, n_layers=2, k_sweeps=1, group=1, weight_dtype="fp32", p_edge=0.3,
+                    w_scale=0.1):
+    """A ragged batch of random DAGs with a random state and random weights."""
+    from workloads import tiny_random_dag, weight_count
+    from workloads.synthetic import Workload
+    n_nodes, n_edges, srcs, dsts, feats, places, curs = [], [], [], [], [], [], []
+    for n in sizes:
+        s, d = tiny_random_dag(rng, n, p_edge)
+        n_nodes.append(n); n_edges.append(len(s)); srcs.append(s); dsts.append(d)
+        feats.append(np.stack([rng.lognormal(0, 1, n), rng.lognormal(2, 1, n), (rng.random(n) < 0.5)], axis=1))
+        places.append(rng.integers(0, D, n)); curs.append(rng.integers(n))
+    weights = rng.normal(0, w_scale, weight_count(D, H, n_layers, bool(group))).astype(np.float32)
+    return Workload(name="custom", B=len(sizes), D=D, H=H, n_layers=n_layers, k_sweeps=k_sweeps,
+                    group_by_device=group, weight_dtype=weight_dtype,
+                    n_nodes=np.array(n_nodes, np.int32), n_edges=np.array(n_edges, np.int32),
+                    edge_src=np.concatenate(srcs).astype(np.int32),
+                    edge_dst=np.concatenate(dsts).astype(np.int32),
+                    node_feats=np.concatenate(feats).astype(np.float32),
+                    placement=np.concatenate(places).astype(np.int32),
+                    cur_node=np.array(curs, np.int32), weights=weights)
+
+
+def run_gradient(w, actions, coeff, handles=None, path=0, accumulate_into=None, cur_node=None):
+    """pl_policy_gradient of workload `w` on cuda:0.  Returns dict(grad, logits, logp) as numpy."""
+    import torch
+    import paper_1906_08879_amd as pl
+    dev = torch.device("cuda:0")
+    if handles is None:
+        g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+        wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+        if path:
+            wt.set_path(path)
+    else:
+        g, wt = handles
+    t_feats = torch.from_numpy(np.ascontiguousarray(w.node_feats, dtype=np.float32)).to(dev)
+    t_place = torch.from_numpy(np.ascontiguousarray(w.placement, dtype=np.int32)).to(dev)
+    t_cur = torch.from_numpy(np.ascontiguousarray(w.cur_node if cur_node is None else cur_node, dtype=np.int32)).to(dev)
+    t_act = torch.from_numpy(np.ascontiguousarray(actions, dtype=np.int32)).to(dev)
+    t_coef = torch.from_numpy(np.ascontiguousarray(coeff, dtype=np.float32)).to(dev)
+    n_par = pl.weights_count(w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+    if accumulate_into is None:
+        grad = torch.full((n_par,), float("nan"), dtype=torch.float32, device=dev)
+    else:
+        grad = torch.from_numpy(np.ascontiguousarray(accumulate_into, dtype=np.float32)).to(dev)
+    logits = torch.full((w.B, w.D), float("nan"), dtype=torch.float32, device=dev)
+    logp = torch.full((w.B,), 7.0, dtype=torch.float32, device=dev)
+    pl.policy_gradient(g, t_feats, t_place, t_cur, wt, t_act, t_coef, grad, logits, logp,
+                       accumulate=accumulate_into is not None)
+    torch.cuda.synchronize()
+    out = dict(grad=grad.cpu().numpy(), logits=logits.cpu().numpy(), logp=logp.cpu().numpy())
+    if handles is None:
+        g.close()
+        wt.close()
+    return out

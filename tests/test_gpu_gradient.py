@@ -1,0 +1,128 @@
+"""GPU parity of pl_policy_gradient (appendix "REINFORCE Algorithm", Eq. 1) against the float64
+autograd oracle on the same seeded inputs, through the C ABI.
+
+Bar: for every layer's block of the gradient (matrix and bias), the largest error is at most
+GRAD_RTOL times the largest entry of the oracle's block plus GRAD_ATOL times the largest entry of
+the whole gradient.  fp32 sums over up to ~10^3 dependent levels and ~10^5 rows per weight; the
+forward states already differ from float64 by ~1e-6 relative, and the reverse pass adds the same
+again."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import gradient as og
+from gpu_common import custom_workload, run_gradient, assert_logits_close
+from workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+
+GRAD_RTOL, GRAD_ATOL = 2e-4, 2e-6
+
+
+def assert_grad_close(got, ref, w, what):
+    assert np.isfinite(got).all(), f"{what}: non-finite gradient"
+    slices, total = og.layer_slices(w.D, w.H, w.n_layers, w.group_by_device)
+    assert total == got.size == ref.size
+    gmax = np.abs(ref).max()
+    worst = 0.0
+    for name, (ws, bs) in slices.items():
+        for part, sl in (("W", ws), ("b", bs)):
+            err = np.abs(got[sl] - ref[sl]).max()
+            bound = GRAD_RTOL * np.abs(ref[sl]).max() + GRAD_ATOL * gmax
+            worst = max(worst, err / max(bound, 1e-300))
+            assert err <= bound, f"{what}: layer {name}.{part}: error {err:.3g} > {bound:.3g} (block max {np.abs(ref[sl]).max():.3g})"
+    return worst
+
+
+def _actions_and_coeff(w, seed):
+    """Half of the graphs take their least likely device (a large gradient), the rest a random one."""
+    rng = np.random.default_rng(seed)
+    ref = oracle.forward_workload(w, n_threads=8, want_emb=False)
+    actions = rng.integers(0, w.D, w.B).astype(np.int32)
+    low = np.argmin(ref["logits"], axis=1).astype(np.int32)
+    pick = rng.random(w.B) < 0.5
+    actions[pick] = low[pick]
+    coeff = rng.normal(0, 1, w.B).astype(np.float32)
+    return actions, coeff, ref
+
+
+def _compare(w, what, seed=0, path=0):
+    actions, coeff, fwd = _actions_and_coeff(w, seed)
+    print(f"[gradient] {what}", flush=True)
+    got = run_gradient(w, actions, coeff, path=path)
+    ref_grad, ref_logp = og.gradient_workload(w, actions, coeff.astype(np.float64))
+    assert_logits_close(got["logits"], fwd["logits"], what)
+    scale = np.abs(fwd["logits"]).max(axis=1)
+    assert (np.abs(got["logp"] - ref_logp) <= 1e-4 * scale + 1e-5).all(), what
+    worst = assert_grad_close(got["grad"], ref_grad, w, what)
+    print(f"[gradient] {what}: worst error / bound = {worst:.3g}", flush=True)
+    return got, ref_grad
+
+
+@pytest.mark.parametrize("D,H,L,k,group,wd", [
+    (2, 8, 2, 1, 1, "fp32"), (1, 5, 1, 1, 1, "fp32"), (16, 16, 2, 1, 1, "fp32"),
+    (4, 48, 3, 1, 1, "fp32"), (3, 100, 2, 1, 0, "fp32"), (4, 32, 2, 0, 1, "fp32"),
+    (8, 128, 2, 1, 1, "bf16"), (2, 256, 2, 1, 1, "fp32"), (4, 64, 4, 1, 1, "bf16"), (12, 6, 2, 1, 1, "fp32"),
+])
+def test_shapes_and_variants(D, H, L, k, group, wd):
+    """Ragged batches (single nodes, edgeless graphs, wide levels) over the supported range of D,
+    H, layers, pooling modes and weight formats; every parameter compared."""
+    rng = np.random.default_rng(100 * D + H)
+    w = custom_workload(rng, [1, 2, 40, 1, 17, 70, 3], D, H, L, k, group, wd)
+    _compare(w, f"D={D} H={H} L={L} k={k} g={group} {wd}")
+
+
+@pytest.mark.parametrize("name,B", [("random32", 4), ("layered200", 4), ("inception", 2)])
+def test_small_batches_of_the_workloads(name, B):
+    _compare(make_workload(name, B=B), name)
+
+
+def test_accumulation_linearity_and_rejected_states():
+    rng = np.random.default_rng(5)
+    w = custom_workload(rng, [30, 12, 25, 8], 4, 32)
+    actions, coeff, _ = _actions_and_coeff(w, 1)
+    base = run_gradient(w, actions, coeff)
+    again = run_gradient(w, actions, coeff)
+    np.testing.assert_array_equal(base["grad"], again["grad"])            # bitwise run to run
+    start = rng.normal(0, 1, base["grad"].size).astype(np.float32)
+    acc = run_gradient(w, actions, coeff, accumulate_into=start)
+    np.testing.assert_allclose(acc["grad"], start + base["grad"], rtol=0, atol=1e-6 * np.abs(base["grad"]).max() + 1e-6)
+    # an out-of-range action or current node contributes nothing and reports NaN
+    bad_a = actions.copy()
+    bad_a[1] = w.D
+    bad_cur = np.array(w.cur_node, copy=True)
+    bad_cur[2] = -1
+    got = run_gradient(w, bad_a, coeff, cur_node=bad_cur)
+    c2 = coeff.copy()
+    c2[1] = 0.0
+    c2[2] = 0.0
+    ref_grad, _ = og.gradient_workload(w, actions, c2.astype(np.float64))
+    assert_grad_close(got["grad"], ref_grad, w, "rejected states")
+    assert np.isnan(got["logp"][1]) and np.isnan(got["logp"][2]) and np.isfinite(got["logp"][[0, 3]]).all()
+
+
+def test_more_than_one_sweep_is_refused():
+    import paper_1906_08879_amd as pl
+    rng = np.random.default_rng(6)
+    w = custom_workload(rng, [9, 5], 3, 16, k_sweeps=2)
+    with pytest.raises(pl.PlacetoError, match="k_sweeps"):
+        run_gradient(w, np.zeros(2, np.int32), np.ones(2, np.float32))
+
+
+def test_full_size_batch_sampled_graphs():
+    """The benchmark's NASNet-like batch (256 graphs) in its launch shape; three graphs carry a
+    non-zero scalar and the oracle differentiates those."""
+    w = make_workload("nasnet")
+    fwd = oracle.forward_workload(w, n_threads=16, want_emb=False)
+    sample = [0, 101, 255]
+    actions = np.argmin(fwd["logits"], axis=1).astype(np.int32)
+    coeff = np.zeros(w.B, np.float32)
+    coeff[sample] = [1.0, -0.5, 2.0]
+    print("[gradient] nasnet full batch", flush=True)
+    got = run_gradient(w, actions, coeff)
+    ref_grad, ref_logp = og.gradient_workload(w, actions, coeff.astype(np.float64), only=sample)
+    worst = assert_grad_close(got["grad"], ref_grad, w, "nasnet full")
+    print(f"[gradient] nasnet full: worst error / bound = {worst:.3g}", flush=True)
+    scale = np.abs(fwd["logits"]).max(axis=1)
+    for b in sample:
+        assert abs(got["logp"][b] - ref_logp[b]) <= 1e-4 * scale[b] + 1e-5
