@@ -76,6 +76,7 @@ def main() -> int:
     ap.add_argument("--workload", default="nasnet")
     ap.add_argument("--batch", type=int, default=None, help="override the number of graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--grad-steps", type=int, default=4, help="timed reverse passes (reported beside the headline)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain 1 GiB device copy five times and exit (reference for "
                          "scaling the FETCH_SIZE / WRITE_SIZE counters)")
@@ -203,6 +204,29 @@ def main() -> int:
                  "events_per_s": round(float(sim_ev.sum().item()) / sim_elapsed, 1),
                  "what": "event-driven run-time simulation of one placement per graph (one wave per graph)"}
 
+    # one REINFORCE term (appendix "REINFORCE Algorithm", Eq. 1) for the same batch: forward pass +
+    # reverse pass, gradient summed over the batch; beside the headline, not in it
+    n_par = pl.weights_count(w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+    gradient = None
+    if w.k_sweeps <= 1:
+        g_act = torch.from_numpy(np.random.default_rng(0).integers(0, w.D, w.B).astype(np.int32)).to(dev)
+        g_coef = torch.from_numpy(np.random.default_rng(1).normal(0, 1, w.B).astype(np.float32)).to(dev)
+        g_grad = torch.empty((n_par,), dtype=torch.float32, device=dev)
+        pl.policy_gradient(g, feats[0], t_place[0], t_cur[0], wt, g_act, g_coef, g_grad, logits, stream=stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.grad_steps):
+            s_ = i % N_STATES
+            pl.policy_gradient(g, feats[s_], t_place[s_], t_cur[s_], wt, g_act, g_coef, g_grad, logits,
+                               accumulate=i > 0, stream=stream)
+        torch.cuda.synchronize()
+        gr_elapsed = (time.perf_counter() - t0) / max(1, args.grad_steps)
+        assert torch.isfinite(g_grad).all(), "non-finite gradient in the timed run"
+        gradient = {"ms_per_step": round(1e3 * gr_elapsed, 4), "steps": args.grad_steps,
+                    "graph_steps_per_s": round(w.B / gr_elapsed, 2), "parameters": int(n_par),
+                    "what": "forward pass + reverse pass (log-probability gradient of one decision per "
+                            "graph, summed over the batch)"}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
@@ -236,6 +260,7 @@ def main() -> int:
         "roofline": roofline,
         "episode": episode,
         "simulator": simulator,
+        "gradient": gradient,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))
