@@ -80,6 +80,7 @@ struct pl_weights {
     std::vector<float> host_blob;   // values as stored (bf16-rounded when asked)
     // matrix-core sweep: packed A fragments and biases (null when the shape is not covered)
     uint16_t *d_wfrag = nullptr;
+    uint16_t *d_wfrag_bw = nullptr;  // the same for the reverse pass (transposed, f before g)
     float *d_sweep_bias = nullptr;
     uint16_t *d_pool_frag = nullptr;
     float *d_pool_bias = nullptr;
@@ -239,10 +240,11 @@ void free_workspace(Workspace &ws)
 
 void free_grad_workspace(GradWorkspace &gw)
 {
-    float *all[] = {gw.fact, gw.gact, gw.agg, gw.dagg, gw.df, gw.dg, gw.lact, gw.dl, gw.demb, gw.dx, gw.phi,
+    float *all[] = {gw.fact, gw.gact, gw.agg, gw.dagg, gw.dfg, gw.extb, gw.lact, gw.dl, gw.demb, gw.dx, gw.phi,
                     gw.pooled, gw.dP, gw.hin, gw.hact, gw.dh, gw.dz, gw.hid, gw.dpre, gw.dlogit, gw.partial};
     for (float *p : all) (void)hipFree(p);
     (void)hipFree(gw.cls);
+    (void)hipFree(gw.mask4);
     gw = GradWorkspace();
 }
 
@@ -299,12 +301,17 @@ int ensure_grad_workspace(pl_graph_batch *g, const ModelView &mv)
     PL_HIP(take(&gw.fact, 2 * L * NH));
     PL_HIP(take(&gw.gact, 2 * L * NH));
     PL_HIP(take(&gw.agg, 2 * NH));
-    PL_HIP(take(&gw.dagg, 2 * NH));
-    PL_HIP(take(&gw.df, 2 * L * NH));
-    PL_HIP(take(&gw.dg, 2 * L * NH));
+    // the matrix-core chain kernel reads row 2 n of dagg as an all-zero row and stores the rows
+    // of unused chunk slots to row 2 n + 1, to row n of demb and to the spare floats of dfg
+    PL_HIP(take(&gw.dagg, 2 * NH + 2 * H));
+    PL_HIP(hipMemset(gw.dagg, 0, sizeof(float) * (2 * NH + 2 * H)));
+    gw.dfg_stride = 2 * L * NH + H;
+    PL_HIP(take(&gw.dfg, 2 * gw.dfg_stride));
+    PL_HIP(take(&gw.extb, 2 * NH + H));
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.mask4), 2 * NH + 16));
     PL_HIP(take(&gw.lact, L * NH));
     PL_HIP(take(&gw.dl, L * NH));
-    PL_HIP(take(&gw.demb, 2 * NH));
+    PL_HIP(take(&gw.demb, 2 * NH + 2 * H));
     PL_HIP(take(&gw.dx, NH));
     PL_HIP(take(&gw.phi, n * mv.F));
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.cls), n + 16));
@@ -603,6 +610,12 @@ int pl_weights_create(const pl_model_cfg *cfg, const float *host_blob, size_t n_
             pl_weights_destroy(w);
             return rc;
         }
+        std::vector<float> unused;
+        pack_sweep_weights(w->view, w->host_blob.data(), w->sweep_ws, &frag, &unused, true);
+        if ((rc = upload(frag, &w->d_wfrag_bw))) {
+            pl_weights_destroy(w);
+            return rc;
+        }
     }
     if (pool_mfma_supported(cfg->H, cfg->n_layers, cfg->weight_dtype)) {
         std::vector<uint16_t> frag;
@@ -632,6 +645,7 @@ int pl_weights_destroy(pl_weights *w)
     (void)hipFree(w->d_blob);
     (void)hipFree(w->d_blob_t);
     (void)hipFree(w->d_wfrag);
+    (void)hipFree(w->d_wfrag_bw);
     (void)hipFree(w->d_sweep_bias);
     (void)hipFree(w->d_pool_frag);
     (void)hipFree(w->d_pool_bias);
@@ -716,8 +730,14 @@ int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t
     if (rc) return rc;
     if (!accumulate) launch_fill_zero(grad, plan_weights(w->cfg, nullptr), s);
     ForwardArgs fa{node_feats, placement, cur_node, out_logits, nullptr, g->gw.pooled};
+    // the chain kernel addresses the delta arrays with 32-bit element offsets
+    const bool fits = (2.0 * mv.L * static_cast<double>(g->host.n_tot) + 1) * mv.H < 2.0e9 &&
+                      (static_cast<double>(g->host.n_tot) + 2) * 2 * mv.H * sizeof(float) < 4.0e9;
+    const bool chain_cores = w->d_wfrag_bw && w->path == 0 && w->cfg.k_sweeps == 1 && fits;
     launch_backward_generic(g->view, mv, w->d_blob_t, g->ws, g->gw, fa, actions, coeff, w->cfg.k_sweeps,
-                            g->ws.n_chunks, grad, out_logp, s);
+                            g->ws.n_chunks, w->path,
+                            chain_cores ? reinterpret_cast<const uint4 *>(w->d_wfrag_bw) : nullptr,
+                            w->d_sweep_bias, w->sweep_ws, grad, out_logp, s);
     PL_HIP(hipGetLastError());
     return PL_OK;
 }

@@ -183,7 +183,11 @@ void launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace 
 struct GradWorkspace {
     float *fact = nullptr, *gact = nullptr;   // [2, L, n_tot, H] layer outputs of f and g
     float *agg = nullptr, *dagg = nullptr;    // [2, n_tot, H] gathered sums and their gradients
-    float *df = nullptr, *dg = nullptr;       // [2, L, n_tot, H] layer deltas of f and g
+    float *dfg = nullptr;                     // per direction [2L, n_tot, H] layer deltas of f, then of g,
+                                              // then H spare floats; dfg_stride floats per direction
+    size_t dfg_stride = 0;
+    float *extb = nullptr;                    // [2, n_tot, H] outside gradient of the states, bucket order
+    uint8_t *mask4 = nullptr;                 // [2, n_tot, H] ReLU gates, bucket order
     float *lact = nullptr, *dl = nullptr;     // [L, n_tot, H] layer outputs / deltas of l (own set)
     float *demb = nullptr;                    // [n_tot, 2H] gradient of the embeddings
     float *dx = nullptr;                      // [n_tot, H] delta of the projection
@@ -204,12 +208,16 @@ void launch_fill_zero(float *p, size_t n, hipStream_t s);
 void launch_backward_generic(const GraphView &gv, const ModelView &mv, const float *blob_t,
                              const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
                              const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
+                             int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
                              float *grad, float *out_logp, hipStream_t s);
 
 // ---- matrix-core sweep (kernels_mfma.hip)
 bool sweep_mfma_supported(int H, int L, int weight_dtype);
 void pack_sweep_weights(const ModelView &mv, const float *blob, int WS, std::vector<uint16_t> *frag,
-                        std::vector<float> *bias);
+                        std::vector<float> *bias, bool reverse = false);
+void launch_sweep_mfma_bw(const GraphView &gv, const ModelView &mv, const uint4 *wfrag, const float *bias,
+                          int WS, const int32_t *cur_node, float *demb, float *extb, float *dagg,
+                          const uint8_t *mask4, float *delta, size_t delta_stride, hipStream_t s);
 void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                        const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
                        bool first_sweep, bool more_sweeps, hipStream_t s);

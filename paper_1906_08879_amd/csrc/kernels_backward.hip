@@ -428,8 +428,7 @@ __global__ __launch_bounds__(kThreads) void k_bw_sweep_generic(GraphView gv, Mod
                                                                const float *__restrict__ gact,
                                                                float *__restrict__ demb,
                                                                float *__restrict__ dagg_base,
-                                                               float *__restrict__ df,
-                                                               float *__restrict__ dg)
+                                                               float *__restrict__ dfg, size_t dfg_stride)
 {
     extern __shared__ float lds[];
     const int H = mv.H, L = mv.L;
@@ -441,6 +440,8 @@ __global__ __launch_bounds__(kThreads) void k_bw_sweep_generic(GraphView gv, Mod
     const int32_t *lvl = gv.lvl_ptr[dir] + gv.lvl_off[b];
     const int depth = gv.lvl_off[b + 1] - gv.lvl_off[b] - 1;
     const MlpRef &fn = mv.f[dir], &gn = mv.g[dir];
+    const size_t NH = static_cast<size_t>(gv.n_tot) * H;
+    float *df = dfg + dir * dfg_stride, *dg = df + L * NH;
 
     for (int level = depth - 1; level >= 0; --level) {
         const int beg = lvl[level], end = lvl[level + 1];
@@ -461,7 +462,7 @@ __global__ __launch_bounds__(kThreads) void k_bw_sweep_generic(GraphView gv, Mod
             for (int l = L - 1; l >= 0; --l) {
                 for (int i = tid; i < rows * H; i += kThreads) {
                     const int r = i / H, h = i - r * H;
-                    df[slab(dir, l, L, gv.n_tot, H) + static_cast<size_t>(order[t0 + r]) * H + h] = dcur[i];
+                    df[l * NH + static_cast<size_t>(order[t0 + r]) * H + h] = dcur[i];
                 }
                 dense_rows<RPT>(blob_t + fn.layer[l].w, H, nullptr, H, H, dcur, H, dnext, H, rows, false);
                 __syncthreads();
@@ -489,7 +490,7 @@ __global__ __launch_bounds__(kThreads) void k_bw_sweep_generic(GraphView gv, Mod
             for (int l = L - 1; l >= 0; --l) {
                 for (int i = tid; i < rows * H; i += kThreads) {
                     const int r = i / H, h = i - r * H;
-                    dg[slab(dir, l, L, gv.n_tot, H) + static_cast<size_t>(order[t0 + r]) * H + h] = dcur[i];
+                    dg[l * NH + static_cast<size_t>(order[t0 + r]) * H + h] = dcur[i];
                 }
                 dense_rows<RPT>(blob_t + gn.layer[l].w, H, nullptr, H, H, dcur, H, dnext, H, rows, false);
                 __syncthreads();
@@ -512,6 +513,35 @@ __global__ __launch_bounds__(kThreads) void k_bw_sweep_generic(GraphView gv, Mod
         // da of this level is read by earlier levels of this same workgroup
         __threadfence_block();
         __syncthreads();
+    }
+}
+
+// (d) inputs of the matrix-core chain kernel, in the bucket order of the direction whose chunks
+// it walks (pd; the sweep being differentiated is sd = 1 - pd): the outside gradient of s_v and
+// the ReLU gates of the node's layers, one byte per (node, column): bit 0 m_v > 0, bit 1 output
+// of f's layer 0 > 0 (L = 2), bit 2 output of g's last layer > 0, bit 3 output of g's layer 0 > 0
+// (L = 2).
+__global__ __launch_bounds__(kThreads) void k_bw_prep(GraphView gv, int H, int L,
+                                                      const float *__restrict__ demb,
+                                                      const float *__restrict__ fact,
+                                                      const float *__restrict__ gact,
+                                                      float *__restrict__ extb,
+                                                      uint8_t *__restrict__ mask4)
+{
+    const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (idx >= static_cast<size_t>(gv.n_tot) * H) return;
+    const int v = static_cast<int>(idx / H), h = static_cast<int>(idx - static_cast<size_t>(v) * H);
+    for (int pd = 0; pd < 2; ++pd) {
+        const int sd = 1 - pd;
+        const size_t at = (static_cast<size_t>(pd) * gv.n_tot + gv.pos[pd][v]) * H + h;
+        extb[at] = demb[static_cast<size_t>(v) * 2 * H + sd * H + h];
+        int bits = fact[slab(sd, L - 1, L, gv.n_tot, H) + idx] > 0.0f ? 1 : 0;
+        bits |= gact[slab(sd, L - 1, L, gv.n_tot, H) + idx] > 0.0f ? 4 : 0;
+        if (L == 2) {
+            bits |= fact[slab(sd, 0, L, gv.n_tot, H) + idx] > 0.0f ? 2 : 0;
+            bits |= gact[slab(sd, 0, L, gv.n_tot, H) + idx] > 0.0f ? 8 : 0;
+        }
+        mask4[at] = static_cast<uint8_t>(bits);
     }
 }
 
@@ -639,6 +669,74 @@ __global__ __launch_bounds__(kThreads) void k_wgrad(const float *__restrict__ A,
     }
 }
 
+// The same contraction on the matrix cores, for I a multiple of 32 and J in {32, 64, 128}:
+// v_mfma_f32_32x32x2_f32 multiplies a 32 x 2 block of A^T by a 2 x 32 block of Dl in fp32, so two
+// contraction rows are consumed per instruction and both operands are read straight from global
+// memory, 32 consecutive floats per half wave (no LDS, no split into bf16 parts).  Wave w of a
+// workgroup owns rows [32 (4 blockIdx.x + w), +32) of the weight matrix and all J columns
+// (NJ accumulator tiles); lanes 0-31 take even rows of the slab, lanes 32-63 odd rows.
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+template <int NJ>
+__global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict__ A, int lda,
+                                                         const float *__restrict__ Dl, int ldd,
+                                                         const uint8_t *__restrict__ row_cls, int want,
+                                                         int R, int I, int rows_per_slab,
+                                                         float *__restrict__ partial)
+{
+    constexpr int J = 32 * NJ;
+    constexpr int U = 4;                       // row pairs in flight
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 31, lk = lane >> 5;
+    const int ib = blockIdx.x * 4 + wave, sl = blockIdx.y;
+    if (ib * 32 >= I) return;                  // no barrier in this kernel
+    const int r_beg = sl * rows_per_slab, r_end = min(R, r_beg + rows_per_slab);
+    f32x16 acc[NJ];
+#pragma unroll
+    for (int jb = 0; jb < NJ; ++jb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[jb][v] = 0.0f;
+    float bsum[NJ];
+#pragma unroll
+    for (int jb = 0; jb < NJ; ++jb) bsum[jb] = 0.0f;
+    const float *Acol = A + ib * 32 + li;
+    const float *Dcol = Dl + li;
+    for (int r0 = r_beg; r0 < r_end; r0 += 2 * U) {
+        float a[U], bq[U][NJ];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int row = r0 + 2 * u + lk;
+            const int rc = min(row, R - 1);
+            ok[u] = row < r_end && (!row_cls || row_cls[rc] == want);
+            a[u] = Acol[static_cast<size_t>(rc) * lda];
+#pragma unroll
+            for (int jb = 0; jb < NJ; ++jb) bq[u][jb] = Dcol[static_cast<size_t>(rc) * ldd + 32 * jb];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float au = ok[u] ? a[u] : 0.0f;
+#pragma unroll
+            for (int jb = 0; jb < NJ; ++jb) {
+                const float bu = ok[u] ? bq[u][jb] : 0.0f;
+                acc[jb] = __builtin_amdgcn_mfma_f32_32x32x2f32(au, bu, acc[jb], 0, 0, 0);
+                bsum[jb] += bu;
+            }
+        }
+    }
+    float *dst = partial + static_cast<size_t>(sl) * (static_cast<size_t>(I) * J + J);
+#pragma unroll
+    for (int jb = 0; jb < NJ; ++jb) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = ib * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+            dst[static_cast<size_t>(i) * J + 32 * jb + li] = acc[jb][v];
+        }
+        const float other = __shfl_xor(bsum[jb], 32);
+        if (ib == 0 && lk == 0) dst[static_cast<size_t>(I) * J + 32 * jb + li] = bsum[jb] + other;
+    }
+}
+
 // out[idx] += sum over slabs, in slab order.
 __global__ __launch_bounds__(kThreads) void k_wgrad_reduce(const float *__restrict__ partial, int n_slabs,
                                                            size_t count, float *__restrict__ out)
@@ -706,14 +804,28 @@ void launch_fill_zero(float *p, size_t n, hipStream_t s)
 }
 
 void launch_wgrad(const float *A, int lda, const float *Dl, int ldd, const uint8_t *row_cls, int want,
-                  int64_t R, const LayerRef &ly, float *partial, float *grad, hipStream_t s)
+                  int64_t R, const LayerRef &ly, float *partial, float *grad, int generic, hipStream_t s)
 {
     if (R <= 0) return;
     const int I = ly.n_in, J = ly.n_out;
     const int per = wgrad_rows_per_slab(R);
     const int slabs = static_cast<int>((R + per - 1) / per);
-    hipLaunchKernelGGL(k_wgrad, dim3((I + kWgI - 1) / kWgI, slabs), dim3(kThreads), 0, s, A, lda, Dl, ldd,
-                       row_cls, want, static_cast<int>(R), I, J, per, partial);
+    const bool cores = generic == 0 && I % 32 == 0 && (J == 32 || J == 64 || J == 128);
+    if (cores) {
+        const dim3 grid((I + 127) / 128, slabs);
+        if (J == 32)
+            hipLaunchKernelGGL(k_wgrad_mfma<1>, grid, dim3(kThreads), 0, s, A, lda, Dl, ldd, row_cls, want,
+                               static_cast<int>(R), I, per, partial);
+        else if (J == 64)
+            hipLaunchKernelGGL(k_wgrad_mfma<2>, grid, dim3(kThreads), 0, s, A, lda, Dl, ldd, row_cls, want,
+                               static_cast<int>(R), I, per, partial);
+        else
+            hipLaunchKernelGGL(k_wgrad_mfma<4>, grid, dim3(kThreads), 0, s, A, lda, Dl, ldd, row_cls, want,
+                               static_cast<int>(R), I, per, partial);
+    } else {
+        hipLaunchKernelGGL(k_wgrad, dim3((I + kWgI - 1) / kWgI, slabs), dim3(kThreads), 0, s, A, lda, Dl, ldd,
+                           row_cls, want, static_cast<int>(R), I, J, per, partial);
+    }
     const size_t count = static_cast<size_t>(I) * J + J;
     hipLaunchKernelGGL(k_wgrad_reduce, dim3(static_cast<unsigned>((count + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, s, partial, slabs, count, grad + ly.w);
@@ -722,6 +834,7 @@ void launch_wgrad(const float *A, int lda, const float *Dl, int ldd, const uint8
 void launch_backward_generic(const GraphView &gv, const ModelView &mv, const float *blob_t,
                              const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
                              const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
+                             int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
                              float *grad, float *out_logp, hipStream_t s)
 {
     if (gv.B == 0) return;
@@ -765,10 +878,17 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
     hipLaunchKernelGGL(k_bw_f_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, ws.emb, gw.fact);   \
     hipLaunchKernelGGL(k_bw_g_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, gw.fact, gw.agg,    \
                        gw.gact);                                                                           \
-    hipLaunchKernelGGL(k_bw_sweep_generic<R>, dim3(B, 2), dim3(kThreads), lds, s, gv, mv, blob_t, gw.fact, \
-                       gw.gact, gw.demb, gw.dagg, gw.df, gw.dg)
+    if (!wfrag_bw)                                                                                         \
+        hipLaunchKernelGGL(k_bw_sweep_generic<R>, dim3(B, 2), dim3(kThreads), lds, s, gv, mv, blob_t,      \
+                           gw.fact, gw.gact, gw.demb, gw.dagg, gw.dfg, gw.dfg_stride)
         PL_DISPATCH_RPT(rpt, CALL)
 #undef CALL
+        if (wfrag_bw) {
+            hipLaunchKernelGGL(k_bw_prep, dim3(static_cast<unsigned>((NH + kThreads - 1) / kThreads)),
+                               dim3(kThreads), 0, s, gv, H, L, gw.demb, gw.fact, gw.gact, gw.extb, gw.mask4);
+            launch_sweep_mfma_bw(gv, mv, wfrag_bw, sweep_bias, sweep_ws, fa.cur_node, gw.demb, gw.extb, gw.dagg,
+                                 gw.mask4, gw.dfg, gw.dfg_stride, s);
+        }
     }
     // 4. projection
     {
@@ -783,31 +903,32 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
         }
     }
     // 5. weight gradients
-    launch_wgrad(gw.phi, mv.F, gw.dx, H, nullptr, 0, n, mv.proj, gw.partial, grad, s);
+    launch_wgrad(gw.phi, mv.F, gw.dx, H, nullptr, 0, n, mv.proj, gw.partial, grad, generic, s);
     if (k_sweeps > 0) {
         for (int dir = 0; dir < 2; ++dir)
             for (int l = 0; l < L; ++l) {
-                const size_t at = (static_cast<size_t>(dir) * L + l) * NH;
+                const float *dfl = gw.dfg + dir * gw.dfg_stride + static_cast<size_t>(l) * NH;
+                const float *dgl = dfl + static_cast<size_t>(L) * NH;
                 const float *fin = l == 0 ? ws.emb + dir * H : gw.fact + (static_cast<size_t>(dir) * L + l - 1) * NH;
-                launch_wgrad(fin, l == 0 ? 2 * H : H, gw.df + at, H, nullptr, 0, n, mv.f[dir].layer[l],
-                             gw.partial, grad, s);
+                launch_wgrad(fin, l == 0 ? 2 * H : H, dfl, H, nullptr, 0, n, mv.f[dir].layer[l],
+                             gw.partial, grad, generic, s);
                 const float *gin = l == 0 ? gw.agg + static_cast<size_t>(dir) * NH
                                           : gw.gact + (static_cast<size_t>(dir) * L + l - 1) * NH;
-                launch_wgrad(gin, H, gw.dg + at, H, nullptr, 0, n, mv.g[dir].layer[l], gw.partial, grad, s);
+                launch_wgrad(gin, H, dgl, H, nullptr, 0, n, mv.g[dir].layer[l], gw.partial, grad, generic, s);
             }
     }
     for (int set = 0; set < 3; ++set)
         for (int l = 0; l < L; ++l) {
             const float *lin = l == 0 ? ws.emb : gw.lact + static_cast<size_t>(l - 1) * NH;
             launch_wgrad(lin, l == 0 ? 2 * H : H, gw.dl + static_cast<size_t>(l) * NH, H, gw.cls, set + 1, n,
-                         mv.l[set].layer[l], gw.partial, grad, s);
+                         mv.l[set].layer[l], gw.partial, grad, generic, s);
             const float *hin = l == 0 ? gw.hin + static_cast<size_t>(set) * BG * H
                                       : gw.hact + (static_cast<size_t>(set) * L + l - 1) * BG * H;
             launch_wgrad(hin, H, gw.dh + (static_cast<size_t>(set) * L + l) * BG * H, H, nullptr, 0,
-                         static_cast<int64_t>(BG), mv.h[set].layer[l], gw.partial, grad, s);
+                         static_cast<int64_t>(BG), mv.h[set].layer[l], gw.partial, grad, generic, s);
         }
-    launch_wgrad(ws.zbuf, mv.Z, gw.dpre, H, nullptr, 0, B, mv.pol1, gw.partial, grad, s);
-    launch_wgrad(gw.hid, H, gw.dlogit, mv.D, nullptr, 0, B, mv.pol2, gw.partial, grad, s);
+    launch_wgrad(ws.zbuf, mv.Z, gw.dpre, H, nullptr, 0, B, mv.pol1, gw.partial, grad, generic, s);
+    launch_wgrad(gw.hid, H, gw.dlogit, mv.D, nullptr, 0, B, mv.pol2, gw.partial, grad, generic, s);
 }
 
 }  // namespace pl

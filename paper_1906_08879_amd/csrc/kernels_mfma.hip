@@ -76,6 +76,13 @@ struct SweepParams {
     const float4 *featb;    // [2, n_tot] {run time, output size, is-visited, bits(device | is-current << 16)}
     const float *proj;      // [(F + 1), H]: rows of W_in, then b_in; NULL when the input comes from xb
     int D;
+    // reverse pass (BW): ReLU masks of the node's layers in bucket order, one byte per (node,
+    // column): bit 0 gates the gathered sum, bits 1..3 the outputs of layers 0 (L = 2 only),
+    // L - 1 and L (L = 2 only); and the layer deltas, 2L arrays [n_tot, H] in node order
+    const uint8_t *mask4;   // [2, n_tot, H]
+    float *delta;           // per sweep direction: [2L][n_tot, H] (f's layers, then g's), then H
+                            // floats that take the stores of a chunk's unused rows
+    size_t delta_stride;    // floats between the two directions' blocks
 };
 
 // Reads a chunk's meta record through the constant address space, so that the wave-uniform
@@ -92,9 +99,19 @@ constexpr int sweep_waves(int H) { return H / 16 > 4 ? 4 : H / 16; }
 
 // FF: first sweep, the input x_v is computed from the raw-feature records; otherwise it is
 // read from xb.  WX: another sweep follows, s_v is also written to xb.
-template <int H, int WS, int L, bool FF, bool WX>
+// BW: the reverse pass of a sweep, which has the same shape.  With the chunks of the OTHER
+// direction (a node's gradient needs those of the nodes that gathered its message, and those
+// come earlier in the other direction's level order) and the transposed weights in the order
+// f then g, a chunk is: gathered sum of da over the consumers, gated by m_v > 0; back through
+// the layers of f; + the outside gradient of s_v (read where the forward pass reads x_v) =
+// ds_v, written where the forward pass writes s_v; gated, back through the layers of g; the
+// result da_v goes where the forward pass puts the message.  ReLU and bias are replaced by the
+// stored gates, table entries are signed (no reachability flag), and every gated layer input
+// is also written to HBM as the layer's delta for the weight gradients.
+template <int H, int WS, int L, bool FF, bool WX, bool BW = false>
 __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepParams P)
 {
+    static_assert(!BW || (!FF && !WX), "the reverse pass reads its input from xb and writes no xb");
     constexpr int NW = sweep_waves(H);         // waves; wave w owns output columns [w WC, (w + 1) WC)
     constexpr int kThreads = 64 * NW;
     constexpr int NTL = H / 16, KS = H / 32;
@@ -210,7 +227,10 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     // ---- gather of a chunk: a_v = sum of neighbour messages, for rows kg and kg + 4 and this
     // wave's columns, from the wave's own part of the LDS table; written as A rows of the first
     // layer.  K entries of every row record are summed (unused entries name the zero row).
-    auto gather_fixed = [&](auto kc, int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT]) {
+    // Reverse pass: the sum is gated by bit 0 of the row's mask and kept in gs (it is the delta
+    // of f's last layer, stored when the chunk is processed).
+    auto gather_fixed = [&](auto kc, int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT],
+                            const int (&mk)[NT][TPW], float (&gs)[NT][TPW]) {
         constexpr int K = decltype(kc)::value;
 #pragma unroll
         for (int ct = 0; ct < NT; ++ct) {
@@ -226,19 +246,27 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
                     const float x = row[wc0 + 16 * t + col];
-                    s[t] = k == 0 ? fabsf(x) : s[t] + fabsf(x);
-                    if (t == 0) signs |= __float_as_uint(x);
+                    const float ax = BW ? x : fabsf(x);
+                    s[t] = k == 0 ? ax : s[t] + ax;
+                    if (!BW && t == 0) signs |= __float_as_uint(x);
                 }
             }
 #pragma unroll
-            for (int t = 0; t < TPW; ++t) put_parts(0, 4 * ct + kg, wc0 + 16 * t + col, s[t]);
+            for (int t = 0; t < TPW; ++t) {
+                if constexpr (BW) {
+                    s[t] = (mk[ct][t] & 1) ? s[t] : 0.0f;
+                    gs[ct][t] = s[t];
+                }
+                put_parts(0, 4 * ct + kg, wc0 + 16 * t + col, s[t]);
+            }
             bit[ct] = static_cast<int>(signs >> 31);
         }
     };
     // The same for a chunk in which some row has more neighbours than its record holds: that
     // row sums a list of table slots (recent sources) and node ids (sources at least three
     // chunks back, read from HBM).
-    auto gather_general = [&](int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT]) {
+    auto gather_general = [&](int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT],
+                              const int (&mk)[NT][TPW], float (&gs)[NT][TPW]) {
 #pragma unroll
         for (int ct = 0; ct < NT; ++ct) {
             bit[ct] = 0;
@@ -256,8 +284,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
                     const float x = row[wc0 + 16 * t + col];
-                    s[t] += fabsf(x);
-                    signs |= __float_as_uint(x);
+                    s[t] += BW ? x : fabsf(x);
+                    if (!BW) signs |= __float_as_uint(x);
                 }
             }
             if (listed) {
@@ -295,16 +323,16 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                                 xl[k][t] = row[wc0 + 16 * t + col];
                                 xg[k][t] = msg[static_cast<uint32_t>(v * H + wc0 + 16 * t + col)];
                             }
-                            rg[k] = reach[static_cast<uint32_t>(v)];
+                            rg[k] = BW ? 0 : reach[static_cast<uint32_t>(v)];
                         }
 #pragma unroll
                         for (int k = 0; k < PB; ++k) {
 #pragma unroll
                             for (int t = 0; t < TPW; ++t) {
-                                s[t] += fabsf(xl[k][t]) + xg[k][t];
-                                signs |= __float_as_uint(xl[k][t]);
+                                s[t] += (BW ? xl[k][t] : fabsf(xl[k][t])) + xg[k][t];
+                                if (!BW) signs |= __float_as_uint(xl[k][t]);
                             }
-                            signs |= ((u[k] >= 0) & ((u[k] == cur) | (rg[k] != 0))) ? 0x80000000u : 0u;
+                            if (!BW) signs |= ((u[k] >= 0) & ((u[k] == cur) | (rg[k] != 0))) ? 0x80000000u : 0u;
                         }
                     }
                 }
@@ -325,34 +353,41 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                             xl[k][t] = row[wc0 + 16 * t + col];
                             xg[k][t] = msg[static_cast<uint32_t>(v * H + wc0 + 16 * t + col)];
                         }
-                        rg[k] = reach[static_cast<uint32_t>(v)];
+                        rg[k] = BW ? 0 : reach[static_cast<uint32_t>(v)];
                     }
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
 #pragma unroll
                         for (int t = 0; t < TPW; ++t) {
-                            s[t] += fabsf(xl[k][t]) + xg[k][t];
-                            signs |= __float_as_uint(xl[k][t]);
+                            s[t] += (BW ? xl[k][t] : fabsf(xl[k][t])) + xg[k][t];
+                            if (!BW) signs |= __float_as_uint(xl[k][t]);
                         }
-                        signs |= ((u[k] >= 0) & ((u[k] == cur) | (rg[k] != 0))) ? 0x80000000u : 0u;
+                        if (!BW) signs |= ((u[k] >= 0) & ((u[k] == cur) | (rg[k] != 0))) ? 0x80000000u : 0u;
                     }
                 }
             }
 #pragma unroll
-            for (int t = 0; t < TPW; ++t) put_parts(0, 4 * ct + kg, wc0 + 16 * t + col, s[t]);
+            for (int t = 0; t < TPW; ++t) {
+                if constexpr (BW) {
+                    s[t] = (mk[ct][t] & 1) ? s[t] : 0.0f;
+                    gs[ct][t] = s[t];
+                }
+                put_parts(0, 4 * ct + kg, wc0 + 16 * t + col, s[t]);
+            }
             bit[ct] = static_cast<int>(signs >> 31);
         }
     };
     // w = meta.w of the chunk: most entries of a row | (a row uses the list) << 8
-    auto gather = [&](int w, int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT]) {
+    auto gather = [&](int w, int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT], const int (&mk)[NT][TPW],
+                      float (&gs)[NT][TPW]) {
         if (w <= 2)
-            gather_fixed(std::integral_constant<int, 2>{}, ntile_x, ent, bit);
+            gather_fixed(std::integral_constant<int, 2>{}, ntile_x, ent, bit, mk, gs);
         else if (w <= 5)
-            gather_fixed(std::integral_constant<int, 5>{}, ntile_x, ent, bit);
+            gather_fixed(std::integral_constant<int, 5>{}, ntile_x, ent, bit, mk, gs);
         else if (w <= kMaxEnt)
-            gather_fixed(std::integral_constant<int, kMaxEnt>{}, ntile_x, ent, bit);
+            gather_fixed(std::integral_constant<int, kMaxEnt>{}, ntile_x, ent, bit, mk, gs);
         else
-            gather_general(ntile_x, ent, bit);
+            gather_general(ntile_x, ent, bit, mk, gs);
     };
 
     // ---- software pipeline state.  m0 describes chunk c, m1 chunk c + 1.  A lane works on
@@ -367,6 +402,17 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     float x1[NT][TPW];       // ... of chunk c + 1                                  (!FF)
     int bit0[NT];            // reachability bits of the rows of chunk c
     int fid1[PFN];           // far sources of chunk c + 1
+    int mk0[NT][TPW], mk1[NT][TPW];   // (BW) gate bytes of the rows of chunk c, c + 1
+    float gs0[NT][TPW];      // (BW) gated gathered sums of chunk c: the delta of f's last layer
+    const uint8_t *mask4 = BW ? P.mask4 + static_cast<size_t>(dir) * gv.n_tot * H : nullptr;
+    float *dlt = BW ? P.delta + static_cast<size_t>(1 - dir) * P.delta_stride : nullptr;
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            mk0[ct][t] = mk1[ct][t] = 0;
+            gs0[ct][t] = 0.0f;
+        }
 #pragma unroll
     for (int ct = 0; ct < NT; ++ct) {
         const int r = 4 * ct + kg;
@@ -381,6 +427,10 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             for (int t = 0; t < TPW; ++t) {
                 x0[ct][t] = xb[static_cast<size_t>(m0.x + rr) * H + wc0 + 16 * t + col];
                 x1[ct][t] = x0[ct][t];
+                if constexpr (BW) {
+                    mk0[ct][t] = mask4[static_cast<size_t>(m0.x + rr) * H + wc0 + 16 * t + col];
+                    mk1[ct][t] = mk0[ct][t];
+                }
             }
         }
     }
@@ -390,7 +440,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         fid1[i] = (f < FCAP) ? plan.far[static_cast<size_t>(clampc(c_begin + 1)) * FCAP + f] : -1;
     }
     __syncthreads();
-    gather(m0.w, (m0.y + kTileNodes - 1) / kTileNodes, ent1, bit0);
+    gather(m0.w, (m0.y + kTileNodes - 1) / kTileNodes, ent1, bit0, mk0, gs0);
     // every load so far has returned before the loop is entered (inside the loop the compiler
     // then never waits for more than the loads of the loop's own batch)
 #pragma unroll
@@ -403,6 +453,10 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         } else {
 #pragma unroll
             for (int t = 0; t < TPW; ++t) asm volatile("" ::"v"(x0[ct][t]), "v"(x1[ct][t]));
+            if constexpr (BW) {
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) asm volatile("" ::"v"(mk0[ct][t]), "v"(mk1[ct][t]));
+            }
         }
     }
     __syncthreads();
@@ -478,6 +532,35 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         const float y1 = acc[1][t][0] + acc[1][t][1] + acc[1][t][2];
                         y += two ? 0.0f : y1;
                     }
+                    if constexpr (BW) {
+                        // delta slot of this layer's gated output: f's layers L-2 .. 0, then g's
+                        // layers L-1 .. 0; slot = index into the 2L delta arrays (f first)
+                        const uint32_t d_row = live ? static_cast<uint32_t>(vg0[ct] * H + m)
+                                                    : static_cast<uint32_t>(2 * L * gv.n_tot * H + m);
+                        auto put_delta = [&](int slot, float val) {
+                            dlt[live ? static_cast<uint32_t>(slot * gv.n_tot * H) + d_row : d_row] = val;
+                        };
+                        if (n == 0) put_delta(L - 1, gs0[ct][t]);
+                        if (n == L - 1) {                // end of f^T: ds_v = outside gradient + f path
+                            y += x0[ct][t];
+                            P.emb[static_cast<uint32_t>(v_emb * 2 * H + (1 - dir) * H + m)] = y;
+                            y = (mk0[ct][t] & 4) ? y : 0.0f;
+                            put_delta(L + L - 1, y);
+                        } else if (n < L - 1) {
+                            y = (mk0[ct][t] & 2) ? y : 0.0f;
+                            put_delta(L - 2 - n, y);
+                        } else if (n < NL - 1) {
+                            y = (mk0[ct][t] & 8) ? y : 0.0f;
+                            put_delta(L + NL - 2 - n, y);
+                        }
+                        if (n == NL - 1) {               // end of g^T: da_v
+                            msg[static_cast<uint32_t>(v_msg * H + m)] = y;
+                            msgtab[(par * CH + r) * LDM + m] = y;
+                        } else {
+                            put_parts((n + 1) & 1, r, m, y);
+                        }
+                        continue;
+                    }
                     y = fmaxf(y + bias[n][t], 0.0f);
                     if (n == L - 1) {                    // end of g: residual update of s_v
                         y += x0[ct][t];
@@ -527,7 +610,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     // that every wave has a load of this batch to wait for
                     const int u = wanted ? fid1[i] : spare_row;
                     pf[i] = *reinterpret_cast<const f32x4 *>(msg + static_cast<uint32_t>(u * H + wc0 + 4 * q));
-                    pf_reach[i] = reach[static_cast<uint32_t>(u)];   // combined with pf_cur at the end of the chunk
+                    pf_reach[i] = BW ? 0 : reach[static_cast<uint32_t>(u)];   // combined with pf_cur at the end of the chunk
                     pf_cur[i] = wanted && u == cur;
                 }
                 if constexpr (FF) {
@@ -555,8 +638,11 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         ft0[ct] = *reinterpret_cast<const f32x4 *>(featb + m1.x + static_cast<uint32_t>(rr));
                     } else {
 #pragma unroll
-                        for (int t = 0; t < TPW; ++t)
+                        for (int t = 0; t < TPW; ++t) {
                             x1[ct][t] = (xb + static_cast<size_t>(m1.x) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
+                            if constexpr (BW)
+                                mk1[ct][t] = (mask4 + static_cast<size_t>(m1.x) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
+                        }
                     }
                 }
 #pragma unroll
@@ -569,11 +655,13 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             if (n == NL - 1) {
                 // Behind the last layer's matrix instructions: the reachability bits of this
                 // chunk's nodes go to HBM and the far messages of the next chunk into the table.
+                if constexpr (!BW) {
 #pragma unroll
-                for (int ct = 0; ct < NT; ++ct) {
-                    const int r = ct * kTileNodes + kg;
-                    reach[static_cast<uint32_t>((wave == 0 && col == 0 && r < rows) ? vg0[ct] : sink_row)] =
-                        static_cast<uint8_t>(bit0[ct]);
+                    for (int ct = 0; ct < NT; ++ct) {
+                        const int r = ct * kTileNodes + kg;
+                        reach[static_cast<uint32_t>((wave == 0 && col == 0 && r < rows) ? vg0[ct] : sink_row)] =
+                            static_cast<uint8_t>(bit0[ct]);
+                    }
                 }
                 // Wait for this wave's prefetch batch whether or not a lane uses it: the stores
                 // that preceded it are then complete too (see the note at the prefetch).
@@ -588,6 +676,10 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     } else {
 #pragma unroll
                         for (int t = 0; t < TPW; ++t) asm volatile("" ::"v"(x1[ct][t]));
+                        if constexpr (BW) {
+#pragma unroll
+                            for (int t = 0; t < TPW; ++t) asm volatile("" ::"v"(mk1[ct][t]));
+                        }
                     }
                 }
                 if (has_next) {
@@ -603,7 +695,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         const int f = e / QW, q = e - f * QW;
                         if (f < m1.z) {
                             const int slot = RING * CH + (par ^ 1) * FCAP + f;
-                            const uint32_t flag = ((pf_reach[i] != 0) | pf_cur[i]) ? 0x80000000u : 0u;
+                            const uint32_t flag = (!BW && ((pf_reach[i] != 0) | pf_cur[i])) ? 0x80000000u : 0u;
                             f32x4 v;
 #pragma unroll
                             for (int k = 0; k < 4; ++k) v[k] = __uint_as_float(__float_as_uint(pf[i][k]) | flag);
@@ -618,7 +710,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
 
             // The table rows that chunk c + 1 sums were all written by this wave (its own
             // columns), so its gather follows without a barrier.
-            if (n == NL - 1 && has_next) gather(m1.w, (m1.y + kTileNodes - 1) / kTileNodes, ent1, bit0);
+            if (n == NL - 1 && has_next) gather(m1.w, (m1.y + kTileNodes - 1) / kTileNodes, ent1, bit0, mk1, gs0);
             lds_barrier();
         }
 
@@ -630,6 +722,10 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             if constexpr (!FF) {
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) x0[ct][t] = x1[ct][t];
+            }
+            if constexpr (BW) {
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) mk0[ct][t] = mk1[ct][t];
             }
         }
     }
@@ -658,8 +754,11 @@ __global__ __launch_bounds__(256) void k_bucket_feats(GraphView gv, const float 
 // Index: ((((dir * 2L + n) * MT + mt) * KS + ks) * WS + ws) * 64 + lane, n = g layers then f
 // layers; lane l holds W[32 ks + 8 (l / 16) + i][16 mt + l % 16], i = 0..7, as bf16 part ws
 // of the exact three-way split (ws = 0 only when the weights are bf16 already).
+// With `reverse`, the fragments of the reverse pass: index dir is the direction whose chunks are
+// walked, the weights are those of the other direction, transposed, f's layers from the last to
+// the first and then g's (biases are not used there).
 void pack_sweep_weights(const ModelView &mv, const float *blob, int WS, std::vector<uint16_t> *frag,
-                        std::vector<float> *bias)
+                        std::vector<float> *bias, bool reverse)
 {
     const int H = mv.H, L = mv.L, MT = H / 16, KS = H / 32, NL = 2 * L;
     frag->assign(static_cast<size_t>(2) * NL * MT * KS * WS * 64 * 8, 0);
@@ -678,14 +777,17 @@ void pack_sweep_weights(const ModelView &mv, const float *blob, int WS, std::vec
     };
     for (int dir = 0; dir < 2; ++dir)
         for (int n = 0; n < NL; ++n) {
-            const LayerRef &lr = (n < L) ? mv.g[dir].layer[n] : mv.f[dir].layer[n - L];
-            for (int h = 0; h < H; ++h) (*bias)[(static_cast<size_t>(dir) * NL + n) * H + h] = blob[lr.b + h];
+            const LayerRef &lr = reverse ? ((n < L) ? mv.f[1 - dir].layer[L - 1 - n] : mv.g[1 - dir].layer[NL - 1 - n])
+                                         : ((n < L) ? mv.g[dir].layer[n] : mv.f[dir].layer[n - L]);
+            for (int h = 0; h < H; ++h)
+                (*bias)[(static_cast<size_t>(dir) * NL + n) * H + h] = reverse ? 0.0f : blob[lr.b + h];
             for (int mt = 0; mt < MT; ++mt)
                 for (int ks = 0; ks < KS; ++ks)
                     for (int lane = 0; lane < 64; ++lane)
                         for (int i = 0; i < 8; ++i) {
                             const int k = 32 * ks + 8 * (lane / 16) + i, m = 16 * mt + lane % 16;
-                            float rest = blob[lr.w + static_cast<size_t>(k) * H + m];
+                            float rest = reverse ? blob[lr.w + static_cast<size_t>(m) * H + k]
+                                                 : blob[lr.w + static_cast<size_t>(k) * H + m];
                             for (int ws = 0; ws < WS; ++ws) {
                                 const uint16_t part = to_bf16(rest);
                                 rest -= from_bf16(part);
@@ -710,7 +812,7 @@ void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace
 {
     if (gv.B == 0) return;
     SweepParams P{gv, wfrag, bias, ws.emb, ws.xb, ws.msg, ws.reach, fa.cur_node,
-                  ws.featb, first_sweep ? mv.blob + mv.proj.w : nullptr, mv.D};
+                  ws.featb, first_sweep ? mv.blob + mv.proj.w : nullptr, mv.D, nullptr, nullptr, 0};
     if (first_sweep)
         hipLaunchKernelGGL(k_bucket_feats, dim3((gv.n_tot + 255) / 256), dim3(256), 0, s, gv, fa.node_feats,
                            fa.placement, fa.cur_node, mv.D, ws.featb);
@@ -727,6 +829,29 @@ void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace
         else                                                                     \
             hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, false, false>), grid, block, 0, s, P); \
         return;                                                                  \
+    }
+    PL_CASE(128, 1, 2) PL_CASE(128, 1, 1)
+    PL_CASE(64, 1, 2) PL_CASE(64, 1, 1) PL_CASE(64, 3, 2) PL_CASE(64, 3, 1)
+    PL_CASE(32, 1, 2) PL_CASE(32, 1, 1) PL_CASE(32, 3, 2) PL_CASE(32, 3, 1)
+#undef PL_CASE
+}
+
+// The reverse pass of one sweep in both directions (see BW at the kernel).  demb [n_tot + 1, 2H]
+// holds the outside gradient of every state on entry (also given in bucket order in extb) and the
+// gradient of the sweep's input on return; dagg [2 n_tot + 2, H] must have its row 2 n_tot zero.
+void launch_sweep_mfma_bw(const GraphView &gv, const ModelView &mv, const uint4 *wfrag, const float *bias,
+                          int WS, const int32_t *cur_node, float *demb, float *extb, float *dagg,
+                          const uint8_t *mask4, float *delta, size_t delta_stride, hipStream_t s)
+{
+    if (gv.B == 0) return;
+    SweepParams P{gv, wfrag, bias, demb, extb, dagg, nullptr, cur_node, nullptr, nullptr, mv.D,
+                  mask4, delta, delta_stride};
+    const dim3 grid(2 * gv.B);
+#define PL_CASE(HH, WW, LL)                                                                  \
+    if (mv.H == HH && WS == WW && mv.L == LL) {                                              \
+        hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, false, false, true>), grid,             \
+                           dim3(64 * sweep_waves(HH)), 0, s, P);                             \
+        return;                                                                              \
     }
     PL_CASE(128, 1, 2) PL_CASE(128, 1, 1)
     PL_CASE(64, 1, 2) PL_CASE(64, 1, 1) PL_CASE(64, 3, 2) PL_CASE(64, 3, 1)
