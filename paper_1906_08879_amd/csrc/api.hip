@@ -245,6 +245,9 @@ void free_grad_workspace(GradWorkspace &gw)
     for (float *p : all) (void)hipFree(p);
     (void)hipFree(gw.cls);
     (void)hipFree(gw.mask4);
+    (void)hipFree(gw.counts);
+    (void)hipFree(gw.blk_cnt);
+    (void)hipFree(gw.lists);
     gw = GradWorkspace();
 }
 
@@ -315,6 +318,9 @@ int ensure_grad_workspace(pl_graph_batch *g, const ModelView &mv)
     PL_HIP(take(&gw.dx, NH));
     PL_HIP(take(&gw.phi, n * mv.F));
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.cls), n + 16));
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.counts), 64));
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.blk_cnt), sizeof(int32_t) * (3 * ((n + 255) / 256) + 4)));
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.lists), sizeof(int32_t) * (3 * n + 4)));
     PL_HIP(take(&gw.pooled, 3 * BG * H));
     PL_HIP(take(&gw.dP, 3 * BG * H));
     PL_HIP(take(&gw.hin, 3 * BG * H));

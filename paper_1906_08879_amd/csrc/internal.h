@@ -193,6 +193,9 @@ struct GradWorkspace {
     float *dx = nullptr;                      // [n_tot, H] delta of the projection
     float *phi = nullptr;                     // [n_tot, F] raw feature rows
     uint8_t *cls = nullptr;                   // [n_tot] node set of every node
+    int32_t *counts = nullptr;                // [4] sizes of the three node sets
+    int32_t *blk_cnt = nullptr;               // [ceil(n_tot / 256), 3] per-block counts, then offsets
+    int32_t *lists = nullptr;                 // [3, n_tot] nodes of each set
     float *pooled = nullptr, *dP = nullptr;   // [B, 3, G, H]
     float *hin = nullptr;                     // [3, B G, H] inputs of h per set
     float *hact = nullptr, *dh = nullptr;     // [3, L, B G, H]

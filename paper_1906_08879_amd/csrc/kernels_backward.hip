@@ -17,6 +17,8 @@
 //              layer input x layer delta, done by one kernel in slabs with a fixed summation
 //              order (no atomics).
 // All arithmetic is fp32 vector FMAs; any H <= 256, D <= 16, 1..4 layers, k <= 1 sweeps.
+#include <algorithm>
+
 #include "internal.h"
 
 namespace pl {
@@ -525,6 +527,7 @@ __global__ __launch_bounds__(kThreads) void k_bw_prep(GraphView gv, int H, int L
                                                       const float *__restrict__ demb,
                                                       const float *__restrict__ fact,
                                                       const float *__restrict__ gact,
+                                                      const float *__restrict__ msgs,
                                                       float *__restrict__ extb,
                                                       uint8_t *__restrict__ mask4)
 {
@@ -535,7 +538,10 @@ __global__ __launch_bounds__(kThreads) void k_bw_prep(GraphView gv, int H, int L
         const int sd = 1 - pd;
         const size_t at = (static_cast<size_t>(pd) * gv.n_tot + gv.pos[pd][v]) * H + h;
         extb[at] = demb[static_cast<size_t>(v) * 2 * H + sd * H + h];
-        int bits = fact[slab(sd, L - 1, L, gv.n_tot, H) + idx] > 0.0f ? 1 : 0;
+        // m_v: from the forward pass's message buffer [2, n_tot, H] when given, else recomputed
+        const float m = msgs ? msgs[static_cast<size_t>(sd) * gv.n_tot * H + idx]
+                             : fact[slab(sd, L - 1, L, gv.n_tot, H) + idx];
+        int bits = m > 0.0f ? 1 : 0;
         bits |= gact[slab(sd, L - 1, L, gv.n_tot, H) + idx] > 0.0f ? 4 : 0;
         if (L == 2) {
             bits |= fact[slab(sd, 0, L, gv.n_tot, H) + idx] > 0.0f ? 2 : 0;
@@ -605,6 +611,263 @@ __global__ __launch_bounds__(kThreads) void k_bw_phi(GraphView gv, ModelView mv,
     phi[idx] = p;
 }
 
+// ------------------------------------------------------------------ dense layers on the matrix cores
+// Y[row][j] = epi(bias[j] + sum_k X[row][k] W[k][j]) for a list of rows, H in {32, 64, 128} output
+// columns (NJ tiles of 32) and K a multiple of 32, in fp32 on v_mfma_f32_32x32x2_f32.
+// A workgroup of four waves takes 128 rows; wave w multiplies rows 32 w .. 32 w + 31 by all
+// columns.  X and W go through LDS in chunks of 32 k, double buffered: the global loads of chunk
+// c + 1 (128-byte row pieces of X, whole rows of W: all coalesced) are issued before the 64
+// matrix instructions of chunk c and written to the other buffer after them; one barrier per
+// chunk.  Lane (row l % 32, half l / 32) of an instruction takes k = 2 s + half: the A operand
+// X[row][k] is read with row stride 33 and the B operand W[k][32 jb + l % 32] with row stride
+// H + 32, which keeps the two halves of a wave on different LDS banks.
+// epi: optional ReLU, optional gate (Y = 0 where M[row][j] <= 0).  rows / n_rows_dev: optional row
+// list and its length in device memory (the grid covers R rows; workgroups past the length exit).
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4v;
+
+constexpr int kDenseKC = 32;                  // k per chunk
+constexpr int kDenseRows = 128;               // rows per workgroup
+constexpr int kDenseLdx = kDenseKC + 1;       // LDS row stride of the X chunk
+
+constexpr size_t dense_lds_bytes(int NJ)
+{
+    return sizeof(float) * 2 * (kDenseRows * kDenseLdx + kDenseKC * (32 * NJ + 32));
+}
+
+template <int NJ>
+__global__ __launch_bounds__(kThreads) void k_dense_mfma(const float *__restrict__ X, int ldx,
+                                                         const int32_t *__restrict__ rows,
+                                                         const int32_t *__restrict__ n_rows_dev, int R, int K,
+                                                         const float *__restrict__ W, int ldw,
+                                                         const float *__restrict__ bias, int relu,
+                                                         const float *__restrict__ M, int ldm,
+                                                         float *__restrict__ Y, int ldy)
+{
+    constexpr int Hc = 32 * NJ, LDW = Hc + 32;
+    constexpr int WQ = kDenseKC * Hc / 4 / kThreads;      // float4 of a W chunk per thread: 1, 2 or 4
+    extern __shared__ float lds[];
+    float *xs = lds;                                       // [2][kDenseRows][kDenseLdx]
+    float *wsh = lds + 2 * kDenseRows * kDenseLdx;         // [2][kDenseKC][LDW]
+    if (n_rows_dev) R = min(R, *n_rows_dev);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lk = lane >> 5;
+    const int tile0 = blockIdx.x * kDenseRows;
+    if (tile0 >= R) return;                                // the whole workgroup, before any barrier
+
+    // this thread's share of a chunk: four pieces of X rows (row xr + 32 q, floats xc .. xc + 3)
+    const int xr = tid >> 3, xc = (tid & 7) * 4;
+    const float *xsrc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int r = min(tile0 + xr + 32 * q, R - 1);
+        xsrc[q] = X + static_cast<size_t>(rows ? rows[r] : r) * ldx + xc;
+    }
+    f32x4v xreg[4], wreg[WQ];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) xreg[q] = *reinterpret_cast<const f32x4v *>(xsrc[q] + k0);
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) {
+            const int e = (tid + kThreads * q) * 4, kk = e / Hc, c = e - kk * Hc;
+            wreg[q] = *reinterpret_cast<const f32x4v *>(W + static_cast<size_t>(k0 + kk) * ldw + c);
+        }
+    };
+    auto stash = [&](int buf) {
+        float *xd = xs + buf * kDenseRows * kDenseLdx;
+        float *wd = wsh + buf * kDenseKC * LDW;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xd[(xr + 32 * q) * kDenseLdx + xc + i] = xreg[q][i];
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) {
+            const int e = (tid + kThreads * q) * 4, kk = e / Hc, c = e - kk * Hc;
+            *reinterpret_cast<f32x4v *>(wd + kk * LDW + c) = wreg[q];
+        }
+    };
+
+    f32x16 acc[NJ];
+#pragma unroll
+    for (int jb = 0; jb < NJ; ++jb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[jb][v] = 0.0f;
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    const int n_chunks = K / kDenseKC;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < n_chunks) fetch((c + 1) * kDenseKC);
+        const float *xa = xs + buf * kDenseRows * kDenseLdx + (32 * wave + li) * kDenseLdx + lk;
+        const float *wb = wsh + buf * kDenseKC * LDW + lk * LDW + li;
+#pragma unroll
+        for (int st = 0; st < kDenseKC / 2; ++st) {
+            const float a = xa[2 * st];
+#pragma unroll
+            for (int jb = 0; jb < NJ; ++jb)
+                acc[jb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, wb[2 * st * LDW + 32 * jb], acc[jb], 0, 0, 0);
+        }
+        if (c + 1 < n_chunks) stash(buf ^ 1);
+        __syncthreads();
+    }
+
+    float bj[NJ];
+#pragma unroll
+    for (int jb = 0; jb < NJ; ++jb) bj[jb] = bias ? bias[32 * jb + li] : 0.0f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int r = tile0 + 32 * wave + 8 * (v / 4) + 4 * lk + (v % 4);
+        const bool ok = r < R;
+        const int rc = min(r, R - 1);
+        const int orow = rows ? rows[rc] : rc;
+#pragma unroll
+        for (int jb = 0; jb < NJ; ++jb) {
+            float y = acc[jb][v] + bj[jb];
+            if (relu) y = fmaxf(y, 0.0f);
+            if (M) y = M[static_cast<size_t>(orow) * ldm + 32 * jb + li] > 0.0f ? y : 0.0f;
+            if (ok) Y[static_cast<size_t>(orow) * ldy + 32 * jb + li] = y;
+        }
+    }
+}
+
+// a_v = sum of the neighbours' messages, for every node and both directions (grid.y).
+__global__ __launch_bounds__(kThreads) void k_bw_agg(GraphView gv, int H,
+                                                     const float *__restrict__ msgs,
+                                                     float *__restrict__ agg)
+{
+    const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (idx >= static_cast<size_t>(gv.n_tot) * H) return;
+    const int dir = blockIdx.y;
+    const int v = static_cast<int>(idx / H), h = static_cast<int>(idx - static_cast<size_t>(v) * H);
+    const float *msg = msgs + static_cast<size_t>(dir) * gv.n_tot * H;   // [2, n_tot, H] from the forward pass
+    const int32_t *nbr_ptr = gv.nbr_ptr[dir], *nbr_idx = gv.nbr_idx[dir];
+    float a = 0.0f;
+    for (int p = nbr_ptr[v]; p < nbr_ptr[v + 1]; ++p) a += msg[static_cast<size_t>(nbr_idx[p]) * H + h];
+    agg[static_cast<size_t>(dir) * gv.n_tot * H + idx] = a;
+}
+
+// Node set of every node and the three sets as row lists in ascending node order, in three
+// steps with no atomics (the lists fix the summation order of l's weight gradients): per block
+// of 256 nodes the number of nodes of each set; an exclusive scan over the blocks; the fill.
+// The first step also copies the gradient of e_{v*} from dz.
+__device__ __forceinline__ int node_class_of(const GraphView &gv, int v, const uint8_t *reach,
+                                             const int32_t *cur_node, int *graph)
+{
+    const int b = gv.node_graph[v];
+    const int n0 = gv.node_off[b], n_b = gv.node_off[b + 1] - n0;
+    const int cl = cur_node[b];
+    const int cur = (cl >= 0 && cl < n_b) ? n0 + cl : -1;
+    *graph = b;
+    return node_class_bw(v, cur, reach, gv.n_tot);
+}
+
+__global__ __launch_bounds__(kThreads) void k_bw_cls_count(GraphView gv, int H, int Z,
+                                                           const uint8_t *__restrict__ reach,
+                                                           const int32_t *__restrict__ cur_node,
+                                                           const float *__restrict__ dz,
+                                                           uint8_t *__restrict__ cls,
+                                                           int32_t *__restrict__ blk_cnt,
+                                                           float *__restrict__ demb)
+{
+    __shared__ int wcnt[4][3];
+    const int v = blockIdx.x * kThreads + threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int k = -1, b = 0;
+    if (v < gv.n_tot) {
+        k = node_class_of(gv, v, reach, cur_node, &b);
+        cls[v] = static_cast<uint8_t>(k);
+    }
+    for (int c = 1; c <= 3; ++c) {
+        const unsigned long long m = __ballot(k == c);
+        if (lane == 0) wcnt[wave][c - 1] = __popcll(m);
+    }
+    __syncthreads();
+    if (threadIdx.x < 3)
+        blk_cnt[blockIdx.x * 3 + threadIdx.x] = wcnt[0][threadIdx.x] + wcnt[1][threadIdx.x] +
+                                                wcnt[2][threadIdx.x] + wcnt[3][threadIdx.x];
+    if (k == 0)
+        for (int i = 0; i < 2 * H; ++i) demb[static_cast<size_t>(v) * 2 * H + i] = dz[static_cast<size_t>(b) * Z + i];
+}
+
+// One workgroup: blk_cnt[blk][c] becomes the position of the block's first node of set c in
+// list c; counts[c] = size of set c.
+__global__ __launch_bounds__(kThreads) void k_bw_cls_scan(int n_blocks, int32_t *__restrict__ blk_cnt,
+                                                          int32_t *__restrict__ counts)
+{
+    __shared__ int part[kThreads][3];
+    const int tid = threadIdx.x;
+    const int per = (n_blocks + kThreads - 1) / kThreads;
+    const int lo = min(n_blocks, tid * per), hi = min(n_blocks, lo + per);
+    int sum[3] = {0, 0, 0};
+    for (int i = lo; i < hi; ++i)
+        for (int c = 0; c < 3; ++c) sum[c] += blk_cnt[i * 3 + c];
+    for (int c = 0; c < 3; ++c) part[tid][c] = sum[c];
+    __syncthreads();
+    if (tid < 3) {
+        int run = 0;
+        for (int t = 0; t < kThreads; ++t) {
+            const int x = part[t][tid];
+            part[t][tid] = run;
+            run += x;
+        }
+        counts[tid] = run;
+    }
+    __syncthreads();
+    int run[3] = {part[tid][0], part[tid][1], part[tid][2]};
+    for (int i = lo; i < hi; ++i)
+        for (int c = 0; c < 3; ++c) {
+            const int x = blk_cnt[i * 3 + c];
+            blk_cnt[i * 3 + c] = run[c];
+            run[c] += x;
+        }
+}
+
+__global__ __launch_bounds__(kThreads) void k_bw_cls_fill(GraphView gv, const uint8_t *__restrict__ cls,
+                                                          const int32_t *__restrict__ blk_off,
+                                                          int32_t *__restrict__ lists)
+{
+    __shared__ int wcnt[4][3];
+    const int v = blockIdx.x * kThreads + threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k = v < gv.n_tot ? cls[v] : -1;
+    int before = 0;
+    for (int c = 1; c <= 3; ++c) {
+        const unsigned long long m = __ballot(k == c);
+        if (lane == 0) wcnt[wave][c - 1] = __popcll(m);
+        if (k == c) before = __popcll(m & ((1ull << lane) - 1));
+    }
+    __syncthreads();
+    if (k >= 1) {
+        int pos = blk_off[blockIdx.x * 3 + k - 1] + before;
+        for (int w = 0; w < wave; ++w) pos += wcnt[w][k - 1];
+        lists[static_cast<size_t>(k - 1) * gv.n_tot + pos] = v;
+    }
+}
+
+// Delta of l's last layer for the rows of one set: dP[set][device of the node], gated by the
+// layer's output; zero for a node whose device id is out of range (it was pooled nowhere).
+__global__ __launch_bounds__(kThreads) void k_bw_pool_seed(GraphView gv, int H, int G, int D, int set,
+                                                           const int32_t *__restrict__ list,
+                                                           const int32_t *__restrict__ count,
+                                                           const int32_t *__restrict__ placement,
+                                                           const float *__restrict__ dP,
+                                                           const float *__restrict__ act,
+                                                           float *__restrict__ dl)
+{
+    const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    const int r = static_cast<int>(idx / H), h = static_cast<int>(idx - static_cast<size_t>(r) * H);
+    if (r >= *count) return;
+    const int v = list[r];
+    const int b = gv.node_graph[v];
+    const int dev = placement[v];
+    const bool ok = dev >= 0 && dev < D;
+    const float g = ok ? dP[((static_cast<size_t>(b) * 3 + set) * G + (G == 1 ? 0 : dev)) * H + h] : 0.0f;
+    const size_t at = static_cast<size_t>(v) * H + h;
+    dl[at] = act[at] > 0.0f ? g : 0.0f;
+}
+
 // ------------------------------------------------------------------ 5. weight gradients
 // partial[slab][i * J + j] = sum over the slab's rows r of A[r][i] * Dl[r][j]  (i in this
 // workgroup's block of kWgI), partial[slab][I * J + j] = sum of Dl[r][j] (the bias).  Rows whose
@@ -616,6 +879,7 @@ __global__ __launch_bounds__(kThreads) void k_wgrad(const float *__restrict__ A,
                                                     int R, int I, int J, int rows_per_slab,
                                                     float *__restrict__ partial)
 {
+    // (the matrix-core version below takes a row list instead of the class filter)
     __shared__ float a_s[kWgRB][kWgI];
     __shared__ int ok_s[kWgRB];
     __shared__ float red[kThreads * (kWgI + 1)];
@@ -675,22 +939,22 @@ __global__ __launch_bounds__(kThreads) void k_wgrad(const float *__restrict__ A,
 // memory, 32 consecutive floats per half wave (no LDS, no split into bf16 parts).  Wave w of a
 // workgroup owns rows [32 (4 blockIdx.x + w), +32) of the weight matrix and all J columns
 // (NJ accumulator tiles); lanes 0-31 take even rows of the slab, lanes 32-63 odd rows.
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-
 template <int NJ>
 __global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict__ A, int lda,
                                                          const float *__restrict__ Dl, int ldd,
-                                                         const uint8_t *__restrict__ row_cls, int want,
+                                                         const int32_t *__restrict__ rows,
+                                                         const int32_t *__restrict__ n_rows_dev,
                                                          int R, int I, int rows_per_slab,
                                                          float *__restrict__ partial)
 {
     constexpr int J = 32 * NJ;
-    constexpr int U = 4;                       // row pairs in flight
+    constexpr int U = 4;                       // row pairs per step
+    if (n_rows_dev) R = min(R, *n_rows_dev);   // slabs past the list's end write zeros
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 31, lk = lane >> 5;
     const int ib = blockIdx.x * 4 + wave, sl = blockIdx.y;
     if (ib * 32 >= I) return;                  // no barrier in this kernel
-    const int r_beg = sl * rows_per_slab, r_end = min(R, r_beg + rows_per_slab);
+    const int r_beg = min(R, sl * rows_per_slab), r_end = min(R, r_beg + rows_per_slab);
     f32x16 acc[NJ];
 #pragma unroll
     for (int jb = 0; jb < NJ; ++jb)
@@ -701,27 +965,40 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict
     for (int jb = 0; jb < NJ; ++jb) bsum[jb] = 0.0f;
     const float *Acol = A + ib * 32 + li;
     const float *Dcol = Dl + li;
-    for (int r0 = r_beg; r0 < r_end; r0 += 2 * U) {
-        float a[U], bq[U][NJ];
-        bool ok[U];
+    float a[U], bq[U][NJ];
+    // operands of rows r0 .. r0 + 2U - 1; rows past the slab's end give zeros (read from row 0)
+    auto fetch = [&](int r0, float (&fa)[U], float (&fb)[U][NJ]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int row = r0 + 2 * u + lk;
-            const int rc = min(row, R - 1);
-            ok[u] = row < r_end && (!row_cls || row_cls[rc] == want);
-            a[u] = Acol[static_cast<size_t>(rc) * lda];
-#pragma unroll
-            for (int jb = 0; jb < NJ; ++jb) bq[u][jb] = Dcol[static_cast<size_t>(rc) * ldd + 32 * jb];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float au = ok[u] ? a[u] : 0.0f;
+            const bool ok = row < r_end;
+            const int rc = ok ? row : 0;
+            const int src = rows ? (ok ? rows[rc] : 0) : rc;
+            const float av = Acol[static_cast<size_t>(src) * lda];
+            fa[u] = ok ? av : 0.0f;
 #pragma unroll
             for (int jb = 0; jb < NJ; ++jb) {
-                const float bu = ok[u] ? bq[u][jb] : 0.0f;
-                acc[jb] = __builtin_amdgcn_mfma_f32_32x32x2f32(au, bu, acc[jb], 0, 0, 0);
-                bsum[jb] += bu;
+                const float bv = Dcol[static_cast<size_t>(src) * ldd + 32 * jb];
+                fb[u][jb] = ok ? bv : 0.0f;
             }
+        }
+    };
+    if (r_beg < r_end) fetch(r_beg, a, bq);
+    for (int r0 = r_beg; r0 < r_end; r0 += 2 * U) {
+        float an[U], bn[U][NJ];
+        fetch(r0 + 2 * U, an, bn);             // the next step's operands travel during this step
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int jb = 0; jb < NJ; ++jb) {
+                acc[jb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], bq[u][jb], acc[jb], 0, 0, 0);
+                bsum[jb] += bq[u][jb];
+            }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a[u] = an[u];
+#pragma unroll
+            for (int jb = 0; jb < NJ; ++jb) bq[u][jb] = bn[u][jb];
         }
     }
     float *dst = partial + static_cast<size_t>(sl) * (static_cast<size_t>(I) * J + J);
@@ -737,15 +1014,25 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict
     }
 }
 
-// out[idx] += sum over slabs, in slab order.
+// out[idx] += sum over slabs.  A workgroup takes 32 consecutive entries; its eight thread rows
+// each add the slabs q, q + 8, ... in order, and the eight sums are added in order: a fixed
+// summation order with enough loads in flight.
 __global__ __launch_bounds__(kThreads) void k_wgrad_reduce(const float *__restrict__ partial, int n_slabs,
                                                            size_t count, float *__restrict__ out)
 {
-    const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (idx >= count) return;
+    __shared__ float part[8][32];
+    const int c = threadIdx.x & 31, q = threadIdx.x >> 5;
+    const size_t idx = static_cast<size_t>(blockIdx.x) * 32 + c;
     float s = 0.0f;
-    for (int sl = 0; sl < n_slabs; ++sl) s += partial[static_cast<size_t>(sl) * count + idx];
-    out[idx] += s;
+    if (idx < count)
+        for (int sl = q; sl < n_slabs; sl += 8) s += partial[static_cast<size_t>(sl) * count + idx];
+    part[q][c] = s;
+    __syncthreads();
+    if (q == 0 && idx < count) {
+        float t = part[0][c];
+        for (int k = 1; k < 8; ++k) t += part[k][c];
+        out[idx] += t;
+    }
 }
 
 __global__ __launch_bounds__(kThreads) void k_fill_zero(float *__restrict__ p, size_t n)
@@ -780,6 +1067,14 @@ void allow_lds_bw(K kernel, size_t bytes)
         default: { CALL(16); break; } \
     }
 
+// the matrix-core contraction wants about four workgroups per CU
+int wgrad_rows_per_slab_cores(int64_t R)
+{
+    int64_t per = (R + 1023) / 1024;
+    if (per < 64) per = 64;
+    return static_cast<int>((per + 7) / 8 * 8);
+}
+
 int wgrad_rows_per_slab(int64_t R)
 {
     int64_t per = (R + 383) / 384;
@@ -791,8 +1086,9 @@ int wgrad_rows_per_slab(int64_t R)
 
 size_t wgrad_partial_floats(int64_t R, int I, int J)
 {
-    const int per = wgrad_rows_per_slab(R);
-    const int64_t slabs = R > 0 ? (R + per - 1) / per : 0;
+    if (R <= 0) return 0;
+    const int per_a = wgrad_rows_per_slab(R), per_b = wgrad_rows_per_slab_cores(R);
+    const int64_t slabs = std::max((R + per_a - 1) / per_a, (R + per_b - 1) / per_b);
     return static_cast<size_t>(slabs) * (static_cast<size_t>(I) * J + J);
 }
 
@@ -804,32 +1100,58 @@ void launch_fill_zero(float *p, size_t n, hipStream_t s)
 }
 
 void launch_wgrad(const float *A, int lda, const float *Dl, int ldd, const uint8_t *row_cls, int want,
-                  int64_t R, const LayerRef &ly, float *partial, float *grad, int generic, hipStream_t s)
+                  const int32_t *list, const int32_t *list_count, int64_t R, const LayerRef &ly, float *partial,
+                  float *grad, int generic, hipStream_t s)
 {
     if (R <= 0) return;
     const int I = ly.n_in, J = ly.n_out;
-    const int per = wgrad_rows_per_slab(R);
-    const int slabs = static_cast<int>((R + per - 1) / per);
     const bool cores = generic == 0 && I % 32 == 0 && (J == 32 || J == 64 || J == 128);
+    const int per = cores ? wgrad_rows_per_slab_cores(R) : wgrad_rows_per_slab(R);
+    const int slabs = static_cast<int>((R + per - 1) / per);
     if (cores) {
+        // with a row list (the nodes of one set, ascending) the class filter is not needed
         const dim3 grid((I + 127) / 128, slabs);
         if (J == 32)
-            hipLaunchKernelGGL(k_wgrad_mfma<1>, grid, dim3(kThreads), 0, s, A, lda, Dl, ldd, row_cls, want,
+            hipLaunchKernelGGL(k_wgrad_mfma<1>, grid, dim3(kThreads), 0, s, A, lda, Dl, ldd, list, list_count,
                                static_cast<int>(R), I, per, partial);
         else if (J == 64)
-            hipLaunchKernelGGL(k_wgrad_mfma<2>, grid, dim3(kThreads), 0, s, A, lda, Dl, ldd, row_cls, want,
+            hipLaunchKernelGGL(k_wgrad_mfma<2>, grid, dim3(kThreads), 0, s, A, lda, Dl, ldd, list, list_count,
                                static_cast<int>(R), I, per, partial);
         else
-            hipLaunchKernelGGL(k_wgrad_mfma<4>, grid, dim3(kThreads), 0, s, A, lda, Dl, ldd, row_cls, want,
+            hipLaunchKernelGGL(k_wgrad_mfma<4>, grid, dim3(kThreads), 0, s, A, lda, Dl, ldd, list, list_count,
                                static_cast<int>(R), I, per, partial);
     } else {
         hipLaunchKernelGGL(k_wgrad, dim3((I + kWgI - 1) / kWgI, slabs), dim3(kThreads), 0, s, A, lda, Dl, ldd,
                            row_cls, want, static_cast<int>(R), I, J, per, partial);
     }
     const size_t count = static_cast<size_t>(I) * J + J;
-    hipLaunchKernelGGL(k_wgrad_reduce, dim3(static_cast<unsigned>((count + kThreads - 1) / kThreads)),
-                       dim3(kThreads), 0, s, partial, slabs, count, grad + ly.w);
+    hipLaunchKernelGGL(k_wgrad_reduce, dim3(static_cast<unsigned>((count + 31) / 32)), dim3(kThreads), 0, s,
+                       partial, slabs, count, grad + ly.w);
 }
+
+namespace {
+
+struct DenseCall {
+    const float *X; int ldx;
+    const int32_t *rows; const int32_t *n_rows_dev; int R; int K;
+    const float *W; int ldw; const float *bias; int relu;
+    const float *M; int ldm;
+    float *Y; int ldy;
+};
+
+void launch_dense(const DenseCall &c, int H, hipStream_t s)
+{
+    if (c.R <= 0) return;
+    const dim3 grid((c.R + kDenseRows - 1) / kDenseRows);
+#define CALL(NJ)                                                                                             \
+    allow_lds_bw(k_dense_mfma<NJ>, dense_lds_bytes(NJ));                                                     \
+    hipLaunchKernelGGL(k_dense_mfma<NJ>, grid, dim3(kThreads), dense_lds_bytes(NJ), s, c.X, c.ldx, c.rows,   \
+                       c.n_rows_dev, c.R, c.K, c.W, c.ldw, c.bias, c.relu, c.M, c.ldm, c.Y, c.ldy)
+    if (H == 32) { CALL(1); } else if (H == 64) { CALL(2); } else { CALL(4); }
+#undef CALL
+}
+
+}  // namespace
 
 void launch_backward_generic(const GraphView &gv, const ModelView &mv, const float *blob_t,
                              const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
@@ -856,8 +1178,34 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
         PL_DISPATCH_RPT(rpt, CALL)
 #undef CALL
     }
+    // matrix-core dense layers: every output width of the embedding networks is H
+    const bool dense = generic == 0 && (H == 32 || H == 64 || H == 128);
     // 2. pooling
-    {
+    if (dense) {
+        const int n_blocks = (n + kThreads - 1) / kThreads;
+        hipLaunchKernelGGL(k_bw_cls_count, dim3(n_blocks), dim3(kThreads), 0, s, gv, H, mv.Z, ws.reach, fa.cur_node,
+                           gw.dz, gw.cls, gw.blk_cnt, gw.demb);
+        hipLaunchKernelGGL(k_bw_cls_scan, dim3(1), dim3(kThreads), 0, s, n_blocks, gw.blk_cnt, gw.counts);
+        hipLaunchKernelGGL(k_bw_cls_fill, dim3(n_blocks), dim3(kThreads), 0, s, gv, gw.cls, gw.blk_cnt, gw.lists);
+        for (int set = 0; set < 3; ++set) {
+            const int32_t *list = gw.lists + static_cast<size_t>(set) * n, *cnt = gw.counts + set;
+            const MlpRef &ln = mv.l[set];
+            for (int l = 0; l < L; ++l)
+                launch_dense({l == 0 ? ws.emb : gw.lact + static_cast<size_t>(l - 1) * NH, l == 0 ? 2 * H : H, list,
+                              cnt, n, l == 0 ? 2 * H : H, mv.blob + ln.layer[l].w, H, mv.blob + ln.layer[l].b, 1,
+                              nullptr, 0, gw.lact + static_cast<size_t>(l) * NH, H}, H, s);
+            hipLaunchKernelGGL(k_bw_pool_seed, dim3(static_cast<unsigned>((NH + kThreads - 1) / kThreads)),
+                               dim3(kThreads), 0, s, gv, H, G, mv.D, set, list, cnt, fa.placement, gw.dP,
+                               gw.lact + static_cast<size_t>(L - 1) * NH, gw.dl + static_cast<size_t>(L - 1) * NH);
+            for (int l = L - 1; l >= 1; --l)
+                launch_dense({gw.dl + static_cast<size_t>(l) * NH, H, list, cnt, n, H, blob_t + ln.layer[l].w, H,
+                              nullptr, 0, gw.lact + static_cast<size_t>(l - 1) * NH, H,
+                              gw.dl + static_cast<size_t>(l - 1) * NH, H}, H, s);
+            for (int half = 0; half < 2; ++half)   // the first layer is [2H, H]: transposed [H][2H]
+                launch_dense({gw.dl, H, list, cnt, n, H, blob_t + ln.layer[0].w + half * H, 2 * H, nullptr, 0,
+                              nullptr, 0, gw.demb + half * H, 2 * H}, H, s);
+        }
+    } else {
         const size_t lds = sizeof(float) * kTile * 4 * H;
 #define CALL(R)                                                                                             \
     allow_lds_bw(k_bw_pool<R>, lds);                                                                        \
@@ -868,6 +1216,27 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
 #undef CALL
     }
     // 3. sweeps
+    if (k_sweeps > 0 && dense) {
+        // the last layer of f is the message itself, which the forward pass left in ws.msg (the
+        // generic chain kernel reads it from fact, so there it is computed again)
+        for (int dir = 0; dir < 2; ++dir)
+            for (int l = 0; l + 1 < L || (l < L && !wfrag_bw); ++l) {
+                const LayerRef &ly = mv.f[dir].layer[l];
+                launch_dense({l == 0 ? ws.emb + dir * H : gw.fact + (static_cast<size_t>(dir) * L + l - 1) * NH,
+                              l == 0 ? 2 * H : H, nullptr, nullptr, n, H, mv.blob + ly.w, H, mv.blob + ly.b, 1,
+                              nullptr, 0, gw.fact + (static_cast<size_t>(dir) * L + l) * NH, H}, H, s);
+            }
+        hipLaunchKernelGGL(k_bw_agg, dim3(static_cast<unsigned>((NH + kThreads - 1) / kThreads), 2), dim3(kThreads),
+                           0, s, gv, H, ws.msg, gw.agg);
+        for (int dir = 0; dir < 2; ++dir)
+            for (int l = 0; l < L; ++l) {
+                const LayerRef &ly = mv.g[dir].layer[l];
+                launch_dense({l == 0 ? gw.agg + static_cast<size_t>(dir) * NH
+                                     : gw.gact + (static_cast<size_t>(dir) * L + l - 1) * NH,
+                              H, nullptr, nullptr, n, H, mv.blob + ly.w, H, mv.blob + ly.b, 1, nullptr, 0,
+                              gw.gact + (static_cast<size_t>(dir) * L + l) * NH, H}, H, s);
+            }
+    }
     if (k_sweeps > 0) {
         const size_t lds = sizeof(float) * 2 * kTile * H;
         const unsigned tiles = static_cast<unsigned>((n + kTile - 1) / kTile);
@@ -875,9 +1244,11 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
     allow_lds_bw(k_bw_f_acts<R>, lds);                                                                     \
     allow_lds_bw(k_bw_g_acts<R>, lds);                                                                     \
     allow_lds_bw(k_bw_sweep_generic<R>, lds);                                                              \
-    hipLaunchKernelGGL(k_bw_f_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, ws.emb, gw.fact);   \
-    hipLaunchKernelGGL(k_bw_g_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, gw.fact, gw.agg,    \
-                       gw.gact);                                                                           \
+    if (!dense) {                                                                                          \
+        hipLaunchKernelGGL(k_bw_f_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, ws.emb, gw.fact); \
+        hipLaunchKernelGGL(k_bw_g_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, gw.fact, gw.agg,  \
+                           gw.gact);                                                                       \
+    }                                                                                                      \
     if (!wfrag_bw)                                                                                         \
         hipLaunchKernelGGL(k_bw_sweep_generic<R>, dim3(B, 2), dim3(kThreads), lds, s, gv, mv, blob_t,      \
                            gw.fact, gw.gact, gw.demb, gw.dagg, gw.dfg, gw.dfg_stride)
@@ -885,7 +1256,8 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
 #undef CALL
         if (wfrag_bw) {
             hipLaunchKernelGGL(k_bw_prep, dim3(static_cast<unsigned>((NH + kThreads - 1) / kThreads)),
-                               dim3(kThreads), 0, s, gv, H, L, gw.demb, gw.fact, gw.gact, gw.extb, gw.mask4);
+                               dim3(kThreads), 0, s, gv, H, L, gw.demb, gw.fact, gw.gact, dense ? ws.msg : nullptr, gw.extb,
+                               gw.mask4);
             launch_sweep_mfma_bw(gv, mv, wfrag_bw, sweep_bias, sweep_ws, fa.cur_node, gw.demb, gw.extb, gw.dagg,
                                  gw.mask4, gw.dfg, gw.dfg_stride, s);
         }
@@ -903,32 +1275,33 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
         }
     }
     // 5. weight gradients
-    launch_wgrad(gw.phi, mv.F, gw.dx, H, nullptr, 0, n, mv.proj, gw.partial, grad, generic, s);
+    launch_wgrad(gw.phi, mv.F, gw.dx, H, nullptr, 0, nullptr, nullptr, n, mv.proj, gw.partial, grad, generic, s);
     if (k_sweeps > 0) {
         for (int dir = 0; dir < 2; ++dir)
             for (int l = 0; l < L; ++l) {
                 const float *dfl = gw.dfg + dir * gw.dfg_stride + static_cast<size_t>(l) * NH;
                 const float *dgl = dfl + static_cast<size_t>(L) * NH;
                 const float *fin = l == 0 ? ws.emb + dir * H : gw.fact + (static_cast<size_t>(dir) * L + l - 1) * NH;
-                launch_wgrad(fin, l == 0 ? 2 * H : H, dfl, H, nullptr, 0, n, mv.f[dir].layer[l],
+                launch_wgrad(fin, l == 0 ? 2 * H : H, dfl, H, nullptr, 0, nullptr, nullptr, n, mv.f[dir].layer[l],
                              gw.partial, grad, generic, s);
                 const float *gin = l == 0 ? gw.agg + static_cast<size_t>(dir) * NH
                                           : gw.gact + (static_cast<size_t>(dir) * L + l - 1) * NH;
-                launch_wgrad(gin, H, dgl, H, nullptr, 0, n, mv.g[dir].layer[l], gw.partial, grad, generic, s);
+                launch_wgrad(gin, H, dgl, H, nullptr, 0, nullptr, nullptr, n, mv.g[dir].layer[l], gw.partial, grad, generic, s);
             }
     }
     for (int set = 0; set < 3; ++set)
         for (int l = 0; l < L; ++l) {
             const float *lin = l == 0 ? ws.emb : gw.lact + static_cast<size_t>(l - 1) * NH;
-            launch_wgrad(lin, l == 0 ? 2 * H : H, gw.dl + static_cast<size_t>(l) * NH, H, gw.cls, set + 1, n,
-                         mv.l[set].layer[l], gw.partial, grad, generic, s);
+            launch_wgrad(lin, l == 0 ? 2 * H : H, gw.dl + static_cast<size_t>(l) * NH, H, gw.cls, set + 1,
+                         dense ? gw.lists + static_cast<size_t>(set) * n : nullptr, dense ? gw.counts + set : nullptr,
+                         n, mv.l[set].layer[l], gw.partial, grad, generic, s);
             const float *hin = l == 0 ? gw.hin + static_cast<size_t>(set) * BG * H
                                       : gw.hact + (static_cast<size_t>(set) * L + l - 1) * BG * H;
-            launch_wgrad(hin, H, gw.dh + (static_cast<size_t>(set) * L + l) * BG * H, H, nullptr, 0,
+            launch_wgrad(hin, H, gw.dh + (static_cast<size_t>(set) * L + l) * BG * H, H, nullptr, 0, nullptr, nullptr,
                          static_cast<int64_t>(BG), mv.h[set].layer[l], gw.partial, grad, generic, s);
         }
-    launch_wgrad(ws.zbuf, mv.Z, gw.dpre, H, nullptr, 0, B, mv.pol1, gw.partial, grad, generic, s);
-    launch_wgrad(gw.hid, H, gw.dlogit, mv.D, nullptr, 0, B, mv.pol2, gw.partial, grad, generic, s);
+    launch_wgrad(ws.zbuf, mv.Z, gw.dpre, H, nullptr, 0, nullptr, nullptr, B, mv.pol1, gw.partial, grad, generic, s);
+    launch_wgrad(gw.hid, H, gw.dlogit, mv.D, nullptr, 0, nullptr, nullptr, B, mv.pol2, gw.partial, grad, generic, s);
 }
 
 }  // namespace pl
