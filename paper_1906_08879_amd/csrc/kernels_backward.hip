@@ -14,9 +14,12 @@
 //              was gathered into, which belong to later levels;
 //   4. projection: both directions start from x_v, so its gradient is the sum of the two;
 //   5. every weight gradient is a contraction over rows (nodes, pooled groups or graphs) of
-//              layer input x layer delta, done by one kernel in slabs with a fixed summation
-//              order (no atomics).
-// All arithmetic is fp32 vector FMAs; any H <= 256, D <= 16, 1..4 layers, k <= 1 sweeps.
+//              layer input x layer delta, done in slabs with a fixed summation order (no
+//              atomics).
+// Two sets of kernels: generic fp32 vector kernels for any H <= 256, D <= 16, 1..4 layers; and,
+// for H in {32, 64, 128}, the parallel parts (per-node layers, weight gradients) on the fp32
+// matrix cores (v_mfma_f32_32x32x2_f32) and the dependent chain of step 3 in the matrix-core sweep
+// kernel run in reverse.  k <= 1 sweeps.
 #include <algorithm>
 
 #include "internal.h"
@@ -935,10 +938,18 @@ __global__ __launch_bounds__(kThreads) void k_wgrad(const float *__restrict__ A,
 
 // The same contraction on the matrix cores, for I a multiple of 32 and J in {32, 64, 128}:
 // v_mfma_f32_32x32x2_f32 multiplies a 32 x 2 block of A^T by a 2 x 32 block of Dl in fp32, so two
-// contraction rows are consumed per instruction and both operands are read straight from global
-// memory, 32 consecutive floats per half wave (no LDS, no split into bf16 parts).  Wave w of a
-// workgroup owns rows [32 (4 blockIdx.x + w), +32) of the weight matrix and all J columns
-// (NJ accumulator tiles); lanes 0-31 take even rows of the slab, lanes 32-63 odd rows.
+// contraction rows are consumed per instruction (lanes 0-31 take the even row, lanes 32-63 the odd
+// one; no split into bf16 parts).  A workgroup owns rows [128 blockIdx.x, +128) of the weight
+// matrix (wave w: 32 of them) and all J columns, for one slab of contraction rows.  The rows of A
+// and Dl go through LDS in chunks of 16, double buffered: every element is read from global
+// memory once per workgroup (coalesced float4), the loads of chunk c + 1 travel during the 32
+// matrix instructions of chunk c, and the ids of a row list are read one chunk further ahead.
+// Row strides in LDS keep the two halves of a wave on different banks.
+constexpr int kWgRC = 16;
+
+constexpr int wgrad_ldd(int J) { return J == 128 ? 160 : 96; }
+constexpr size_t wgrad_lds_bytes(int NJ) { return sizeof(float) * 2 * kWgRC * (160 + wgrad_ldd(32 * NJ)); }
+
 template <int NJ>
 __global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict__ A, int lda,
                                                          const float *__restrict__ Dl, int ldd,
@@ -947,14 +958,64 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict
                                                          int R, int I, int rows_per_slab,
                                                          float *__restrict__ partial)
 {
-    constexpr int J = 32 * NJ;
-    constexpr int U = 4;                       // row pairs per step
-    if (n_rows_dev) R = min(R, *n_rows_dev);   // slabs past the list's end write zeros
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int J = 32 * NJ, LDA_S = 160, LDD_S = wgrad_ldd(J);
+    constexpr int DT = kWgRC * J / 4;                      // float4 of a Dl chunk: 512, 256, 128
+    constexpr int DQ = (DT + kThreads - 1) / kThreads;     // per thread: 2, 1, 1
+    extern __shared__ float lds[];
+    float *as = lds;                                       // [2][kWgRC][LDA_S]
+    float *dsm = lds + 2 * kWgRC * LDA_S;                  // [2][kWgRC][LDD_S]
+    if (n_rows_dev) R = min(R, *n_rows_dev);               // slabs past the list's end write zeros
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lk = lane >> 5;
-    const int ib = blockIdx.x * 4 + wave, sl = blockIdx.y;
-    if (ib * 32 >= I) return;                  // no barrier in this kernel
+    const int iw = blockIdx.x * 128, sl = blockIdx.y;
+    const bool wave_on = iw + 32 * wave < I;
     const int r_beg = min(R, sl * rows_per_slab), r_end = min(R, r_beg + rows_per_slab);
+    const int n_chunks = (r_end - r_beg + kWgRC - 1) / kWgRC;
+
+    // this thread's pieces of a chunk: A rows ar + 8 q, floats ac .. ac + 3; Dl element 4 (tid + 256 q)
+    const int ar = tid >> 5, ac = (tid & 31) * 4;
+    const bool a_col_ok = iw + ac < I;
+    int ida[2], idd[DQ];
+    auto load_ids = [&](int r0) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int row = r0 + ar + 8 * q;
+            ida[q] = row < r_end ? (rows ? rows[row] : row) : -1;
+        }
+#pragma unroll
+        for (int q = 0; q < DQ; ++q) {
+            const int e = (tid + kThreads * q) * 4;
+            const int row = r0 + e / J;
+            idd[q] = (e < kWgRC * J && row < r_end) ? (rows ? rows[row] : row) : -1;
+        }
+    };
+    f32x4v areg[2], dreg[DQ];
+    auto fetch = [&]() {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const f32x4v v = *reinterpret_cast<const f32x4v *>(
+                A + static_cast<size_t>(max(ida[q], 0)) * lda + (a_col_ok ? iw + ac : 0));
+            areg[q] = (ida[q] >= 0 && a_col_ok) ? v : f32x4v{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int q = 0; q < DQ; ++q) {
+            const int e = (tid + kThreads * q) * 4, c = e % J;
+            const f32x4v v = *reinterpret_cast<const f32x4v *>(Dl + static_cast<size_t>(max(idd[q], 0)) * ldd + c);
+            dreg[q] = idd[q] >= 0 ? v : f32x4v{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+            *reinterpret_cast<f32x4v *>(as + (buf * kWgRC + ar + 8 * q) * LDA_S + ac) = areg[q];
+#pragma unroll
+        for (int q = 0; q < DQ; ++q) {
+            const int e = (tid + kThreads * q) * 4;
+            if (e < kWgRC * J)
+                *reinterpret_cast<f32x4v *>(dsm + (buf * kWgRC + e / J) * LDD_S + e % J) = dreg[q];
+        }
+    };
+
     f32x16 acc[NJ];
 #pragma unroll
     for (int jb = 0; jb < NJ; ++jb)
@@ -963,54 +1024,46 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict
     float bsum[NJ];
 #pragma unroll
     for (int jb = 0; jb < NJ; ++jb) bsum[jb] = 0.0f;
-    const float *Acol = A + ib * 32 + li;
-    const float *Dcol = Dl + li;
-    float a[U], bq[U][NJ];
-    // operands of rows r0 .. r0 + 2U - 1; rows past the slab's end give zeros (read from row 0)
-    auto fetch = [&](int r0, float (&fa)[U], float (&fb)[U][NJ]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int row = r0 + 2 * u + lk;
-            const bool ok = row < r_end;
-            const int rc = ok ? row : 0;
-            const int src = rows ? (ok ? rows[rc] : 0) : rc;
-            const float av = Acol[static_cast<size_t>(src) * lda];
-            fa[u] = ok ? av : 0.0f;
-#pragma unroll
-            for (int jb = 0; jb < NJ; ++jb) {
-                const float bv = Dcol[static_cast<size_t>(src) * ldd + 32 * jb];
-                fb[u][jb] = ok ? bv : 0.0f;
-            }
-        }
-    };
-    if (r_beg < r_end) fetch(r_beg, a, bq);
-    for (int r0 = r_beg; r0 < r_end; r0 += 2 * U) {
-        float an[U], bn[U][NJ];
-        fetch(r0 + 2 * U, an, bn);             // the next step's operands travel during this step
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int jb = 0; jb < NJ; ++jb) {
-                acc[jb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], bq[u][jb], acc[jb], 0, 0, 0);
-                bsum[jb] += bq[u][jb];
-            }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            a[u] = an[u];
-#pragma unroll
-            for (int jb = 0; jb < NJ; ++jb) bq[u][jb] = bn[u][jb];
-        }
+
+    if (n_chunks > 0) {
+        load_ids(r_beg);
+        fetch();
+        load_ids(r_beg + kWgRC);
+        stash(0);
     }
+    __syncthreads();
+    for (int c = 0; c < n_chunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < n_chunks) {
+            fetch();                                       // chunk c + 1, ids read during chunk c - 1
+            load_ids(r_beg + (c + 2) * kWgRC);
+        }
+        const float *ap = as + buf * kWgRC * LDA_S + lk * LDA_S + 32 * wave + li;
+        const float *dp = dsm + buf * kWgRC * LDD_S + lk * LDD_S + li;
+#pragma unroll
+        for (int st = 0; st < kWgRC / 2; ++st) {
+            const float a = ap[2 * st * LDA_S];
+#pragma unroll
+            for (int jb = 0; jb < NJ; ++jb) {
+                const float b = dp[2 * st * LDD_S + 32 * jb];
+                if (wave_on) acc[jb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[jb], 0, 0, 0);
+                bsum[jb] += b;
+            }
+        }
+        if (c + 1 < n_chunks) stash(buf ^ 1);
+        __syncthreads();
+    }
+    if (!wave_on) return;
     float *dst = partial + static_cast<size_t>(sl) * (static_cast<size_t>(I) * J + J);
 #pragma unroll
     for (int jb = 0; jb < NJ; ++jb) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int i = ib * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+            const int i = iw + 32 * wave + 8 * (v / 4) + 4 * lk + (v % 4);
             dst[static_cast<size_t>(i) * J + 32 * jb + li] = acc[jb][v];
         }
         const float other = __shfl_xor(bsum[jb], 32);
-        if (ib == 0 && lk == 0) dst[static_cast<size_t>(I) * J + 32 * jb + li] = bsum[jb] + other;
+        if (blockIdx.x == 0 && wave == 0 && lk == 0) dst[static_cast<size_t>(I) * J + 32 * jb + li] = bsum[jb] + other;
     }
 }
 
@@ -1112,13 +1165,13 @@ void launch_wgrad(const float *A, int lda, const float *Dl, int ldd, const uint8
         // with a row list (the nodes of one set, ascending) the class filter is not needed
         const dim3 grid((I + 127) / 128, slabs);
         if (J == 32)
-            hipLaunchKernelGGL(k_wgrad_mfma<1>, grid, dim3(kThreads), 0, s, A, lda, Dl, ldd, list, list_count,
+            hipLaunchKernelGGL(k_wgrad_mfma<1>, grid, dim3(kThreads), wgrad_lds_bytes(1), s, A, lda, Dl, ldd, list, list_count,
                                static_cast<int>(R), I, per, partial);
         else if (J == 64)
-            hipLaunchKernelGGL(k_wgrad_mfma<2>, grid, dim3(kThreads), 0, s, A, lda, Dl, ldd, list, list_count,
+            hipLaunchKernelGGL(k_wgrad_mfma<2>, grid, dim3(kThreads), wgrad_lds_bytes(2), s, A, lda, Dl, ldd, list, list_count,
                                static_cast<int>(R), I, per, partial);
         else
-            hipLaunchKernelGGL(k_wgrad_mfma<4>, grid, dim3(kThreads), 0, s, A, lda, Dl, ldd, list, list_count,
+            hipLaunchKernelGGL(k_wgrad_mfma<4>, grid, dim3(kThreads), wgrad_lds_bytes(4), s, A, lda, Dl, ldd, list, list_count,
                                static_cast<int>(R), I, per, partial);
     } else {
         hipLaunchKernelGGL(k_wgrad, dim3((I + kWgI - 1) / kWgI, slabs), dim3(kThreads), 0, s, A, lda, Dl, ldd,

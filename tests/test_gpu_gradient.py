@@ -3,9 +3,11 @@ autograd oracle on the same seeded inputs, through the C ABI.
 
 Bar: for every layer's block of the gradient (matrix and bias), the largest error is at most
 GRAD_RTOL times the largest entry of the oracle's block plus GRAD_ATOL times the largest entry of
-the whole gradient.  fp32 sums over up to ~10^3 dependent levels and ~10^5 rows per weight; the
-forward states already differ from float64 by ~1e-6 relative, and the reverse pass adds the same
-again."""
+the whole gradient.  A weight's gradient is an fp32 sum over up to ~10^6 rows of products of two
+fp32 chains (~10^3 dependent levels each) whose values differ from float64 by ~1e-6 relative, so
+single entries formed by cancellation cannot meet a bound relative to their own size; the block's
+largest entry sets the scale, as the row's largest logit does for the forward pass.  2e-5 is a
+fifth of the forward pass's 1e-4; measured worst case: 0.08 of the bound."""
 import numpy as np
 import pytest
 
@@ -16,7 +18,7 @@ from workloads import make_workload
 
 pytestmark = pytest.mark.gpu
 
-GRAD_RTOL, GRAD_ATOL = 2e-4, 2e-6
+GRAD_RTOL, GRAD_ATOL = 2e-5, 2e-7
 
 
 def assert_grad_close(got, ref, w, what):
@@ -63,6 +65,8 @@ def _compare(w, what, seed=0, path=0):
     (2, 8, 2, 1, 1, "fp32"), (1, 5, 1, 1, 1, "fp32"), (16, 16, 2, 1, 1, "fp32"),
     (4, 48, 3, 1, 1, "fp32"), (3, 100, 2, 1, 0, "fp32"), (4, 32, 2, 0, 1, "fp32"),
     (8, 128, 2, 1, 1, "bf16"), (2, 256, 2, 1, 1, "fp32"), (4, 64, 4, 1, 1, "bf16"), (12, 6, 2, 1, 1, "fp32"),
+    (4, 64, 1, 1, 1, "bf16"), (4, 32, 2, 1, 1, "bf16"), (4, 64, 2, 1, 1, "fp32"), (3, 128, 1, 1, 0, "bf16"),
+    (5, 128, 2, 1, 1, "fp32"), (4, 32, 1, 1, 1, "fp32"),
 ])
 def test_shapes_and_variants(D, H, L, k, group, wd):
     """Ragged batches (single nodes, edgeless graphs, wide levels) over the supported range of D,
@@ -72,9 +76,33 @@ def test_shapes_and_variants(D, H, L, k, group, wd):
     _compare(w, f"D={D} H={H} L={L} k={k} g={group} {wd}")
 
 
-@pytest.mark.parametrize("name,B", [("random32", 4), ("layered200", 4), ("inception", 2)])
+@pytest.mark.parametrize("name,B", [("random32", 4), ("layered200", 4), ("inception", 2), ("nmt", 2), ("nasnet", 1)])
 def test_small_batches_of_the_workloads(name, B):
     _compare(make_workload(name, B=B), name)
+
+
+@pytest.mark.parametrize("H,wd", [(32, "fp32"), (64, "bf16"), (128, "bf16")])
+def test_dense_graphs_with_long_neighbour_lists(H, wd):
+    """Nodes with dozens of parents and children: the reverse chain sums their gradients through
+    the overflow lists of the chunk plan (both list walks of the kernel: one and two column tiles
+    per wave)."""
+    rng = np.random.default_rng(40 + H)
+    w = custom_workload(rng, [150, 90, 33], 4, H, 2, 1, 1, wd, p_edge=0.4, w_scale=0.05)
+    _compare(w, f"dense graphs H={H} {wd}")
+
+
+@pytest.mark.parametrize("name", ["layered200", "nmt"])
+def test_generic_kernels_on_matrix_core_shapes(name):
+    """pl_weights_set_path(1): the generic fp32 reverse-pass kernels on shapes that normally take
+    the matrix-core kernels meet the same bar, and the two paths agree closely."""
+    w = make_workload(name, B=2)
+    actions, coeff, _ = _actions_and_coeff(w, 3)
+    ref_grad, _ = og.gradient_workload(w, actions, coeff.astype(np.float64))
+    slow = run_gradient(w, actions, coeff, path=1)
+    fast = run_gradient(w, actions, coeff, path=0)
+    assert_grad_close(slow["grad"], ref_grad, w, name + " generic")
+    assert_grad_close(fast["grad"], ref_grad, w, name + " matrix-core")
+    assert np.abs(fast["grad"] - slow["grad"]).max() <= 1e-4 * np.abs(ref_grad).max()
 
 
 def test_accumulation_linearity_and_rejected_states():
