@@ -316,7 +316,7 @@ int ensure_grad_workspace(pl_graph_batch *g, const ModelView &mv)
     PL_HIP(take(&gw.dl, L * NH));
     PL_HIP(take(&gw.demb, 2 * NH + 2 * H));
     PL_HIP(take(&gw.dx, NH));
-    PL_HIP(take(&gw.phi, n * mv.F));
+    PL_HIP(take(&gw.phi, n * 32));   // F <= 20 columns, padded to 32 on the matrix-core path
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.cls), n + 16));
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.counts), 64));
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.blk_cnt), sizeof(int32_t) * (3 * ((n + 255) / 256) + 4)));
@@ -331,7 +331,7 @@ int ensure_grad_workspace(pl_graph_batch *g, const ModelView &mv)
     PL_HIP(take(&gw.dpre, B * H));
     PL_HIP(take(&gw.dlogit, B * mv.D));
     size_t part = wgrad_partial_floats(static_cast<int64_t>(n), 2 * mv.H, mv.H);
-    part = std::max(part, wgrad_partial_floats(static_cast<int64_t>(n), mv.F, mv.H));
+    part = std::max(part, wgrad_partial_floats(static_cast<int64_t>(n), 32, mv.H));
     part = std::max(part, wgrad_partial_floats(static_cast<int64_t>(BG), mv.H, mv.H));
     part = std::max(part, wgrad_partial_floats(static_cast<int64_t>(B), mv.Z, mv.H));
     part = std::max(part, wgrad_partial_floats(static_cast<int64_t>(B), mv.H, mv.D));

@@ -563,9 +563,9 @@ __global__ __launch_bounds__(kThreads) void k_bw_proj(GraphView gv, ModelView mv
                                                       const int32_t *__restrict__ cur_node,
                                                       const float *__restrict__ demb,
                                                       float *__restrict__ dx,
-                                                      float *__restrict__ phi)
+                                                      float *__restrict__ phi, int phi_ld)
 {
-    const int H = mv.H, D = mv.D, F = mv.F;
+    const int H = mv.H, D = mv.D;
     const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
     if (idx >= static_cast<size_t>(gv.n_tot) * H) return;
     const int v = static_cast<int>(idx / H), h = static_cast<int>(idx - static_cast<size_t>(v) * H);
@@ -581,14 +581,15 @@ __global__ __launch_bounds__(kThreads) void k_bw_proj(GraphView gv, ModelView mv
     s = fmaf(feats[v * 3 + 2], W[(3 + D) * H + h], s);
     const float g = demb[static_cast<size_t>(v) * 2 * H + h] + demb[static_cast<size_t>(v) * 2 * H + H + h];
     dx[idx] = s > 0.0f ? g : 0.0f;
-    if (h < F) {
+    if (h < phi_ld) {                       // phi_ld >= F: columns past F are zero
         float p;
         if (h == 0) p = feats[v * 3 + 0];
         else if (h == 1) p = feats[v * 3 + 1];
         else if (h < 2 + D) p = (dev == h - 2) ? 1.0f : 0.0f;
         else if (h == 2 + D) p = is_cur ? 1.0f : 0.0f;
-        else p = feats[v * 3 + 2];
-        phi[static_cast<size_t>(v) * F + h] = p;
+        else if (h == 3 + D) p = feats[v * 3 + 2];
+        else p = 0.0f;
+        phi[static_cast<size_t>(v) * phi_ld + h] = p;
     }
 }
 
@@ -736,19 +737,22 @@ __global__ __launch_bounds__(kThreads) void k_dense_mfma(const float *__restrict
 }
 
 // a_v = sum of the neighbours' messages, for every node and both directions (grid.y).
+// Four columns per thread (H is a multiple of 32 on this path).
 __global__ __launch_bounds__(kThreads) void k_bw_agg(GraphView gv, int H,
                                                      const float *__restrict__ msgs,
                                                      float *__restrict__ agg)
 {
     const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (idx >= static_cast<size_t>(gv.n_tot) * H) return;
+    const int q = H / 4;
+    if (idx >= static_cast<size_t>(gv.n_tot) * q) return;
     const int dir = blockIdx.y;
-    const int v = static_cast<int>(idx / H), h = static_cast<int>(idx - static_cast<size_t>(v) * H);
+    const int v = static_cast<int>(idx / q), h = 4 * static_cast<int>(idx - static_cast<size_t>(v) * q);
     const float *msg = msgs + static_cast<size_t>(dir) * gv.n_tot * H;   // [2, n_tot, H] from the forward pass
     const int32_t *nbr_ptr = gv.nbr_ptr[dir], *nbr_idx = gv.nbr_idx[dir];
-    float a = 0.0f;
-    for (int p = nbr_ptr[v]; p < nbr_ptr[v + 1]; ++p) a += msg[static_cast<size_t>(nbr_idx[p]) * H + h];
-    agg[static_cast<size_t>(dir) * gv.n_tot * H + idx] = a;
+    f32x4v a{0.f, 0.f, 0.f, 0.f};
+    for (int p = nbr_ptr[v]; p < nbr_ptr[v + 1]; ++p)
+        a += *reinterpret_cast<const f32x4v *>(msg + static_cast<size_t>(nbr_idx[p]) * H + h);
+    *reinterpret_cast<f32x4v *>(agg + (static_cast<size_t>(dir) * gv.n_tot + v) * H + h) = a;
 }
 
 // Node set of every node and the three sets as row lists in ascending node order, in three
@@ -849,26 +853,33 @@ __global__ __launch_bounds__(kThreads) void k_bw_cls_fill(GraphView gv, const ui
     }
 }
 
-// Delta of l's last layer for the rows of one set: dP[set][device of the node], gated by the
-// layer's output; zero for a node whose device id is out of range (it was pooled nowhere).
-__global__ __launch_bounds__(kThreads) void k_bw_pool_seed(GraphView gv, int H, int G, int D, int set,
-                                                           const int32_t *__restrict__ list,
-                                                           const int32_t *__restrict__ count,
+// Delta of l's last layer for every node: dP[set of the node][device of the node], gated by the
+// layer's output; zero for a node whose device id is out of range (it was pooled nowhere).  Four
+// columns per thread.
+__global__ __launch_bounds__(kThreads) void k_bw_pool_seed(GraphView gv, int H, int G, int D,
+                                                           const uint8_t *__restrict__ cls,
                                                            const int32_t *__restrict__ placement,
                                                            const float *__restrict__ dP,
                                                            const float *__restrict__ act,
                                                            float *__restrict__ dl)
 {
     const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
-    const int r = static_cast<int>(idx / H), h = static_cast<int>(idx - static_cast<size_t>(r) * H);
-    if (r >= *count) return;
-    const int v = list[r];
+    const int q = H / 4;
+    if (idx >= static_cast<size_t>(gv.n_tot) * q) return;
+    const int v = static_cast<int>(idx / q), h = 4 * static_cast<int>(idx - static_cast<size_t>(v) * q);
+    const int k = cls[v];
+    if (k == 0) return;                       // the current node is in no set
     const int b = gv.node_graph[v];
     const int dev = placement[v];
     const bool ok = dev >= 0 && dev < D;
-    const float g = ok ? dP[((static_cast<size_t>(b) * 3 + set) * G + (G == 1 ? 0 : dev)) * H + h] : 0.0f;
     const size_t at = static_cast<size_t>(v) * H + h;
-    dl[at] = act[at] > 0.0f ? g : 0.0f;
+    const f32x4v a = *reinterpret_cast<const f32x4v *>(act + at);
+    f32x4v g{0.f, 0.f, 0.f, 0.f};
+    if (ok) g = *reinterpret_cast<const f32x4v *>(dP + ((static_cast<size_t>(b) * 3 + (k - 1)) * G + (G == 1 ? 0 : dev)) * H + h);
+    f32x4v o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = a[i] > 0.0f ? g[i] : 0.0f;
+    *reinterpret_cast<f32x4v *>(dl + at) = o;
 }
 
 // ------------------------------------------------------------------ 5. weight gradients
@@ -1070,15 +1081,19 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict
 // out[idx] += sum over slabs.  A workgroup takes 32 consecutive entries; its eight thread rows
 // each add the slabs q, q + 8, ... in order, and the eight sums are added in order: a fixed
 // summation order with enough loads in flight.
+// A slab holds src_count floats; entry idx of the output comes from entry idx of the slab, or from
+// idx + src_skip for idx >= n_main (the bias row, when the slab's matrix was padded to more rows).
 __global__ __launch_bounds__(kThreads) void k_wgrad_reduce(const float *__restrict__ partial, int n_slabs,
-                                                           size_t count, float *__restrict__ out)
+                                                           size_t count, size_t src_count, size_t n_main,
+                                                           size_t src_skip, float *__restrict__ out)
 {
     __shared__ float part[8][32];
     const int c = threadIdx.x & 31, q = threadIdx.x >> 5;
     const size_t idx = static_cast<size_t>(blockIdx.x) * 32 + c;
+    const size_t src = idx < n_main ? idx : idx + src_skip;
     float s = 0.0f;
     if (idx < count)
-        for (int sl = q; sl < n_slabs; sl += 8) s += partial[static_cast<size_t>(sl) * count + idx];
+        for (int sl = q; sl < n_slabs; sl += 8) s += partial[static_cast<size_t>(sl) * src_count + src];
     part[q][c] = s;
     __syncthreads();
     if (q == 0 && idx < count) {
@@ -1154,10 +1169,11 @@ void launch_fill_zero(float *p, size_t n, hipStream_t s)
 
 void launch_wgrad(const float *A, int lda, const float *Dl, int ldd, const uint8_t *row_cls, int want,
                   const int32_t *list, const int32_t *list_count, int64_t R, const LayerRef &ly, float *partial,
-                  float *grad, int generic, hipStream_t s)
+                  float *grad, int generic, hipStream_t s, int I_pad = 0)
 {
+    // I_pad: A has I_pad >= n_in columns, the extra ones zero (lets a narrow layer use the matrix cores)
     if (R <= 0) return;
-    const int I = ly.n_in, J = ly.n_out;
+    const int I = I_pad ? I_pad : ly.n_in, J = ly.n_out;
     const bool cores = generic == 0 && I % 32 == 0 && (J == 32 || J == 64 || J == 128);
     const int per = cores ? wgrad_rows_per_slab_cores(R) : wgrad_rows_per_slab(R);
     const int slabs = static_cast<int>((R + per - 1) / per);
@@ -1177,9 +1193,10 @@ void launch_wgrad(const float *A, int lda, const float *Dl, int ldd, const uint8
         hipLaunchKernelGGL(k_wgrad, dim3((I + kWgI - 1) / kWgI, slabs), dim3(kThreads), 0, s, A, lda, Dl, ldd,
                            row_cls, want, static_cast<int>(R), I, J, per, partial);
     }
-    const size_t count = static_cast<size_t>(I) * J + J;
+    const size_t n_main = static_cast<size_t>(ly.n_in) * J, count = n_main + J;
+    const size_t src_count = static_cast<size_t>(I) * J + J;
     hipLaunchKernelGGL(k_wgrad_reduce, dim3(static_cast<unsigned>((count + 31) / 32)), dim3(kThreads), 0, s,
-                       partial, slabs, count, grad + ly.w);
+                       partial, slabs, count, src_count, n_main, src_count - count, grad + ly.w);
 }
 
 namespace {
@@ -1247,9 +1264,13 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
                 launch_dense({l == 0 ? ws.emb : gw.lact + static_cast<size_t>(l - 1) * NH, l == 0 ? 2 * H : H, list,
                               cnt, n, l == 0 ? 2 * H : H, mv.blob + ln.layer[l].w, H, mv.blob + ln.layer[l].b, 1,
                               nullptr, 0, gw.lact + static_cast<size_t>(l) * NH, H}, H, s);
-            hipLaunchKernelGGL(k_bw_pool_seed, dim3(static_cast<unsigned>((NH + kThreads - 1) / kThreads)),
-                               dim3(kThreads), 0, s, gv, H, G, mv.D, set, list, cnt, fa.placement, gw.dP,
-                               gw.lact + static_cast<size_t>(L - 1) * NH, gw.dl + static_cast<size_t>(L - 1) * NH);
+        }
+        hipLaunchKernelGGL(k_bw_pool_seed, dim3(static_cast<unsigned>((NH / 4 + kThreads - 1) / kThreads)),
+                           dim3(kThreads), 0, s, gv, H, G, mv.D, gw.cls, fa.placement, gw.dP,
+                           gw.lact + static_cast<size_t>(L - 1) * NH, gw.dl + static_cast<size_t>(L - 1) * NH);
+        for (int set = 0; set < 3; ++set) {
+            const int32_t *list = gw.lists + static_cast<size_t>(set) * n, *cnt = gw.counts + set;
+            const MlpRef &ln = mv.l[set];
             for (int l = L - 1; l >= 1; --l)
                 launch_dense({gw.dl + static_cast<size_t>(l) * NH, H, list, cnt, n, H, blob_t + ln.layer[l].w, H,
                               nullptr, 0, gw.lact + static_cast<size_t>(l - 1) * NH, H,
@@ -1279,7 +1300,7 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
                               l == 0 ? 2 * H : H, nullptr, nullptr, n, H, mv.blob + ly.w, H, mv.blob + ly.b, 1,
                               nullptr, 0, gw.fact + (static_cast<size_t>(dir) * L + l) * NH, H}, H, s);
             }
-        hipLaunchKernelGGL(k_bw_agg, dim3(static_cast<unsigned>((NH + kThreads - 1) / kThreads), 2), dim3(kThreads),
+        hipLaunchKernelGGL(k_bw_agg, dim3(static_cast<unsigned>((NH / 4 + kThreads - 1) / kThreads), 2), dim3(kThreads),
                            0, s, gv, H, ws.msg, gw.agg);
         for (int dir = 0; dir < 2; ++dir)
             for (int l = 0; l < L; ++l) {
@@ -1320,7 +1341,7 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
         const size_t total = NH;
         hipLaunchKernelGGL(k_bw_proj, dim3(static_cast<unsigned>((total + kThreads - 1) / kThreads)),
                            dim3(kThreads), 0, s, gv, mv, fa.node_feats, fa.placement, fa.cur_node, gw.demb,
-                           gw.dx, gw.phi);
+                           gw.dx, gw.phi, dense ? 32 : mv.F);
         if (H < mv.F) {
             const size_t tf = static_cast<size_t>(n) * mv.F;
             hipLaunchKernelGGL(k_bw_phi, dim3(static_cast<unsigned>((tf + kThreads - 1) / kThreads)),
@@ -1328,7 +1349,10 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
         }
     }
     // 5. weight gradients
-    launch_wgrad(gw.phi, mv.F, gw.dx, H, nullptr, 0, nullptr, nullptr, n, mv.proj, gw.partial, grad, generic, s);
+    if (dense)   // raw features padded to 32 columns
+        launch_wgrad(gw.phi, 32, gw.dx, H, nullptr, 0, nullptr, nullptr, n, mv.proj, gw.partial, grad, generic, s, 32);
+    else
+        launch_wgrad(gw.phi, mv.F, gw.dx, H, nullptr, 0, nullptr, nullptr, n, mv.proj, gw.partial, grad, generic, s);
     if (k_sweeps > 0) {
         for (int dir = 0; dir < 2; ++dir)
             for (int l = 0; l < L; ++l) {
