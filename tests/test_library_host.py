@@ -145,3 +145,19 @@ def test_episode_entry_points_reject_bad_arguments(lib):
     raw.pl_last_error.restype = ctypes.c_char_p
     assert b"NULL" in raw.pl_last_error()
     g.close()
+
+
+def test_policy_gradient_rejects_null_handles(lib):
+    """pl_policy_gradient without a graph batch or weights handle returns PL_ERR_NULL with a message
+    (no device is touched)."""
+    import ctypes
+    raw = ctypes.CDLL(pl.library_path())
+    null = ctypes.c_void_p(None)
+    g = pl.GraphBatch([3], [2], [0, 1], [1, 2])
+    args = [g._h, null, null, null, null, null, null, ctypes.c_int32(0), null, null, null, null]
+    assert raw.pl_policy_gradient(*args) == -1                          # weights handle is NULL
+    args[0] = null
+    assert raw.pl_policy_gradient(*args) == -1                          # graph batch is NULL
+    raw.pl_last_error.restype = ctypes.c_char_p
+    assert b"NULL" in raw.pl_last_error()
+    g.close()
