@@ -199,6 +199,41 @@ int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t
                        const float *coeff, int32_t accumulate, float *grad, float *out_logits,
                        float *out_logp, void *stream);
 
+/* The weights of that sum for T steps of B rollouts (Eq. 1: the return after each decision minus
+ * a baseline; the baseline of step i is the average of that return over the independent
+ * rollouts of the same graph):
+ *     G[t][b] = sum_{t' >= t} rewards[t'][b]
+ *     out_baseline[t][g] = mean of G[t][b] over the rollouts b with group[b] == g (0 if none)
+ *     out_coeff[t][b] = G[t][b] - out_baseline[t][group[b]]
+ *   rewards       dev [T, B] fp32   reward after step t of rollout b (0 after a rollout's end)
+ *   group         dev [B] int32     id in [0, n_groups) shared by the rollouts of one graph; an id
+ *                                   outside that range keeps the plain return
+ *   out_coeff     dev [T, B] fp32;  out_baseline  dev [T, n_groups] fp32
+ * n_groups = 0 gives the plain returns (group and out_baseline may then be NULL).  fp32 sums in a
+ * fixed order (steps from the last backwards, rollouts ascending).  Asynchronous on `stream`;
+ * allocates nothing. */
+int pl_reinforce_coeff(int32_t T, int32_t B, const float *rewards, const int32_t *group, int32_t n_groups,
+                       float *out_coeff, float *out_baseline, void *stream);
+
+/* The whole sum of Eq. 1 for steps t0 .. t0 + n_steps - 1 of a recorded episode: for every step,
+ * pl_policy_gradient on the current state with that step's actions and weights (accumulating
+ * into grad), then the transition of Section 2.1 with the recorded action (as pl_episode_step,
+ * nothing sampled), all enqueued on `stream` without host synchronisation.
+ *   node_feats, placement, cur_node   dev, in/out: the state at step t0 (e.g. a copy of the
+ *                                     state the rollout started from); advanced by n_steps
+ *   order         dev [N_tot]         the visiting order used by the rollout
+ *   actions       dev [n_steps, B]    e.g. out_actions of pl_episode_run
+ *   coeff         dev [n_steps, B]    e.g. out_coeff of pl_reinforce_coeff
+ *   accumulate                        0: grad is overwritten by the sum; else added to
+ *   grad          dev [pl_weights_count];  logits  dev [B, D] scratch (last step's logits)
+ *   out_logp      dev [n_steps, B] or NULL: log pi(a | s) of every replayed decision (NaN once a
+ *                                     graph's episode is over)
+ * Same limits as pl_policy_gradient. */
+int pl_episode_gradient(pl_graph_batch *g, const pl_weights *w, float *node_feats, int32_t *placement,
+                        int32_t *cur_node, const int32_t *order, const int32_t *actions, const float *coeff,
+                        int32_t t0, int32_t n_steps, int32_t accumulate, float *grad, float *logits,
+                        float *out_logp, void *stream);
+
 /* ---- run time of a placement from the event-driven simulator of the paper's appendix
  * ("Simulator"), for every graph of the batch: per device a FIFO queue of runnable operations
  * and a FIFO queue of outgoing tensors, one operation per device and one transfer per bus at a

@@ -10,12 +10,14 @@ from .binding import (  # noqa: F401
     PlacetoError,
     Weights,
     embed_forward,
+    episode_gradient,
     episode_run,
     episode_step,
     library_path,
     load_library,
     node_classes,
     policy_gradient,
+    reinforce_coeff,
     simulate_runtime,
     weights_count,
 )

@@ -66,6 +66,9 @@ def load_library(path: Optional[str] = None):
         "pl_episode_run": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
                                           vp, ctypes.c_int32, vp, vp, vp]),
         "pl_policy_gradient": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp, vp]),
+        "pl_reinforce_coeff": (ctypes.c_int, [ctypes.c_int32, ctypes.c_int32, vp, vp, ctypes.c_int32, vp, vp, vp]),
+        "pl_episode_gradient": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
+                                               ctypes.c_int32, vp, vp, vp, vp]),
         "pl_simulate_runtime": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, ctypes.c_float, vp, vp, vp]),
         "pl_profile_enable": (ctypes.c_int, [vp, ctypes.c_int32]),
         "pl_profile_read": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_double), i64p,
@@ -304,4 +307,38 @@ def policy_gradient(g: GraphBatch, node_feats, placement, cur_node, w: Weights, 
         1 if accumulate else 0, _dev_ptr(grad, torch.float32, n_par, "grad"),
         _dev_ptr(out_logits, torch.float32, g.B * w.D, "out_logits"),
         _dev_ptr(out_logp, torch.float32, g.B, "out_logp"), _stream_ptr(stream)), "pl_policy_gradient")
+    return grad
+
+
+def reinforce_coeff(rewards, group, n_groups: int, out_coeff, out_baseline=None, stream=None):
+    """pl_reinforce_coeff on device tensors: rewards [T, B] -> return-minus-baseline weights [T, B]."""
+    import torch
+    lib = load_library()
+    T, B = int(rewards.shape[0]), int(rewards.shape[1])
+    _check(lib.pl_reinforce_coeff(
+        T, B, _dev_ptr(rewards, torch.float32, T * B, "rewards"),
+        _dev_ptr(group, torch.int32, B, "group"), int(n_groups),
+        _dev_ptr(out_coeff, torch.float32, T * B, "out_coeff"),
+        _dev_ptr(out_baseline, torch.float32, T * n_groups, "out_baseline"), _stream_ptr(stream)),
+        "pl_reinforce_coeff")
+    return out_coeff
+
+
+def episode_gradient(g: GraphBatch, w: Weights, node_feats, placement, cur_node, order, actions, coeff,
+                     t0: int, n_steps: int, grad, logits, out_logp=None, accumulate: bool = False, stream=None):
+    """pl_episode_gradient on device tensors: the REINFORCE sum over n_steps recorded steps."""
+    import torch
+    lib = load_library()
+    n_par = int(lib.pl_weights_count(ctypes.byref(w.cfg)))
+    _check(lib.pl_episode_gradient(
+        g._h, w._h, _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
+        _dev_ptr(placement, torch.int32, g.n_tot, "placement"),
+        _dev_ptr(cur_node, torch.int32, g.B, "cur_node"),
+        _dev_ptr(order, torch.int32, g.n_tot, "order"),
+        _dev_ptr(actions, torch.int32, g.B * n_steps, "actions"),
+        _dev_ptr(coeff, torch.float32, g.B * n_steps, "coeff"), int(t0), int(n_steps),
+        1 if accumulate else 0, _dev_ptr(grad, torch.float32, n_par, "grad"),
+        _dev_ptr(logits, torch.float32, g.B * w.D, "logits"),
+        _dev_ptr(out_logp, torch.float32, g.B * n_steps, "out_logp"), _stream_ptr(stream)),
+        "pl_episode_gradient")
     return grad

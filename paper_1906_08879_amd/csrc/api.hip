@@ -715,6 +715,50 @@ int pl_episode_run(pl_graph_batch *g, const pl_weights *w, float *node_feats, in
     return PL_OK;
 }
 
+int pl_reinforce_coeff(int32_t T, int32_t B, const float *rewards, const int32_t *group, int32_t n_groups,
+                       float *out_coeff, float *out_baseline, void *stream)
+{
+    if (T < 0 || B < 0 || n_groups < 0) return fail(PL_ERR_SHAPE, "T, B and n_groups must not be negative");
+    if (static_cast<double>(T) * std::max(B, n_groups) >= 2.0e9)
+        return fail(PL_ERR_SHAPE, "T x B is too large");
+    if (T == 0 || B == 0) return PL_OK;
+    if (!rewards || !out_coeff) return fail(PL_ERR_NULL, "rewards and out_coeff are required");
+    if (n_groups > 0 && (!group || !out_baseline))
+        return fail(PL_ERR_NULL, "group and out_baseline are required when n_groups > 0");
+    launch_reinforce_coeff(T, B, n_groups, rewards, group, out_coeff, out_baseline,
+                           static_cast<hipStream_t>(stream));
+    PL_HIP(hipGetLastError());
+    return PL_OK;
+}
+
+int pl_episode_gradient(pl_graph_batch *g, const pl_weights *w, float *node_feats, int32_t *placement,
+                        int32_t *cur_node, const int32_t *order, const int32_t *actions, const float *coeff,
+                        int32_t t0, int32_t n_steps, int32_t accumulate, float *grad, float *logits,
+                        float *out_logp, void *stream)
+{
+    if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
+    if (t0 < 0 || n_steps < 0) return fail(PL_ERR_SHAPE, "t0 and n_steps must not be negative");
+    if (g->host.B == 0) return PL_OK;
+    if (!node_feats || !placement || !cur_node || !order || !actions || !coeff || !grad || !logits)
+        return fail(PL_ERR_NULL, "a required device array is NULL");
+    const size_t B = static_cast<size_t>(g->host.B);
+    if (n_steps == 0 && !accumulate) {
+        launch_fill_zero(grad, plan_weights(w->cfg, nullptr), static_cast<hipStream_t>(stream));
+        PL_HIP(hipGetLastError());
+        return PL_OK;
+    }
+    for (int32_t i = 0; i < n_steps; ++i) {
+        int rc = pl_policy_gradient(g, node_feats, placement, cur_node, w, actions + i * B, coeff + i * B,
+                                    (accumulate || i > 0) ? 1 : 0, grad, logits,
+                                    out_logp ? out_logp + i * B : nullptr, stream);
+        if (rc) return rc;
+        launch_episode_apply(g->view, w->cfg.D, actions + i * B, order, t0 + i, node_feats, placement, cur_node,
+                             static_cast<hipStream_t>(stream));
+    }
+    PL_HIP(hipGetLastError());
+    return PL_OK;
+}
+
 int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
                        const int32_t *cur_node, const pl_weights *w, const int32_t *actions,
                        const float *coeff, int32_t accumulate, float *grad, float *out_logits,

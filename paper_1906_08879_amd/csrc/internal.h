@@ -164,6 +164,11 @@ void launch_episode_step(const GraphView &gv, int D, const float *logits, const 
                          const int32_t *order, int t, float *node_feats, int32_t *placement,
                          int32_t *cur_node, int32_t *out_action, float *out_logp, hipStream_t s);
 
+void launch_episode_apply(const GraphView &gv, int D, const int32_t *actions, const int32_t *order, int t,
+                          float *node_feats, int32_t *placement, int32_t *cur_node, hipStream_t s);
+void launch_reinforce_coeff(int T, int B, int n_groups, const float *rewards, const int32_t *group,
+                            float *coeff, float *baseline, hipStream_t s);
+
 // ---- run-time simulator of a placement (kernels_simulator.hip); n_max / e_max: largest graph
 size_t simulator_lds_bytes(int n_max, int e_max);
 int launch_simulate(const GraphView &gv, int D, int n_max, int e_max, const float *node_feats,

@@ -161,3 +161,18 @@ def test_policy_gradient_rejects_null_handles(lib):
     raw.pl_last_error.restype = ctypes.c_char_p
     assert b"NULL" in raw.pl_last_error()
     g.close()
+
+
+def test_reinforce_entry_points_reject_bad_arguments(lib):
+    """Error paths that need no device: negative sizes, missing arrays, NULL handles."""
+    import ctypes
+    raw = ctypes.CDLL(pl.library_path())
+    null = ctypes.c_void_p(None)
+    i32 = ctypes.c_int32
+    assert raw.pl_reinforce_coeff(i32(-1), i32(4), null, null, i32(0), null, null, null) == -2   # PL_ERR_SHAPE
+    assert raw.pl_reinforce_coeff(i32(0), i32(4), null, null, i32(0), null, null, null) == 0     # nothing to do
+    assert raw.pl_reinforce_coeff(i32(3), i32(4), null, null, i32(0), null, null, null) == -1    # PL_ERR_NULL
+    g = pl.GraphBatch([2], [1], [0], [1])
+    args = [g._h, null, null, null, null, null, null, null, i32(0), i32(1), i32(0), null, null, null, null]
+    assert raw.pl_episode_gradient(*args) == -1                                                 # weights handle is NULL
+    g.close()
