@@ -82,7 +82,7 @@ def main() -> int:
                          "scaling the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; the path shards over the batch of "
+        print("bench.py: the library runs on ONE GPU; the path shards over the batch of "
               "independent graphs and no multi-GPU figure is produced (--gpus must be 1).",
               file=sys.stderr)
         return 2
