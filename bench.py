@@ -146,7 +146,7 @@ def main() -> int:
 
     ms_per_step = 1e3 * elapsed / args.steps
     steps_per_s = w.B * args.steps / elapsed
-    stage_ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in stages.items()}
+    stage_ms = {k: v[0] / v[1] for k, v in stages.items() if v[1]}
     sweep_ms, sweep_launches = stages["sweep"]
     launches_per_step = max(1, w.k_sweeps)
     avg_launch_ms = sweep_ms / max(1, sweep_launches) / launches_per_step
@@ -214,6 +214,8 @@ def main() -> int:
         g_grad = torch.empty((n_par,), dtype=torch.float32, device=dev)
         pl.policy_gradient(g, feats[0], t_place[0], t_cur[0], wt, g_act, g_coef, g_grad, logits, stream=stream)
         torch.cuda.synchronize()
+        g.profile_enable(True)
+        g.profile_read(reset=True)
         t0 = time.perf_counter()
         for i in range(args.grad_steps):
             s_ = i % N_STATES
@@ -221,9 +223,12 @@ def main() -> int:
                                accumulate=i > 0, stream=stream)
         torch.cuda.synchronize()
         gr_elapsed = (time.perf_counter() - t0) / max(1, args.grad_steps)
+        gr_stages = g.profile_read(reset=True)
+        g.profile_enable(False)
         assert torch.isfinite(g_grad).all(), "non-finite gradient in the timed run"
         gradient = {"ms_per_step": round(1e3 * gr_elapsed, 4), "steps": args.grad_steps,
                     "graph_steps_per_s": round(w.B / gr_elapsed, 2), "parameters": int(n_par),
+                    "stage_ms": {k: round(v[0] / v[1], 4) for k, v in gr_stages.items() if v[1]},
                     "what": "forward pass + reverse pass (log-probability gradient of one decision per "
                             "graph, summed over the batch)"}
 

@@ -252,13 +252,17 @@ int pl_episode_gradient(pl_graph_batch *g, const pl_weights *w, float *node_feat
 int pl_simulate_runtime(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
                         float inv_bandwidth, float *out_runtime, int32_t *out_events, void *stream);
 
-/* ---- per-stage timing, for benchmarks.  While enabled, forward calls bracket each
- * kernel stage with HIP events on the caller's stream.  pl_profile_read synchronises those
+/* ---- per-stage timing, for benchmarks.  While enabled, forward and gradient calls bracket each
+ * kernel stage with HIP events on the caller's stream (the BW stages are those of the reverse
+ * pass: head, pooling, per-node layers at the final states, the dependent chain, projection,
+ * weight gradients).  pl_profile_read synchronises those
  * events and returns, per stage, the summed milliseconds and the number of launches since
  * the last reset.  Stage ids: see pl_stage. */
 typedef enum {
     PL_STAGE_PROJECT = 0, PL_STAGE_SWEEP = 1, PL_STAGE_POOL = 2, PL_STAGE_HEAD = 3,
-    PL_STAGE_COUNT = 4
+    PL_STAGE_BW_HEAD = 4, PL_STAGE_BW_POOL = 5, PL_STAGE_BW_ACTS = 6, PL_STAGE_BW_CHAIN = 7,
+    PL_STAGE_BW_PROJ = 8, PL_STAGE_BW_WGRAD = 9,
+    PL_STAGE_COUNT = 10
 } pl_stage;
 int pl_profile_enable(pl_graph_batch *g, int32_t on);
 int pl_profile_read(pl_graph_batch *g, double *ms_sum /*[PL_STAGE_COUNT]*/,

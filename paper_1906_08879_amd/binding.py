@@ -17,7 +17,7 @@ _LIB_PATH = os.path.join(_HERE, "libplaceto.so")
 _lib = None
 
 PL_WEIGHTS = {"fp32": 0, "bf16": 1}
-STAGES = ("project", "sweep", "pool", "head")
+STAGES = ("project", "sweep", "pool", "head", "bw_head", "bw_pool", "bw_acts", "bw_chain", "bw_proj", "bw_wgrad")
 
 
 class PlacetoError(RuntimeError):

@@ -46,8 +46,8 @@ int upload(const std::vector<T> &host, T **dev)
 
 struct StageTimer {
     std::vector<hipEvent_t> ev[PL_STAGE_COUNT];   // start/stop pairs not yet read
-    double ms_sum[PL_STAGE_COUNT] = {0, 0, 0, 0};
-    int64_t launches[PL_STAGE_COUNT] = {0, 0, 0, 0};
+    double ms_sum[PL_STAGE_COUNT] = {};
+    int64_t launches[PL_STAGE_COUNT] = {};
     bool on = false;
 };
 
@@ -369,6 +369,23 @@ struct StageScope {
         }
     }
 };
+
+// StageMarks hook over a batch's timer: an event at the beginning and at the end of a stage.
+void stage_mark(void *ctx, int stage, bool begin, hipStream_t s)
+{
+    StageTimer &t = *static_cast<StageTimer *>(ctx);
+    if (!t.on) return;
+    auto &ev = t.ev[stage];
+    if (!begin && (ev.size() & 1u) == 0) return;    // no open pair
+    hipEvent_t e;
+    if (hipEventCreate(&e) == hipSuccess) {
+        (void)hipEventRecord(e, s);
+        ev.push_back(e);
+    } else if (!begin) {
+        (void)hipEventDestroy(ev.back());
+        ev.pop_back();
+    }
+}
 
 int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
                  const int32_t *cur_node, const pl_weights *w, float *out_logits, float *out_probs,
@@ -784,10 +801,11 @@ int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t
     const bool fits = (2.0 * mv.L * static_cast<double>(g->host.n_tot) + 1) * mv.H < 2.0e9 &&
                       (static_cast<double>(g->host.n_tot) + 2) * 2 * mv.H * sizeof(float) < 4.0e9;
     const bool chain_cores = w->d_wfrag_bw && w->path == 0 && w->cfg.k_sweeps == 1 && fits;
+    const StageMarks marks{&g->timer, stage_mark};
     launch_backward_generic(g->view, mv, w->d_blob_t, g->ws, g->gw, fa, actions, coeff, w->cfg.k_sweeps,
                             g->ws.n_chunks, w->path,
                             chain_cores ? reinterpret_cast<const uint4 *>(w->d_wfrag_bw) : nullptr,
-                            w->d_sweep_bias, w->sweep_ws, grad, out_logp, s);
+                            w->d_sweep_bias, w->sweep_ws, grad, out_logp, &marks, s);
     PL_HIP(hipGetLastError());
     return PL_OK;
 }

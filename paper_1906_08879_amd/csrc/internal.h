@@ -211,13 +211,19 @@ struct GradWorkspace {
     int32_t H = 0, G = 0, L = 0, D = 0;
 };
 
+// Optional per-stage timing hook: called at the beginning and the end of every stage of a pass.
+struct StageMarks {
+    void *ctx;
+    void (*mark)(void *ctx, int stage, bool begin, hipStream_t s);
+};
+
 size_t wgrad_partial_floats(int64_t R, int I, int J);
 void launch_fill_zero(float *p, size_t n, hipStream_t s);
 void launch_backward_generic(const GraphView &gv, const ModelView &mv, const float *blob_t,
                              const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
                              const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
                              int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
-                             float *grad, float *out_logp, hipStream_t s);
+                             float *grad, float *out_logp, const StageMarks *marks, hipStream_t s);
 
 // ---- matrix-core sweep (kernels_mfma.hip)
 bool sweep_mfma_supported(int H, int L, int weight_dtype);

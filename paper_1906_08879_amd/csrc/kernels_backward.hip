@@ -1227,7 +1227,7 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
                              const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
                              const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
                              int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
-                             float *grad, float *out_logp, hipStream_t s)
+                             float *grad, float *out_logp, const StageMarks *marks, hipStream_t s)
 {
     if (gv.B == 0) return;
     const int H = mv.H, L = mv.L, G = mv.G, B = gv.B, n = gv.n_tot;
@@ -1236,7 +1236,11 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
     const size_t NH = static_cast<size_t>(n) * H;
     const size_t BG = static_cast<size_t>(B) * G;
 
+    auto mark = [&](int stage, bool begin) {
+        if (marks && marks->mark) marks->mark(marks->ctx, stage, begin, s);
+    };
     // 1. head
+    mark(PL_STAGE_BW_HEAD, true);
     hipLaunchKernelGGL(k_bw_head, dim3(B), dim3(kThreads), 0, s, gv, mv, blob_t, ws.hidp, n_slices, fa.cur_node,
                        actions, coeff, gw.hid, gw.dpre, gw.dlogit, gw.dz, out_logp);
     {
@@ -1248,6 +1252,8 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
         PL_DISPATCH_RPT(rpt, CALL)
 #undef CALL
     }
+    mark(PL_STAGE_BW_HEAD, false);
+    mark(PL_STAGE_BW_POOL, true);
     // matrix-core dense layers: every output width of the embedding networks is H
     const bool dense = generic == 0 && (H == 32 || H == 64 || H == 128);
     // 2. pooling
@@ -1289,7 +1295,9 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
         PL_DISPATCH_RPT(rpt, CALL)
 #undef CALL
     }
+    mark(PL_STAGE_BW_POOL, false);
     // 3. sweeps
+    mark(PL_STAGE_BW_ACTS, true);
     if (k_sweeps > 0 && dense) {
         // the last layer of f is the message itself, which the forward pass left in ws.msg (the
         // generic chain kernel reads it from fact, so there it is computed again)
@@ -1314,29 +1322,38 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
     if (k_sweeps > 0) {
         const size_t lds = sizeof(float) * 2 * kTile * H;
         const unsigned tiles = static_cast<unsigned>((n + kTile - 1) / kTile);
-#define CALL(R)                                                                                            \
-    allow_lds_bw(k_bw_f_acts<R>, lds);                                                                     \
-    allow_lds_bw(k_bw_g_acts<R>, lds);                                                                     \
-    allow_lds_bw(k_bw_sweep_generic<R>, lds);                                                              \
-    if (!dense) {                                                                                          \
-        hipLaunchKernelGGL(k_bw_f_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, ws.emb, gw.fact); \
-        hipLaunchKernelGGL(k_bw_g_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, gw.fact, gw.agg,  \
-                           gw.gact);                                                                       \
-    }                                                                                                      \
-    if (!wfrag_bw)                                                                                         \
-        hipLaunchKernelGGL(k_bw_sweep_generic<R>, dim3(B, 2), dim3(kThreads), lds, s, gv, mv, blob_t,      \
-                           gw.fact, gw.gact, gw.demb, gw.dagg, gw.dfg, gw.dfg_stride)
-        PL_DISPATCH_RPT(rpt, CALL)
+        if (!dense) {
+#define CALL(R)                                                                                              \
+    allow_lds_bw(k_bw_f_acts<R>, lds);                                                                       \
+    allow_lds_bw(k_bw_g_acts<R>, lds);                                                                       \
+    hipLaunchKernelGGL(k_bw_f_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, ws.emb, gw.fact);     \
+    hipLaunchKernelGGL(k_bw_g_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, gw.fact, gw.agg, gw.gact)
+            PL_DISPATCH_RPT(rpt, CALL)
 #undef CALL
-        if (wfrag_bw) {
+        }
+        if (wfrag_bw)
             hipLaunchKernelGGL(k_bw_prep, dim3(static_cast<unsigned>((NH + kThreads - 1) / kThreads)),
                                dim3(kThreads), 0, s, gv, H, L, gw.demb, gw.fact, gw.gact, dense ? ws.msg : nullptr, gw.extb,
                                gw.mask4);
+        mark(PL_STAGE_BW_ACTS, false);
+        mark(PL_STAGE_BW_CHAIN, true);
+        if (wfrag_bw) {
             launch_sweep_mfma_bw(gv, mv, wfrag_bw, sweep_bias, sweep_ws, fa.cur_node, gw.demb, gw.extb, gw.dagg,
                                  gw.mask4, gw.dfg, gw.dfg_stride, s);
+        } else {
+#define CALL(R)                                                                                            \
+    allow_lds_bw(k_bw_sweep_generic<R>, lds);                                                              \
+    hipLaunchKernelGGL(k_bw_sweep_generic<R>, dim3(B, 2), dim3(kThreads), lds, s, gv, mv, blob_t, gw.fact, \
+                       gw.gact, gw.demb, gw.dagg, gw.dfg, gw.dfg_stride)
+            PL_DISPATCH_RPT(rpt, CALL)
+#undef CALL
         }
+        mark(PL_STAGE_BW_CHAIN, false);
+    } else {
+        mark(PL_STAGE_BW_ACTS, false);
     }
     // 4. projection
+    mark(PL_STAGE_BW_PROJ, true);
     {
         const size_t total = NH;
         hipLaunchKernelGGL(k_bw_proj, dim3(static_cast<unsigned>((total + kThreads - 1) / kThreads)),
@@ -1348,7 +1365,9 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
                                dim3(kThreads), 0, s, gv, mv, fa.node_feats, fa.placement, fa.cur_node, gw.phi);
         }
     }
+    mark(PL_STAGE_BW_PROJ, false);
     // 5. weight gradients
+    mark(PL_STAGE_BW_WGRAD, true);
     if (dense)   // raw features padded to 32 columns
         launch_wgrad(gw.phi, 32, gw.dx, H, nullptr, 0, nullptr, nullptr, n, mv.proj, gw.partial, grad, generic, s, 32);
     else
@@ -1379,6 +1398,7 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
         }
     launch_wgrad(ws.zbuf, mv.Z, gw.dpre, H, nullptr, 0, nullptr, nullptr, B, mv.pol1, gw.partial, grad, generic, s);
     launch_wgrad(gw.hid, H, gw.dlogit, mv.D, nullptr, 0, nullptr, nullptr, B, mv.pol2, gw.partial, grad, generic, s);
+    mark(PL_STAGE_BW_WGRAD, false);
 }
 
 }  // namespace pl
