@@ -129,6 +129,71 @@ def test_accumulation_linearity_and_rejected_states():
     assert np.isnan(got["logp"][1]) and np.isnan(got["logp"][2]) and np.isfinite(got["logp"][[0, 3]]).all()
 
 
+def test_gradient_replays_from_a_hip_graph():
+    """After the first call on a batch a gradient call only launches kernels (the zero fill is a
+    kernel too), so it can be captured once and replayed: replays on new states, with eager work
+    in between, each equal bit for bit to the eager result on the same state."""
+    import torch
+    import paper_1906_08879_amd as pl
+    from workloads import make_states
+    dev = torch.device("cuda:0")
+    w = make_workload("layered200", B=8)
+    placement, cur, done = make_states(w, 3)
+    g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+    wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+    n_par = pl.weights_count(w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+    rng = np.random.default_rng(2)
+    act = torch.from_numpy(rng.integers(0, w.D, w.B).astype(np.int32)).to(dev)
+    coef = torch.from_numpy(rng.normal(0, 1, w.B).astype(np.float32)).to(dev)
+
+    def state(s):
+        f = np.array(w.node_feats, dtype=np.float32)
+        f[:, 2] = done[s]
+        return torch.from_numpy(f).to(dev), torch.from_numpy(placement[s]).to(dev), torch.from_numpy(cur[s]).to(dev)
+
+    f_in, p_in, c_in = state(0)
+    logits = torch.empty((w.B, w.D), dtype=torch.float32, device=dev)
+    grad = torch.empty((n_par,), dtype=torch.float32, device=dev)
+    eager = torch.empty_like(grad)
+    pl.policy_gradient(g, f_in, p_in, c_in, wt, act, coef, eager, logits)      # first call: allocates
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        pl.policy_gradient(g, f_in, p_in, c_in, wt, act, coef, grad, logits, stream=side)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    for s in (1, 2, 1):
+        f, p, c = state(s)
+        pl.policy_gradient(g, f, p, c, wt, act, coef, eager, logits)            # eager work between the replays
+        torch.cuda.synchronize()
+        f_in.copy_(f); p_in.copy_(p); c_in.copy_(c)
+        grad.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(grad.cpu().numpy(), eager.cpu().numpy())
+    del graph
+    g.close()
+    wt.close()
+
+
+def test_empty_batch_is_accepted():
+    import torch
+    import paper_1906_08879_amd as pl
+    dev = torch.device("cuda:0")
+    g = pl.GraphBatch([], [], [], [])
+    wt = pl.Weights(np.zeros(pl.weights_count(2, 8), np.float32), 2, 8)
+    z_f, z_i = torch.zeros(4, dtype=torch.float32, device=dev), torch.zeros(4, dtype=torch.int32, device=dev)
+    grad = torch.full((pl.weights_count(2, 8),), 3.0, dtype=torch.float32, device=dev)
+    pl.policy_gradient(g, z_f, z_i, z_i, wt, z_i, z_f, grad, z_f)
+    torch.cuda.synchronize()
+    assert (grad == 3.0).all()                  # nothing to add, nothing touched
+    g.close()
+    wt.close()
+
+
 def test_more_than_one_sweep_is_refused():
     import paper_1906_08879_amd as pl
     rng = np.random.default_rng(6)
