@@ -240,7 +240,7 @@ void free_workspace(Workspace &ws)
 
 void free_grad_workspace(GradWorkspace &gw)
 {
-    float *all[] = {gw.fact, gw.gact, gw.agg, gw.dagg, gw.dfg, gw.extb, gw.lact, gw.dl, gw.demb, gw.dx, gw.phi,
+    float *all[] = {gw.fact, gw.gact, gw.agg, gw.dagg, gw.dfg, gw.keep, gw.extb, gw.lact, gw.dl, gw.demb, gw.dx, gw.phi,
                     gw.pooled, gw.dP, gw.hin, gw.hact, gw.dh, gw.dz, gw.hid, gw.dpre, gw.dlogit, gw.partial};
     for (float *p : all) (void)hipFree(p);
     (void)hipFree(gw.cls);
@@ -310,6 +310,7 @@ int ensure_grad_workspace(pl_graph_batch *g, const ModelView &mv)
     PL_HIP(hipMemset(gw.dagg, 0, sizeof(float) * (2 * NH + 2 * H)));
     gw.dfg_stride = 2 * L * NH + H;
     PL_HIP(take(&gw.dfg, 2 * gw.dfg_stride));
+    PL_HIP(take(&gw.keep, 2 * gw.dfg_stride));
     PL_HIP(take(&gw.extb, 2 * NH + H));
     PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.mask4), 2 * NH + 16));
     PL_HIP(take(&gw.lact, L * NH));
@@ -389,7 +390,8 @@ void stage_mark(void *ctx, int stage, bool begin, hipStream_t s)
 
 int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
                  const int32_t *cur_node, const pl_weights *w, float *out_logits, float *out_probs,
-                 float *out_node_emb, float *out_pooled, void *stream)
+                 float *out_node_emb, float *out_pooled, void *stream, float *keep = nullptr,
+                 size_t keep_stride = 0)
 {
     if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
     if (g->host.B == 0) return PL_OK;
@@ -416,7 +418,7 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
         for (int k = 0; k < w->cfg.k_sweeps; ++k) {
             if (mfma)
                 launch_sweep_mfma(gv, mv, g->ws, fa, reinterpret_cast<const uint4 *>(w->d_wfrag),
-                                  w->d_sweep_bias, w->sweep_ws, k == 0, k + 1 < w->cfg.k_sweeps, s);
+                                  w->d_sweep_bias, w->sweep_ws, k == 0, k + 1 < w->cfg.k_sweeps, keep, keep_stride, s);
             else
                 launch_sweep_generic(gv, mv, g->ws, fa, k == 0, s);
         }
@@ -793,19 +795,22 @@ int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t
     const ModelView &mv = w->view;
     if ((rc = ensure_grad_workspace(g, mv))) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    rc = forward_impl(g, node_feats, placement, cur_node, w, out_logits, nullptr, nullptr, g->gw.pooled, stream);
-    if (rc) return rc;
-    if (!accumulate) launch_fill_zero(grad, plan_weights(w->cfg, nullptr), s);
-    ForwardArgs fa{node_feats, placement, cur_node, out_logits, nullptr, g->gw.pooled};
     // the chain kernel addresses the delta arrays with 32-bit element offsets
     const bool fits = (2.0 * mv.L * static_cast<double>(g->host.n_tot) + 1) * mv.H < 2.0e9 &&
                       (static_cast<double>(g->host.n_tot) + 2) * 2 * mv.H * sizeof(float) < 4.0e9;
     const bool chain_cores = w->d_wfrag_bw && w->path == 0 && w->cfg.k_sweeps == 1 && fits;
+    // on that path the forward sweep keeps a_v and the layer outputs, so nothing is computed twice
+    float *keep = chain_cores ? g->gw.keep : nullptr;
+    rc = forward_impl(g, node_feats, placement, cur_node, w, out_logits, nullptr, nullptr, g->gw.pooled, stream,
+                      keep, g->gw.dfg_stride);
+    if (rc) return rc;
+    if (!accumulate) launch_fill_zero(grad, plan_weights(w->cfg, nullptr), s);
+    ForwardArgs fa{node_feats, placement, cur_node, out_logits, nullptr, g->gw.pooled};
     const StageMarks marks{&g->timer, stage_mark};
     launch_backward_generic(g->view, mv, w->d_blob_t, g->ws, g->gw, fa, actions, coeff, w->cfg.k_sweeps,
                             g->ws.n_chunks, w->path,
                             chain_cores ? reinterpret_cast<const uint4 *>(w->d_wfrag_bw) : nullptr,
-                            w->d_sweep_bias, w->sweep_ws, grad, out_logp, &marks, s);
+                            w->d_sweep_bias, w->sweep_ws, keep, grad, out_logp, &marks, s);
     PL_HIP(hipGetLastError());
     return PL_OK;
 }

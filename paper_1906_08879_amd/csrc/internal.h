@@ -191,6 +191,8 @@ struct GradWorkspace {
     float *dfg = nullptr;                     // per direction [2L, n_tot, H] layer deltas of f, then of g,
                                               // then H spare floats; dfg_stride floats per direction
     size_t dfg_stride = 0;
+    float *keep = nullptr;                    // per direction [2L, n_tot, H]: a_v and layer outputs stored by
+                                              // the forward sweep (same stride as dfg)
     float *extb = nullptr;                    // [2, n_tot, H] outside gradient of the states, bucket order
     uint8_t *mask4 = nullptr;                 // [2, n_tot, H] ReLU gates, bucket order
     float *lact = nullptr, *dl = nullptr;     // [L, n_tot, H] layer outputs / deltas of l (own set)
@@ -223,7 +225,8 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
                              const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
                              const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
                              int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
-                             float *grad, float *out_logp, const StageMarks *marks, hipStream_t s);
+                             const float *keep, float *grad, float *out_logp, const StageMarks *marks,
+                             hipStream_t s);
 
 // ---- matrix-core sweep (kernels_mfma.hip)
 bool sweep_mfma_supported(int H, int L, int weight_dtype);
@@ -234,6 +237,6 @@ void launch_sweep_mfma_bw(const GraphView &gv, const ModelView &mv, const uint4 
                           const uint8_t *mask4, float *delta, size_t delta_stride, hipStream_t s);
 void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                        const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
-                       bool first_sweep, bool more_sweeps, hipStream_t s);
+                       bool first_sweep, bool more_sweeps, float *keep, size_t keep_stride, hipStream_t s);
 
 }  // namespace pl

@@ -526,12 +526,16 @@ __global__ __launch_bounds__(kThreads) void k_bw_sweep_generic(GraphView gv, Mod
 // the ReLU gates of the node's layers, one byte per (node, column): bit 0 m_v > 0, bit 1 output
 // of f's layer 0 > 0 (L = 2), bit 2 output of g's last layer > 0, bit 3 output of g's layer 0 > 0
 // (L = 2).
+struct GateSrc {
+    const float *m;        // [n_tot, H] messages (output of f's last layer)
+    const float *f0;       // output of f's layer 0 (L = 2)
+    const float *g_last;   // output of g's last layer
+    const float *g0;       // output of g's layer 0 (L = 2)
+};
+
 __global__ __launch_bounds__(kThreads) void k_bw_prep(GraphView gv, int H, int L,
-                                                      const float *__restrict__ demb,
-                                                      const float *__restrict__ fact,
-                                                      const float *__restrict__ gact,
-                                                      const float *__restrict__ msgs,
-                                                      float *__restrict__ extb,
+                                                      const float *__restrict__ demb, GateSrc src0,
+                                                      GateSrc src1, float *__restrict__ extb,
                                                       uint8_t *__restrict__ mask4)
 {
     const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
@@ -541,14 +545,12 @@ __global__ __launch_bounds__(kThreads) void k_bw_prep(GraphView gv, int H, int L
         const int sd = 1 - pd;
         const size_t at = (static_cast<size_t>(pd) * gv.n_tot + gv.pos[pd][v]) * H + h;
         extb[at] = demb[static_cast<size_t>(v) * 2 * H + sd * H + h];
-        // m_v: from the forward pass's message buffer [2, n_tot, H] when given, else recomputed
-        const float m = msgs ? msgs[static_cast<size_t>(sd) * gv.n_tot * H + idx]
-                             : fact[slab(sd, L - 1, L, gv.n_tot, H) + idx];
-        int bits = m > 0.0f ? 1 : 0;
-        bits |= gact[slab(sd, L - 1, L, gv.n_tot, H) + idx] > 0.0f ? 4 : 0;
+        const GateSrc &gs = sd ? src1 : src0;
+        int bits = gs.m[idx] > 0.0f ? 1 : 0;
+        bits |= gs.g_last[idx] > 0.0f ? 4 : 0;
         if (L == 2) {
-            bits |= fact[slab(sd, 0, L, gv.n_tot, H) + idx] > 0.0f ? 2 : 0;
-            bits |= gact[slab(sd, 0, L, gv.n_tot, H) + idx] > 0.0f ? 8 : 0;
+            bits |= gs.f0[idx] > 0.0f ? 2 : 0;
+            bits |= gs.g0[idx] > 0.0f ? 8 : 0;
         }
         mask4[at] = static_cast<uint8_t>(bits);
     }
@@ -1227,7 +1229,8 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
                              const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
                              const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
                              int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
-                             float *grad, float *out_logp, const StageMarks *marks, hipStream_t s)
+                             const float *keep, float *grad, float *out_logp, const StageMarks *marks,
+                             hipStream_t s)
 {
     if (gv.B == 0) return;
     const int H = mv.H, L = mv.L, G = mv.G, B = gv.B, n = gv.n_tot;
@@ -1296,9 +1299,21 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
 #undef CALL
     }
     mark(PL_STAGE_BW_POOL, false);
-    // 3. sweeps
+    // 3. sweeps.  Where the layer outputs live: kept by the forward sweep (keep: slot 0 a_v, slots
+    // 1 .. L g's layers, then f's layers but the last), or recomputed into fact / gact / agg.
+    auto agg_of = [&](int dir) {
+        return keep ? keep + dir * gw.dfg_stride : gw.agg + static_cast<size_t>(dir) * NH;
+    };
+    auto gact_of = [&](int dir, int l) {
+        return keep ? keep + dir * gw.dfg_stride + static_cast<size_t>(1 + l) * NH
+                    : gw.gact + (static_cast<size_t>(dir) * L + l) * NH;
+    };
+    auto fact_of = [&](int dir, int l) {       // l < L - 1 on the keep path (the last layer is ws.msg)
+        return keep ? keep + dir * gw.dfg_stride + static_cast<size_t>(1 + L + l) * NH
+                    : gw.fact + (static_cast<size_t>(dir) * L + l) * NH;
+    };
     mark(PL_STAGE_BW_ACTS, true);
-    if (k_sweeps > 0 && dense) {
+    if (k_sweeps > 0 && dense && !keep) {
         // the last layer of f is the message itself, which the forward pass left in ws.msg (the
         // generic chain kernel reads it from fact, so there it is computed again)
         for (int dir = 0; dir < 2; ++dir)
@@ -1331,10 +1346,18 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
             PL_DISPATCH_RPT(rpt, CALL)
 #undef CALL
         }
-        if (wfrag_bw)
+        if (wfrag_bw) {
+            GateSrc src[2];
+            for (int sd = 0; sd < 2; ++sd) {
+                const bool from_msg = keep || dense;
+                src[sd].m = from_msg ? ws.msg + static_cast<size_t>(sd) * NH : fact_of(sd, L - 1);
+                src[sd].f0 = L == 2 ? fact_of(sd, 0) : nullptr;
+                src[sd].g_last = gact_of(sd, L - 1);
+                src[sd].g0 = L == 2 ? gact_of(sd, 0) : nullptr;
+            }
             hipLaunchKernelGGL(k_bw_prep, dim3(static_cast<unsigned>((NH + kThreads - 1) / kThreads)),
-                               dim3(kThreads), 0, s, gv, H, L, gw.demb, gw.fact, gw.gact, dense ? ws.msg : nullptr, gw.extb,
-                               gw.mask4);
+                               dim3(kThreads), 0, s, gv, H, L, gw.demb, src[0], src[1], gw.extb, gw.mask4);
+        }
         mark(PL_STAGE_BW_ACTS, false);
         mark(PL_STAGE_BW_CHAIN, true);
         if (wfrag_bw) {
@@ -1377,11 +1400,10 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
             for (int l = 0; l < L; ++l) {
                 const float *dfl = gw.dfg + dir * gw.dfg_stride + static_cast<size_t>(l) * NH;
                 const float *dgl = dfl + static_cast<size_t>(L) * NH;
-                const float *fin = l == 0 ? ws.emb + dir * H : gw.fact + (static_cast<size_t>(dir) * L + l - 1) * NH;
+                const float *fin = l == 0 ? ws.emb + dir * H : fact_of(dir, l - 1);
                 launch_wgrad(fin, l == 0 ? 2 * H : H, dfl, H, nullptr, 0, nullptr, nullptr, n, mv.f[dir].layer[l],
                              gw.partial, grad, generic, s);
-                const float *gin = l == 0 ? gw.agg + static_cast<size_t>(dir) * NH
-                                          : gw.gact + (static_cast<size_t>(dir) * L + l - 1) * NH;
+                const float *gin = l == 0 ? agg_of(dir) : gact_of(dir, l - 1);
                 launch_wgrad(gin, H, dgl, H, nullptr, 0, nullptr, nullptr, n, mv.g[dir].layer[l], gw.partial, grad, generic, s);
             }
     }

@@ -108,10 +108,15 @@ constexpr int sweep_waves(int H) { return H / 16 > 4 ? 4 : H / 16; }
 // result da_v goes where the forward pass puts the message.  ReLU and bias are replaced by the
 // stored gates, table entries are signed (no reachability flag), and every gated layer input
 // is also written to HBM as the layer's delta for the weight gradients.
-template <int H, int WS, int L, bool FF, bool WX, bool BW = false>
+// TR: a forward sweep that also keeps what the reverse pass needs of every node: the gathered
+// sum a_v and the output of every layer but the last (the last is the message, stored anyway),
+// 2L arrays [n_tot, H] per direction in `delta` (slot 0: a_v, slots 1 .. L: g's layers, slots
+// L + 1 .. 2L - 1: f's layers but the last).
+template <int H, int WS, int L, bool FF, bool WX, bool BW = false, bool TR = false>
 __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepParams P)
 {
     static_assert(!BW || (!FF && !WX), "the reverse pass reads its input from xb and writes no xb");
+    static_assert(!TR || (FF && !WX && !BW), "activations are kept for a single forward sweep");
     constexpr int NW = sweep_waves(H);         // waves; wave w owns output columns [w WC, (w + 1) WC)
     constexpr int kThreads = 64 * NW;
     constexpr int NTL = H / 16, KS = H / 32;
@@ -257,6 +262,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     s[t] = (mk[ct][t] & 1) ? s[t] : 0.0f;
                     gs[ct][t] = s[t];
                 }
+                if constexpr (TR) gs[ct][t] = s[t];
                 put_parts(0, 4 * ct + kg, wc0 + 16 * t + col, s[t]);
             }
             bit[ct] = static_cast<int>(signs >> 31);
@@ -372,6 +378,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     s[t] = (mk[ct][t] & 1) ? s[t] : 0.0f;
                     gs[ct][t] = s[t];
                 }
+                if constexpr (TR) gs[ct][t] = s[t];
                 put_parts(0, 4 * ct + kg, wc0 + 16 * t + col, s[t]);
             }
             bit[ct] = static_cast<int>(signs >> 31);
@@ -405,7 +412,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     int mk0[NT][TPW], mk1[NT][TPW];   // (BW) gate bytes of the rows of chunk c, c + 1
     float gs0[NT][TPW];      // (BW) gated gathered sums of chunk c: the delta of f's last layer
     const uint8_t *mask4 = BW ? P.mask4 + static_cast<size_t>(dir) * gv.n_tot * H : nullptr;
-    float *dlt = BW ? P.delta + static_cast<size_t>(1 - dir) * P.delta_stride : nullptr;
+    float *dlt = BW ? P.delta + static_cast<size_t>(1 - dir) * P.delta_stride
+                    : (TR ? P.delta + static_cast<size_t>(dir) * P.delta_stride : nullptr);
 #pragma unroll
     for (int ct = 0; ct < NT; ++ct)
 #pragma unroll
@@ -562,6 +570,12 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         continue;
                     }
                     y = fmaxf(y + bias[n][t], 0.0f);
+                    if constexpr (TR) {
+                        const uint32_t d_row = live ? static_cast<uint32_t>(vg0[ct] * H + m)
+                                                    : static_cast<uint32_t>(2 * L * gv.n_tot * H + m);
+                        if (n == 0) dlt[d_row] = gs0[ct][t];
+                        if (n < NL - 1) dlt[live ? static_cast<uint32_t>((1 + n) * gv.n_tot * H) + d_row : d_row] = y;
+                    }
                     if (n == L - 1) {                    // end of g: residual update of s_v
                         y += x0[ct][t];
                         P.emb[static_cast<uint32_t>(v_emb * 2 * H + dir * H + m)] = y;
@@ -808,11 +822,14 @@ bool sweep_mfma_supported(int H, int L, int weight_dtype)
 
 void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                        const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
-                       bool first_sweep, bool more_sweeps, hipStream_t s)
+                       bool first_sweep, bool more_sweeps, float *keep, size_t keep_stride, hipStream_t s)
 {
     if (gv.B == 0) return;
+    // keep: where a single sweep also stores a_v and the layer outputs for the reverse pass (TR)
+    const bool tr = keep && first_sweep && !more_sweeps;
     SweepParams P{gv, wfrag, bias, ws.emb, ws.xb, ws.msg, ws.reach, fa.cur_node,
-                  ws.featb, first_sweep ? mv.blob + mv.proj.w : nullptr, mv.D, nullptr, nullptr, 0};
+                  ws.featb, first_sweep ? mv.blob + mv.proj.w : nullptr, mv.D, nullptr, tr ? keep : nullptr,
+                  tr ? keep_stride : 0};
     if (first_sweep)
         hipLaunchKernelGGL(k_bucket_feats, dim3((gv.n_tot + 255) / 256), dim3(256), 0, s, gv, fa.node_feats,
                            fa.placement, fa.cur_node, mv.D, ws.featb);
@@ -820,7 +837,9 @@ void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace
 #define PL_CASE(HH, WW, LL)                                                      \
     if (mv.H == HH && WS == WW && mv.L == LL) {                                  \
         const dim3 block(64 * sweep_waves(HH));                                  \
-        if (first_sweep && more_sweeps)                                          \
+        if (tr)                                                                  \
+            hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, true, false, false, true>), grid, block, 0, s, P); \
+        else if (first_sweep && more_sweeps)                                     \
             hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, true, true>), grid, block, 0, s, P);   \
         else if (first_sweep)                                                    \
             hipLaunchKernelGGL((k_sweep_mfma<HH, WW, LL, true, false>), grid, block, 0, s, P);  \
