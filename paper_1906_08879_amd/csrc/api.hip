@@ -391,7 +391,7 @@ void stage_mark(void *ctx, int stage, bool begin, hipStream_t s)
 int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
                  const int32_t *cur_node, const pl_weights *w, float *out_logits, float *out_probs,
                  float *out_node_emb, float *out_pooled, void *stream, float *keep = nullptr,
-                 size_t keep_stride = 0)
+                 size_t keep_stride = 0, float *keep_pool = nullptr, bool *pool_kept = nullptr)
 {
     if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
     if (g->host.B == 0) return PL_OK;
@@ -428,9 +428,10 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
         StageScope scope(g->timer, PL_STAGE_POOL, s);
         if (pool_mfma)
             launch_pool_mfma(gv, mv, g->ws, fa, reinterpret_cast<const uint4 *>(w->d_pool_frag),
-                             w->d_pool_bias, w->sweep_ws, s);
+                             w->d_pool_bias, w->sweep_ws, keep_pool, s);
         else
             launch_pool_generic(gv, mv, g->ws, fa, s);
+        if (pool_kept) *pool_kept = pool_mfma && keep_pool;
     }
     {
         StageScope scope(g->timer, PL_STAGE_HEAD, s);
@@ -801,8 +802,10 @@ int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t
     const bool chain_cores = w->d_wfrag_bw && w->path == 0 && w->cfg.k_sweeps == 1 && fits;
     // on that path the forward sweep keeps a_v and the layer outputs, so nothing is computed twice
     float *keep = chain_cores ? g->gw.keep : nullptr;
+    // likewise the matrix-core pooling kernel keeps the outputs of l's layers
+    bool pool_kept = false;
     rc = forward_impl(g, node_feats, placement, cur_node, w, out_logits, nullptr, nullptr, g->gw.pooled, stream,
-                      keep, g->gw.dfg_stride);
+                      keep, g->gw.dfg_stride, w->path == 0 ? g->gw.lact : nullptr, &pool_kept);
     if (rc) return rc;
     if (!accumulate) launch_fill_zero(grad, plan_weights(w->cfg, nullptr), s);
     ForwardArgs fa{node_feats, placement, cur_node, out_logits, nullptr, g->gw.pooled};
@@ -810,7 +813,7 @@ int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t
     launch_backward_generic(g->view, mv, w->d_blob_t, g->ws, g->gw, fa, actions, coeff, w->cfg.k_sweeps,
                             g->ws.n_chunks, w->path,
                             chain_cores ? reinterpret_cast<const uint4 *>(w->d_wfrag_bw) : nullptr,
-                            w->d_sweep_bias, w->sweep_ws, keep, grad, out_logp, &marks, s);
+                            w->d_sweep_bias, w->sweep_ws, keep, pool_kept, grad, out_logp, &marks, s);
     PL_HIP(hipGetLastError());
     return PL_OK;
 }

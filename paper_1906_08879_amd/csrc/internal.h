@@ -182,7 +182,7 @@ void pack_pool_weights(const ModelView &mv, const float *blob, int WS, std::vect
                        std::vector<float> *bias);
 void launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                       const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
-                      hipStream_t s);
+                      float *keep, hipStream_t s);
 
 // ---- policy gradient (kernels_backward.hip): buffers owned by a batch for one (D, H, L)
 struct GradWorkspace {
@@ -225,8 +225,8 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
                              const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
                              const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
                              int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
-                             const float *keep, float *grad, float *out_logp, const StageMarks *marks,
-                             hipStream_t s);
+                             const float *keep, bool pool_kept, float *grad, float *out_logp,
+                             const StageMarks *marks, hipStream_t s);
 
 // ---- matrix-core sweep (kernels_mfma.hip)
 bool sweep_mfma_supported(int H, int L, int weight_dtype);

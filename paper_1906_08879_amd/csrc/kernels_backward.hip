@@ -1229,8 +1229,8 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
                              const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
                              const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
                              int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
-                             const float *keep, float *grad, float *out_logp, const StageMarks *marks,
-                             hipStream_t s)
+                             const float *keep, bool pool_kept, float *grad, float *out_logp,
+                             const StageMarks *marks, hipStream_t s)
 {
     if (gv.B == 0) return;
     const int H = mv.H, L = mv.L, G = mv.G, B = gv.B, n = gv.n_tot;
@@ -1269,7 +1269,7 @@ void launch_backward_generic(const GraphView &gv, const ModelView &mv, const flo
         for (int set = 0; set < 3; ++set) {
             const int32_t *list = gw.lists + static_cast<size_t>(set) * n, *cnt = gw.counts + set;
             const MlpRef &ln = mv.l[set];
-            for (int l = 0; l < L; ++l)
+            for (int l = 0; l < L && !pool_kept; ++l)     // kept: the forward pooling kernel wrote lact
                 launch_dense({l == 0 ? ws.emb : gw.lact + static_cast<size_t>(l - 1) * NH, l == 0 ? 2 * H : H, list,
                               cnt, n, l == 0 ? 2 * H : H, mv.blob + ln.layer[l].w, H, mv.blob + ln.layer[l].b, 1,
                               nullptr, 0, gw.lact + static_cast<size_t>(l) * NH, H}, H, s);

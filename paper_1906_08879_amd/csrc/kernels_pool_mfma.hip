@@ -55,9 +55,12 @@ struct PoolParams {
     float *partial;            // [B, max_slices, 3, G, H] sums over a slice of the graph's nodes
     int max_slices;
     int D, G;
+    float *keep;               // (KEEP) [L][n_tot, H]: the outputs of l's layers for every node of a set
 };
 
-template <int H, int WS, int L>
+// KEEP: the outputs of every layer of l_i are also written to HBM, by the lane that holds them,
+// for the reverse pass (a node belongs to one set and is handled by one workgroup).
+template <int H, int WS, int L, bool KEEP = false>
 __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
 {
     constexpr int K1 = 2 * H;                    // input width of the first layer
@@ -247,6 +250,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
                     const float r = y - trunc_bf16(y);
                     const float l = r - trunc_bf16(r);
                     const int node = 4 * kg + i, c = 16 * nt + col;
+                    if constexpr (KEEP) {
+                        if (node < cnt) P.keep[static_cast<size_t>(batch_node[my_slot][node]) * H + c] = y;
+                    }
                     reinterpret_cast<unsigned short *>(&act2[0][node][c])[0] = static_cast<unsigned short>(__float_as_uint(y) >> 16);
                     reinterpret_cast<unsigned short *>(&act2[1][node][c])[0] = static_cast<unsigned short>(__float_as_uint(r) >> 16);
                     reinterpret_cast<unsigned short *>(&act2[2][node][c])[0] = static_cast<unsigned short>(__float_as_uint(l) >> 16);
@@ -283,6 +289,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
             for (int t = 0; t < TPW; ++t) {
                 const float bl = (L > 1) ? bias2[t] : bias1[t];
                 y[i][t] = fmaxf(acc[0][t][i] + acc[1][t][i] + acc[2][t][i] + bl, 0.0f);
+                if constexpr (KEEP) {
+                    const int nt = wave * TPW + t;
+                    if (node < cnt && nt < NTL)
+                        P.keep[(static_cast<size_t>(L - 1) * gv.n_tot + batch_node[my_slot][node]) * H + 16 * nt + col] = y[i][t];
+                }
             }
         }
         // rows past the end of the batch hold earlier, finite outputs: weight 0 removes them
@@ -376,16 +387,19 @@ bool pool_mfma_supported(int H, int L, int weight_dtype)
 
 void launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                       const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
-                      hipStream_t s)
+                      float *keep, hipStream_t s)
 {
     if (gv.B == 0) return;
     PoolParams P{gv, wfrag, bias, ws.emb, ws.reach, fa.placement, fa.cur_node, ws.partial,
-                 kPoolSlices, mv.D, mv.G};
+                 kPoolSlices, mv.D, mv.G, keep};
     const dim3 grid(3, kPoolSlices, gv.B), block(kThreads);
-#define PL_CASE(HH, WW, LL)                                                    \
-    if (mv.H == HH && WS == WW && mv.L == LL) {                                \
-        hipLaunchKernelGGL((k_pool_mfma<HH, WW, LL>), grid, block, 0, s, P);   \
-        return;                                                                \
+#define PL_CASE(HH, WW, LL)                                                          \
+    if (mv.H == HH && WS == WW && mv.L == LL) {                                      \
+        if (keep)                                                                    \
+            hipLaunchKernelGGL((k_pool_mfma<HH, WW, LL, true>), grid, block, 0, s, P); \
+        else                                                                         \
+            hipLaunchKernelGGL((k_pool_mfma<HH, WW, LL>), grid, block, 0, s, P);     \
+        return;                                                                      \
     }
     PL_CASE(128, 1, 2) PL_CASE(128, 1, 1)
     PL_CASE(64, 1, 2) PL_CASE(64, 1, 1) PL_CASE(64, 3, 2) PL_CASE(64, 3, 1)
