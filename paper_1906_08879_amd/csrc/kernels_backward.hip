@@ -958,7 +958,7 @@ __global__ __launch_bounds__(kThreads) void k_wgrad(const float *__restrict__ A,
 // memory once per workgroup (coalesced float4), the loads of chunk c + 1 travel during the 32
 // matrix instructions of chunk c, and the ids of a row list are read one chunk further ahead.
 // Row strides in LDS keep the two halves of a wave on different banks.
-constexpr int kWgRC = 16;
+constexpr int kWgRC = 32;
 
 constexpr int wgrad_ldd(int J) { return J == 128 ? 160 : 96; }
 constexpr size_t wgrad_lds_bytes(int NJ) { return sizeof(float) * 2 * kWgRC * (160 + wgrad_ldd(32 * NJ)); }
@@ -988,10 +988,11 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict
     // this thread's pieces of a chunk: A rows ar + 8 q, floats ac .. ac + 3; Dl element 4 (tid + 256 q)
     const int ar = tid >> 5, ac = (tid & 31) * 4;
     const bool a_col_ok = iw + ac < I;
-    int ida[2], idd[DQ];
+    constexpr int AQ = kWgRC / 8;                          // A pieces per thread and chunk
+    int ida[AQ], idd[DQ];
     auto load_ids = [&](int r0) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < AQ; ++q) {
             const int row = r0 + ar + 8 * q;
             ida[q] = row < r_end ? (rows ? rows[row] : row) : -1;
         }
@@ -1002,10 +1003,10 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict
             idd[q] = (e < kWgRC * J && row < r_end) ? (rows ? rows[row] : row) : -1;
         }
     };
-    f32x4v areg[2], dreg[DQ];
+    f32x4v areg[AQ], dreg[DQ];
     auto fetch = [&]() {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < AQ; ++q) {
             const f32x4v v = *reinterpret_cast<const f32x4v *>(
                 A + static_cast<size_t>(max(ida[q], 0)) * lda + (a_col_ok ? iw + ac : 0));
             areg[q] = (ida[q] >= 0 && a_col_ok) ? v : f32x4v{0.f, 0.f, 0.f, 0.f};
@@ -1019,7 +1020,7 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict
     };
     auto stash = [&](int buf) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
+        for (int q = 0; q < AQ; ++q)
             *reinterpret_cast<f32x4v *>(as + (buf * kWgRC + ar + 8 * q) * LDA_S + ac) = areg[q];
 #pragma unroll
         for (int q = 0; q < DQ; ++q) {
@@ -1140,7 +1141,7 @@ void allow_lds_bw(K kernel, size_t bytes)
 // the matrix-core contraction wants about four workgroups per CU
 int wgrad_rows_per_slab_cores(int64_t R)
 {
-    int64_t per = (R + 1023) / 1024;
+    int64_t per = (R + 511) / 512;
     if (per < 64) per = 64;
     return static_cast<int>((per + 7) / 8 * 8);
 }
@@ -1182,15 +1183,12 @@ void launch_wgrad(const float *A, int lda, const float *Dl, int ldd, const uint8
     if (cores) {
         // with a row list (the nodes of one set, ascending) the class filter is not needed
         const dim3 grid((I + 127) / 128, slabs);
-        if (J == 32)
-            hipLaunchKernelGGL(k_wgrad_mfma<1>, grid, dim3(kThreads), wgrad_lds_bytes(1), s, A, lda, Dl, ldd, list, list_count,
-                               static_cast<int>(R), I, per, partial);
-        else if (J == 64)
-            hipLaunchKernelGGL(k_wgrad_mfma<2>, grid, dim3(kThreads), wgrad_lds_bytes(2), s, A, lda, Dl, ldd, list, list_count,
-                               static_cast<int>(R), I, per, partial);
-        else
-            hipLaunchKernelGGL(k_wgrad_mfma<4>, grid, dim3(kThreads), wgrad_lds_bytes(4), s, A, lda, Dl, ldd, list, list_count,
-                               static_cast<int>(R), I, per, partial);
+#define CALL(NJ)                                                                                           \
+    allow_lds_bw(k_wgrad_mfma<NJ>, wgrad_lds_bytes(NJ));                                                   \
+    hipLaunchKernelGGL(k_wgrad_mfma<NJ>, grid, dim3(kThreads), wgrad_lds_bytes(NJ), s, A, lda, Dl, ldd, list, \
+                       list_count, static_cast<int>(R), I, per, partial)
+        if (J == 32) { CALL(1); } else if (J == 64) { CALL(2); } else { CALL(4); }
+#undef CALL
     } else {
         hipLaunchKernelGGL(k_wgrad, dim3((I + kWgI - 1) / kWgI, slabs), dim3(kThreads), 0, s, A, lda, Dl, ldd,
                            row_cls, want, static_cast<int>(R), I, J, per, partial);
