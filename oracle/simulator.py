@@ -22,7 +22,16 @@ Readings where the paper is silent:
  * timestamps are float32, formed as start + cost and start + size * (1 / bandwidth) with one
    rounding per operation: the event order is an integer decision taken in this precision
    on both sides, so the two timelines are identical event by event;
- * the peak-memory term of the reward is not modelled (the paper gives no formula for it).
+ * peak memory (the paper only says that the start and end timestamps of the operations and the
+   tensor sizes are used to predict it; the model below is this build's reading): the output of
+   an operation occupies its own device from the operation's START until the latest of its own
+   end, the end of its last consumer on that device and the arrival of its last outgoing
+   transfer; on every other device that consumes it, a copy lives from the transfer's arrival
+   until the end of its last consumer there.  Intervals are half-open [alloc, free): what is
+   freed at time t does not count at t.  A device's peak is the largest sum of live sizes at
+   any allocation time (the sum can only grow at an allocation); m is the largest peak over
+   the devices, and the reward's memory-penalised run time is the appendix's
+   R(p) = r if m <= M else r + c (m - M), c = 2 in the paper.
 """
 from __future__ import annotations
 
@@ -63,6 +72,8 @@ def simulate(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth, trace=No
                 o = q_op[d].popleft()
                 ev[d] = (F(now + cost[o]), seq, o, -1)
                 seq += 1
+                if trace is not None:
+                    trace.append(("start", o, d, float(now)))
         for d in range(D):
             if D + d not in ev and q_tr[d]:
                 o, dc = q_tr[d].popleft()
@@ -102,3 +113,64 @@ def simulate(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth, trace=No
         wake(now)
     assert (pend == 0).all(), "an operation never became runnable"
     return last, n_events
+
+
+def timeline(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth):
+    """The simulated timeline: (runtime, op_start [n], op_end [n], arrival [n, D]) with
+    arrival[v, d] = time at which v's output reached device d over the bus (-1: it never went
+    there).  float32 timestamps as produced by `simulate`."""
+    trace = []
+    runtime, _ = simulate(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth, trace)
+    op_start = np.full(n, -1.0, dtype=F)
+    op_end = np.full(n, -1.0, dtype=F)
+    arrival = np.full((n, D), -1.0, dtype=F)
+    for kind, o, d, t in trace:
+        if kind == "start":
+            op_start[o] = F(t)
+        elif kind == "op":
+            op_end[o] = F(t)
+        else:
+            arrival[o, d] = F(t)
+    return runtime, op_start, op_end, arrival
+
+
+def tensor_lifetimes(n, src, dst, placement, D, op_start, op_end, arrival):
+    """alloc [n, D], free [n, D]: the interval during which a copy of v's output occupies device d
+    (-1, -1: no copy there), by the reading stated in the module docstring."""
+    placement = np.asarray(placement, dtype=np.int64)
+    alloc = np.full((n, D), -1.0)
+    free = np.full((n, D), -1.0)
+    last_use = np.full((n, D), -1.0)          # end of the last consumer of v on device d
+    for u, c in zip(np.asarray(src).tolist(), np.asarray(dst).tolist()):
+        pc = int(placement[c])
+        last_use[u, pc] = max(last_use[u, pc], float(op_end[c]))
+    for v in range(n):
+        d = int(placement[v])
+        alloc[v, d] = float(op_start[v])
+        free[v, d] = max(float(op_end[v]), last_use[v, d])
+        for o in range(D):
+            if o != d and arrival[v, o] >= 0:
+                free[v, d] = max(free[v, d], float(arrival[v, o]))     # the source stays until it has been sent
+                alloc[v, o] = float(arrival[v, o])
+                free[v, o] = max(float(arrival[v, o]), last_use[v, o])
+    return alloc, free
+
+
+def peak_memory(n, src, dst, out_bytes, placement, D, op_start, op_end, arrival) -> np.ndarray:
+    """peak [D] in float64: for every device the largest sum, over all allocation times t, of the
+    sizes of the copies with alloc <= t < free."""
+    alloc, free = tensor_lifetimes(n, src, dst, placement, D, op_start, op_end, arrival)
+    size = np.asarray(out_bytes, dtype=np.float64)
+    peak = np.zeros(D)
+    for d in range(D):
+        have = alloc[:, d] >= 0
+        a, f, s = alloc[have, d], free[have, d], size[have]
+        for t in a:
+            live = s[(a <= t) & (t < f)].sum()
+            peak[d] = max(peak[d], live)
+    return peak
+
+
+def penalised_runtime(r, m, M, c=2.0):
+    """R(p) of the appendix ("Reward"): r if m <= M, else r + c (m - M)."""
+    return float(r) if m <= M else float(r) + c * (float(m) - float(M))

@@ -60,7 +60,7 @@ def test_device_queue_is_fifo_in_ready_order():
     trace = []
     run(4, [(0, 2), (1, 3)], [2, 1, 5, 5], [0, 0, 0, 0], [0, 0, 0, 0], 1, trace=trace)
     # single device: 0 (0..2), 1 (2..3), then 2 was queued at t=2, 3 at t=3
-    assert [t[1] for t in trace] == [0, 1, 2, 3]
+    assert [t[1] for t in trace if t[0] == "op"] == [0, 1, 2, 3]
     trace = []
     run(4, [(0, 2), (1, 3)], [2, 1, 5, 5], [0, 0, 0, 0], [0, 1, 1, 1], 2, trace=trace)
     order_on_1 = [t[1] for t in trace if t[0] == "op" and t[2] == 1]
@@ -115,3 +115,79 @@ def test_runs_on_a_workload_graph():
     n, src, dst = w.graph(0)[:3]
     r, ev = sim.simulate(n, src, dst, w.node_feats[:n, 0], w.node_feats[:n, 1], w.placement[:n], w.D, 1e-9)
     assert np.isfinite(r) and r > 0 and ev >= n
+
+
+# ---------------------------------------------------------------- peak memory and R(p)
+def _mem(n, edges, cost, size, placement, D, inv_bw=1.0):
+    src = np.array([e[0] for e in edges], dtype=np.int32)
+    dst = np.array([e[1] for e in edges], dtype=np.int32)
+    r, st, en, arr = sim.timeline(n, src, dst, cost, size, placement, D, inv_bw)
+    return r, st, en, arr, sim.peak_memory(n, src, dst, size, placement, D, st, en, arr)
+
+
+def test_peak_memory_of_a_chain_on_one_device():
+    """a -> b -> c on device 0, costs 1, 2, 3, sizes 5, 7, 11.  a lives [0, 3) (until b ends), b
+    [1, 6), c [3, 6): at t = 0: 5; at t = 1: 5 + 7; at t = 3: a is freed, 7 + 11."""
+    r, st, en, arr, peak = _mem(3, [(0, 1), (1, 2)], [1, 2, 3], [5, 7, 11], [0, 0, 0], 2)
+    np.testing.assert_array_equal(st, [0, 1, 3])
+    np.testing.assert_array_equal(en, [1, 3, 6])
+    assert (arr < 0).all()
+    np.testing.assert_allclose(peak, [18.0, 0.0])
+    # a large first tensor instead: the peak is while b runs
+    _, _, _, _, peak = _mem(3, [(0, 1), (1, 2)], [1, 2, 3], [50, 7, 11], [0, 0, 0], 2)
+    np.testing.assert_allclose(peak, [57.0, 0.0])
+
+
+def test_peak_memory_with_a_transfer():
+    """a (device 0, cost 1, size 4) -> b (device 1, cost 2, size 3), bandwidth 1: the transfer runs
+    [1, 5).  Device 0 holds a from its start until the transfer has arrived; device 1 receives the
+    copy at 5 and holds it, with b's output, until b ends at 7."""
+    r, st, en, arr, peak = _mem(2, [(0, 1)], [1, 2], [4, 3], [0, 1], 2)
+    assert r == 7 and arr[0, 1] == 5 and st[1] == 5
+    np.testing.assert_allclose(peak, [4.0, 7.0])
+    src, dst = np.array([0], np.int32), np.array([1], np.int32)
+    alloc, free = sim.tensor_lifetimes(2, src, dst, [0, 1], 2, st, en, arr)
+    np.testing.assert_allclose(alloc, [[0, 5], [-1, 5]])
+    np.testing.assert_allclose(free, [[5, 7], [-1, 7]])
+
+
+def test_peak_memory_fork_join_and_bounds():
+    """a feeds b (same device) and c (other device); d joins them on device 0.  Checked against the
+    intervals written out by hand, and against bounds that hold for any graph."""
+    #      a(0) cost 1 size 2;  b(0) cost 4 size 3;  c(1) cost 1 size 5;  d(0) cost 1 size 7; bandwidth 1
+    r, st, en, arr, peak = _mem(4, [(0, 1), (0, 2), (1, 3), (2, 3)], [1, 4, 1, 1], [2, 3, 5, 7],
+                                [0, 0, 1, 0], 2)
+    # a: [0,1); b: [1,5); transfer a->dev1: [1,3); c on dev1: [3,4); transfer c->dev0: [4,9); d: [9,10)
+    np.testing.assert_array_equal(st, [0, 1, 3, 9])
+    np.testing.assert_array_equal(en, [1, 5, 4, 10])
+    assert arr[0, 1] == 3 and arr[2, 0] == 9 and r == 10
+    # device 0: a [0,5) (b, its consumer, ends at 5), b [1,10), copy of c [9,10), d [9,10)
+    #           t=0: 2; t=1: 2+3; t=9: 3+5+7 = 15
+    # device 1: copy of a [3,4), c [3,9) (until its transfer has arrived): t=3: 2+5 = 7
+    np.testing.assert_allclose(peak, [15.0, 7.0])
+    rng = np.random.default_rng(5)
+    for seed in range(6):
+        n = 14
+        src, dst = tiny_random_dag(np.random.default_rng(seed), n, 0.3)
+        cost = rng.integers(1, 5, n).astype(np.float32)
+        size = rng.integers(1, 9, n).astype(np.float32)
+        D = 3
+        placement = rng.integers(0, D, n)
+        r, st, en, arr = sim.timeline(n, src, dst, cost, size, placement, D, 0.5)
+        peak = sim.peak_memory(n, src, dst, size, placement, D, st, en, arr)
+        alloc, free = sim.tensor_lifetimes(n, src, dst, placement, D, st, en, arr)
+        for d in range(D):
+            on = placement == d
+            copies = alloc[:, d] >= 0
+            assert peak[d] >= (size[on].max() if on.any() else 0.0)        # an output is live while its op runs
+            assert peak[d] <= size[copies].sum() + 1e-9                       # never more than everything at once
+            assert (free[copies, d] >= alloc[copies, d]).all()
+        assert (en >= st).all() and (st >= 0).all()
+
+
+def test_penalised_runtime_formula():
+    """R(p) = r below the limit, r + c (m - M) above it, c = 2 by default (appendix, "Reward")."""
+    assert sim.penalised_runtime(3.0, 10.0, 10.7) == 3.0
+    assert sim.penalised_runtime(3.0, 10.7, 10.7) == 3.0
+    assert abs(sim.penalised_runtime(3.0, 12.7, 10.7) - 7.0) < 1e-12
+    assert abs(sim.penalised_runtime(3.0, 12.7, 10.7, c=0.5) - 4.0) < 1e-12
