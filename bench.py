@@ -199,7 +199,16 @@ def main() -> int:
         pl.simulate_runtime(g, w.D, feats[0], t_place[i % N_STATES], inv_bw, sim_rt, sim_ev, stream=stream)
     torch.cuda.synchronize()
     sim_elapsed = (time.perf_counter() - t0) / sim_reps
+    sim_rew = torch.empty((w.B,), dtype=torch.float32, device=dev)
+    pl.simulate_reward(g, w.D, feats[0], t_place[0], inv_bw, 1e12, 2.0, sim_rew, stream=stream)   # allocates
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(sim_reps):
+        pl.simulate_reward(g, w.D, feats[0], t_place[i % N_STATES], inv_bw, 1e12, 2.0, sim_rew, stream=stream)
+    torch.cuda.synchronize()
+    rew_elapsed = (time.perf_counter() - t0) / sim_reps
     simulator = {"ms_per_batch": round(1e3 * sim_elapsed, 4),
+                 "ms_per_batch_with_peak_memory": round(1e3 * rew_elapsed, 4),
                  "placements_per_s": round(w.B / sim_elapsed, 1),
                  "events_per_s": round(float(sim_ev.sum().item()) / sim_elapsed, 1),
                  "what": "event-driven run-time simulation of one placement per graph (one wave per graph)"}

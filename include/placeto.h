@@ -238,7 +238,7 @@ int pl_episode_gradient(pl_graph_batch *g, const pl_weights *w, float *node_feat
  * ("Simulator"), for every graph of the batch: per device a FIFO queue of runnable operations
  * and a FIFO queue of outgoing tensors, one operation per device and one transfer per bus at a
  * time, transfers overlapping compute; the result is the timestamp of the last op-done event.
- * This is the run time r of the reward R(p); the peak-memory term of R(p) is not modelled.
+ * This is the run time r of the reward R(p); pl_simulate_reward adds the peak-memory term.
  *   node_feats     dev [N_tot, 3]  column 0: run time of the operation, column 1: size of its output
  *   placement      dev [N_tot]     device of every node, in [0, D)
  *   inv_bandwidth                  seconds per unit of output size (a transfer takes size x this)
@@ -251,6 +251,26 @@ int pl_episode_gradient(pl_graph_batch *g, const pl_weights *w, float *node_feat
  * 18 n + 11 e bytes <= 160 KB, else PL_ERR_SHAPE.  Asynchronous on `stream`. */
 int pl_simulate_runtime(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
                         float inv_bandwidth, float *out_runtime, int32_t *out_events, void *stream);
+
+/* The memory-penalised run time of the appendix ("Reward"): R(p) = r if m <= M, else
+ * r + c (m - M), with r the simulated run time (as above), m the largest peak memory over the
+ * devices and c = 2 in the paper.  The appendix says only that the start and end timestamps of
+ * the operations and the tensor sizes predict the peak memory; the model used here: the output
+ * of an operation occupies its device from the operation's start until the latest of its own
+ * end, the end of its last consumer there and the arrival of its last outgoing transfer; on
+ * every other device that consumes it a copy lives from the transfer's arrival until the end of
+ * its last consumer there; intervals are half-open; a device's peak is the largest sum of live
+ * output sizes (column 1 of node_feats, summed in float64) at any allocation time.
+ *   mem_limit      M, in the unit of the output sizes;  mem_penalty  c (>= 0)
+ *   out_reward     dev [B] fp32     R(p); NaN for a graph with a device id outside [0, D)
+ *   out_runtime    dev [B] fp32     r, or NULL
+ *   out_peak_mem   dev [B, D] fp32  peak of every device, or NULL
+ *   out_events     dev [B] int32    as above, or NULL
+ * Other arguments, limits and tie rules as pl_simulate_runtime.  The first call on a batch
+ * allocates the timeline buffers ((2 + 3 D) N_tot floats); asynchronous on `stream`. */
+int pl_simulate_reward(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
+                       float inv_bandwidth, float mem_limit, float mem_penalty, float *out_reward,
+                       float *out_runtime, float *out_peak_mem, int32_t *out_events, void *stream);
 
 /* ---- per-stage timing, for benchmarks.  While enabled, forward and gradient calls bracket each
  * kernel stage with HIP events on the caller's stream (the BW stages are those of the reverse

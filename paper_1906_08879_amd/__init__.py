@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     node_classes,
     policy_gradient,
     reinforce_coeff,
+    simulate_reward,
     simulate_runtime,
     weights_count,
 )

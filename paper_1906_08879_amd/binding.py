@@ -70,6 +70,8 @@ def load_library(path: Optional[str] = None):
         "pl_episode_gradient": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
                                                ctypes.c_int32, vp, vp, vp, vp]),
         "pl_simulate_runtime": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, ctypes.c_float, vp, vp, vp]),
+        "pl_simulate_reward": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_float,
+                                              ctypes.c_float, vp, vp, vp, vp, vp]),
         "pl_profile_enable": (ctypes.c_int, [vp, ctypes.c_int32]),
         "pl_profile_read": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_double), i64p,
                                            ctypes.c_int32]),
@@ -342,3 +344,19 @@ def episode_gradient(g: GraphBatch, w: Weights, node_feats, placement, cur_node,
         _dev_ptr(out_logp, torch.float32, g.B * n_steps, "out_logp"), _stream_ptr(stream)),
         "pl_episode_gradient")
     return grad
+
+
+def simulate_reward(g: GraphBatch, D: int, node_feats, placement, inv_bandwidth: float, mem_limit: float,
+                    mem_penalty: float, out_reward, out_runtime=None, out_peak_mem=None, out_events=None,
+                    stream=None):
+    """pl_simulate_reward on device tensors: memory-penalised run time R(p) of every graph's placement."""
+    import torch
+    lib = load_library()
+    _check(lib.pl_simulate_reward(
+        g._h, int(D), _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
+        _dev_ptr(placement, torch.int32, g.n_tot, "placement"), float(inv_bandwidth), float(mem_limit),
+        float(mem_penalty), _dev_ptr(out_reward, torch.float32, g.B, "out_reward"),
+        _dev_ptr(out_runtime, torch.float32, g.B, "out_runtime"),
+        _dev_ptr(out_peak_mem, torch.float32, g.B * D, "out_peak_mem"),
+        _dev_ptr(out_events, torch.int32, g.B, "out_events"), _stream_ptr(stream)), "pl_simulate_reward")
+    return out_reward

@@ -69,6 +69,11 @@ struct pl_graph_batch {
     pl::GraphView view{};
     pl::Workspace ws;
     pl::GradWorkspace gw;
+    // timeline of the simulator (pl_simulate_reward): op_start, op_end [n_tot]; arrival, alloc, free
+    // [n_tot, sim_D]; run times [B]
+    float *sim_start = nullptr, *sim_end = nullptr, *sim_arrival = nullptr, *sim_alloc = nullptr,
+          *sim_free = nullptr, *sim_rt = nullptr;
+    int sim_D = 0;
     pl::StageTimer timer;
 };
 
@@ -497,6 +502,7 @@ int pl_graph_batch_destroy(pl_graph_batch *g)
     }
     free_workspace(g->ws);
     free_grad_workspace(g->gw);
+    for (float *p : {g->sim_start, g->sim_end, g->sim_arrival, g->sim_alloc, g->sim_free, g->sim_rt}) (void)hipFree(p);
     for (auto &v : g->timer.ev)
         for (hipEvent_t e : v) (void)hipEventDestroy(e);
     delete g;
@@ -839,6 +845,50 @@ int pl_simulate_runtime(pl_graph_batch *g, int32_t D, const float *node_feats, c
     if (rc) return rc;
     rc = launch_simulate(g->view, D, static_cast<int>(n_max), static_cast<int>(e_max), node_feats, placement,
                          inv_bandwidth, out_runtime, out_events, static_cast<hipStream_t>(stream));
+    if (rc) return rc;
+    PL_HIP(hipGetLastError());
+    return PL_OK;
+}
+
+int pl_simulate_reward(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
+                       float inv_bandwidth, float mem_limit, float mem_penalty, float *out_reward,
+                       float *out_runtime, float *out_peak_mem, int32_t *out_events, void *stream)
+{
+    if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
+    if (D < 1 || D > kMaxD) return fail(PL_ERR_SHAPE, "D must be in [1, 16]");
+    if (!(inv_bandwidth >= 0.0f)) return fail(PL_ERR_SHAPE, "inv_bandwidth must not be negative");
+    if (!(mem_penalty >= 0.0f) || mem_limit != mem_limit)
+        return fail(PL_ERR_SHAPE, "mem_penalty must not be negative and mem_limit must be a number");
+    if (g->host.B == 0) return PL_OK;
+    if (!node_feats || !placement || !out_reward) return fail(PL_ERR_NULL, "a required device array is NULL");
+    int64_t n_max = 0, e_max = 0;
+    for (int32_t b = 0; b < g->host.B; ++b) {
+        n_max = std::max<int64_t>(n_max, g->host.node_off[b + 1] - g->host.node_off[b]);
+        e_max = std::max<int64_t>(e_max, g->host.edge_off[b + 1] - g->host.edge_off[b]);
+    }
+    if (n_max >= 0xFFFF || e_max >= 0xFFFF ||
+        simulator_lds_bytes(static_cast<int>(n_max), static_cast<int>(e_max)) > 160 * 1024)
+        return fail(PL_ERR_SHAPE, "a graph is too large for the simulator (its state must fit in 160 KB of LDS)");
+    int rc = ensure_on_device(g);
+    if (rc) return rc;
+    const size_t n = static_cast<size_t>(g->host.n_tot);
+    if (!g->sim_start || g->sim_D < D) {
+        for (float **p : {&g->sim_start, &g->sim_end, &g->sim_arrival, &g->sim_alloc, &g->sim_free, &g->sim_rt}) {
+            (void)hipFree(*p);
+            *p = nullptr;
+        }
+        PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_start), sizeof(float) * (n + 4)));
+        PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_end), sizeof(float) * (n + 4)));
+        PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_arrival), sizeof(float) * (n * D + 4)));
+        PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_alloc), sizeof(float) * (n * D + 4)));
+        PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_free), sizeof(float) * (n * D + 4)));
+        PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_rt), sizeof(float) * (g->host.B + 4)));
+        g->sim_D = D;
+    }
+    rc = launch_simulate_reward(g->view, D, static_cast<int>(n_max), static_cast<int>(e_max), node_feats, placement,
+                                inv_bandwidth, mem_limit, mem_penalty, g->sim_start, g->sim_end, g->sim_arrival,
+                                g->sim_alloc, g->sim_free, out_runtime ? out_runtime : g->sim_rt, out_peak_mem,
+                                out_reward, out_events, static_cast<hipStream_t>(stream));
     if (rc) return rc;
     PL_HIP(hipGetLastError());
     return PL_OK;

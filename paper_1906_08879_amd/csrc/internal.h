@@ -175,6 +175,12 @@ int launch_simulate(const GraphView &gv, int D, int n_max, int e_max, const floa
                     const int32_t *placement, float inv_bw, float *out_runtime, int32_t *out_events,
                     hipStream_t s);
 
+int launch_simulate_reward(const GraphView &gv, int D, int n_max, int e_max, const float *node_feats,
+                           const int32_t *placement, float inv_bw, float mem_limit, float penalty,
+                           float *op_start, float *op_end, float *arrival, float *alloc, float *free_t,
+                           float *runtime, float *out_peak, float *out_reward, int32_t *out_events,
+                           hipStream_t s);
+
 // ---- matrix-core pooling (kernels_pool_mfma.hip); writes ws.partial as [B, kPoolSlices, 3G, H]
 constexpr int kPoolSlices = 4;
 bool pool_mfma_supported(int H, int L, int weight_dtype);

@@ -71,11 +71,16 @@ __device__ __forceinline__ unsigned int row_pair_min(unsigned int v)
     return r0 < r1 ? r0 : r1;
 }
 
+// TL: the timeline is written out as well (for the peak-memory model): start and end of every
+// operation, and the time at which an output arrived on every device it was sent to.
+template <bool TL>
 __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max, int e_max,
                                                  const float *__restrict__ node_feats,
                                                  const int32_t *__restrict__ placement, float inv_bw,
                                                  float *__restrict__ out_runtime,
-                                                 int32_t *__restrict__ out_events)
+                                                 int32_t *__restrict__ out_events,
+                                                 float *__restrict__ op_start, float *__restrict__ op_end,
+                                                 float *__restrict__ arrival)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const SimLds S = carve(lds_raw, n_max, e_max);
@@ -155,6 +160,12 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
             ev_seq = seq + __popcll(m & ((1ull << lane) - 1ull));
             ev_node = o;
             ev_dst = dst;
+            if constexpr (TL) {
+                if (lane < D) {
+                    op_start[n0 + o] = now;
+                    op_end[n0 + o] = ev_time;
+                }
+            }
         }
         seq += __popcll(m);
     };
@@ -197,6 +208,9 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
         const int here = op_done ? slot : dst;
         const float dur = op_done ? __fmul_rn(S.size[o], inv_bw) : 0.0f;
         if (op_done) last = now;
+        if constexpr (TL) {
+            if (!op_done && lane == 0) arrival[static_cast<size_t>(n0 + o) * D + dst] = now;
+        }
         unsigned int sent = 0;
         for (int base = 0; base < cnt; base += 64) {
             const bool valid = base + lane < cnt;
@@ -231,6 +245,117 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
     }
 }
 
+// ---- peak memory of every device from the timeline (appendix "Simulator": the start and end
+// timestamps of the operations and the tensor sizes predict the peak memory).  The model: the
+// output of v occupies v's device from v's start until the latest of v's end, the end of its last
+// consumer there and the arrival of its last outgoing transfer; on another device that consumes
+// it, a copy lives from the transfer's arrival until the end of its last consumer there.
+// Intervals are half-open [alloc, free).
+
+__global__ __launch_bounds__(256) void k_fill_value(float *__restrict__ p, size_t n, float value)
+{
+    const size_t idx = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (idx < n) p[idx] = value;
+}
+
+// One thread per node: alloc[v][d], free[v][d] for every device (-1: no copy there).
+__global__ __launch_bounds__(256) void k_lifetimes(GraphView gv, int D, const int32_t *__restrict__ placement,
+                                                   const float *__restrict__ op_start,
+                                                   const float *__restrict__ op_end,
+                                                   const float *__restrict__ arrival,
+                                                   float *__restrict__ alloc, float *__restrict__ free_t)
+{
+    const int v = blockIdx.x * 256 + threadIdx.x;
+    if (v >= gv.n_tot) return;
+    float *fr = free_t + static_cast<size_t>(v) * D, *al = alloc + static_cast<size_t>(v) * D;
+    const int d = placement[v];
+    for (int o = 0; o < D; ++o) fr[o] = -1.0f;
+    if (d < 0 || d >= D) {                 // the simulator reports the graph as invalid
+        for (int o = 0; o < D; ++o) al[o] = -1.0f;
+        return;
+    }
+    // end of the last consumer on every device, kept in this node's own row
+    for (int p = gv.nbr_ptr[1][v]; p < gv.nbr_ptr[1][v + 1]; ++p) {
+        const int c = gv.nbr_idx[1][p];
+        const int pc = placement[c];
+        if (pc >= 0 && pc < D) fr[pc] = fmaxf(fr[pc], op_end[c]);
+    }
+    float own_free = fmaxf(op_end[v], fr[d]);
+    for (int o = 0; o < D; ++o) {
+        if (o == d) continue;
+        const float arr = arrival[static_cast<size_t>(v) * D + o];
+        if (arr >= 0.0f) {
+            own_free = fmaxf(own_free, arr);   // the source stays until it has been sent
+            al[o] = arr;
+            fr[o] = fmaxf(arr, fr[o]);
+        } else {
+            al[o] = -1.0f;
+            fr[o] = -1.0f;
+        }
+    }
+    al[d] = op_start[v];
+    fr[d] = own_free;
+}
+
+// One workgroup per graph: for every device the largest sum of live sizes at any allocation time
+// (the sum only grows at an allocation), summed in float64 in ascending node order; then the
+// memory-penalised run time R(p) = r if m <= M else r + c (m - M) (appendix, "Reward").
+__global__ __launch_bounds__(256) void k_peak_memory(GraphView gv, int D, int n_max,
+                                                     const float *__restrict__ node_feats,
+                                                     const float *__restrict__ alloc,
+                                                     const float *__restrict__ free_t,
+                                                     const float *__restrict__ runtime, float mem_limit,
+                                                     float penalty, float *__restrict__ out_peak,
+                                                     float *__restrict__ out_reward)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    float *a_d = reinterpret_cast<float *>(lds_raw), *f_d = a_d + n_max, *sz = f_d + n_max;
+    __shared__ double red[256];
+    __shared__ double peak_all;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int n0 = gv.node_off[b], n = gv.node_off[b + 1] - n0;
+    const float r = runtime[b];
+    if (!(r == r)) {                       // invalid placement: the simulator wrote NaN
+        if (tid == 0 && out_reward) out_reward[b] = r;
+        if (out_peak) for (int d = tid; d < D; d += 256) out_peak[static_cast<size_t>(b) * D + d] = r;
+        return;
+    }
+    for (int u = tid; u < n; u += 256) sz[u] = node_feats[static_cast<size_t>(n0 + u) * 3 + 1];
+    if (tid == 0) peak_all = 0.0;
+    for (int d = 0; d < D; ++d) {
+        __syncthreads();
+        for (int u = tid; u < n; u += 256) {
+            a_d[u] = alloc[static_cast<size_t>(n0 + u) * D + d];
+            f_d[u] = free_t[static_cast<size_t>(n0 + u) * D + d];
+        }
+        __syncthreads();
+        double mx = 0.0;
+        for (int v = tid; v < n; v += 256) {
+            const float t = a_d[v];
+            if (t < 0.0f) continue;
+            double live = 0.0;
+            for (int u = 0; u < n; ++u)
+                if (a_d[u] <= t && t < f_d[u]) live += static_cast<double>(sz[u]);
+            mx = live > mx ? live : mx;
+        }
+        red[tid] = mx;
+        __syncthreads();
+        for (int step = 128; step > 0; step >>= 1) {
+            if (tid < step) red[tid] = red[tid + step] > red[tid] ? red[tid + step] : red[tid];
+            __syncthreads();
+        }
+        if (tid == 0) {
+            if (out_peak) out_peak[static_cast<size_t>(b) * D + d] = static_cast<float>(red[0]);
+            peak_all = red[0] > peak_all ? red[0] : peak_all;
+        }
+    }
+    __syncthreads();
+    if (tid == 0 && out_reward) {
+        const double m = peak_all, M = static_cast<double>(mem_limit);
+        out_reward[b] = m <= M ? r : static_cast<float>(static_cast<double>(r) + static_cast<double>(penalty) * (m - M));
+    }
+}
+
 }  // namespace
 
 size_t simulator_lds_bytes(int n_max, int e_max)
@@ -247,10 +372,38 @@ int launch_simulate(const GraphView &gv, int D, int n_max, int e_max, const floa
     if (gv.B == 0) return PL_OK;
     const size_t lds = simulator_lds_bytes(n_max, e_max);
     if (lds > 64 * 1024)
-        PL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_simulate),
+        PL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_simulate<false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
-    hipLaunchKernelGGL(k_simulate, dim3(gv.B), dim3(64), lds, s, gv, D, n_max, e_max, node_feats, placement, inv_bw,
-                       out_runtime, out_events);
+    hipLaunchKernelGGL(k_simulate<false>, dim3(gv.B), dim3(64), lds, s, gv, D, n_max, e_max, node_feats, placement,
+                       inv_bw, out_runtime, out_events, nullptr, nullptr, nullptr);
+    return PL_OK;
+}
+
+// Simulation with the timeline, then lifetimes, peaks and R(p).  scratch: op_start, op_end
+// [n_tot]; arrival, alloc, free_t [n_tot, D].
+int launch_simulate_reward(const GraphView &gv, int D, int n_max, int e_max, const float *node_feats,
+                           const int32_t *placement, float inv_bw, float mem_limit, float penalty,
+                           float *op_start, float *op_end, float *arrival, float *alloc, float *free_t,
+                           float *runtime, float *out_peak, float *out_reward, int32_t *out_events,
+                           hipStream_t s)
+{
+    if (gv.B == 0) return PL_OK;
+    const size_t lds = simulator_lds_bytes(n_max, e_max);
+    if (lds > 64 * 1024)
+        PL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_simulate<true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+    const size_t nd = static_cast<size_t>(gv.n_tot) * D;
+    hipLaunchKernelGGL(k_fill_value, dim3(static_cast<unsigned>((nd + 255) / 256)), dim3(256), 0, s, arrival, nd, -1.0f);
+    hipLaunchKernelGGL(k_simulate<true>, dim3(gv.B), dim3(64), lds, s, gv, D, n_max, e_max, node_feats, placement,
+                       inv_bw, runtime, out_events, op_start, op_end, arrival);
+    hipLaunchKernelGGL(k_lifetimes, dim3((gv.n_tot + 255) / 256), dim3(256), 0, s, gv, D, placement, op_start, op_end,
+                       arrival, alloc, free_t);
+    const size_t lds2 = sizeof(float) * 3 * static_cast<size_t>(n_max);
+    if (lds2 > 48 * 1024)
+        PL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_peak_memory),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds2)));
+    hipLaunchKernelGGL(k_peak_memory, dim3(gv.B), dim3(256), lds2, s, gv, D, n_max, node_feats, alloc, free_t, runtime,
+                       mem_limit, penalty, out_peak, out_reward);
     return PL_OK;
 }
 

@@ -91,3 +91,96 @@ def test_full_batch_sampled():
     for b in (0, 100, w.B - 1):
         r, e = oracle_graph(w, b, w.placement, np.float32(5e-5))
         assert (got_r[b], got_e[b]) == (r, e)
+
+
+# ---------------------------------------------------------------- peak memory and R(p)
+def run_device_reward(w, placement, inv_bw, M, c, handles=None):
+    import torch
+    import paper_1906_08879_amd as pl
+    dev = torch.device("cuda:0")
+    g = handles or pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+    rew = torch.full((w.B,), -1.0, dtype=torch.float32, device=dev)
+    rt = torch.full((w.B,), -1.0, dtype=torch.float32, device=dev)
+    peak = torch.full((w.B, w.D), -1.0, dtype=torch.float32, device=dev)
+    ev = torch.full((w.B,), -7, dtype=torch.int32, device=dev)
+    pl.simulate_reward(g, w.D, torch.from_numpy(np.ascontiguousarray(w.node_feats, dtype=np.float32)).to(dev),
+                       torch.from_numpy(np.ascontiguousarray(placement, dtype=np.int32)).to(dev), inv_bw, M, c,
+                       rew, rt, peak, ev)
+    torch.cuda.synchronize()
+    if handles is None:
+        g.close()
+    return rew.cpu().numpy(), rt.cpu().numpy(), peak.cpu().numpy(), ev.cpu().numpy()
+
+
+def oracle_reward(w, b, placement, inv_bw, M, c):
+    n0, n1 = int(w.node_off[b]), int(w.node_off[b + 1])
+    e0, e1 = int(w.edge_off[b]), int(w.edge_off[b + 1])
+    n, src, dst = n1 - n0, w.edge_src[e0:e1], w.edge_dst[e0:e1]
+    size = w.node_feats[n0:n1, 1]
+    r, st, en, arr = sim.timeline(n, src, dst, w.node_feats[n0:n1, 0], size, placement[n0:n1], w.D, np.float32(inv_bw))
+    peak = sim.peak_memory(n, src, dst, size, placement[n0:n1], w.D, st, en, arr)
+    return r, peak, sim.penalised_runtime(r, peak.max(), M, c)
+
+
+@pytest.mark.parametrize("name,B,inv_bw", [("random32", 1, 1e-4), ("layered200", 8, 1e-4), ("inception", 3, 3e-5),
+                                           ("nmt", 2, 1e-4), ("nasnet", 2, 5e-5)])
+def test_peak_memory_and_penalised_run_time(name, B, inv_bw):
+    """Run time bit for bit; peaks (float64 sums rounded once to fp32) and R(p) to 1e-6 relative.  The
+    limit M is set between the smallest and the largest peak of the batch, so both branches of R(p)
+    occur."""
+    w = make_workload(name, B=B)
+    rng = np.random.default_rng(23)
+    for trial in range(2):
+        placement = w.placement if trial == 0 else rng.integers(0, w.D, w.n_tot).astype(np.int32)
+        refs = [oracle_reward(w, b, placement, inv_bw, 0.0, 0.0) for b in range(w.B)]
+        peaks = np.array([p.max() for _, p, _ in refs])
+        M = float(np.float32(0.5 * (peaks.min() + peaks.max())))
+        c = 2.0 * float(max(r for r, _, _ in refs)) / float(peaks.max())    # a penalty of the run time's size
+        rew, rt, peak, ev = run_device_reward(w, placement, inv_bw, M, c)
+        above = 0
+        for b in range(w.B):
+            r, p, _ = refs[b]
+            assert rt[b] == r, (name, b)
+            np.testing.assert_allclose(peak[b], p, rtol=1e-6, atol=0, err_msg=f"{name} graph {b}")
+            want = sim.penalised_runtime(r, p.max(), M, np.float32(c))
+            assert abs(rew[b] - want) <= 2e-6 * abs(want), (name, b, rew[b], want)
+            above += p.max() > M
+        if w.B > 1:
+            assert 0 < above < w.B or peaks.min() == peaks.max()
+
+
+def test_reward_edge_cases():
+    """One device (nothing ever crosses), an edgeless graph, a bad device id, and the plain run time
+    when the limit is never reached."""
+    rng = np.random.default_rng(4)
+    n = 30
+    src, dst = tiny_random_dag(rng, n, 0.2)
+    feats = np.stack([rng.integers(1, 6, n), rng.integers(1, 50, n), np.zeros(n)], axis=1).astype(np.float32)
+    for D, edges in ((1, (src, dst)), (3, (np.zeros(0, np.int32), np.zeros(0, np.int32))), (4, (src, dst))):
+        placement = rng.integers(0, D, n).astype(np.int32)
+        w = Workload(name="t", B=1, D=D, H=8, n_layers=1, k_sweeps=1, group_by_device=1, weight_dtype="fp32",
+                     n_nodes=np.array([n], np.int32), n_edges=np.array([len(edges[0])], np.int32),
+                     edge_src=edges[0], edge_dst=edges[1], node_feats=feats, placement=placement,
+                     cur_node=np.zeros(1, np.int32), weights=np.zeros(1, np.float32))
+        r, p, _ = oracle_reward(w, 0, placement, 0.25, 0.0, 0.0)
+        rew, rt, peak, ev = run_device_reward(w, placement, 0.25, 1e9, 2.0)
+        assert rt[0] == r and rew[0] == r                      # below the limit: R(p) = r
+        np.testing.assert_allclose(peak[0], p, rtol=1e-6)
+        rew, _, _, _ = run_device_reward(w, placement, 0.25, 0.0, 2.0)
+        assert abs(rew[0] - (float(r) + 2.0 * p.max())) <= 2e-6 * (float(r) + 2.0 * p.max())
+    bad = placement.copy()
+    bad[3] = 9
+    rew, rt, peak, ev = run_device_reward(w, bad, 0.25, 1.0, 2.0)
+    assert np.isnan(rew[0]) and np.isnan(rt[0]) and np.isnan(peak[0]).all() and ev[0] == -1
+
+
+def test_full_batch_reward_sampled_graphs():
+    w = make_workload("nasnet")
+    rng = np.random.default_rng(31)
+    placement = rng.integers(0, w.D, w.n_tot).astype(np.int32)
+    rew, rt, peak, ev = run_device_reward(w, placement, 5e-5, 0.0, 1e-6)
+    for b in (0, 77, 255):
+        r, p, want = oracle_reward(w, b, placement, 5e-5, 0.0, np.float32(1e-6))
+        assert rt[b] == r
+        np.testing.assert_allclose(peak[b], p, rtol=1e-6)
+        assert abs(rew[b] - want) <= 2e-6 * abs(want)

@@ -176,3 +176,20 @@ def test_reinforce_entry_points_reject_bad_arguments(lib):
     args = [g._h, null, null, null, null, null, null, null, i32(0), i32(1), i32(0), null, null, null, null]
     assert raw.pl_episode_gradient(*args) == -1                                                 # weights handle is NULL
     g.close()
+
+
+def test_simulate_reward_rejects_bad_arguments(lib):
+    import ctypes
+    raw = ctypes.CDLL(pl.library_path())
+    null = ctypes.c_void_p(None)
+    f = ctypes.c_float
+    raw.pl_simulate_reward.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, f, f, f,
+                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_void_p]
+    assert raw.pl_simulate_reward(null, 4, null, null, f(1.0), f(1.0), f(2.0), null, null, null, null, null) == -1
+    g = pl.GraphBatch([2], [1], [0], [1])
+    assert raw.pl_simulate_reward(g._h, 99, null, null, f(1.0), f(1.0), f(2.0), null, null, null, null, null) == -2
+    assert raw.pl_simulate_reward(g._h, 4, null, null, f(-1.0), f(1.0), f(2.0), null, null, null, null, null) == -2
+    assert raw.pl_simulate_reward(g._h, 4, null, null, f(1.0), f(1.0), f(-2.0), null, null, null, null, null) == -2
+    assert raw.pl_simulate_reward(g._h, 4, null, null, f(1.0), f(1.0), f(2.0), null, null, null, null, null) == -1
+    g.close()
