@@ -300,6 +300,9 @@ __global__ __launch_bounds__(256) void k_lifetimes(GraphView gv, int D, const in
 // One workgroup per graph: for every device the largest sum of live sizes at any allocation time
 // (the sum only grows at an allocation), summed in float64 in ascending node order; then the
 // memory-penalised run time R(p) = r if m <= M else r + c (m - M) (appendix, "Reward").
+// Per device, the copies that live there are first packed into LDS (alloc, free, size; node order
+// kept), padded to a multiple of four with entries that are never live; every packed entry is a
+// candidate time, and its live sum runs over the packed entries four at a time.
 __global__ __launch_bounds__(256) void k_peak_memory(GraphView gv, int D, int n_max,
                                                      const float *__restrict__ node_feats,
                                                      const float *__restrict__ alloc,
@@ -308,11 +311,15 @@ __global__ __launch_bounds__(256) void k_peak_memory(GraphView gv, int D, int n_
                                                      float penalty, float *__restrict__ out_peak,
                                                      float *__restrict__ out_reward)
 {
+    typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    float *a_d = reinterpret_cast<float *>(lds_raw), *f_d = a_d + n_max, *sz = f_d + n_max;
+    const int cap = (n_max + 3) / 4 * 4 + 4;
+    float *ca = reinterpret_cast<float *>(lds_raw), *cf = ca + cap, *cs = cf + cap;
     __shared__ double red[256];
     __shared__ double peak_all;
-    const int b = blockIdx.x, tid = threadIdx.x;
+    __shared__ int wave_cnt[4];
+    __shared__ int packed;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n0 = gv.node_off[b], n = gv.node_off[b + 1] - n0;
     const float r = runtime[b];
     if (!(r == r)) {                       // invalid placement: the simulator wrote NaN
@@ -320,22 +327,52 @@ __global__ __launch_bounds__(256) void k_peak_memory(GraphView gv, int D, int n_
         if (out_peak) for (int d = tid; d < D; d += 256) out_peak[static_cast<size_t>(b) * D + d] = r;
         return;
     }
-    for (int u = tid; u < n; u += 256) sz[u] = node_feats[static_cast<size_t>(n0 + u) * 3 + 1];
     if (tid == 0) peak_all = 0.0;
     for (int d = 0; d < D; ++d) {
         __syncthreads();
-        for (int u = tid; u < n; u += 256) {
-            a_d[u] = alloc[static_cast<size_t>(n0 + u) * D + d];
-            f_d[u] = free_t[static_cast<size_t>(n0 + u) * D + d];
+        if (tid == 0) packed = 0;
+        __syncthreads();
+        for (int base = 0; base < n; base += 256) {
+            const int u = base + tid;
+            float a = -1.0f, f = -1.0f;
+            if (u < n) {
+                a = alloc[static_cast<size_t>(n0 + u) * D + d];
+                f = free_t[static_cast<size_t>(n0 + u) * D + d];
+            }
+            const bool have = a >= 0.0f;
+            const unsigned long long m = __ballot(have);
+            if (lane == 0) wave_cnt[wave] = __popcll(m);
+            __syncthreads();
+            int pos = packed + __popcll(m & ((1ull << lane) - 1ull));
+            for (int w = 0; w < wave; ++w) pos += wave_cnt[w];
+            if (have) {
+                ca[pos] = a;
+                cf[pos] = f;
+                cs[pos] = node_feats[static_cast<size_t>(n0 + u) * 3 + 1];
+            }
+            __syncthreads();
+            if (tid == 0) packed += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+            __syncthreads();
+        }
+        const int k = packed, k4 = (k + 3) / 4 * 4;
+        for (int i = k + tid; i < k4; i += 256) {      // padding: allocated after every time, never live
+            ca[i] = __builtin_inff();
+            cf[i] = -1.0f;
+            cs[i] = 0.0f;
         }
         __syncthreads();
         double mx = 0.0;
-        for (int v = tid; v < n; v += 256) {
-            const float t = a_d[v];
-            if (t < 0.0f) continue;
+        for (int i = tid; i < k; i += 256) {
+            const float t = ca[i];
             double live = 0.0;
-            for (int u = 0; u < n; ++u)
-                if (a_d[u] <= t && t < f_d[u]) live += static_cast<double>(sz[u]);
+            for (int j = 0; j < k4; j += 4) {
+                const f32x4 a4 = *reinterpret_cast<const f32x4 *>(ca + j);
+                const f32x4 f4 = *reinterpret_cast<const f32x4 *>(cf + j);
+                const f32x4 s4 = *reinterpret_cast<const f32x4 *>(cs + j);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    live += (a4[q] <= t && t < f4[q]) ? static_cast<double>(s4[q]) : 0.0;
+            }
             mx = live > mx ? live : mx;
         }
         red[tid] = mx;
@@ -398,7 +435,7 @@ int launch_simulate_reward(const GraphView &gv, int D, int n_max, int e_max, con
                        inv_bw, runtime, out_events, op_start, op_end, arrival);
     hipLaunchKernelGGL(k_lifetimes, dim3((gv.n_tot + 255) / 256), dim3(256), 0, s, gv, D, placement, op_start, op_end,
                        arrival, alloc, free_t);
-    const size_t lds2 = sizeof(float) * 3 * static_cast<size_t>(n_max);
+    const size_t lds2 = sizeof(float) * 3 * (static_cast<size_t>(n_max + 3) / 4 * 4 + 4);
     if (lds2 > 48 * 1024)
         PL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_peak_memory),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds2)));
