@@ -191,7 +191,7 @@ int pl_episode_run(pl_graph_batch *g, const pl_weights *w, float *node_feats, in
  *   out_logp    dev [B] fp32    log pi(a_b | s_b); NULL to skip
  * A graph whose cur_node or action is out of range adds nothing and gets out_logp = NaN.
  * ReLU's derivative at 0 is taken as 0.  Covers k_sweeps <= 1 (PL_ERR_SHAPE otherwise).  The
- * first call on a batch allocates the buffers of the reverse pass (about (10 n_layers + 7)
+ * first call on a batch allocates the buffers of the reverse pass (about (14 n_layers + 10)
  * x N_tot x H floats); later calls only launch kernels.  Asynchronous on `stream`; summation
  * orders are fixed, so equal inputs give bit-equal gradients. */
 int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
