@@ -38,7 +38,7 @@ def path_algorithmic_bytes(n_tot: int, e_tot: int, H: int) -> int:
     return sweep_algorithmic_bytes(n_tot, e_tot, H) + n_tot * (16 * H + 12 + 4 + 2)
 
 
-SWEEP_SOURCES = ("kernels_mfma.hip", "plan.cpp", "internal.h")
+SWEEP_SOURCES = ("kernels_mfma.hip", "plan.cpp", "sweep_plan.h")
 
 
 def csrc_digest() -> str:

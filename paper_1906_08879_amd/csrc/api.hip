@@ -816,7 +816,7 @@ int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t
     if (!accumulate) launch_fill_zero(grad, plan_weights(w->cfg, nullptr), s);
     ForwardArgs fa{node_feats, placement, cur_node, out_logits, nullptr, g->gw.pooled};
     const StageMarks marks{&g->timer, stage_mark};
-    launch_backward_generic(g->view, mv, w->d_blob_t, g->ws, g->gw, fa, actions, coeff, w->cfg.k_sweeps,
+    launch_backward(g->view, mv, w->d_blob_t, g->ws, g->gw, fa, actions, coeff, w->cfg.k_sweeps,
                             g->ws.n_chunks, w->path,
                             chain_cores ? reinterpret_cast<const uint4 *>(w->d_wfrag_bw) : nullptr,
                             w->d_sweep_bias, w->sweep_ws, keep, pool_kept, grad, out_logp, &marks, s);

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "placeto.h"
+#include "sweep_plan.h"
 
 namespace pl {
 
@@ -50,37 +51,6 @@ struct HostLayout {
 
 int build_layout(int32_t B, const int32_t *n_nodes, const int32_t *n_edges,
                  const int32_t *edge_src, const int32_t *edge_dst, HostLayout *out);
-
-// ---- gather plan of the matrix-core sweep kernel (plan.cpp)
-constexpr int kChunkRows = 8;    // nodes per chunk: two MFMA row tiles of four nodes
-constexpr int kFarCap = 16;      // far sources staged per chunk
-constexpr int kRing = 2;         // chunks whose messages stay in the LDS table
-constexpr int kMaxEnt = 20;      // neighbours per row held in the chunk record (6 bits each, 5 per word)
-constexpr int kMsgSlots = kRing * kChunkRows + 2 * kFarCap;
-
-struct SweepPlanHost {
-    std::vector<int32_t> ck_off;   // [B+1] chunk range of each graph
-    std::vector<int32_t> meta;     // [n_chunks][4]: global bucket position, rows, n_far,
-                                   // most table entries of a row | (some row uses the overflow list) << 8
-    std::vector<uint32_t> ent;     // [n_chunks][kChunkRows][4]: twenty 6-bit table slots, entry k in bits
-                                   // 6 (k % 5) .. of word k / 5; unused entries = kMsgSlots, the table's
-                                   // zero row.  Bit 30 of word 0 set: the row uses the overflow list
-                                   // (word 1 = its offset in ovf, word 2 = its length)
-    std::vector<int32_t> far;      // [n_chunks][kFarCap] global node ids staged for the chunk
-    std::vector<int32_t> ovf;      // neighbour lists of rows that do not fit their record:
-                                   // >= 0 global node id (>= 3 chunks back), < 0: -1 - table slot
-    int64_t n_chunks = 0;
-};
-
-int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out);
-
-struct SweepPlanView {
-    const int32_t *ck_off;
-    const int4 *meta;
-    const uint4 *ent;
-    const int32_t *far;
-    const int32_t *ovf;
-};
 
 // ---- device-side view of a batch, passed to kernels by value
 struct GraphView {
@@ -227,7 +197,7 @@ struct StageMarks {
 
 size_t wgrad_partial_floats(int64_t R, int I, int J);
 void launch_fill_zero(float *p, size_t n, hipStream_t s);
-void launch_backward_generic(const GraphView &gv, const ModelView &mv, const float *blob_t,
+void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob_t,
                              const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
                              const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
                              int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,

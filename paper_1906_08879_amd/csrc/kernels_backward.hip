@@ -1223,7 +1223,7 @@ void launch_dense(const DenseCall &c, int H, hipStream_t s)
 
 }  // namespace
 
-void launch_backward_generic(const GraphView &gv, const ModelView &mv, const float *blob_t,
+void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob_t,
                              const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
                              const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
                              int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
