@@ -11,6 +11,9 @@ returns
     grad = sum_b  coeff[b] * d/d theta  log softmax(logits_theta(s_b))[a_b]
 
 with theta the flat weight blob of the policy network.  The scalars coeff[b] are inputs.
+Appendix A.7 ("Entropy") adds an entropy term to the loss to encourage exploration; with a
+second scalar per state, beta[b], the sum also holds beta[b] * d/d theta H(pi_theta(. | s_b)),
+H(pi) = - sum_d pi_d log pi_d.
 
 How: the forward pass of Section 2.2 / Appendix A.7 is written out once more here, node by
 node in a topological order, with plain PyTorch CPU operations in float64 (the same readings
@@ -163,11 +166,19 @@ def logits_graph(theta, n, src, dst, feats, placement, cur, D, H, n_layers=2, k_
     return torch.relu(z @ W1 + b1) @ W2 + b2
 
 
+def entropy(logits) -> "torch.Tensor":
+    """H(softmax(logits)) = - sum_d pi_d log pi_d."""
+    lp = torch.log_softmax(logits, dim=0)
+    return -(torch.exp(lp) * lp).sum()
+
+
 def policy_gradient(n_nodes, n_edges, src, dst, feats, placement, cur, weights, actions, coeff,
-                    D, H, n_layers=2, k_sweeps=1, group_by_device=1, only=None):
-    """grad [n_params] float64 = sum_b coeff[b] * d log pi(a_b | s_b) / d theta, and
-    logp [B] = log pi(a_b | s_b).  `only` restricts the work to the listed graphs (the others
-    count as coeff 0 and get logp = nan)."""
+                    D, H, n_layers=2, k_sweeps=1, group_by_device=1, only=None, entropy_coeff=None,
+                    want_entropy=False):
+    """grad [n_params] float64 = sum_b coeff[b] * d log pi(a_b | s_b) / d theta
+    (+ entropy_coeff[b] * d H(pi(. | s_b)) / d theta when given), and logp [B] = log pi(a_b | s_b).
+    `only` restricts the work to the listed graphs (the others count as zero and get logp = nan).
+    With want_entropy the entropies [B] are returned as a third value."""
     n_nodes = np.asarray(n_nodes, dtype=np.int64)
     n_edges = np.asarray(n_edges, dtype=np.int64)
     B = len(n_nodes)
@@ -177,6 +188,7 @@ def policy_gradient(n_nodes, n_edges, src, dst, feats, placement, cur, weights, 
     theta = torch.tensor(np.asarray(weights, dtype=np.float64), requires_grad=True)
     grad = np.zeros(theta.numel())
     logp = np.full(B, np.nan)
+    ent = np.full(B, np.nan)
     todo = range(B) if only is None else only
     for b in todo:
         lo, hi, elo, ehi = noff[b], noff[b + 1], eoff[b], eoff[b + 1]
@@ -185,16 +197,23 @@ def policy_gradient(n_nodes, n_edges, src, dst, feats, placement, cur, weights, 
                               group_by_device)
         lp = torch.log_softmax(logits, dim=0)[int(actions[b])]
         logp[b] = float(lp.detach())
-        if coeff[b] != 0.0:
+        h = entropy(logits)
+        ent[b] = float(h.detach())
+        beta = 0.0 if entropy_coeff is None else float(entropy_coeff[b])
+        if coeff[b] != 0.0 and beta == 0.0:
             (g,) = torch.autograd.grad(lp, theta)
             grad += float(coeff[b]) * g.numpy()
-    return grad, logp
+        elif coeff[b] != 0.0 or beta != 0.0:
+            (g,) = torch.autograd.grad(float(coeff[b]) * lp + beta * h, theta)
+            grad += g.numpy()
+    return (grad, logp, ent) if want_entropy else (grad, logp)
 
 
-def gradient_workload(w, actions, coeff, only=None):
+def gradient_workload(w, actions, coeff, only=None, entropy_coeff=None, want_entropy=False):
     """policy_gradient on a workloads.Workload, with the weights at the precision it stores."""
     from . import weights_as_stored
     blob = weights_as_stored(w.weights, w.D, w.H, w.n_layers, w.group_by_device, w.weight_dtype)
     return policy_gradient(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst, w.node_feats, w.placement,
                            w.cur_node, blob, actions, coeff, w.D, w.H, w.n_layers, w.k_sweeps,
-                           w.group_by_device, only=only)
+                           w.group_by_device, only=only, entropy_coeff=entropy_coeff,
+                           want_entropy=want_entropy)

@@ -118,3 +118,52 @@ def test_parameters_that_cannot_matter_get_zero_gradient():
             assert not g.any(), name
     assert np.abs(grad[slices["pol.0"][0]]).max() > 0
     assert np.abs(grad[slices["proj"][0]]).max() > 0
+
+
+def _c_entropy(c, theta):
+    p = _c_logp(c, theta, 0)[1]["probs"]
+    return float(-(p * np.log(p)).sum())
+
+
+def test_entropy_gradient_equals_central_differences_of_the_c_oracle():
+    """Appendix A.7 "Entropy": d H / d theta with H = - sum pi log pi computed from the C oracle's
+    probabilities, for sampled parameters of every layer; and the value of H itself."""
+    c = _case(21, n=10)
+    grad, logp, ent = og.policy_gradient([c["n"]], [len(c["src"])], c["src"], c["dst"], c["feats"], c["placement"],
+                                         [c["cur"]], c["theta"], [1], [0.0], D, H, entropy_coeff=[1.0],
+                                         want_entropy=True)
+    assert abs(ent[0] - _c_entropy(c, c["theta"])) < 1e-12
+    assert 0.0 < ent[0] <= np.log(D) + 1e-12
+    slices, _ = og.layer_slices(D, H, 2, 1)
+    rng = np.random.default_rng(1)
+    h = 1e-6
+    for name, (ws, bs) in slices.items():
+        for i in list(rng.choice(np.arange(ws.start, ws.stop), size=2, replace=False)) + [int(rng.integers(bs.start, bs.stop))]:
+            tp, tm = c["theta"].copy(), c["theta"].copy()
+            tp[i] += h
+            tm[i] -= h
+            fd = (_c_entropy(c, tp) - _c_entropy(c, tm)) / (2 * h)
+            assert abs(fd - grad[i]) <= 1e-6 * max(1.0, abs(grad[i])) + 2e-8, (name, i, fd, grad[i])
+    assert np.abs(grad).max() > 1e-4
+
+
+def test_entropy_gradient_closed_form_and_mixture():
+    """d H / d logits = - pi (log pi + H), through the output bias; and the two terms add."""
+    c = _case(22)
+    _, ref = _c_logp(c, c["theta"], 0)
+    p = ref["probs"]
+    Hh = -(p * np.log(p)).sum()
+    slices, _ = og.layer_slices(D, H, 2, 1)
+    args = ([c["n"]], [len(c["src"])], c["src"], c["dst"], c["feats"], c["placement"], [c["cur"]], c["theta"])
+    g_ent, _ = og.policy_gradient(*args, [2], [0.0], D, H, entropy_coeff=[0.7])
+    np.testing.assert_allclose(g_ent[slices["pol.1"][1]], 0.7 * (-p * (np.log(p) + Hh)), rtol=1e-10, atol=1e-14)
+    assert abs(g_ent[slices["pol.1"][1]].sum()) < 1e-13
+    g_lp, _ = og.policy_gradient(*args, [2], [-1.5], D, H)
+    g_mix, _ = og.policy_gradient(*args, [2], [-1.5], D, H, entropy_coeff=[0.7])
+    np.testing.assert_allclose(g_mix, g_lp + g_ent, rtol=1e-10, atol=1e-13)
+    # equal logits: the entropy is at its maximum log D and its gradient vanishes
+    import torch
+    l = torch.zeros(D, dtype=torch.float64, requires_grad=True)
+    h = og.entropy(l)
+    (gl,) = torch.autograd.grad(h, l)
+    assert abs(float(h) - np.log(D)) < 1e-14 and float(gl.abs().max()) < 1e-15
