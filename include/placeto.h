@@ -199,6 +199,18 @@ int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t
                        const float *coeff, int32_t accumulate, float *grad, float *out_logits,
                        float *out_logp, void *stream);
 
+/* Same, with the entropy term that Appendix A.7 ("Entropy") adds to the loss to encourage
+ * exploration: grad (+)= sum_b [ coeff[b] * d log pi(a_b | s_b) + entropy_coeff[b] * d H(pi(. | s_b)) ]
+ * / d theta, H(pi) = - sum_d pi_d log pi_d (its derivative with respect to logit d is
+ * - pi_d (log pi_d + H)).
+ *   entropy_coeff  dev [B] fp32  the entropy factor of every state, or NULL for none
+ *   out_entropy    dev [B] fp32  H(pi(. | s_b)), NaN for a graph whose cur_node is out of range; NULL to skip
+ * A graph whose cur_node or action is out of range adds nothing for either term. */
+int pl_policy_gradient_ex(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                          const int32_t *cur_node, const pl_weights *w, const int32_t *actions,
+                          const float *coeff, const float *entropy_coeff, int32_t accumulate, float *grad,
+                          float *out_logits, float *out_logp, float *out_entropy, void *stream);
+
 /* The weights of that sum for T steps of B rollouts (Eq. 1: the return after each decision minus
  * a baseline; the baseline of step i is the average of that return over the independent
  * rollouts of the same graph):
@@ -224,6 +236,7 @@ int pl_reinforce_coeff(int32_t T, int32_t B, const float *rewards, const int32_t
  *   order         dev [N_tot]         the visiting order used by the rollout
  *   actions       dev [n_steps, B]    e.g. out_actions of pl_episode_run
  *   coeff         dev [n_steps, B]    e.g. out_coeff of pl_reinforce_coeff
+ *   entropy_coeff dev [n_steps, B]    entropy factors as in pl_policy_gradient_ex, or NULL
  *   accumulate                        0: grad is overwritten by the sum; else added to
  *   grad          dev [pl_weights_count];  logits  dev [B, D] scratch (last step's logits)
  *   out_logp      dev [n_steps, B] or NULL: log pi(a | s) of every replayed decision (NaN once a
@@ -231,8 +244,8 @@ int pl_reinforce_coeff(int32_t T, int32_t B, const float *rewards, const int32_t
  * Same limits as pl_policy_gradient. */
 int pl_episode_gradient(pl_graph_batch *g, const pl_weights *w, float *node_feats, int32_t *placement,
                         int32_t *cur_node, const int32_t *order, const int32_t *actions, const float *coeff,
-                        int32_t t0, int32_t n_steps, int32_t accumulate, float *grad, float *logits,
-                        float *out_logp, void *stream);
+                        const float *entropy_coeff, int32_t t0, int32_t n_steps, int32_t accumulate, float *grad,
+                        float *logits, float *out_logp, void *stream);
 
 /* ---- run time of a placement from the event-driven simulator of the paper's appendix
  * ("Simulator"), for every graph of the batch: per device a FIFO queue of runnable operations

@@ -50,11 +50,13 @@ def advantages(rewards, group, n_groups: int):
     return coeff, base
 
 
-def episode_gradient(w, order, actions, coeff, placement0=None):
+def episode_gradient(w, order, actions, coeff, placement0=None, entropy_coeff=None):
     """sum over steps t and rollouts b of coeff[t, b] * d log pi(actions[t, b] | s_t,b) / d theta for
     the batch of workloads.Workload `w`, every graph starting unvisited from `placement0` (default
     all on device 0) and visiting its nodes in `order` (per graph a permutation of its node ids,
-    concatenated).  Returns (grad [n_params], logp [T, B] with 0 after a graph's last step)."""
+    concatenated); with entropy_coeff [T, B], plus entropy_coeff[t, b] * d H(pi(. | s_t,b)) / d theta
+    (Appendix A.7, "Entropy").  Returns (grad [n_params], logp [T, B] with 0 after a graph's last
+    step)."""
     from . import weights_as_stored
     blob = weights_as_stored(w.weights, w.D, w.H, w.n_layers, w.group_by_device, w.weight_dtype)
     actions = np.asarray(actions)
@@ -74,7 +76,8 @@ def episode_gradient(w, order, actions, coeff, placement0=None):
         for t in range(min(T, n)):
             g, lp = og.policy_gradient([n], [len(src)], src, dst, f, placement, [cur], blob,
                                        [int(actions[t, b])], [coeff[t, b]], w.D, w.H, w.n_layers,
-                                       w.k_sweeps, w.group_by_device)
+                                       w.k_sweeps, w.group_by_device,
+                                       entropy_coeff=None if entropy_coeff is None else [entropy_coeff[t, b]])
             grad += g
             logp[t, b] = lp[0]
             cur = oe.transition(placement, f[:, 2], ordb, t, cur, int(actions[t, b]))

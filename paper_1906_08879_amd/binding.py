@@ -66,8 +66,9 @@ def load_library(path: Optional[str] = None):
         "pl_episode_run": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
                                           vp, ctypes.c_int32, vp, vp, vp]),
         "pl_policy_gradient": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp, vp]),
+        "pl_policy_gradient_ex": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp, vp, vp]),
         "pl_reinforce_coeff": (ctypes.c_int, [ctypes.c_int32, ctypes.c_int32, vp, vp, ctypes.c_int32, vp, vp, vp]),
-        "pl_episode_gradient": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
+        "pl_episode_gradient": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
                                                ctypes.c_int32, vp, vp, vp, vp]),
         "pl_simulate_runtime": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, ctypes.c_float, vp, vp, vp]),
         "pl_simulate_reward": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_float,
@@ -296,19 +297,26 @@ def simulate_runtime(g: GraphBatch, D: int, node_feats, placement, inv_bandwidth
 
 
 def policy_gradient(g: GraphBatch, node_feats, placement, cur_node, w: Weights, actions, coeff, grad,
-                    out_logits, out_logp=None, accumulate: bool = False, stream=None):
-    """pl_policy_gradient on device tensors: grad (+)= sum_b coeff[b] * d log pi(a_b | s_b) / d theta."""
+                    out_logits, out_logp=None, accumulate: bool = False, stream=None, entropy_coeff=None,
+                    out_entropy=None):
+    """pl_policy_gradient / pl_policy_gradient_ex on device tensors:
+    grad (+)= sum_b coeff[b] * d log pi(a_b | s_b) / d theta (+ entropy_coeff[b] * d H(pi) / d theta)."""
     import torch
     lib = load_library()
     n_par = int(lib.pl_weights_count(ctypes.byref(w.cfg)))
-    _check(lib.pl_policy_gradient(
-        g._h, _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
-        _dev_ptr(placement, torch.int32, g.n_tot, "placement"),
-        _dev_ptr(cur_node, torch.int32, g.B, "cur_node"), w._h,
-        _dev_ptr(actions, torch.int32, g.B, "actions"), _dev_ptr(coeff, torch.float32, g.B, "coeff"),
-        1 if accumulate else 0, _dev_ptr(grad, torch.float32, n_par, "grad"),
-        _dev_ptr(out_logits, torch.float32, g.B * w.D, "out_logits"),
-        _dev_ptr(out_logp, torch.float32, g.B, "out_logp"), _stream_ptr(stream)), "pl_policy_gradient")
+    head = [g._h, _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
+            _dev_ptr(placement, torch.int32, g.n_tot, "placement"),
+            _dev_ptr(cur_node, torch.int32, g.B, "cur_node"), w._h,
+            _dev_ptr(actions, torch.int32, g.B, "actions"), _dev_ptr(coeff, torch.float32, g.B, "coeff")]
+    tail = [1 if accumulate else 0, _dev_ptr(grad, torch.float32, n_par, "grad"),
+            _dev_ptr(out_logits, torch.float32, g.B * w.D, "out_logits"),
+            _dev_ptr(out_logp, torch.float32, g.B, "out_logp")]
+    if entropy_coeff is None and out_entropy is None:
+        _check(lib.pl_policy_gradient(*head, *tail, _stream_ptr(stream)), "pl_policy_gradient")
+    else:
+        _check(lib.pl_policy_gradient_ex(
+            *head, _dev_ptr(entropy_coeff, torch.float32, g.B, "entropy_coeff"), *tail,
+            _dev_ptr(out_entropy, torch.float32, g.B, "out_entropy"), _stream_ptr(stream)), "pl_policy_gradient_ex")
     return grad
 
 
@@ -327,7 +335,8 @@ def reinforce_coeff(rewards, group, n_groups: int, out_coeff, out_baseline=None,
 
 
 def episode_gradient(g: GraphBatch, w: Weights, node_feats, placement, cur_node, order, actions, coeff,
-                     t0: int, n_steps: int, grad, logits, out_logp=None, accumulate: bool = False, stream=None):
+                     t0: int, n_steps: int, grad, logits, out_logp=None, accumulate: bool = False, stream=None,
+                     entropy_coeff=None):
     """pl_episode_gradient on device tensors: the REINFORCE sum over n_steps recorded steps."""
     import torch
     lib = load_library()
@@ -338,7 +347,8 @@ def episode_gradient(g: GraphBatch, w: Weights, node_feats, placement, cur_node,
         _dev_ptr(cur_node, torch.int32, g.B, "cur_node"),
         _dev_ptr(order, torch.int32, g.n_tot, "order"),
         _dev_ptr(actions, torch.int32, g.B * n_steps, "actions"),
-        _dev_ptr(coeff, torch.float32, g.B * n_steps, "coeff"), int(t0), int(n_steps),
+        _dev_ptr(coeff, torch.float32, g.B * n_steps, "coeff"),
+        _dev_ptr(entropy_coeff, torch.float32, g.B * n_steps, "entropy_coeff"), int(t0), int(n_steps),
         1 if accumulate else 0, _dev_ptr(grad, torch.float32, n_par, "grad"),
         _dev_ptr(logits, torch.float32, g.B * w.D, "logits"),
         _dev_ptr(out_logp, torch.float32, g.B * n_steps, "out_logp"), _stream_ptr(stream)),

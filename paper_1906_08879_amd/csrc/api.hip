@@ -759,8 +759,8 @@ int pl_reinforce_coeff(int32_t T, int32_t B, const float *rewards, const int32_t
 
 int pl_episode_gradient(pl_graph_batch *g, const pl_weights *w, float *node_feats, int32_t *placement,
                         int32_t *cur_node, const int32_t *order, const int32_t *actions, const float *coeff,
-                        int32_t t0, int32_t n_steps, int32_t accumulate, float *grad, float *logits,
-                        float *out_logp, void *stream)
+                        const float *entropy_coeff, int32_t t0, int32_t n_steps, int32_t accumulate, float *grad,
+                        float *logits, float *out_logp, void *stream)
 {
     if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
     if (t0 < 0 || n_steps < 0) return fail(PL_ERR_SHAPE, "t0 and n_steps must not be negative");
@@ -774,9 +774,10 @@ int pl_episode_gradient(pl_graph_batch *g, const pl_weights *w, float *node_feat
         return PL_OK;
     }
     for (int32_t i = 0; i < n_steps; ++i) {
-        int rc = pl_policy_gradient(g, node_feats, placement, cur_node, w, actions + i * B, coeff + i * B,
-                                    (accumulate || i > 0) ? 1 : 0, grad, logits,
-                                    out_logp ? out_logp + i * B : nullptr, stream);
+        int rc = pl_policy_gradient_ex(g, node_feats, placement, cur_node, w, actions + i * B, coeff + i * B,
+                                       entropy_coeff ? entropy_coeff + i * B : nullptr,
+                                       (accumulate || i > 0) ? 1 : 0, grad, logits,
+                                       out_logp ? out_logp + i * B : nullptr, nullptr, stream);
         if (rc) return rc;
         launch_episode_apply(g->view, w->cfg.D, actions + i * B, order, t0 + i, node_feats, placement, cur_node,
                              static_cast<hipStream_t>(stream));
@@ -789,6 +790,15 @@ int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t
                        const int32_t *cur_node, const pl_weights *w, const int32_t *actions,
                        const float *coeff, int32_t accumulate, float *grad, float *out_logits,
                        float *out_logp, void *stream)
+{
+    return pl_policy_gradient_ex(g, node_feats, placement, cur_node, w, actions, coeff, nullptr, accumulate, grad,
+                                 out_logits, out_logp, nullptr, stream);
+}
+
+int pl_policy_gradient_ex(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                          const int32_t *cur_node, const pl_weights *w, const int32_t *actions,
+                          const float *coeff, const float *entropy_coeff, int32_t accumulate, float *grad,
+                          float *out_logits, float *out_logp, float *out_entropy, void *stream)
 {
     if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
     if (w->cfg.k_sweeps > 1)
@@ -816,10 +826,10 @@ int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t
     if (!accumulate) launch_fill_zero(grad, plan_weights(w->cfg, nullptr), s);
     ForwardArgs fa{node_feats, placement, cur_node, out_logits, nullptr, g->gw.pooled};
     const StageMarks marks{&g->timer, stage_mark};
-    launch_backward(g->view, mv, w->d_blob_t, g->ws, g->gw, fa, actions, coeff, w->cfg.k_sweeps,
-                            g->ws.n_chunks, w->path,
-                            chain_cores ? reinterpret_cast<const uint4 *>(w->d_wfrag_bw) : nullptr,
-                            w->d_sweep_bias, w->sweep_ws, keep, pool_kept, grad, out_logp, &marks, s);
+    const BackwardArgs ba{actions, coeff, entropy_coeff, grad, out_logp, out_entropy};
+    launch_backward(g->view, mv, w->d_blob_t, g->ws, g->gw, fa, ba, w->cfg.k_sweeps, g->ws.n_chunks, w->path,
+                    chain_cores ? reinterpret_cast<const uint4 *>(w->d_wfrag_bw) : nullptr, w->d_sweep_bias,
+                    w->sweep_ws, keep, pool_kept, &marks, s);
     PL_HIP(hipGetLastError());
     return PL_OK;
 }

@@ -197,12 +197,20 @@ struct StageMarks {
 
 size_t wgrad_partial_floats(int64_t R, int I, int J);
 void launch_fill_zero(float *p, size_t n, hipStream_t s);
-void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob_t,
-                             const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
-                             const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
-                             int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
-                             const float *keep, bool pool_kept, float *grad, float *out_logp,
-                             const StageMarks *marks, hipStream_t s);
+// what a reverse pass is asked for (device arrays; the last three may be null)
+struct BackwardArgs {
+    const int32_t *actions;
+    const float *coeff;
+    const float *entropy_coeff;
+    float *grad;
+    float *out_logp;
+    float *out_entropy;
+};
+
+void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob_t, const Workspace &ws,
+                     const GradWorkspace &gw, const ForwardArgs &fa, const BackwardArgs &ba, int k_sweeps,
+                     int pool_chunks, int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
+                     const float *keep, bool pool_kept, const StageMarks *marks, hipStream_t s);
 
 // ---- matrix-core sweep (kernels_mfma.hip)
 bool sweep_mfma_supported(int H, int L, int weight_dtype);

@@ -94,6 +94,8 @@ __global__ __launch_bounds__(kThreads) void k_bw_head(GraphView gv, ModelView mv
                                                       const int32_t *__restrict__ cur_node,
                                                       const int32_t *__restrict__ actions,
                                                       const float *__restrict__ coeff,
+                                                      const float *__restrict__ ent_coeff,
+                                                      float *__restrict__ out_entropy,
                                                       float *__restrict__ hid_out,
                                                       float *__restrict__ dpre_out,
                                                       float *__restrict__ dlogit_out,
@@ -129,11 +131,21 @@ __global__ __launch_bounds__(kThreads) void k_bw_head(GraphView gv, ModelView mv
         const int a = actions[b];
         const bool ok = cur_ok && a >= 0 && a < D;
         const float c = ok ? coeff[b] : 0.0f;
+        // entropy term (Appendix A.7): H = - sum p log p, dH / d logit_d = - p_d (log p_d + H), with
+        // log p_d = logit_d - max - log(sum), which stays finite where p_d underflows to 0
+        const float beta = (ok && ent_coeff) ? ent_coeff[b] : 0.0f;
+        const float lse = logf(tot);
+        float ent = 0.0f;
         for (int d = 0; d < D; ++d) {
             const float p = expf(logit[d] - mx) / tot;
-            dlog[d] = c * ((d == a ? 1.0f : 0.0f) - p);
+            ent -= p * ((logit[d] - mx) - lse);
         }
-        if (out_logp) out_logp[b] = ok ? (logit[a] - mx) - logf(tot) : __builtin_nanf("");
+        for (int d = 0; d < D; ++d) {
+            const float p = expf(logit[d] - mx) / tot;
+            dlog[d] = c * ((d == a ? 1.0f : 0.0f) - p) - beta * p * (((logit[d] - mx) - lse) + ent);
+        }
+        if (out_logp) out_logp[b] = ok ? (logit[a] - mx) - lse : __builtin_nanf("");
+        if (out_entropy) out_entropy[b] = cur_ok ? ent : __builtin_nanf("");
     }
     __syncthreads();
     for (int j = tid; j < H; j += kThreads) {
@@ -1223,14 +1235,13 @@ void launch_dense(const DenseCall &c, int H, hipStream_t s)
 
 }  // namespace
 
-void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob_t,
-                             const Workspace &ws, const GradWorkspace &gw, const ForwardArgs &fa,
-                             const int32_t *actions, const float *coeff, int k_sweeps, int pool_chunks,
-                             int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
-                             const float *keep, bool pool_kept, float *grad, float *out_logp,
-                             const StageMarks *marks, hipStream_t s)
+void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob_t, const Workspace &ws,
+                     const GradWorkspace &gw, const ForwardArgs &fa, const BackwardArgs &ba, int k_sweeps,
+                     int pool_chunks, int generic, const uint4 *wfrag_bw, const float *sweep_bias, int sweep_ws,
+                     const float *keep, bool pool_kept, const StageMarks *marks, hipStream_t s)
 {
     if (gv.B == 0) return;
+    float *grad = ba.grad;
     const int H = mv.H, L = mv.L, G = mv.G, B = gv.B, n = gv.n_tot;
     const int rpt = pick_rpt_bw(H);
     const int n_slices = (mv.Z + 255) / 256;
@@ -1243,7 +1254,8 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
     // 1. head
     mark(PL_STAGE_BW_HEAD, true);
     hipLaunchKernelGGL(k_bw_head, dim3(B), dim3(kThreads), 0, s, gv, mv, blob_t, ws.hidp, n_slices, fa.cur_node,
-                       actions, coeff, gw.hid, gw.dpre, gw.dlogit, gw.dz, out_logp);
+                       ba.actions, ba.coeff, ba.entropy_coeff, ba.out_entropy, gw.hid, gw.dpre, gw.dlogit, gw.dz,
+                       ba.out_logp);
     {
         const size_t lds = sizeof(float) * 3 * kTile * H;
 #define CALL(R)                                                                                          \

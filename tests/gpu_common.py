@@ -112,7 +112,8 @@ def custom_workload(rng, sizes, D, H, n_layers=2, k_sweeps=1, group=1, weight_dt
                     cur_node=np.array(curs, np.int32), weights=weights)
 
 
-def run_gradient(w, actions, coeff, handles=None, path=0, accumulate_into=None, cur_node=None):
+def run_gradient(w, actions, coeff, handles=None, path=0, accumulate_into=None, cur_node=None,
+                 entropy_coeff=None):
     """pl_policy_gradient of workload `w` on cuda:0.  Returns dict(grad, logits, logp) as numpy."""
     import torch
     import paper_1906_08879_amd as pl
@@ -136,10 +137,14 @@ def run_gradient(w, actions, coeff, handles=None, path=0, accumulate_into=None, 
         grad = torch.from_numpy(np.ascontiguousarray(accumulate_into, dtype=np.float32)).to(dev)
     logits = torch.full((w.B, w.D), float("nan"), dtype=torch.float32, device=dev)
     logp = torch.full((w.B,), 7.0, dtype=torch.float32, device=dev)
+    ent = torch.full((w.B,), 7.0, dtype=torch.float32, device=dev)
+    t_ent = None if entropy_coeff is None else torch.from_numpy(np.ascontiguousarray(entropy_coeff, dtype=np.float32)).to(dev)
     pl.policy_gradient(g, t_feats, t_place, t_cur, wt, t_act, t_coef, grad, logits, logp,
-                       accumulate=accumulate_into is not None)
+                       accumulate=accumulate_into is not None, entropy_coeff=t_ent,
+                       out_entropy=None if entropy_coeff is None else ent)
     torch.cuda.synchronize()
-    out = dict(grad=grad.cpu().numpy(), logits=logits.cpu().numpy(), logp=logp.cpu().numpy())
+    out = dict(grad=grad.cpu().numpy(), logits=logits.cpu().numpy(), logp=logp.cpu().numpy(),
+               entropy=ent.cpu().numpy())
     if handles is None:
         g.close()
         wt.close()

@@ -129,6 +129,39 @@ def test_accumulation_linearity_and_rejected_states():
     assert np.isnan(got["logp"][1]) and np.isnan(got["logp"][2]) and np.isfinite(got["logp"][[0, 3]]).all()
 
 
+@pytest.mark.parametrize("case", ["generic", "matrix-core", "nmt"])
+def test_entropy_term(case):
+    """Appendix A.7 "Entropy": the loss also carries beta * H(pi); gradient and entropies against the
+    oracle, alone and mixed with the log-probability term; a graph without a valid current node
+    adds nothing."""
+    rng = np.random.default_rng(12)
+    if case == "generic":
+        w = custom_workload(rng, [25, 9, 40, 1], 5, 12, w_scale=0.12)
+    elif case == "matrix-core":
+        w = custom_workload(rng, [25, 9, 40, 1], 4, 64, 2, 1, 1, "bf16", w_scale=0.06)
+    else:
+        w = make_workload("nmt", B=2)
+    actions, coeff, fwd = _actions_and_coeff(w, 4)
+    beta = rng.uniform(0.1, 2.0, w.B).astype(np.float32)
+    for c, what in ((np.zeros(w.B, np.float32), "entropy only"), (coeff, "mixed")):
+        got = run_gradient(w, actions, c, entropy_coeff=beta)
+        ref_grad, _, ref_ent = og.gradient_workload(w, actions, c.astype(np.float64), entropy_coeff=beta.astype(np.float64),
+                                                    want_entropy=True)
+        worst = assert_grad_close(got["grad"], ref_grad, w, f"{case} {what}")
+        print(f"[gradient] entropy {case} {what}: worst error / bound = {worst:.3g}", flush=True)
+        scale = np.abs(fwd["logits"]).max(axis=1)
+        assert (np.abs(got["entropy"] - ref_ent) <= 1e-4 * scale + 1e-5).all(), (got["entropy"], ref_ent)
+    bad_cur = np.array(w.cur_node, copy=True)
+    bad_cur[0] = -1
+    got = run_gradient(w, actions, coeff, entropy_coeff=beta, cur_node=bad_cur)
+    c2, b2 = coeff.copy(), beta.copy()
+    c2[0] = 0.0
+    b2[0] = 0.0
+    ref_grad, _ = og.gradient_workload(w, actions, c2.astype(np.float64), entropy_coeff=b2.astype(np.float64))
+    assert_grad_close(got["grad"], ref_grad, w, f"{case} rejected state")
+    assert np.isnan(got["entropy"][0]) and np.isfinite(got["entropy"][1:]).all()
+
+
 def test_gradient_replays_from_a_hip_graph():
     """After the first call on a batch a gradient call only launches kernels (the zero fill is a
     kernel too), so it can be captured once and replayed: replays on new states, with eager work

@@ -62,7 +62,8 @@ def _rollout_batch(w, rollouts):
 def test_one_policy_gradient_estimate_end_to_end(name, rollouts):
     """Rollouts of the same graphs under one policy (different random numbers), intermediate
     rewards = decrease of the simulated run time at every step (Appendix A.7 "Intermediate
-    Rewards"), baseline = mean over the rollouts of the graph, gradient by replay."""
+    Rewards"), baseline = mean over the rollouts of the graph, gradient by replay, with an entropy
+    term per decision (Appendix A.7 "Entropy")."""
     import torch
     import paper_1906_08879_amd as pl
     if name == "ragged":     # graphs of different length on the matrix-core path (H = 32, fp32 weights)
@@ -104,7 +105,8 @@ def test_one_policy_gradient_estimate_end_to_end(name, rollouts):
     n_par = pl.weights_count(w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
     grad = torch.full((n_par,), float("nan"), dtype=torch.float32, device=dev)
     logp_replay = torch.empty((T, w.B), dtype=torch.float32, device=dev)
-    pl.episode_gradient(g, wt, d_f, d_p, d_c, d_o, actions, coeff, 0, T, grad, logits, logp_replay)
+    beta = torch.from_numpy(np.random.default_rng(5).uniform(0.0, 0.5, (T, w.B)).astype(np.float32)).to(dev)
+    pl.episode_gradient(g, wt, d_f, d_p, d_c, d_o, actions, coeff, 0, T, grad, logits, logp_replay, entropy_coeff=beta)
     torch.cuda.synchronize()
     act = actions.cpu().numpy()
     rt = runtime.cpu().numpy()
@@ -131,7 +133,8 @@ def test_one_policy_gradient_estimate_end_to_end(name, rollouts):
     assert np.abs(ref_coeff).max() > 0 and (act[:, 0] != act[:, 1]).any(), "degenerate case: identical rollouts"
     cscale = np.abs(ref_coeff).max()
     assert np.abs(coeff.cpu().numpy() - ref_coeff).max() <= 1e-5 * max(cscale, np.abs(ref_rt).max()), name
-    ref_grad, ref_logp = orf.episode_gradient(w, order, act, ref_coeff, placement0)
+    ref_grad, ref_logp = orf.episode_gradient(w, order, act, ref_coeff, placement0,
+                                              entropy_coeff=beta.cpu().numpy().astype(np.float64))
     assert np.abs(logp_roll.cpu().numpy() - ref_logp)[live].max() <= 2e-3
     worst = assert_grad_close(grad.cpu().numpy(), ref_grad, w, name + " REINFORCE sum")
     print(f"[reinforce] {name}: worst error / bound = {worst:.3g}", flush=True)

@@ -173,7 +173,7 @@ def test_reinforce_entry_points_reject_bad_arguments(lib):
     assert raw.pl_reinforce_coeff(i32(0), i32(4), null, null, i32(0), null, null, null) == 0     # nothing to do
     assert raw.pl_reinforce_coeff(i32(3), i32(4), null, null, i32(0), null, null, null) == -1    # PL_ERR_NULL
     g = pl.GraphBatch([2], [1], [0], [1])
-    args = [g._h, null, null, null, null, null, null, null, i32(0), i32(1), i32(0), null, null, null, null]
+    args = [g._h, null, null, null, null, null, null, null, null, i32(0), i32(1), i32(0), null, null, null, null]
     assert raw.pl_episode_gradient(*args) == -1                                                 # weights handle is NULL
     g.close()
 
