@@ -20,6 +20,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 N_STATES = 8
 CPU_SAMPLE_GRAPHS = {"random32": 1, "layered200": 64, "inception": 128, "nmt": 64, "nasnet": 256}
@@ -240,6 +241,18 @@ def main() -> int:
                     "stage_ms": {k: round(v[0] / v[1], 4) for k, v in gr_stages.items() if v[1]},
                     "what": "forward pass + reverse pass (log-probability gradient of one decision per "
                             "graph, summed over the batch)"}
+        # the reverse pass's largest stage: every layer's weight gradient is a contraction over rows,
+        # 2 R I J flops each: projection (32 padded columns), 2 directions x (f, g) x L layers of H x H,
+        # l (2H x H, then H x H) over the nodes of the three sets (all nodes but the current ones)
+        wg_ms = gradient["stage_ms"].get("bw_wgrad")
+        if wg_ms:
+            n, H, L = float(w.n_tot), float(w.H), float(w.n_layers)
+            flops = 2.0 * n * H * (32.0 + (4.0 * L * H if w.k_sweeps else 0.0) + (2.0 * H + (L - 1.0) * H))
+            tf = flops / (wg_ms * 1e-3) / 1e12
+            gradient["roofline"] = {"kernel": "weight-gradient contractions (fp32 matrix cores) + slab sums",
+                                    "bound": "mfma", "achieved": round(tf, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
+                                    "unit": "TFLOP/s", "frac": round(tf / FP32_MFMA_PEAK_TFLOPS, 4),
+                                    "flops_per_step": int(flops), "traffic": None}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -256,6 +269,17 @@ def main() -> int:
                         "sample": f"one forward of the first {n_s} graphs of '{args.workload}' "
                                   f"({int(ws.n_tot)} nodes), float64 C oracle, {dt:.2f} s wall",
                         "node_embeddings_per_s": round(ws.n_tot / dt, 1)}
+        # the oracles of the rows beside the headline, on bounded samples (one graph each)
+        from oracle import gradient as og, simulator as osim
+        w1 = make_workload(args.workload, B=1)
+        t0 = time.perf_counter()
+        osim.simulate(int(w1.n_nodes[0]), w1.edge_src, w1.edge_dst, w1.node_feats[:, 0], w1.node_feats[:, 1],
+                      w1.placement, w1.D, np.float32(inv_bw))
+        simulator["cpu_oracle_placements_per_s"] = round(1.0 / (time.perf_counter() - t0), 2)
+        if gradient is not None:
+            t0 = time.perf_counter()
+            og.gradient_workload(w1, [0], [1.0])
+            gradient["cpu_oracle_graph_steps_per_s"] = round(1.0 / (time.perf_counter() - t0), 3)
 
     out = {
         "metric": "policy forward steps/sec (graphs x steps)",
