@@ -190,7 +190,9 @@ int pl_episode_run(pl_graph_batch *g, const pl_weights *w, float *node_feats, in
  *   out_logits  dev [B, D] fp32 logits of the forward pass (required)
  *   out_logp    dev [B] fp32    log pi(a_b | s_b); NULL to skip
  * A graph whose cur_node or action is out of range adds nothing and gets out_logp = NaN.
- * ReLU's derivative at 0 is taken as 0.  Covers k_sweeps <= 1 (PL_ERR_SHAPE otherwise).  The
+ * ReLU's derivative at 0 is taken as 0.  With k_sweeps >= 2 the states and messages after every
+ * sweep but the last are copied aside during the forward pass ((k_sweeps - 1) x 4 N_tot H floats
+ * more) and the sweeps are differentiated from the last to the first.  The
  * first call on a batch allocates the buffers of the reverse pass (about (14 n_layers + 10)
  * x N_tot x H floats); later calls only launch kernels.  Asynchronous on `stream`; summation
  * orders are fixed, so equal inputs give bit-equal gradients. */
@@ -241,7 +243,7 @@ int pl_reinforce_coeff(int32_t T, int32_t B, const float *rewards, const int32_t
  *   grad          dev [pl_weights_count];  logits  dev [B, D] scratch (last step's logits)
  *   out_logp      dev [n_steps, B] or NULL: log pi(a | s) of every replayed decision (NaN once a
  *                                     graph's episode is over)
- * Same limits as pl_policy_gradient. */
+ * Same behaviour as pl_policy_gradient_ex otherwise. */
 int pl_episode_gradient(pl_graph_batch *g, const pl_weights *w, float *node_feats, int32_t *placement,
                         int32_t *cur_node, const int32_t *order, const int32_t *actions, const float *coeff,
                         const float *entropy_coeff, int32_t t0, int32_t n_steps, int32_t accumulate, float *grad,

@@ -245,7 +245,7 @@ void free_workspace(Workspace &ws)
 
 void free_grad_workspace(GradWorkspace &gw)
 {
-    float *all[] = {gw.fact, gw.gact, gw.agg, gw.dagg, gw.dfg, gw.keep, gw.extb, gw.lact, gw.dl, gw.demb, gw.dx, gw.phi,
+    float *all[] = {gw.fact, gw.gact, gw.agg, gw.dagg, gw.dfg, gw.keep, gw.snap_emb, gw.snap_msg, gw.extb, gw.lact, gw.dl, gw.demb, gw.dx, gw.phi,
                     gw.pooled, gw.dP, gw.hin, gw.hact, gw.dh, gw.dz, gw.hid, gw.dpre, gw.dlogit, gw.partial};
     for (float *p : all) (void)hipFree(p);
     (void)hipFree(gw.cls);
@@ -396,7 +396,8 @@ void stage_mark(void *ctx, int stage, bool begin, hipStream_t s)
 int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
                  const int32_t *cur_node, const pl_weights *w, float *out_logits, float *out_probs,
                  float *out_node_emb, float *out_pooled, void *stream, float *keep = nullptr,
-                 size_t keep_stride = 0, float *keep_pool = nullptr, bool *pool_kept = nullptr)
+                 size_t keep_stride = 0, float *keep_pool = nullptr, bool *pool_kept = nullptr,
+                 float *snap_emb = nullptr, float *snap_msg = nullptr)
 {
     if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
     if (g->host.B == 0) return PL_OK;
@@ -426,6 +427,12 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
                                   w->d_sweep_bias, w->sweep_ws, k == 0, k + 1 < w->cfg.k_sweeps, keep, keep_stride, s);
             else
                 launch_sweep_generic(gv, mv, g->ws, fa, k == 0, s);
+            if (snap_emb && k + 1 < w->cfg.k_sweeps) {
+                // the reverse pass of a multi-sweep network needs the states and messages after this sweep
+                const size_t span = static_cast<size_t>(g->host.n_tot) * 2 * mv.H;
+                PL_HIP(hipMemcpyAsync(snap_emb + k * span, g->ws.emb, sizeof(float) * span, hipMemcpyDeviceToDevice, s));
+                PL_HIP(hipMemcpyAsync(snap_msg + k * span, g->ws.msg, sizeof(float) * span, hipMemcpyDeviceToDevice, s));
+            }
         }
     }
     const bool pool_mfma = w->d_pool_frag && w->path == 0;
@@ -801,9 +808,6 @@ int pl_policy_gradient_ex(pl_graph_batch *g, const float *node_feats, const int3
                           float *out_logits, float *out_logp, float *out_entropy, void *stream)
 {
     if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
-    if (w->cfg.k_sweeps > 1)
-        return fail(PL_ERR_SHAPE, "the gradient pass covers k_sweeps <= 1 (later sweeps overwrite the states "
-                                  "that the earlier ones would need)");
     if (g->host.B == 0) return PL_OK;
     if (!node_feats || !placement || !cur_node || !actions || !coeff || !grad || !out_logits)
         return fail(PL_ERR_NULL, "a required device array is NULL");
@@ -815,18 +819,30 @@ int pl_policy_gradient_ex(pl_graph_batch *g, const float *node_feats, const int3
     // the chain kernel addresses the delta arrays with 32-bit element offsets
     const bool fits = (2.0 * mv.L * static_cast<double>(g->host.n_tot) + 1) * mv.H < 2.0e9 &&
                       (static_cast<double>(g->host.n_tot) + 2) * 2 * mv.H * sizeof(float) < 4.0e9;
-    const bool chain_cores = w->d_wfrag_bw && w->path == 0 && w->cfg.k_sweeps == 1 && fits;
-    // on that path the forward sweep keeps a_v and the layer outputs, so nothing is computed twice
-    float *keep = chain_cores ? g->gw.keep : nullptr;
+    const bool chain_cores = w->d_wfrag_bw && w->path == 0 && w->cfg.k_sweeps >= 1 && fits;
+    // on that path a single forward sweep keeps a_v and the layer outputs, so nothing is computed twice
+    float *keep = (chain_cores && w->cfg.k_sweeps == 1) ? g->gw.keep : nullptr;
+    // several sweeps: the states and messages after every sweep but the last are copied aside
+    if (w->cfg.k_sweeps > 1 && g->gw.snap_sweeps < w->cfg.k_sweeps - 1) {
+        (void)hipFree(g->gw.snap_emb);
+        (void)hipFree(g->gw.snap_msg);
+        g->gw.snap_emb = g->gw.snap_msg = nullptr;
+        g->gw.snap_sweeps = 0;
+        const size_t span = static_cast<size_t>(g->host.n_tot) * 2 * mv.H * (w->cfg.k_sweeps - 1);
+        PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->gw.snap_emb), sizeof(float) * (span + 4)));
+        PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->gw.snap_msg), sizeof(float) * (span + 4)));
+        g->gw.snap_sweeps = w->cfg.k_sweeps - 1;
+    }
     // likewise the matrix-core pooling kernel keeps the outputs of l's layers
     bool pool_kept = false;
     rc = forward_impl(g, node_feats, placement, cur_node, w, out_logits, nullptr, nullptr, g->gw.pooled, stream,
-                      keep, g->gw.dfg_stride, w->path == 0 ? g->gw.lact : nullptr, &pool_kept);
+                      keep, g->gw.dfg_stride, w->path == 0 ? g->gw.lact : nullptr, &pool_kept,
+                      w->cfg.k_sweeps > 1 ? g->gw.snap_emb : nullptr, g->gw.snap_msg);
     if (rc) return rc;
     if (!accumulate) launch_fill_zero(grad, plan_weights(w->cfg, nullptr), s);
     ForwardArgs fa{node_feats, placement, cur_node, out_logits, nullptr, g->gw.pooled};
     const StageMarks marks{&g->timer, stage_mark};
-    const BackwardArgs ba{actions, coeff, entropy_coeff, grad, out_logp, out_entropy};
+    const BackwardArgs ba{actions, coeff, entropy_coeff, grad, out_logp, out_entropy, g->gw.snap_emb, g->gw.snap_msg};
     launch_backward(g->view, mv, w->d_blob_t, g->ws, g->gw, fa, ba, w->cfg.k_sweeps, g->ws.n_chunks, w->path,
                     chain_cores ? reinterpret_cast<const uint4 *>(w->d_wfrag_bw) : nullptr, w->d_sweep_bias,
                     w->sweep_ws, keep, pool_kept, &marks, s);

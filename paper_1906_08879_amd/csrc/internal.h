@@ -169,6 +169,9 @@ struct GradWorkspace {
     size_t dfg_stride = 0;
     float *keep = nullptr;                    // per direction [2L, n_tot, H]: a_v and layer outputs stored by
                                               // the forward sweep (same stride as dfg)
+    float *snap_emb = nullptr, *snap_msg = nullptr;   // k >= 2 sweeps: states and messages after every
+                                              // sweep but the last, [k - 1][2 n_tot H] each
+    int32_t snap_sweeps = 0;
     float *extb = nullptr;                    // [2, n_tot, H] outside gradient of the states, bucket order
     uint8_t *mask4 = nullptr;                 // [2, n_tot, H] ReLU gates, bucket order
     float *lact = nullptr, *dl = nullptr;     // [L, n_tot, H] layer outputs / deltas of l (own set)
@@ -205,6 +208,9 @@ struct BackwardArgs {
     float *grad;
     float *out_logp;
     float *out_entropy;
+    // states [k - 1][n_tot, 2H] and messages [k - 1][2, n_tot, H] after every sweep but the last
+    const float *snap_emb;
+    const float *snap_msg;
 };
 
 void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob_t, const Workspace &ws,

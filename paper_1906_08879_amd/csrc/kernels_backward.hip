@@ -19,7 +19,7 @@
 // Two sets of kernels: generic fp32 vector kernels for any H <= 256, D <= 16, 1..4 layers; and,
 // for H in {32, 64, 128}, the parallel parts (per-node layers, weight gradients) on the fp32
 // matrix cores (v_mfma_f32_32x32x2_f32) and the dependent chain of step 3 in the matrix-core sweep
-// kernel run in reverse.  k <= 1 sweeps.
+// kernel run in reverse.  Several sweeps are differentiated from the last to the first.
 #include <algorithm>
 
 #include "internal.h"
@@ -1322,19 +1322,25 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
         return keep ? keep + dir * gw.dfg_stride + static_cast<size_t>(1 + L + l) * NH
                     : gw.fact + (static_cast<size_t>(dir) * L + l) * NH;
     };
+    // one sweep at a time, from the last to the first: demb holds the outside gradient of the sweep's
+    // output on entry and the gradient of its input on exit; the states and messages of an earlier
+    // sweep come from the snapshots taken during the forward pass
+    for (int j = k_sweeps - 1; j >= 0; --j) {
+    const float *emb_j = j == k_sweeps - 1 ? ws.emb : ba.snap_emb + static_cast<size_t>(j) * 2 * NH;
+    const float *msg_j = j == k_sweeps - 1 ? ws.msg : ba.snap_msg + static_cast<size_t>(j) * 2 * NH;
     mark(PL_STAGE_BW_ACTS, true);
-    if (k_sweeps > 0 && dense && !keep) {
-        // the last layer of f is the message itself, which the forward pass left in ws.msg (the
+    if (dense && !keep) {
+        // the last layer of f is the message itself, which the forward pass left in msg_j (the
         // generic chain kernel reads it from fact, so there it is computed again)
         for (int dir = 0; dir < 2; ++dir)
             for (int l = 0; l + 1 < L || (l < L && !wfrag_bw); ++l) {
                 const LayerRef &ly = mv.f[dir].layer[l];
-                launch_dense({l == 0 ? ws.emb + dir * H : gw.fact + (static_cast<size_t>(dir) * L + l - 1) * NH,
+                launch_dense({l == 0 ? emb_j + dir * H : gw.fact + (static_cast<size_t>(dir) * L + l - 1) * NH,
                               l == 0 ? 2 * H : H, nullptr, nullptr, n, H, mv.blob + ly.w, H, mv.blob + ly.b, 1,
                               nullptr, 0, gw.fact + (static_cast<size_t>(dir) * L + l) * NH, H}, H, s);
             }
         hipLaunchKernelGGL(k_bw_agg, dim3(static_cast<unsigned>((NH / 4 + kThreads - 1) / kThreads), 2), dim3(kThreads),
-                           0, s, gv, H, ws.msg, gw.agg);
+                           0, s, gv, H, msg_j, gw.agg);
         for (int dir = 0; dir < 2; ++dir)
             for (int l = 0; l < L; ++l) {
                 const LayerRef &ly = mv.g[dir].layer[l];
@@ -1344,14 +1350,14 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
                               gw.gact + (static_cast<size_t>(dir) * L + l) * NH, H}, H, s);
             }
     }
-    if (k_sweeps > 0) {
+    {
         const size_t lds = sizeof(float) * 2 * kTile * H;
         const unsigned tiles = static_cast<unsigned>((n + kTile - 1) / kTile);
         if (!dense) {
 #define CALL(R)                                                                                              \
     allow_lds_bw(k_bw_f_acts<R>, lds);                                                                       \
     allow_lds_bw(k_bw_g_acts<R>, lds);                                                                       \
-    hipLaunchKernelGGL(k_bw_f_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, ws.emb, gw.fact);     \
+    hipLaunchKernelGGL(k_bw_f_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, emb_j, gw.fact);     \
     hipLaunchKernelGGL(k_bw_g_acts<R>, dim3(tiles, 2), dim3(kThreads), lds, s, gv, mv, gw.fact, gw.agg, gw.gact)
             PL_DISPATCH_RPT(rpt, CALL)
 #undef CALL
@@ -1360,7 +1366,7 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
             GateSrc src[2];
             for (int sd = 0; sd < 2; ++sd) {
                 const bool from_msg = keep || dense;
-                src[sd].m = from_msg ? ws.msg + static_cast<size_t>(sd) * NH : fact_of(sd, L - 1);
+                src[sd].m = from_msg ? msg_j + static_cast<size_t>(sd) * NH : fact_of(sd, L - 1);
                 src[sd].f0 = L == 2 ? fact_of(sd, 0) : nullptr;
                 src[sd].g_last = gact_of(sd, L - 1);
                 src[sd].g0 = L == 2 ? gact_of(sd, 0) : nullptr;
@@ -1382,8 +1388,21 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
 #undef CALL
         }
         mark(PL_STAGE_BW_CHAIN, false);
-    } else {
-        mark(PL_STAGE_BW_ACTS, false);
+    }
+    {
+        mark(PL_STAGE_BW_WGRAD, true);
+        for (int dir = 0; dir < 2; ++dir)
+            for (int l = 0; l < L; ++l) {
+                const float *dfl = gw.dfg + dir * gw.dfg_stride + static_cast<size_t>(l) * NH;
+                const float *dgl = dfl + static_cast<size_t>(L) * NH;
+                const float *fin = l == 0 ? emb_j + dir * H : fact_of(dir, l - 1);
+                launch_wgrad(fin, l == 0 ? 2 * H : H, dfl, H, nullptr, 0, nullptr, nullptr, n, mv.f[dir].layer[l],
+                             gw.partial, grad, generic, s);
+                const float *gin = l == 0 ? agg_of(dir) : gact_of(dir, l - 1);
+                launch_wgrad(gin, H, dgl, H, nullptr, 0, nullptr, nullptr, n, mv.g[dir].layer[l], gw.partial, grad, generic, s);
+            }
+        mark(PL_STAGE_BW_WGRAD, false);
+    }
     }
     // 4. projection
     mark(PL_STAGE_BW_PROJ, true);
@@ -1405,18 +1424,6 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
         launch_wgrad(gw.phi, 32, gw.dx, H, nullptr, 0, nullptr, nullptr, n, mv.proj, gw.partial, grad, generic, s, 32);
     else
         launch_wgrad(gw.phi, mv.F, gw.dx, H, nullptr, 0, nullptr, nullptr, n, mv.proj, gw.partial, grad, generic, s);
-    if (k_sweeps > 0) {
-        for (int dir = 0; dir < 2; ++dir)
-            for (int l = 0; l < L; ++l) {
-                const float *dfl = gw.dfg + dir * gw.dfg_stride + static_cast<size_t>(l) * NH;
-                const float *dgl = dfl + static_cast<size_t>(L) * NH;
-                const float *fin = l == 0 ? ws.emb + dir * H : fact_of(dir, l - 1);
-                launch_wgrad(fin, l == 0 ? 2 * H : H, dfl, H, nullptr, 0, nullptr, nullptr, n, mv.f[dir].layer[l],
-                             gw.partial, grad, generic, s);
-                const float *gin = l == 0 ? agg_of(dir) : gact_of(dir, l - 1);
-                launch_wgrad(gin, H, dgl, H, nullptr, 0, nullptr, nullptr, n, mv.g[dir].layer[l], gw.partial, grad, generic, s);
-            }
-    }
     for (int set = 0; set < 3; ++set)
         for (int l = 0; l < L; ++l) {
             const float *lin = l == 0 ? ws.emb : gw.lact + static_cast<size_t>(l - 1) * NH;

@@ -227,12 +227,15 @@ def test_empty_batch_is_accepted():
     wt.close()
 
 
-def test_more_than_one_sweep_is_refused():
-    import paper_1906_08879_amd as pl
-    rng = np.random.default_rng(6)
-    w = custom_workload(rng, [9, 5], 3, 16, k_sweeps=2)
-    with pytest.raises(pl.PlacetoError, match="k_sweeps"):
-        run_gradient(w, np.zeros(2, np.int32), np.ones(2, np.float32))
+@pytest.mark.parametrize("D,H,L,k,wd", [(3, 12, 2, 2, "fp32"), (4, 32, 2, 2, "fp32"), (4, 64, 2, 3, "bf16"),
+                                        (2, 128, 1, 2, "bf16"), (4, 64, 3, 2, "bf16"), (5, 128, 2, 2, "fp32")])
+def test_several_sweeps(D, H, L, k, wd):
+    """k >= 2 repetitions of the message passing (Section 2.2 step 2): the sweeps are differentiated
+    from the last to the first with the states and messages that the forward pass copied aside;
+    generic kernels, matrix-core chain, and matrix-core dense layers with the generic chain."""
+    rng = np.random.default_rng(7 * H + k)
+    w = custom_workload(rng, [30, 1, 12, 45], D, H, L, k, 1, wd, w_scale=0.07)
+    _compare(w, f"k={k} D={D} H={H} L={L} {wd}")
 
 
 def test_full_size_batch_sampled_graphs():
