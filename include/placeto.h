@@ -49,6 +49,11 @@ typedef struct {
     int32_t k_sweeps;        /* repetitions of the message passing (Section 2.2 step 2), 0..8 */
     int32_t group_by_device; /* 1: pool per (set, device); 0: per set only, as printed   */
     int32_t weight_dtype;    /* PL_WEIGHTS_FP32 or PL_WEIGHTS_BF16                       */
+    int32_t single_set;      /* 0: the three node sets of Section 2.2 step 3; 1: every node
+                                other than v* is pooled in the first set (the "simple aggregator"
+                                of the paper's comparison of policy architectures; with
+                                k_sweeps = 0 on top of it nothing of the graph structure is used;
+                                k_sweeps = 0 alone is its "simple partitioner")          */
 } pl_model_cfg;
 
 enum { PL_WEIGHTS_FP32 = 0, PL_WEIGHTS_BF16 = 1 };

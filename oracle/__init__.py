@@ -26,7 +26,8 @@ _lib = None
 
 class OracleCfg(ctypes.Structure):
     _fields_ = [("D", ctypes.c_int32), ("H", ctypes.c_int32), ("n_layers", ctypes.c_int32),
-                ("k_sweeps", ctypes.c_int32), ("group_by_device", ctypes.c_int32)]
+                ("k_sweeps", ctypes.c_int32), ("group_by_device", ctypes.c_int32),
+                ("single_set", ctypes.c_int32)]
 
 
 def build(force: bool = True, src: str = _SRC, out: str = _LIB) -> str:
@@ -149,10 +150,10 @@ def classes(n, src, dst, cur, lib=None) -> np.ndarray:
 
 
 def forward_graph(n, src, dst, feats, placement, cur, weights, D, H, n_layers=2, k_sweeps=1,
-                  group_by_device=1, lib=None):
+                  group_by_device=1, lib=None, single_set=0):
     """One graph.  Returns dict(logits [D], probs [D], emb [n,2H], pooled [3,G,H])."""
     lib = lib or _get()
-    cfg = OracleCfg(D, H, n_layers, k_sweeps, group_by_device)
+    cfg = OracleCfg(D, H, n_layers, k_sweeps, group_by_device, single_set)
     G = D if group_by_device else 1
     src, ps = _i32(src)
     dst, pd = _i32(dst)
@@ -174,11 +175,11 @@ def forward_graph(n, src, dst, feats, placement, cur, weights, D, H, n_layers=2,
 
 def forward_batch(n_nodes, n_edges, src, dst, feats, placement, cur, weights, D, H,
                   n_layers=2, k_sweeps=1, group_by_device=1, n_threads=1, want_emb=True,
-                  lib=None):
+                  lib=None, single_set=0):
     """A concatenated batch.  Returns dict(logits [B,D], probs [B,D], emb [N_tot,2H] or None,
     pooled [B,3,G,H])."""
     lib = lib or _get()
-    cfg = OracleCfg(D, H, n_layers, k_sweeps, group_by_device)
+    cfg = OracleCfg(D, H, n_layers, k_sweeps, group_by_device, single_set)
     G = D if group_by_device else 1
     n_nodes, pn = _i32(n_nodes)
     n_edges, pe_ = _i32(n_edges)
@@ -215,4 +216,5 @@ def forward_workload(w, n_threads=1, want_emb=True, placement=None, cur_node=Non
     return forward_batch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst, feats,
                          w.placement if placement is None else placement,
                          w.cur_node if cur_node is None else cur_node, blob, w.D, w.H,
-                         w.n_layers, w.k_sweeps, w.group_by_device, n_threads, want_emb)
+                         w.n_layers, w.k_sweeps, w.group_by_device, n_threads, want_emb,
+                         single_set=getattr(w, "single_set", 0))

@@ -122,7 +122,7 @@ def _sweep(par, f_name, g_name, n_layers, H, order, nbr, s):
 
 
 def logits_graph(theta, n, src, dst, feats, placement, cur, D, H, n_layers=2, k_sweeps=1,
-                 group_by_device=1):
+                 group_by_device=1, single_set=0):
     """Pre-softmax outputs [D] of the policy for one graph, as a float64 tensor that depends
     differentiably on the flat weight tensor `theta`."""
     G = D if group_by_device else 1
@@ -154,6 +154,8 @@ def logits_graph(theta, n, src, dst, feats, placement, cur, D, H, n_layers=2, k_
             if u == cur:
                 continue
             cls = 0 if u in up else (1 if u in down else 2)
+            if single_set:                  # the "simple aggregator": no partition, one set
+                cls = 0
             if cls != i:
                 continue
             d = int(placement[u]) if group_by_device else 0
@@ -174,7 +176,7 @@ def entropy(logits) -> "torch.Tensor":
 
 def policy_gradient(n_nodes, n_edges, src, dst, feats, placement, cur, weights, actions, coeff,
                     D, H, n_layers=2, k_sweeps=1, group_by_device=1, only=None, entropy_coeff=None,
-                    want_entropy=False):
+                    want_entropy=False, single_set=0):
     """grad [n_params] float64 = sum_b coeff[b] * d log pi(a_b | s_b) / d theta
     (+ entropy_coeff[b] * d H(pi(. | s_b)) / d theta when given), and logp [B] = log pi(a_b | s_b).
     `only` restricts the work to the listed graphs (the others count as zero and get logp = nan).
@@ -194,7 +196,7 @@ def policy_gradient(n_nodes, n_edges, src, dst, feats, placement, cur, weights, 
         lo, hi, elo, ehi = noff[b], noff[b + 1], eoff[b], eoff[b + 1]
         logits = logits_graph(theta, int(n_nodes[b]), src[elo:ehi], dst[elo:ehi], feats[lo:hi],
                               placement[lo:hi], int(cur[b]), D, H, n_layers, k_sweeps,
-                              group_by_device)
+                              group_by_device, single_set)
         lp = torch.log_softmax(logits, dim=0)[int(actions[b])]
         logp[b] = float(lp.detach())
         h = entropy(logits)
@@ -216,4 +218,4 @@ def gradient_workload(w, actions, coeff, only=None, entropy_coeff=None, want_ent
     return policy_gradient(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst, w.node_feats, w.placement,
                            w.cur_node, blob, actions, coeff, w.D, w.H, w.n_layers, w.k_sweeps,
                            w.group_by_device, only=only, entropy_coeff=entropy_coeff,
-                           want_entropy=want_entropy)
+                           want_entropy=want_entropy, single_set=getattr(w, "single_set", 0))

@@ -39,6 +39,9 @@ typedef struct {
     int32_t n_layers;        /* layers in each of f, g, l, h (Appendix A.7 uses 1) */
     int32_t k_sweeps;        /* repetitions of the message passing (Section 2.2 step 2) */
     int32_t group_by_device; /* 1: pool per (set, device); 0: per set, as printed */
+    int32_t single_set;      /* 1: the "simple aggregator" of the paper's comparison of policy
+                                architectures (Section 3.3): no partition into parents / children /
+                                parallel nodes, every node other than v* is pooled in the first set */
 } orc_cfg;
 
 enum { ORC_OK = 0, ORC_ERR_ARG = -1, ORC_ERR_CYCLE = -2, ORC_ERR_MEM = -3 };
@@ -358,6 +361,8 @@ int orc_forward_graph(const orc_cfg *c, int32_t n, int32_t n_edges,
      * e_u = [td_u ; bu_u]; then q[i][d] = h_i(P[i][d]), also for empty groups. */
     rc = classes_from_adj(&a, cur, cls);
     if (rc) goto done;
+    if (c->single_set)
+        for (int32_t u = 0; u < n; ++u) cls[u] = (u == cur) ? 0 : 1;
     for (int32_t u = 0; u < n; ++u) {
         if (cls[u] == 0) continue;
         int32_t i = cls[u] - 1;

@@ -27,7 +27,7 @@ class PlacetoError(RuntimeError):
 class ModelCfg(ctypes.Structure):
     _fields_ = [("D", ctypes.c_int32), ("H", ctypes.c_int32), ("n_layers", ctypes.c_int32),
                 ("k_sweeps", ctypes.c_int32), ("group_by_device", ctypes.c_int32),
-                ("weight_dtype", ctypes.c_int32)]
+                ("weight_dtype", ctypes.c_int32), ("single_set", ctypes.c_int32)]
 
 
 def library_path() -> str:
@@ -118,7 +118,7 @@ def _stream_ptr(stream):
 
 
 def weights_count(D, H, n_layers=2, k_sweeps=1, group_by_device=1, weight_dtype="fp32") -> int:
-    cfg = ModelCfg(D, H, n_layers, k_sweeps, group_by_device, PL_WEIGHTS[weight_dtype])
+    cfg = ModelCfg(D, H, n_layers, k_sweeps, group_by_device, PL_WEIGHTS[weight_dtype], 0)
     return int(load_library().pl_weights_count(ctypes.byref(cfg)))
 
 
@@ -188,9 +188,10 @@ class GraphBatch:
 class Weights:
     """pl_weights: device copy of the parameter blob."""
 
-    def __init__(self, blob, D, H, n_layers=2, k_sweeps=1, group_by_device=1, weight_dtype="fp32"):
+    def __init__(self, blob, D, H, n_layers=2, k_sweeps=1, group_by_device=1, weight_dtype="fp32",
+                 single_set=0):
         lib = load_library()
-        self.cfg = ModelCfg(D, H, n_layers, k_sweeps, group_by_device, PL_WEIGHTS[weight_dtype])
+        self.cfg = ModelCfg(D, H, n_layers, k_sweeps, group_by_device, PL_WEIGHTS[weight_dtype], int(single_set))
         blob = np.ascontiguousarray(blob, dtype=np.float32)
         self._h = ctypes.c_void_p()
         _check(lib.pl_weights_create(ctypes.byref(self.cfg),

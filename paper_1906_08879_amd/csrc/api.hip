@@ -101,6 +101,7 @@ bool cfg_ok(const pl_model_cfg *c)
     return c && c->D >= 1 && c->D <= kMaxD && c->H >= 1 && c->H <= kMaxH && c->n_layers >= 1 &&
            c->n_layers <= kMaxLayers && c->k_sweeps >= 0 && c->k_sweeps <= kMaxSweeps &&
            (c->group_by_device == 0 || c->group_by_device == 1) &&
+           (c->single_set == 0 || c->single_set == 1) &&
            (c->weight_dtype == PL_WEIGHTS_FP32 || c->weight_dtype == PL_WEIGHTS_BF16);
 }
 
@@ -113,6 +114,7 @@ size_t plan_weights(const pl_model_cfg &c, ModelView *mv)
     m.L = c.n_layers;
     m.G = c.group_by_device ? c.D : 1;
     m.F = c.D + 4;
+    m.single_set = c.single_set;
     m.Z = (2 + 3 * m.G) * c.H;
     size_t pos = 0;
     auto take = [&pos](int n_in, int n_out) {

@@ -82,6 +82,7 @@ struct MlpRef {
 
 struct ModelView {
     int32_t D, H, L, G, Z, F;
+    int32_t single_set;      // 1: every node other than v* belongs to the first node set
     const float *blob;       // fp32 (bf16-rounded values when the model stores bf16)
     LayerRef proj;
     MlpRef f[2], g[2];       // [direction]

@@ -229,9 +229,10 @@ __global__ __launch_bounds__(kThreads) void k_bw_head_sets(GraphView gv, ModelVi
 }
 
 // Section 2.2 step 3: 0 = v*, 1 = can reach v*, 2 = reachable from v*, 3 = neither.
-__device__ __forceinline__ int node_class_bw(int v, int cur, const uint8_t *reach, int n_tot)
+__device__ __forceinline__ int node_class_bw(int v, int cur, const uint8_t *reach, int n_tot, int single)
 {
     if (v == cur) return 0;
+    if (single) return 1;                  // every node other than v* is in the first set
     if (reach[static_cast<size_t>(n_tot) + v]) return 1;
     if (reach[v]) return 2;
     return 3;
@@ -282,7 +283,7 @@ __global__ __launch_bounds__(kThreads) void k_bw_pool(GraphView gv, ModelView mv
     for (int s0 = lo; s0 < hi; s0 += kPoolSub) {
         const int cnt = min(kPoolSub, hi - s0);
         if (tid < cnt) {
-            const int k = node_class_bw(s0 + tid, cur, reach, gv.n_tot);
+            const int k = node_class_bw(s0 + tid, cur, reach, gv.n_tot, mv.single_set);
             s_cls[tid] = static_cast<int8_t>(k);
             cls_out[s0 + tid] = static_cast<uint8_t>(k);
         }
@@ -774,17 +775,17 @@ __global__ __launch_bounds__(kThreads) void k_bw_agg(GraphView gv, int H,
 // of 256 nodes the number of nodes of each set; an exclusive scan over the blocks; the fill.
 // The first step also copies the gradient of e_{v*} from dz.
 __device__ __forceinline__ int node_class_of(const GraphView &gv, int v, const uint8_t *reach,
-                                             const int32_t *cur_node, int *graph)
+                                             const int32_t *cur_node, int single, int *graph)
 {
     const int b = gv.node_graph[v];
     const int n0 = gv.node_off[b], n_b = gv.node_off[b + 1] - n0;
     const int cl = cur_node[b];
     const int cur = (cl >= 0 && cl < n_b) ? n0 + cl : -1;
     *graph = b;
-    return node_class_bw(v, cur, reach, gv.n_tot);
+    return node_class_bw(v, cur, reach, gv.n_tot, single);
 }
 
-__global__ __launch_bounds__(kThreads) void k_bw_cls_count(GraphView gv, int H, int Z,
+__global__ __launch_bounds__(kThreads) void k_bw_cls_count(GraphView gv, int H, int Z, int single,
                                                            const uint8_t *__restrict__ reach,
                                                            const int32_t *__restrict__ cur_node,
                                                            const float *__restrict__ dz,
@@ -797,7 +798,7 @@ __global__ __launch_bounds__(kThreads) void k_bw_cls_count(GraphView gv, int H, 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int k = -1, b = 0;
     if (v < gv.n_tot) {
-        k = node_class_of(gv, v, reach, cur_node, &b);
+        k = node_class_of(gv, v, reach, cur_node, single, &b);
         cls[v] = static_cast<uint8_t>(k);
     }
     for (int c = 1; c <= 3; ++c) {
@@ -1272,7 +1273,8 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
     // 2. pooling
     if (dense) {
         const int n_blocks = (n + kThreads - 1) / kThreads;
-        hipLaunchKernelGGL(k_bw_cls_count, dim3(n_blocks), dim3(kThreads), 0, s, gv, H, mv.Z, ws.reach, fa.cur_node,
+        hipLaunchKernelGGL(k_bw_cls_count, dim3(n_blocks), dim3(kThreads), 0, s, gv, H, mv.Z, mv.single_set, ws.reach,
+                           fa.cur_node,
                            gw.dz, gw.cls, gw.blk_cnt, gw.demb);
         hipLaunchKernelGGL(k_bw_cls_scan, dim3(1), dim3(kThreads), 0, s, n_blocks, gw.blk_cnt, gw.counts);
         hipLaunchKernelGGL(k_bw_cls_fill, dim3(n_blocks), dim3(kThreads), 0, s, gv, gw.cls, gw.blk_cnt, gw.lists);

@@ -212,9 +212,11 @@ __global__ __launch_bounds__(kThreads) void k_reach_only(GraphView gv,
 }
 
 // Section 2.2 step 3: 0 = v*, 1 = can reach v*, 2 = reachable from v*, 3 = neither.
-__device__ __forceinline__ int node_class(int v, int cur, const uint8_t *reach, int n_tot)
+// With `single` every node other than v* counts as a member of the first set.
+__device__ __forceinline__ int node_class(int v, int cur, const uint8_t *reach, int n_tot, int single = 0)
 {
     if (v == cur) return 0;
+    if (single) return 1;
     if (reach[static_cast<size_t>(n_tot) + v]) return 1;   // bottom-up bit: ancestor of v*
     if (reach[v]) return 2;                                // top-down bit: descendant of v*
     return 3;
@@ -274,7 +276,7 @@ __global__ __launch_bounds__(kThreads) void k_pool_generic(GraphView gv, ModelVi
 
     for (int s0 = lo; s0 < hi; s0 += kSub) {
         const int cnt = min(kSub, hi - s0);
-        if (tid < cnt) s_cls[tid] = static_cast<int8_t>(node_class(s0 + tid, cur, reach, gv.n_tot));
+        if (tid < cnt) s_cls[tid] = static_cast<int8_t>(node_class(s0 + tid, cur, reach, gv.n_tot, mv.single_set));
         __syncthreads();
         if (tid < 3) {
             int m = 0;

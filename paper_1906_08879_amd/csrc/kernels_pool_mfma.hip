@@ -56,6 +56,7 @@ struct PoolParams {
     int max_slices;
     int D, G;
     float *keep;               // (KEEP) [L][n_tot, H]: the outputs of l's layers for every node of a set
+    int single;                // 1: every node other than v* belongs to the first set
 };
 
 // KEEP: the outputs of every layer of l_i are also written to HBM, by the lane that holds them,
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
             const int v = n0 + scan + tid;
             bool mine = false;
             if (scan + tid < n_b && v != cur) {
-                const int c = P.reach[static_cast<size_t>(gv.n_tot) + v] ? 0 : (P.reach[v] ? 1 : 2);
+                const int c = P.single ? 0 : (P.reach[static_cast<size_t>(gv.n_tot) + v] ? 0 : (P.reach[v] ? 1 : 2));
                 mine = (c == set);
             }
             const unsigned long long m = __ballot(mine);
@@ -391,7 +392,7 @@ void launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace 
 {
     if (gv.B == 0) return;
     PoolParams P{gv, wfrag, bias, ws.emb, ws.reach, fa.placement, fa.cur_node, ws.partial,
-                 kPoolSlices, mv.D, mv.G, keep};
+                 kPoolSlices, mv.D, mv.G, keep, mv.single_set};
     const dim3 grid(3, kPoolSlices, gv.B), block(kThreads);
 #define PL_CASE(HH, WW, LL)                                                          \
     if (mv.H == HH && WS == WW && mv.L == LL) {                                      \

@@ -13,7 +13,7 @@ def run_library(w, placement=None, cur_node=None, done=None, want_emb=True, hand
     if handles is None:
         g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
         wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device,
-                        w.weight_dtype)
+                        w.weight_dtype, getattr(w, "single_set", 0))
         if path:
             wt.set_path(path)
     else:
@@ -120,7 +120,8 @@ def run_gradient(w, actions, coeff, handles=None, path=0, accumulate_into=None, 
     dev = torch.device("cuda:0")
     if handles is None:
         g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
-        wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+        wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype,
+                        getattr(w, "single_set", 0))
         if path:
             wt.set_path(path)
     else:

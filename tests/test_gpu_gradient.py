@@ -105,6 +105,29 @@ def test_generic_kernels_on_matrix_core_shapes(name):
     assert np.abs(fast["grad"] - slow["grad"]).max() <= 1e-4 * np.abs(ref_grad).max()
 
 
+@pytest.mark.parametrize("D,H,L,k,group,wd,path", [
+    (3, 12, 2, 1, 1, "fp32", 0), (4, 32, 2, 0, 1, "fp32", 0), (4, 64, 2, 1, 1, "bf16", 0),
+    (4, 64, 2, 1, 1, "bf16", 1), (5, 128, 1, 1, 0, "fp32", 0), (4, 32, 2, 2, 1, "fp32", 0),
+])
+def test_one_set_pooling(D, H, L, k, group, wd, path):
+    """pl_model_cfg.single_set = 1 (the "simple aggregator" of Section 3.3): logits and every
+    parameter's gradient; the networks of the two unused sets get exactly zero."""
+    rng = np.random.default_rng(7 * D + H + k)
+    w = custom_workload(rng, [1, 2, 40, 1, 17, 70, 3], D, H, L, k, group, wd)
+    w.single_set = 1
+    got, ref_grad = _compare(w, f"one set D={D} H={H} L={L} k={k} g={group} {wd} path={path}", path=path)
+    slices, _ = og.layer_slices(D, H, L, group)
+    for name, (ws, bs) in slices.items():
+        if name.startswith("l_chi") or name.startswith("l_pll"):
+            assert not got["grad"][ws].any() and not got["grad"][bs].any(), name
+            assert not ref_grad[ws].any() and not ref_grad[bs].any(), name
+    # the same inputs with the three sets give other logits: the flag reached the kernels
+    w.single_set = 0
+    actions, coeff, _ = _actions_and_coeff(w, 0)
+    three = run_gradient(w, actions, coeff, path=path)
+    assert np.abs(three["logits"] - got["logits"]).max() > 1e-6
+
+
 def test_accumulation_linearity_and_rejected_states():
     rng = np.random.default_rng(5)
     w = custom_workload(rng, [30, 12, 25, 8], 4, 32)

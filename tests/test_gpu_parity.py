@@ -190,6 +190,24 @@ def test_architecture_variants_on_deep_graphs(name, k, group, layers):
     _compare(w, f"{name} k={k} group={group} layers={layers}")
 
 
+@pytest.mark.parametrize("name,k,group,path", [("nasnet", 1, 1, 0), ("nmt", 0, 1, 0), ("inception", 1, 0, 0),
+                                               ("layered200", 1, 1, 1), ("random32", 0, 1, 0)])
+def test_one_set_pooling(name, k, group, path):
+    """pl_model_cfg.single_set = 1, the "simple aggregator" of the comparison of policy
+    architectures (Section 3.3): every node other than v* pooled by the first set's networks;
+    with k = 0 on top nothing of the graph structure is read."""
+    w = make_workload(name, B=3, k_sweeps=k, group_by_device=group)
+    w.single_set = 1
+    ref = oracle.forward_workload(w, n_threads=THREADS, want_emb=False)
+    got = run_library(w, want_emb=False, path=path)
+    assert_logits_close(got["logits"], ref["logits"], f"{name} one set k={k} group={group} path={path}")
+    scale = np.abs(ref["pooled"]).max()
+    assert np.abs(got["pooled"] - ref["pooled"]).max() <= 2e-5 * scale
+    assert not got["pooled"][:, 1:].any() and np.abs(got["pooled"][:, 0]).max() > 0
+    w.single_set = 0
+    assert np.abs(run_library(w, want_emb=False, path=path)["logits"] - got["logits"]).max() > 1e-6
+
+
 def test_forward_replays_from_a_hip_graph():
     """After the first call on a batch a forward pass only launches kernels, so it can be
     captured once and replayed: three replays on new states, with eager work in between,

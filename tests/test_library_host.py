@@ -121,6 +121,9 @@ def test_null_and_shape_errors(lib):
     assert lib.pl_weights_create(ctypes.byref(cfg), blob.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
                                  10, ctypes.byref(out)) == -2
     assert b"expected" in lib.pl_last_error()
+    assert lib.pl_weights_count(ctypes.byref(pl.ModelCfg(4, 32, 2, 1, 1, 0, 1))) == \
+        lib.pl_weights_count(ctypes.byref(pl.ModelCfg(4, 32, 2, 1, 1, 0, 0))) > 0
+    assert lib.pl_weights_count(ctypes.byref(pl.ModelCfg(4, 32, 2, 1, 1, 0, 2))) == 0   # single_set is 0 or 1
     assert lib.pl_graph_batch_destroy(None) == 0 and lib.pl_weights_destroy(None) == 0
 
 

@@ -351,6 +351,7 @@ class Workload:
     cur_node: np.ndarray
     weights: np.ndarray
     seed: int = 0
+    single_set: int = 0       # 1: pooling over one set (every node other than the current one)
     node_off: np.ndarray = field(default=None, repr=False)
     edge_off: np.ndarray = field(default=None, repr=False)
 
