@@ -238,7 +238,8 @@ def main() -> int:
         assert torch.isfinite(g_grad).all(), "non-finite gradient in the timed run"
         gradient = {"ms_per_step": round(1e3 * gr_elapsed, 4), "steps": args.grad_steps,
                     "graph_steps_per_s": round(w.B / gr_elapsed, 2), "parameters": int(n_par),
-                    "stage_ms": {k: round(v[0] / v[1], 4) for k, v in gr_stages.items() if v[1]},
+                    # per step: a stage may be timed in several intervals of one call
+                    "stage_ms": {k: round(v[0] / max(1, args.grad_steps), 4) for k, v in gr_stages.items() if v[1]},
                     "what": "forward pass + reverse pass (log-probability gradient of one decision per "
                             "graph, summed over the batch)"}
         # the reverse pass's largest stage: every layer's weight gradient is a contraction over rows,
@@ -269,6 +270,11 @@ def main() -> int:
                         "sample": f"one forward of the first {n_s} graphs of '{args.workload}' "
                                   f"({int(ws.n_tot)} nodes), float64 C oracle, {dt:.2f} s wall",
                         "node_embeddings_per_s": round(ws.n_tot / dt, 1)}
+        # the same oracle on one thread, on the layered-DAG configuration (its whole batch)
+        wl = make_workload("layered200")
+        t0 = time.perf_counter()
+        oracle.forward_workload(wl, n_threads=1, want_emb=False)
+        cpu_baseline["one_thread_layered200_graph_steps_per_s"] = round(wl.B / (time.perf_counter() - t0), 2)
         # the oracles of the rows beside the headline, on bounded samples (one graph each)
         from oracle import gradient as og, simulator as osim
         w1 = make_workload(args.workload, B=1)
