@@ -77,6 +77,12 @@ def main() -> int:
     ap.add_argument("--workload", default="nasnet")
     ap.add_argument("--batch", type=int, default=None, help="override the number of graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    # architecture variants (the headline is the default of each): sweeps per direction, layers
+    # per network, pooling per (set, device) or per set, one pooled set instead of three
+    ap.add_argument("--k-sweeps", type=int, default=1)
+    ap.add_argument("--n-layers", type=int, default=2)
+    ap.add_argument("--group-by-device", type=int, default=1, choices=(0, 1))
+    ap.add_argument("--single-set", type=int, default=0, choices=(0, 1))
     ap.add_argument("--grad-steps", type=int, default=4, help="timed reverse passes (reported beside the headline)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain 1 GiB device copy five times and exit (reference for "
@@ -111,12 +117,15 @@ def main() -> int:
         return 3
     dev = torch.device("cuda:0")
 
-    w = make_workload(args.workload, B=args.batch)
+    w = make_workload(args.workload, B=args.batch, k_sweeps=args.k_sweeps, n_layers=args.n_layers,
+                      group_by_device=args.group_by_device)
+    w.single_set = args.single_set
     placement, cur, done = make_states(w, N_STATES)
     t_build = time.perf_counter()
     g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
     layout_build_ms = 1e3 * (time.perf_counter() - t_build)     # host: CSR, levels, buckets (once per batch)
-    wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+    wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype,
+                    w.single_set)
     feats = []
     for s in range(N_STATES):
         f = np.array(w.node_feats, dtype=np.float32, copy=True)
@@ -150,13 +159,14 @@ def main() -> int:
     stage_ms = {k: v[0] / v[1] for k, v in stages.items() if v[1]}
     sweep_ms, sweep_launches = stages["sweep"]
     launches_per_step = max(1, w.k_sweeps)
+    default_variant = (args.k_sweeps, args.n_layers, args.group_by_device, args.single_set) == (1, 2, 1, 0)
     avg_launch_ms = sweep_ms / max(1, sweep_launches) / launches_per_step
     alg = sweep_algorithmic_bytes(w.n_tot, w.e_tot, w.H)
     achieved = alg / (avg_launch_ms * 1e-3) / 1e9 if avg_launch_ms > 0 else 0.0
     roofline = {"kernel": "sweep (message passing, both directions)", "bound": "hbm",
                 "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 5),
-                "traffic": measured_traffic(args.workload, int(w.B)),
+                "traffic": measured_traffic(args.workload, int(w.B)) if default_variant else None,
                 "algorithmic_bytes_per_launch": alg, "avg_launch_ms": round(avg_launch_ms, 5),
                 "path_algorithmic_bytes_per_step": path_algorithmic_bytes(w.n_tot, w.e_tot, w.H),
                 "path_frac": round(path_algorithmic_bytes(w.n_tot, w.e_tot, w.H)
@@ -218,7 +228,7 @@ def main() -> int:
     # reverse pass, gradient summed over the batch; beside the headline, not in it
     n_par = pl.weights_count(w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
     gradient = None
-    if w.k_sweeps <= 1:
+    if args.grad_steps > 0:
         g_act = torch.from_numpy(np.random.default_rng(0).integers(0, w.D, w.B).astype(np.int32)).to(dev)
         g_coef = torch.from_numpy(np.random.default_rng(1).normal(0, 1, w.B).astype(np.float32)).to(dev)
         g_grad = torch.empty((n_par,), dtype=torch.float32, device=dev)
@@ -248,7 +258,7 @@ def main() -> int:
         wg_ms = gradient["stage_ms"].get("bw_wgrad")
         if wg_ms:
             n, H, L = float(w.n_tot), float(w.H), float(w.n_layers)
-            flops = 2.0 * n * H * (32.0 + (4.0 * L * H if w.k_sweeps else 0.0) + (2.0 * H + (L - 1.0) * H))
+            flops = 2.0 * n * H * (32.0 + 4.0 * L * H * w.k_sweeps + (2.0 * H + (L - 1.0) * H))
             tf = flops / (wg_ms * 1e-3) / 1e12
             gradient["roofline"] = {"kernel": "weight-gradient contractions (fp32 matrix cores) + slab sums",
                                     "bound": "mfma", "achieved": round(tf, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
@@ -259,7 +269,9 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         n_s = min(w.B, CPU_SAMPLE_GRAPHS.get(args.workload, 32))
-        ws = make_workload(args.workload, B=n_s)
+        ws = make_workload(args.workload, B=n_s, k_sweeps=args.k_sweeps, n_layers=args.n_layers,
+                           group_by_device=args.group_by_device)
+        ws.single_set = args.single_set
         threads = min(16, os.cpu_count() or 1)
         oracle.load()
         t0 = time.perf_counter()
@@ -277,7 +289,9 @@ def main() -> int:
         cpu_baseline["one_thread_layered200_graph_steps_per_s"] = round(wl.B / (time.perf_counter() - t0), 2)
         # the oracles of the rows beside the headline, on bounded samples (one graph each)
         from oracle import gradient as og, simulator as osim
-        w1 = make_workload(args.workload, B=1)
+        w1 = make_workload(args.workload, B=1, k_sweeps=args.k_sweeps, n_layers=args.n_layers,
+                           group_by_device=args.group_by_device)
+        w1.single_set = args.single_set
         t0 = time.perf_counter()
         osim.simulate(int(w1.n_nodes[0]), w1.edge_src, w1.edge_dst, w1.node_feats[:, 0], w1.node_feats[:, 1],
                       w1.placement, w1.D, np.float32(inv_bw))
@@ -297,7 +311,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": args.workload, "B": int(w.B), "N_tot": int(w.n_tot),
                    "E_tot": int(w.e_tot), "D": w.D, "H": w.H, "n_layers": w.n_layers,
-                   "k_sweeps": w.k_sweeps, "max_depth": int(g.max_depth),
+                   "k_sweeps": w.k_sweeps, "group_by_device": w.group_by_device,
+                   "single_set": w.single_set, "max_depth": int(g.max_depth),
                    "weight_dtype": w.weight_dtype, "states": N_STATES},
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
         "layout_build_ms": round(layout_build_ms, 2),

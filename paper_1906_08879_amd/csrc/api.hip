@@ -422,7 +422,8 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
     }
     {
         StageScope scope(g->timer, PL_STAGE_SWEEP, s);
-        if (w->cfg.k_sweeps == 0) launch_reach_only(gv, cur_node, g->ws.reach, s);
+        // without sweeps the node sets still need reachability from v*, unless there is one set
+        if (w->cfg.k_sweeps == 0 && !w->cfg.single_set) launch_reach_only(gv, cur_node, g->ws.reach, s);
         for (int k = 0; k < w->cfg.k_sweeps; ++k) {
             if (mfma)
                 launch_sweep_mfma(gv, mv, g->ws, fa, reinterpret_cast<const uint4 *>(w->d_wfrag),

@@ -608,6 +608,61 @@ __global__ __launch_bounds__(kThreads) void k_bw_proj(GraphView gv, ModelView mv
     }
 }
 
+// The same with four columns per thread, for H a multiple of four (vector loads and stores; the
+// per-node values are read once per four columns).  The sum takes its terms in the order of
+// k_bw_proj, which is the forward pass's.
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4p;
+__global__ __launch_bounds__(kThreads) void k_bw_proj4(GraphView gv, ModelView mv,
+                                                       const float *__restrict__ feats,
+                                                       const int32_t *__restrict__ placement,
+                                                       const int32_t *__restrict__ cur_node,
+                                                       const float *__restrict__ demb,
+                                                       float *__restrict__ dx,
+                                                       float *__restrict__ phi, int phi_ld)
+{
+    const int H = mv.H, D = mv.D, q = H / 4;
+    const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (idx >= static_cast<size_t>(gv.n_tot) * q) return;
+    const int v = static_cast<int>(idx / q), h = 4 * static_cast<int>(idx - static_cast<size_t>(v) * q);
+    const int b = gv.node_graph[v];
+    const float *W = mv.blob + mv.proj.w;
+    auto row = [&](int r) { return *reinterpret_cast<const f32x4p *>(W + static_cast<size_t>(r) * H + h); };
+    const float f_time = feats[v * 3 + 0], f_size = feats[v * 3 + 1], f_vis = feats[v * 3 + 2];
+    const int dev = placement[v];
+    const bool on_dev = dev >= 0 && dev < D;
+    const bool is_cur = v - gv.node_off[b] == cur_node[b];
+    const f32x4p bias = *reinterpret_cast<const f32x4p *>(mv.blob + mv.proj.b + h);
+    const f32x4p w0 = row(0), w1 = row(1), wd = row(2 + (on_dev ? dev : 0)), wc = row(2 + D), wv = row(3 + D);
+    const float *de = demb + static_cast<size_t>(v) * 2 * H + h;
+    const f32x4p g0 = *reinterpret_cast<const f32x4p *>(de), g1 = *reinterpret_cast<const f32x4p *>(de + H);
+    f32x4p out;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float s = bias[k];
+        s = fmaf(f_time, w0[k], s);
+        s = fmaf(f_size, w1[k], s);
+        if (on_dev) s += wd[k];
+        if (is_cur) s += wc[k];
+        s = fmaf(f_vis, wv[k], s);
+        out[k] = s > 0.0f ? g0[k] + g1[k] : 0.0f;
+    }
+    *reinterpret_cast<f32x4p *>(dx + static_cast<size_t>(v) * H + h) = out;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int c = h + k;
+        if (c < phi_ld) {                   // phi_ld >= F: columns past F are zero
+            float p;
+            if (c == 0) p = f_time;
+            else if (c == 1) p = f_size;
+            else if (c < 2 + D) p = (dev == c - 2) ? 1.0f : 0.0f;
+            else if (c == 2 + D) p = is_cur ? 1.0f : 0.0f;
+            else if (c == 3 + D) p = f_vis;
+            else p = 0.0f;
+            phi[static_cast<size_t>(v) * phi_ld + c] = p;
+        }
+    }
+}
+
 // phi rows when H < F (more raw features than embedding columns): one thread per (node, feature).
 __global__ __launch_bounds__(kThreads) void k_bw_phi(GraphView gv, ModelView mv,
                                                      const float *__restrict__ feats,
@@ -1410,9 +1465,14 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
     mark(PL_STAGE_BW_PROJ, true);
     {
         const size_t total = NH;
-        hipLaunchKernelGGL(k_bw_proj, dim3(static_cast<unsigned>((total + kThreads - 1) / kThreads)),
-                           dim3(kThreads), 0, s, gv, mv, fa.node_feats, fa.placement, fa.cur_node, gw.demb,
-                           gw.dx, gw.phi, dense ? 32 : mv.F);
+        if (H % 4 == 0)
+            hipLaunchKernelGGL(k_bw_proj4, dim3(static_cast<unsigned>((total / 4 + kThreads - 1) / kThreads)),
+                               dim3(kThreads), 0, s, gv, mv, fa.node_feats, fa.placement, fa.cur_node, gw.demb,
+                               gw.dx, gw.phi, dense ? 32 : mv.F);
+        else
+            hipLaunchKernelGGL(k_bw_proj, dim3(static_cast<unsigned>((total + kThreads - 1) / kThreads)),
+                               dim3(kThreads), 0, s, gv, mv, fa.node_feats, fa.placement, fa.cur_node, gw.demb,
+                               gw.dx, gw.phi, dense ? 32 : mv.F);
         if (H < mv.F) {
             const size_t tf = static_cast<size_t>(n) * mv.F;
             hipLaunchKernelGGL(k_bw_phi, dim3(static_cast<unsigned>((tf + kThreads - 1) / kThreads)),

@@ -130,6 +130,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     constexpr int PFN = (FCAP * QW + 63) / 64; // staged far float4 per lane
     constexpr int NACC = KS > 1 ? 2 : 1;       // independent accumulation chains per tile
     constexpr int kZeroSlot = kMsgSlots;
+    constexpr int kWarmAhead = 12;             // chunks between touching a chunk record and reading it
     static_assert(NTL % NW == 0, "column tiles must divide over the waves");
 
     // Message table: H floats per row.  Messages are ReLU outputs, so their sign bit is free:
@@ -481,6 +482,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         int pf_reach[PFN];
         bool pf_cur[PFN];
         int4 m2 = m1;
+        int warm = 0;            // see the prefetch of the chunk records below
         // Accumulators: a chunk of one row tile splits its k-steps over two chains per column
         // tile (acc[chain][t]); a chunk of two row tiles runs one chain per (row tile, column
         // tile) (acc[ct][t]): four independent chains either way.
@@ -627,6 +629,16 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     pf_reach[i] = BW ? 0 : reach[static_cast<uint32_t>(u)];   // combined with pf_cur at the end of the chunk
                     pf_cur[i] = wanted && u == cur;
                 }
+                // The chunk records come in through the scalar cache, and a scalar load cannot be
+                // overlapped with LDS work: every wait for LDS data also waits for the scalar loads
+                // in flight.  So a vector load touches the record of a chunk some way ahead (its
+                // value is not used): the scalar load of that record then finds its line in L2
+                // instead of going to HBM every fourth chunk.
+                {
+                    int opaque = 0;
+                    asm volatile("" : "+v"(opaque));
+                    warm = reinterpret_cast<const int *>(plan.meta + clampc(c + kWarmAhead))[opaque];
+                }
                 if constexpr (FF) {
 #pragma unroll
                     for (int ct = 0; ct < NT; ++ct)
@@ -681,6 +693,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 // that preceded it are then complete too (see the note at the prefetch).
 #pragma unroll
                 for (int i = 0; i < PFN; ++i) asm volatile("" ::"v"(pf[i][0]), "v"(pf_reach[i]), "v"(fid1[i]));
+                asm volatile("" ::"v"(warm));
                 // ... and for the rest of the batch, which the next chunk then uses without waiting
 #pragma unroll
                 for (int ct = 0; ct < NT; ++ct) {
