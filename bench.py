@@ -20,7 +20,6 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 N_STATES = 8
 CPU_SAMPLE_GRAPHS = {"random32": 1, "layered200": 64, "inception": 128, "nmt": 64, "nasnet": 256}
@@ -253,17 +252,27 @@ def main() -> int:
                     "what": "forward pass + reverse pass (log-probability gradient of one decision per "
                             "graph, summed over the batch)"}
         # the reverse pass's largest stage: every layer's weight gradient is a contraction over rows,
-        # 2 R I J flops each: projection (32 padded columns), 2 directions x (f, g) x L layers of H x H,
-        # l (2H x H, then H x H) over the nodes of the three sets (all nodes but the current ones)
+        # 2 R I J flops each, that reads its two operands (R x I inputs, R x J deltas, fp32) once:
+        # projection (F inputs), 2 directions x (f, g) x L layers of H x H per sweep, l (2H x H, then
+        # H x H) over the nodes of the three sets (all nodes but the current ones).  With each operand
+        # split into three bf16 parts and six products kept, the matrix cores have 6 x those flops to
+        # do at the bf16 rate (less time than the operands take to arrive): the stage is priced
+        # against HBM.
         wg_ms = gradient["stage_ms"].get("bw_wgrad")
         if wg_ms:
-            n, H, L = float(w.n_tot), float(w.H), float(w.n_layers)
-            flops = 2.0 * n * H * (32.0 + 4.0 * L * H * w.k_sweeps + (2.0 * H + (L - 1.0) * H))
-            tf = flops / (wg_ms * 1e-3) / 1e12
-            gradient["roofline"] = {"kernel": "weight-gradient contractions (fp32 matrix cores) + slab sums",
-                                    "bound": "mfma", "achieved": round(tf, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
-                                    "unit": "TFLOP/s", "frac": round(tf / FP32_MFMA_PEAK_TFLOPS, 4),
-                                    "flops_per_step": int(flops), "traffic": None}
+            n, H, L, F = float(w.n_tot), float(w.H), float(w.n_layers), float(w.D + 4)
+            n_set = n - w.B
+            flops = 2.0 * H * (n * F + n * 4.0 * L * H * w.k_sweeps + n_set * (2.0 * H + (L - 1.0) * H))
+            alg = 4.0 * (n * (F + H) + n * 4.0 * L * 2.0 * H * w.k_sweeps
+                         + n_set * (3.0 * H + (L - 1.0) * 2.0 * H))
+            gbs = alg / (wg_ms * 1e-3) / 1e9
+            gradient["roofline"] = {"kernel": "weight-gradient contractions (bf16 matrix cores, operands split "
+                                              "in three parts) + slab sums",
+                                    "bound": "hbm", "achieved": round(gbs, 2), "peak": HBM_PEAK_GBS,
+                                    "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                                    "algorithmic_bytes_per_step": int(alg), "flops_per_step": int(flops),
+                                    "matrix_core_tflops": round(6.0 * flops / (wg_ms * 1e-3) / 1e12, 1),
+                                    "traffic": None}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:

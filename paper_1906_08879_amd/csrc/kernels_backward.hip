@@ -1149,6 +1149,204 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict
     }
 }
 
+// The same contraction on the bf16 matrix cores at fp32 accuracy.  Every fp32 operand is split
+// exactly into three bf16 parts by truncation (x = hi + mid + lo, 8 + 8 + 8 mantissa bits) and six
+// of the nine products of parts are accumulated in fp32: hi hi, hi mid, mid hi, hi lo, lo hi,
+// mid mid; the three left out are below 2^-24 of the product.  On v_mfma_f32_32x32x16_bf16 that
+// is 2.7 times the rate of the fp32 instruction.
+// A chunk is 32 contraction rows.  LDS holds the parts fragment-major: a 16-byte cell is the eight
+// bf16 of one column for eight consecutive rows and the cells of consecutive columns are
+// adjacent, so a fragment (lane = column, eight rows) is one conflict-free ds_read_b128.  A
+// thread stages whole cells: eight rows of one column (the lanes of a wave on consecutive
+// columns, 256-byte row segments), split in registers, three 16-byte stores.  The rows of chunk
+// c + 1 are in flight in registers while chunk c is multiplied; the ids of a row list are staged
+// in LDS one chunk further ahead.  Column sums of Dl (the bias gradient) are taken in fp32 from
+// the staged values, by the thread that stages the column.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8w;
+
+constexpr size_t wgrad_split_lds_bytes(int NJ)
+{
+    return static_cast<size_t>(16) * 3 * 4 * (128 + 32 * NJ) + sizeof(int32_t) * 2 * kWgRC + sizeof(float) * kThreads;
+}
+
+template <int NJ>
+__global__ __launch_bounds__(kThreads) void k_wgrad_split(const float *__restrict__ A, int lda,
+                                                          const float *__restrict__ Dl, int ldd,
+                                                          const int32_t *__restrict__ rows,
+                                                          const int32_t *__restrict__ n_rows_dev,
+                                                          int R, int I, int rows_per_slab,
+                                                          float *__restrict__ partial)
+{
+    constexpr int J = 32 * NJ;
+    constexpr int NDC = (4 * J + kThreads - 1) / kThreads;     // Dl cells per thread: 2, 1, 1
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    uint4 *cell_a = reinterpret_cast<uint4 *>(lds_raw);                       // [3 parts][4 row groups][128 columns]
+    uint4 *cell_d = cell_a + 3 * 4 * 128;                                      // [3 parts][4 row groups][J columns]
+    int32_t *tab = reinterpret_cast<int32_t *>(cell_d + 3 * 4 * J);           // [2][32] row ids of a chunk
+    float *bsh = reinterpret_cast<float *>(tab + 2 * kWgRC);                  // [256] column sums at the end
+    if (n_rows_dev) R = min(R, *n_rows_dev);               // slabs past the list's end write zeros
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lk = lane >> 5;
+    const int iw = blockIdx.x * 128, sl = blockIdx.y;
+    const bool wave_on = iw + 32 * wave < I;
+    const int r_beg = min(R, sl * rows_per_slab), r_end = min(R, r_beg + rows_per_slab);
+    const int n_chunks = (r_end - r_beg + kWgRC - 1) / kWgRC;
+
+    // this thread's cells: A column ca, row groups ga and ga + 2; Dl column cd, row groups of cell tid + 256 q
+    const int ca = tid & 127, ga = tid >> 7;
+    const bool a_col_ok = iw + ca < I;
+    const int cd = tid % J;
+    float av[2][8], dv[NDC][8];       // the values of the chunk in flight, unmasked
+    uint32_t amask = 0, dmask = 0;    // bit 8 q + k: value [q][k] belongs to the slab
+    // ids of rows 8 grp .. 8 grp + 7 of the chunk at r0: from the staged list, or the row numbers
+    // themselves; -1 past the slab's end.  Straight-line code: the loads that follow are all
+    // issued before the first of them is used.
+    auto row_ids = [&](int r0, int slot, int grp, int (&ids)[8]) {
+        const int4 t0 = *reinterpret_cast<const int4 *>(tab + slot * kWgRC + 8 * grp);
+        const int4 t1 = *reinterpret_cast<const int4 *>(tab + slot * kWgRC + 8 * grp + 4);
+        const int listed[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int r = r0 + 8 * grp + k;
+            ids[k] = rows ? listed[k] : (r < r_end ? r : -1);
+        }
+    };
+    auto fetch = [&](int r0, int slot) {
+        int ida[2][8], idd[NDC][8];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) row_ids(r0, slot, ga + 2 * q, ida[q]);
+#pragma unroll
+        for (int q = 0; q < NDC; ++q) {
+            const int cell = tid + kThreads * q;
+            row_ids(r0, slot, cell < 4 * J ? cell / J : 0, idd[q]);
+        }
+        const int col_a = a_col_ok ? iw + ca : 0;
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int k = 0; k < 8; ++k)    // (the launcher checks that 32-bit element offsets suffice)
+                av[q][k] = A[static_cast<uint32_t>(max(ida[q][k], 0)) * static_cast<uint32_t>(lda) + static_cast<uint32_t>(col_a)];
+#pragma unroll
+        for (int q = 0; q < NDC; ++q)
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                dv[q][k] = Dl[static_cast<uint32_t>(max(idd[q][k], 0)) * static_cast<uint32_t>(ldd) + static_cast<uint32_t>(cd)];
+        // which of them count: one bit per value
+        amask = 0;
+        dmask = 0;
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) amask |= (ida[q][k] >= 0 && a_col_ok) ? 1u << (8 * q + k) : 0u;
+#pragma unroll
+        for (int q = 0; q < NDC; ++q)
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                dmask |= (idd[q][k] >= 0 && tid + kThreads * q < 4 * J) ? 1u << (8 * q + k) : 0u;
+    };
+    // the three bf16 parts of eight values, eight to a 16-byte cell
+    auto put_cells = [&](uint4 *cells, int C, int grp, int c, const float (&v)[8], uint32_t ok) {
+        uint32_t h[4], m[4], l[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float x0 = (ok >> (2 * k)) & 1u ? v[2 * k] : 0.0f, x1 = (ok >> (2 * k + 1)) & 1u ? v[2 * k + 1] : 0.0f;
+            const float r0 = x0 - __uint_as_float(__float_as_uint(x0) & 0xFFFF0000u);
+            const float r1 = x1 - __uint_as_float(__float_as_uint(x1) & 0xFFFF0000u);
+            const float l0 = r0 - __uint_as_float(__float_as_uint(r0) & 0xFFFF0000u);
+            const float l1 = r1 - __uint_as_float(__float_as_uint(r1) & 0xFFFF0000u);
+            h[k] = (__float_as_uint(x0) >> 16) | (__float_as_uint(x1) & 0xFFFF0000u);
+            m[k] = (__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xFFFF0000u);
+            l[k] = (__float_as_uint(l0) >> 16) | (__float_as_uint(l1) & 0xFFFF0000u);
+        }
+        cells[(0 * 4 + grp) * C + c] = uint4{h[0], h[1], h[2], h[3]};
+        cells[(1 * 4 + grp) * C + c] = uint4{m[0], m[1], m[2], m[3]};
+        cells[(2 * 4 + grp) * C + c] = uint4{l[0], l[1], l[2], l[3]};
+    };
+    float bsum = 0.0f;
+    auto stash = [&]() {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) put_cells(cell_a, 128, ga + 2 * q, ca, av[q], amask >> (8 * q));
+#pragma unroll
+        for (int q = 0; q < NDC; ++q) {
+            const int cell = tid + kThreads * q;
+            if (cell < 4 * J) {
+                put_cells(cell_d, J, cell / J, cd, dv[q], dmask >> (8 * q));
+#pragma unroll
+                for (int k = 0; k < 8; ++k) bsum += (dmask >> (8 * q + k)) & 1u ? dv[q][k] : 0.0f;
+            }
+        }
+    };
+    auto list_id = [&](int r0) {                           // thread k < 32: id of row k of the chunk at r0
+        return (rows && tid < kWgRC && r0 + tid < r_end) ? rows[r0 + tid] : -1;
+    };
+
+    f32x16 acc[NJ];
+#pragma unroll
+    for (int jb = 0; jb < NJ; ++jb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[jb][v] = 0.0f;
+
+    if (tid < kWgRC) {
+        tab[tid] = list_id(r_beg);
+        tab[kWgRC + tid] = list_id(r_beg + kWgRC);
+    }
+    __syncthreads();
+    if (n_chunks > 0) fetch(r_beg, 0);
+    for (int c = 0; c < n_chunks; ++c) {
+        const int next_id = list_id(r_beg + (c + 2) * kWgRC);      // in flight until the end of the iteration
+        stash();                                                   // chunk c: registers -> cells
+        __syncthreads();
+        if (c + 1 < n_chunks) fetch(r_beg + (c + 1) * kWgRC, (c + 1) & 1);
+        if (wave_on) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const int grp = 2 * ks + lk;
+                bf16x8w a[3];
+#pragma unroll
+                for (int p = 0; p < 3; ++p)
+                    a[p] = *reinterpret_cast<const bf16x8w *>(&cell_a[(p * 4 + grp) * 128 + 32 * wave + li]);
+                // two column tiles at a time, so that consecutive matrix instructions do not
+                // wait for each other's accumulator
+                constexpr int JP = NJ > 1 ? 2 : 1;
+                constexpr int pa[6] = {2, 0, 1, 1, 0, 0}, pb[6] = {0, 2, 1, 0, 1, 0};   // small products first
+#pragma unroll
+                for (int j0 = 0; j0 < NJ; j0 += JP) {
+                    bf16x8w b[JP][3];
+#pragma unroll
+                    for (int u = 0; u < JP; ++u)
+#pragma unroll
+                        for (int p = 0; p < 3; ++p)
+                            b[u][p] = *reinterpret_cast<const bf16x8w *>(&cell_d[(p * 4 + grp) * J + 32 * (j0 + u) + li]);
+#pragma unroll
+                    for (int t = 0; t < 6; ++t)
+#pragma unroll
+                        for (int u = 0; u < JP; ++u)
+                            acc[j0 + u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[pa[t]], b[u][pb[t]], acc[j0 + u], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();
+        if (tid < kWgRC) tab[(c & 1) * kWgRC + tid] = next_id;     // chunk c + 2; this half was last read for chunk c
+    }
+    // column sums of Dl: the threads that staged column j are tid = j, j + J, ...
+    bsh[tid] = bsum;
+    __syncthreads();
+    float *dst = partial + static_cast<size_t>(sl) * (static_cast<size_t>(I) * J + J);
+    if (blockIdx.x == 0 && tid < J) {
+        float t = bsh[tid];
+        for (int k = tid + J; k < kThreads && k < 4 * J; k += J) t += bsh[k];
+        dst[static_cast<size_t>(I) * J + tid] = t;
+    }
+    if (!wave_on) return;
+#pragma unroll
+    for (int jb = 0; jb < NJ; ++jb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = iw + 32 * wave + 8 * (v / 4) + 4 * lk + (v % 4);
+            dst[static_cast<size_t>(i) * J + 32 * jb + li] = acc[jb][v];
+        }
+}
+
 // out[idx] += sum over slabs.  A workgroup takes 32 consecutive entries; its eight thread rows
 // each add the slabs q, q + 8, ... in order, and the eight sums are added in order: a fixed
 // summation order with enough loads in flight.
@@ -1251,10 +1449,18 @@ void launch_wgrad(const float *A, int lda, const float *Dl, int ldd, const uint8
     if (cores) {
         // with a row list (the nodes of one set, ascending) the class filter is not needed
         const dim3 grid((I + 127) / 128, slabs);
-#define CALL(NJ)                                                                                           \
-    allow_lds_bw(k_wgrad_mfma<NJ>, wgrad_lds_bytes(NJ));                                                   \
-    hipLaunchKernelGGL(k_wgrad_mfma<NJ>, grid, dim3(kThreads), wgrad_lds_bytes(NJ), s, A, lda, Dl, ldd, list, \
-                       list_count, static_cast<int>(R), I, per, partial)
+        // the bf16-split kernel addresses its operands with 32-bit element offsets
+        const bool small = static_cast<double>(R) * std::max(lda, ldd) < 4.0e9;
+#define CALL(NJ)                                                                                                  \
+    if (small) {                                                                                                  \
+        allow_lds_bw(k_wgrad_split<NJ>, wgrad_split_lds_bytes(NJ));                                               \
+        hipLaunchKernelGGL(k_wgrad_split<NJ>, grid, dim3(kThreads), wgrad_split_lds_bytes(NJ), s, A, lda, Dl, ldd, \
+                           list, list_count, static_cast<int>(R), I, per, partial);                               \
+    } else {                                                                                                      \
+        allow_lds_bw(k_wgrad_mfma<NJ>, wgrad_lds_bytes(NJ));                                                      \
+        hipLaunchKernelGGL(k_wgrad_mfma<NJ>, grid, dim3(kThreads), wgrad_lds_bytes(NJ), s, A, lda, Dl, ldd, list,  \
+                           list_count, static_cast<int>(R), I, per, partial);                                     \
+    }
         if (J == 32) { CALL(1); } else if (J == 64) { CALL(2); } else { CALL(4); }
 #undef CALL
     } else {
