@@ -1170,7 +1170,7 @@ constexpr size_t wgrad_split_lds_bytes(int NJ)
 }
 
 template <int NJ>
-__global__ __launch_bounds__(kThreads) void k_wgrad_split(const float *__restrict__ A, int lda,
+__global__ __launch_bounds__(kThreads, 3) void k_wgrad_split(const float *__restrict__ A, int lda,
                                                           const float *__restrict__ Dl, int ldd,
                                                           const int32_t *__restrict__ rows,
                                                           const int32_t *__restrict__ n_rows_dev,
@@ -1244,37 +1244,104 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_split(const float *__restric
             for (int k = 0; k < 8; ++k)
                 dmask |= (idd[q][k] >= 0 && tid + kThreads * q < 4 * J) ? 1u << (8 * q + k) : 0u;
     };
-    // the three bf16 parts of eight values, eight to a 16-byte cell
-    auto put_cells = [&](uint4 *cells, int C, int grp, int c, const float (&v)[8], uint32_t ok) {
+    // the three bf16 parts of eight values, eight to a 16-byte cell (masked: the values whose bit
+    // of ok is clear count as zero)
+    auto put_cells = [&](auto masked, uint4 *cells, int C, int grp, int c, const float (&v)[8], uint32_t ok) {
         uint32_t h[4], m[4], l[4];
+        auto top = [](float x) { return __uint_as_float(__float_as_uint(x) & 0xFFFF0000u); };
+        auto pack = [](float lo, float hi) {       // the upper halves of two floats in one word
+            return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+        };
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const float x0 = (ok >> (2 * k)) & 1u ? v[2 * k] : 0.0f, x1 = (ok >> (2 * k + 1)) & 1u ? v[2 * k + 1] : 0.0f;
-            const float r0 = x0 - __uint_as_float(__float_as_uint(x0) & 0xFFFF0000u);
-            const float r1 = x1 - __uint_as_float(__float_as_uint(x1) & 0xFFFF0000u);
-            const float l0 = r0 - __uint_as_float(__float_as_uint(r0) & 0xFFFF0000u);
-            const float l1 = r1 - __uint_as_float(__float_as_uint(r1) & 0xFFFF0000u);
-            h[k] = (__float_as_uint(x0) >> 16) | (__float_as_uint(x1) & 0xFFFF0000u);
-            m[k] = (__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xFFFF0000u);
-            l[k] = (__float_as_uint(l0) >> 16) | (__float_as_uint(l1) & 0xFFFF0000u);
+            float x0 = v[2 * k], x1 = v[2 * k + 1];
+            if constexpr (decltype(masked)::value) {
+                x0 = (ok >> (2 * k)) & 1u ? x0 : 0.0f;
+                x1 = (ok >> (2 * k + 1)) & 1u ? x1 : 0.0f;
+            }
+            const float r0 = x0 - top(x0), r1 = x1 - top(x1);
+            const float l0 = r0 - top(r0), l1 = r1 - top(r1);
+            h[k] = pack(x0, x1);
+            m[k] = pack(r0, r1);
+            l[k] = pack(l0, l1);
         }
         cells[(0 * 4 + grp) * C + c] = uint4{h[0], h[1], h[2], h[3]};
         cells[(1 * 4 + grp) * C + c] = uint4{m[0], m[1], m[2], m[3]};
         cells[(2 * 4 + grp) * C + c] = uint4{l[0], l[1], l[2], l[3]};
     };
     float bsum = 0.0f;
+    bool whole = false;               // the chunk in flight came in with fetch_whole(): nothing to mask
     auto stash = [&]() {
+        if (whole) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) put_cells(cell_a, 128, ga + 2 * q, ca, av[q], amask >> (8 * q));
+            for (int q = 0; q < 2; ++q) put_cells(std::false_type{}, cell_a, 128, ga + 2 * q, ca, av[q], 0u);
+#pragma unroll
+            for (int q = 0; q < NDC; ++q) {
+                put_cells(std::false_type{}, cell_d, J, (tid + kThreads * q) / J, cd, dv[q], 0u);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) bsum += dv[q][k];
+            }
+            return;
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) put_cells(std::true_type{}, cell_a, 128, ga + 2 * q, ca, av[q], amask >> (8 * q));
 #pragma unroll
         for (int q = 0; q < NDC; ++q) {
             const int cell = tid + kThreads * q;
             if (cell < 4 * J) {
-                put_cells(cell_d, J, cell / J, cd, dv[q], dmask >> (8 * q));
+                put_cells(std::true_type{}, cell_d, J, cell / J, cd, dv[q], dmask >> (8 * q));
 #pragma unroll
                 for (int k = 0; k < 8; ++k) bsum += (dmask >> (8 * q + k)) & 1u ? dv[q][k] : 0.0f;
             }
         }
+    };
+    // A chunk that lies wholly inside the slab, for J >= 64: the row group of each of a thread's
+    // cells is the same over its wave, so row ids and row addresses are scalars and a load costs no
+    // vector arithmetic; nothing is masked (columns past I load column 0 and are zeroed here).
+    auto fetch_whole = [&](auto listed, int r0, int slot) {
+        constexpr bool kListed = decltype(listed)::value;
+        // ids of the eight rows of a group, as scalars (all reads of the list first, then the loads)
+        auto group_ids = [&](int grp, int (&ids)[8]) {
+            if constexpr (kListed) {
+                const int4 t0 = *reinterpret_cast<const int4 *>(tab + slot * kWgRC + 8 * grp);
+                const int4 t1 = *reinterpret_cast<const int4 *>(tab + slot * kWgRC + 8 * grp + 4);
+                const int v[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+#pragma unroll
+                for (int k = 0; k < 8; ++k) ids[k] = __builtin_amdgcn_readfirstlane(v[k]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) ids[k] = r0 + 8 * grp + k;
+            }
+        };
+        int ida[2][8], idd[NDC][8];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) group_ids(__builtin_amdgcn_readfirstlane(ga + 2 * q), ida[q]);
+#pragma unroll
+        for (int q = 0; q < NDC; ++q) group_ids(__builtin_amdgcn_readfirstlane((tid + kThreads * q) / J), idd[q]);
+        const uint32_t col_a = a_col_ok ? iw + ca : 0;
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) av[q][k] = (A + static_cast<size_t>(ida[q][k]) * lda)[col_a];
+#pragma unroll
+        for (int q = 0; q < NDC; ++q)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) dv[q][k] = (Dl + static_cast<size_t>(idd[q][k]) * ldd)[static_cast<uint32_t>(cd)];
+        if (!a_col_ok) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int k = 0; k < 8; ++k) av[q][k] = 0.0f;
+        }
+    };
+    auto fetch_chunk = [&](int r0, int slot) {
+        whole = J >= 64 && r0 + kWgRC <= r_end;
+        if (!whole)
+            fetch(r0, slot);
+        else if (rows)
+            fetch_whole(std::true_type{}, r0, slot);
+        else
+            fetch_whole(std::false_type{}, r0, slot);
     };
     auto list_id = [&](int r0) {                           // thread k < 32: id of row k of the chunk at r0
         return (rows && tid < kWgRC && r0 + tid < r_end) ? rows[r0 + tid] : -1;
@@ -1291,12 +1358,12 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_split(const float *__restric
         tab[kWgRC + tid] = list_id(r_beg + kWgRC);
     }
     __syncthreads();
-    if (n_chunks > 0) fetch(r_beg, 0);
+    if (n_chunks > 0) fetch_chunk(r_beg, 0);
     for (int c = 0; c < n_chunks; ++c) {
         const int next_id = list_id(r_beg + (c + 2) * kWgRC);      // in flight until the end of the iteration
         stash();                                                   // chunk c: registers -> cells
         __syncthreads();
-        if (c + 1 < n_chunks) fetch(r_beg + (c + 1) * kWgRC, (c + 1) & 1);
+        if (c + 1 < n_chunks) fetch_chunk(r_beg + (c + 1) * kWgRC, (c + 1) & 1);
         if (wave_on) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
@@ -1404,7 +1471,8 @@ void allow_lds_bw(K kernel, size_t bytes)
         default: { CALL(16); break; } \
     }
 
-// the matrix-core contraction wants about four workgroups per CU
+// about two slabs per CU (768, one for each of the three workgroups a CU holds, was slower: the
+// slab sums grow with the slab count)
 int wgrad_rows_per_slab_cores(int64_t R)
 {
     int64_t per = (R + 511) / 512;
