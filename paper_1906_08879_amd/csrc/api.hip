@@ -338,7 +338,8 @@ int ensure_grad_workspace(pl_graph_batch *g, const ModelView &mv)
     PL_HIP(take(&gw.hid, B * H));
     PL_HIP(take(&gw.dpre, B * H));
     PL_HIP(take(&gw.dlogit, B * mv.D));
-    size_t part = wgrad_partial_floats(static_cast<int64_t>(n), 2 * mv.H, mv.H);
+    // (three times: the gradients of l's layers are taken for the three node sets in one launch)
+    size_t part = 3 * wgrad_partial_floats(static_cast<int64_t>(n), 2 * mv.H, mv.H);
     part = std::max(part, wgrad_partial_floats(static_cast<int64_t>(n), 32, mv.H));
     part = std::max(part, wgrad_partial_floats(static_cast<int64_t>(BG), mv.H, mv.H));
     part = std::max(part, wgrad_partial_floats(static_cast<int64_t>(B), mv.Z, mv.H));

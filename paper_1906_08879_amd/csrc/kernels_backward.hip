@@ -686,79 +686,94 @@ __global__ __launch_bounds__(kThreads) void k_bw_phi(GraphView gv, ModelView mv,
 }
 
 // ------------------------------------------------------------------ dense layers on the matrix cores
-// Y[row][j] = epi(bias[j] + sum_k X[row][k] W[k][j]) for a list of rows, H in {32, 64, 128} output
-// columns (NJ tiles of 32) and K a multiple of 32, in fp32 on v_mfma_f32_32x32x2_f32.
-// A workgroup of four waves takes 128 rows; wave w multiplies rows 32 w .. 32 w + 31 by all
-// columns.  X and W go through LDS in chunks of 32 k, double buffered: the global loads of chunk
-// c + 1 (128-byte row pieces of X, whole rows of W: all coalesced) are issued before the 64
-// matrix instructions of chunk c and written to the other buffer after them; one barrier per
-// chunk.  Lane (row l % 32, half l / 32) of an instruction takes k = 2 s + half: the A operand
-// X[row][k] is read with row stride 33 and the B operand W[k][32 jb + l % 32] with row stride
-// H + 32, which keeps the two halves of a wave on different LDS banks.
+// Y[row][j] = epi(bias[j] + sum_k X[row][k] Wt[j][k]) for a list of rows, H in {32, 64, 128} output
+// columns (NJ tiles of 32) and K a multiple of 32.  A workgroup of four waves takes 128 rows; wave
+// w multiplies rows 32 w .. 32 w + 31 by all columns; X and Wt go through LDS in chunks of 32 k.
 // epi: optional ReLU, optional gate (Y = 0 where M[row][j] <= 0).  rows / n_rows_dev: optional row
 // list and its length in device memory (the grid covers R rows; workgroups past the length exit).
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8w;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4v;
 
 constexpr int kDenseKC = 32;                  // k per chunk
 constexpr int kDenseRows = 128;               // rows per workgroup
-constexpr int kDenseLdx = kDenseKC + 1;       // LDS row stride of the X chunk
 
-constexpr size_t dense_lds_bytes(int NJ)
-{
-    return sizeof(float) * 2 * (kDenseRows * kDenseLdx + kDenseKC * (32 * NJ + 32));
-}
+// On the bf16 matrix cores at fp32 accuracy (operands split into three bf16 parts, six products
+// kept: see k_wgrad_split).  The weights come in the transposed layout
+// Wt[j][k] (row j holds the K inputs of output column j), so that both operands are contiguous
+// along k: a 16-byte LDS cell holds the eight bf16 of one row (or output column) for eight
+// consecutive k, and a fragment of v_mfma_f32_32x32x16_bf16 (lane = row, eight k) is one
+// ds_read_b128.  A thread stages half cells: a float4 (coalesced along k: 128-byte row pieces),
+// split in registers, three 8-byte stores; the row-group stride of 136 cells puts the two groups
+// a store instruction touches on different halves of the banks.  One LDS buffer, the next chunk
+// in registers meanwhile, two barriers per chunk; grid.z walks several row lists (z-th list,
+// count, weights and bias: strides given) in one launch.
+constexpr int kDsGS = 136;                    // cells between the row groups of the X parts
+constexpr size_t dense_split_lds_bytes(int NJ) { return static_cast<size_t>(16) * 3 * 4 * (kDsGS + 32 * NJ + 8); }
 
 template <int NJ>
-__global__ __launch_bounds__(kThreads) void k_dense_mfma(const float *__restrict__ X, int ldx,
-                                                         const int32_t *__restrict__ rows,
-                                                         const int32_t *__restrict__ n_rows_dev, int R, int K,
-                                                         const float *__restrict__ W, int ldw,
-                                                         const float *__restrict__ bias, int relu,
-                                                         const float *__restrict__ M, int ldm,
-                                                         float *__restrict__ Y, int ldy)
+__global__ __launch_bounds__(kThreads, 3) void k_dense_split(const float *__restrict__ X, int ldx,
+                                                             const int32_t *__restrict__ rows,
+                                                             const int32_t *__restrict__ n_rows_dev, int R, int K,
+                                                             const float *__restrict__ Wt, int ldwt,
+                                                             const float *__restrict__ bias, int relu,
+                                                             const float *__restrict__ M, int ldm,
+                                                             float *__restrict__ Y, int ldy, size_t list_stride,
+                                                             size_t w_stride, size_t b_stride)
 {
-    constexpr int Hc = 32 * NJ, LDW = Hc + 32;
-    constexpr int WQ = kDenseKC * Hc / 4 / kThreads;      // float4 of a W chunk per thread: 1, 2 or 4
-    extern __shared__ float lds[];
-    float *xs = lds;                                       // [2][kDenseRows][kDenseLdx]
-    float *wsh = lds + 2 * kDenseRows * kDenseLdx;         // [2][kDenseKC][LDW]
-    if (n_rows_dev) R = min(R, *n_rows_dev);
+    constexpr int Hc = 32 * NJ, GSW = Hc + 8;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    uint2 *half_x = reinterpret_cast<uint2 *>(lds_raw);                 // [3][4][kDsGS] cells of two halves
+    uint2 *half_w = half_x + 2 * 3 * 4 * kDsGS;                         // [3][4][GSW]
+    const uint4 *cell_x = reinterpret_cast<const uint4 *>(half_x);
+    const uint4 *cell_w = reinterpret_cast<const uint4 *>(half_w);
+    rows += blockIdx.z * list_stride;
+    if (n_rows_dev) R = min(R, n_rows_dev[blockIdx.z]);
+    Wt += blockIdx.z * w_stride;
+    if (bias) bias += blockIdx.z * b_stride;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lk = lane >> 5;
     const int tile0 = blockIdx.x * kDenseRows;
     if (tile0 >= R) return;                                // the whole workgroup, before any barrier
 
-    // this thread's share of a chunk: four pieces of X rows (row xr + 32 q, floats xc .. xc + 3)
+    // this thread's share of a chunk: float4 number (tid & 7) of the 32 k, of rows xr + 32 q and of
+    // output columns xr + 32 q
     const int xr = tid >> 3, xc = (tid & 7) * 4;
+    const int grp = xc >> 3, hf = (xc >> 2) & 1;
     const float *xsrc[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int r = min(tile0 + xr + 32 * q, R - 1);
         xsrc[q] = X + static_cast<size_t>(rows ? rows[r] : r) * ldx + xc;
     }
-    f32x4v xreg[4], wreg[WQ];
+    f32x4v xreg[4], wreg[NJ];
     auto fetch = [&](int k0) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) xreg[q] = *reinterpret_cast<const f32x4v *>(xsrc[q] + k0);
 #pragma unroll
-        for (int q = 0; q < WQ; ++q) {
-            const int e = (tid + kThreads * q) * 4, kk = e / Hc, c = e - kk * Hc;
-            wreg[q] = *reinterpret_cast<const f32x4v *>(W + static_cast<size_t>(k0 + kk) * ldw + c);
-        }
+        for (int q = 0; q < NJ; ++q)
+            wreg[q] = *reinterpret_cast<const f32x4v *>(Wt + static_cast<size_t>(xr + 32 * q) * ldwt + k0 + xc);
     };
-    auto stash = [&](int buf) {
-        float *xd = xs + buf * kDenseRows * kDenseLdx;
-        float *wd = wsh + buf * kDenseKC * LDW;
+    auto put_half = [&](uint2 *cells, int stride, int c, const f32x4v &v) {
+        auto top = [](float x) { return __uint_as_float(__float_as_uint(x) & 0xFFFF0000u); };
+        auto pack = [](float lo, float hi) {
+            return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+        };
+        float r[4], l[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) xd[(xr + 32 * q) * kDenseLdx + xc + i] = xreg[q][i];
-#pragma unroll
-        for (int q = 0; q < WQ; ++q) {
-            const int e = (tid + kThreads * q) * 4, kk = e / Hc, c = e - kk * Hc;
-            *reinterpret_cast<f32x4v *>(wd + kk * LDW + c) = wreg[q];
+        for (int i = 0; i < 4; ++i) {
+            r[i] = v[i] - top(v[i]);
+            l[i] = r[i] - top(r[i]);
         }
+        cells[2 * ((0 * 4 + grp) * stride + c) + hf] = uint2{pack(v[0], v[1]), pack(v[2], v[3])};
+        cells[2 * ((1 * 4 + grp) * stride + c) + hf] = uint2{pack(r[0], r[1]), pack(r[2], r[3])};
+        cells[2 * ((2 * 4 + grp) * stride + c) + hf] = uint2{pack(l[0], l[1]), pack(l[2], l[3])};
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) put_half(half_x, kDsGS, xr + 32 * q, xreg[q]);
+#pragma unroll
+        for (int q = 0; q < NJ; ++q) put_half(half_w, GSW, xr + 32 * q, wreg[q]);
     };
 
     f32x16 acc[NJ];
@@ -767,43 +782,72 @@ __global__ __launch_bounds__(kThreads) void k_dense_mfma(const float *__restrict
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[jb][v] = 0.0f;
 
-    fetch(0);
-    stash(0);
-    __syncthreads();
     const int n_chunks = K / kDenseKC;
+    fetch(0);
     for (int c = 0; c < n_chunks; ++c) {
-        const int buf = c & 1;
+        stash();
+        __syncthreads();
         if (c + 1 < n_chunks) fetch((c + 1) * kDenseKC);
-        const float *xa = xs + buf * kDenseRows * kDenseLdx + (32 * wave + li) * kDenseLdx + lk;
-        const float *wb = wsh + buf * kDenseKC * LDW + lk * LDW + li;
 #pragma unroll
-        for (int st = 0; st < kDenseKC / 2; ++st) {
-            const float a = xa[2 * st];
+        for (int ks = 0; ks < 2; ++ks) {
+            const int g = 2 * ks + lk;
+            bf16x8w a[3];
 #pragma unroll
-            for (int jb = 0; jb < NJ; ++jb)
-                acc[jb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, wb[2 * st * LDW + 32 * jb], acc[jb], 0, 0, 0);
+            for (int p = 0; p < 3; ++p)
+                a[p] = *reinterpret_cast<const bf16x8w *>(&cell_x[(p * 4 + g) * kDsGS + 32 * wave + li]);
+            constexpr int JP = NJ > 1 ? 2 : 1;
+            constexpr int pa[6] = {2, 0, 1, 1, 0, 0}, pb[6] = {0, 2, 1, 0, 1, 0};   // small products first
+#pragma unroll
+            for (int j0 = 0; j0 < NJ; j0 += JP) {
+                bf16x8w b[JP][3];
+#pragma unroll
+                for (int u = 0; u < JP; ++u)
+#pragma unroll
+                    for (int p = 0; p < 3; ++p)
+                        b[u][p] = *reinterpret_cast<const bf16x8w *>(&cell_w[(p * 4 + g) * GSW + 32 * (j0 + u) + li]);
+#pragma unroll
+                for (int t = 0; t < 6; ++t)
+#pragma unroll
+                    for (int u = 0; u < JP; ++u)
+                        acc[j0 + u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[pa[t]], b[u][pb[t]], acc[j0 + u], 0, 0, 0);
+            }
         }
-        if (c + 1 < n_chunks) stash(buf ^ 1);
         __syncthreads();
     }
 
     float bj[NJ];
 #pragma unroll
     for (int jb = 0; jb < NJ; ++jb) bj[jb] = bias ? bias[32 * jb + li] : 0.0f;
+    int orow[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-        const int r = tile0 + 32 * wave + 8 * (v / 4) + 4 * lk + (v % 4);
-        const bool ok = r < R;
-        const int rc = min(r, R - 1);
-        const int orow = rows ? rows[rc] : rc;
+        const int rc = min(tile0 + 32 * wave + 8 * (v / 4) + 4 * lk + (v % 4), R - 1);
+        orow[v] = rows ? rows[rc] : rc;
+    }
+    auto finish = [&](auto gated) {
+        // with gates: all gate values of a column tile are loaded before its first store (loads
+        // and stores retire in order: a load behind a store would wait for it)
 #pragma unroll
         for (int jb = 0; jb < NJ; ++jb) {
-            float y = acc[jb][v] + bj[jb];
-            if (relu) y = fmaxf(y, 0.0f);
-            if (M) y = M[static_cast<size_t>(orow) * ldm + 32 * jb + li] > 0.0f ? y : 0.0f;
-            if (ok) Y[static_cast<size_t>(orow) * ldy + 32 * jb + li] = y;
+            float gate[16];
+            if constexpr (decltype(gated)::value) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) gate[v] = M[static_cast<size_t>(orow[v]) * ldm + 32 * jb + li];
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = tile0 + 32 * wave + 8 * (v / 4) + 4 * lk + (v % 4);
+                float y = acc[jb][v] + bj[jb];
+                if (relu) y = fmaxf(y, 0.0f);
+                if constexpr (decltype(gated)::value) y = gate[v] > 0.0f ? y : 0.0f;
+                if (r < R) Y[static_cast<size_t>(orow[v]) * ldy + 32 * jb + li] = y;
+            }
         }
-    }
+    };
+    if (M)
+        finish(std::true_type{});
+    else
+        finish(std::false_type{});
 }
 
 // a_v = sum of the neighbours' messages, for every node and both directions (grid.y).
@@ -1162,7 +1206,6 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_mfma(const float *__restrict
 // c + 1 are in flight in registers while chunk c is multiplied; the ids of a row list are staged
 // in LDS one chunk further ahead.  Column sums of Dl (the bias gradient) are taken in fp32 from
 // the staged values, by the thread that stages the column.
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8w;
 
 constexpr size_t wgrad_split_lds_bytes(int NJ)
 {
@@ -1175,10 +1218,15 @@ __global__ __launch_bounds__(kThreads, 3) void k_wgrad_split(const float *__rest
                                                           const int32_t *__restrict__ rows,
                                                           const int32_t *__restrict__ n_rows_dev,
                                                           int R, int I, int rows_per_slab,
-                                                          float *__restrict__ partial)
+                                                          float *__restrict__ partial, size_t list_stride,
+                                                          size_t partial_stride)
 {
     constexpr int J = 32 * NJ;
     constexpr int NDC = (4 * J + kThreads - 1) / kThreads;     // Dl cells per thread: 2, 1, 1
+    // grid.z > 1: the same contraction over several row lists at once (list z, its length, its slabs)
+    rows += blockIdx.z * list_stride;
+    n_rows_dev += blockIdx.z;
+    partial += blockIdx.z * partial_stride;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     uint4 *cell_a = reinterpret_cast<uint4 *>(lds_raw);                       // [3 parts][4 row groups][128 columns]
     uint4 *cell_d = cell_a + 3 * 4 * 128;                                      // [3 parts][4 row groups][J columns]
@@ -1504,9 +1552,12 @@ void launch_fill_zero(float *p, size_t n, hipStream_t s)
                        s, p, n);
 }
 
+// n_lists > 1 (matrix-core path with row lists only): the contraction is taken for n_lists row
+// lists, list_stride apart with consecutive counts, in one launch, for the layers lys[0..n_lists).
 void launch_wgrad(const float *A, int lda, const float *Dl, int ldd, const uint8_t *row_cls, int want,
                   const int32_t *list, const int32_t *list_count, int64_t R, const LayerRef &ly, float *partial,
-                  float *grad, int generic, hipStream_t s, int I_pad = 0)
+                  float *grad, int generic, hipStream_t s, int I_pad = 0, int n_lists = 1, size_t list_stride = 0,
+                  const LayerRef *lys = nullptr)
 {
     // I_pad: A has I_pad >= n_in columns, the extra ones zero (lets a narrow layer use the matrix cores)
     if (R <= 0) return;
@@ -1516,14 +1567,15 @@ void launch_wgrad(const float *A, int lda, const float *Dl, int ldd, const uint8
     const int slabs = static_cast<int>((R + per - 1) / per);
     if (cores) {
         // with a row list (the nodes of one set, ascending) the class filter is not needed
-        const dim3 grid((I + 127) / 128, slabs);
+        const dim3 grid((I + 127) / 128, slabs, n_lists);
+        const size_t slab_floats = static_cast<size_t>(slabs) * (static_cast<size_t>(I) * J + J);
         // the bf16-split kernel addresses its operands with 32-bit element offsets
-        const bool small = static_cast<double>(R) * std::max(lda, ldd) < 4.0e9;
+        const bool small = static_cast<double>(R) * std::max(lda, ldd) < 4.0e9;   // the caller's duty if n_lists > 1
 #define CALL(NJ)                                                                                                  \
     if (small) {                                                                                                  \
         allow_lds_bw(k_wgrad_split<NJ>, wgrad_split_lds_bytes(NJ));                                               \
         hipLaunchKernelGGL(k_wgrad_split<NJ>, grid, dim3(kThreads), wgrad_split_lds_bytes(NJ), s, A, lda, Dl, ldd, \
-                           list, list_count, static_cast<int>(R), I, per, partial);                               \
+                           list, list_count, static_cast<int>(R), I, per, partial, list_stride, slab_floats);     \
     } else {                                                                                                      \
         allow_lds_bw(k_wgrad_mfma<NJ>, wgrad_lds_bytes(NJ));                                                      \
         hipLaunchKernelGGL(k_wgrad_mfma<NJ>, grid, dim3(kThreads), wgrad_lds_bytes(NJ), s, A, lda, Dl, ldd, list,  \
@@ -1537,8 +1589,10 @@ void launch_wgrad(const float *A, int lda, const float *Dl, int ldd, const uint8
     }
     const size_t n_main = static_cast<size_t>(ly.n_in) * J, count = n_main + J;
     const size_t src_count = static_cast<size_t>(I) * J + J;
-    hipLaunchKernelGGL(k_wgrad_reduce, dim3(static_cast<unsigned>((count + 31) / 32)), dim3(kThreads), 0, s,
-                       partial, slabs, count, src_count, n_main, src_count - count, grad + ly.w);
+    for (int z = 0; z < n_lists; ++z)
+        hipLaunchKernelGGL(k_wgrad_reduce, dim3(static_cast<unsigned>((count + 31) / 32)), dim3(kThreads), 0, s,
+                           partial + z * static_cast<size_t>(slabs) * src_count, slabs, count, src_count, n_main,
+                           src_count - count, grad + (lys ? lys[z].w : ly.w));
 }
 
 namespace {
@@ -1546,19 +1600,24 @@ namespace {
 struct DenseCall {
     const float *X; int ldx;
     const int32_t *rows; const int32_t *n_rows_dev; int R; int K;
-    const float *W; int ldw; const float *bias; int relu;
+    const float *Wt; int ldwt;     // row j = the K inputs of output column j
+    const float *bias; int relu;
     const float *M; int ldm;
     float *Y; int ldy;
+    // n_lists row lists in one launch: z-th list at rows + z list_stride with count n_rows_dev[z],
+    // weights at Wt + z w_stride, bias + z b_stride
+    int n_lists = 1; size_t list_stride = 0, w_stride = 0, b_stride = 0;
 };
 
 void launch_dense(const DenseCall &c, int H, hipStream_t s)
 {
     if (c.R <= 0) return;
-    const dim3 grid((c.R + kDenseRows - 1) / kDenseRows);
-#define CALL(NJ)                                                                                             \
-    allow_lds_bw(k_dense_mfma<NJ>, dense_lds_bytes(NJ));                                                     \
-    hipLaunchKernelGGL(k_dense_mfma<NJ>, grid, dim3(kThreads), dense_lds_bytes(NJ), s, c.X, c.ldx, c.rows,   \
-                       c.n_rows_dev, c.R, c.K, c.W, c.ldw, c.bias, c.relu, c.M, c.ldm, c.Y, c.ldy)
+    const dim3 grid((c.R + kDenseRows - 1) / kDenseRows, 1, c.n_lists);
+#define CALL(NJ)                                                                                                 \
+    allow_lds_bw(k_dense_split<NJ>, dense_split_lds_bytes(NJ));                                                  \
+    hipLaunchKernelGGL(k_dense_split<NJ>, grid, dim3(kThreads), dense_split_lds_bytes(NJ), s, c.X, c.ldx, c.rows, \
+                       c.n_rows_dev, c.R, c.K, c.Wt, c.ldwt, c.bias, c.relu, c.M, c.ldm, c.Y, c.ldy, c.list_stride, \
+                       c.w_stride, c.b_stride)
     if (H == 32) { CALL(1); } else if (H == 64) { CALL(2); } else { CALL(4); }
 #undef CALL
 }
@@ -1612,22 +1671,36 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
             const MlpRef &ln = mv.l[set];
             for (int l = 0; l < L && !pool_kept; ++l)     // kept: the forward pooling kernel wrote lact
                 launch_dense({l == 0 ? ws.emb : gw.lact + static_cast<size_t>(l - 1) * NH, l == 0 ? 2 * H : H, list,
-                              cnt, n, l == 0 ? 2 * H : H, mv.blob + ln.layer[l].w, H, mv.blob + ln.layer[l].b, 1,
-                              nullptr, 0, gw.lact + static_cast<size_t>(l) * NH, H}, H, s);
+                              cnt, n, l == 0 ? 2 * H : H, blob_t + ln.layer[l].w, l == 0 ? 2 * H : H,
+                              mv.blob + ln.layer[l].b, 1, nullptr, 0, gw.lact + static_cast<size_t>(l) * NH, H}, H, s);
         }
         hipLaunchKernelGGL(k_bw_pool_seed, dim3(static_cast<unsigned>((NH / 4 + kThreads - 1) / kThreads)),
                            dim3(kThreads), 0, s, gv, H, G, mv.D, gw.cls, fa.placement, gw.dP,
                            gw.lact + static_cast<size_t>(L - 1) * NH, gw.dl + static_cast<size_t>(L - 1) * NH);
-        for (int set = 0; set < 3; ++set) {
-            const int32_t *list = gw.lists + static_cast<size_t>(set) * n, *cnt = gw.counts + set;
-            const MlpRef &ln = mv.l[set];
-            for (int l = L - 1; l >= 1; --l)
-                launch_dense({gw.dl + static_cast<size_t>(l) * NH, H, list, cnt, n, H, blob_t + ln.layer[l].w, H,
-                              nullptr, 0, gw.lact + static_cast<size_t>(l - 1) * NH, H,
-                              gw.dl + static_cast<size_t>(l - 1) * NH, H}, H, s);
-            for (int half = 0; half < 2; ++half)   // the first layer is [2H, H]: transposed [H][2H]
-                launch_dense({gw.dl, H, list, cnt, n, H, blob_t + ln.layer[0].w + half * H, 2 * H, nullptr, 0,
-                              nullptr, 0, gw.demb + half * H, 2 * H}, H, s);
+        {
+            // back through l's layers, the three sets' row lists in one launch each.  The weights go
+            // in as they are stored (row i of a layer = the outputs fed by input i), which is the
+            // transposed layout of this contraction; the three networks are equally far apart.
+            const MlpRef &l0 = mv.l[0];
+            const size_t w_stride = static_cast<size_t>(mv.l[1].layer[0].w - l0.layer[0].w);
+            for (int l = L - 1; l >= 1; --l) {
+                DenseCall c{gw.dl + static_cast<size_t>(l) * NH, H, gw.lists, gw.counts, n, H, mv.blob + l0.layer[l].w, H,
+                            nullptr, 0, gw.lact + static_cast<size_t>(l - 1) * NH, H,
+                            gw.dl + static_cast<size_t>(l - 1) * NH, H};
+                c.n_lists = 3;
+                c.list_stride = static_cast<size_t>(n);
+                c.w_stride = w_stride;
+                launch_dense(c, H, s);
+            }
+            for (int half = 0; half < 2; ++half) {   // the first layer is [2H, H]: inputs half H .. half H + H - 1
+                DenseCall c{gw.dl, H, gw.lists, gw.counts, n, H,
+                            mv.blob + l0.layer[0].w + static_cast<size_t>(half) * H * H, H, nullptr, 0, nullptr, 0,
+                            gw.demb + half * H, 2 * H};
+                c.n_lists = 3;
+                c.list_stride = static_cast<size_t>(n);
+                c.w_stride = w_stride;
+                launch_dense(c, H, s);
+            }
         }
     } else {
         const size_t lds = sizeof(float) * kTile * 4 * H;
@@ -1667,7 +1740,7 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
             for (int l = 0; l + 1 < L || (l < L && !wfrag_bw); ++l) {
                 const LayerRef &ly = mv.f[dir].layer[l];
                 launch_dense({l == 0 ? emb_j + dir * H : gw.fact + (static_cast<size_t>(dir) * L + l - 1) * NH,
-                              l == 0 ? 2 * H : H, nullptr, nullptr, n, H, mv.blob + ly.w, H, mv.blob + ly.b, 1,
+                              l == 0 ? 2 * H : H, nullptr, nullptr, n, H, blob_t + ly.w, H, mv.blob + ly.b, 1,
                               nullptr, 0, gw.fact + (static_cast<size_t>(dir) * L + l) * NH, H}, H, s);
             }
         hipLaunchKernelGGL(k_bw_agg, dim3(static_cast<unsigned>((NH / 4 + kThreads - 1) / kThreads), 2), dim3(kThreads),
@@ -1677,7 +1750,7 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
                 const LayerRef &ly = mv.g[dir].layer[l];
                 launch_dense({l == 0 ? gw.agg + static_cast<size_t>(dir) * NH
                                      : gw.gact + (static_cast<size_t>(dir) * L + l - 1) * NH,
-                              H, nullptr, nullptr, n, H, mv.blob + ly.w, H, mv.blob + ly.b, 1, nullptr, 0,
+                              H, nullptr, nullptr, n, H, blob_t + ly.w, H, mv.blob + ly.b, 1, nullptr, 0,
                               gw.gact + (static_cast<size_t>(dir) * L + l) * NH, H}, H, s);
             }
     }
@@ -1760,12 +1833,23 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
         launch_wgrad(gw.phi, 32, gw.dx, H, nullptr, 0, nullptr, nullptr, n, mv.proj, gw.partial, grad, generic, s, 32);
     else
         launch_wgrad(gw.phi, mv.F, gw.dx, H, nullptr, 0, nullptr, nullptr, n, mv.proj, gw.partial, grad, generic, s);
+    // the three sets' row lists in one launch per layer of l (all slabs of the three lists together
+    // fill the chip; one list alone leaves most of its slabs empty)
+    const bool sets_together = dense && static_cast<double>(n) * 2 * H < 4.0e9;
+    if (sets_together)
+        for (int l = 0; l < L; ++l) {
+            const float *lin = l == 0 ? ws.emb : gw.lact + static_cast<size_t>(l - 1) * NH;
+            const LayerRef lys[3] = {mv.l[0].layer[l], mv.l[1].layer[l], mv.l[2].layer[l]};
+            launch_wgrad(lin, l == 0 ? 2 * H : H, gw.dl + static_cast<size_t>(l) * NH, H, gw.cls, 0, gw.lists,
+                         gw.counts, n, lys[0], gw.partial, grad, generic, s, 0, 3, static_cast<size_t>(n), lys);
+        }
     for (int set = 0; set < 3; ++set)
         for (int l = 0; l < L; ++l) {
             const float *lin = l == 0 ? ws.emb : gw.lact + static_cast<size_t>(l - 1) * NH;
-            launch_wgrad(lin, l == 0 ? 2 * H : H, gw.dl + static_cast<size_t>(l) * NH, H, gw.cls, set + 1,
-                         dense ? gw.lists + static_cast<size_t>(set) * n : nullptr, dense ? gw.counts + set : nullptr,
-                         n, mv.l[set].layer[l], gw.partial, grad, generic, s);
+            if (!sets_together)
+                launch_wgrad(lin, l == 0 ? 2 * H : H, gw.dl + static_cast<size_t>(l) * NH, H, gw.cls, set + 1,
+                             dense ? gw.lists + static_cast<size_t>(set) * n : nullptr,
+                             dense ? gw.counts + set : nullptr, n, mv.l[set].layer[l], gw.partial, grad, generic, s);
             const float *hin = l == 0 ? gw.hin + static_cast<size_t>(set) * BG * H
                                       : gw.hact + (static_cast<size_t>(set) * L + l - 1) * BG * H;
             launch_wgrad(hin, H, gw.dh + (static_cast<size_t>(set) * L + l) * BG * H, H, nullptr, 0, nullptr, nullptr,
