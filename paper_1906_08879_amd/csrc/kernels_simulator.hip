@@ -116,6 +116,10 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
     bool active = false;
     float ev_time = 0.0f;
     int ev_seq = 0, ev_node = 0, ev_dst = 0;
+    // what the event's handler needs of its operation, read when the event is created (off the
+    // handler's chain of dependent LDS reads): its children and the duration of its transfers
+    int ev_c0 = 0, ev_cnt = 0;
+    float ev_dur = 0.0f;
     int seq = 0, n_tr = 0, n_events = 0;
     float last = 0.0f;
 
@@ -156,6 +160,9 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
             }
             if (q_head == kNone) q_tail = kNone;
             active = true;
+            ev_c0 = S.cptr[o];
+            ev_cnt = S.cptr[o + 1] - ev_c0;
+            ev_dur = __fmul_rn(S.size[o], inv_bw);
             ev_time = __fadd_rn(now, dur);
             ev_seq = seq + __popcll(m & ((1ull << lane) - 1ull));
             ev_node = o;
@@ -191,9 +198,15 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
         const unsigned int t_bits = active ? __float_as_uint(ev_time) : 0xFFFFFFFFu;
         const unsigned int t_min = row_pair_min(t_bits);
         if (t_min == 0xFFFFFFFFu) break;                  // nothing pending: the simulation is over
-        const unsigned int s_bits = (active && t_bits == t_min) ? static_cast<unsigned int>(ev_seq) : 0xFFFFFFFFu;
-        const unsigned int s_min = row_pair_min(s_bits);
-        const int slot = __ffsll(static_cast<long long>(__ballot(s_bits == s_min && active && t_bits == t_min))) - 1;
+        // Usually one pending event carries the smallest timestamp; only ties need the second
+        // reduction, over the creation numbers.
+        unsigned long long first = __ballot(active && t_bits == t_min);
+        if (first & (first - 1)) {
+            const unsigned int s_bits = (active && t_bits == t_min) ? static_cast<unsigned int>(ev_seq) : 0xFFFFFFFFu;
+            const unsigned int s_min = row_pair_min(s_bits);
+            first = __ballot(s_bits == s_min && active && t_bits == t_min);
+        }
+        const int slot = __ffsll(static_cast<long long>(first)) - 1;
         const float now = __uint_as_float(t_min);
         const int o = __builtin_amdgcn_readlane(ev_node, slot);
         const int dst = __builtin_amdgcn_readlane(ev_dst, slot);
@@ -203,10 +216,10 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
         // (its own device after op-done, the destination after transfer-done) have one input
         // fewer to wait for; after op-done the others make the output cross, once per device.
         // Queues are filled in ascending child id (= lane order), as a scalar loop would.
-        const int c0 = S.cptr[o], cnt = S.cptr[o + 1] - c0;
+        const int c0 = __builtin_amdgcn_readlane(ev_c0, slot), cnt = __builtin_amdgcn_readlane(ev_cnt, slot);
         const bool op_done = slot < D;
         const int here = op_done ? slot : dst;
-        const float dur = op_done ? __fmul_rn(S.size[o], inv_bw) : 0.0f;
+        const float dur = op_done ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ev_dur), slot)) : 0.0f;
         if (op_done) last = now;
         if constexpr (TL) {
             if (!op_done && lane == 0) arrival[static_cast<size_t>(n0 + o) * D + dst] = now;
