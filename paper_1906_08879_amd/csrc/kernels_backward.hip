@@ -1475,10 +1475,20 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_reduce(const float *__restri
     const int c = threadIdx.x & 31, q = threadIdx.x >> 5;
     const size_t idx = static_cast<size_t>(blockIdx.x) * 32 + c;
     const size_t src = idx < n_main ? idx : idx + src_skip;
-    float s = 0.0f;
-    if (idx < count)
-        for (int sl = q; sl < n_slabs; sl += 8) s += partial[static_cast<size_t>(sl) * src_count + src];
-    part[q][c] = s;
+    // four running sums per thread row (slabs q, q + 8, q + 16, q + 24, then again), added in order
+    // at the end: still one fixed order, with four loads in flight
+    float s4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (idx < count) {
+        int sl = q;
+        for (; sl + 24 < n_slabs; sl += 32) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s4[u] += partial[static_cast<size_t>(sl + 8 * u) * src_count + src];
+        }
+#pragma unroll
+        for (int u = 0; u < 3; ++u)     // at most three slabs are left
+            if (sl + 8 * u < n_slabs) s4[u] += partial[static_cast<size_t>(sl + 8 * u) * src_count + src];
+    }
+    part[q][c] = (s4[0] + s4[1]) + (s4[2] + s4[3]);
     __syncthreads();
     if (q == 0 && idx < count) {
         float t = part[0][c];
