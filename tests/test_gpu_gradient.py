@@ -235,6 +235,35 @@ def test_gradient_replays_from_a_hip_graph():
     wt.close()
 
 
+def test_interleaved_handles_share_nothing():
+    """Two graph batches and two weight sets of different shapes, used alternately for forward
+    passes and gradients: every result equals the one computed with fresh handles."""
+    import paper_1906_08879_amd as pl
+    from gpu_common import run_library
+    wa = make_workload("layered200", B=3)
+    rng = np.random.default_rng(77)
+    wb = custom_workload(rng, [30, 5, 61], 3, 64, 2, 1, 1, "bf16")
+    act_a, co_a, _ = _actions_and_coeff(wa, 1)
+    act_b, co_b, _ = _actions_and_coeff(wb, 2)
+    alone = {"a": run_gradient(wa, act_a, co_a), "b": run_gradient(wb, act_b, co_b),
+             "fa": run_library(wa, want_emb=False), "fb": run_library(wb, want_emb=False)}
+    ha = (pl.GraphBatch(wa.n_nodes, wa.n_edges, wa.edge_src, wa.edge_dst),
+          pl.Weights(wa.weights, wa.D, wa.H, wa.n_layers, wa.k_sweeps, wa.group_by_device, wa.weight_dtype))
+    hb = (pl.GraphBatch(wb.n_nodes, wb.n_edges, wb.edge_src, wb.edge_dst),
+          pl.Weights(wb.weights, wb.D, wb.H, wb.n_layers, wb.k_sweeps, wb.group_by_device, wb.weight_dtype))
+    for _ in range(2):
+        ga = run_gradient(wa, act_a, co_a, handles=ha)
+        fb = run_library(wb, want_emb=False, handles=hb)
+        gb = run_gradient(wb, act_b, co_b, handles=hb)
+        fa = run_library(wa, want_emb=False, handles=ha)
+        np.testing.assert_array_equal(ga["grad"], alone["a"]["grad"])
+        np.testing.assert_array_equal(gb["grad"], alone["b"]["grad"])
+        np.testing.assert_array_equal(fa["logits"], alone["fa"]["logits"])
+        np.testing.assert_array_equal(fb["logits"], alone["fb"]["logits"])
+    for h in ha + hb:
+        h.close()
+
+
 def test_empty_batch_is_accepted():
     import torch
     import paper_1906_08879_amd as pl
