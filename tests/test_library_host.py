@@ -196,3 +196,15 @@ def test_simulate_reward_rejects_bad_arguments(lib):
     assert raw.pl_simulate_reward(g._h, 4, null, null, f(1.0), f(1.0), f(-2.0), null, null, null, null, null) == -2
     assert raw.pl_simulate_reward(g._h, 4, null, null, f(1.0), f(1.0), f(2.0), null, null, null, null, null) == -1
     g.close()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: a larger --gpus ends with a message, before anything touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
