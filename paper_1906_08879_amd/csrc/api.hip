@@ -379,6 +379,20 @@ struct StageScope {
     }
 };
 
+// Nodes and edges of the batch's largest graph.
+struct GraphExtent {
+    int n_max, e_max;
+};
+GraphExtent graph_extent(const HostLayout &h)
+{
+    int64_t n_max = 0, e_max = 0;
+    for (int32_t b = 0; b < h.B; ++b) {
+        n_max = std::max<int64_t>(n_max, h.node_off[b + 1] - h.node_off[b]);
+        e_max = std::max<int64_t>(e_max, h.edge_off[b + 1] - h.edge_off[b]);
+    }
+    return {static_cast<int>(n_max), static_cast<int>(e_max)};
+}
+
 // StageMarks hook over a batch's timer: an event at the beginning and at the end of a stage.
 void stage_mark(void *ctx, int stage, bool begin, hipStream_t s)
 {
@@ -424,7 +438,10 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
     {
         StageScope scope(g->timer, PL_STAGE_SWEEP, s);
         // without sweeps the node sets still need reachability from v*, unless there is one set
-        if (w->cfg.k_sweeps == 0 && !w->cfg.single_set) launch_reach_only(gv, cur_node, g->ws.reach, s);
+        if (w->cfg.k_sweeps == 0 && !w->cfg.single_set) {
+            const GraphExtent x = graph_extent(g->host);
+            launch_reach_only(gv, cur_node, g->ws.reach, x.n_max, x.e_max, g->host.max_depth, s);
+        }
         for (int k = 0; k < w->cfg.k_sweeps; ++k) {
             if (mfma)
                 launch_sweep_mfma(gv, mv, g->ws, fa, reinterpret_cast<const uint4 *>(w->d_wfrag),
@@ -567,7 +584,8 @@ int pl_node_classes(pl_graph_batch *g, const int32_t *cur_node, uint8_t *out_cla
     if (rc) return rc;
     if ((rc = ensure_reach(g))) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    launch_reach_only(g->view, cur_node, g->ws.reach, s);
+    const GraphExtent x = graph_extent(g->host);
+    launch_reach_only(g->view, cur_node, g->ws.reach, x.n_max, x.e_max, g->host.max_depth, s);
     launch_classes(g->view, cur_node, g->ws.reach, out_class, s);
     PL_HIP(hipGetLastError());
     return PL_OK;

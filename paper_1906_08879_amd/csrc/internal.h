@@ -121,8 +121,8 @@ void launch_project(const GraphView &gv, const ModelView &mv, const Workspace &w
                     const ForwardArgs &fa, bool to_emb, bool to_xb, hipStream_t s);
 void launch_sweep_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                           const ForwardArgs &fa, bool write_reach, hipStream_t s);
-void launch_reach_only(const GraphView &gv, const int32_t *cur_node, uint8_t *reach,
-                       hipStream_t s);
+void launch_reach_only(const GraphView &gv, const int32_t *cur_node, uint8_t *reach, int n_max, int e_max,
+                       int depth_max, hipStream_t s);
 void launch_classes(const GraphView &gv, const int32_t *cur_node, const uint8_t *reach,
                     uint8_t *out_class, hipStream_t s);
 void launch_pool_generic(const GraphView &gv, const ModelView &mv, const Workspace &ws,

@@ -96,6 +96,50 @@ __global__ __launch_bounds__(kThreads) void k_project(GraphView gv, ModelView mv
     }
 }
 
+// The same with four columns per thread, for H a multiple of four (vector loads and stores; the
+// terms are added in the same order).
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4j;
+__global__ __launch_bounds__(kThreads) void k_project4(GraphView gv, ModelView mv,
+                                                       const float *__restrict__ feats,
+                                                       const int32_t *__restrict__ placement,
+                                                       const int32_t *__restrict__ cur_node,
+                                                       float *__restrict__ emb,
+                                                       float *__restrict__ xb)
+{
+    const int H = mv.H, D = mv.D, q = H / 4;
+    const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (idx >= static_cast<size_t>(gv.n_tot) * q) return;
+    const int v = static_cast<int>(idx / q), h = 4 * static_cast<int>(idx - static_cast<size_t>(v) * q);
+    const int b = gv.node_graph[v];
+    const float *W = mv.blob + mv.proj.w;
+    auto row = [&](int r) { return *reinterpret_cast<const f32x4j *>(W + static_cast<size_t>(r) * H + h); };
+    const float f_time = feats[v * 3 + 0], f_size = feats[v * 3 + 1], f_vis = feats[v * 3 + 2];
+    const int dev = placement[v];
+    const bool on_dev = dev >= 0 && dev < D;
+    const bool is_cur = v - gv.node_off[b] == cur_node[b];
+    const f32x4j bias = *reinterpret_cast<const f32x4j *>(mv.blob + mv.proj.b + h);
+    const f32x4j w0 = row(0), w1 = row(1), wd = row(2 + (on_dev ? dev : 0)), wc = row(2 + D), wv = row(3 + D);
+    f32x4j out;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float s = bias[k];
+        s = fmaf(f_time, w0[k], s);
+        s = fmaf(f_size, w1[k], s);
+        if (on_dev) s += wd[k];
+        if (is_cur) s += wc[k];
+        s = fmaf(f_vis, wv[k], s);
+        out[k] = fmaxf(s, 0.0f);
+    }
+    if (emb) {
+        *reinterpret_cast<f32x4j *>(emb + static_cast<size_t>(v) * 2 * H + h) = out;
+        *reinterpret_cast<f32x4j *>(emb + static_cast<size_t>(v) * 2 * H + H + h) = out;
+    }
+    if (xb) {
+        *reinterpret_cast<f32x4j *>(xb + static_cast<size_t>(gv.pos[0][v]) * H + h) = out;
+        *reinterpret_cast<f32x4j *>(xb + (static_cast<size_t>(gv.n_tot) + gv.pos[1][v]) * H + h) = out;
+    }
+}
+
 // ------------------------------------------------------------------ step 2: one sweep
 // One workgroup per (graph, direction) walks the graph's levels in order; graphs are
 // independent, so no grid-wide barrier is needed.  For every node v of a level:
@@ -209,6 +253,51 @@ __global__ __launch_bounds__(kThreads) void k_reach_only(GraphView gv,
         __threadfence_block();
         __syncthreads();
     }
+}
+
+// The same for graphs whose lists fit in LDS: one wave per (graph, direction) copies the graph's
+// bucket order, neighbour lists (graph-local ids) and level bounds into LDS and walks the levels
+// there; a level then costs a chain of LDS reads instead of a chain of global loads.
+__global__ __launch_bounds__(64) void k_reach_lds(GraphView gv, const int32_t *__restrict__ cur_node,
+                                                  uint8_t *__restrict__ reach_base, int n_max, int e_max,
+                                                  int depth_max)
+{
+    extern __shared__ int32_t reach_sm[];
+    int32_t *s_order = reach_sm;                    // [n_max]     local ids in bucket order
+    int32_t *s_ptr = s_order + n_max;               // [n_max + 1] local offsets of the neighbour lists
+    int32_t *s_idx = s_ptr + n_max + 1;             // [e_max]     local neighbour ids
+    int32_t *s_lvl = s_idx + e_max;                 // [depth_max + 1] local bucket bounds
+    uint8_t *s_bit = reinterpret_cast<uint8_t *>(s_lvl + depth_max + 1);   // [n_max]
+    const int b = blockIdx.x, dir = blockIdx.y, lane = threadIdx.x;
+    const int n0 = gv.node_off[b], n_b = gv.node_off[b + 1] - n0;
+    const int32_t *nbr_ptr = gv.nbr_ptr[dir] + n0;
+    const int e0 = nbr_ptr[0], e_b = nbr_ptr[n_b] - e0;
+    const int32_t *lvl = gv.lvl_ptr[dir] + gv.lvl_off[b];
+    const int depth = gv.lvl_off[b + 1] - gv.lvl_off[b] - 1;
+    const int cur_local = cur_node[b];
+    const int cur = (cur_local >= 0 && cur_local < n_b) ? cur_local : -1;
+    for (int i = lane; i < n_b; i += 64) {
+        s_order[i] = gv.order[dir][n0 + i] - n0;
+        s_bit[i] = 0;
+    }
+    for (int i = lane; i <= n_b; i += 64) s_ptr[i] = nbr_ptr[i] - e0;
+    for (int i = lane; i < e_b; i += 64) s_idx[i] = gv.nbr_idx[dir][e0 + i] - n0;
+    for (int i = lane; i <= depth; i += 64) s_lvl[i] = lvl[i] - n0;
+    __syncthreads();
+    for (int level = 0; level < depth; ++level) {
+        for (int t = s_lvl[level] + lane; t < s_lvl[level + 1]; t += 64) {
+            const int v = s_order[t];
+            int bit = 0;
+            for (int p = s_ptr[v]; p < s_ptr[v + 1]; ++p) {
+                const int u = s_idx[p];
+                bit |= (u == cur) | s_bit[u];
+            }
+            s_bit[v] = static_cast<uint8_t>(bit);
+        }
+        __syncthreads();
+    }
+    uint8_t *reach = reach_base + static_cast<size_t>(dir) * gv.n_tot + n0;
+    for (int i = lane; i < n_b; i += 64) reach[i] = s_bit[i];
 }
 
 // Section 2.2 step 3: 0 = v*, 1 = can reach v*, 2 = reachable from v*, 3 = neither.
@@ -502,6 +591,12 @@ void launch_project(const GraphView &gv, const ModelView &mv, const Workspace &w
 {
     const size_t total = static_cast<size_t>(gv.n_tot) * mv.H;
     if (total == 0) return;
+    if (mv.H % 4 == 0) {
+        const unsigned blocks = static_cast<unsigned>((total / 4 + kThreads - 1) / kThreads);
+        hipLaunchKernelGGL(k_project4, dim3(blocks), dim3(kThreads), 0, s, gv, mv, fa.node_feats,
+                           fa.placement, fa.cur_node, to_emb ? ws.emb : nullptr, to_xb ? ws.xb : nullptr);
+        return;
+    }
     const unsigned blocks = static_cast<unsigned>((total + kThreads - 1) / kThreads);
     hipLaunchKernelGGL(k_project, dim3(blocks), dim3(kThreads), 0, s, gv, mv, fa.node_feats,
                        fa.placement, fa.cur_node, to_emb ? ws.emb : nullptr, to_xb ? ws.xb : nullptr);
@@ -520,9 +615,17 @@ void launch_sweep_generic(const GraphView &gv, const ModelView &mv, const Worksp
 #undef CALL
 }
 
-void launch_reach_only(const GraphView &gv, const int32_t *cur_node, uint8_t *reach, hipStream_t s)
+void launch_reach_only(const GraphView &gv, const int32_t *cur_node, uint8_t *reach, int n_max, int e_max,
+                       int depth_max, hipStream_t s)
 {
     if (gv.B == 0) return;
+    // largest graph's order, list offsets, lists, level bounds and bits
+    const size_t lds = sizeof(int32_t) * (2 * static_cast<size_t>(n_max) + 1 + e_max + depth_max + 1) + n_max;
+    if (n_max > 0 && lds <= 64 * 1024) {
+        allow_lds(k_reach_lds, lds);
+        hipLaunchKernelGGL(k_reach_lds, dim3(gv.B, 2), dim3(64), lds, s, gv, cur_node, reach, n_max, e_max, depth_max);
+        return;
+    }
     hipLaunchKernelGGL(k_reach_only, dim3(gv.B, 2), dim3(kThreads), 0, s, gv, cur_node, reach);
 }
 
