@@ -39,22 +39,26 @@ def path_algorithmic_bytes(n_tot: int, e_tot: int, H: int) -> int:
 
 
 SWEEP_SOURCES = ("kernels_mfma.hip", "plan.cpp", "sweep_plan.h")
+WGRAD_SOURCES = ("kernels_backward.hip",)
 
 
-def csrc_digest() -> str:
-    """sha256 over the sources of the dominant kernel (the sweep kernel, its gather plan and the
-    shared declarations): ties a stored counter measurement to the kernel it was taken on."""
+def csrc_digest(sources=SWEEP_SOURCES) -> str:
+    """sha256 over the sources of a kernel (by default the dominant one: the sweep kernel, its
+    gather plan and the shared declarations): ties a stored counter measurement to the kernel it
+    was taken on."""
     import hashlib
     h = hashlib.sha256()
-    for name in SWEEP_SOURCES:
+    for name in sources:
         h.update(name.encode())
         h.update(open(os.path.join(ROOT, "paper_1906_08879_amd", "csrc", name), "rb").read())
     return h.hexdigest()
 
 
-def measured_traffic(workload: str, batch: int):
-    """HBM bytes per sweep launch from the stored rocprofv3 counter summary, or None when
-    there is none for this workload or the kernels have changed since it was taken."""
+def measured_traffic(workload: str, batch: int, key: str = "sweep_traffic_bytes_per_launch",
+                     digest_key: str = "source_sha256", sources=SWEEP_SOURCES):
+    """HBM bytes (per sweep launch by default; per gradient step for the weight-gradient stage)
+    from the stored rocprofv3 counter summary, or None when there is none for this workload or
+    the kernels have changed since it was taken."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}_B{batch}.txt")
     if not os.path.exists(path):
         return None
@@ -63,9 +67,9 @@ def measured_traffic(workload: str, batch: int):
         if not line.startswith("#") and ":" in line:
             k, v = line.split(":", 1)
             rec[k.strip()] = v.strip()
-    if rec.get("source_sha256") != csrc_digest() or "sweep_traffic_bytes_per_launch" not in rec:
+    if rec.get(digest_key) != csrc_digest(sources) or key not in rec:
         return None
-    return int(rec["sweep_traffic_bytes_per_launch"])
+    return int(rec[key])
 
 
 def main() -> int:
@@ -272,7 +276,10 @@ def main() -> int:
                                     "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                                     "algorithmic_bytes_per_step": int(alg), "flops_per_step": int(flops),
                                     "matrix_core_tflops": round(6.0 * flops / (wg_ms * 1e-3) / 1e12, 1),
-                                    "traffic": None}
+                                    "traffic": measured_traffic(args.workload, int(w.B),
+                                                                "wgrad_stage_traffic_bytes_per_step",
+                                                                "backward_sha256", WGRAD_SOURCES)
+                                    if default_variant else None}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
