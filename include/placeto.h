@@ -17,6 +17,12 @@
  *     was current when they were first used by a device call.
  *   - A forward call is asynchronous on the given stream.  Two calls that use the same
  *     pl_graph_batch must not overlap in time: the batch owns the intermediate buffers.
+ *   - Device-resident state is not range-checked by default (out-of-range values are contained,
+ *     see pl_embed_forward).  With PL_VALIDATE=1 in the environment, pl_embed_forward(_ex),
+ *     pl_policy_gradient(_ex), pl_episode_run and pl_episode_gradient first synchronise the stream,
+ *     copy placement, cur_node (and actions) to the host and return PL_ERR_RANGE, launching
+ *     nothing, if a device id or action is outside [0, D) or a current node outside its graph
+ *     (in the two episode calls a cur_node of -1, a finished graph, is accepted).
  */
 #ifndef PLACETO_H
 #define PLACETO_H
@@ -104,6 +110,9 @@ int pl_graph_batch_layout(const pl_graph_batch *g, int64_t *par_ptr, int32_t *pa
  * Asynchronous on `stream` (a hipStream_t, NULL = default stream). */
 int pl_node_classes(pl_graph_batch *g, const int32_t *cur_node, uint8_t *out_class,
                     void *stream);
+/* The same call under its debugging name. */
+int pl_debug_node_classes(pl_graph_batch *g, const int32_t *cur_node, uint8_t *out_class,
+                          void *stream);
 
 /* ---- parameters.  The blob holds, for every layer, a row-major [in, out] matrix followed
  * by `out` biases, in this order: input projection (D+4 -> H); f top-down, g top-down,
@@ -141,11 +150,15 @@ int pl_embed_forward(pl_graph_batch *g, const float *node_feats, const int32_t *
 /* Same, with optional extra outputs (NULL to skip):
  *   out_probs     dev [B, D]        softmax of the logits
  *   out_node_emb  dev [N_tot, 2H]   [top-down ; bottom-up] embedding of every node
- *   out_pooled    dev [B, 3, G, H]  summed l_i outputs per (set, device group) */
+ *   out_pooled    dev [B, 3, G, H]  summed l_i outputs per (set, device group)
+ *   out_class     dev [N_tot] uint8 the node sets of Section 2.2 step 3 exactly as this pass's
+ *                                   pooling used them (coded as in pl_node_classes): taken from
+ *                                   the reachability bits that the message-passing kernels of this
+ *                                   very call left behind, not from a separate traversal */
 int pl_embed_forward_ex(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
                         const int32_t *cur_node, const pl_weights *w, float *out_logits,
                         float *out_probs, float *out_node_emb, float *out_pooled,
-                        void *stream);
+                        uint8_t *out_class, void *stream);
 
 /* ---- the MDP transition (Section 2.1) on the device, for every graph of the batch: an
  * action a is drawn from softmax(logits[b]) (Appendix A.7) by inverse CDF, i.e. the first

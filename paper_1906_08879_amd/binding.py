@@ -54,13 +54,14 @@ def load_library(path: Optional[str] = None):
         "pl_graph_batch_levels": (ctypes.c_int, [vp, i32p, i32p]),
         "pl_graph_batch_layout": (ctypes.c_int, [vp, i64p, i32p, i64p, i32p, i32p, i32p]),
         "pl_node_classes": (ctypes.c_int, [vp, vp, vp, vp]),
+        "pl_debug_node_classes": (ctypes.c_int, [vp, vp, vp, vp]),
         "pl_weights_count": (ctypes.c_size_t, [cfgp]),
         "pl_weights_create": (ctypes.c_int, [cfgp, ctypes.POINTER(ctypes.c_float),
                                              ctypes.c_size_t, ctypes.POINTER(vp)]),
         "pl_weights_destroy": (ctypes.c_int, [vp]),
         "pl_weights_set_path": (ctypes.c_int, [vp, ctypes.c_int32]),
         "pl_embed_forward": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp]),
-        "pl_embed_forward_ex": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "pl_embed_forward_ex": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "pl_episode_step": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, vp, ctypes.c_int32, vp, vp, vp,
                                            vp, vp, vp]),
         "pl_episode_run": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
@@ -226,7 +227,7 @@ def node_classes(g: GraphBatch, cur_node, out_class, stream=None):
 
 
 def embed_forward(g: GraphBatch, node_feats, placement, cur_node, w: Weights, out_logits,
-                  out_probs=None, out_node_emb=None, out_pooled=None, stream=None):
+                  out_probs=None, out_node_emb=None, out_pooled=None, stream=None, out_class=None):
     """pl_embed_forward / pl_embed_forward_ex on device tensors; asynchronous on `stream`
     (default: torch's current stream)."""
     import torch
@@ -237,13 +238,14 @@ def embed_forward(g: GraphBatch, node_feats, placement, cur_node, w: Weights, ou
             _dev_ptr(cur_node, torch.int32, g.B, "cur_node"),
             w._h,
             _dev_ptr(out_logits, torch.float32, g.B * w.D, "out_logits")]
-    if out_probs is None and out_node_emb is None and out_pooled is None:
+    if out_probs is None and out_node_emb is None and out_pooled is None and out_class is None:
         _check(lib.pl_embed_forward(*args, _stream_ptr(stream)), "pl_embed_forward")
     else:
         _check(lib.pl_embed_forward_ex(
             *args, _dev_ptr(out_probs, torch.float32, g.B * w.D, "out_probs"),
             _dev_ptr(out_node_emb, torch.float32, g.n_tot * 2 * w.H, "out_node_emb"),
             _dev_ptr(out_pooled, torch.float32, g.B * 3 * w.G * w.H, "out_pooled"),
+            _dev_ptr(out_class, torch.uint8, g.n_tot, "out_class"),
             _stream_ptr(stream)), "pl_embed_forward_ex")
     return out_logits
 

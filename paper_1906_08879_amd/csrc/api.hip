@@ -3,6 +3,7 @@
 // steps 1-3 and the policy head of Appendix A.7).
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -162,9 +163,22 @@ void round_layer(std::vector<float> &blob, const LayerRef &r)
         blob[r.w + i] = round_bf16(blob[r.w + i]);
 }
 
+int upload_batch(pl_graph_batch *g);
+
+// Device copies of the batch's index data, made once.  Host allocations of the conversion are
+// guarded: no exception crosses the C boundary.
 int ensure_on_device(pl_graph_batch *g)
 {
     if (g->on_device) return PL_OK;
+    try {
+        return upload_batch(g);
+    } catch (const std::bad_alloc &) {
+        return fail(PL_ERR_NOMEM, "out of host memory");
+    }
+}
+
+int upload_batch(pl_graph_batch *g)
+{
     const HostLayout &L = g->host;
     PL_HIP(hipGetDevice(&g->device));
     std::vector<int32_t> node_off(L.node_off.begin(), L.node_off.end());
@@ -234,15 +248,39 @@ int ensure_on_device(pl_graph_batch *g)
 
 void free_workspace(Workspace &ws)
 {
-    (void)hipFree(ws.emb);
-    (void)hipFree(ws.msg);
-    (void)hipFree(ws.xb);
-    (void)hipFree(ws.featb);
+    (void)hipFree(ws.base);
     (void)hipFree(ws.reach);
-    (void)hipFree(ws.partial);
-    (void)hipFree(ws.zbuf);
-    (void)hipFree(ws.hidp);
     ws = Workspace();
+}
+
+// Lays the intermediate buffers of one forward pass out in one block starting at `base` (which
+// may be null: then only the size is computed) and returns the block's size in bytes.  Every
+// buffer starts on a 256-byte boundary.  With `with_reach` the reachability bytes are part of
+// the block, otherwise ws->reach is left alone.
+// Rows past the data (matrix-core sweep): emb row n, msg row 2n + 1, xb row 2n and reach byte
+// 2n + 1 take the stores of a chunk's unused rows; msg row 2n and reach byte 2n are never
+// written, must read as zero, and are the target of dummy loads.
+size_t carve_workspace(unsigned char *base, size_t n, size_t B, const ModelView &mv, bool with_reach, Workspace *ws)
+{
+    size_t at = 0;
+    auto take = [&](size_t bytes) {
+        unsigned char *p = base ? base + at : nullptr;
+        at += (bytes + 255) / 256 * 256;
+        return p;
+    };
+    const size_t H = mv.H;
+    ws->n_chunks = 8;
+    ws->emb = reinterpret_cast<float *>(take(sizeof(float) * ((n + 1) * 2 * H + 4)));
+    ws->msg = reinterpret_cast<float *>(take(sizeof(float) * ((2 * n + 2) * H + 4)));
+    ws->xb = reinterpret_cast<float *>(take(sizeof(float) * ((2 * n + 1) * H + 4)));
+    ws->featb = reinterpret_cast<float4 *>(take(sizeof(float4) * (2 * n + 1)));
+    ws->partial = reinterpret_cast<float *>(take(sizeof(float) * (B * ws->n_chunks * 3 * mv.G * H + 4)));
+    ws->zbuf = reinterpret_cast<float *>(take(sizeof(float) * (B * mv.Z + 4)));
+    ws->hidp = reinterpret_cast<double *>(take(sizeof(double) * (static_cast<size_t>((mv.Z + 255) / 256) * B * H + 4)));
+    if (with_reach) ws->reach = take(2 * n + 32);
+    ws->H = mv.H;
+    ws->G = mv.G;
+    return at;
 }
 
 void free_grad_workspace(GradWorkspace &gw)
@@ -275,26 +313,16 @@ int ensure_workspace(pl_graph_batch *g, const ModelView &mv)
     ws.reach = nullptr;
     free_workspace(ws);
     ws.reach = keep;
-    const size_t n = static_cast<size_t>(g->host.n_tot), H = mv.H;
+    const size_t n = static_cast<size_t>(g->host.n_tot), B = static_cast<size_t>(g->host.B);
     int rc = ensure_reach(g);
     if (rc) return rc;
-    // Rows past the data (matrix-core sweep): emb row n, msg row 2n + 1, xb row 2n and reach
-    // byte 2n + 1 take the stores of a chunk's unused rows; msg row 2n and reach byte 2n are
-    // never written and are the target of dummy loads.
-    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.emb), sizeof(float) * ((n + 1) * 2 * H + 4)));
-    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.msg), sizeof(float) * ((2 * n + 2) * H + 4)));
-    PL_HIP(hipMemset(ws.msg, 0, sizeof(float) * ((2 * n + 2) * H + 4)));
-    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.xb), sizeof(float) * ((2 * n + 1) * H + 4)));
-    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.featb), sizeof(float4) * (2 * n + 1)));
-    ws.n_chunks = 8;
-    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.partial),
-                     sizeof(float) * (static_cast<size_t>(g->host.B) * ws.n_chunks * 3 * mv.G * H + 4)));
-    const size_t B = static_cast<size_t>(g->host.B);
-    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.zbuf), sizeof(float) * (B * mv.Z + 4)));
-    PL_HIP(hipMalloc(reinterpret_cast<void **>(&ws.hidp),
-                     sizeof(float) * (static_cast<size_t>((mv.Z + 255) / 256) * B * H + 4)));
-    ws.H = mv.H;
-    ws.G = mv.G;
+    Workspace sized;
+    const size_t bytes = carve_workspace(nullptr, n, B, mv, false, &sized);
+    unsigned char *base = nullptr;
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&base), bytes));
+    ws.base = base;
+    carve_workspace(base, n, B, mv, false, &ws);
+    PL_HIP(hipMemset(ws.msg, 0, sizeof(float) * ((2 * n + 2) * mv.H + 4)));
     return PL_OK;
 }
 
@@ -349,6 +377,54 @@ int ensure_grad_workspace(pl_graph_batch *g, const ModelView &mv)
     gw.G = mv.G;
     gw.L = mv.L;
     gw.D = mv.D;
+    return PL_OK;
+}
+
+// PL_VALIDATE=1 in the environment: the device-resident state of a call is copied to the host
+// and range-checked before any kernel is launched (a debugging aid: it synchronises the stream).
+bool validate_enabled()
+{
+    const char *e = std::getenv("PL_VALIDATE");
+    return e && e[0] == '1' && e[1] == '\0';
+}
+
+// allow_finished: a cur_node of -1 (the marker pl_episode_step leaves when a graph's episode is
+// over) is accepted, and so is an action of -1 for such a graph.
+int validate_state(const pl_graph_batch *g, int D, const int32_t *placement, const int32_t *cur_node,
+                   const int32_t *actions, bool allow_finished, hipStream_t s)
+{
+    try {
+        const HostLayout &L = g->host;
+        std::vector<int32_t> pl_h(static_cast<size_t>(L.n_tot)), cur_h(static_cast<size_t>(L.B)), act_h;
+        PL_HIP(hipStreamSynchronize(s));
+        if (placement)
+            PL_HIP(hipMemcpy(pl_h.data(), placement, sizeof(int32_t) * pl_h.size(), hipMemcpyDeviceToHost));
+        if (cur_node)
+            PL_HIP(hipMemcpy(cur_h.data(), cur_node, sizeof(int32_t) * cur_h.size(), hipMemcpyDeviceToHost));
+        if (actions) {
+            act_h.resize(static_cast<size_t>(L.B));
+            PL_HIP(hipMemcpy(act_h.data(), actions, sizeof(int32_t) * act_h.size(), hipMemcpyDeviceToHost));
+        }
+        if (placement)
+            for (int64_t v = 0; v < L.n_tot; ++v)
+                if (pl_h[v] < 0 || pl_h[v] >= D)
+                    return fail(PL_ERR_RANGE, "PL_VALIDATE: placement[" + std::to_string(v) + "] = " +
+                                                  std::to_string(pl_h[v]) + " is outside [0, " + std::to_string(D) + ")");
+        for (int32_t b = 0; b < L.B; ++b) {
+            const int64_t n_b = L.node_off[b + 1] - L.node_off[b];
+            const bool finished = allow_finished && cur_node && cur_h[b] == -1;
+            if (finished) continue;
+            if (cur_node && (cur_h[b] < 0 || cur_h[b] >= n_b))
+                return fail(PL_ERR_RANGE, "PL_VALIDATE: cur_node[" + std::to_string(b) + "] = " +
+                                              std::to_string(cur_h[b]) + " is outside the graph's " +
+                                              std::to_string(n_b) + " nodes");
+            if (actions && (act_h[b] < 0 || act_h[b] >= D))
+                return fail(PL_ERR_RANGE, "PL_VALIDATE: actions[" + std::to_string(b) + "] = " +
+                                              std::to_string(act_h[b]) + " is outside [0, " + std::to_string(D) + ")");
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(PL_ERR_NOMEM, "out of host memory");
+    }
     return PL_OK;
 }
 
@@ -410,21 +486,33 @@ void stage_mark(void *ctx, int stage, bool begin, hipStream_t s)
     }
 }
 
+// static_ws: the intermediate buffers of a call that must not allocate (the batch is on the
+// device already, stage timing is off); otherwise the batch's own buffers are used, allocated on
+// the first call.
 int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
                  const int32_t *cur_node, const pl_weights *w, float *out_logits, float *out_probs,
-                 float *out_node_emb, float *out_pooled, void *stream, float *keep = nullptr,
-                 size_t keep_stride = 0, float *keep_pool = nullptr, bool *pool_kept = nullptr,
-                 float *snap_emb = nullptr, float *snap_msg = nullptr)
+                 float *out_node_emb, float *out_pooled, uint8_t *out_class, void *stream, bool validate,
+                 float *keep = nullptr, size_t keep_stride = 0, float *keep_pool = nullptr,
+                 bool *pool_kept = nullptr, float *snap_emb = nullptr, float *snap_msg = nullptr,
+                 const Workspace *static_ws = nullptr)
 {
     if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
     if (g->host.B == 0) return PL_OK;
     if (!node_feats || !placement || !cur_node || !out_logits)
         return fail(PL_ERR_NULL, "node_feats, placement, cur_node and out_logits are required");
-    int rc = ensure_on_device(g);
-    if (rc) return rc;
-    const ModelView &mv = w->view;
-    if ((rc = ensure_workspace(g, mv))) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc;
+    if (validate && validate_enabled() &&
+        (rc = validate_state(g, w->cfg.D, placement, cur_node, nullptr, false, s)))
+        return rc;
+    const ModelView &mv = w->view;
+    if (!static_ws) {
+        if ((rc = ensure_on_device(g))) return rc;
+        if ((rc = ensure_workspace(g, mv))) return rc;
+    }
+    const Workspace &ws = static_ws ? *static_ws : g->ws;
+    StageTimer off;
+    StageTimer &timer = static_ws ? off : g->timer;
     ForwardArgs fa{node_feats, placement, cur_node, out_logits, out_probs, out_pooled};
     const GraphView &gv = g->view;
     // the matrix-core sweep addresses its buffers with 32-bit offsets
@@ -432,46 +520,49 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
     const bool mfma = w->d_wfrag && w->path == 0 && w->cfg.k_sweeps > 0 && fits32;
     {
         // the matrix-core sweep computes x_v itself from the raw features (first sweep)
-        StageScope scope(g->timer, PL_STAGE_PROJECT, s);
-        if (!mfma) launch_project(gv, mv, g->ws, fa, true, false, s);
+        StageScope scope(timer, PL_STAGE_PROJECT, s);
+        if (!mfma) launch_project(gv, mv, ws, fa, true, false, s);
     }
     {
-        StageScope scope(g->timer, PL_STAGE_SWEEP, s);
+        StageScope scope(timer, PL_STAGE_SWEEP, s);
         // without sweeps the node sets still need reachability from v*, unless there is one set
-        if (w->cfg.k_sweeps == 0 && !w->cfg.single_set) {
+        // (one set without sweeps needs none, unless the caller asks for the sets themselves)
+        if (w->cfg.k_sweeps == 0 && (!w->cfg.single_set || out_class)) {
             const GraphExtent x = graph_extent(g->host);
-            launch_reach_only(gv, cur_node, g->ws.reach, x.n_max, x.e_max, g->host.max_depth, s);
+            launch_reach_only(gv, cur_node, ws.reach, x.n_max, x.e_max, g->host.max_depth, s);
         }
         for (int k = 0; k < w->cfg.k_sweeps; ++k) {
             if (mfma)
-                launch_sweep_mfma(gv, mv, g->ws, fa, reinterpret_cast<const uint4 *>(w->d_wfrag),
+                launch_sweep_mfma(gv, mv, ws, fa, reinterpret_cast<const uint4 *>(w->d_wfrag),
                                   w->d_sweep_bias, w->sweep_ws, k == 0, k + 1 < w->cfg.k_sweeps, keep, keep_stride, s);
             else
-                launch_sweep_generic(gv, mv, g->ws, fa, k == 0, s);
+                launch_sweep_generic(gv, mv, ws, fa, k == 0, s);
             if (snap_emb && k + 1 < w->cfg.k_sweeps) {
                 // the reverse pass of a multi-sweep network needs the states and messages after this sweep
                 const size_t span = static_cast<size_t>(g->host.n_tot) * 2 * mv.H;
-                PL_HIP(hipMemcpyAsync(snap_emb + k * span, g->ws.emb, sizeof(float) * span, hipMemcpyDeviceToDevice, s));
-                PL_HIP(hipMemcpyAsync(snap_msg + k * span, g->ws.msg, sizeof(float) * span, hipMemcpyDeviceToDevice, s));
+                PL_HIP(hipMemcpyAsync(snap_emb + k * span, ws.emb, sizeof(float) * span, hipMemcpyDeviceToDevice, s));
+                PL_HIP(hipMemcpyAsync(snap_msg + k * span, ws.msg, sizeof(float) * span, hipMemcpyDeviceToDevice, s));
             }
         }
     }
+    // the node sets as the pooling below reads them: from the reachability bits the sweeps left
+    if (out_class) launch_classes(gv, cur_node, ws.reach, out_class, s);
     const bool pool_mfma = w->d_pool_frag && w->path == 0;
     {
-        StageScope scope(g->timer, PL_STAGE_POOL, s);
+        StageScope scope(timer, PL_STAGE_POOL, s);
         if (pool_mfma)
-            launch_pool_mfma(gv, mv, g->ws, fa, reinterpret_cast<const uint4 *>(w->d_pool_frag),
+            launch_pool_mfma(gv, mv, ws, fa, reinterpret_cast<const uint4 *>(w->d_pool_frag),
                              w->d_pool_bias, w->sweep_ws, keep_pool, s);
         else
-            launch_pool_generic(gv, mv, g->ws, fa, s);
+            launch_pool_generic(gv, mv, ws, fa, s);
         if (pool_kept) *pool_kept = pool_mfma && keep_pool;
     }
     {
-        StageScope scope(g->timer, PL_STAGE_HEAD, s);
-        launch_head_generic(gv, mv, g->ws, fa, pool_mfma ? kPoolSlices : g->ws.n_chunks, s);
+        StageScope scope(timer, PL_STAGE_HEAD, s);
+        launch_head_generic(gv, mv, ws, fa, pool_mfma ? kPoolSlices : ws.n_chunks, s);
     }
     if (out_node_emb)
-        PL_HIP(hipMemcpyAsync(out_node_emb, g->ws.emb,
+        PL_HIP(hipMemcpyAsync(out_node_emb, ws.emb,
                               sizeof(float) * static_cast<size_t>(g->host.n_tot) * 2 * mv.H,
                               hipMemcpyDeviceToDevice, s));
     PL_HIP(hipGetLastError());
@@ -589,6 +680,11 @@ int pl_node_classes(pl_graph_batch *g, const int32_t *cur_node, uint8_t *out_cla
     launch_classes(g->view, cur_node, g->ws.reach, out_class, s);
     PL_HIP(hipGetLastError());
     return PL_OK;
+}
+
+int pl_debug_node_classes(pl_graph_batch *g, const int32_t *cur_node, uint8_t *out_class, void *stream)
+{
+    return pl_node_classes(g, cur_node, out_class, stream);
 }
 
 size_t pl_weights_count(const pl_model_cfg *cfg)
@@ -718,15 +814,16 @@ int pl_embed_forward(pl_graph_batch *g, const float *node_feats, const int32_t *
                      const int32_t *cur_node, const pl_weights *w, float *out_logits, void *stream)
 {
     return forward_impl(g, node_feats, placement, cur_node, w, out_logits, nullptr, nullptr,
-                        nullptr, stream);
+                        nullptr, nullptr, stream, true);
 }
 
 int pl_embed_forward_ex(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
                         const int32_t *cur_node, const pl_weights *w, float *out_logits,
-                        float *out_probs, float *out_node_emb, float *out_pooled, void *stream)
+                        float *out_probs, float *out_node_emb, float *out_pooled, uint8_t *out_class,
+                        void *stream)
 {
     return forward_impl(g, node_feats, placement, cur_node, w, out_logits, out_probs, out_node_emb,
-                        out_pooled, stream);
+                        out_pooled, out_class, stream, true);
 }
 
 int pl_episode_step(pl_graph_batch *g, int32_t D, const float *logits, const float *uniforms,
@@ -756,10 +853,15 @@ int pl_episode_run(pl_graph_batch *g, const pl_weights *w, float *node_feats, in
     if (g->host.B == 0 || n_steps == 0) return PL_OK;
     if (!logits || !uniforms || !order || !node_feats || !placement || !cur_node)
         return fail(PL_ERR_NULL, "a required device array is NULL");
+    if (validate_enabled()) {
+        const int rc = validate_state(g, w->cfg.D, placement, cur_node, nullptr, true, static_cast<hipStream_t>(stream));
+        if (rc) return rc;
+    }
     const size_t B = static_cast<size_t>(g->host.B), D = static_cast<size_t>(w->cfg.D);
     for (int32_t i = 0; i < n_steps; ++i) {
         float *l = keep_logits ? logits + static_cast<size_t>(i) * B * D : logits;
-        int rc = forward_impl(g, node_feats, placement, cur_node, w, l, nullptr, nullptr, nullptr, stream);
+        int rc = forward_impl(g, node_feats, placement, cur_node, w, l, nullptr, nullptr, nullptr, nullptr, stream,
+                              false);
         if (rc) return rc;
         launch_episode_step(g->view, w->cfg.D, l, uniforms + static_cast<size_t>(i) * B, order, t0 + i,
                             node_feats, placement, cur_node, out_actions ? out_actions + static_cast<size_t>(i) * B : nullptr,
@@ -786,6 +888,12 @@ int pl_reinforce_coeff(int32_t T, int32_t B, const float *rewards, const int32_t
     return PL_OK;
 }
 
+static int policy_gradient_impl(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                                const int32_t *cur_node, const pl_weights *w, const int32_t *actions,
+                                const float *coeff, const float *entropy_coeff, int32_t accumulate, float *grad,
+                                float *out_logits, float *out_logp, float *out_entropy, void *stream,
+                                bool allow_finished);
+
 int pl_episode_gradient(pl_graph_batch *g, const pl_weights *w, float *node_feats, int32_t *placement,
                         int32_t *cur_node, const int32_t *order, const int32_t *actions, const float *coeff,
                         const float *entropy_coeff, int32_t t0, int32_t n_steps, int32_t accumulate, float *grad,
@@ -803,10 +911,10 @@ int pl_episode_gradient(pl_graph_batch *g, const pl_weights *w, float *node_feat
         return PL_OK;
     }
     for (int32_t i = 0; i < n_steps; ++i) {
-        int rc = pl_policy_gradient_ex(g, node_feats, placement, cur_node, w, actions + i * B, coeff + i * B,
-                                       entropy_coeff ? entropy_coeff + i * B : nullptr,
-                                       (accumulate || i > 0) ? 1 : 0, grad, logits,
-                                       out_logp ? out_logp + i * B : nullptr, nullptr, stream);
+        int rc = policy_gradient_impl(g, node_feats, placement, cur_node, w, actions + i * B, coeff + i * B,
+                                      entropy_coeff ? entropy_coeff + i * B : nullptr,
+                                      (accumulate || i > 0) ? 1 : 0, grad, logits,
+                                      out_logp ? out_logp + i * B : nullptr, nullptr, stream, true);
         if (rc) return rc;
         launch_episode_apply(g->view, w->cfg.D, actions + i * B, order, t0 + i, node_feats, placement, cur_node,
                              static_cast<hipStream_t>(stream));
@@ -824,17 +932,21 @@ int pl_policy_gradient(pl_graph_batch *g, const float *node_feats, const int32_t
                                  out_logits, out_logp, nullptr, stream);
 }
 
-int pl_policy_gradient_ex(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
-                          const int32_t *cur_node, const pl_weights *w, const int32_t *actions,
-                          const float *coeff, const float *entropy_coeff, int32_t accumulate, float *grad,
-                          float *out_logits, float *out_logp, float *out_entropy, void *stream)
+static int policy_gradient_impl(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                                const int32_t *cur_node, const pl_weights *w, const int32_t *actions,
+                                const float *coeff, const float *entropy_coeff, int32_t accumulate, float *grad,
+                                float *out_logits, float *out_logp, float *out_entropy, void *stream,
+                                bool allow_finished)
 {
     if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
     if (g->host.B == 0) return PL_OK;
     if (!node_feats || !placement || !cur_node || !actions || !coeff || !grad || !out_logits)
         return fail(PL_ERR_NULL, "a required device array is NULL");
-    int rc = ensure_on_device(g);
-    if (rc) return rc;
+    int rc;
+    if (validate_enabled() && (rc = validate_state(g, w->cfg.D, placement, cur_node, actions, allow_finished,
+                                                   static_cast<hipStream_t>(stream))))
+        return rc;
+    if ((rc = ensure_on_device(g))) return rc;
     const ModelView &mv = w->view;
     if ((rc = ensure_grad_workspace(g, mv))) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -857,8 +969,8 @@ int pl_policy_gradient_ex(pl_graph_batch *g, const float *node_feats, const int3
     }
     // likewise the matrix-core pooling kernel keeps the outputs of l's layers
     bool pool_kept = false;
-    rc = forward_impl(g, node_feats, placement, cur_node, w, out_logits, nullptr, nullptr, g->gw.pooled, stream,
-                      keep, g->gw.dfg_stride, w->path == 0 ? g->gw.lact : nullptr, &pool_kept,
+    rc = forward_impl(g, node_feats, placement, cur_node, w, out_logits, nullptr, nullptr, g->gw.pooled, nullptr,
+                      stream, false, keep, g->gw.dfg_stride, w->path == 0 ? g->gw.lact : nullptr, &pool_kept,
                       w->cfg.k_sweeps > 1 ? g->gw.snap_emb : nullptr, g->gw.snap_msg);
     if (rc) return rc;
     if (!accumulate) launch_fill_zero(grad, plan_weights(w->cfg, nullptr), s);
@@ -870,6 +982,15 @@ int pl_policy_gradient_ex(pl_graph_batch *g, const float *node_feats, const int3
                     w->sweep_ws, keep, pool_kept, &marks, s);
     PL_HIP(hipGetLastError());
     return PL_OK;
+}
+
+int pl_policy_gradient_ex(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                          const int32_t *cur_node, const pl_weights *w, const int32_t *actions,
+                          const float *coeff, const float *entropy_coeff, int32_t accumulate, float *grad,
+                          float *out_logits, float *out_logp, float *out_entropy, void *stream)
+{
+    return policy_gradient_impl(g, node_feats, placement, cur_node, w, actions, coeff, entropy_coeff, accumulate,
+                                grad, out_logits, out_logp, out_entropy, stream, false);
 }
 
 int pl_simulate_runtime(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,

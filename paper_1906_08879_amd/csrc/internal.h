@@ -90,8 +90,27 @@ struct ModelView {
     LayerRef pol1, pol2;
 };
 
+// ---- the policy network's hidden unit j and logit d of graph b (Appendix A.7), in float64 from
+// the partial products of its first layer; one definition for the forward and the reverse pass.
+__device__ __forceinline__ double policy_hidden(const ModelView &mv, const double *__restrict__ hidp,
+                                                int n_slices, int B, int b, int j)
+{
+    double s = static_cast<double>(mv.blob[mv.pol1.b + j]);
+    for (int sl = 0; sl < n_slices; ++sl) s += hidp[(static_cast<size_t>(sl) * B + b) * mv.H + j];
+    return s > 0.0 ? s : 0.0;
+}
+
+__device__ __forceinline__ float policy_logit(const ModelView &mv, const double *hid, int d)
+{
+    const float *W = mv.blob + mv.pol2.w;
+    double s = static_cast<double>(mv.blob[mv.pol2.b + d]);
+    for (int k = 0; k < mv.H; ++k) s = fma(hid[k], static_cast<double>(W[k * mv.D + d]), s);
+    return static_cast<float>(s);
+}
+
 // ---- scratch owned by a batch for one (D, H)
 struct Workspace {
+    unsigned char *base = nullptr;  // the one allocation that holds every buffer but reach (null: not owned)
     float *emb = nullptr;       // [n_tot, 2H]  [td ; bu]
     float *msg = nullptr;       // [2, n_tot, H]
     float *xb = nullptr;        // [2, n_tot, H]  sweep input in bucket order (matrix-core path)
@@ -99,7 +118,7 @@ struct Workspace {
     uint8_t *reach = nullptr;   // [2, n_tot]   0: descendant-of-v* bit, 1: ancestor-of-v* bit
     float *partial = nullptr;   // [B, n_chunks_max, 3G, H] pooling partial sums
     float *zbuf = nullptr;      // [B, Z] policy inputs
-    float *hidp = nullptr;      // [ceil(Z / 256), B, H] partial products of policy layer 1
+    double *hidp = nullptr;     // [ceil(Z / 256), B, H] partial products of policy layer 1 (float64 sums)
     int32_t *chunk_off = nullptr; // [B+1] first pooling chunk of each graph
     int32_t n_chunks = 0;
     int32_t H = 0, G = 0;

@@ -90,7 +90,7 @@ __device__ __forceinline__ size_t slab(int dir, int l, int L, int n_tot, int H)
 // A graph whose current node or action is out of range gets a zero gradient and logp = NaN.
 __global__ __launch_bounds__(kThreads) void k_bw_head(GraphView gv, ModelView mv,
                                                       const float *__restrict__ blob_t,
-                                                      const float *__restrict__ hidp, int n_slices,
+                                                      const double *__restrict__ hidp, int n_slices,
                                                       const int32_t *__restrict__ cur_node,
                                                       const int32_t *__restrict__ actions,
                                                       const float *__restrict__ coeff,
@@ -102,6 +102,7 @@ __global__ __launch_bounds__(kThreads) void k_bw_head(GraphView gv, ModelView mv
                                                       float *__restrict__ dz,
                                                       float *__restrict__ out_logp)
 {
+    __shared__ double hid64[kMaxH];
     __shared__ float hid[kMaxH];
     __shared__ float dpre[kMaxH];
     __shared__ float logit[kMaxD];
@@ -111,17 +112,11 @@ __global__ __launch_bounds__(kThreads) void k_bw_head(GraphView gv, ModelView mv
     const int cl = cur_node[b];
     const bool cur_ok = cl >= 0 && cl < n_b;
     for (int j = tid; j < H; j += kThreads) {
-        float s = mv.blob[mv.pol1.b + j];
-        for (int sl = 0; sl < n_slices; ++sl) s += hidp[(static_cast<size_t>(sl) * gv.B + b) * H + j];
-        hid[j] = fmaxf(s, 0.0f);
+        hid64[j] = policy_hidden(mv, hidp, n_slices, gv.B, b, j);
+        hid[j] = static_cast<float>(hid64[j]);
     }
     __syncthreads();
-    if (tid < D) {
-        const float *W = mv.blob + mv.pol2.w;
-        float s = mv.blob[mv.pol2.b + tid];
-        for (int k = 0; k < H; ++k) s = fmaf(hid[k], W[k * D + tid], s);
-        logit[tid] = s;
-    }
+    if (tid < D) logit[tid] = policy_logit(mv, hid64, tid);
     __syncthreads();
     if (tid == 0) {
         float mx = logit[0];

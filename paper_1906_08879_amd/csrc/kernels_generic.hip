@@ -466,10 +466,14 @@ __global__ __launch_bounds__(kThreads) void k_head_sets(GraphView gv, ModelView 
 
 // (2) workgroup (row tile, slice): partial products of policy layer 1 for 16 graphs and one
 // slice of z: hidp[slice][b][j] = sum over k in the slice of z[b][k] W1[k][j].
+// The two policy layers accumulate in float64 (products of two fp32 values are exact there):
+// z holds sums over thousands of nodes, so a logit is a difference of terms far larger than
+// itself, and an fp32 sum over the (2 + 3G) H inputs alone would cost about 1e-6 of the
+// largest logit of the graph, ten times what the rest of the pass contributes.
 template <int RPT>
 __global__ __launch_bounds__(kThreads) void k_head_policy1(ModelView mv, int B,
                                                            const float *__restrict__ zbuf,
-                                                           float *__restrict__ hidp)
+                                                           double *__restrict__ hidp)
 {
     __shared__ float x[kTile][kZSlice];
     const int H = mv.H, Z = mv.Z, tid = threadIdx.x;
@@ -486,11 +490,11 @@ __global__ __launch_bounds__(kThreads) void k_head_policy1(ModelView mv, int B,
     if (groups > kTile) groups = kTile;
     const int grp = tid / H, j = tid - grp * H;
     if (grp >= groups || grp >= rows) return;
-    float acc[RPT];
+    double acc[RPT];
     int xoff[RPT];
 #pragma unroll
     for (int i = 0; i < RPT; ++i) {
-        acc[i] = 0.0f;
+        acc[i] = 0.0;
         xoff[i] = min(grp + i * groups, rows - 1) * kZSlice;
     }
     const float *W = mv.blob + mv.pol1.w + static_cast<size_t>(k0) * H;
@@ -498,18 +502,18 @@ __global__ __launch_bounds__(kThreads) void k_head_policy1(ModelView mv, int B,
     constexpr int KB = 16;      // weights per batch of loads, as in dense_layer
     int k = 0;
     for (; k + KB <= kn; k += KB) {
-        float w[KB];
+        double w[KB];
 #pragma unroll
-        for (int u = 0; u < KB; ++u) w[u] = W[static_cast<size_t>(k + u) * H + j];
+        for (int u = 0; u < KB; ++u) w[u] = static_cast<double>(W[static_cast<size_t>(k + u) * H + j]);
 #pragma unroll
         for (int u = 0; u < KB; ++u)
 #pragma unroll
-            for (int i = 0; i < RPT; ++i) acc[i] = fmaf(xf[xoff[i] + k + u], w[u], acc[i]);
+            for (int i = 0; i < RPT; ++i) acc[i] = fma(static_cast<double>(xf[xoff[i] + k + u]), w[u], acc[i]);
     }
     for (; k < kn; ++k) {
-        const float w = W[static_cast<size_t>(k) * H + j];
+        const double w = static_cast<double>(W[static_cast<size_t>(k) * H + j]);
 #pragma unroll
-        for (int i = 0; i < RPT; ++i) acc[i] = fmaf(xf[xoff[i] + k], w, acc[i]);
+        for (int i = 0; i < RPT; ++i) acc[i] = fma(static_cast<double>(xf[xoff[i] + k]), w, acc[i]);
     }
 #pragma unroll
     for (int i = 0; i < RPT; ++i) {
@@ -519,30 +523,23 @@ __global__ __launch_bounds__(kThreads) void k_head_policy1(ModelView mv, int B,
 }
 
 // (3) one workgroup per graph: hidden = relu(sum of the slices + bias), output layer, softmax.
+// policy_hidden / policy_logit (internal.h) are shared with the reverse pass, which forms the same
+// logits again and must get the same bits.
 __global__ __launch_bounds__(64) void k_head_out(GraphView gv, ModelView mv,
-                                                 const float *__restrict__ hidp, int n_slices,
+                                                 const double *__restrict__ hidp, int n_slices,
                                                  const int32_t *__restrict__ cur_node,
                                                  float *__restrict__ out_logits,
                                                  float *__restrict__ out_probs)
 {
-    __shared__ float hid[kMaxH];
+    __shared__ double hid[kMaxH];
     __shared__ float logit[kMaxD];
     const int H = mv.H, D = mv.D, b = blockIdx.x, tid = threadIdx.x;
     const int n_b = gv.node_off[b + 1] - gv.node_off[b];
     const int cl = cur_node[b];
     const bool cur_ok = cl >= 0 && cl < n_b;
-    for (int j = tid; j < H; j += 64) {
-        float s = mv.blob[mv.pol1.b + j];
-        for (int sl = 0; sl < n_slices; ++sl) s += hidp[(static_cast<size_t>(sl) * gv.B + b) * H + j];
-        hid[j] = fmaxf(s, 0.0f);
-    }
+    for (int j = tid; j < H; j += 64) hid[j] = policy_hidden(mv, hidp, n_slices, gv.B, b, j);
     __syncthreads();
-    if (tid < D) {
-        const float *W = mv.blob + mv.pol2.w;
-        float s = mv.blob[mv.pol2.b + tid];
-        for (int k = 0; k < H; ++k) s = fmaf(hid[k], W[k * D + tid], s);
-        logit[tid] = s;
-    }
+    if (tid < D) logit[tid] = policy_logit(mv, hid, tid);
     __syncthreads();
     if (tid == 0) {
         float mx = logit[0];

@@ -3,10 +3,11 @@
 // directions, and per-graph level buckets.
 //
 // Section 2 of the paper models a network as a DAG whose ops receive tensors from their
-// parent ops; Section 2.2 step 2 passes messages "top-down from root groups and bottom-up
-// from leaf groups".  A node's level is the length of the longest path from a root
-// (top-down) or to a leaf (bottom-up), so every neighbour a node aggregates over sits on a
-// strictly lower level and is final before the node is visited.
+// parent ops; the message passing of Section 2.2 step 2 runs in two directions, one starting
+// at the nodes without parents and one starting at the nodes without children.  A node's
+// level is the length of the longest path from a root (top-down) or to a leaf (bottom-up), so
+// every neighbour a node aggregates over sits on a strictly lower level and is final before
+// the node is visited.
 #include <algorithm>
 #include <cstdint>
 #include <numeric>

@@ -5,8 +5,10 @@ import numpy as np
 RTOL, ATOL = 1e-4, 1e-5     # fp32 logits vs the float64 oracle
 
 
-def run_library(w, placement=None, cur_node=None, done=None, want_emb=True, handles=None, path=0):
-    """One forward pass of workload `w` on cuda:0.  Returns dict of numpy arrays."""
+def run_library(w, placement=None, cur_node=None, done=None, want_emb=True, handles=None, path=0,
+                want_class=False):
+    """One forward pass of workload `w` on cuda:0.  Returns dict of numpy arrays.  With
+    want_class the node sets that this very pass pooled over come back as `classes`."""
     import torch
     import paper_1906_08879_amd as pl
     dev = torch.device("cuda:0")
@@ -31,10 +33,12 @@ def run_library(w, placement=None, cur_node=None, done=None, want_emb=True, hand
     probs = torch.full((w.B, w.D), float("nan"), dtype=torch.float32, device=dev)
     pooled = torch.full((w.B, 3, G, w.H), float("nan"), dtype=torch.float32, device=dev)
     emb = torch.full((w.n_tot, 2 * w.H), float("nan"), dtype=torch.float32, device=dev) if want_emb else None
-    pl.embed_forward(g, t_feats, t_place, t_cur, wt, logits, probs, emb, pooled)
+    cls = torch.full((w.n_tot,), 255, dtype=torch.uint8, device=dev) if want_class else None
+    pl.embed_forward(g, t_feats, t_place, t_cur, wt, logits, probs, emb, pooled, out_class=cls)
     torch.cuda.synchronize()
     out = dict(logits=logits.cpu().numpy(), probs=probs.cpu().numpy(), pooled=pooled.cpu().numpy(),
-               emb=None if emb is None else emb.cpu().numpy())
+               emb=None if emb is None else emb.cpu().numpy(),
+               classes=None if cls is None else cls.cpu().numpy())
     if handles is None:
         g.close()
         wt.close()
@@ -62,21 +66,65 @@ def logit_errors(got, ref):
                 n_elem_fail=int(np.sum(elem > 1.0)))
 
 
-def assert_logits_close(got, ref, what=""):
+def assert_logits_close(got, ref, what="", max_fail_frac=0.0):
     """The bar for fp32 logits against the float64 oracle: 1e-4 relative + 1e-5 absolute.
 
-    It is applied (a) to every graph's logit vector in the max norm and (b) literally, per
-    element, to every logit that is not small against its own row (|ref| >= 0.1 max|ref|).
-    A logit that the last linear layer forms by cancellation (|ref| << the terms it sums)
-    cannot meet a bound relative to its own size in fp32 arithmetic: its error is set by
-    the row's scale.  Such elements are counted and reported, not hidden: `n_elem_fail`."""
+    It is applied (a) to every graph's logit vector in the max norm, (b) literally, per
+    element, to every logit that is not small against its own row (|ref| >= 0.1 max|ref|),
+    and (c) literally to every other element too, except for at most `max_fail_frac` of all
+    elements.  (c) is 0 unless the caller states a ceiling: with raw feature scales (output
+    sizes about e^10) a logit that the last linear layer forms by cancellation (|ref| << the
+    terms it sums) cannot meet a bound relative to its own size in fp32 arithmetic, its error
+    is set by the row's scale; the tests on such inputs state the measured fraction as their
+    ceiling, and the same graphs with features scaled to O(1) are held to the literal bound
+    on every element."""
     assert np.isfinite(got).all(), f"{what}: non-finite logits"
     e = logit_errors(got, ref)
     msg = (f"{what}: row-norm ratio {e['row']:.3g}, per-element ratio {e['elem']:.3g} "
            f"({e['n_elem_fail']} of {np.size(ref)} elements outside the literal bound), "
            f"worst error {e['scale']:.3g} of the row scale")
     assert e["row"] <= 1.0 and e["big"] <= 1.0, msg
+    assert e["n_elem_fail"] <= max_fail_frac * np.size(ref), msg
     return e
+
+
+def row_error_ratio(got, ref, width):
+    """Worst over rows of max|err| / max|ref| where a row is `width` consecutive values of the
+    last axis (one direction's state of one node, one pooled vector): an error confined to one
+    node or one vector is measured against that node's own scale, not the batch's."""
+    ref = np.asarray(ref, dtype=np.float64).reshape(-1, width)
+    got = np.asarray(got, dtype=np.float64).reshape(-1, width)
+    if ref.size == 0:
+        return 0.0
+    scale = np.abs(ref).max(axis=1)
+    err = np.abs(got - ref).max(axis=1)
+    return float(np.max(err / np.maximum(scale, 1e-30) * (scale > 0) + (err > 0) * (scale == 0) * 1e30))
+
+
+ROW_TOL = 2e-5      # per-row bar of embeddings and pooled sums (see assert_rows_close)
+
+
+def assert_rows_close(got, ref, width, what="", tol=ROW_TOL):
+    """Embeddings [N, 2H] (width H: each direction's state of each node on its own) and pooled
+    sums [B, 3, G, H] (width H) against the oracle: every row within `tol` of its own largest
+    entry.  fp32 arithmetic with exact products and fp32 accumulation over a few hundred terms
+    of the row's scale gives errors of a few 1e-7 of that scale per layer; the bar leaves room
+    for the depth of the graphs (errors add up along a path), not for a dropped term."""
+    r = row_error_ratio(got, ref, width)
+    assert r <= tol, f"{what}: worst row error {r:.3g} of the row's own scale (bar {tol:g})"
+    return r
+
+
+def normalised(w):
+    """The same workload with run times and output sizes divided by their batch means, i.e.
+    features of order one (the paper states no normalisation; this is the test's own input)."""
+    import copy
+    v = copy.copy(w)
+    f = np.array(w.node_feats, dtype=np.float64, copy=True)
+    f[:, 0] /= f[:, 0].mean()
+    f[:, 1] /= f[:, 1].mean()
+    v.node_feats = f.astype(np.float32)
+    return v
 
 
 def assert_probs_close(got, ref_probs, ref_logits, what=""):
