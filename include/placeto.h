@@ -43,7 +43,8 @@ typedef enum {
     PL_ERR_DUP_EDGE = -5,   /* the same (src, dst) pair twice in one graph              */
     PL_ERR_CYCLE = -6,      /* the graph is not acyclic                                 */
     PL_ERR_HIP = -7,        /* a HIP runtime call failed (message has the HIP error)    */
-    PL_ERR_NOMEM = -8       /* host allocation failed                                   */
+    PL_ERR_NOMEM = -8,      /* host allocation failed                                   */
+    PL_ERR_STATE = -9       /* a handle is not in the state the call needs              */
 } pl_status;
 
 /* Network configuration.  Appendix A.7: the message-passing and aggregation networks are
@@ -159,6 +160,29 @@ int pl_embed_forward_ex(pl_graph_batch *g, const float *node_feats, const int32_
                         const int32_t *cur_node, const pl_weights *w, float *out_logits,
                         float *out_probs, float *out_node_emb, float *out_pooled,
                         uint8_t *out_class, void *stream);
+
+/* ---- for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid it): pl_embed_forward with its intermediate buffers
+ * (embeddings, messages, bucketed features, reachability bytes, pooling partial sums, policy
+ * inputs) in a fixed block of device memory that is part of the library image, 32 MiB per
+ * device (pl_embed_forward_static_limit), instead of buffers allocated on the batch's first call.
+ * It calls no hipMalloc / hipFree and creates no events; it only launches kernels on `stream`.
+ *   - The batch must be on the device already: pl_graph_batch_upload(g) makes the device copies
+ *     of the index data (it allocates; call it once at set-up, with the device current that the
+ *     later calls run on), else PL_ERR_STATE.  pl_weights handles are on the device from creation.
+ *   - pl_embed_forward_static_bytes(g, w) is the size the call needs, about
+ *     N_tot (24 H + 34) bytes; beyond the limit the call returns PL_ERR_SHAPE and launches nothing.
+ *   - Every call on a device uses that device's one block, which keeps the last call's contents
+ *     (what must read as zero is cleared by a small kernel at the start of each call): calls
+ *     that overlap in time on one device race, whatever batches they use; calls on one stream,
+ *     or otherwise ordered, are safe.  Stage timing (pl_profile_enable) does not cover it.
+ * Arguments and results as pl_embed_forward; out_probs [B, D] may be NULL. */
+int pl_graph_batch_upload(pl_graph_batch *g);
+size_t pl_embed_forward_static_limit(void);
+size_t pl_embed_forward_static_bytes(const pl_graph_batch *g, const pl_weights *w);
+int pl_embed_forward_static(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                            const int32_t *cur_node, const pl_weights *w, float *out_logits,
+                            float *out_probs, void *stream);
 
 /* ---- the MDP transition (Section 2.1) on the device, for every graph of the batch: an
  * action a is drawn from softmax(logits[b]) (Appendix A.7) by inverse CDF, i.e. the first

@@ -10,6 +10,10 @@ from .binding import (  # noqa: F401
     PlacetoError,
     Weights,
     embed_forward,
+    embed_forward_static,
+    embed_forward_static_bytes,
+    embed_forward_static_limit,
+    graph_batch_upload,
     episode_gradient,
     episode_run,
     episode_step,

@@ -62,6 +62,10 @@ def load_library(path: Optional[str] = None):
         "pl_weights_set_path": (ctypes.c_int, [vp, ctypes.c_int32]),
         "pl_embed_forward": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp]),
         "pl_embed_forward_ex": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "pl_graph_batch_upload": (ctypes.c_int, [vp]),
+        "pl_embed_forward_static_limit": (ctypes.c_size_t, []),
+        "pl_embed_forward_static_bytes": (ctypes.c_size_t, [vp, vp]),
+        "pl_embed_forward_static": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, vp]),
         "pl_episode_step": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, vp, ctypes.c_int32, vp, vp, vp,
                                            vp, vp, vp]),
         "pl_episode_run": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
@@ -247,6 +251,33 @@ def embed_forward(g: GraphBatch, node_feats, placement, cur_node, w: Weights, ou
             _dev_ptr(out_pooled, torch.float32, g.B * 3 * w.G * w.H, "out_pooled"),
             _dev_ptr(out_class, torch.uint8, g.n_tot, "out_class"),
             _stream_ptr(stream)), "pl_embed_forward_ex")
+    return out_logits
+
+
+def graph_batch_upload(g: GraphBatch):
+    """pl_graph_batch_upload: device copies of the batch's index data, made now."""
+    _check(load_library().pl_graph_batch_upload(g._h), "pl_graph_batch_upload")
+
+
+def embed_forward_static_limit() -> int:
+    return int(load_library().pl_embed_forward_static_limit())
+
+
+def embed_forward_static_bytes(g: GraphBatch, w: Weights) -> int:
+    return int(load_library().pl_embed_forward_static_bytes(g._h, w._h))
+
+
+def embed_forward_static(g: GraphBatch, node_feats, placement, cur_node, w: Weights, out_logits,
+                         out_probs=None, stream=None):
+    """pl_embed_forward_static on device tensors: the forward pass without any allocation."""
+    import torch
+    _check(load_library().pl_embed_forward_static(
+        g._h, _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
+        _dev_ptr(placement, torch.int32, g.n_tot, "placement"),
+        _dev_ptr(cur_node, torch.int32, g.B, "cur_node"), w._h,
+        _dev_ptr(out_logits, torch.float32, g.B * w.D, "out_logits"),
+        _dev_ptr(out_probs, torch.float32, g.B * w.D, "out_probs"), _stream_ptr(stream)),
+        "pl_embed_forward_static")
     return out_logits
 
 

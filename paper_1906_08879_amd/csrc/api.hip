@@ -11,6 +11,10 @@
 
 #include "internal.h"
 
+// Intermediate buffers of pl_embed_forward_static: device memory that exists from the moment the
+// library is loaded on a device, 32 MiB per device, shared by every call on that device.
+static __device__ __align__(256) unsigned char scratch[static_cast<size_t>(32) << 20];
+
 namespace pl {
 
 namespace {
@@ -569,6 +573,26 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
     return PL_OK;
 }
 
+// ---- intermediate buffers for callers that cannot allocate: one fixed block per device
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(32) << 20;
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of `scratch`, looked up once per device.
+int scratch_address(void **out)
+{
+    int dev = -1;
+    PL_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(PL_ERR_SHAPE, "device index beyond the supported range");
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        PL_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PL_OK;
+}
+
 }  // namespace
 }  // namespace pl
 
@@ -824,6 +848,58 @@ int pl_embed_forward_ex(pl_graph_batch *g, const float *node_feats, const int32_
 {
     return forward_impl(g, node_feats, placement, cur_node, w, out_logits, out_probs, out_node_emb,
                         out_pooled, out_class, stream, true);
+}
+
+int pl_graph_batch_upload(pl_graph_batch *g)
+{
+    if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
+    void *unused = nullptr;
+    int rc = scratch_address(&unused);
+    if (rc) return rc;
+    if (g->host.B == 0) return PL_OK;
+    return ensure_on_device(g);
+}
+
+size_t pl_embed_forward_static_limit(void) { return kStaticScratchBytes; }
+
+size_t pl_embed_forward_static_bytes(const pl_graph_batch *g, const pl_weights *w)
+{
+    if (!g || !w) return 0;
+    Workspace sized;
+    return carve_workspace(nullptr, static_cast<size_t>(g->host.n_tot), static_cast<size_t>(g->host.B), w->view,
+                           true, &sized);
+}
+
+int pl_embed_forward_static(pl_graph_batch *g, const float *node_feats, const int32_t *placement,
+                            const int32_t *cur_node, const pl_weights *w, float *out_logits,
+                            float *out_probs, void *stream)
+{
+    if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
+    if (g->host.B == 0) return PL_OK;
+    if (!g->on_device)
+        return fail(PL_ERR_STATE, "the batch is not on the device yet: call pl_graph_batch_upload first "
+                                  "(this entry point allocates nothing)");
+    int dev = -1;
+    PL_HIP(hipGetDevice(&dev));
+    if (dev != g->device) return fail(PL_ERR_STATE, "the batch lives on another device than the current one");
+    const size_t n = static_cast<size_t>(g->host.n_tot), B = static_cast<size_t>(g->host.B);
+    Workspace ws;
+    const size_t need = carve_workspace(nullptr, n, B, w->view, true, &ws);
+    if (need > kStaticScratchBytes)
+        return fail(PL_ERR_SHAPE, "this batch and model need " + std::to_string(need) +
+                                      " bytes of intermediate buffers, more than the fixed block of " +
+                                      std::to_string(kStaticScratchBytes) + " bytes: use pl_embed_forward");
+    void *ptr = nullptr;
+    int rc = scratch_address(&ptr);
+    if (rc) return rc;
+    carve_workspace(static_cast<unsigned char *>(ptr), n, B, w->view, true, &ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the block keeps the last call's contents: the rows and bytes that the kernels read as zero
+    // without ever writing them are cleared by a fill kernel (a memset node must not be captured)
+    launch_fill_zero(ws.msg + 2 * n * w->view.H, 2 * static_cast<size_t>(w->view.H), s);
+    launch_fill_zero(reinterpret_cast<float *>(ws.reach + (2 * n) / 4 * 4), 5, s);
+    return forward_impl(g, node_feats, placement, cur_node, w, out_logits, out_probs, nullptr, nullptr, nullptr,
+                        stream, false, nullptr, 0, nullptr, nullptr, nullptr, nullptr, &ws);
 }
 
 int pl_episode_step(pl_graph_batch *g, int32_t D, const float *logits, const float *uniforms,
