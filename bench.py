@@ -33,9 +33,9 @@ def sweep_algorithmic_bytes(n_tot: int, e_tot: int, H: int) -> int:
 
 
 def path_algorithmic_bytes(n_tot: int, e_tot: int, H: int) -> int:
-    """The whole path: the sweeps, one write of x (2 x 4H), one read of [td;bu] in pooling
-    (8H), raw features, placement and flags."""
-    return sweep_algorithmic_bytes(n_tot, e_tot, H) + n_tot * (16 * H + 12 + 4 + 2)
+    """The whole path: the sweeps, one read of [td;bu] in pooling (8H), raw features, placement
+    and flags: 4H (8 + 2 deg) per node plus indices."""
+    return sweep_algorithmic_bytes(n_tot, e_tot, H) + n_tot * (8 * H + 12 + 4 + 2)
 
 
 SWEEP_SOURCES = ("kernels_mfma.hip", "plan.cpp", "sweep_plan.h")
@@ -72,6 +72,38 @@ def measured_traffic(workload: str, batch: int, key: str = "sweep_traffic_bytes_
     return int(rec[key])
 
 
+def forward_only(pl, torch, w, steps: int, warmup: int) -> dict:
+    """ms per forward pass of workload `w` (one state), with its depth and stage times."""
+    import numpy as np
+    dev = torch.device("cuda:0")
+    g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+    wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+    f = torch.from_numpy(np.ascontiguousarray(w.node_feats, dtype=np.float32)).to(dev)
+    p = torch.from_numpy(np.ascontiguousarray(w.placement, dtype=np.int32)).to(dev)
+    c = torch.from_numpy(np.ascontiguousarray(w.cur_node, dtype=np.int32)).to(dev)
+    logits = torch.empty((w.B, w.D), dtype=torch.float32, device=dev)
+    for _ in range(warmup):
+        pl.embed_forward(g, f, p, c, wt, logits)
+    torch.cuda.synchronize()
+    g.profile_enable(True)
+    g.profile_read(reset=True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        pl.embed_forward(g, f, p, c, wt, logits)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    stages = g.profile_read(reset=True)
+    g.profile_enable(False)
+    sweep = stages["sweep"][0] / max(1, stages["sweep"][1])
+    out = {"B": int(w.B), "N_tot": int(w.n_tot), "H": w.H, "ms_per_step": round(1e3 * dt, 4),
+           "graph_steps_per_s": round(w.B / dt, 1), "levels": int(g.max_depth),
+           "sweep_ms": round(sweep, 4), "us_per_level": round(1e3 * sweep / max(1, int(g.max_depth)), 3),
+           "stage_ms": {k: round(v[0] / v[1], 4) for k, v in stages.items() if v[1]}}
+    g.close()
+    wt.close()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,6 +119,8 @@ def main() -> int:
     ap.add_argument("--group-by-device", type=int, default=1, choices=(0, 1))
     ap.add_argument("--single-set", type=int, default=0, choices=(0, 1))
     ap.add_argument("--grad-steps", type=int, default=4, help="timed reverse passes (reported beside the headline)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short forward-only runs of the other configurations")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain 1 GiB device copy five times and exit (reference for "
                          "scaling the FETCH_SIZE / WRITE_SIZE counters)")
@@ -177,6 +211,18 @@ def main() -> int:
                 # what actually bounds the sweep: one dependent step per level of the deepest graph
                 "levels": int(g.max_depth),
                 "us_per_level": round(1e3 * avg_launch_ms / max(1, int(g.max_depth)), 4)}
+
+    # a plain device copy of 1 GiB on the same GPU: what the published peak means in practice here
+    cp_a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+    cp_b = torch.empty_like(cp_a)
+    cp_b.copy_(cp_a)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        cp_b.copy_(cp_a)
+    torch.cuda.synchronize()
+    roofline["device_copy_GBs"] = round(5 * 2 * 4 * (1 << 28) / (time.perf_counter() - t0) / 1e9, 1)
+    del cp_a, cp_b
 
     # the same path driven as an episode (Section 2.1): forward pass + on-device transition per
     # step, enqueued without host synchronisation; reported beside the headline, not in it
@@ -281,6 +327,16 @@ def main() -> int:
                                                                 "backward_sha256", WGRAD_SOURCES)
                                     if default_variant else None}
 
+    # the other configurations, forward pass only, a few steps each: what bounds them is the number
+    # of dependent level steps (levels x time per level), not bandwidth
+    other = None
+    if default_variant and args.batch is None and not args.no_other_workloads:
+        other = {}
+        for name in ("random32", "layered200", "inception", "nmt", "nasnet"):
+            if name == args.workload:
+                continue
+            other[name] = forward_only(pl, torch, make_workload(name), 20, 3)
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
@@ -333,6 +389,7 @@ def main() -> int:
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
         "layout_build_ms": round(layout_build_ms, 2),
         "roofline": roofline,
+        "other_workloads": other,
         "episode": episode,
         "simulator": simulator,
         "gradient": gradient,

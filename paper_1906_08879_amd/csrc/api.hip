@@ -51,9 +51,22 @@ int upload(const std::vector<T> &host, T **dev)
 
 struct StageTimer {
     std::vector<hipEvent_t> ev[PL_STAGE_COUNT];   // start/stop pairs not yet read
+    std::vector<hipEvent_t> pool;                 // created events that are free for reuse
     double ms_sum[PL_STAGE_COUNT] = {};
     int64_t launches[PL_STAGE_COUNT] = {};
     bool on = false;
+
+    // An event from the pool (filled when timing is switched on, so that no event is created
+    // between two timed launches), or a new one when the pool is empty.
+    bool take(hipEvent_t *e)
+    {
+        if (!pool.empty()) {
+            *e = pool.back();
+            pool.pop_back();
+            return true;
+        }
+        return hipEventCreate(e) == hipSuccess;
+    }
 };
 
 }  // namespace
@@ -440,7 +453,7 @@ struct StageScope {
     {
         if (!t.on) return;
         hipEvent_t e;
-        if (hipEventCreate(&e) == hipSuccess) {
+        if (t.take(&e)) {
             (void)hipEventRecord(e, s);
             t.ev[stage].push_back(e);
         }
@@ -449,11 +462,11 @@ struct StageScope {
     {
         if (!t.on || (t.ev[stage].size() & 1u) == 0) return;
         hipEvent_t e;
-        if (hipEventCreate(&e) == hipSuccess) {
+        if (t.take(&e)) {
             (void)hipEventRecord(e, s);
             t.ev[stage].push_back(e);
         } else {
-            (void)hipEventDestroy(t.ev[stage].back());
+            t.pool.push_back(t.ev[stage].back());
             t.ev[stage].pop_back();
         }
     }
@@ -481,11 +494,11 @@ void stage_mark(void *ctx, int stage, bool begin, hipStream_t s)
     auto &ev = t.ev[stage];
     if (!begin && (ev.size() & 1u) == 0) return;    // no open pair
     hipEvent_t e;
-    if (hipEventCreate(&e) == hipSuccess) {
+    if (t.take(&e)) {
         (void)hipEventRecord(e, s);
         ev.push_back(e);
     } else if (!begin) {
-        (void)hipEventDestroy(ev.back());
+        t.pool.push_back(ev.back());
         ev.pop_back();
     }
 }
@@ -648,6 +661,7 @@ int pl_graph_batch_destroy(pl_graph_batch *g)
     for (float *p : {g->sim_start, g->sim_end, g->sim_arrival, g->sim_alloc, g->sim_free, g->sim_rt}) (void)hipFree(p);
     for (auto &v : g->timer.ev)
         for (hipEvent_t e : v) (void)hipEventDestroy(e);
+    for (hipEvent_t e : g->timer.pool) (void)hipEventDestroy(e);
     delete g;
     return PL_OK;
 }
@@ -1143,6 +1157,17 @@ int pl_profile_enable(pl_graph_batch *g, int32_t on)
 {
     if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
     g->timer.on = on != 0;
+    // events for a few hundred timed calls are created now, not between the launches they time
+    constexpr size_t kPooled = 2048;
+    try {
+        while (on && g->timer.pool.size() < kPooled) {
+            hipEvent_t e;
+            PL_HIP(hipEventCreate(&e));
+            g->timer.pool.push_back(e);
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(PL_ERR_NOMEM, "out of host memory");
+    }
     return PL_OK;
 }
 
@@ -1150,6 +1175,7 @@ int pl_profile_read(pl_graph_batch *g, double *ms_sum, int64_t *launches, int32_
 {
     if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
     StageTimer &t = g->timer;
+    try {
     for (int st = 0; st < PL_STAGE_COUNT; ++st) {
         auto &ev = t.ev[st];
         for (size_t i = 0; i + 1 < ev.size(); i += 2) {
@@ -1159,7 +1185,7 @@ int pl_profile_read(pl_graph_batch *g, double *ms_sum, int64_t *launches, int32_
             t.ms_sum[st] += ms;
             t.launches[st] += 1;
         }
-        for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+        for (hipEvent_t e : ev) t.pool.push_back(e);     // kept for the next timed calls
         ev.clear();
         if (ms_sum) ms_sum[st] = t.ms_sum[st];
         if (launches) launches[st] = t.launches[st];
@@ -1167,6 +1193,9 @@ int pl_profile_read(pl_graph_batch *g, double *ms_sum, int64_t *launches, int32_
             t.ms_sum[st] = 0.0;
             t.launches[st] = 0;
         }
+    }
+    } catch (const std::bad_alloc &) {
+        return fail(PL_ERR_NOMEM, "out of host memory");
     }
     return PL_OK;
 }
