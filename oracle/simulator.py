@@ -13,7 +13,16 @@ size / bandwidth.
 Readings where the paper is silent:
  * one run time per operation (the synthetic workloads have one cost per node, so all devices
    are alike);
- * an output tensor is sent once per destination device, however many children wait there;
+ * transfers per output tensor: the printed op-done handler walks the children of the finished
+   operation and enqueues the output for every child that sits on another device, and the
+   printed transfer-done handler then looks at the one operation that takes the tensor as its
+   input.  Read literally, an output needed by k children on one remote device crosses the bus
+   k times (`per_child=True`).  The default (`per_child=False`) sends it once per destination
+   device and releases every child waiting there when it arrives: a tensor that is on a device
+   is there for all its consumers, which is how the framework whose graphs the paper places
+   moves tensors between devices.  The two differ whenever several children of one operation
+   share a remote device; both are kept, pinned by hand-computed timelines, and the build's
+   other pieces (rewards, benchmarks) use the default;
  * operations without parents are queued in ascending node id at time 0; the children of a
    finished operation are visited in ascending node id;
  * events are taken in order of (timestamp, creation number); after every event the free
@@ -42,10 +51,11 @@ import numpy as np
 F = np.float32
 
 
-def simulate(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth, trace=None):
+def simulate(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth, trace=None, per_child=False):
     """Run time of one placement of one graph.  src/dst: edges (parent, child), graph-local
     ids.  Returns (runtime float32, n_events).  `trace`, if a list, receives
-    (kind, node, device, timestamp) per processed event."""
+    (kind, node, device, timestamp) per processed event.  per_child: one transfer per child on
+    another device (the printed handlers) instead of one per destination device."""
     src = np.asarray(src, dtype=np.int64)
     dst = np.asarray(dst, dtype=np.int64)
     cost = np.asarray(cost, dtype=F)
@@ -76,8 +86,8 @@ def simulate(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth, trace=No
                     trace.append(("start", o, d, float(now)))
         for d in range(D):
             if D + d not in ev and q_tr[d]:
-                o, dc = q_tr[d].popleft()
-                ev[D + d] = (F(now + F(out_bytes[o] * inv_bw)), seq, o, dc)
+                o, dc, child = q_tr[d].popleft()
+                ev[D + d] = (F(now + F(out_bytes[o] * inv_bw)), seq, o, (dc, child))
                 seq += 1
 
     wake(F(0.0))
@@ -99,13 +109,16 @@ def simulate(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth, trace=No
                     pend[c] -= 1
                     if pend[c] == 0:
                         q_op[pc].append(c)
+                elif per_child:
+                    q_tr[d].append((o, pc, c))          # one crossing for this child alone
                 elif pc not in sent:
                     sent.add(pc)
-                    q_tr[d].append((o, pc))
+                    q_tr[d].append((o, pc, -1))         # one crossing for every child on pc
         else:                              # transfer-done: o's output has arrived on device dc
+            dc, child = dc
             if trace is not None:
                 trace.append(("tr", o, dc, float(now)))
-            for c in children[o]:
+            for c in ([child] if per_child else children[o]):
                 if int(placement[c]) == dc:
                     pend[c] -= 1
                     if pend[c] == 0:
@@ -115,29 +128,36 @@ def simulate(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth, trace=No
     return last, n_events
 
 
-def timeline(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth):
+def timeline(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth, per_child=False):
     """The simulated timeline: (runtime, op_start [n], op_end [n], arrival [n, D]) with
     arrival[v, d] = time at which v's output reached device d over the bus (-1: it never went
-    there).  float32 timestamps as produced by `simulate`."""
+    there).  float32 timestamps as produced by `simulate`.  With per_child an output may reach a
+    device several times: arrival is then a pair (first [n, D], last [n, D])."""
     trace = []
-    runtime, _ = simulate(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth, trace)
+    runtime, _ = simulate(n, src, dst, cost, out_bytes, placement, D, inv_bandwidth, trace, per_child)
     op_start = np.full(n, -1.0, dtype=F)
     op_end = np.full(n, -1.0, dtype=F)
-    arrival = np.full((n, D), -1.0, dtype=F)
+    first = np.full((n, D), -1.0, dtype=F)
+    last = np.full((n, D), -1.0, dtype=F)
     for kind, o, d, t in trace:
         if kind == "start":
             op_start[o] = F(t)
         elif kind == "op":
             op_end[o] = F(t)
         else:
-            arrival[o, d] = F(t)
-    return runtime, op_start, op_end, arrival
+            if first[o, d] < 0:
+                first[o, d] = F(t)
+            last[o, d] = F(t)                 # events come in time order
+    return runtime, op_start, op_end, ((first, last) if per_child else last)
 
 
 def tensor_lifetimes(n, src, dst, placement, D, op_start, op_end, arrival):
     """alloc [n, D], free [n, D]: the interval during which a copy of v's output occupies device d
-    (-1, -1: no copy there), by the reading stated in the module docstring."""
+    (-1, -1: no copy there), by the reading stated in the module docstring.  `arrival` is [n, D],
+    or (first, last) when an output may cross to a device more than once (per-child transfers):
+    the copy is there from the first arrival, the source waits for the last."""
     placement = np.asarray(placement, dtype=np.int64)
+    arrival, arrival_last = arrival if isinstance(arrival, tuple) else (arrival, arrival)
     alloc = np.full((n, D), -1.0)
     free = np.full((n, D), -1.0)
     last_use = np.full((n, D), -1.0)          # end of the last consumer of v on device d
@@ -150,7 +170,7 @@ def tensor_lifetimes(n, src, dst, placement, D, op_start, op_end, arrival):
         free[v, d] = max(float(op_end[v]), last_use[v, d])
         for o in range(D):
             if o != d and arrival[v, o] >= 0:
-                free[v, d] = max(free[v, d], float(arrival[v, o]))     # the source stays until it has been sent
+                free[v, d] = max(free[v, d], float(arrival_last[v, o]))   # the source stays until it has been sent
                 alloc[v, o] = float(arrival[v, o])
                 free[v, o] = max(float(arrival[v, o]), last_use[v, o])
     return alloc, free

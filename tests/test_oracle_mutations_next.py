@@ -90,7 +90,17 @@ MEMORY = [
     ("closed intervals: what is freed at t still counts at t", "(a <= t) & (t < f)", "(a <= t) & (t <= f)"),
     ("a remote copy exists from the producer's start", "alloc[v, o] = float(arrival[v, o])", "alloc[v, o] = float(op_start[v])"),
     ("the source does not wait for its transfer",
-     "free[v, d] = max(free[v, d], float(arrival[v, o]))     # the source stays until it has been sent", "pass"),
+     "free[v, d] = max(free[v, d], float(arrival_last[v, o]))   # the source stays until it has been sent", "pass"),
+    ("with repeated crossings the source waits for the first arrival only",
+     "arrival, arrival_last = arrival if isinstance(arrival, tuple) else (arrival, arrival)",
+     "arrival, arrival_last = (arrival[0], arrival[0]) if isinstance(arrival, tuple) else (arrival, arrival)"),
+    ("with repeated crossings the copy appears at the last arrival",
+     "arrival, arrival_last = arrival if isinstance(arrival, tuple) else (arrival, arrival)",
+     "arrival, arrival_last = (arrival[1], arrival[1]) if isinstance(arrival, tuple) else (arrival, arrival)"),
+    ("per-child transfers still release every child waiting on the device",
+     "for c in ([child] if per_child else children[o]):", "for c in children[o]:"),
+    ("per-child transfers are sent once per device after all",
+     "elif per_child:", "elif per_child and pc not in sent:\n                    sent.add(pc)"),
     ("an output is allocated when its op ends", "alloc[v, d] = float(op_start[v])", "alloc[v, d] = float(op_end[v])"),
     ("the penalty ignores the limit", "float(r) + c * (float(m) - float(M))", "float(r) + c * float(m)"),
     ("last consumer taken over all devices", "last_use[u, pc] = max(last_use[u, pc], float(op_end[c]))",
@@ -104,5 +114,7 @@ def test_memory_model_mistake_is_caught(what, old, new, tmp_path, monkeypatch):
     pins = [pins_simulator.test_peak_memory_of_a_chain_on_one_device,
             pins_simulator.test_peak_memory_with_a_transfer,
             pins_simulator.test_peak_memory_fork_join_and_bounds,
-            pins_simulator.test_penalised_runtime_formula]
+            pins_simulator.test_penalised_runtime_formula,
+            pins_simulator.test_two_children_on_one_remote_device_one_transfer_or_two,
+            pins_simulator.test_per_child_transfers_on_a_mixed_fan_out]
     assert some_pin_fails(pins), f"no pin notices: {what}"

@@ -9,10 +9,10 @@ from workloads import make_workload, tiny_random_dag
 BW = 1.0 / 1024.0     # seconds per byte in these tests is 1/1024: sizes in KiB become seconds
 
 
-def run(n, edges, cost, size, place, D, inv_bw=BW, trace=None):
+def run(n, edges, cost, size, place, D, inv_bw=BW, trace=None, per_child=False):
     src = [e[0] for e in edges]
     dst = [e[1] for e in edges]
-    return sim.simulate(n, src, dst, cost, size, place, D, inv_bw, trace)
+    return sim.simulate(n, src, dst, cost, size, place, D, inv_bw, trace, per_child)
 
 
 def test_chain_on_one_device_is_the_sum_of_costs():
@@ -53,6 +53,70 @@ def test_one_transfer_per_destination_device_and_bus_is_fifo():
     assert ev == 6 + 2
     # device 1 runs 2, 3, 4 (ready at 5, ascending ids), then 5 (ready at 6): 5..9
     assert r == 9.0
+
+
+def test_two_children_on_one_remote_device_one_transfer_or_two():
+    """Appendix "Simulator", op-done handler read literally (one transfer per child on another
+    device) against one transfer per destination device.  0 runs 0..1 on device 0; its output
+    (2 s on the bus) is needed by 1 and 2 on device 1.
+    Per destination: bus 1..3; 1 runs 3..4, 2 runs 4..5: r = 5, 3 + 1 events.
+    Per child: bus 1..3 for child 1 and 3..5 for child 2; 1 runs 3..4, 2 runs 5..6: r = 6, 3 + 2 events."""
+    g = dict(n=3, edges=[(0, 1), (0, 2)], cost=[1, 1, 1], size=[2048, 512, 256], place=[0, 1, 1], D=2)
+    trace = []
+    r, ev = run(**g, trace=trace)
+    assert (r, ev) == (5.0, 4)
+    assert [t for t in trace if t[0] == "tr"] == [("tr", 0, 1, 3.0)]
+    trace = []
+    r, ev = run(**g, trace=trace, per_child=True)
+    assert (r, ev) == (6.0, 5)
+    assert [t for t in trace if t[0] == "tr"] == [("tr", 0, 1, 3.0), ("tr", 0, 1, 5.0)]
+    assert [t for t in trace if t[0] == "op"] == [("op", 0, 0, 1.0), ("op", 1, 1, 4.0), ("op", 2, 1, 6.0)]
+    # peak memory with repeated crossings: 0's output stays on device 0 until its LAST transfer has
+    # arrived (0..5) and is on device 1 from the FIRST arrival to the end of its last consumer
+    # (3..6); 1's output lives 3..4, 2's 5..6: device 1 holds 2048 + 512 at t = 3, 2048 + 256 at t = 5
+    src, dst = [0, 0], [1, 2]
+    rt, start, end, arr = sim.timeline(3, src, dst, g["cost"], g["size"], g["place"], 2, BW, per_child=True)
+    first, last = arr
+    assert first[0, 1] == 3.0 and last[0, 1] == 5.0 and first[0, 0] == -1.0
+    alloc, free = sim.tensor_lifetimes(3, src, dst, g["place"], 2, start, end, arr)
+    assert (alloc[0, 0], free[0, 0]) == (0.0, 5.0) and (alloc[0, 1], free[0, 1]) == (3.0, 6.0)
+    peak = sim.peak_memory(3, src, dst, g["size"], g["place"], 2, start, end, arr)
+    assert list(peak) == [2048.0, 2560.0]
+    # the default on the same graph: the source is released at 3, the copy lives 3..5
+    rt, start, end, arr = sim.timeline(3, src, dst, g["cost"], g["size"], g["place"], 2, BW)
+    alloc, free = sim.tensor_lifetimes(3, src, dst, g["place"], 2, start, end, arr)
+    assert (alloc[0, 0], free[0, 0]) == (0.0, 3.0) and (alloc[0, 1], free[0, 1]) == (3.0, 5.0)
+
+
+def test_per_child_transfers_on_a_mixed_fan_out():
+    """0 (device 0, 1 s on the bus) feeds 1 (device 0), 2 and 3 (device 1), 4 (device 2); unit costs.
+    Per destination: bus 1..2 (to 1), 2..3 (to 2); 2 runs 2..3, 3 runs 3..4, 4 runs 3..4: r = 4, 5 + 2 events.
+    Per child: bus 1..2, 2..3 (both to 1), 3..4 (to 2); 2 runs 2..3, 3 runs 3..4, 4 runs 4..5: r = 5, 5 + 3 events."""
+    g = dict(n=5, edges=[(0, 1), (0, 2), (0, 3), (0, 4)], cost=[1] * 5, size=[1024, 0, 0, 0, 0],
+             place=[0, 0, 1, 1, 2], D=3)
+    assert run(**g) == (4.0, 7)
+    assert run(**g, per_child=True) == (5.0, 8)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_per_child_transfers_event_count_and_agreement_without_shared_destinations(seed):
+    """Per child, every edge that crosses devices is one transfer: events = n + crossing edges.
+    Where no operation has two children on one remote device the two readings are the same
+    simulation, event by event."""
+    rng = np.random.default_rng(400 + seed)
+    n, D = int(rng.integers(5, 40)), int(rng.integers(2, 5))
+    src, dst = tiny_random_dag(rng, n, 0.2)
+    cost, size = rng.lognormal(0, 1, n), rng.lognormal(7, 1, n)
+    place = rng.integers(0, D, n)
+    r, ev = sim.simulate(n, src, dst, cost, size, place, D, BW, per_child=True)
+    assert ev == n + int((place[src] != place[dst]).sum())
+    # a chain visits every device in turn: no shared destinations, so both readings agree exactly
+    chain = [(i, i + 1) for i in range(n - 1)]
+    cs, cd = [e[0] for e in chain], [e[1] for e in chain]
+    t1, t2 = [], []
+    a = sim.simulate(n, cs, cd, cost, size, place, D, BW, t1)
+    b = sim.simulate(n, cs, cd, cost, size, place, D, BW, t2, per_child=True)
+    assert a == b and t1 == t2
 
 
 def test_device_queue_is_fifo_in_ready_order():
