@@ -305,9 +305,19 @@ int pl_episode_gradient(pl_graph_batch *g, const pl_weights *w, float *node_feat
  * ascending node id, an output crosses once per destination device, events are ordered by
  * (float32 timestamp, creation number), idle devices are started before idle buses, both in
  * ascending index.  A graph must fit in LDS: fewer than 65535 nodes and edges and
- * 18 n + 11 e bytes <= 160 KB, else PL_ERR_SHAPE.  Asynchronous on `stream`. */
+ * 18 n + 13 e bytes <= 160 KB, else PL_ERR_SHAPE.  Asynchronous on `stream`. */
 int pl_simulate_runtime(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
                         float inv_bandwidth, float *out_runtime, int32_t *out_events, void *stream);
+
+/* The same with the choice of how often an output crosses the bus (appendix "Simulator", op-done
+ * and transfer-done handlers).  per_child_transfers = 0 (what pl_simulate_runtime does): once per
+ * destination device; its arrival releases every child waiting there.  per_child_transfers = 1:
+ * the handlers as printed: the output is enqueued once for every child placed on another device
+ * (children in ascending id), and the end of a transfer releases that one child; an output
+ * needed by k children on one remote device then occupies the bus k times. */
+int pl_simulate_runtime_ex(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
+                           float inv_bandwidth, int32_t per_child_transfers, float *out_runtime,
+                           int32_t *out_events, void *stream);
 
 /* The memory-penalised run time of the appendix ("Reward"): R(p) = r if m <= M, else
  * r + c (m - M), with r the simulated run time (as above), m the largest peak memory over the
@@ -324,10 +334,18 @@ int pl_simulate_runtime(pl_graph_batch *g, int32_t D, const float *node_feats, c
  *   out_peak_mem   dev [B, D] fp32  peak of every device, or NULL
  *   out_events     dev [B] int32    as above, or NULL
  * Other arguments, limits and tie rules as pl_simulate_runtime.  The first call on a batch
- * allocates the timeline buffers ((2 + 3 D) N_tot floats); asynchronous on `stream`. */
+ * allocates the timeline buffers ((2 + 4 D) N_tot floats); asynchronous on `stream`. */
 int pl_simulate_reward(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
                        float inv_bandwidth, float mem_limit, float mem_penalty, float *out_reward,
                        float *out_runtime, float *out_peak_mem, int32_t *out_events, void *stream);
+
+/* The same with per_child_transfers as in pl_simulate_runtime_ex.  Where an output reaches a
+ * device more than once, the copy there exists from its first arrival and the source is kept
+ * until the last one. */
+int pl_simulate_reward_ex(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
+                          float inv_bandwidth, int32_t per_child_transfers, float mem_limit, float mem_penalty,
+                          float *out_reward, float *out_runtime, float *out_peak_mem, int32_t *out_events,
+                          void *stream);
 
 /* ---- per-stage timing, for benchmarks.  While enabled, forward and gradient calls bracket each
  * kernel stage with HIP events on the caller's stream (the BW stages are those of the reverse

@@ -76,6 +76,9 @@ def load_library(path: Optional[str] = None):
         "pl_episode_gradient": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
                                                ctypes.c_int32, vp, vp, vp, vp]),
         "pl_simulate_runtime": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, ctypes.c_float, vp, vp, vp]),
+        "pl_simulate_runtime_ex": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int32, vp, vp, vp]),
+        "pl_simulate_reward_ex": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_int32,
+                                                 ctypes.c_float, ctypes.c_float, vp, vp, vp, vp, vp]),
         "pl_simulate_reward": (ctypes.c_int, [vp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_float,
                                               ctypes.c_float, vp, vp, vp, vp, vp]),
         "pl_profile_enable": (ctypes.c_int, [vp, ctypes.c_int32]),
@@ -318,15 +321,18 @@ def episode_run(g: GraphBatch, w: Weights, node_feats, placement, cur_node, orde
 
 
 def simulate_runtime(g: GraphBatch, D: int, node_feats, placement, inv_bandwidth: float, out_runtime,
-                     out_events=None, stream=None):
-    """pl_simulate_runtime on device tensors: simulated run time of the placement of every graph."""
+                     out_events=None, stream=None, per_child_transfers=None):
+    """pl_simulate_runtime(_ex) on device tensors: simulated run time of the placement of every graph."""
     import torch
     lib = load_library()
-    _check(lib.pl_simulate_runtime(
-        g._h, int(D), _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
-        _dev_ptr(placement, torch.int32, g.n_tot, "placement"), float(inv_bandwidth),
-        _dev_ptr(out_runtime, torch.float32, g.B, "out_runtime"),
-        _dev_ptr(out_events, torch.int32, g.B, "out_events"), _stream_ptr(stream)), "pl_simulate_runtime")
+    head = [g._h, int(D), _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
+            _dev_ptr(placement, torch.int32, g.n_tot, "placement"), float(inv_bandwidth)]
+    tail = [_dev_ptr(out_runtime, torch.float32, g.B, "out_runtime"),
+            _dev_ptr(out_events, torch.int32, g.B, "out_events"), _stream_ptr(stream)]
+    if per_child_transfers is None:
+        _check(lib.pl_simulate_runtime(*head, *tail), "pl_simulate_runtime")
+    else:
+        _check(lib.pl_simulate_runtime_ex(*head, int(per_child_transfers), *tail), "pl_simulate_runtime_ex")
     return out_runtime
 
 
@@ -392,15 +398,18 @@ def episode_gradient(g: GraphBatch, w: Weights, node_feats, placement, cur_node,
 
 def simulate_reward(g: GraphBatch, D: int, node_feats, placement, inv_bandwidth: float, mem_limit: float,
                     mem_penalty: float, out_reward, out_runtime=None, out_peak_mem=None, out_events=None,
-                    stream=None):
-    """pl_simulate_reward on device tensors: memory-penalised run time R(p) of every graph's placement."""
+                    stream=None, per_child_transfers=None):
+    """pl_simulate_reward(_ex) on device tensors: memory-penalised run time R(p) of every graph's placement."""
     import torch
     lib = load_library()
-    _check(lib.pl_simulate_reward(
-        g._h, int(D), _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
-        _dev_ptr(placement, torch.int32, g.n_tot, "placement"), float(inv_bandwidth), float(mem_limit),
-        float(mem_penalty), _dev_ptr(out_reward, torch.float32, g.B, "out_reward"),
-        _dev_ptr(out_runtime, torch.float32, g.B, "out_runtime"),
-        _dev_ptr(out_peak_mem, torch.float32, g.B * D, "out_peak_mem"),
-        _dev_ptr(out_events, torch.int32, g.B, "out_events"), _stream_ptr(stream)), "pl_simulate_reward")
+    head = [g._h, int(D), _dev_ptr(node_feats, torch.float32, g.n_tot * 3, "node_feats"),
+            _dev_ptr(placement, torch.int32, g.n_tot, "placement"), float(inv_bandwidth)]
+    tail = [float(mem_limit), float(mem_penalty), _dev_ptr(out_reward, torch.float32, g.B, "out_reward"),
+            _dev_ptr(out_runtime, torch.float32, g.B, "out_runtime"),
+            _dev_ptr(out_peak_mem, torch.float32, g.B * D, "out_peak_mem"),
+            _dev_ptr(out_events, torch.int32, g.B, "out_events"), _stream_ptr(stream)]
+    if per_child_transfers is None:
+        _check(lib.pl_simulate_reward(*head, *tail), "pl_simulate_reward")
+    else:
+        _check(lib.pl_simulate_reward_ex(*head, int(per_child_transfers), *tail), "pl_simulate_reward_ex")
     return out_reward

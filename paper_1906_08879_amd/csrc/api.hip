@@ -89,8 +89,8 @@ struct pl_graph_batch {
     pl::GradWorkspace gw;
     // timeline of the simulator (pl_simulate_reward): op_start, op_end [n_tot]; arrival, alloc, free
     // [n_tot, sim_D]; run times [B]
-    float *sim_start = nullptr, *sim_end = nullptr, *sim_arrival = nullptr, *sim_alloc = nullptr,
-          *sim_free = nullptr, *sim_rt = nullptr;
+    float *sim_start = nullptr, *sim_end = nullptr, *sim_arrival = nullptr, *sim_arrival_last = nullptr,
+          *sim_alloc = nullptr, *sim_free = nullptr, *sim_rt = nullptr;
     int sim_D = 0;
     pl::StageTimer timer;
 };
@@ -658,7 +658,8 @@ int pl_graph_batch_destroy(pl_graph_batch *g)
     }
     free_workspace(g->ws);
     free_grad_workspace(g->gw);
-    for (float *p : {g->sim_start, g->sim_end, g->sim_arrival, g->sim_alloc, g->sim_free, g->sim_rt}) (void)hipFree(p);
+    for (float *p : {g->sim_start, g->sim_end, g->sim_arrival, g->sim_arrival_last, g->sim_alloc, g->sim_free, g->sim_rt})
+        (void)hipFree(p);
     for (auto &v : g->timer.ev)
         for (hipEvent_t e : v) (void)hipEventDestroy(e);
     for (hipEvent_t e : g->timer.pool) (void)hipEventDestroy(e);
@@ -1086,6 +1087,13 @@ int pl_policy_gradient_ex(pl_graph_batch *g, const float *node_feats, const int3
 int pl_simulate_runtime(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
                         float inv_bandwidth, float *out_runtime, int32_t *out_events, void *stream)
 {
+    return pl_simulate_runtime_ex(g, D, node_feats, placement, inv_bandwidth, 0, out_runtime, out_events, stream);
+}
+
+int pl_simulate_runtime_ex(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
+                           float inv_bandwidth, int32_t per_child_transfers, float *out_runtime,
+                           int32_t *out_events, void *stream)
+{
     if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
     if (D < 1 || D > kMaxD) return fail(PL_ERR_SHAPE, "D must be in [1, 16]");
     if (!(inv_bandwidth >= 0.0f)) return fail(PL_ERR_SHAPE, "inv_bandwidth must not be negative");
@@ -1103,7 +1111,8 @@ int pl_simulate_runtime(pl_graph_batch *g, int32_t D, const float *node_feats, c
     int rc = ensure_on_device(g);
     if (rc) return rc;
     rc = launch_simulate(g->view, D, static_cast<int>(n_max), static_cast<int>(e_max), node_feats, placement,
-                         inv_bandwidth, out_runtime, out_events, static_cast<hipStream_t>(stream));
+                         inv_bandwidth, per_child_transfers != 0, out_runtime, out_events,
+                         static_cast<hipStream_t>(stream));
     if (rc) return rc;
     PL_HIP(hipGetLastError());
     return PL_OK;
@@ -1112,6 +1121,15 @@ int pl_simulate_runtime(pl_graph_batch *g, int32_t D, const float *node_feats, c
 int pl_simulate_reward(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
                        float inv_bandwidth, float mem_limit, float mem_penalty, float *out_reward,
                        float *out_runtime, float *out_peak_mem, int32_t *out_events, void *stream)
+{
+    return pl_simulate_reward_ex(g, D, node_feats, placement, inv_bandwidth, 0, mem_limit, mem_penalty, out_reward,
+                                 out_runtime, out_peak_mem, out_events, stream);
+}
+
+int pl_simulate_reward_ex(pl_graph_batch *g, int32_t D, const float *node_feats, const int32_t *placement,
+                          float inv_bandwidth, int32_t per_child_transfers, float mem_limit, float mem_penalty,
+                          float *out_reward, float *out_runtime, float *out_peak_mem, int32_t *out_events,
+                          void *stream)
 {
     if (!g) return fail(PL_ERR_NULL, "graph batch is NULL");
     if (D < 1 || D > kMaxD) return fail(PL_ERR_SHAPE, "D must be in [1, 16]");
@@ -1132,21 +1150,24 @@ int pl_simulate_reward(pl_graph_batch *g, int32_t D, const float *node_feats, co
     if (rc) return rc;
     const size_t n = static_cast<size_t>(g->host.n_tot);
     if (!g->sim_start || g->sim_D < D) {
-        for (float **p : {&g->sim_start, &g->sim_end, &g->sim_arrival, &g->sim_alloc, &g->sim_free, &g->sim_rt}) {
+        for (float **p : {&g->sim_start, &g->sim_end, &g->sim_arrival, &g->sim_arrival_last, &g->sim_alloc,
+                          &g->sim_free, &g->sim_rt}) {
             (void)hipFree(*p);
             *p = nullptr;
         }
         PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_start), sizeof(float) * (n + 4)));
         PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_end), sizeof(float) * (n + 4)));
         PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_arrival), sizeof(float) * (n * D + 4)));
+        PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_arrival_last), sizeof(float) * (n * D + 4)));
         PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_alloc), sizeof(float) * (n * D + 4)));
         PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_free), sizeof(float) * (n * D + 4)));
         PL_HIP(hipMalloc(reinterpret_cast<void **>(&g->sim_rt), sizeof(float) * (g->host.B + 4)));
         g->sim_D = D;
     }
     rc = launch_simulate_reward(g->view, D, static_cast<int>(n_max), static_cast<int>(e_max), node_feats, placement,
-                                inv_bandwidth, mem_limit, mem_penalty, g->sim_start, g->sim_end, g->sim_arrival,
-                                g->sim_alloc, g->sim_free, out_runtime ? out_runtime : g->sim_rt, out_peak_mem,
+                                inv_bandwidth, per_child_transfers != 0, mem_limit, mem_penalty, g->sim_start,
+                                g->sim_end, g->sim_arrival, g->sim_arrival_last, g->sim_alloc, g->sim_free,
+                                out_runtime ? out_runtime : g->sim_rt, out_peak_mem,
                                 out_reward, out_events, static_cast<hipStream_t>(stream));
     if (rc) return rc;
     PL_HIP(hipGetLastError());

@@ -162,13 +162,13 @@ void launch_reinforce_coeff(int T, int B, int n_groups, const float *rewards, co
 // ---- run-time simulator of a placement (kernels_simulator.hip); n_max / e_max: largest graph
 size_t simulator_lds_bytes(int n_max, int e_max);
 int launch_simulate(const GraphView &gv, int D, int n_max, int e_max, const float *node_feats,
-                    const int32_t *placement, float inv_bw, float *out_runtime, int32_t *out_events,
-                    hipStream_t s);
+                    const int32_t *placement, float inv_bw, bool per_child, float *out_runtime,
+                    int32_t *out_events, hipStream_t s);
 
 int launch_simulate_reward(const GraphView &gv, int D, int n_max, int e_max, const float *node_feats,
-                           const int32_t *placement, float inv_bw, float mem_limit, float penalty,
-                           float *op_start, float *op_end, float *arrival, float *alloc, float *free_t,
-                           float *runtime, float *out_peak, float *out_reward, int32_t *out_events,
+                           const int32_t *placement, float inv_bw, bool per_child, float mem_limit, float penalty,
+                           float *op_start, float *op_end, float *arrival, float *arrival_last, float *alloc,
+                           float *free_t, float *runtime, float *out_peak, float *out_reward, int32_t *out_events,
                            hipStream_t s);
 
 // ---- matrix-core pooling (kernels_pool_mfma.hip); writes ws.partial as [B, kPoolSlices, 3G, H]

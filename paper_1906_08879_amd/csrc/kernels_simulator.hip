@@ -32,6 +32,7 @@ struct SimLds {
     uint16_t *tr_op;      // [e] transfer records: producer
     uint16_t *tr_next;    // [e] link of the per-bus transfer queues
     uint8_t *tr_dst;      // [e] destination device
+    uint16_t *tr_child;   // [e] (one transfer per child) the child the transfer is for
 };
 
 __device__ __forceinline__ SimLds carve(unsigned char *base, int n_max, int e_max)
@@ -47,7 +48,8 @@ __device__ __forceinline__ SimLds carve(unsigned char *base, int n_max, int e_ma
     s.next_op = reinterpret_cast<uint16_t *>(p); p += sizeof(uint16_t) * (n_max + (n_max & 1));
     s.tr_op = reinterpret_cast<uint16_t *>(p); p += sizeof(uint16_t) * (e_max + (e_max & 1));
     s.tr_next = reinterpret_cast<uint16_t *>(p); p += sizeof(uint16_t) * (e_max + (e_max & 1));
-    s.tr_dst = p;
+    s.tr_dst = p;                                p += e_max + (e_max & 1);
+    s.tr_child = reinterpret_cast<uint16_t *>(p);
     return s;
 }
 
@@ -73,14 +75,19 @@ __device__ __forceinline__ unsigned int row_pair_min(unsigned int v)
 
 // TL: the timeline is written out as well (for the peak-memory model): start and end of every
 // operation, and the time at which an output arrived on every device it was sent to.
-template <bool TL>
+// PC: the op-done handler as the appendix prints it: the output is enqueued once for EVERY child
+// on another device and a transfer-done event releases that one child (so an output needed by
+// several children on one remote device crosses the bus several times; the timeline then keeps
+// the first and the last arrival per device).  Otherwise an output crosses once per destination
+// device and its arrival releases every child waiting there.
+template <bool TL, bool PC>
 __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max, int e_max,
                                                  const float *__restrict__ node_feats,
                                                  const int32_t *__restrict__ placement, float inv_bw,
                                                  float *__restrict__ out_runtime,
                                                  int32_t *__restrict__ out_events,
                                                  float *__restrict__ op_start, float *__restrict__ op_end,
-                                                 float *__restrict__ arrival)
+                                                 float *__restrict__ arrival, float *__restrict__ arrival_last)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const SimLds S = carve(lds_raw, n_max, e_max);
@@ -115,7 +122,7 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
     int q_head = kNone, q_tail = kNone;
     bool active = false;
     float ev_time = 0.0f;
-    int ev_seq = 0, ev_node = 0, ev_dst = 0;
+    int ev_seq = 0, ev_node = 0, ev_dst = 0, ev_child = 0;
     // what the event's handler needs of its operation, read when the event is created (off the
     // handler's chain of dependent LDS reads): its children and the duration of its transfers
     int ev_c0 = 0, ev_cnt = 0;
@@ -129,10 +136,11 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
             q_tail = v;
         }
     };
-    auto enqueue_transfer = [&](int dev, int o, int dst, float dur) {
+    auto enqueue_transfer = [&](int dev, int o, int dst, float dur, int child) {
         const int k = n_tr++;
         S.tr_op[k] = static_cast<uint16_t>(o);
         S.tr_dst[k] = static_cast<uint8_t>(dst);
+        if constexpr (PC) S.tr_child[k] = static_cast<uint16_t>(child);
         S.tr_dur[k] = dur;
         S.tr_next[k] = kNone;
         if (lane == D + dev) {
@@ -146,7 +154,7 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
         const unsigned long long m = __ballot(start);
         if (start) {
             const int item = q_head;
-            int o, dst = -1;
+            int o, dst = -1, child = 0;
             float dur;
             if (lane < D) {
                 o = item;
@@ -155,9 +163,11 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
             } else {
                 o = S.tr_op[item];
                 dst = S.tr_dst[item];
+                if constexpr (PC) child = S.tr_child[item];
                 q_head = S.tr_next[item];
                 dur = S.tr_dur[item];
             }
+            ev_child = child;
             if (q_head == kNone) q_tail = kNone;
             active = true;
             ev_c0 = S.cptr[o];
@@ -222,7 +232,24 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
         const float dur = op_done ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ev_dur), slot)) : 0.0f;
         if (op_done) last = now;
         if constexpr (TL) {
-            if (!op_done && lane == 0) arrival[static_cast<size_t>(n0 + o) * D + dst] = now;
+            if (!op_done && lane == 0) {
+                const size_t at = static_cast<size_t>(n0 + o) * D + dst;
+                if constexpr (PC) {
+                    if (arrival[at] < 0.0f) arrival[at] = now;       // first crossing to this device
+                    arrival_last[at] = now;
+                } else {
+                    arrival[at] = now;
+                }
+            }
+        }
+        if (PC && !op_done) {
+            // the transfer was made for one child: it alone has one input fewer to wait for
+            const int c = __builtin_amdgcn_readlane(ev_child, slot);
+            const uint32_t word = S.node[c];
+            if (lane == 0) S.node[c] = word - 0x100u;
+            if ((word >> 8) == 1u) enqueue_op(dst, c);
+            wake(now);
+            continue;
         }
         unsigned int sent = 0;
         for (int base = 0; base < cnt; base += 64) {
@@ -244,9 +271,9 @@ __global__ __launch_bounds__(64) void k_simulate(GraphView gv, int D, int n_max,
                 const int l = __ffsll(static_cast<long long>(cross)) - 1;
                 cross &= cross - 1;
                 const int pd = __builtin_amdgcn_readlane(pc, l);
-                if (((sent >> pd) & 1u) == 0) {           // the output crosses once per destination
+                if (PC || ((sent >> pd) & 1u) == 0) {     // once per child, or once per destination
                     sent |= 1u << pd;
-                    enqueue_transfer(slot, o, pd, dur);
+                    enqueue_transfer(slot, o, pd, dur, __builtin_amdgcn_readlane(c, l));
                 }
             }
         }
@@ -276,8 +303,11 @@ __global__ __launch_bounds__(256) void k_lifetimes(GraphView gv, int D, const in
                                                    const float *__restrict__ op_start,
                                                    const float *__restrict__ op_end,
                                                    const float *__restrict__ arrival,
+                                                   const float *__restrict__ arrival_last,
                                                    float *__restrict__ alloc, float *__restrict__ free_t)
 {
+    // arrival: first crossing to a device (the copy exists from then on); arrival_last: last
+    // crossing (the source is kept until then); the same array unless an output may cross twice
     const int v = blockIdx.x * 256 + threadIdx.x;
     if (v >= gv.n_tot) return;
     float *fr = free_t + static_cast<size_t>(v) * D, *al = alloc + static_cast<size_t>(v) * D;
@@ -298,7 +328,7 @@ __global__ __launch_bounds__(256) void k_lifetimes(GraphView gv, int D, const in
         if (o == d) continue;
         const float arr = arrival[static_cast<size_t>(v) * D + o];
         if (arr >= 0.0f) {
-            own_free = fmaxf(own_free, arr);   // the source stays until it has been sent
+            own_free = fmaxf(own_free, arrival_last[static_cast<size_t>(v) * D + o]);   // the source stays until it has been sent
             al[o] = arr;
             fr[o] = fmaxf(arr, fr[o]);
         } else {
@@ -412,42 +442,50 @@ size_t simulator_lds_bytes(int n_max, int e_max)
 {
     return sizeof(int32_t) * (n_max + 1) + 2 * sizeof(float) * n_max + sizeof(float) * e_max +
            3 * sizeof(uint16_t) * (e_max + (e_max & 1)) + sizeof(uint32_t) * n_max +
-           sizeof(uint16_t) * (n_max + (n_max & 1)) + e_max + 16;
+           sizeof(uint16_t) * (n_max + (n_max & 1)) + e_max + 16 + sizeof(uint16_t) * (e_max + 2);
 }
 
 int launch_simulate(const GraphView &gv, int D, int n_max, int e_max, const float *node_feats,
-                    const int32_t *placement, float inv_bw, float *out_runtime, int32_t *out_events,
-                    hipStream_t s)
+                    const int32_t *placement, float inv_bw, bool per_child, float *out_runtime,
+                    int32_t *out_events, hipStream_t s)
 {
     if (gv.B == 0) return PL_OK;
     const size_t lds = simulator_lds_bytes(n_max, e_max);
-    if (lds > 64 * 1024)
-        PL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_simulate<false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
-    hipLaunchKernelGGL(k_simulate<false>, dim3(gv.B), dim3(64), lds, s, gv, D, n_max, e_max, node_feats, placement,
-                       inv_bw, out_runtime, out_events, nullptr, nullptr, nullptr);
-    return PL_OK;
+    auto run = [&](auto kernel) {
+        if (lds > 64 * 1024)
+            PL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+        hipLaunchKernelGGL(kernel, dim3(gv.B), dim3(64), lds, s, gv, D, n_max, e_max, node_feats, placement,
+                           inv_bw, out_runtime, out_events, nullptr, nullptr, nullptr, nullptr);
+        return static_cast<int>(PL_OK);
+    };
+    return per_child ? run(k_simulate<false, true>) : run(k_simulate<false, false>);
 }
 
 // Simulation with the timeline, then lifetimes, peaks and R(p).  scratch: op_start, op_end
-// [n_tot]; arrival, alloc, free_t [n_tot, D].
+// [n_tot]; arrival, arrival_last (used with per_child only), alloc, free_t [n_tot, D].
 int launch_simulate_reward(const GraphView &gv, int D, int n_max, int e_max, const float *node_feats,
-                           const int32_t *placement, float inv_bw, float mem_limit, float penalty,
-                           float *op_start, float *op_end, float *arrival, float *alloc, float *free_t,
-                           float *runtime, float *out_peak, float *out_reward, int32_t *out_events,
+                           const int32_t *placement, float inv_bw, bool per_child, float mem_limit, float penalty,
+                           float *op_start, float *op_end, float *arrival, float *arrival_last, float *alloc,
+                           float *free_t, float *runtime, float *out_peak, float *out_reward, int32_t *out_events,
                            hipStream_t s)
 {
     if (gv.B == 0) return PL_OK;
     const size_t lds = simulator_lds_bytes(n_max, e_max);
-    if (lds > 64 * 1024)
-        PL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_simulate<true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
     const size_t nd = static_cast<size_t>(gv.n_tot) * D;
     hipLaunchKernelGGL(k_fill_value, dim3(static_cast<unsigned>((nd + 255) / 256)), dim3(256), 0, s, arrival, nd, -1.0f);
-    hipLaunchKernelGGL(k_simulate<true>, dim3(gv.B), dim3(64), lds, s, gv, D, n_max, e_max, node_feats, placement,
-                       inv_bw, runtime, out_events, op_start, op_end, arrival);
+    auto run = [&](auto kernel) {
+        if (lds > 64 * 1024)
+            PL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+        hipLaunchKernelGGL(kernel, dim3(gv.B), dim3(64), lds, s, gv, D, n_max, e_max, node_feats, placement,
+                           inv_bw, runtime, out_events, op_start, op_end, arrival, arrival_last);
+        return static_cast<int>(PL_OK);
+    };
+    const int rc = per_child ? run(k_simulate<true, true>) : run(k_simulate<true, false>);
+    if (rc) return rc;
     hipLaunchKernelGGL(k_lifetimes, dim3((gv.n_tot + 255) / 256), dim3(256), 0, s, gv, D, placement, op_start, op_end,
-                       arrival, alloc, free_t);
+                       arrival, per_child ? arrival_last : arrival, alloc, free_t);
     const size_t lds2 = sizeof(float) * 3 * (static_cast<size_t>(n_max + 3) / 4 * 4 + 4);
     if (lds2 > 48 * 1024)
         PL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_peak_memory),

@@ -184,3 +184,103 @@ def test_full_batch_reward_sampled_graphs():
         assert rt[b] == r
         np.testing.assert_allclose(peak[b], p, rtol=1e-6)
         assert abs(rew[b] - want) <= 2e-6 * abs(want)
+
+
+# ---------------------------------------------------------------- one transfer per child
+def _device_both(w, placement, inv_bw, per_child, M=1e30, c=2.0):
+    import torch
+    import paper_1906_08879_amd as pl
+    dev = torch.device("cuda:0")
+    g = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+    f = torch.from_numpy(np.ascontiguousarray(w.node_feats, dtype=np.float32)).to(dev)
+    p = torch.from_numpy(np.ascontiguousarray(placement, dtype=np.int32)).to(dev)
+    rt = torch.full((w.B,), -1.0, dtype=torch.float32, device=dev)
+    ev = torch.full((w.B,), -7, dtype=torch.int32, device=dev)
+    pl.simulate_runtime(g, w.D, f, p, inv_bw, rt, ev, per_child_transfers=per_child)
+    rew = torch.full((w.B,), -1.0, dtype=torch.float32, device=dev)
+    rt2 = torch.full((w.B,), -1.0, dtype=torch.float32, device=dev)
+    peak = torch.full((w.B, w.D), -1.0, dtype=torch.float32, device=dev)
+    ev2 = torch.full((w.B,), -7, dtype=torch.int32, device=dev)
+    pl.simulate_reward(g, w.D, f, p, inv_bw, M, c, rew, rt2, peak, ev2, per_child_transfers=per_child)
+    torch.cuda.synchronize()
+    g.close()
+    np.testing.assert_array_equal(rt.cpu().numpy(), rt2.cpu().numpy())
+    np.testing.assert_array_equal(ev.cpu().numpy(), ev2.cpu().numpy())
+    return rt.cpu().numpy(), ev.cpu().numpy(), peak.cpu().numpy(), rew.cpu().numpy()
+
+
+def _oracle_both(w, b, placement, inv_bw, per_child):
+    n0, n1 = int(w.node_off[b]), int(w.node_off[b + 1])
+    e0, e1 = int(w.edge_off[b]), int(w.edge_off[b + 1])
+    n, src, dst = n1 - n0, w.edge_src[e0:e1], w.edge_dst[e0:e1]
+    cost, size = w.node_feats[n0:n1, 0], w.node_feats[n0:n1, 1]
+    r, e = sim.simulate(n, src, dst, cost, size, placement[n0:n1], w.D, np.float32(inv_bw), per_child=bool(per_child))
+    r2, st, en, arr = sim.timeline(n, src, dst, cost, size, placement[n0:n1], w.D, np.float32(inv_bw), per_child=bool(per_child))
+    assert r2 == r
+    return r, e, sim.peak_memory(n, src, dst, size, placement[n0:n1], w.D, st, en, arr)
+
+
+def test_two_children_on_one_remote_device_on_the_device():
+    """The hand-computed example of the oracle's pin (tests/test_oracle_simulator.py): r = 5 with one
+    transfer per destination device, r = 6 with one per child; peaks 2048 / 2560."""
+    w = Workload(name="t", B=1, D=2, H=8, n_layers=1, k_sweeps=1, group_by_device=1, weight_dtype="fp32",
+                 n_nodes=np.array([3], np.int32), n_edges=np.array([2], np.int32), edge_src=np.array([0, 0], np.int32),
+                 edge_dst=np.array([1, 2], np.int32),
+                 node_feats=np.array([[1, 2048, 0], [1, 512, 0], [1, 256, 0]], np.float32),
+                 placement=np.array([0, 1, 1], np.int32), cur_node=np.zeros(1, np.int32), weights=np.zeros(1, np.float32))
+    rt, ev, peak, _ = _device_both(w, w.placement, 1.0 / 1024.0, 0)
+    assert (rt[0], ev[0]) == (5.0, 4) and list(peak[0]) == [2048.0, 2560.0]
+    rt, ev, peak, _ = _device_both(w, w.placement, 1.0 / 1024.0, 1)
+    assert (rt[0], ev[0]) == (6.0, 5) and list(peak[0]) == [2048.0, 2560.0]
+
+
+@pytest.mark.parametrize("name,B,inv_bw", [("random32", 1, 1e-4), ("layered200", 8, 1e-4), ("inception", 3, 3e-5),
+                                           ("nmt", 2, 1e-4), ("nasnet", 2, 5e-5)])
+def test_per_child_transfers_bit_exact(name, B, inv_bw):
+    """The printed op-done / transfer-done handlers (one transfer per child on another device): run
+    times and event counts bit for bit, peaks to 1e-6 relative, on every workload; the run differs
+    from the default wherever an operation has two children on one remote device."""
+    w = make_workload(name, B=B)
+    rng = np.random.default_rng(29)
+    differs = 0
+    for trial in range(2):
+        placement = w.placement if trial == 0 else rng.integers(0, w.D, w.n_tot).astype(np.int32)
+        rt, ev, peak, _ = _device_both(w, placement, inv_bw, 1)
+        rt0, ev0, _, _ = _device_both(w, placement, inv_bw, 0)
+        for b in range(w.B):
+            r, e, p = _oracle_both(w, b, placement, inv_bw, 1)
+            assert (rt[b], ev[b]) == (r, e), (name, b, rt[b], r, ev[b], e)
+            np.testing.assert_allclose(peak[b], p, rtol=1e-6, atol=0, err_msg=f"{name} graph {b}")
+            n0, n1 = int(w.node_off[b]), int(w.node_off[b + 1])
+            e0, e1 = int(w.edge_off[b]), int(w.edge_off[b + 1])
+            crossing = int((placement[n0:n1][w.edge_src[e0:e1]] != placement[n0:n1][w.edge_dst[e0:e1]]).sum())
+            assert ev[b] == (n1 - n0) + crossing
+            differs += ev[b] != ev0[b]
+    assert differs > 0 or name == "random32"
+
+
+def test_per_child_transfers_with_ties_and_at_full_size():
+    rng = np.random.default_rng(8)
+    sizes = [1, 2, 30, 64, 100, 7]
+    n_nodes, n_edges, srcs, dsts, feats = [], [], [], [], []
+    for n in sizes:
+        s, d = tiny_random_dag(rng, n, 0.3)
+        n_nodes.append(n); n_edges.append(len(s)); srcs.append(s); dsts.append(d)
+        feats.append(np.stack([rng.integers(1, 4, n), rng.integers(0, 3, n), np.zeros(n)], axis=1))
+    w = Workload(name="custom", B=len(sizes), D=3, H=8, n_layers=1, k_sweeps=1, group_by_device=1, weight_dtype="fp32",
+                 n_nodes=np.array(n_nodes, np.int32), n_edges=np.array(n_edges, np.int32),
+                 edge_src=np.concatenate(srcs).astype(np.int32), edge_dst=np.concatenate(dsts).astype(np.int32),
+                 node_feats=np.concatenate(feats).astype(np.float32),
+                 placement=rng.integers(0, 3, sum(sizes)).astype(np.int32),
+                 cur_node=np.zeros(len(sizes), np.int32), weights=np.zeros(1, np.float32))
+    rt, ev, peak, _ = _device_both(w, w.placement, 1.0, 1)
+    for b in range(w.B):
+        r, e, p = _oracle_both(w, b, w.placement, 1.0, 1)
+        assert (rt[b], ev[b]) == (r, e), b
+        np.testing.assert_allclose(peak[b], p, rtol=1e-6, atol=0)
+    w = make_workload("nasnet")
+    rt, ev, peak, _ = _device_both(w, w.placement, 5e-5, 1)
+    for b in (0, 131, w.B - 1):
+        r, e, p = _oracle_both(w, b, w.placement, 5e-5, 1)
+        assert (rt[b], ev[b]) == (r, e), b
+        np.testing.assert_allclose(peak[b], p, rtol=1e-6, atol=0)
