@@ -84,6 +84,14 @@ typedef struct pl_weights pl_weights;          /* opaque: device copy of the par
 int pl_graph_batch_create(int32_t B, const int32_t *n_nodes, const int32_t *n_edges,
                           const int32_t *edge_src, const int32_t *edge_dst,
                           pl_graph_batch **out);
+/* A batch of R copies of ONE graph: the batch of independent rollouts of the same graph over
+ * which the appendix's REINFORCE section averages its per-step baseline.  The result behaves in
+ * every call exactly like pl_graph_batch_create on the graph repeated R times (same layout, same
+ * results bit for bit); the host builds the layout once instead of R times, and what depends on
+ * the topology alone (the message-passing kernel's gather plan) exists once on the device and is
+ * read by all R copies.  Arguments as above for one graph; R >= 1. */
+int pl_graph_batch_create_replicated(int32_t n_nodes, int32_t n_edges, const int32_t *edge_src,
+                                     const int32_t *edge_dst, int32_t R, pl_graph_batch **out);
 int pl_graph_batch_destroy(pl_graph_batch *g);   /* NULL is accepted */
 
 /* Sizes of a batch: any output pointer may be NULL.  max_depth = largest number of levels

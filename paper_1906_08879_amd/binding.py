@@ -49,6 +49,8 @@ def load_library(path: Optional[str] = None):
     sig = {
         "pl_graph_batch_create": (ctypes.c_int, [ctypes.c_int32, i32p, i32p, i32p, i32p,
                                                  ctypes.POINTER(vp)]),
+        "pl_graph_batch_create_replicated": (ctypes.c_int, [ctypes.c_int32, ctypes.c_int32, i32p, i32p,
+                                                            ctypes.c_int32, ctypes.POINTER(vp)]),
         "pl_graph_batch_destroy": (ctypes.c_int, [vp]),
         "pl_graph_batch_info": (ctypes.c_int, [vp, i32p, i64p, i64p, i32p]),
         "pl_graph_batch_levels": (ctypes.c_int, [vp, i32p, i32p]),
@@ -133,17 +135,25 @@ def weights_count(D, H, n_layers=2, k_sweeps=1, group_by_device=1, weight_dtype=
 class GraphBatch:
     """pl_graph_batch: a batch of DAGs with its CSR, levels, buckets and scratch buffers."""
 
-    def __init__(self, n_nodes, n_edges, edge_src, edge_dst):
+    def __init__(self, n_nodes, n_edges, edge_src, edge_dst, replicate=None):
+        """replicate = R: n_nodes / n_edges are the sizes of ONE graph, and the batch holds R copies of
+        it that share one layout (pl_graph_batch_create_replicated)."""
         lib = load_library()
-        n_nodes, pn = _i32(n_nodes)
-        n_edges, pe = _i32(n_edges)
+        self._h = ctypes.c_void_p()
         src, ps = _i32(edge_src)
         dst, pd = _i32(edge_dst)
-        if len(n_nodes) != len(n_edges) or len(src) != len(dst) or len(src) != int(n_edges.sum()):
-            raise PlacetoError("inconsistent graph batch arrays")
-        self._h = ctypes.c_void_p()
-        _check(lib.pl_graph_batch_create(len(n_nodes), pn, pe, ps, pd, ctypes.byref(self._h)),
-               "pl_graph_batch_create")
+        if replicate is not None:
+            if len(src) != len(dst) or len(src) != int(n_edges):
+                raise PlacetoError("inconsistent graph arrays")
+            _check(lib.pl_graph_batch_create_replicated(int(n_nodes), int(n_edges), ps, pd, int(replicate),
+                                                        ctypes.byref(self._h)), "pl_graph_batch_create_replicated")
+        else:
+            n_nodes, pn = _i32(n_nodes)
+            n_edges, pe = _i32(n_edges)
+            if len(n_nodes) != len(n_edges) or len(src) != len(dst) or len(src) != int(n_edges.sum()):
+                raise PlacetoError("inconsistent graph batch arrays")
+            _check(lib.pl_graph_batch_create(len(n_nodes), pn, pe, ps, pd, ctypes.byref(self._h)),
+                   "pl_graph_batch_create")
         B, n_tot, e_tot, depth = ctypes.c_int32(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32()
         _check(lib.pl_graph_batch_info(self._h, ctypes.byref(B), ctypes.byref(n_tot),
                                        ctypes.byref(e_tot), ctypes.byref(depth)),

@@ -80,10 +80,9 @@ struct pl_graph_batch {
     int32_t *d_node_off = nullptr, *d_lvl_off = nullptr, *d_node_graph = nullptr;
     int32_t *d_nbr_ptr[2] = {nullptr, nullptr}, *d_nbr_idx[2] = {nullptr, nullptr};
     int32_t *d_order[2] = {nullptr, nullptr}, *d_lvl_ptr[2] = {nullptr, nullptr};
-    int32_t *d_ck_off[2] = {nullptr, nullptr}, *d_ck_meta[2] = {nullptr, nullptr};
-    int32_t *d_ck_far[2] = {nullptr, nullptr}, *d_ck_ovf[2] = {nullptr, nullptr};
-    int32_t *d_pos[2] = {nullptr, nullptr};
-    uint32_t *d_ck_ent[2] = {nullptr, nullptr};
+    int32_t *d_ck_off[2] = {nullptr, nullptr}, *d_ck_ovf[2] = {nullptr, nullptr};
+    int32_t *d_pos[2] = {nullptr, nullptr}, *d_tmpl = nullptr;
+    uint32_t *d_ck_rec[2] = {nullptr, nullptr};
     pl::GraphView view{};
     pl::Workspace ws;
     pl::GradWorkspace gw;
@@ -225,6 +224,7 @@ int upload_batch(pl_graph_batch *g)
     if ((rc = upload(node_off, &g->d_node_off))) return rc;
     if ((rc = upload(lvl_off, &g->d_lvl_off))) return rc;
     if ((rc = upload(node_graph, &g->d_node_graph))) return rc;
+    if ((rc = upload(L.tmpl, &g->d_tmpl))) return rc;
     for (int dir = 0; dir < 2; ++dir) {
         if ((rc = upload(ptr[dir], &g->d_nbr_ptr[dir]))) return rc;
         if ((rc = upload(idx[dir], &g->d_nbr_idx[dir]))) return rc;
@@ -233,9 +233,7 @@ int upload_batch(pl_graph_batch *g)
         SweepPlanHost plan;
         if ((rc = build_sweep_plan(L, dir, &plan))) return rc;
         if ((rc = upload(plan.ck_off, &g->d_ck_off[dir]))) return rc;
-        if ((rc = upload(plan.meta, &g->d_ck_meta[dir]))) return rc;
-        if ((rc = upload(plan.ent, &g->d_ck_ent[dir]))) return rc;
-        if ((rc = upload(plan.far, &g->d_ck_far[dir]))) return rc;
+        if ((rc = upload(plan.rec, &g->d_ck_rec[dir]))) return rc;
         if ((rc = upload(plan.ovf, &g->d_ck_ovf[dir]))) return rc;
         std::vector<int32_t> pos(L.n_tot);
         for (int64_t p = 0; p < L.n_tot; ++p) pos[order[dir][p]] = static_cast<int32_t>(p);
@@ -247,15 +245,14 @@ int upload_batch(pl_graph_batch *g)
     v.node_off = g->d_node_off;
     v.lvl_off = g->d_lvl_off;
     v.node_graph = g->d_node_graph;
+    v.tmpl = g->d_tmpl;
     for (int dir = 0; dir < 2; ++dir) {
         v.nbr_ptr[dir] = g->d_nbr_ptr[dir];
         v.nbr_idx[dir] = g->d_nbr_idx[dir];
         v.order[dir] = g->d_order[dir];
         v.lvl_ptr[dir] = g->d_lvl_ptr[dir];
         v.plan[dir].ck_off = g->d_ck_off[dir];
-        v.plan[dir].meta = reinterpret_cast<const int4 *>(g->d_ck_meta[dir]);
-        v.plan[dir].ent = reinterpret_cast<const uint4 *>(g->d_ck_ent[dir]);
-        v.plan[dir].far = g->d_ck_far[dir];
+        v.plan[dir].rec = reinterpret_cast<const uint4 *>(g->d_ck_rec[dir]);
         v.plan[dir].ovf = g->d_ck_ovf[dir];
         v.pos[dir] = g->d_pos[dir];
     }
@@ -636,6 +633,30 @@ int pl_graph_batch_create(int32_t B, const int32_t *n_nodes, const int32_t *n_ed
     return PL_OK;
 }
 
+int pl_graph_batch_create_replicated(int32_t n_nodes, int32_t n_edges, const int32_t *edge_src,
+                                     const int32_t *edge_dst, int32_t R, pl_graph_batch **out)
+{
+    if (!out) return fail(PL_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    if (R < 1) return fail(PL_ERR_SHAPE, "the number of copies must be at least 1");
+    pl_graph_batch *g = new (std::nothrow) pl_graph_batch();
+    if (!g) return fail(PL_ERR_NOMEM, "out of host memory");
+    int rc;
+    try {
+        HostLayout one;
+        rc = build_layout(1, &n_nodes, &n_edges, edge_src, edge_dst, &one);
+        if (!rc) rc = replicate_layout(one, R, &g->host);
+    } catch (const std::bad_alloc &) {
+        rc = fail(PL_ERR_NOMEM, "out of host memory");
+    }
+    if (rc) {
+        delete g;
+        return rc;
+    }
+    *out = g;
+    return PL_OK;
+}
+
 int pl_graph_batch_destroy(pl_graph_batch *g)
 {
     if (!g) return PL_OK;
@@ -643,15 +664,14 @@ int pl_graph_batch_destroy(pl_graph_batch *g)
         (void)hipFree(g->d_node_off);
         (void)hipFree(g->d_lvl_off);
         (void)hipFree(g->d_node_graph);
+        (void)hipFree(g->d_tmpl);
         for (int dir = 0; dir < 2; ++dir) {
             (void)hipFree(g->d_nbr_ptr[dir]);
             (void)hipFree(g->d_nbr_idx[dir]);
             (void)hipFree(g->d_order[dir]);
             (void)hipFree(g->d_lvl_ptr[dir]);
             (void)hipFree(g->d_ck_off[dir]);
-            (void)hipFree(g->d_ck_meta[dir]);
-            (void)hipFree(g->d_ck_ent[dir]);
-            (void)hipFree(g->d_ck_far[dir]);
+            (void)hipFree(g->d_ck_rec[dir]);
             (void)hipFree(g->d_ck_ovf[dir]);
             (void)hipFree(g->d_pos[dir]);
         }

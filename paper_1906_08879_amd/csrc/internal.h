@@ -47,10 +47,18 @@ struct HostLayout {
     std::vector<int64_t> lvl_off;    // [B+1] offset of graph b's level pointers
     std::vector<int32_t> td_lvl_ptr; // [lvl_off[B]] per graph depth+1 positions into its order
     std::vector<int32_t> bu_lvl_ptr; // same for bottom-up
+    // graphs of the same topology (the rollouts of one graph) share what depends on the
+    // topology alone: graph b uses the plan of template tmpl[b]; tmpl_graph[t] is a graph with it
+    int32_t n_templates = 0;
+    std::vector<int32_t> tmpl;       // [B]
+    std::vector<int32_t> tmpl_graph; // [n_templates]
 };
 
 int build_layout(int32_t B, const int32_t *n_nodes, const int32_t *n_edges,
                  const int32_t *edge_src, const int32_t *edge_dst, HostLayout *out);
+// The layout of R copies of the one graph of `one`, equal to what build_layout gives for the
+// graph repeated R times, with all copies sharing one template.
+int replicate_layout(const HostLayout &one, int32_t R, HostLayout *out);
 
 // ---- device-side view of a batch, passed to kernels by value
 struct GraphView {
@@ -65,6 +73,7 @@ struct GraphView {
     const int32_t *lvl_ptr[2]; // per graph depth+1 GLOBAL positions into order
     const int32_t *node_graph; // [n_tot] graph of each node
     const int32_t *pos[2];     // [n_tot] bucket position of each node (inverse of order)
+    const int32_t *tmpl;       // [B] which plan (distinct topology) graph b uses
     SweepPlanView plan[2];     // per direction
 };
 

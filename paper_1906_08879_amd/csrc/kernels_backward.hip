@@ -554,7 +554,7 @@ __global__ __launch_bounds__(kThreads) void k_bw_prep(GraphView gv, int H, int L
         const size_t at = (static_cast<size_t>(pd) * gv.n_tot + gv.pos[pd][v]) * H + h;
         extb[at] = demb[static_cast<size_t>(v) * 2 * H + sd * H + h];
         const GateSrc &gs = sd ? src1 : src0;
-        int bits = gs.m[idx] > 0.0f ? 1 : 0;
+        int bits = fabsf(gs.m[idx]) > 0.0f ? 1 : 0;     // messages may carry a flag in their sign bit
         bits |= gs.g_last[idx] > 0.0f ? 4 : 0;
         if (L == 2) {
             bits |= gs.f0[idx] > 0.0f ? 2 : 0;
@@ -859,8 +859,11 @@ __global__ __launch_bounds__(kThreads) void k_bw_agg(GraphView gv, int H,
     const float *msg = msgs + static_cast<size_t>(dir) * gv.n_tot * H;   // [2, n_tot, H] from the forward pass
     const int32_t *nbr_ptr = gv.nbr_ptr[dir], *nbr_idx = gv.nbr_idx[dir];
     f32x4v a{0.f, 0.f, 0.f, 0.f};
-    for (int p = nbr_ptr[v]; p < nbr_ptr[v + 1]; ++p)
-        a += *reinterpret_cast<const f32x4v *>(msg + static_cast<size_t>(nbr_idx[p]) * H + h);
+    for (int p = nbr_ptr[v]; p < nbr_ptr[v + 1]; ++p) {
+        // messages are ReLU outputs; the matrix-core sweep keeps a flag in their sign bit
+        const f32x4v m = *reinterpret_cast<const f32x4v *>(msg + static_cast<size_t>(nbr_idx[p]) * H + h);
+        a += f32x4v{fabsf(m[0]), fabsf(m[1]), fabsf(m[2]), fabsf(m[3])};
+    }
     *reinterpret_cast<f32x4v *>(agg + (static_cast<size_t>(dir) * gv.n_tot + v) * H + h) = a;
 }
 

@@ -5,6 +5,8 @@
 // Section 2.2 of the paper: (1) raw features, (2) two-way message passing
 // x_v <- g(sum_{u in xi(v)} f(x_u)), (3) pooling h_i(sum_{u in S_i(v)} l_i(x_u)) over the
 // parent / child / parallel sets of the current node, then the policy head (Appendix A.7).
+#include <type_traits>
+
 #include "internal.h"
 
 namespace pl {
@@ -18,7 +20,7 @@ constexpr int kTile = 16;   // rows (nodes) pushed through a network together
 // x and y live in LDS.  Thread (grp, j): column j = tid % n_out, row group grp = tid / n_out;
 // it owns rows grp, grp + groups, ... (at most RPT of them), so one weight load feeds up to
 // RPT FMAs.  Requires n_out <= kThreads and min(kThreads / n_out, kTile) * RPT >= kTile.
-template <int RPT>
+template <int RPT, bool WIDE = false>
 __device__ __forceinline__ void dense_layer(const float *__restrict__ W,
                                             const float *__restrict__ bias, int n_in, int n_out,
                                             const float *x, int ldx, float *y, int ldy, int rows,
@@ -29,7 +31,10 @@ __device__ __forceinline__ void dense_layer(const float *__restrict__ W,
     if (groups > kTile) groups = kTile;
     const int grp = tid / n_out, j = tid - grp * n_out;
     if (grp >= groups || grp >= rows) return;
-    float acc[RPT];
+    // WIDE: blocks of sixteen fp32 terms are added up in float64 (the policy head's networks,
+    // whose inputs are sums over thousands of nodes)
+    typedef typename std::conditional<WIDE, double, float>::type acc_t;
+    acc_t acc[RPT];
     const float bj = bias[j];
 #pragma unroll
     for (int i = 0; i < RPT; ++i) acc[i] = bj;
@@ -44,6 +49,18 @@ __device__ __forceinline__ void dense_layer(const float *__restrict__ W,
         float w[KB];
 #pragma unroll
         for (int u = 0; u < KB; ++u) w[u] = W[static_cast<size_t>(k + u) * n_out + j];
+        if constexpr (WIDE) {
+            float part[RPT];
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) part[i] = 0.0f;
+#pragma unroll
+            for (int u = 0; u < KB; ++u)
+#pragma unroll
+                for (int i = 0; i < RPT; ++i) part[i] = fmaf(x[xoff[i] + k + u], w[u], part[i]);
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) acc[i] += static_cast<double>(part[i]);
+            continue;
+        }
 #pragma unroll
         for (int u = 0; u < KB; ++u)
 #pragma unroll
@@ -52,12 +69,18 @@ __device__ __forceinline__ void dense_layer(const float *__restrict__ W,
     for (; k < n_in; ++k) {
         const float w = W[static_cast<size_t>(k) * n_out + j];
 #pragma unroll
-        for (int i = 0; i < RPT; ++i) acc[i] = fmaf(x[xoff[i] + k], w, acc[i]);
+        for (int i = 0; i < RPT; ++i) {
+            if constexpr (WIDE)
+                acc[i] += static_cast<double>(x[xoff[i] + k]) * static_cast<double>(w);
+            else
+                acc[i] = fmaf(x[xoff[i] + k], w, acc[i]);
+        }
     }
 #pragma unroll
     for (int i = 0; i < RPT; ++i) {
         const int r = grp + i * groups;
-        if (r < rows) y[r * ldy + j] = relu ? fmaxf(acc[i], 0.0f) : acc[i];
+        const float out = static_cast<float>(acc[i]);
+        if (r < rows) y[r * ldy + j] = relu ? fmaxf(out, 0.0f) : out;
     }
 }
 
@@ -457,7 +480,7 @@ __global__ __launch_bounds__(kThreads) void k_head_sets(GraphView gv, ModelView 
     const float *in = P;
     for (int l = 0; l < L; ++l) {
         float *out = (l & 1) ? buf_b : buf_a;
-        dense_layer<RPT>(mv.blob + hn.layer[l].w, mv.blob + hn.layer[l].b, H, H, in, H, out, H, G, true);
+        dense_layer<RPT, true>(mv.blob + hn.layer[l].w, mv.blob + hn.layer[l].b, H, H, in, H, out, H, G, true);
         __syncthreads();
         in = out;
     }
@@ -466,10 +489,10 @@ __global__ __launch_bounds__(kThreads) void k_head_sets(GraphView gv, ModelView 
 
 // (2) workgroup (row tile, slice): partial products of policy layer 1 for 16 graphs and one
 // slice of z: hidp[slice][b][j] = sum over k in the slice of z[b][k] W1[k][j].
-// The two policy layers accumulate in float64 (products of two fp32 values are exact there):
+// The two policy layers accumulate in float64 (the first one in blocks of sixteen fp32 terms):
 // z holds sums over thousands of nodes, so a logit is a difference of terms far larger than
-// itself, and an fp32 sum over the (2 + 3G) H inputs alone would cost about 1e-6 of the
-// largest logit of the graph, ten times what the rest of the pass contributes.
+// itself, and a running fp32 sum over the (2 + 3G) H inputs alone would cost about 1e-6 of the
+// largest logit of the graph, several times what the rest of the pass contributes.
 template <int RPT>
 __global__ __launch_bounds__(kThreads) void k_head_policy1(ModelView mv, int B,
                                                            const float *__restrict__ zbuf,
@@ -502,13 +525,20 @@ __global__ __launch_bounds__(kThreads) void k_head_policy1(ModelView mv, int B,
     constexpr int KB = 16;      // weights per batch of loads, as in dense_layer
     int k = 0;
     for (; k + KB <= kn; k += KB) {
-        double w[KB];
+        float w[KB];
 #pragma unroll
-        for (int u = 0; u < KB; ++u) w[u] = static_cast<double>(W[static_cast<size_t>(k + u) * H + j]);
+        for (int u = 0; u < KB; ++u) w[u] = W[static_cast<size_t>(k + u) * H + j];
+        // sixteen terms in fp32, the blocks in float64: rounding errors stay relative to a
+        // block's own size instead of the running sum's
+        float part[RPT];
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) part[i] = 0.0f;
 #pragma unroll
         for (int u = 0; u < KB; ++u)
 #pragma unroll
-            for (int i = 0; i < RPT; ++i) acc[i] = fma(static_cast<double>(xf[xoff[i] + k + u]), w[u], acc[i]);
+            for (int i = 0; i < RPT; ++i) part[i] = fmaf(xf[xoff[i] + k + u], w[u], part[i]);
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) acc[i] += static_cast<double>(part[i]);
     }
     for (; k < kn; ++k) {
         const double w = static_cast<double>(W[static_cast<size_t>(k) * H + j]);

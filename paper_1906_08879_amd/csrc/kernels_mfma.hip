@@ -13,24 +13,29 @@
 //     matrix cores without any cross-lane traffic.
 //   * The weight fragments of all layers of one direction live in registers for the whole
 //     kernel (bf16 weights: 128 VGPRs per wave at H = 128); only activations move through LDS.
+//     A lane that owns two output columns writes them as ONE 32-bit word per bf16 part: the
+//     contraction index of the next layer is permuted accordingly (columns c and c + 16 of a
+//     wave are neighbours in A), so an activation row is exchanged with three conflict-free
+//     word stores per lane instead of six half-word stores.
 //   * A wave owns its output columns from end to end: it writes its columns of a message into
-//     an LDS table, stages its columns of older messages (prefetched from HBM one chunk ahead)
-//     into the same table, and sums its columns for the next chunk, in the MFMA result layout
-//     (lane = node of the tile, column).  The table therefore needs no barrier; only the A
-//     rows of the next layer cross waves: one LDS barrier per layer, four per chunk.
-//   * Messages are ReLU outputs, so in the table their sign bit carries the reachability flag
-//     of Section 2.2 step 3 (the node is v* or was computed from v*): sums take |x| and OR the
-//     signs.  Row records name a fixed number of table slots (unused ones a zero row), so the
-//     common gather is branch-free.
+//     an LDS table that holds the last kRing chunks ("near" sources), reads its columns of
+//     older messages ("far" sources) back from HBM straight into the registers that sum them,
+//     two chunks ahead of their use, and sums its columns for the next chunk, in the MFMA result
+//     layout (lane = node of the tile, column).  The table therefore needs no barrier; only the
+//     A rows of the next layer cross waves: one LDS barrier per layer, four per chunk.
+//   * Messages are ReLU outputs, so their sign bit carries the reachability flag of Section 2.2
+//     step 3 (the node is v* or was computed from v*), in the table and in HBM alike: sums take
+//     |x| and OR the signs.  A row record names a fixed number of table slots (unused ones the
+//     table's zero row) and one far source (or a row of zeros), so the common gather is
+//     branch-free; rows with more sources walk a list.
 //   * On the first sweep the same lane computes its columns of x_v = relu(W_in^T phi_v + b)
 //     (step 1) from the node's 16-byte feature record: x never exists in HBM.
-//   * Barriers order LDS traffic only, so global prefetches stay in flight across them.
-//     A message written to HBM in chunk c is only read back from HBM from chunk c + 3 on
-//     (nearer consumers use the LDS table); by then the store has retired, because each
-//     wave waits once per chunk for a batch of loads that it issued after that store.
-//     Every global store is on every path (unused rows store to sink rows), so the number of
-//     stores behind a load is known at compile time and waiting for the load never waits for
-//     the stores.
+//   * Everything a chunk needs from HBM (row records three chunks ahead, feature records one,
+//     far messages two) is loaded by plain vector loads behind the matrix instructions of an
+//     earlier chunk; barriers order LDS traffic only, so those loads stay in flight across them.
+//     A far message was stored by this same wave at least kRing + 1 chunks before it is used and
+//     at least kRing - 1 chunks before it is loaded; in between the wave has waited for loads that
+//     it issued after that store, so the store has retired.
 //   * The kernel runs a dependent chain (about a thousand chunks of four layers per graph),
 //     so it is bound by LDS round trips, MFMA latency and barriers, not by HBM bandwidth.
 #include <type_traits>
@@ -45,11 +50,11 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int CH = kChunkRows, FCAP = kFarCap, RING = kRing;
+constexpr int CH = kChunkRows, RING = kRing;
 constexpr int kTileNodes = 4;                 // nodes per 16-row MFMA tile (hi, mid, lo, zero rows)
 constexpr int NT = CH / kTileNodes;           // row tiles per chunk
 
-// Workgroup barrier that orders LDS traffic only: global prefetches stay outstanding.
+// Workgroup barrier that orders LDS traffic only: global loads and stores stay outstanding.
 __device__ __forceinline__ void lds_barrier()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -60,6 +65,12 @@ __device__ __forceinline__ void lds_barrier()
 __device__ __forceinline__ float trunc_bf16(float x)
 {
     return __uint_as_float(__float_as_uint(x) & 0xFFFF0000u);
+}
+
+// {high half of a, high half of b} as one word, a in the low half
+__device__ __forceinline__ uint32_t pack_hi16(float a, float b)
+{
+    return __builtin_amdgcn_perm(__float_as_uint(b), __float_as_uint(a), 0x07060302u);
 }
 
 struct SweepParams {
@@ -85,16 +96,6 @@ struct SweepParams {
     size_t delta_stride;    // floats between the two directions' blocks
 };
 
-// Reads a chunk's meta record through the constant address space, so that the wave-uniform
-// record comes in with a scalar load.
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ int4 load_uniform(const int4 *p)
-{
-    const i32x4 r = *reinterpret_cast<const __attribute__((address_space(4))) i32x4 *>(
-        reinterpret_cast<uintptr_t>(p));
-    return int4{r.x, r.y, r.z, r.w};
-}
-
 constexpr int sweep_waves(int H) { return H / 16 > 4 ? 4 : H / 16; }
 
 // FF: first sweep, the input x_v is computed from the raw-feature records; otherwise it is
@@ -106,8 +107,8 @@ constexpr int sweep_waves(int H) { return H / 16 > 4 ? 4 : H / 16; }
 // the layers of f; + the outside gradient of s_v (read where the forward pass reads x_v) =
 // ds_v, written where the forward pass writes s_v; gated, back through the layers of g; the
 // result da_v goes where the forward pass puts the message.  ReLU and bias are replaced by the
-// stored gates, table entries are signed (no reachability flag), and every gated layer input
-// is also written to HBM as the layer's delta for the weight gradients.
+// stored gates, table entries and stored values are signed (no reachability flag), and every
+// gated layer input is also written to HBM as the layer's delta for the weight gradients.
 // TR: a forward sweep that also keeps what the reverse pass needs of every node: the gathered
 // sum a_v and the output of every layer but the last (the last is the message, stored anyway),
 // 2L arrays [n_tot, H] per direction in `delta` (slot 0: a_v, slots 1 .. L: g's layers, slots
@@ -126,17 +127,14 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     constexpr int LDA = H + 8;                 // bf16 row stride of the activation buffers
     constexpr int LDM = H + 16;                // float row stride of the message table (16 mod 64:
                                                // four consecutive rows fall on disjoint banks)
-    constexpr int QW = WC / 4;                 // float4 per far row and wave
-    constexpr int PFN = (FCAP * QW + 63) / 64; // staged far float4 per lane
-    constexpr int NACC = KS > 1 ? 2 : 1;       // independent accumulation chains per tile
     constexpr int kZeroSlot = kMsgSlots;
-    constexpr int kWarmAhead = 12;             // chunks between touching a chunk record and reading it
     static_assert(NTL % NW == 0, "column tiles must divide over the waves");
+    static_assert(TPW == 1 || TPW == 2, "a lane owns one or two output columns");
 
     // Message table: H floats per row.  Messages are ReLU outputs, so their sign bit is free:
-    // in the table it carries the reachability flag of the row's node (set if the node is v* or
-    // has v* among the nodes it was computed from); sums take |x|.  A wave reads and writes
-    // only its own columns, so the table needs no barrier.  The last row stays zero.
+    // it carries the reachability flag of the row's node (set if the node is v* or has v* among
+    // the nodes it was computed from); sums take |x|.  A wave reads and writes only its own
+    // columns, so the table needs no barrier.  The last row stays zero.
     __shared__ __attribute__((aligned(16))) float msgtab[(kMsgSlots + 1) * LDM];
     __shared__ __attribute__((aligned(16))) __bf16 actbuf[2][NT * 16][LDA];
     __shared__ float proj_dev[(kMaxD + 1) * H];   // one-hot device rows of W_in, then a zero row
@@ -148,20 +146,21 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
 
     const GraphView &gv = P.gv;
     const SweepPlanView plan = gv.plan[dir];
-    const int32_t *order = gv.order[dir];
     float *msg = P.msg + static_cast<size_t>(dir) * gv.n_tot * H;
     float *xb = P.xb + static_cast<size_t>(dir) * gv.n_tot * H;
     uint8_t *reach = P.reach + static_cast<size_t>(dir) * gv.n_tot;
     const int n0 = gv.node_off[b], n_b = gv.node_off[b + 1] - n0;
     const int cl = P.cur_node[b];
     const int cur = (cl >= 0 && cl < n_b) ? n0 + cl : -1;
-    const int c_begin = plan.ck_off[b], c_end = plan.ck_off[b + 1];
+    const int tm = gv.tmpl[b];
+    const int c_begin = plan.ck_off[tm], c_end = plan.ck_off[tm + 1];
     if (c_begin >= c_end) return;
-    // one row past both directions' messages (and one byte past both directions' bits) is
-    // never written: the address of dummy loads, relative to this direction's base.  The row
-    // (byte) after it, and row n_tot of emb, take the stores of a chunk's unused rows: every
-    // lane stores on every chunk, so the number of stores in flight behind a load is known
-    // when the kernel is compiled and a wait for that load does not wait for the stores.
+    // one row past both directions' messages is never written and reads as zero: the address of
+    // the loads of rows without a far source, relative to this direction's base.  The row after
+    // it (and the byte past both directions' bits, and row n_tot of emb) take the stores of a
+    // chunk's unused rows: every lane stores on every chunk, so the number of stores in flight
+    // behind a load is known when the kernel is compiled and a wait for that load does not wait
+    // for the stores.
     const int spare_row = (2 - dir) * gv.n_tot;
     const int sink_row = spare_row + 1;
 
@@ -202,7 +201,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         for (int i = tid; i < (kMaxD + 1) * H; i += kThreads)
             proj_dev[i] = (i < D * H) ? P.proj[2 * H + i] : 0.0f;
     }
-    const float4 *featb = P.featb + static_cast<size_t>(dir) * gv.n_tot;
+    const float4 *featb = P.featb + static_cast<size_t>(dir) * gv.n_tot + n0;
     // the device's row of W_in comes from LDS: read early (device_term), used late (project)
     auto device_term = [&](const f32x4 ft, int t) {
         const int dev = __float_as_int(ft[3]) & 0xFFFF;
@@ -220,272 +219,257 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     for (int i = tid; i < (kMsgSlots + 1) * LDM; i += kThreads) msgtab[i] = 0.0f;
     for (int i = tid; i < 2 * NT * 16 * LDA; i += kThreads) (&actbuf[0][0][0])[i] = static_cast<__bf16>(0.0f);
 
-    // Writes y, split exactly into three bf16 parts, as rows 4 r .. 4 r + 2 of an A operand.
-    auto put_parts = [&](int buf, int r, int m, float y) {
-        const float rr = y - trunc_bf16(y);
-        const float ll = rr - trunc_bf16(rr);
-        unsigned short *dst = reinterpret_cast<unsigned short *>(&actbuf[buf][4 * r][m]);
-        dst[0] = static_cast<unsigned short>(__float_as_uint(y) >> 16);
-        dst[LDA] = static_cast<unsigned short>(__float_as_uint(rr) >> 16);
-        dst[2 * LDA] = static_cast<unsigned short>(__float_as_uint(ll) >> 16);
+    // Writes this lane's values of node row r, split exactly into three bf16 parts, as rows
+    // 4 r .. 4 r + 2 of an A operand.  Two columns per lane travel as one word per part: word
+    // 16 wave + col of a row holds columns wc0 + col (low half) and wc0 + 16 + col (high half),
+    // which is the order in which pack_sweep_weights lays out the contraction index.
+    auto put_rows = [&](int buf, int r, const float (&y)[TPW]) {
+        float rr[TPW], ll[TPW];
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            rr[t] = y[t] - trunc_bf16(y[t]);
+            ll[t] = rr[t] - trunc_bf16(rr[t]);
+        }
+        if constexpr (TPW == 2) {
+            uint32_t *dst = reinterpret_cast<uint32_t *>(&actbuf[buf][4 * r][0]) + 16 * wave + col;
+            dst[0] = pack_hi16(y[0], y[1]);
+            dst[LDA / 2] = pack_hi16(rr[0], rr[1]);
+            dst[LDA] = pack_hi16(ll[0], ll[1]);
+        } else {
+            unsigned short *dst = reinterpret_cast<unsigned short *>(&actbuf[buf][4 * r][wc0 + col]);
+            dst[0] = static_cast<unsigned short>(__float_as_uint(y[0]) >> 16);
+            dst[LDA] = static_cast<unsigned short>(__float_as_uint(rr[0]) >> 16);
+            dst[2 * LDA] = static_cast<unsigned short>(__float_as_uint(ll[0]) >> 16);
+        }
     };
 
     // ---- gather of a chunk: a_v = sum of neighbour messages, for rows kg and kg + 4 and this
-    // wave's columns, from the wave's own part of the LDS table; written as A rows of the first
-    // layer.  K entries of every row record are summed (unused entries name the zero row).
-    // Reverse pass: the sum is gated by bit 0 of the row's mask and kept in gs (it is the delta
-    // of f's last layer, stored when the chunk is processed).
-    auto gather_fixed = [&](auto kc, int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT],
-                            const int (&mk)[NT][TPW], float (&gs)[NT][TPW]) {
+    // wave's columns: K table slots of the row's record (unused entries name the zero row) and
+    // the row's far message, which is already in registers (zeros if the row has none); written
+    // as A rows of the first layer.  Reverse pass: the sum is gated by bit 0 of the row's mask
+    // and kept in gs (it is the delta of f's last layer, stored when the chunk is processed).
+    auto finish_row = [&](int ct, float (&s)[TPW], uint32_t signs, int (&bit)[NT], const int (&mk)[NT][TPW],
+                          float (&gs)[NT][TPW]) {
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            if constexpr (BW) {
+                s[t] = (mk[ct][t] & 1) ? s[t] : 0.0f;
+                gs[ct][t] = s[t];
+            }
+            if constexpr (TR) gs[ct][t] = s[t];
+        }
+        put_rows(0, 4 * ct + kg, s);
+        bit[ct] = static_cast<int>(signs >> 31);
+    };
+    auto sum_slots = [&](auto kc, uint32_t slots, const float (&far)[TPW], float (&s)[TPW], uint32_t &signs) {
         constexpr int K = decltype(kc)::value;
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            s[t] = BW ? far[t] : fabsf(far[t]);
+            if (!BW && t == 0) signs |= __float_as_uint(far[t]);
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int slot = static_cast<int>((slots >> (6 * k)) & 63u);
+            const float *row = msgtab + slot * LDM;
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) {
+                const float x = row[wc0 + 16 * t + col];
+                s[t] += BW ? x : fabsf(x);
+                if (!BW && t == 0) signs |= __float_as_uint(x);
+            }
+        }
+    };
+    auto gather_fixed = [&](auto kc, int ntile_x, const u32x4 (&rec)[NT], const float (&far)[NT][TPW], int (&bit)[NT],
+                            const int (&mk)[NT][TPW], float (&gs)[NT][TPW]) {
 #pragma unroll
         for (int ct = 0; ct < NT; ++ct) {
             bit[ct] = 0;
             if (ct >= ntile_x) continue;
-            const u32x4 rec = ent[ct];
             float s[TPW];
             uint32_t signs = 0;
-#pragma unroll
-            for (int k = 0; k < K; ++k) {
-                const int slot = static_cast<int>((rec[k / 5] >> (6 * (k % 5))) & 63u);
-                const float *row = msgtab + slot * LDM;
-#pragma unroll
-                for (int t = 0; t < TPW; ++t) {
-                    const float x = row[wc0 + 16 * t + col];
-                    const float ax = BW ? x : fabsf(x);
-                    s[t] = k == 0 ? ax : s[t] + ax;
-                    if (!BW && t == 0) signs |= __float_as_uint(x);
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < TPW; ++t) {
-                if constexpr (BW) {
-                    s[t] = (mk[ct][t] & 1) ? s[t] : 0.0f;
-                    gs[ct][t] = s[t];
-                }
-                if constexpr (TR) gs[ct][t] = s[t];
-                put_parts(0, 4 * ct + kg, wc0 + 16 * t + col, s[t]);
-            }
-            bit[ct] = static_cast<int>(signs >> 31);
+            sum_slots(kc, rec[ct][0], far[ct], s, signs);
+            finish_row(ct, s, signs, bit, mk, gs);
         }
     };
-    // The same for a chunk in which some row has more neighbours than its record holds: that
-    // row sums a list of table slots (recent sources) and node ids (sources at least three
-    // chunks back, read from HBM).
-    auto gather_general = [&](int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT],
+    // The same for a chunk in which some row has more sources than its record holds: that row
+    // sums a list of table slots (near sources) and node ids (far sources, read from HBM here).
+    auto gather_general = [&](int ntile_x, const u32x4 (&rec)[NT], const float (&far)[NT][TPW], int (&bit)[NT],
                               const int (&mk)[NT][TPW], float (&gs)[NT][TPW]) {
 #pragma unroll
         for (int ct = 0; ct < NT; ++ct) {
             bit[ct] = 0;
             if (ct >= ntile_x) continue;
-            const u32x4 rec = ent[ct];
-            const bool listed = ((rec[0] >> 30) & 1u) != 0;
             float s[TPW];
             uint32_t signs = 0;
+            if ((rec[ct][0] & kRecListed) == 0) {
+                sum_slots(std::integral_constant<int, kMaxNear>{}, rec[ct][0], far[ct], s, signs);
+            } else {
 #pragma unroll
-            for (int t = 0; t < TPW; ++t) s[t] = 0.0f;
+                for (int t = 0; t < TPW; ++t) s[t] = 0.0f;
+                const int d0 = static_cast<int>(rec[ct][1]);
+                const int d1 = d0 + static_cast<int>(rec[ct][0] & 0xFFFFFFu);
+                // An entry is a table slot or a node id; the other source of the pair is the
+                // table's zero row or the spare (all-zero, never written) row of msg, so both are
+                // always read and added, in list order.
+                if constexpr (TPW == 1) {
+                    // The list is walked in passes of PB entries, three passes per step.  The
+                    // sixteen lanes of the row's group first load the step's entries (one load
+                    // each per pass, all in flight together) and hand them round with lane
+                    // shuffles; then a pass issues all its loads before the first use.
+                    constexpr int PB = 16;
+                    for (int p0 = d0; p0 < d1; p0 += 3 * PB) {
+                        int idv[3];
 #pragma unroll
-            for (int k = 0; k < kMaxEnt; ++k) {
-                const int raw = static_cast<int>((rec[k / 5] >> (6 * (k % 5))) & 63u);
-                const float *row = msgtab + (listed ? kZeroSlot : raw) * LDM;
+                        for (int q = 0; q < 3; ++q) {
+                            const int at = p0 + q * PB + (col % PB);
+                            idv[q] = (at < d1) ? plan.ovf[at] : -1 - kZeroSlot;
+                        }
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) {
-                    const float x = row[wc0 + 16 * t + col];
-                    s[t] += BW ? x : fabsf(x);
-                    if (!BW) signs |= __float_as_uint(x);
-                }
-            }
-            if (listed) {
-                const int d0 = static_cast<int>(rec[1]);
-                const int d1 = d0 + static_cast<int>(rec[2]);
-                // The list is walked in passes of PB entries, three passes per step.  The sixteen
-                // lanes of the row's group first load the step's entries (one load each per
-                // pass, all in flight together) and hand them round with lane shuffles; then a
-                // pass issues all its loads before the first use.  An entry is a table slot or a
-                // node id; the other source of the pair is the table's zero row or the spare
-                // (all-zero, never written) row of msg, so both are always read and added, in
-                // list order.
-                constexpr int PB = 16;
-                if constexpr (TPW == 1)
-                for (int p0 = d0; p0 < d1; p0 += 3 * PB) {
-                    int idv[3];
+                        for (int q = 0; q < 3; ++q) {
+                            if (p0 + q * PB >= d1) break;
+                            float xl[PB], xg[PB];
 #pragma unroll
-                    for (int q = 0; q < 3; ++q) {
-                        const int at = p0 + q * PB + (col % PB);
-                        idv[q] = (at < d1) ? plan.ovf[at] : -1 - kZeroSlot;
+                            for (int k = 0; k < PB; ++k) {
+                                const int u = __shfl(idv[q], (lane & 48) + k);
+                                const float *row = msgtab + (u < 0 ? -1 - u : kZeroSlot) * LDM;
+                                const int v = u >= 0 ? n0 + u : spare_row;
+                                xl[k] = row[wc0 + col];
+                                xg[k] = msg[static_cast<uint32_t>(v * H + wc0 + col)];
+                            }
+#pragma unroll
+                            for (int k = 0; k < PB; ++k) {
+                                s[0] += BW ? xl[k] + xg[k] : fabsf(xl[k]) + fabsf(xg[k]);
+                                if (!BW) signs |= __float_as_uint(xl[k]) | __float_as_uint(xg[k]);
+                            }
+                        }
                     }
+                } else {
+                    // two column tiles per wave leave no registers for that: four entries at a time
+                    for (int p = d0; p < d1; p += 4) {
+                        int u[4];
 #pragma unroll
-                    for (int q = 0; q < 3; ++q) {
-                        if (p0 + q * PB >= d1) break;
-                        int u[PB];
-                        float xl[PB][TPW], xg[PB][TPW];
-                        int rg[PB];
+                        for (int k = 0; k < 4; ++k) u[k] = p + k < d1 ? plan.ovf[p + k] : -1 - kZeroSlot;
+                        float xl[4][TPW], xg[4][TPW];
 #pragma unroll
-                        for (int k = 0; k < PB; ++k) {
-                            u[k] = __shfl(idv[q], (lane & 48) + k);
+                        for (int k = 0; k < 4; ++k) {
                             const float *row = msgtab + (u[k] < 0 ? -1 - u[k] : kZeroSlot) * LDM;
-                            const int v = u[k] >= 0 ? u[k] : spare_row;
+                            const int v = u[k] >= 0 ? n0 + u[k] : spare_row;
 #pragma unroll
                             for (int t = 0; t < TPW; ++t) {
                                 xl[k][t] = row[wc0 + 16 * t + col];
                                 xg[k][t] = msg[static_cast<uint32_t>(v * H + wc0 + 16 * t + col)];
                             }
-                            rg[k] = BW ? 0 : reach[static_cast<uint32_t>(v)];
                         }
 #pragma unroll
-                        for (int k = 0; k < PB; ++k) {
+                        for (int k = 0; k < 4; ++k) {
 #pragma unroll
-                            for (int t = 0; t < TPW; ++t) {
-                                s[t] += (BW ? xl[k][t] : fabsf(xl[k][t])) + xg[k][t];
-                                if (!BW) signs |= __float_as_uint(xl[k][t]);
-                            }
-                            if (!BW) signs |= ((u[k] >= 0) & ((u[k] == cur) | (rg[k] != 0))) ? 0x80000000u : 0u;
+                            for (int t = 0; t < TPW; ++t)
+                                s[t] += BW ? xl[k][t] + xg[k][t] : fabsf(xl[k][t]) + fabsf(xg[k][t]);
+                            if (!BW) signs |= __float_as_uint(xl[k][0]) | __float_as_uint(xg[k][0]);
                         }
-                    }
-                }
-                // two column tiles per wave leave no registers for that: four entries at a time
-                if constexpr (TPW > 1)
-                for (int p = d0; p < d1; p += 4) {
-                    int u[4];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) u[k] = p + k < d1 ? plan.ovf[p + k] : -1 - kZeroSlot;
-                    float xl[4][TPW], xg[4][TPW];
-                    int rg[4];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const float *row = msgtab + (u[k] < 0 ? -1 - u[k] : kZeroSlot) * LDM;
-                        const int v = u[k] >= 0 ? u[k] : spare_row;
-#pragma unroll
-                        for (int t = 0; t < TPW; ++t) {
-                            xl[k][t] = row[wc0 + 16 * t + col];
-                            xg[k][t] = msg[static_cast<uint32_t>(v * H + wc0 + 16 * t + col)];
-                        }
-                        rg[k] = BW ? 0 : reach[static_cast<uint32_t>(v)];
-                    }
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-#pragma unroll
-                        for (int t = 0; t < TPW; ++t) {
-                            s[t] += (BW ? xl[k][t] : fabsf(xl[k][t])) + xg[k][t];
-                            if (!BW) signs |= __float_as_uint(xl[k][t]);
-                        }
-                        if (!BW) signs |= ((u[k] >= 0) & ((u[k] == cur) | (rg[k] != 0))) ? 0x80000000u : 0u;
                     }
                 }
             }
-#pragma unroll
-            for (int t = 0; t < TPW; ++t) {
-                if constexpr (BW) {
-                    s[t] = (mk[ct][t] & 1) ? s[t] : 0.0f;
-                    gs[ct][t] = s[t];
-                }
-                if constexpr (TR) gs[ct][t] = s[t];
-                put_parts(0, 4 * ct + kg, wc0 + 16 * t + col, s[t]);
-            }
-            bit[ct] = static_cast<int>(signs >> 31);
+            finish_row(ct, s, signs, bit, mk, gs);
         }
     };
-    // w = meta.w of the chunk: most entries of a row | (a row uses the list) << 8
-    auto gather = [&](int w, int ntile_x, const u32x4 (&ent)[NT], int (&bit)[NT], const int (&mk)[NT][TPW],
-                      float (&gs)[NT][TPW]) {
-        if (w <= 2)
-            gather_fixed(std::integral_constant<int, 2>{}, ntile_x, ent, bit, mk, gs);
-        else if (w <= 5)
-            gather_fixed(std::integral_constant<int, 5>{}, ntile_x, ent, bit, mk, gs);
-        else if (w <= kMaxEnt)
-            gather_fixed(std::integral_constant<int, kMaxEnt>{}, ntile_x, ent, bit, mk, gs);
+    // info = word 3 of a record of the chunk (its chunk-wide bits)
+    auto gather = [&](uint32_t info, const u32x4 (&rec)[NT], const float (&far)[NT][TPW], int (&bit)[NT],
+                      const int (&mk)[NT][TPW], float (&gs)[NT][TPW]) {
+        const int ntile_x = (static_cast<int>((info >> kRecRowsShift) & 7u) + kTileNodes) / kTileNodes;
+        const int cls = static_cast<int>((info >> kRecNearShift) & 3u);
+        if ((info >> kRecGeneralBit) & 1u)
+            gather_general(ntile_x, rec, far, bit, mk, gs);
+        else if (cls == 0)
+            gather_fixed(std::integral_constant<int, 1>{}, ntile_x, rec, far, bit, mk, gs);
+        else if (cls == 1)
+            gather_fixed(std::integral_constant<int, 2>{}, ntile_x, rec, far, bit, mk, gs);
         else
-            gather_general(ntile_x, ent, bit, mk, gs);
+            gather_fixed(std::integral_constant<int, kMaxNear>{}, ntile_x, rec, far, bit, mk, gs);
     };
+    auto rows_of = [](uint32_t info) { return static_cast<int>((info >> kRecRowsShift) & 7u) + 1; };
 
-    // ---- software pipeline state.  m0 describes chunk c, m1 chunk c + 1.  A lane works on
-    // rows kg (tile 0) and kg + 4 (tile 1) of a chunk.
+    // ---- software pipeline state.  rc1, rc2 are the records of chunks c + 1 and c + 2; of chunk
+    // c only the node ids, the row count and the bucket position are kept.  A lane works on rows
+    // kg (tile 0) and kg + 4 (tile 1) of a chunk.
     auto clampc = [&](int c) { return c < c_end ? c : c_end - 1; };
-    int4 m0 = load_uniform(plan.meta + c_begin);
-    int4 m1 = load_uniform(plan.meta + clampc(c_begin + 1));
-    u32x4 ent1[NT];          // neighbour records of the rows of the chunk gathered next
-    int vg0[NT], vg1[NT];    // node ids of the rows of chunk c, c + 1
+    auto load_rec = [&](int c, int ct) {
+        return *reinterpret_cast<const u32x4 *>(plan.rec + static_cast<size_t>(clampc(c)) * CH + 4 * ct + kg);
+    };
+    u32x4 rc1[NT], rc2[NT];
+    int vg0[NT];             // global node ids of the rows of chunk c (any valid id for unused rows)
+    int rows0, p0;           // rows and first bucket position (within the graph) of chunk c
     f32x4 ft0[NT];           // raw-feature records of the rows of chunk c        (FF)
     float x0[NT][TPW];       // residual inputs x_v of chunk c
     float x1[NT][TPW];       // ... of chunk c + 1                                  (!FF)
     int bit0[NT];            // reachability bits of the rows of chunk c
-    int fid1[PFN];           // far sources of chunk c + 1
+    float far1[NT][TPW];     // far messages of the rows of chunk c + 1 (arrived or arriving)
+    float far2[NT][TPW];     // ... of chunk c + 2 (loaded during chunk c)
     int mk0[NT][TPW], mk1[NT][TPW];   // (BW) gate bytes of the rows of chunk c, c + 1
     float gs0[NT][TPW];      // (BW) gated gathered sums of chunk c: the delta of f's last layer
-    const uint8_t *mask4 = BW ? P.mask4 + static_cast<size_t>(dir) * gv.n_tot * H : nullptr;
+    const uint8_t *mask4 = BW ? P.mask4 + (static_cast<size_t>(dir) * gv.n_tot + n0) * H : nullptr;
+    const float *xin = xb + static_cast<size_t>(n0) * H;
     float *dlt = BW ? P.delta + static_cast<size_t>(1 - dir) * P.delta_stride
                     : (TR ? P.delta + static_cast<size_t>(dir) * P.delta_stride : nullptr);
+    {
+        u32x4 rc0[NT];
 #pragma unroll
-    for (int ct = 0; ct < NT; ++ct)
-#pragma unroll
-        for (int t = 0; t < TPW; ++t) {
-            mk0[ct][t] = mk1[ct][t] = 0;
-            gs0[ct][t] = 0.0f;
-        }
-#pragma unroll
-    for (int ct = 0; ct < NT; ++ct) {
-        const int r = 4 * ct + kg;
-        const int rr = r < m0.y ? r : 0;
-        ent1[ct] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(c_begin) * CH + r);
-        vg0[ct] = order[m0.x + rr];
-        vg1[ct] = vg0[ct];
-        if constexpr (FF) {
-            ft0[ct] = *reinterpret_cast<const f32x4 *>(featb + m0.x + rr);
-        } else {
+        for (int ct = 0; ct < NT; ++ct) {
+            rc0[ct] = load_rec(c_begin, ct);
+            rc1[ct] = load_rec(c_begin + 1, ct);
+            rc2[ct] = load_rec(c_begin + 2, ct);
 #pragma unroll
             for (int t = 0; t < TPW; ++t) {
-                x0[ct][t] = xb[static_cast<size_t>(m0.x + rr) * H + wc0 + 16 * t + col];
-                x1[ct][t] = x0[ct][t];
-                if constexpr (BW) {
-                    mk0[ct][t] = mask4[static_cast<size_t>(m0.x + rr) * H + wc0 + 16 * t + col];
-                    mk1[ct][t] = mk0[ct][t];
+                far1[ct][t] = far2[ct][t] = 0.0f;     // the first kRing + 1 chunks have no far sources
+                mk0[ct][t] = mk1[ct][t] = 0;
+                gs0[ct][t] = 0.0f;
+                x0[ct][t] = x1[ct][t] = 0.0f;
+            }
+        }
+        const uint32_t info0 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rc0[0][3])));
+        rows0 = rows_of(info0);
+        p0 = __builtin_amdgcn_readfirstlane(static_cast<int>(rc0[0][2]));
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) {
+            const int r = 4 * ct + kg;
+            const int rr = r < rows0 ? r : 0;
+            const uint32_t id = rc0[ct][3] & kRecNoNode;
+            vg0[ct] = n0 + static_cast<int>(id == kRecNoNode ? 0u : id);
+            if constexpr (FF) {
+                ft0[ct] = *reinterpret_cast<const f32x4 *>(featb + p0 + rr);
+            } else {
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) {
+                    x0[ct][t] = xin[static_cast<size_t>(p0 + rr) * H + wc0 + 16 * t + col];
+                    if constexpr (BW) mk0[ct][t] = mask4[static_cast<size_t>(p0 + rr) * H + wc0 + 16 * t + col];
                 }
             }
         }
-    }
-#pragma unroll
-    for (int i = 0; i < PFN; ++i) {
-        const int f = (lane + 64 * i) / QW;
-        fid1[i] = (f < FCAP) ? plan.far[static_cast<size_t>(clampc(c_begin + 1)) * FCAP + f] : -1;
-    }
-    __syncthreads();
-    gather(m0.w, (m0.y + kTileNodes - 1) / kTileNodes, ent1, bit0, mk0, gs0);
-    // every load so far has returned before the loop is entered (inside the loop the compiler
-    // then never waits for more than the loads of the loop's own batch)
-#pragma unroll
-    for (int i = 0; i < PFN; ++i) asm volatile("" ::"v"(fid1[i]));
-#pragma unroll
-    for (int ct = 0; ct < NT; ++ct) {
-        asm volatile("" ::"v"(vg0[ct]), "v"(vg1[ct]));
-        if constexpr (FF) {
-            asm volatile("" ::"v"(ft0[ct][0]));
-        } else {
-#pragma unroll
-            for (int t = 0; t < TPW; ++t) asm volatile("" ::"v"(x0[ct][t]), "v"(x1[ct][t]));
-            if constexpr (BW) {
-#pragma unroll
-                for (int t = 0; t < TPW; ++t) asm volatile("" ::"v"(mk0[ct][t]), "v"(mk1[ct][t]));
-            }
-        }
+        __syncthreads();
+        gather(info0, rc0, far1, bit0, mk0, gs0);
     }
     __syncthreads();
 
     for (int c = c_begin; c < c_end; ++c) {
-        const int rows = m0.y;
+        const int rows = rows0;
         const bool two = rows > kTileNodes;      // the chunk fills a second row tile
         const bool has_next = c + 1 < c_end;
-        const int par = (c - c_begin) & 1;
+        const int ring = (c - c_begin) % RING;   // table rows ring * CH .. of this chunk's messages
+        const uint32_t info1 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rc1[0][3])));
+        const int rows1 = rows_of(info1);
+        const int p1 = __builtin_amdgcn_readfirstlane(static_cast<int>(rc1[0][2]));
 
-        // Plain vector types on purpose: arrays of the HIP float4 class that are written in one
-        // unrolled branch and read in another are not always split into registers.
-        f32x4 pf[PFN];           // far messages of chunk c + 1, in flight during the later layers
-        int pf_reach[PFN];
-        bool pf_cur[PFN];
-        int4 m2 = m1;
-        int warm = 0;            // see the prefetch of the chunk records below
-        // Accumulators: a chunk of one row tile splits its k-steps over two chains per column
-        // tile (acc[chain][t]); a chunk of two row tiles runs one chain per (row tile, column
-        // tile) (acc[ct][t]): four independent chains either way.
+        u32x4 rc3[NT];
+        f32x4 ft1[NT];
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) {
+            rc3[ct] = rc2[ct];
+            if constexpr (FF) ft1[ct] = ft0[ct];
+        }
+        // Accumulators, one chain per (row tile, column tile): acc[ct][t].  The chains of a wave's
+        // column tiles (and of the co-resident workgroup) interleave, so a dependent matrix
+        // instruction never waits for its predecessor.
         f32x4 acc[2][TPW];
 
 #pragma unroll
@@ -499,14 +483,9 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     for (int t = 0; t < TPW; ++t)
 #pragma unroll
                         for (int ws = 0; ws < WS; ++ws) {
-                            const f32x4 c_in = (ks < NACC && ws == 0) ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[ks % NACC][t];
-                            acc[ks % NACC][t] =
-                                __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W[n][t][ks][ws], c_in, 0, 0, 0);
+                            const f32x4 c_in = (ks == 0 && ws == 0) ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[0][t];
+                            acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W[n][t][ks][ws], c_in, 0, 0, 0);
                         }
-                }
-                if constexpr (NACC == 1) {
-#pragma unroll
-                    for (int t = 0; t < TPW; ++t) acc[1][t] = f32x4{0.f, 0.f, 0.f, 0.f};
                 }
             };
             auto mfma_two_tiles = [&]() {
@@ -526,7 +505,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     }
             };
             // ---- epilogue: lane (col, kg) holds, for node 4 ct + kg and output column
-            // wc0 + 16 t + col, the three partial products in rows 0..2 of its accumulators
+            // wc0 + 16 t + col, the three partial products in rows 0..2 of its accumulators.
             // Row tile 0 is handled by code common to both kinds of chunk, so that its stores
             // are on every path (see sink_row).
             auto epilogue = [&](int ct) {
@@ -534,14 +513,11 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 const bool live = r < rows;
                 const int v_emb = live ? vg0[ct] : gv.n_tot;
                 const int v_msg = live ? vg0[ct] : sink_row;
+                float yv[TPW];
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
                     const int m = wc0 + 16 * t + col;
                     float y = acc[ct][t][0] + acc[ct][t][1] + acc[ct][t][2];
-                    if (ct == 0) {                       // one row tile: acc[1] is the second chain
-                        const float y1 = acc[1][t][0] + acc[1][t][1] + acc[1][t][2];
-                        y += two ? 0.0f : y1;
-                    }
                     if constexpr (BW) {
                         // delta slot of this layer's gated output: f's layers L-2 .. 0, then g's
                         // layers L-1 .. 0; slot = index into the 2L delta arrays (f first)
@@ -565,10 +541,9 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         }
                         if (n == NL - 1) {               // end of g^T: da_v
                             msg[static_cast<uint32_t>(v_msg * H + m)] = y;
-                            msgtab[(par * CH + r) * LDM + m] = y;
-                        } else {
-                            put_parts((n + 1) & 1, r, m, y);
+                            msgtab[(ring * CH + r) * LDM + m] = y;
                         }
+                        yv[t] = y;
                         continue;
                     }
                     y = fmaxf(y + bias[n][t], 0.0f);
@@ -581,16 +556,17 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     if (n == L - 1) {                    // end of g: residual update of s_v
                         y += x0[ct][t];
                         P.emb[static_cast<uint32_t>(v_emb * 2 * H + dir * H + m)] = y;
-                        if constexpr (WX) xb[static_cast<uint32_t>((live ? m0.x + r : spare_row) * H + m)] = y;
+                        if constexpr (WX) xb[static_cast<uint32_t>((live ? n0 + p0 + r : spare_row) * H + m)] = y;
                     }
-                    if (n == NL - 1) {                   // end of f: the message of v
-                        msg[static_cast<uint32_t>(v_msg * H + m)] = y;
+                    if (n == NL - 1) {                   // end of f: the message of v, flagged
                         const uint32_t flag = (bit0[ct] | (vg0[ct] == cur)) ? 0x80000000u : 0u;
-                        msgtab[(par * CH + r) * LDM + m] = __uint_as_float(__float_as_uint(y) | flag);
-                    } else {
-                        put_parts((n + 1) & 1, r, m, y);
+                        const float flagged = __uint_as_float(__float_as_uint(y) | flag);
+                        msg[static_cast<uint32_t>(v_msg * H + m)] = flagged;
+                        msgtab[(ring * CH + r) * LDM + m] = flagged;
                     }
+                    yv[t] = y;
                 }
+                if (n < NL - 1) put_rows((n + 1) & 1, r, yv);
             };
 
             if (two)
@@ -599,14 +575,12 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 mfma_one_tile();
 
             if (n == 0) {
-                // The inputs of this chunk's residual, then the loads for the next chunk, issued
-                // behind the first layer's matrix instructions.  The loads may read messages
-                // that this workgroup stored to HBM at least two chunks ago.  Those stores are
-                // complete: vector memory operations of a wave retire in order, and every wave
-                // waited for its own previous batch of these loads (issued after those stores)
-                // before the last barrier of the previous chunk.
-                // Work for a second row tile (rows 4..7) is skipped when the chunk has none, and
-                // far rows beyond the first 64 / QW only when the next chunk stages that many.
+                // Behind the first layer's matrix instructions: the far messages of chunk c + 2
+                // (this wave's columns, in the layout in which they are summed).  A row without
+                // a far source reads the row of zeros.  The messages were stored by this wave
+                // at least kRing - 1 chunks ago; see the note at the top of the file.
+                const uint32_t info2 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rc2[0][3])));
+                const bool two2 = rows_of(info2) > kTileNodes;
                 float dterm[NT][TPW];
                 if constexpr (FF) {
 #pragma unroll
@@ -617,27 +591,14 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         }
                 }
 #pragma unroll
-                for (int i = 0; i < PFN; ++i) {
-                    if (i > 0 && m1.z <= i * (64 / QW)) continue;
-                    const int e = lane + 64 * i;
-                    const int f = e / QW, q = e - f * QW;
-                    const bool wanted = has_next && f < m1.z && fid1[i] >= 0;
-                    // lanes without a far source read a spare row that is never written, so
-                    // that every wave has a load of this batch to wait for
-                    const int u = wanted ? fid1[i] : spare_row;
-                    pf[i] = *reinterpret_cast<const f32x4 *>(msg + static_cast<uint32_t>(u * H + wc0 + 4 * q));
-                    pf_reach[i] = BW ? 0 : reach[static_cast<uint32_t>(u)];   // combined with pf_cur at the end of the chunk
-                    pf_cur[i] = wanted && u == cur;
-                }
-                // The chunk records come in through the scalar cache, and a scalar load cannot be
-                // overlapped with LDS work: every wait for LDS data also waits for the scalar loads
-                // in flight.  So a vector load touches the record of a chunk some way ahead (its
-                // value is not used): the scalar load of that record then finds its line in L2
-                // instead of going to HBM every fourth chunk.
-                {
-                    int opaque = 0;
-                    asm volatile("" : "+v"(opaque));
-                    warm = reinterpret_cast<const int *>(plan.meta + clampc(c + kWarmAhead))[opaque];
+                for (int ct = 0; ct < NT; ++ct) {
+                    if (ct > 0 && !two2) continue;
+                    const uint32_t u = rc2[ct][1];
+                    const bool wanted = (rc2[ct][0] & kRecListed) == 0 && u != kNoFar;
+                    const int row = wanted ? n0 + static_cast<int>(u) : spare_row;
+#pragma unroll
+                    for (int t = 0; t < TPW; ++t)
+                        far2[ct][t] = msg[static_cast<uint32_t>(row * H + wc0 + 16 * t + col)];
                 }
                 if constexpr (FF) {
 #pragma unroll
@@ -649,85 +610,37 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 }
             }
             if (n == (NL > 2 ? 1 : 0)) {
-                // the rest of the batch, behind the second layer's matrix instructions
-                const bool two_next = m1.y > kTileNodes;
-                m2 = load_uniform(plan.meta + clampc(c + 2));
+                // behind the second layer's matrix instructions: the records of chunk c + 3 and
+                // the inputs of chunk c + 1
+                const bool two1 = rows1 > kTileNodes;
 #pragma unroll
                 for (int ct = 0; ct < NT; ++ct) {
-                    if (ct > 0 && !two_next) continue;
+                    rc3[ct] = load_rec(c + 3, ct);
+                    if (ct > 0 && !two1) continue;
                     const int r = 4 * ct + kg;
-                    const int rr = (r < m1.y) ? r : 0;
-                    ent1[ct] = *reinterpret_cast<const u32x4 *>(plan.ent + static_cast<size_t>(clampc(c + 1)) * CH +
-                                                               static_cast<uint32_t>(r));
-                    vg1[ct] = (order + m1.x)[static_cast<uint32_t>(rr)];
+                    const int rr = (r < rows1) ? r : 0;
                     if constexpr (FF) {
-                        ft0[ct] = *reinterpret_cast<const f32x4 *>(featb + m1.x + static_cast<uint32_t>(rr));
+                        ft1[ct] = *reinterpret_cast<const f32x4 *>(featb + p1 + static_cast<uint32_t>(rr));
                     } else {
 #pragma unroll
                         for (int t = 0; t < TPW; ++t) {
-                            x1[ct][t] = (xb + static_cast<size_t>(m1.x) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
+                            x1[ct][t] = (xin + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
                             if constexpr (BW)
-                                mk1[ct][t] = (mask4 + static_cast<size_t>(m1.x) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
+                                mk1[ct][t] = (mask4 + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
                         }
                     }
-                }
-#pragma unroll
-                for (int i = 0; i < PFN; ++i) {     // ids staged two chunks ahead of their data
-                    const int f = (lane + 64 * i) / QW;
-                    fid1[i] = (f < FCAP) ? (plan.far + static_cast<size_t>(clampc(c + 2)) * FCAP)[static_cast<uint32_t>(f)] : -1;
                 }
             }
 
             if (n == NL - 1) {
                 // Behind the last layer's matrix instructions: the reachability bits of this
-                // chunk's nodes go to HBM and the far messages of the next chunk into the table.
+                // chunk's nodes go to HBM (for the pooling kernel).
                 if constexpr (!BW) {
 #pragma unroll
                     for (int ct = 0; ct < NT; ++ct) {
                         const int r = ct * kTileNodes + kg;
-                        reach[static_cast<uint32_t>((wave == 0 && col == 0 && r < rows) ? vg0[ct] : sink_row)] =
-                            static_cast<uint8_t>(bit0[ct]);
-                    }
-                }
-                // Wait for this wave's prefetch batch whether or not a lane uses it: the stores
-                // that preceded it are then complete too (see the note at the prefetch).
-#pragma unroll
-                for (int i = 0; i < PFN; ++i) asm volatile("" ::"v"(pf[i][0]), "v"(pf_reach[i]), "v"(fid1[i]));
-                asm volatile("" ::"v"(warm));
-                // ... and for the rest of the batch, which the next chunk then uses without waiting
-#pragma unroll
-                for (int ct = 0; ct < NT; ++ct) {
-                    asm volatile("" ::"v"(ent1[ct][0]), "v"(vg1[ct]));
-                    if constexpr (FF) {
-                        asm volatile("" ::"v"(ft0[ct][0]));
-                    } else {
-#pragma unroll
-                        for (int t = 0; t < TPW; ++t) asm volatile("" ::"v"(x1[ct][t]));
-                        if constexpr (BW) {
-#pragma unroll
-                            for (int t = 0; t < TPW; ++t) asm volatile("" ::"v"(mk1[ct][t]));
-                        }
-                    }
-                }
-                if (has_next) {
-                    // An offset the compiler cannot see through, defined only here: without it
-                    // the staged LDS stores below are scheduled right behind their loads, which
-                    // puts the whole HBM latency back on the critical path.
-                    int late = 0;
-                    asm volatile("" : "+v"(late));
-#pragma unroll
-                    for (int i = 0; i < PFN; ++i) {     // far messages of chunk c + 1, this wave's columns
-                        if (m1.z <= i * (64 / QW)) continue;
-                        const int e = lane + 64 * i;
-                        const int f = e / QW, q = e - f * QW;
-                        if (f < m1.z) {
-                            const int slot = RING * CH + (par ^ 1) * FCAP + f;
-                            const uint32_t flag = (!BW && ((pf_reach[i] != 0) | pf_cur[i])) ? 0x80000000u : 0u;
-                            f32x4 v;
-#pragma unroll
-                            for (int k = 0; k < 4; ++k) v[k] = __uint_as_float(__float_as_uint(pf[i][k]) | flag);
-                            *reinterpret_cast<f32x4 *>(msgtab + slot * LDM + wc0 + 4 * q + late) = v;
-                        }
+                        const bool mine = wave == 0 && col == 0 && r < rows;
+                        reach[static_cast<uint32_t>(mine ? vg0[ct] : sink_row)] = static_cast<uint8_t>(bit0[ct]);
                     }
                 }
             }
@@ -737,22 +650,28 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
 
             // The table rows that chunk c + 1 sums were all written by this wave (its own
             // columns), so its gather follows without a barrier.
-            if (n == NL - 1 && has_next) gather(m1.w, (m1.y + kTileNodes - 1) / kTileNodes, ent1, bit0, mk1, gs0);
+            if (n == NL - 1 && has_next) gather(info1, rc1, far1, bit0, mk1, gs0);
             lds_barrier();
         }
 
-        m0 = m1;
-        m1 = m2;
+        rows0 = rows1;
+        p0 = p1;
 #pragma unroll
         for (int ct = 0; ct < NT; ++ct) {
-            vg0[ct] = vg1[ct];
-            if constexpr (!FF) {
+            const uint32_t id = rc1[ct][3] & kRecNoNode;
+            vg0[ct] = n0 + static_cast<int>(id == kRecNoNode ? 0u : id);
+            rc1[ct] = rc2[ct];
+            rc2[ct] = rc3[ct];
+            if constexpr (FF) {
+                ft0[ct] = ft1[ct];
+            } else {
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) x0[ct][t] = x1[ct][t];
             }
-            if constexpr (BW) {
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) mk0[ct][t] = mk1[ct][t];
+            for (int t = 0; t < TPW; ++t) {
+                far1[ct][t] = far2[ct][t];
+                if constexpr (BW) mk0[ct][t] = mk1[ct][t];
             }
         }
     }
@@ -779,8 +698,11 @@ __global__ __launch_bounds__(256) void k_bucket_feats(GraphView gv, const float 
 
 // Packs the f and g weights of both directions into MFMA B-operand fragments.
 // Index: ((((dir * 2L + n) * MT + mt) * KS + ks) * WS + ws) * 64 + lane, n = g layers then f
-// layers; lane l holds W[32 ks + 8 (l / 16) + i][16 mt + l % 16], i = 0..7, as bf16 part ws
-// of the exact three-way split (ws = 0 only when the weights are bf16 already).
+// layers; lane l holds W[k(ks, l / 16, i)][16 mt + l % 16], i = 0..7, as bf16 part ws of the
+// exact three-way split (ws = 0 only when the weights are bf16 already).  k is the position of
+// an input column in the kernel's activation rows: 32 ks + 8 (l / 16) + i where a lane owns one
+// output column, and 32 ks + 16 (i % 2) + 4 (l / 16) + i / 2 where it owns two (H = 128: the
+// columns c and c + 16 of a wave travel as the two halves of one word).
 // With `reverse`, the fragments of the reverse pass: index dir is the direction whose chunks are
 // walked, the weights are those of the other direction, transposed, f's layers from the last to
 // the first and then g's (biases are not used there).
@@ -788,6 +710,7 @@ void pack_sweep_weights(const ModelView &mv, const float *blob, int WS, std::vec
                         std::vector<float> *bias, bool reverse)
 {
     const int H = mv.H, L = mv.L, MT = H / 16, KS = H / 32, NL = 2 * L;
+    const bool paired = MT / sweep_waves(H) == 2;
     frag->assign(static_cast<size_t>(2) * NL * MT * KS * WS * 64 * 8, 0);
     bias->assign(static_cast<size_t>(2) * NL * H, 0.0f);
     auto to_bf16 = [](float x) {
@@ -812,7 +735,9 @@ void pack_sweep_weights(const ModelView &mv, const float *blob, int WS, std::vec
                 for (int ks = 0; ks < KS; ++ks)
                     for (int lane = 0; lane < 64; ++lane)
                         for (int i = 0; i < 8; ++i) {
-                            const int k = 32 * ks + 8 * (lane / 16) + i, m = 16 * mt + lane % 16;
+                            const int k = paired ? 32 * ks + 16 * (i % 2) + 4 * (lane / 16) + i / 2
+                                                 : 32 * ks + 8 * (lane / 16) + i;
+                            const int m = 16 * mt + lane % 16;
                             float rest = reverse ? blob[lr.w + static_cast<size_t>(m) * H + k]
                                                  : blob[lr.w + static_cast<size_t>(k) * H + m];
                             for (int ws = 0; ws < WS; ++ws) {

@@ -137,6 +137,57 @@ int build_layout(int32_t B, const int32_t *n_nodes, const int32_t *n_edges,
         bucket_by_level(n_nodes[b], L.depth[b], &L.bu_level[n0], &L.bu_order[n0],
                         &L.bu_lvl_ptr[L.lvl_off[b]]);
     }
+    L.n_templates = B;
+    L.tmpl.resize(B);
+    std::iota(L.tmpl.begin(), L.tmpl.end(), 0);
+    L.tmpl_graph = L.tmpl;
+    return PL_OK;
+}
+
+int replicate_layout(const HostLayout &one, int32_t R, HostLayout *out)
+{
+    if (one.B != 1) return fail(PL_ERR_SHAPE, "only a single graph can be replicated");
+    if (R < 1) return fail(PL_ERR_SHAPE, "the number of copies must be at least 1");
+    const int64_t n = one.n_tot, e = one.e_tot;
+    if (n * R > INT32_MAX / 2 || e * R > INT32_MAX / 2)
+        return fail(PL_ERR_SHAPE, "batch too large for 32-bit device indices");
+    HostLayout &L = *out;
+    L = HostLayout();
+    L.B = R;
+    L.n_tot = n * R;
+    L.e_tot = e * R;
+    L.max_depth = one.max_depth;
+    L.depth.assign(R, one.depth[0]);
+    L.node_off.resize(static_cast<size_t>(R) + 1);
+    L.edge_off.resize(static_cast<size_t>(R) + 1);
+    L.lvl_off.resize(static_cast<size_t>(R) + 1);
+    for (int32_t r = 0; r <= R; ++r) {
+        L.node_off[r] = n * r;
+        L.edge_off[r] = e * r;
+        L.lvl_off[r] = one.lvl_off[1] * r;
+    }
+    auto tile = [R](const auto &src, auto &dst) {      // the same values for every copy
+        dst.reserve(src.size() * R);
+        for (int32_t r = 0; r < R; ++r) dst.insert(dst.end(), src.begin(), src.end());
+    };
+    tile(one.par_idx, L.par_idx);
+    tile(one.chi_idx, L.chi_idx);
+    tile(one.td_level, L.td_level);
+    tile(one.bu_level, L.bu_level);
+    tile(one.td_order, L.td_order);
+    tile(one.bu_order, L.bu_order);
+    tile(one.td_lvl_ptr, L.td_lvl_ptr);
+    tile(one.bu_lvl_ptr, L.bu_lvl_ptr);
+    L.par_ptr.resize(L.n_tot + 1);                      // offsets into the batch-wide lists
+    L.chi_ptr.resize(L.n_tot + 1);
+    for (int32_t r = 0; r < R; ++r)
+        for (int64_t v = 0; v <= n; ++v) {
+            L.par_ptr[n * r + v] = one.par_ptr[v] + e * r;
+            L.chi_ptr[n * r + v] = one.chi_ptr[v] + e * r;
+        }
+    L.n_templates = 1;
+    L.tmpl.assign(R, 0);
+    L.tmpl_graph.assign(1, 0);
     return PL_OK;
 }
 

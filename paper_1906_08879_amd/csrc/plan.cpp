@@ -2,11 +2,11 @@
 //
 // The sweep (Section 2.2 step 2) visits a graph level by level; a level is cut into chunks
 // of at most kChunkRows nodes.  The kernel keeps the messages of the last kRing chunks in an
-// LDS table and stages messages from older chunks ("far" sources) into the same table one
-// chunk ahead.  This file turns the CSR into, per chunk: its position and row count, for
-// every row the LDS table slots of its neighbours (unused entries name the table's zero row,
-// slot kMsgSlots, so that a fixed number of entries can be summed without tests), and the
-// list of far sources to stage.
+// LDS table ("near" sources) and reads older messages ("far" sources) back from HBM, two
+// chunks ahead of their use.  This file turns the CSR into one 16-byte record per chunk row:
+// the table slots of its near sources, its far source, where the chunk starts in the bucket
+// order, and the node id; rows with more sources than a record holds get a list.  Everything
+// is local to the graph, and graphs of the same topology (rollouts of one graph) share a plan.
 #include <algorithm>
 #include <cstdint>
 #include <vector>
@@ -15,7 +15,7 @@
 
 namespace pl {
 
-static_assert(kMsgSlots < 64 && kMaxEnt <= 20, "table slots are stored in six bits, twenty per record");
+static_assert(kMsgSlots < 64 && kMaxNear <= 5, "table slots are stored in six bits, five per word");
 
 int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
 {
@@ -25,94 +25,87 @@ int build_sweep_plan(const HostLayout &L, int dir, SweepPlanHost *out)
     const auto &idx = dir ? L.chi_idx : L.par_idx;
     const auto &order = dir ? L.bu_order : L.td_order;
     const auto &lvl_ptr = dir ? L.bu_lvl_ptr : L.td_lvl_ptr;
-    P.ck_off.assign(static_cast<size_t>(L.B) + 1, 0);
+    P.ck_off.assign(static_cast<size_t>(L.n_templates) + 1, 0);
     std::vector<int32_t> node_chunk, node_row;
-    for (int32_t b = 0; b < L.B; ++b) {
+    uint32_t empty_slots = 0;
+    for (int i = 0; i < kMaxNear; ++i) empty_slots |= static_cast<uint32_t>(kMsgSlots) << (6 * i);
+    for (int32_t t = 0; t < L.n_templates; ++t) {
+        const int32_t b = L.tmpl_graph[t];
         const int64_t n0 = L.node_off[b];
         const int32_t n = static_cast<int32_t>(L.node_off[b + 1] - n0);
+        if (n > static_cast<int32_t>(kRecNoNode)) return fail(PL_ERR_SHAPE, "a graph has more than 2^24 - 1 nodes");
         const int32_t *lp = &lvl_ptr[L.lvl_off[b]];
         node_chunk.assign(n, 0);
         node_row.assign(n, 0);
-        const int32_t first = static_cast<int32_t>(P.meta.size() / 4);
+        const size_t first = P.rec.size() / (kChunkRows * 4);
         // pass 1: cut levels into chunks
-        for (int32_t level = 0; level < L.depth[b]; ++level) {
+        std::vector<int32_t> start, rows_of;
+        for (int32_t level = 0; level < L.depth[b]; ++level)
             for (int32_t p0 = lp[level]; p0 < lp[level + 1]; p0 += kChunkRows) {
                 const int32_t rows = std::min(kChunkRows, lp[level + 1] - p0);
-                const int32_t c = static_cast<int32_t>(P.meta.size() / 4) - first;
+                const int32_t c = static_cast<int32_t>(start.size());
                 for (int32_t r = 0; r < rows; ++r) {
                     node_chunk[order[n0 + p0 + r]] = c;
                     node_row[order[n0 + p0 + r]] = r;
                 }
-                P.meta.insert(P.meta.end(), {static_cast<int32_t>(n0) + p0, rows, 0, 0});
+                start.push_back(p0);
+                rows_of.push_back(rows);
             }
-        }
-        const int32_t n_chunks = static_cast<int32_t>(P.meta.size() / 4) - first;
-        P.ck_off[b + 1] = first + n_chunks;
-        // every record starts as "no neighbours": all twenty entries the table's zero row
-        {
-            uint32_t empty = 0;
-            for (int i = 0; i < 5; ++i) empty |= static_cast<uint32_t>(kMsgSlots) << (6 * i);
-            P.ent.resize(static_cast<size_t>(first + n_chunks) * kChunkRows * 4, empty);
-        }
-        P.far.resize(static_cast<size_t>(first + n_chunks) * kFarCap, -1);
-        // pass 2: neighbour slots
+        const int32_t n_chunks = static_cast<int32_t>(start.size());
+        P.ck_off[t + 1] = static_cast<int32_t>(first) + n_chunks;
+        P.rec.resize((first + n_chunks) * kChunkRows * 4, 0);
+        // pass 2: one record per row
         for (int32_t c = 0; c < n_chunks; ++c) {
-            int32_t *meta = &P.meta[static_cast<size_t>(first + c) * 4];
-            int32_t *far = &P.far[static_cast<size_t>(first + c) * kFarCap];
-            int32_t n_far = 0, max_ent = 0, has_ovf = 0;
-            const int32_t p0 = meta[0] - static_cast<int32_t>(n0);
-            for (int32_t r = 0; r < meta[1]; ++r) {
-                uint32_t *ent = &P.ent[(static_cast<size_t>(first + c) * kChunkRows + r) * 4];
-                const int32_t v = order[n0 + p0 + r];
+            uint32_t *rec = &P.rec[(first + c) * kChunkRows * 4];
+            int32_t max_near = 0;
+            bool any_far = false, any_listed = false;
+            for (int32_t r = 0; r < kChunkRows; ++r) {
+                uint32_t *w = rec + 4 * r;
+                w[0] = empty_slots;
+                w[1] = kNoFar;
+                w[2] = static_cast<uint32_t>(start[c]);
+                w[3] = kRecNoNode;
+                if (r >= rows_of[c]) continue;
+                const int32_t v = order[n0 + start[c] + r];
+                w[3] = static_cast<uint32_t>(v);
                 const int64_t e0 = ptr[n0 + v], e1 = ptr[n0 + v + 1];
-                const int32_t deg = static_cast<int32_t>(e1 - e0);
-                bool direct = deg > kMaxEnt;
-                int32_t new_far = 0;
-                if (!direct) {
-                    for (int64_t e = e0; e < e1; ++e) {
-                        const int32_t u = idx[e];
-                        if (c - node_chunk[u] > kRing &&
-                            std::find(far, far + n_far, static_cast<int32_t>(n0) + u) == far + n_far)
-                            ++new_far;   // (a source repeated inside this row cannot occur: simple graph)
-                    }
-                    direct = n_far + new_far > kFarCap;
-                }
-                if (direct) {            // the row's list goes to the overflow array
-                    const uint32_t off = static_cast<uint32_t>(P.ovf.size());
-                    has_ovf = 1;
-                    ent[0] |= 1u << 30;
-                    ent[1] = off;
-                    ent[2] = static_cast<uint32_t>(deg);
+                int32_t near = 0, far = 0;
+                for (int64_t e = e0; e < e1; ++e) (c - node_chunk[idx[e]] <= kRing ? near : far) += 1;
+                if (near > kMaxNear || far > 1) {     // all sources of the row go to a list
+                    any_listed = true;
+                    w[0] = kRecListed | static_cast<uint32_t>(e1 - e0);
+                    w[1] = static_cast<uint32_t>(P.ovf.size());
                     for (int64_t e = e0; e < e1; ++e) {
                         const int32_t u = idx[e];
                         if (c - node_chunk[u] <= kRing)
                             P.ovf.push_back(-1 - ((node_chunk[u] % kRing) * kChunkRows + node_row[u]));
                         else
-                            P.ovf.push_back(static_cast<int32_t>(n0) + u);
+                            P.ovf.push_back(u);
                     }
                     continue;
                 }
-                max_ent = std::max(max_ent, deg);
+                max_near = std::max(max_near, near);
+                int k = 0;
                 for (int64_t e = e0; e < e1; ++e) {
                     const int32_t u = idx[e];
-                    int32_t slot;
                     if (c - node_chunk[u] <= kRing) {
-                        slot = (node_chunk[u] % kRing) * kChunkRows + node_row[u];
+                        const uint32_t slot = static_cast<uint32_t>((node_chunk[u] % kRing) * kChunkRows + node_row[u]);
+                        w[0] = (w[0] & ~(63u << (6 * k))) | (slot << (6 * k));
+                        ++k;
                     } else {
-                        const int32_t gu = static_cast<int32_t>(n0) + u;
-                        int32_t f = static_cast<int32_t>(std::find(far, far + n_far, gu) - far);
-                        if (f == n_far) far[n_far++] = gu;
-                        slot = kRing * kChunkRows + (c % 2) * kFarCap + f;
+                        w[1] = static_cast<uint32_t>(u);
+                        any_far = true;
                     }
-                    const int k = static_cast<int>(e - e0);
-                    ent[k / 5] = (ent[k / 5] & ~(63u << (6 * (k % 5)))) | (static_cast<uint32_t>(slot) << (6 * (k % 5)));
                 }
             }
-            meta[2] = n_far;
-            meta[3] = max_ent | (has_ovf << 8);
+            const uint32_t chunk_bits = (static_cast<uint32_t>(rows_of[c] - 1) << kRecRowsShift) |
+                                        (any_listed ? 1u << kRecGeneralBit : 0u) | (any_far ? 1u << kRecFarBit : 0u) |
+                                        (static_cast<uint32_t>(max_near <= 1 ? 0 : (max_near == 2 ? 1 : 2)) << kRecNearShift);
+            for (int32_t r = 0; r < kChunkRows; ++r) rec[4 * r + 3] |= chunk_bits;
         }
     }
-    P.n_chunks = static_cast<int64_t>(P.meta.size() / 4);
+    P.n_chunks = static_cast<int64_t>(P.rec.size() / (kChunkRows * 4));
+    if (P.ovf.size() >= (1u << 30)) return fail(PL_ERR_SHAPE, "source lists of the sweep plan too long");
     return PL_OK;
 }
 

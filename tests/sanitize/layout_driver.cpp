@@ -6,8 +6,8 @@
 // Input: int32 B, e_tot; int32 n_nodes[B], n_edges[B], src[e_tot], dst[e_tot].
 // Output: int32 status; then, if 0: int64 n_tot, e_tot; int32 max_depth; int32 td_level[n_tot],
 // bu_level[n_tot], td_order[n_tot], bu_order[n_tot]; int64 par_ptr[n_tot + 1], chi_ptr[n_tot + 1];
-// int32 par_idx[e_tot], chi_idx[e_tot]; per direction: int64 n_chunks, sizes of ent / far / ovf,
-// and a 64-bit checksum of each plan array.
+// int32 par_idx[e_tot], chi_idx[e_tot]; per direction the gather plan of the matrix-core sweep
+// kernel: int64 sizes of ck_off / rec / ovf, then the three arrays.
 #include <cstdio>
 #include <cstdlib>
 #include <string>
@@ -43,15 +43,6 @@ static void put(FILE *o, const std::vector<T> &v)
     if (!v.empty()) fwrite(v.data(), sizeof(T), v.size(), o);
 }
 
-template <typename T>
-static uint64_t checksum(const std::vector<T> &v)
-{
-    uint64_t h = 1469598103934665603ull;
-    const unsigned char *p = reinterpret_cast<const unsigned char *>(v.data());
-    for (size_t i = 0; i < v.size() * sizeof(T); ++i) h = (h ^ p[i]) * 1099511628211ull;
-    return h;
-}
-
 int main(int argc, char **argv)
 {
     if (argc != 3) return 2;
@@ -83,12 +74,12 @@ int main(int argc, char **argv)
             pl::SweepPlanHost P;
             const int rc = pl::build_sweep_plan(L, dir, &P);
             if (rc) return 3;
-            const int64_t sizes[4] = {P.n_chunks, static_cast<int64_t>(P.ent.size()), static_cast<int64_t>(P.far.size()),
+            const int64_t sizes[3] = {static_cast<int64_t>(P.ck_off.size()), static_cast<int64_t>(P.rec.size()),
                                       static_cast<int64_t>(P.ovf.size())};
-            fwrite(sizes, sizeof(int64_t), 4, o);
-            const uint64_t sums[5] = {checksum(P.ck_off), checksum(P.meta), checksum(P.ent), checksum(P.far),
-                                      checksum(P.ovf)};
-            fwrite(sums, sizeof(uint64_t), 5, o);
+            fwrite(sizes, sizeof(int64_t), 3, o);
+            put(o, P.ck_off);
+            put(o, P.rec);
+            put(o, P.ovf);
         }
     }
     fclose(o);

@@ -196,12 +196,94 @@ def _check_layout(w, layout_exe, tmp_path):
                       ("par_idx", par_idx), ("chi_idx", chi_idx)):
         np.testing.assert_array_equal(arr, lay[name], err_msg=name)
     g.close()
+    for dirn in range(2):                                                  # the sweep kernel's gather plan
+        n_ck, n_rec, n_ovf = take(np.int64, 3)
+        ck_off, rec, ovf = take(np.int32, int(n_ck)), take(np.uint32, int(n_rec)), take(np.int32, int(n_ovf))
+        _check_plan(w, dirn, td if dirn == 0 else bu, td_o if dirn == 0 else bu_o, ck_off, rec.reshape(-1, 8, 4), ovf)
+    assert at == len(raw)
     for b in range(w.B):                                                   # and the oracle's levels
         n, src, dst, *_ = w.graph(b)
         t, u = oracle.levels(n, src, dst)
         sl = slice(int(w.node_off[b]), int(w.node_off[b + 1]))
         np.testing.assert_array_equal(td[sl], t)
         np.testing.assert_array_equal(bu[sl], u)
+
+
+RING, CH, MAX_NEAR = 4, 8, 5      # constants of the plan (sweep_plan.h)
+
+
+def _check_plan(w, dirn, level, order, ck_off, rec, ovf):
+    """Every row record of the gather plan against the edge list: the chunk cuts levels in bucket
+    order; the near slots (messages of the last RING chunks), the far source or the row's list name
+    exactly the row's neighbours; the chunk-wide bits say what the rows need."""
+    assert len(ck_off) == w.B + 1
+    for b in range(w.B):
+        n0, n = int(w.node_off[b]), int(w.n_nodes[b])
+        e0, e1 = int(w.edge_off[b]), int(w.edge_off[b + 1])
+        src, dst = w.edge_src[e0:e1], w.edge_dst[e0:e1]
+        nbr = [[] for _ in range(n)]
+        for u, v in zip(src.tolist(), dst.tolist()):
+            (nbr[v] if dirn == 0 else nbr[u]).append(u if dirn == 0 else v)
+        lev, ordr = level[n0:n0 + n], order[n0:n0 + n]
+        chunk_of, row_of = np.full(n, -1), np.full(n, -1)
+        pos = 0
+        recs = rec[ck_off[b]:ck_off[b + 1]]
+        for c, ck in enumerate(recs):
+            info = int(ck[0, 3])
+            rows = ((info >> 24) & 7) + 1
+            assert all(int(ck[r, 3]) >> 24 == info >> 24 for r in range(CH))          # chunk-wide bits agree
+            assert all(int(ck[r, 2]) == pos for r in range(CH))                       # first bucket position
+            ids = [int(ck[r, 3]) & 0xFFFFFF for r in range(CH)]
+            assert ids[:rows] == ordr[pos:pos + rows].tolist() and all(i == 0xFFFFFF for i in ids[rows:])
+            assert len(set(lev[ids[:rows]].tolist())) == 1                            # one level per chunk
+            if pos + rows < n and rows < CH:
+                assert lev[ordr[pos + rows]] != lev[ids[0]]                           # a chunk ends with its level or when full
+            any_listed = any_far = False
+            widest = 0
+            for r in range(rows):
+                v = ids[r]
+                chunk_of[v], row_of[v] = c, r
+                w0, w1 = int(ck[r, 0]), int(ck[r, 1])
+                got = []
+                if w0 & (1 << 30):
+                    any_listed = True
+                    cnt = w0 & 0xFFFFFF
+                    for x in ovf[w1:w1 + cnt].tolist():
+                        if x >= 0:
+                            assert c - chunk_of[x] > RING
+                            got.append(x)
+                        else:
+                            slot = -1 - x
+                            u = [q for q in nbr[v] if chunk_of[q] % RING == slot // CH and row_of[q] == slot % CH
+                                 and 0 < c - chunk_of[q] <= RING]
+                            assert len(u) == 1
+                            got.append(u[0])
+                    near = sum(1 for q in nbr[v] if c - chunk_of[q] <= RING)
+                    assert near > MAX_NEAR or len(nbr[v]) - near > 1                  # listed only when needed
+                else:
+                    k_near = 0
+                    for k in range(MAX_NEAR):
+                        slot = (w0 >> (6 * k)) & 63
+                        if slot == RING * CH:
+                            continue
+                        assert slot < RING * CH and k == k_near                        # used slots first
+                        k_near += 1
+                        u = [q for q in nbr[v] if chunk_of[q] % RING == slot // CH and row_of[q] == slot % CH
+                             and 0 < c - chunk_of[q] <= RING]
+                        assert len(u) == 1
+                        got.append(u[0])
+                    widest = max(widest, k_near)
+                    if w1 != 0xFFFFFFFF:
+                        any_far = True
+                        assert c - chunk_of[w1] > RING
+                        got.append(w1)
+                assert sorted(got) == sorted(nbr[v]), (b, c, r)
+            for r in range(rows, CH):
+                assert int(ck[r, 0]) == sum((RING * CH) << (6 * k) for k in range(MAX_NEAR)) and int(ck[r, 1]) == 0xFFFFFFFF
+            assert (info >> 27) & 1 == int(any_listed) and (info >> 28) & 1 == int(any_far)
+            assert (info >> 29) & 3 == (0 if widest <= 1 else (1 if widest == 2 else 2))
+            pos += rows
+        assert pos == n
 
 
 @pytest.mark.parametrize("name,B", [("random32", 1), ("layered200", 6), ("nmt", 2), ("nasnet", 2)])
