@@ -291,6 +291,8 @@ size_t carve_workspace(unsigned char *base, size_t n, size_t B, const ModelView 
     ws->partial = reinterpret_cast<float *>(take(sizeof(float) * (B * ws->n_chunks * 3 * mv.G * H + 4)));
     ws->zbuf = reinterpret_cast<float *>(take(sizeof(float) * (B * mv.Z + 4)));
     ws->hidp = reinterpret_cast<double *>(take(sizeof(double) * (static_cast<size_t>((mv.Z + 255) / 256) * B * H + 4)));
+    ws->klist = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * (n + 16)));
+    ws->koff = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * (B * (3 * kMaxD + 1) + 4)));
     if (with_reach) ws->reach = take(2 * n + 32);
     ws->H = mv.H;
     ws->G = mv.G;

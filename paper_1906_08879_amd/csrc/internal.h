@@ -128,7 +128,8 @@ struct Workspace {
     float *partial = nullptr;   // [B, n_chunks_max, 3G, H] pooling partial sums
     float *zbuf = nullptr;      // [B, Z] policy inputs
     double *hidp = nullptr;     // [ceil(Z / 256), B, H] partial products of policy layer 1 (float64 sums)
-    int32_t *chunk_off = nullptr; // [B+1] first pooling chunk of each graph
+    int32_t *klist = nullptr;   // [n_tot] node ids grouped by (set, device group), per graph (matrix-core pooling)
+    int32_t *koff = nullptr;    // [B][3 kMaxD + 1] first position of every key within its graph
     int32_t n_chunks = 0;
     int32_t H = 0, G = 0;
 };

@@ -1,18 +1,25 @@
-// Matrix-core pooling kernel for gfx950: Section 2.2 step 3,
+// Matrix-core pooling for gfx950: Section 2.2 step 3,
 //   P[i][d] = sum over nodes u of set i placed on device d of l_i([td_u ; bu_u]),
 // for H in {32, 64, 128} and one or two layers in l_i.
 //
-// One workgroup per (graph, slice of its nodes, set).  It scans its nodes in node order, queues
-// the nodes of its set, and pushes them through l_i sixteen at a time:
+// Two kernels per pass:
+//   k_pool_sort   one workgroup per graph: a counting sort of the graph's nodes by
+//                 key = (set, device group), without atomics (a thread counts and places a
+//                 contiguous block of nodes), so the order is the same on every run;
+//   k_pool_tiles  one workgroup per (set, slice of the set's tiles, graph).  A tile is up to
+//                 sixteen nodes of ONE key, so the sum over a tile's rows needs no per-device
+//                 selection: a lane adds its four nodes' outputs to one running sum, which is
+//                 written out when the device changes.
+// In k_pool_tiles:
 //   * the fp32 embedding row of a node is split exactly into three bf16 parts (truncation);
 //     the hi, mid and lo parts of the sixteen nodes form three 16-row MFMA A tiles, so a lane
 //     finds the three partial products of (node, column) in the same element of three
 //     accumulators and adds them there: no cross-lane traffic and no wasted rows;
 //   * the weights of l_i are the B operand and stay in registers for the whole kernel;
-//   * the rows of the next batch are loaded from HBM while the current one is computed;
-//   * the per-device sums are taken in registers, by the lane that holds a node's output in
-//     its accumulators, in batch order; the four lanes of a column are added once at the end
-//     in a fixed order, so the result is bitwise reproducible.
+//   * the rows of the next tile are loaded from HBM while the current one is computed;
+//   * a lane that owns two output columns hands them to the second layer as one word per part
+//     (the second layer's contraction index is permuted to match, see pack_pool_weights);
+//   * all sums are taken in a fixed order, so the result is bitwise reproducible.
 #include "internal.h"
 
 namespace pl {
@@ -23,9 +30,9 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int kThreads = 256;
-constexpr int kBatch = 16;          // nodes per batch: one MFMA row tile per bf16 part
-constexpr int kWindow = 256;        // nodes classified per scan step
-constexpr int kQueue = 512;         // circular queue of node ids (power of two > kWindow + kBatch)
+constexpr int kBatch = 16;          // nodes per tile: one MFMA row tile per bf16 part
+constexpr int kMaxKeys = 3 * kMaxD; // (set, device group) keys of a graph
+constexpr int kAhead = 2;            // k-steps between reading an A fragment from LDS and using it
 
 __device__ __forceinline__ void lds_barrier()
 {
@@ -44,25 +51,86 @@ __device__ __forceinline__ float trunc_bf16(float x)
     return __uint_as_float(__float_as_uint(x) & 0xFFFF0000u);
 }
 
+// ---- counting sort of a graph's nodes by (set, device group).  klist gets the graph's node ids
+// (global) grouped by key, koff[b][k] the position (within the graph) of key k's first node,
+// koff[b][3G] the number of pooled nodes.  The current node and nodes with a device id outside
+// [0, D) belong to no key.  Thread t counts, then places, the nodes of its own contiguous block.
+__global__ __launch_bounds__(kThreads) void k_pool_sort(GraphView gv, const uint8_t *__restrict__ reach,
+                                                        const int32_t *__restrict__ placement,
+                                                        const int32_t *__restrict__ cur_node, int D, int G,
+                                                        int single, int32_t *__restrict__ klist,
+                                                        int32_t *__restrict__ koff)
+{
+    __shared__ uint16_t hist[kMaxKeys][kThreads];    // nodes of key k in thread t's block, then their first position
+    __shared__ int total[kMaxKeys + 1];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int n0 = gv.node_off[b], n_b = gv.node_off[b + 1] - n0;
+    const int cl = cur_node[b];
+    const int cur = (cl >= 0 && cl < n_b) ? n0 + cl : -1;
+    const int K = 3 * G;
+    const int per = (n_b + kThreads - 1) / kThreads;
+    const int lo = n0 + min(tid * per, n_b), hi = n0 + min((tid + 1) * per, n_b);
+    auto key_of = [&](int v) {
+        if (v == cur) return -1;
+        const int d = placement[v];
+        if (d < 0 || d >= D) return -1;
+        const int set = single ? 0 : (reach[static_cast<size_t>(gv.n_tot) + v] ? 0 : (reach[v] ? 1 : 2));
+        return set * G + (G == 1 ? 0 : d);
+    };
+    for (int k = 0; k < K; ++k) hist[k][tid] = 0;
+    for (int v = lo; v < hi; ++v) {
+        const int k = key_of(v);
+        if (k >= 0) hist[k][tid] += 1;
+    }
+    __syncthreads();
+    if (tid < K) {                                   // exclusive prefix over the threads, per key
+        int run = 0;
+        for (int t = 0; t < kThreads; ++t) {
+            const int c = hist[tid][t];
+            hist[tid][t] = static_cast<uint16_t>(run);
+            run += c;
+        }
+        total[tid] = run;
+    }
+    __syncthreads();
+    if (tid == 0) {                                  // exclusive prefix over the keys
+        int run = 0;
+        for (int k = 0; k < K; ++k) {
+            const int c = total[k];
+            total[k] = run;
+            run += c;
+        }
+        total[K] = run;
+    }
+    __syncthreads();
+    int32_t *kb = koff + static_cast<size_t>(b) * (kMaxKeys + 1);
+    if (tid <= K) kb[tid] = total[tid];
+    for (int v = lo; v < hi; ++v) {
+        const int k = key_of(v);
+        if (k < 0) continue;
+        const int at = total[k] + hist[k][tid];
+        hist[k][tid] += 1;
+        klist[n0 + at] = v;
+    }
+}
+
 struct PoolParams {
     GraphView gv;
     const uint4 *wfrag;        // packed B fragments of l_par, l_chi, l_pll (see pack_pool_weights)
     const float *bias;         // [3 sets][L][H]
     const float *emb;          // [n_tot, 2H]
-    const uint8_t *reach;      // [2, n_tot]
-    const int32_t *placement;  // [n_tot]
-    const int32_t *cur_node;   // [B]
-    float *partial;            // [B, max_slices, 3, G, H] sums over a slice of the graph's nodes
+    const int32_t *klist;      // [n_tot] node ids grouped by key, per graph
+    const int32_t *koff;       // [B][kMaxKeys + 1]
+    float *partial;            // [B, max_slices, 3, G, H] sums over a slice of the set's tiles
     int max_slices;
-    int D, G;
+    int G;
     float *keep;               // (KEEP) [L][n_tot, H]: the outputs of l's layers for every node of a set
-    int single;                // 1: every node other than v* belongs to the first set
 };
 
 // KEEP: the outputs of every layer of l_i are also written to HBM, by the lane that holds them,
 // for the reverse pass (a node belongs to one set and is handled by one workgroup).
 template <int H, int WS, int L, bool KEEP = false>
-__global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
+__global__ __launch_bounds__(kThreads, 2) void k_pool_tiles(PoolParams P)
 {
     constexpr int K1 = 2 * H;                    // input width of the first layer
     constexpr int KS1 = K1 / 32, KS2 = H / 32;
@@ -70,37 +138,37 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
     constexpr int TPW = (NTL + 3) / 4;           // column tiles per wave
     constexpr int LD1 = K1 + 8, LD2 = H + 8;     // bf16 row strides
     constexpr int QPR = K1 / 4;                  // float4 per embedding row
-    constexpr int NLD = kBatch * QPR / kThreads; // float4 loads per thread and batch
-    static_assert(kBatch * QPR % kThreads == 0, "batch rows must divide over the threads");
+    constexpr int NLD = kBatch * QPR / kThreads; // float4 loads per thread and tile
+    static_assert(kBatch * QPR % kThreads == 0, "tile rows must divide over the threads");
+    static_assert(TPW == 1 || TPW == 2, "a lane owns one or two output columns");
 
-    // [part][node][k] bf16 parts of the input rows and of the layer-1 outputs; the same memory
-    // holds the final cross-lane reduction
-    constexpr size_t kAct1 = sizeof(__bf16) * 3 * kBatch * LD1, kAct2 = sizeof(__bf16) * 3 * kBatch * LD2;
-    constexpr size_t kRed = sizeof(float) * 4 * kMaxD * H;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[kAct1 + kAct2 > kRed ? kAct1 + kAct2 : kRed];
-    __bf16 (*act1)[kBatch][LD1] = reinterpret_cast<__bf16 (*)[kBatch][LD1]>(smem);
-    __bf16 (*act2)[kBatch][LD2] = reinterpret_cast<__bf16 (*)[kBatch][LD2]>(smem + kAct1);
-    __shared__ int queue[kQueue];
-    __shared__ int batch_node[2][kBatch];
-    __shared__ int batch_dev[2][kBatch];
-    __shared__ int wave_cnt[4];
+    // [part][node][k] bf16 parts of the input rows and of the layer-1 outputs
+    __shared__ __attribute__((aligned(16))) __bf16 act1[2][3][kBatch][LD1];   // two tiles: one is read while the next is written
+    __shared__ __attribute__((aligned(16))) __bf16 act2[L > 1 ? 3 : 1][kBatch][LD2];
+    __shared__ int tile_node[8][kBatch];     // node ids of the tiles t - 1 .. t + 4 (slot = tile & 7)
 
     const int set = blockIdx.x, slice = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, kg = lane >> 4;
     const GraphView &gv = P.gv;
     const int g0 = gv.node_off[b], g_n = gv.node_off[b + 1] - g0;
-    const int cl = P.cur_node[b];
-    const int cur = (cl >= 0 && cl < g_n) ? g0 + cl : -1;
-    const int G = P.G, D = P.D;
-    // the graph's nodes are cut into slices (same rule as the generic pooling kernel); this
-    // workgroup owns nodes [n0, n0 + n_b)
+    const int G = P.G;
+    // a graph's sets are cut into slices (as many as the generic pooling kernel uses chunks)
     int slices = (g_n + kPoolChunk - 1) / kPoolChunk;
     if (slices > P.max_slices) slices = P.max_slices;
     if (slice >= slices) return;
-    const int per = (g_n + slices - 1) / slices;
-    const int n0 = g0 + slice * per;
-    const int n_b = min(per, g_n - slice * per);
+    // tiles of this set: for every device group ceil(count / 16), in device order; this
+    // workgroup takes the tiles [t_lo, t_hi) of that list
+    const int32_t *kb = P.koff + static_cast<size_t>(b) * (kMaxKeys + 1) + set * G;
+    int n_tiles = 0;
+    for (int d = 0; d < G; ++d) n_tiles += (kb[d + 1] - kb[d] + kBatch - 1) / kBatch;
+    const int t_lo = static_cast<int>(static_cast<long long>(n_tiles) * slice / slices);
+    const int t_hi = static_cast<int>(static_cast<long long>(n_tiles) * (slice + 1) / slices);
+    float *dst = P.partial + (((static_cast<size_t>(b) * P.max_slices + slice) * 3 + set) * G) * H;
+    if (t_lo >= t_hi) {
+        for (int i = tid; i < G * H; i += kThreads) dst[i] = 0.0f;
+        return;
+    }
 
     // ---- weights of l_set into registers (B operand: lane holds column 16 nt + col)
     bf16x8 W1[TPW][KS1][WS];
@@ -135,205 +203,261 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_mfma(PoolParams P)
             }
         }
     }
-    for (int i = tid; i < static_cast<int>((kAct1 + kAct2) / 4); i += kThreads) reinterpret_cast<uint32_t *>(smem)[i] = 0u;
+    const bool my_cols = wave * TPW < NTL;        // narrow networks leave the last waves without columns
+
+    // ---- tile walk: (device group d, first node position p, node count) of tile t
+    int d_cur = 0, d_first = 0;                   // device group of the walk; tiles before it
+    auto seek = [&](int t) {                      // t only grows
+        while (d_cur < G && t >= d_first + (kb[d_cur + 1] - kb[d_cur] + kBatch - 1) / kBatch) {
+            d_first += (kb[d_cur + 1] - kb[d_cur] + kBatch - 1) / kBatch;
+            ++d_cur;
+        }
+    };
+    // Rows travel two tiles ahead of the matrix instructions (a workgroup keeps 32 KB of loads
+    // in flight); the node ids of a tile are staged in LDS earlier still, so a row load never
+    // waits for an id load.  Ring of eight id slots (slot = tile & 7).
+    // The id of a tile's node tid (threads 0..15) is fetched before the row loads of the same
+    // iteration are issued and published after them: loads return in order, so the wait for the
+    // id then leaves the row loads in flight.
+    auto fetch_id = [&](int t, int &cnt, int &dev) {
+        seek(t);
+        const int p = kb[d_cur] + (t - d_first) * kBatch;
+        cnt = min(kBatch, kb[d_cur + 1] - p);
+        dev = d_cur;
+        return tid < kBatch ? P.klist[g0 + p + (tid < cnt ? tid : 0)] : 0;   // rows past the end repeat the first
+    };
+    auto publish_id = [&](int t, int id) {
+        if (tid < kBatch) tile_node[t & 7][tid] = id;
+    };
+    auto load_rows = [&](int t, f32x4 (&x)[NLD]) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int e = tid + i * kThreads;
+            const int node = e / QPR, q = e - node * QPR;
+            x[i] = *reinterpret_cast<const f32x4 *>(P.emb + static_cast<size_t>(tile_node[t & 7][node]) * K1 + 4 * q);
+        }
+    };
+    // Splits item i of a tile's rows exactly into three bf16 parts and writes them as MFMA A rows.
+    auto split_item = [&](int buf, const f32x4 (&x)[NLD], int i) {
+        const int e = tid + i * kThreads;
+        const int node = e / QPR, q = e - node * QPR;
+        float r[4], l[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            r[k] = x[i][k] - trunc_bf16(x[i][k]);
+            l[k] = r[k] - trunc_bf16(r[k]);
+        }
+        *reinterpret_cast<uint2 *>(&act1[buf][0][node][4 * q]) = uint2{pack_hi16(x[i][0], x[i][1]), pack_hi16(x[i][2], x[i][3])};
+        *reinterpret_cast<uint2 *>(&act1[buf][1][node][4 * q]) = uint2{pack_hi16(r[0], r[1]), pack_hi16(r[2], r[3])};
+        *reinterpret_cast<uint2 *>(&act1[buf][2][node][4 * q]) = uint2{pack_hi16(l[0], l[1]), pack_hi16(l[2], l[3])};
+    };
+
+    float run[TPW];           // running sum over this lane's nodes (4 kg .. 4 kg + 3 of every tile) of the current device group
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) run[t] = 0.0f;
+    int run_dev = -1;
+    unsigned written = 0;     // device groups whose sum has been written
+    // Adds the four lanes of a column (kg = 0..3) in a fixed order and writes the device group's sum.
+    auto flush = [&]() {
+        if (run_dev < 0) return;
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            float s = run[t];
+            s += __shfl_xor(s, 16);
+            s += __shfl_xor(s, 32);
+            const int nt = wave * TPW + t;
+            if (kg == 0 && nt < NTL) dst[run_dev * H + 16 * nt + col] = s;
+            run[t] = 0.0f;
+        }
+        written |= 1u << run_dev;
+    };
+
+    f32x4 xa[NLD], xb[NLD];            // rows of the next two tiles, alternately
+    int cnt_r[5], dev_r[5];            // nodes and device group of the tiles t .. t + 4 (uniform)
+#pragma unroll
+    for (int j = 0; j < 5; ++j) cnt_r[j] = dev_r[j] = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (t_lo + j < t_hi) publish_id(t_lo + j, fetch_id(t_lo + j, cnt_r[j], dev_r[j]));
     __syncthreads();
+    load_rows(t_lo, xa);
+    if (t_lo + 1 < t_hi) load_rows(t_lo + 1, xb);
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) split_item(0, xa, i);
+    if (t_lo + 2 < t_hi) load_rows(t_lo + 2, xa);
 
-    int q_head = 0;           // position of the oldest queued node (uniform)
-    int q_len = 0;            // queued nodes not yet batched (uniform)
-    int scan = 0;             // next node of the graph to classify (uniform)
-    int have = 0;             // nodes of the batch whose rows are in flight (uniform)
-    int slot = 0;             // batch_node buffer of the in-flight batch
-    f32x4 x[NLD];             // the in-flight rows: item e = tid + i * 256 -> (node e / QPR, float4 e % QPR)
-    float acc_dev[kMaxD][TPW];   // per-device sums over this lane's nodes (4 kg .. 4 kg + 3 of every batch) and columns
-#pragma unroll
-    for (int d = 0; d < kMaxD; ++d)
-#pragma unroll
-        for (int t = 0; t < TPW; ++t) acc_dev[d][t] = 0.0f;
-
-    // Fills the queue until it holds a full batch or the graph is exhausted.
-    auto refill = [&]() {
-        while (q_len < kBatch && scan < n_b) {
-            const int v = n0 + scan + tid;
-            bool mine = false;
-            if (scan + tid < n_b && v != cur) {
-                const int c = P.single ? 0 : (P.reach[static_cast<size_t>(gv.n_tot) + v] ? 0 : (P.reach[v] ? 1 : 2));
-                mine = (c == set);
-            }
-            const unsigned long long m = __ballot(mine);
-            if (lane == 0) wave_cnt[wave] = __popcll(m);
-            lds_barrier();
-            int base = q_len;
-            for (int w = 0; w < wave; ++w) base += wave_cnt[w];
-            if (mine) queue[(q_head + base + __popcll(m & ((1ull << lane) - 1ull))) & (kQueue - 1)] = v;
-            q_len += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
-            scan += kWindow;
-            lds_barrier();
+    // One tile: the matrix instructions of tile t, with the split of tile t + 1's rows (xs)
+    // interleaved between the k-steps of the first layer, into the other half of act1.
+    auto step = [&](int t, f32x4 (&xs)[NLD]) {
+        const int cnt = cnt_r[0], dev = dev_r[0], my_slot = t & 7, buf = (t - t_lo) & 1;
+        const bool more = t + 1 < t_hi;
+        int id4 = 0;
+        if (t + 4 < t_hi) id4 = fetch_id(t + 4, cnt_r[4], dev_r[4]);
+        // every wave has finished tile t - 1 (its reads of act2 and of the other half of act1),
+        // and the rows of tile t, split during tile t - 1, are visible
+        lds_barrier();
+        if (t + 4 < t_hi) publish_id(t + 4, id4);
+        if (dev != run_dev) {
+            flush();
+            run_dev = dev;
         }
-    };
-    // Takes up to a batch from the queue and issues the loads of its rows.
-    auto issue = [&]() {
-        have = q_len < kBatch ? q_len : kBatch;
-        slot ^= 1;
-        if (tid < kBatch) batch_node[slot][tid] = tid < have ? queue[(q_head + tid) & (kQueue - 1)] : -1;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int e = tid + i * kThreads;
-            const int node = e / QPR, q = e - node * QPR;
-            const int v = node < have ? queue[(q_head + node) & (kQueue - 1)] : n0;   // any valid row if empty
-            x[i] = *reinterpret_cast<const f32x4 *>(P.emb + static_cast<size_t>(v) * K1 + 4 * q);
-        }
-        q_head = (q_head + have) & (kQueue - 1);
-        q_len -= have;
-        lds_barrier();      // orders LDS only: the row loads stay in flight
-    };
-
-    refill();
-    issue();
-    while (have > 0) {
-        const int cnt = have;
-        const int my_slot = slot;
-        // ---- (1) split the rows that arrived and publish them as MFMA A rows
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int e = tid + i * kThreads;
-            const int node = e / QPR, q = e - node * QPR;
-            float r[4], l[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                r[k] = x[i][k] - trunc_bf16(x[i][k]);
-                l[k] = r[k] - trunc_bf16(r[k]);
-            }
-            *reinterpret_cast<uint2 *>(&act1[0][node][4 * q]) = uint2{pack_hi16(x[i][0], x[i][1]), pack_hi16(x[i][2], x[i][3])};
-            *reinterpret_cast<uint2 *>(&act1[1][node][4 * q]) = uint2{pack_hi16(r[0], r[1]), pack_hi16(r[2], r[3])};
-            *reinterpret_cast<uint2 *>(&act1[2][node][4 * q]) = uint2{pack_hi16(l[0], l[1]), pack_hi16(l[2], l[3])};
-        }
-        if (tid < kBatch) {
-            const int v = batch_node[my_slot][tid];
-            int dev = -1;
-            if (v >= 0) {
-                const int d = P.placement[v];
-                dev = (d >= 0 && d < D) ? (G == 1 ? 0 : d) : -1;
-            }
-            batch_dev[my_slot][tid] = dev;
-        }
-        // ---- (2) next batch: queue it and put its loads in flight
-        refill();
-        issue();          // ends with a barrier: act1 and batch_dev are visible
-
-        // ---- (3) layer 1.  acc[part][t]: element i of lane (col, kg) belongs to node 4 kg + i
-        // and output column 16 nt + col.  3 * TPW independent accumulation chains are in
-        // flight, which hides the latency of a dependent MFMA.  Rows past the batch's end hold
-        // stale data that is never summed.
+        // ---- layer 1.  acc[part][tt]: element i of lane (col, kg) belongs to node 4 kg + i and
+        // output column 16 nt + col.  3 * TPW independent accumulation chains are in flight.
+        // Rows past the tile's end hold a copy of its first row and are never summed.
         f32x4 acc[3][TPW];
 #pragma unroll
         for (int p = 0; p < 3; ++p)
 #pragma unroll
-            for (int t = 0; t < TPW; ++t) acc[p][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int tt = 0; tt < TPW; ++tt) acc[p][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        {
+            // The A fragments are read kAhead k-steps before the matrix instructions that use
+            // them; the scheduling barriers keep the order written here: reads, then the matrix
+            // instructions of a k-step, then a piece of the next tile's split, which the vector
+            // unit works off while the matrix core is busy.
+            bf16x8 a[kAhead + 1][3];
+            if (my_cols) {
 #pragma unroll
-        for (int ks = 0; ks < KS1; ++ks)
+                for (int ks = 0; ks < kAhead && ks < KS1; ++ks)
 #pragma unroll
-            for (int p = 0; p < 3; ++p) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&act1[p][col][32 * ks + 8 * kg]);
-#pragma unroll
-                for (int t = 0; t < TPW; ++t)
-#pragma unroll
-                    for (int ws = 0; ws < WS; ++ws)
-                        acc[p][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W1[t][ks][ws], acc[p][t], 0, 0, 0);
+                    for (int p = 0; p < 3; ++p)
+                        a[ks][p] = *reinterpret_cast<const bf16x8 *>(&act1[buf][p][col][32 * ks + 8 * kg]);
             }
-        if constexpr (L > 1) {
 #pragma unroll
-            for (int t = 0; t < TPW; ++t) {
-                const int nt = wave * TPW + t;
-                if (nt >= NTL) continue;
+            for (int ks = 0; ks < KS1; ++ks) {
+                if (my_cols) {
+                    if (ks + kAhead < KS1) {
+#pragma unroll
+                        for (int p = 0; p < 3; ++p)
+                            a[(ks + kAhead) % (kAhead + 1)][p] =
+                                *reinterpret_cast<const bf16x8 *>(&act1[buf][p][col][32 * (ks + kAhead) + 8 * kg]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int p = 0; p < 3; ++p)
+#pragma unroll
+                        for (int tt = 0; tt < TPW; ++tt)
+#pragma unroll
+                            for (int ws = 0; ws < WS; ++ws)
+                                acc[p][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks % (kAhead + 1)][p], W1[tt][ks][ws],
+                                                                                    acc[p][tt], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // NLD items of the split spread over the KS1 k-steps
+                if (more) {
+#pragma unroll
+                    for (int i = 0; i < NLD; ++i)
+                        if (i * KS1 / NLD == ks) split_item(buf ^ 1, xs, i);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // the registers of the split rows are free: the rows of tile t + 3 go in flight
+        if (t + 3 < t_hi) load_rows(t + 3, xs);
+        if constexpr (L > 1) {
+            if (my_cols) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float y = fmaxf(acc[0][t][i] + acc[1][t][i] + acc[2][t][i] + bias1[t], 0.0f);
-                    const float r = y - trunc_bf16(y);
-                    const float l = r - trunc_bf16(r);
-                    const int node = 4 * kg + i, c = 16 * nt + col;
-                    if constexpr (KEEP) {
-                        if (node < cnt) P.keep[static_cast<size_t>(batch_node[my_slot][node]) * H + c] = y;
+                    const int node = 4 * kg + i;
+                    float y[TPW], r[TPW], l[TPW];
+#pragma unroll
+                    for (int tt = 0; tt < TPW; ++tt) {
+                        y[tt] = fmaxf(acc[0][tt][i] + acc[1][tt][i] + acc[2][tt][i] + bias1[tt], 0.0f);
+                        r[tt] = y[tt] - trunc_bf16(y[tt]);
+                        l[tt] = r[tt] - trunc_bf16(r[tt]);
+                        if constexpr (KEEP) {
+                            if (node < cnt)
+                                P.keep[static_cast<size_t>(tile_node[my_slot][node]) * H + 16 * (wave * TPW + tt) + col] = y[tt];
+                        }
                     }
-                    reinterpret_cast<unsigned short *>(&act2[0][node][c])[0] = static_cast<unsigned short>(__float_as_uint(y) >> 16);
-                    reinterpret_cast<unsigned short *>(&act2[1][node][c])[0] = static_cast<unsigned short>(__float_as_uint(r) >> 16);
-                    reinterpret_cast<unsigned short *>(&act2[2][node][c])[0] = static_cast<unsigned short>(__float_as_uint(l) >> 16);
+                    if constexpr (TPW == 2) {
+                        // word 16 wave + col of a row: columns 32 wave + col and 32 wave + 16 + col
+                        uint32_t *w0 = reinterpret_cast<uint32_t *>(&act2[0][node][0]) + 16 * wave + col;
+                        w0[0] = pack_hi16(y[0], y[1]);
+                        w0[kBatch * LD2 / 2] = pack_hi16(r[0], r[1]);
+                        w0[2 * (kBatch * LD2 / 2)] = pack_hi16(l[0], l[1]);
+                    } else {
+                        const int c = 16 * wave + col;
+                        reinterpret_cast<unsigned short *>(&act2[0][node][c])[0] = static_cast<unsigned short>(__float_as_uint(y[0]) >> 16);
+                        reinterpret_cast<unsigned short *>(&act2[1][node][c])[0] = static_cast<unsigned short>(__float_as_uint(r[0]) >> 16);
+                        reinterpret_cast<unsigned short *>(&act2[2][node][c])[0] = static_cast<unsigned short>(__float_as_uint(l[0]) >> 16);
+                    }
                 }
             }
             lds_barrier();
-            // ---- (4) layer 2
+            // ---- layer 2
 #pragma unroll
             for (int p = 0; p < 3; ++p)
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) acc[p][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int tt = 0; tt < TPW; ++tt) acc[p][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (my_cols) {
+                bf16x8 a[kAhead + 1][3];
 #pragma unroll
-            for (int ks = 0; ks < KS2; ++ks)
+                for (int ks = 0; ks < kAhead && ks < KS2; ++ks)
 #pragma unroll
-                for (int p = 0; p < 3; ++p) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&act2[p][col][32 * ks + 8 * kg]);
+                    for (int p = 0; p < 3; ++p) a[ks][p] = *reinterpret_cast<const bf16x8 *>(&act2[p][col][32 * ks + 8 * kg]);
 #pragma unroll
-                    for (int t = 0; t < TPW; ++t)
+                for (int ks = 0; ks < KS2; ++ks) {
+                    if (ks + kAhead < KS2) {
 #pragma unroll
-                        for (int ws = 0; ws < WS; ++ws)
-                            acc[p][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W2[t][ks][ws], acc[p][t], 0, 0, 0);
+                        for (int p = 0; p < 3; ++p)
+                            a[(ks + kAhead) % (kAhead + 1)][p] =
+                                *reinterpret_cast<const bf16x8 *>(&act2[p][col][32 * (ks + kAhead) + 8 * kg]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int p = 0; p < 3; ++p)
+#pragma unroll
+                        for (int tt = 0; tt < TPW; ++tt)
+#pragma unroll
+                            for (int ws = 0; ws < WS; ++ws)
+                                acc[p][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks % (kAhead + 1)][p], W2[tt][ks][ws],
+                                                                                    acc[p][tt], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+            }
         }
-        // ---- (5) per-device sums in registers: lane (col, kg) adds the outputs of its own
-        // nodes (4 kg + i) to the sum of the node's device; nodes past the end of the batch
-        // have device -1 and are never added
-        float y[4][TPW];
-        int dv[4];
+        // ---- the tile's rows all belong to one device group: a lane adds the outputs of its own
+        // nodes (4 kg + i, those inside the tile) to the running sum, in node order
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int node = 4 * kg + i;
-            dv[i] = node < cnt ? batch_dev[my_slot][node] : -1;
 #pragma unroll
-            for (int t = 0; t < TPW; ++t) {
-                const float bl = (L > 1) ? bias2[t] : bias1[t];
-                y[i][t] = fmaxf(acc[0][t][i] + acc[1][t][i] + acc[2][t][i] + bl, 0.0f);
+            for (int tt = 0; tt < TPW; ++tt) {
+                const float bl = (L > 1) ? bias2[tt] : bias1[tt];
+                const float y = fmaxf(acc[0][tt][i] + acc[1][tt][i] + acc[2][tt][i] + bl, 0.0f);
                 if constexpr (KEEP) {
-                    const int nt = wave * TPW + t;
+                    const int nt = wave * TPW + tt;
                     if (node < cnt && nt < NTL)
-                        P.keep[(static_cast<size_t>(L - 1) * gv.n_tot + batch_node[my_slot][node]) * H + 16 * nt + col] = y[i][t];
+                        P.keep[(static_cast<size_t>(L - 1) * gv.n_tot + tile_node[my_slot][node]) * H + 16 * nt + col] = y;
                 }
+                run[tt] += node < cnt ? y : 0.0f;
             }
         }
-        // rows past the end of the batch hold earlier, finite outputs: weight 0 removes them
 #pragma unroll
-        for (int d = 0; d < kMaxD; ++d) {
-            if (d >= G) break;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float wgt = dv[i] == d ? 1.0f : 0.0f;
-#pragma unroll
-                for (int t = 0; t < TPW; ++t) acc_dev[d][t] = fmaf(wgt, y[i][t], acc_dev[d][t]);
-            }
+        for (int j = 0; j < 4; ++j) {
+            cnt_r[j] = cnt_r[j + 1];
+            dev_r[j] = dev_r[j + 1];
         }
+    };
+    for (int t = t_lo; t < t_hi; t += 2) {
+        step(t, xb);
+        if (t + 1 < t_hi) step(t + 1, xa);
     }
-
-    // ---- the four lanes of a column (kg = 0..3) are added in order; the buffer of the first
-    // layer's A rows is free now and holds the partial sums
-    __syncthreads();
-    float *red = reinterpret_cast<float *>(smem);             // [4 kg][G][H]
-#pragma unroll
-    for (int t = 0; t < TPW; ++t) {
-        const int nt = wave * TPW + t;
-        if (nt >= NTL) continue;
-#pragma unroll
-        for (int d = 0; d < kMaxD; ++d) {
-            if (d >= G) break;
-            red[(kg * G + d) * H + 16 * nt + col] = acc_dev[d][t];
-        }
+    flush();
+    // device groups without a tile in this slice
+    for (int d = 0; d < G; ++d) {
+        if ((written >> d) & 1u) continue;
+        for (int i = tid; i < H; i += kThreads) dst[d * H + i] = 0.0f;
     }
-    __syncthreads();
-    float *dst = P.partial + (((static_cast<size_t>(b) * P.max_slices + slice) * 3 + set) * G) * H;
-    for (int i = tid; i < G * H; i += kThreads)
-        dst[i] = ((red[i] + red[G * H + i]) + red[2 * G * H + i]) + red[3 * G * H + i];
 }
 
 // Appends the MFMA B-operand fragments of one layer: index ((nt * KS + ks) * WS + ws) * 64 + lane,
 // lane l holds W[32 ks + 8 (l / 16) + i][16 nt + l % 16], i = 0..7, as bf16 part ws of the exact
 // three-way split of the weight (ws = 0 only when the weights are bf16 already).
-void append_fragments(const float *blob, const LayerRef &lr, int WS, std::vector<uint16_t> *out)
+// With `paired` the contraction index follows the order in which a lane that owns two output
+// columns of the previous layer writes them (columns c and c + 16 of a wave as the halves of one
+// word): k = 32 ks + 16 (i % 2) + 4 (l / 16) + i / 2.
+void append_fragments(const float *blob, const LayerRef &lr, int WS, std::vector<uint16_t> *out, bool paired = false)
 {
     const int NTL = lr.n_out / 16, KS = lr.n_in / 32;
     const size_t base = out->size();
@@ -354,7 +478,8 @@ void append_fragments(const float *blob, const LayerRef &lr, int WS, std::vector
         for (int ks = 0; ks < KS; ++ks)
             for (int lane = 0; lane < 64; ++lane)
                 for (int i = 0; i < 8; ++i) {
-                    const int k = 32 * ks + 8 * (lane / 16) + i, m = 16 * nt + lane % 16;
+                    const int k = paired ? 32 * ks + 16 * (i % 2) + 4 * (lane / 16) + i / 2 : 32 * ks + 8 * (lane / 16) + i;
+                    const int m = 16 * nt + lane % 16;
                     float rest = blob[lr.w + static_cast<size_t>(k) * lr.n_out + m];
                     for (int ws = 0; ws < WS; ++ws) {
                         const uint16_t part = to_bf16(rest);
@@ -373,7 +498,7 @@ void pack_pool_weights(const ModelView &mv, const float *blob, int WS, std::vect
     bias->assign(static_cast<size_t>(3) * mv.L * mv.H, 0.0f);
     for (int set = 0; set < 3; ++set)
         for (int l = 0; l < mv.L; ++l) {
-            append_fragments(blob, mv.l[set].layer[l], WS, frag);
+            append_fragments(blob, mv.l[set].layer[l], WS, frag, l > 0 && (mv.H / 16 + 3) / 4 == 2);
             for (int h = 0; h < mv.H; ++h)
                 (*bias)[(static_cast<size_t>(set) * mv.L + l) * mv.H + h] = blob[mv.l[set].layer[l].b + h];
         }
@@ -391,15 +516,16 @@ void launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace 
                       float *keep, hipStream_t s)
 {
     if (gv.B == 0) return;
-    PoolParams P{gv, wfrag, bias, ws.emb, ws.reach, fa.placement, fa.cur_node, ws.partial,
-                 kPoolSlices, mv.D, mv.G, keep, mv.single_set};
+    hipLaunchKernelGGL(k_pool_sort, dim3(gv.B), dim3(kThreads), 0, s, gv, ws.reach, fa.placement, fa.cur_node, mv.D,
+                       mv.G, mv.single_set, ws.klist, ws.koff);
+    PoolParams P{gv, wfrag, bias, ws.emb, ws.klist, ws.koff, ws.partial, kPoolSlices, mv.G, keep};
     const dim3 grid(3, kPoolSlices, gv.B), block(kThreads);
 #define PL_CASE(HH, WW, LL)                                                          \
     if (mv.H == HH && WS == WW && mv.L == LL) {                                      \
         if (keep)                                                                    \
-            hipLaunchKernelGGL((k_pool_mfma<HH, WW, LL, true>), grid, block, 0, s, P); \
+            hipLaunchKernelGGL((k_pool_tiles<HH, WW, LL, true>), grid, block, 0, s, P); \
         else                                                                         \
-            hipLaunchKernelGGL((k_pool_mfma<HH, WW, LL>), grid, block, 0, s, P);     \
+            hipLaunchKernelGGL((k_pool_tiles<HH, WW, LL>), grid, block, 0, s, P);    \
         return;                                                                      \
     }
     PL_CASE(128, 1, 2) PL_CASE(128, 1, 1)

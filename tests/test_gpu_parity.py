@@ -413,3 +413,39 @@ def test_full_size_sampled_embeddings_and_pooled_sums(name):
         assert_rows_close(got["emb"][n0:n0 + n], ref["emb"], w.H, f"{name} graph {b} embeddings")
         assert_rows_close(got["pooled"][b], ref["pooled"], w.H, f"{name} graph {b} pooled sums")
         assert_logits_close(got["logits"][b:b + 1], ref["logits"].reshape(1, -1), f"{name} graph {b}", 1.0)
+
+
+def test_rollouts_of_one_graph_share_a_layout_bit_for_bit():
+    """A batch of R rollouts of ONE graph (appendix "REINFORCE Algorithm": the baseline averages
+    independent rollouts of the same graph) built with pl_graph_batch_create_replicated: logits,
+    embeddings, pooled sums, node sets and the policy gradient equal, bit for bit, those of the
+    ordinary batch holding the graph R times, on different states per rollout."""
+    import torch
+    import paper_1906_08879_amd as pl
+    from gpu_common import run_gradient
+    for name, R in (("nasnet", 5), ("nmt", 4), ("layered200", 7)):
+        one = make_workload(name, B=1)
+        w = make_workload(name, B=R)                      # R different states, features and current nodes ...
+        n, e = int(one.n_nodes[0]), int(one.n_edges[0])   # ... on R copies of the first graph's topology
+        w.n_nodes, w.n_edges = np.full(R, n, np.int32), np.full(R, e, np.int32)
+        w.edge_src, w.edge_dst = np.tile(one.edge_src, R), np.tile(one.edge_dst, R)
+        rng = np.random.default_rng(3)
+        w.node_feats = np.stack([rng.lognormal(0, 1, n * R), rng.lognormal(10, 1, n * R), rng.random(n * R) < 0.5], axis=1).astype(np.float32)
+        w.placement = rng.integers(0, w.D, n * R).astype(np.int32)
+        w.cur_node = rng.integers(0, n, R).astype(np.int32)
+        w.__post_init__()
+        wt = pl.Weights(w.weights, w.D, w.H, w.n_layers, w.k_sweeps, w.group_by_device, w.weight_dtype)
+        g_rep = pl.GraphBatch(n, e, one.edge_src, one.edge_dst, replicate=R)
+        g_ord = pl.GraphBatch(w.n_nodes, w.n_edges, w.edge_src, w.edge_dst)
+        a = run_library(w, handles=(g_rep, wt), want_class=True)
+        b = run_library(w, handles=(g_ord, wt), want_class=True)
+        for key in ("logits", "probs", "emb", "pooled", "classes"):
+            np.testing.assert_array_equal(a[key], b[key], err_msg=f"{name} {key}")
+        ref = oracle.forward_workload(w, n_threads=THREADS, want_emb=False)
+        assert_logits_close(a["logits"], ref["logits"], name + " replicated", 0.2)
+        actions = rng.integers(0, w.D, R).astype(np.int32)
+        coeff = rng.normal(0, 1, R).astype(np.float32)
+        ga = run_gradient(w, actions, coeff, handles=(g_rep, wt))
+        gb = run_gradient(w, actions, coeff, handles=(g_ord, wt))
+        np.testing.assert_array_equal(ga["grad"], gb["grad"], err_msg=name + " gradient")
+        g_rep.close(); g_ord.close(); wt.close()

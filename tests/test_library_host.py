@@ -208,3 +208,25 @@ def test_bench_refuses_more_than_one_gpu():
                        text=True, timeout=120)
     assert r.returncode == 2
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_replicated_batch_has_the_layout_of_the_repeated_graph():
+    """pl_graph_batch_create_replicated (R rollouts of one graph, the batch shape of the appendix's
+    REINFORCE section): levels, CSR and bucket orders equal those of the graph repeated R times."""
+    import paper_1906_08879_amd as pl
+    from workloads import make_workload
+    w = make_workload("inception", B=1)
+    R = 5
+    rep = pl.GraphBatch(int(w.n_nodes[0]), int(w.n_edges[0]), w.edge_src, w.edge_dst, replicate=R)
+    ordinary = pl.GraphBatch(np.tile(w.n_nodes, R), np.tile(w.n_edges, R), np.tile(w.edge_src, R), np.tile(w.edge_dst, R))
+    assert (rep.B, rep.n_tot, rep.e_tot, rep.max_depth) == (ordinary.B, ordinary.n_tot, ordinary.e_tot, ordinary.max_depth)
+    for a, b in zip(rep.levels(), ordinary.levels()):
+        np.testing.assert_array_equal(a, b)
+    la, lb = rep.layout(), ordinary.layout()
+    for key in la:
+        np.testing.assert_array_equal(la[key], lb[key], err_msg=key)
+    rep.close(); ordinary.close()
+    with pytest.raises(pl.PlacetoError):
+        pl.GraphBatch(3, 3, [0, 1, 2], [1, 2, 0], replicate=4)       # a cycle is refused as usual
+    with pytest.raises(pl.PlacetoError):
+        pl.GraphBatch(3, 1, [0], [1], replicate=0)
