@@ -203,11 +203,11 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     }
     const float4 *featb = P.featb + static_cast<size_t>(dir) * gv.n_tot + n0;
     // the device's row of W_in comes from LDS: read early (device_term), used late (project)
-    auto device_term = [&](const f32x4 ft, int t) {
+    auto device_term = [&](const f32x4 ft, int t) __attribute__((always_inline)) {
         const int dev = __float_as_int(ft[3]) & 0xFFFF;
         return proj_dev[(dev < D ? dev : D) * H + wc0 + 16 * t + col];
     };
-    auto project = [&](const f32x4 ft, float dev_term, int t) {
+    auto project = [&](const f32x4 ft, float dev_term, int t) __attribute__((always_inline)) {
         const int bits = __float_as_int(ft[3]);
         float o = pw_b[t];
         o = fmaf(ft[0], pw_time[t], o);
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     // 4 r .. 4 r + 2 of an A operand.  Two columns per lane travel as one word per part: word
     // 16 wave + col of a row holds columns wc0 + col (low half) and wc0 + 16 + col (high half),
     // which is the order in which pack_sweep_weights lays out the contraction index.
-    auto put_rows = [&](int buf, int r, const float (&y)[TPW]) {
+    auto put_rows = [&](int buf, int r, const float (&y)[TPW]) __attribute__((always_inline)) {
         float rr[TPW], ll[TPW];
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
@@ -249,7 +249,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     // as A rows of the first layer.  Reverse pass: the sum is gated by bit 0 of the row's mask
     // and kept in gs (it is the delta of f's last layer, stored when the chunk is processed).
     auto finish_row = [&](int ct, float (&s)[TPW], uint32_t signs, int (&bit)[NT], const int (&mk)[NT][TPW],
-                          float (&gs)[NT][TPW]) {
+                          float (&gs)[NT][TPW]) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
             if constexpr (BW) {
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         put_rows(0, 4 * ct + kg, s);
         bit[ct] = static_cast<int>(signs >> 31);
     };
-    auto sum_slots = [&](auto kc, uint32_t slots, const float (&far)[TPW], float (&s)[TPW], uint32_t &signs) {
+    auto sum_slots = [&](auto kc, uint32_t slots, const float (&far)[TPW], float (&s)[TPW], uint32_t &signs) __attribute__((always_inline)) {
         constexpr int K = decltype(kc)::value;
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         }
     };
     auto gather_fixed = [&](auto kc, int ntile_x, const u32x4 (&rec)[NT], const float (&far)[NT][TPW], int (&bit)[NT],
-                            const int (&mk)[NT][TPW], float (&gs)[NT][TPW]) {
+                            const int (&mk)[NT][TPW], float (&gs)[NT][TPW]) __attribute__((always_inline)) {
 #pragma unroll
         for (int ct = 0; ct < NT; ++ct) {
             bit[ct] = 0;
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     // The same for a chunk in which some row has more sources than its record holds: that row
     // sums a list of table slots (near sources) and node ids (far sources, read from HBM here).
     auto gather_general = [&](int ntile_x, const u32x4 (&rec)[NT], const float (&far)[NT][TPW], int (&bit)[NT],
-                              const int (&mk)[NT][TPW], float (&gs)[NT][TPW]) {
+                              const int (&mk)[NT][TPW], float (&gs)[NT][TPW]) __attribute__((always_inline)) {
 #pragma unroll
         for (int ct = 0; ct < NT; ++ct) {
             bit[ct] = 0;
@@ -376,7 +376,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     };
     // info = word 3 of a record of the chunk (its chunk-wide bits)
     auto gather = [&](uint32_t info, const u32x4 (&rec)[NT], const float (&far)[NT][TPW], int (&bit)[NT],
-                      const int (&mk)[NT][TPW], float (&gs)[NT][TPW]) {
+                      const int (&mk)[NT][TPW], float (&gs)[NT][TPW]) __attribute__((always_inline)) {
         const int ntile_x = (static_cast<int>((info >> kRecRowsShift) & 7u) + kTileNodes) / kTileNodes;
         const int cls = static_cast<int>((info >> kRecNearShift) & 3u);
         if ((info >> kRecGeneralBit) & 1u)
@@ -388,25 +388,32 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         else
             gather_fixed(std::integral_constant<int, kMaxNear>{}, ntile_x, rec, far, bit, mk, gs);
     };
-    auto rows_of = [](uint32_t info) { return static_cast<int>((info >> kRecRowsShift) & 7u) + 1; };
+    auto rows_of = [](uint32_t info) __attribute__((always_inline)) { return static_cast<int>((info >> kRecRowsShift) & 7u) + 1; };
 
-    // ---- software pipeline state.  rc1, rc2 are the records of chunks c + 1 and c + 2; of chunk
-    // c only the node ids, the row count and the bucket position are kept.  A lane works on rows
-    // kg (tile 0) and kg + 4 (tile 1) of a chunk.
-    auto clampc = [&](int c) { return c < c_end ? c : c_end - 1; };
-    auto load_rec = [&](int c, int ct) {
+    // ---- software pipeline state.  A lane works on rows kg (tile 0) and kg + 4 (tile 1) of a
+    // chunk.  Everything that is loaded for a later chunk lives in a pair of register sets that
+    // swap roles from chunk to chunk (the chunk loop is unrolled by two): a register that a load is still filling is never copied, so no wait falls earlier
+    // than the first real use of the data.
+    //   rcA            records of chunk c + 1 (arrived)
+    //   rcX0 / rcX1    records of chunk c + 2 (loaded during chunk c - 1) / target of the records
+    //                  of chunk c + 3
+    //   ftp0 / ftp1    raw-feature records of chunk c (FF) / target for chunk c + 1
+    //   xs, mks        the same for residual inputs and gate bytes (!FF / BW)
+    //   farp0 / farp1  far messages of chunk c + 1 / target for chunk c + 2
+    // Of chunk c itself only the node ids, the row count and the bucket position are kept.
+    auto clampc = [&](int c) __attribute__((always_inline)) { return c < c_end ? c : c_end - 1; };
+    auto load_rec = [&](int c, int ct) __attribute__((always_inline)) {
         return *reinterpret_cast<const u32x4 *>(plan.rec + static_cast<size_t>(clampc(c)) * CH + 4 * ct + kg);
     };
-    u32x4 rc1[NT], rc2[NT];
+    u32x4 rcA[NT], rcX0[NT], rcX1[NT];
     int vg0[NT];             // global node ids of the rows of chunk c (any valid id for unused rows)
     int rows0, p0;           // rows and first bucket position (within the graph) of chunk c
-    f32x4 ft0[NT];           // raw-feature records of the rows of chunk c        (FF)
-    float x0[NT][TPW];       // residual inputs x_v of chunk c
-    float x1[NT][TPW];       // ... of chunk c + 1                                  (!FF)
+    f32x4 ftp0[NT], ftp1[NT];
+    float x0[NT][TPW];       // (FF) residual inputs x_v of chunk c, computed from its feature records
+    float xs0[NT][TPW], xs1[NT][TPW];
+    int mks0[NT][TPW], mks1[NT][TPW];
     int bit0[NT];            // reachability bits of the rows of chunk c
-    float far1[NT][TPW];     // far messages of the rows of chunk c + 1 (arrived or arriving)
-    float far2[NT][TPW];     // ... of chunk c + 2 (loaded during chunk c)
-    int mk0[NT][TPW], mk1[NT][TPW];   // (BW) gate bytes of the rows of chunk c, c + 1
+    float farp0[NT][TPW], farp1[NT][TPW];
     float gs0[NT][TPW];      // (BW) gated gathered sums of chunk c: the delta of f's last layer
     const uint8_t *mask4 = BW ? P.mask4 + (static_cast<size_t>(dir) * gv.n_tot + n0) * H : nullptr;
     const float *xin = xb + static_cast<size_t>(n0) * H;
@@ -417,14 +424,15 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
 #pragma unroll
         for (int ct = 0; ct < NT; ++ct) {
             rc0[ct] = load_rec(c_begin, ct);
-            rc1[ct] = load_rec(c_begin + 1, ct);
-            rc2[ct] = load_rec(c_begin + 2, ct);
+            rcA[ct] = load_rec(c_begin + 1, ct);
+            rcX0[ct] = load_rec(c_begin + 2, ct);
+            rcX1[ct] = rcX0[ct];
 #pragma unroll
             for (int t = 0; t < TPW; ++t) {
-                far1[ct][t] = far2[ct][t] = 0.0f;     // the first kRing + 1 chunks have no far sources
-                mk0[ct][t] = mk1[ct][t] = 0;
+                farp0[ct][t] = farp1[ct][t] = 0.0f;     // the first kRing + 1 chunks have no far sources
+                mks0[ct][t] = mks1[ct][t] = 0;
                 gs0[ct][t] = 0.0f;
-                x0[ct][t] = x1[ct][t] = 0.0f;
+                x0[ct][t] = xs0[ct][t] = xs1[ct][t] = 0.0f;
             }
         }
         const uint32_t info0 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rc0[0][3])));
@@ -437,36 +445,35 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             const uint32_t id = rc0[ct][3] & kRecNoNode;
             vg0[ct] = n0 + static_cast<int>(id == kRecNoNode ? 0u : id);
             if constexpr (FF) {
-                ft0[ct] = *reinterpret_cast<const f32x4 *>(featb + p0 + rr);
+                ftp0[ct] = *reinterpret_cast<const f32x4 *>(featb + p0 + rr);
+                ftp1[ct] = ftp0[ct];
             } else {
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
-                    x0[ct][t] = xin[static_cast<size_t>(p0 + rr) * H + wc0 + 16 * t + col];
-                    if constexpr (BW) mk0[ct][t] = mask4[static_cast<size_t>(p0 + rr) * H + wc0 + 16 * t + col];
+                    xs0[ct][t] = xin[static_cast<size_t>(p0 + rr) * H + wc0 + 16 * t + col];
+                    if constexpr (BW) mks0[ct][t] = mask4[static_cast<size_t>(p0 + rr) * H + wc0 + 16 * t + col];
                 }
             }
         }
         __syncthreads();
-        gather(info0, rc0, far1, bit0, mk0, gs0);
+        gather(info0, rc0, farp0, bit0, mks0, gs0);
     }
     __syncthreads();
 
-    for (int c = c_begin; c < c_end; ++c) {
+    // rB / rC: records of chunk c + 2 / target of chunk c + 3's; fC / fN: feature records of chunk
+    // c / target of chunk c + 1's; xC, mC / xN, mN: the same for residual inputs and gate bytes;
+    // farA / farB: far messages of chunk c + 1 / target of chunk c + 2's
+    auto step = [&](int c, u32x4 (&rB)[NT], u32x4 (&rC)[NT], f32x4 (&fC)[NT], f32x4 (&fN)[NT],
+                    float (&xC)[NT][TPW], float (&xN)[NT][TPW], int (&mC)[NT][TPW], int (&mN)[NT][TPW],
+                    float (&farA)[NT][TPW], float (&farB)[NT][TPW]) __attribute__((always_inline)) {
         const int rows = rows0;
         const bool two = rows > kTileNodes;      // the chunk fills a second row tile
         const bool has_next = c + 1 < c_end;
         const int ring = (c - c_begin) % RING;   // table rows ring * CH .. of this chunk's messages
-        const uint32_t info1 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rc1[0][3])));
+        const uint32_t info1 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rcA[0][3])));
         const int rows1 = rows_of(info1);
-        const int p1 = __builtin_amdgcn_readfirstlane(static_cast<int>(rc1[0][2]));
+        const int p1 = __builtin_amdgcn_readfirstlane(static_cast<int>(rcA[0][2]));
 
-        u32x4 rc3[NT];
-        f32x4 ft1[NT];
-#pragma unroll
-        for (int ct = 0; ct < NT; ++ct) {
-            rc3[ct] = rc2[ct];
-            if constexpr (FF) ft1[ct] = ft0[ct];
-        }
         // Accumulators, one chain per (row tile, column tile): acc[ct][t].  The chains of a wave's
         // column tiles (and of the co-resident workgroup) interleave, so a dependent matrix
         // instruction never waits for its predecessor.
@@ -475,7 +482,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
 #pragma unroll
         for (int n = 0; n < NL; ++n) {
             // ---- rows of A from LDS (activation parts), weights from registers
-            auto mfma_one_tile = [&]() {
+            auto mfma_one_tile = [&]() __attribute__((always_inline)) {
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&actbuf[n & 1][col][32 * ks + 8 * kg]);
@@ -488,7 +495,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         }
                 }
             };
-            auto mfma_two_tiles = [&]() {
+            auto mfma_two_tiles = [&]() __attribute__((always_inline)) {
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -508,7 +515,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             // wc0 + 16 t + col, the three partial products in rows 0..2 of its accumulators.
             // Row tile 0 is handled by code common to both kinds of chunk, so that its stores
             // are on every path (see sink_row).
-            auto epilogue = [&](int ct) {
+            auto epilogue = [&](int ct) __attribute__((always_inline)) {
                 const int r = ct * kTileNodes + kg;
                 const bool live = r < rows;
                 const int v_emb = live ? vg0[ct] : gv.n_tot;
@@ -523,20 +530,20 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         // layers L-1 .. 0; slot = index into the 2L delta arrays (f first)
                         const uint32_t d_row = live ? static_cast<uint32_t>(vg0[ct] * H + m)
                                                     : static_cast<uint32_t>(2 * L * gv.n_tot * H + m);
-                        auto put_delta = [&](int slot, float val) {
+                        auto put_delta = [&](int slot, float val) __attribute__((always_inline)) {
                             dlt[live ? static_cast<uint32_t>(slot * gv.n_tot * H) + d_row : d_row] = val;
                         };
                         if (n == 0) put_delta(L - 1, gs0[ct][t]);
                         if (n == L - 1) {                // end of f^T: ds_v = outside gradient + f path
-                            y += x0[ct][t];
+                            y += FF ? x0[ct][t] : xC[ct][t];
                             P.emb[static_cast<uint32_t>(v_emb * 2 * H + (1 - dir) * H + m)] = y;
-                            y = (mk0[ct][t] & 4) ? y : 0.0f;
+                            y = (mC[ct][t] & 4) ? y : 0.0f;
                             put_delta(L + L - 1, y);
                         } else if (n < L - 1) {
-                            y = (mk0[ct][t] & 2) ? y : 0.0f;
+                            y = (mC[ct][t] & 2) ? y : 0.0f;
                             put_delta(L - 2 - n, y);
                         } else if (n < NL - 1) {
-                            y = (mk0[ct][t] & 8) ? y : 0.0f;
+                            y = (mC[ct][t] & 8) ? y : 0.0f;
                             put_delta(L + NL - 2 - n, y);
                         }
                         if (n == NL - 1) {               // end of g^T: da_v
@@ -554,7 +561,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         if (n < NL - 1) dlt[live ? static_cast<uint32_t>((1 + n) * gv.n_tot * H) + d_row : d_row] = y;
                     }
                     if (n == L - 1) {                    // end of g: residual update of s_v
-                        y += x0[ct][t];
+                        y += FF ? x0[ct][t] : xC[ct][t];
                         P.emb[static_cast<uint32_t>(v_emb * 2 * H + dir * H + m)] = y;
                         if constexpr (WX) xb[static_cast<uint32_t>((live ? n0 + p0 + r : spare_row) * H + m)] = y;
                     }
@@ -579,7 +586,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 // (this wave's columns, in the layout in which they are summed).  A row without
                 // a far source reads the row of zeros.  The messages were stored by this wave
                 // at least kRing - 1 chunks ago; see the note at the top of the file.
-                const uint32_t info2 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rc2[0][3])));
+                const uint32_t info2 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rB[0][3])));
                 const bool two2 = rows_of(info2) > kTileNodes;
                 float dterm[NT][TPW];
                 if constexpr (FF) {
@@ -587,25 +594,25 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     for (int ct = 0; ct < NT; ++ct)
                         if (ct == 0 || two) {
 #pragma unroll
-                            for (int t = 0; t < TPW; ++t) dterm[ct][t] = device_term(ft0[ct], t);
+                            for (int t = 0; t < TPW; ++t) dterm[ct][t] = device_term(fC[ct], t);
                         }
                 }
 #pragma unroll
                 for (int ct = 0; ct < NT; ++ct) {
                     if (ct > 0 && !two2) continue;
-                    const uint32_t u = rc2[ct][1];
-                    const bool wanted = (rc2[ct][0] & kRecListed) == 0 && u != kNoFar;
+                    const uint32_t u = rB[ct][1];
+                    const bool wanted = (rB[ct][0] & kRecListed) == 0 && u != kNoFar;
                     const int row = wanted ? n0 + static_cast<int>(u) : spare_row;
 #pragma unroll
                     for (int t = 0; t < TPW; ++t)
-                        far2[ct][t] = msg[static_cast<uint32_t>(row * H + wc0 + 16 * t + col)];
+                        farB[ct][t] = msg[static_cast<uint32_t>(row * H + wc0 + 16 * t + col)];
                 }
                 if constexpr (FF) {
 #pragma unroll
                     for (int ct = 0; ct < NT; ++ct)
                         if (ct == 0 || two) {
 #pragma unroll
-                            for (int t = 0; t < TPW; ++t) x0[ct][t] = project(ft0[ct], dterm[ct][t], t);
+                            for (int t = 0; t < TPW; ++t) x0[ct][t] = project(fC[ct], dterm[ct][t], t);
                         }
                 }
             }
@@ -615,18 +622,18 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 const bool two1 = rows1 > kTileNodes;
 #pragma unroll
                 for (int ct = 0; ct < NT; ++ct) {
-                    rc3[ct] = load_rec(c + 3, ct);
+                    rC[ct] = load_rec(c + 3, ct);
                     if (ct > 0 && !two1) continue;
                     const int r = 4 * ct + kg;
                     const int rr = (r < rows1) ? r : 0;
                     if constexpr (FF) {
-                        ft1[ct] = *reinterpret_cast<const f32x4 *>(featb + p1 + static_cast<uint32_t>(rr));
+                        fN[ct] = *reinterpret_cast<const f32x4 *>(featb + p1 + static_cast<uint32_t>(rr));
                     } else {
 #pragma unroll
                         for (int t = 0; t < TPW; ++t) {
-                            x1[ct][t] = (xin + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
+                            xN[ct][t] = (xin + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
                             if constexpr (BW)
-                                mk1[ct][t] = (mask4 + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
+                                mN[ct][t] = (mask4 + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
                         }
                     }
                 }
@@ -650,7 +657,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
 
             // The table rows that chunk c + 1 sums were all written by this wave (its own
             // columns), so its gather follows without a barrier.
-            if (n == NL - 1 && has_next) gather(info1, rc1, far1, bit0, mk1, gs0);
+            if (n == NL - 1 && has_next) gather(info1, rcA, farA, bit0, mN, gs0);
             lds_barrier();
         }
 
@@ -658,22 +665,14 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         p0 = p1;
 #pragma unroll
         for (int ct = 0; ct < NT; ++ct) {
-            const uint32_t id = rc1[ct][3] & kRecNoNode;
+            const uint32_t id = rcA[ct][3] & kRecNoNode;
             vg0[ct] = n0 + static_cast<int>(id == kRecNoNode ? 0u : id);
-            rc1[ct] = rc2[ct];
-            rc2[ct] = rc3[ct];
-            if constexpr (FF) {
-                ft0[ct] = ft1[ct];
-            } else {
-#pragma unroll
-                for (int t = 0; t < TPW; ++t) x0[ct][t] = x1[ct][t];
-            }
-#pragma unroll
-            for (int t = 0; t < TPW; ++t) {
-                far1[ct][t] = far2[ct][t];
-                if constexpr (BW) mk0[ct][t] = mk1[ct][t];
-            }
+            rcA[ct] = rB[ct];       // arrived: its far ids were used behind this chunk's first layer
         }
+    };
+    for (int c = c_begin; c < c_end; c += 2) {
+        step(c, rcX0, rcX1, ftp0, ftp1, xs0, xs1, mks0, mks1, farp0, farp1);
+        if (c + 1 < c_end) step(c + 1, rcX1, rcX0, ftp1, ftp0, xs1, xs0, mks1, mks0, farp1, farp0);
     }
 }
 
