@@ -337,6 +337,36 @@ def main() -> int:
                 continue
             other[name] = forward_only(pl, torch, make_workload(name), 20, 3)
 
+    # a batch of rollouts of ONE graph (the batch shape of the REINFORCE baseline): the layout is
+    # built once and the sweep kernel's plan is shared by all copies
+    replicated = None
+    if default_variant and args.batch is None and not args.no_other_workloads:
+        one = make_workload(args.workload, B=1)
+        t0 = time.perf_counter()
+        g_rep = pl.GraphBatch(int(one.n_nodes[0]), int(one.n_edges[0]), one.edge_src, one.edge_dst, replicate=int(w.B))
+        rep_build_ms = 1e3 * (time.perf_counter() - t0)
+        n1 = int(one.n_nodes[0])
+        rng = np.random.default_rng(5)
+        r_f = torch.from_numpy(np.tile(np.asarray(one.node_feats, np.float32), (int(w.B), 1))).to(dev)
+        r_p = torch.from_numpy(rng.integers(0, w.D, n1 * int(w.B)).astype(np.int32)).to(dev)
+        r_c = torch.from_numpy(rng.integers(0, n1, int(w.B)).astype(np.int32)).to(dev)
+        for _ in range(3):
+            pl.embed_forward(g_rep, r_f, r_p, r_c, wt, logits)
+        torch.cuda.synchronize()
+        g_rep.profile_enable(True)
+        g_rep.profile_read(reset=True)
+        t0 = time.perf_counter()
+        for _ in range(10):
+            pl.embed_forward(g_rep, r_f, r_p, r_c, wt, logits)
+        torch.cuda.synchronize()
+        rep_ms = 1e2 * (time.perf_counter() - t0)
+        rep_st = g_rep.profile_read(reset=True)
+        replicated = {"rollouts": int(w.B), "nodes_per_graph": n1, "levels": int(g_rep.max_depth),
+                      "layout_build_ms": round(rep_build_ms, 2), "ms_per_step": round(rep_ms, 4),
+                      "stage_ms": {k: round(v[0] / v[1], 4) for k, v in rep_st.items() if v[1]},
+                      "what": "B rollouts of the first graph of the workload, one shared layout and gather plan"}
+        g_rep.close()
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
@@ -390,6 +420,7 @@ def main() -> int:
         "layout_build_ms": round(layout_build_ms, 2),
         "roofline": roofline,
         "other_workloads": other,
+        "replicated_batch": replicated,
         "episode": episode,
         "simulator": simulator,
         "gradient": gradient,
