@@ -130,6 +130,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     constexpr int kZeroSlot = kMsgSlots;
     static_assert(NTL % NW == 0, "column tiles must divide over the waves");
     static_assert(TPW == 1 || TPW == 2, "a lane owns one or two output columns");
+    constexpr bool kReadFirst = TPW == 1;
 
     // Message table: H floats per row.  Messages are ReLU outputs, so their sign bit is free:
     // it carries the reachability flag of the row's node (set if the node is v* or has v* among
@@ -482,16 +483,23 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
 #pragma unroll
         for (int n = 0; n < NL; ++n) {
             // ---- rows of A from LDS (activation parts), weights from registers
+            // One row tile: the A fragments are read first (a1), the loads and stores of the
+            // pipeline ("mid block") are issued while they travel, then the matrix instructions.
+            bf16x8 a1[KS];
+            auto read_one_tile = [&]() __attribute__((always_inline)) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    a1[ks] = *reinterpret_cast<const bf16x8 *>(&actbuf[n & 1][col][32 * ks + 8 * kg]);
+            };
             auto mfma_one_tile = [&]() __attribute__((always_inline)) {
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&actbuf[n & 1][col][32 * ks + 8 * kg]);
 #pragma unroll
                     for (int t = 0; t < TPW; ++t)
 #pragma unroll
                         for (int ws = 0; ws < WS; ++ws) {
                             const f32x4 c_in = (ks == 0 && ws == 0) ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[0][t];
-                            acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, W[n][t][ks][ws], c_in, 0, 0, 0);
+                            acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[ks], W[n][t][ks][ws], c_in, 0, 0, 0);
                         }
                 }
             };
@@ -576,80 +584,99 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 if (n < NL - 1) put_rows((n + 1) & 1, r, yv);
             };
 
-            if (two)
-                mfma_two_tiles();
-            else
-                mfma_one_tile();
-
-            if (n == 0) {
-                // Behind the first layer's matrix instructions: the far messages of chunk c + 2
-                // (this wave's columns, in the layout in which they are summed).  A row without
-                // a far source reads the row of zeros.  The messages were stored by this wave
-                // at least kRing - 1 chunks ago; see the note at the top of the file.
-                const uint32_t info2 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rB[0][3])));
-                const bool two2 = rows_of(info2) > kTileNodes;
-                float dterm[NT][TPW];
-                if constexpr (FF) {
-#pragma unroll
-                    for (int ct = 0; ct < NT; ++ct)
-                        if (ct == 0 || two) {
-#pragma unroll
-                            for (int t = 0; t < TPW; ++t) dterm[ct][t] = device_term(fC[ct], t);
-                        }
-                }
-#pragma unroll
-                for (int ct = 0; ct < NT; ++ct) {
-                    if (ct > 0 && !two2) continue;
-                    const uint32_t u = rB[ct][1];
-                    const bool wanted = (rB[ct][0] & kRecListed) == 0 && u != kNoFar;
-                    const int row = wanted ? n0 + static_cast<int>(u) : spare_row;
-#pragma unroll
-                    for (int t = 0; t < TPW; ++t)
-                        farB[ct][t] = msg[static_cast<uint32_t>(row * H + wc0 + 16 * t + col)];
-                }
-                if constexpr (FF) {
-#pragma unroll
-                    for (int ct = 0; ct < NT; ++ct)
-                        if (ct == 0 || two) {
-#pragma unroll
-                            for (int t = 0; t < TPW; ++t) x0[ct][t] = project(fC[ct], dterm[ct][t], t);
-                        }
-                }
-            }
-            if (n == (NL > 2 ? 1 : 0)) {
-                // behind the second layer's matrix instructions: the records of chunk c + 3 and
-                // the inputs of chunk c + 1
-                const bool two1 = rows1 > kTileNodes;
-#pragma unroll
-                for (int ct = 0; ct < NT; ++ct) {
-                    rC[ct] = load_rec(c + 3, ct);
-                    if (ct > 0 && !two1) continue;
-                    const int r = 4 * ct + kg;
-                    const int rr = (r < rows1) ? r : 0;
+            // The loads and stores of the pipeline (the "mid block" below) are issued while the A
+            // fragments travel from LDS where a wave has the registers to hold the fragments
+            // meanwhile (one column tile per wave); otherwise behind the matrix instructions.
+            auto mid_block = [&]() __attribute__((always_inline)) {
+                if (n == 0) {
+                    // First layer: the far messages of chunk c + 2
+                    // (this wave's columns, in the layout in which they are summed).  A row without
+                    // a far source reads the row of zeros.  The messages were stored by this wave
+                    // at least kRing - 1 chunks ago; see the note at the top of the file.
+                    const uint32_t info2 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rB[0][3])));
+                    const bool two2 = rows_of(info2) > kTileNodes;
+                    float dterm[NT][TPW];
                     if constexpr (FF) {
-                        fN[ct] = *reinterpret_cast<const f32x4 *>(featb + p1 + static_cast<uint32_t>(rr));
-                    } else {
 #pragma unroll
-                        for (int t = 0; t < TPW; ++t) {
-                            xN[ct][t] = (xin + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
-                            if constexpr (BW)
-                                mN[ct][t] = (mask4 + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
-                        }
+                        for (int ct = 0; ct < NT; ++ct)
+                            if (ct == 0 || two) {
+#pragma unroll
+                                for (int t = 0; t < TPW; ++t) dterm[ct][t] = device_term(fC[ct], t);
+                            }
                     }
-                }
-            }
-
-            if (n == NL - 1) {
-                // Behind the last layer's matrix instructions: the reachability bits of this
-                // chunk's nodes go to HBM (for the pooling kernel).
-                if constexpr (!BW) {
 #pragma unroll
                     for (int ct = 0; ct < NT; ++ct) {
-                        const int r = ct * kTileNodes + kg;
-                        const bool mine = wave == 0 && col == 0 && r < rows;
-                        reach[static_cast<uint32_t>(mine ? vg0[ct] : sink_row)] = static_cast<uint8_t>(bit0[ct]);
+                        if (ct > 0 && !two2) continue;
+                        const uint32_t u = rB[ct][1];
+                        const bool wanted = (rB[ct][0] & kRecListed) == 0 && u != kNoFar;
+                        const int row = wanted ? n0 + static_cast<int>(u) : spare_row;
+#pragma unroll
+                        for (int t = 0; t < TPW; ++t)
+                            farB[ct][t] = msg[static_cast<uint32_t>(row * H + wc0 + 16 * t + col)];
+                    }
+                    if constexpr (FF) {
+#pragma unroll
+                        for (int ct = 0; ct < NT; ++ct)
+                            if (ct == 0 || two) {
+#pragma unroll
+                                for (int t = 0; t < TPW; ++t) x0[ct][t] = project(fC[ct], dterm[ct][t], t);
+                            }
                     }
                 }
+                if (n == (NL > 2 ? 1 : 0)) {
+                    // second layer: the records of chunk c + 3 and
+                    // the inputs of chunk c + 1
+                    const bool two1 = rows1 > kTileNodes;
+#pragma unroll
+                    for (int ct = 0; ct < NT; ++ct) {
+                        rC[ct] = load_rec(c + 3, ct);
+                        if (ct > 0 && !two1) continue;
+                        const int r = 4 * ct + kg;
+                        const int rr = (r < rows1) ? r : 0;
+                        if constexpr (FF) {
+                            fN[ct] = *reinterpret_cast<const f32x4 *>(featb + p1 + static_cast<uint32_t>(rr));
+                        } else {
+#pragma unroll
+                            for (int t = 0; t < TPW; ++t) {
+                                xN[ct][t] = (xin + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
+                                if constexpr (BW)
+                                    mN[ct][t] = (mask4 + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
+                            }
+                        }
+                    }
+                }
+
+                if (n == NL - 1) {
+                    // Last layer: the reachability bits of this
+                    // chunk's nodes go to HBM (for the pooling kernel).
+                    if constexpr (!BW) {
+#pragma unroll
+                        for (int ct = 0; ct < NT; ++ct) {
+                            const int r = ct * kTileNodes + kg;
+                            const bool mine = wave == 0 && col == 0 && r < rows;
+                            reach[static_cast<uint32_t>(mine ? vg0[ct] : sink_row)] = static_cast<uint8_t>(bit0[ct]);
+                        }
+                    }
+                }
+
+            };
+            if constexpr (kReadFirst) {
+                if (!two) read_one_tile();
+                __builtin_amdgcn_sched_barrier(0);
+                mid_block();
+                __builtin_amdgcn_sched_barrier(0);
+                if (two)
+                    mfma_two_tiles();
+                else
+                    mfma_one_tile();
+            } else {
+                if (two) {
+                    mfma_two_tiles();
+                } else {
+                    read_one_tile();
+                    mfma_one_tile();
+                }
+                mid_block();
             }
 
             epilogue(0);
