@@ -301,7 +301,7 @@ size_t carve_workspace(unsigned char *base, size_t n, size_t B, const ModelView 
 
 void free_grad_workspace(GradWorkspace &gw)
 {
-    float *all[] = {gw.fact, gw.gact, gw.agg, gw.dagg, gw.dfg, gw.keep, gw.snap_emb, gw.snap_msg, gw.extb, gw.lact, gw.dl, gw.demb, gw.dx, gw.phi,
+    float *all[] = {gw.fact, gw.gact, gw.agg, gw.dagg, gw.dfg, gw.keep, gw.snap_emb, gw.snap_msg, gw.lact, gw.dl, gw.demb, gw.dx, gw.phi,
                     gw.pooled, gw.dP, gw.hin, gw.hact, gw.dh, gw.dz, gw.hid, gw.dpre, gw.dlogit, gw.partial};
     for (float *p : all) (void)hipFree(p);
     (void)hipFree(gw.cls);
@@ -362,8 +362,7 @@ int ensure_grad_workspace(pl_graph_batch *g, const ModelView &mv)
     gw.dfg_stride = 2 * L * NH + H;
     PL_HIP(take(&gw.dfg, 2 * gw.dfg_stride));
     PL_HIP(take(&gw.keep, 2 * gw.dfg_stride));
-    PL_HIP(take(&gw.extb, 2 * NH + H));
-    PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.mask4), 2 * NH + 16));
+    PL_HIP(hipMalloc(reinterpret_cast<void **>(&gw.mask4), 2 * NH + H + 16));
     PL_HIP(take(&gw.lact, L * NH));
     PL_HIP(take(&gw.dl, L * NH));
     PL_HIP(take(&gw.demb, 2 * NH + 2 * H));
@@ -510,7 +509,7 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
                  float *out_node_emb, float *out_pooled, uint8_t *out_class, void *stream, bool validate,
                  float *keep = nullptr, size_t keep_stride = 0, float *keep_pool = nullptr,
                  bool *pool_kept = nullptr, float *snap_emb = nullptr, float *snap_msg = nullptr,
-                 const Workspace *static_ws = nullptr)
+                 const Workspace *static_ws = nullptr, uint8_t *gates = nullptr)
 {
     if (!g || !w) return fail(PL_ERR_NULL, "graph batch or weights handle is NULL");
     if (g->host.B == 0) return PL_OK;
@@ -550,7 +549,8 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
         for (int k = 0; k < w->cfg.k_sweeps; ++k) {
             if (mfma)
                 launch_sweep_mfma(gv, mv, ws, fa, reinterpret_cast<const uint4 *>(w->d_wfrag),
-                                  w->d_sweep_bias, w->sweep_ws, k == 0, k + 1 < w->cfg.k_sweeps, keep, keep_stride, s);
+                                  w->d_sweep_bias, w->sweep_ws, k == 0, k + 1 < w->cfg.k_sweeps, keep, keep_stride,
+                                  gates, s);
             else
                 launch_sweep_generic(gv, mv, ws, fa, k == 0, s);
             if (snap_emb && k + 1 < w->cfg.k_sweeps) {
@@ -1084,7 +1084,7 @@ static int policy_gradient_impl(pl_graph_batch *g, const float *node_feats, cons
     bool pool_kept = false;
     rc = forward_impl(g, node_feats, placement, cur_node, w, out_logits, nullptr, nullptr, g->gw.pooled, nullptr,
                       stream, false, keep, g->gw.dfg_stride, w->path == 0 ? g->gw.lact : nullptr, &pool_kept,
-                      w->cfg.k_sweeps > 1 ? g->gw.snap_emb : nullptr, g->gw.snap_msg);
+                      w->cfg.k_sweeps > 1 ? g->gw.snap_emb : nullptr, g->gw.snap_msg, nullptr, g->gw.mask4);
     if (rc) return rc;
     if (!accumulate) launch_fill_zero(grad, plan_weights(w->cfg, nullptr), s);
     ForwardArgs fa{node_feats, placement, cur_node, out_logits, nullptr, g->gw.pooled};

@@ -202,8 +202,7 @@ struct GradWorkspace {
     float *snap_emb = nullptr, *snap_msg = nullptr;   // k >= 2 sweeps: states and messages after every
                                               // sweep but the last, [k - 1][2 n_tot H] each
     int32_t snap_sweeps = 0;
-    float *extb = nullptr;                    // [2, n_tot, H] outside gradient of the states, bucket order
-    uint8_t *mask4 = nullptr;                 // [2, n_tot, H] ReLU gates, bucket order
+    uint8_t *mask4 = nullptr;                 // [2 n_tot + 1, H] ReLU gates per (sweep direction, node, column)
     float *lact = nullptr, *dl = nullptr;     // [L, n_tot, H] layer outputs / deltas of l (own set)
     float *demb = nullptr;                    // [n_tot, 2H] gradient of the embeddings
     float *dx = nullptr;                      // [n_tot, H] delta of the projection
@@ -253,10 +252,11 @@ bool sweep_mfma_supported(int H, int L, int weight_dtype);
 void pack_sweep_weights(const ModelView &mv, const float *blob, int WS, std::vector<uint16_t> *frag,
                         std::vector<float> *bias, bool reverse = false);
 void launch_sweep_mfma_bw(const GraphView &gv, const ModelView &mv, const uint4 *wfrag, const float *bias,
-                          int WS, const int32_t *cur_node, float *demb, float *extb, float *dagg,
-                          const uint8_t *mask4, float *delta, size_t delta_stride, hipStream_t s);
+                          int WS, const int32_t *cur_node, float *demb, float *dagg, uint8_t *mask4,
+                          float *delta, size_t delta_stride, hipStream_t s);
 void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                        const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
-                       bool first_sweep, bool more_sweeps, float *keep, size_t keep_stride, hipStream_t s);
+                       bool first_sweep, bool more_sweeps, float *keep, size_t keep_stride, uint8_t *gates,
+                       hipStream_t s);
 
 }  // namespace pl

@@ -541,18 +541,12 @@ struct GateSrc {
     const float *g0;       // output of g's layer 0 (L = 2)
 };
 
-__global__ __launch_bounds__(kThreads) void k_bw_prep(GraphView gv, int H, int L,
-                                                      const float *__restrict__ demb, GateSrc src0,
-                                                      GateSrc src1, float *__restrict__ extb,
-                                                      uint8_t *__restrict__ mask4)
+__global__ __launch_bounds__(kThreads) void k_bw_gates(GraphView gv, int H, int L, GateSrc src0, GateSrc src1,
+                                                       uint8_t *__restrict__ mask4)
 {
     const size_t idx = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
     if (idx >= static_cast<size_t>(gv.n_tot) * H) return;
-    const int v = static_cast<int>(idx / H), h = static_cast<int>(idx - static_cast<size_t>(v) * H);
-    for (int pd = 0; pd < 2; ++pd) {
-        const int sd = 1 - pd;
-        const size_t at = (static_cast<size_t>(pd) * gv.n_tot + gv.pos[pd][v]) * H + h;
-        extb[at] = demb[static_cast<size_t>(v) * 2 * H + sd * H + h];
+    for (int sd = 0; sd < 2; ++sd) {
         const GateSrc &gs = sd ? src1 : src0;
         int bits = fabsf(gs.m[idx]) > 0.0f ? 1 : 0;     // messages may carry a flag in their sign bit
         bits |= gs.g_last[idx] > 0.0f ? 4 : 0;
@@ -560,7 +554,7 @@ __global__ __launch_bounds__(kThreads) void k_bw_prep(GraphView gv, int H, int L
             bits |= gs.f0[idx] > 0.0f ? 2 : 0;
             bits |= gs.g0[idx] > 0.0f ? 8 : 0;
         }
-        mask4[at] = static_cast<uint8_t>(bits);
+        mask4[static_cast<size_t>(sd) * gv.n_tot * H + idx] = static_cast<uint8_t>(bits);
     }
 }
 
@@ -1774,23 +1768,24 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
             PL_DISPATCH_RPT(rpt, CALL)
 #undef CALL
         }
-        if (wfrag_bw) {
+        if (wfrag_bw && !keep) {
+            // the forward sweep that keeps activations also writes the gate bytes; otherwise they
+            // are taken from the recomputed layer outputs here
             GateSrc src[2];
             for (int sd = 0; sd < 2; ++sd) {
-                const bool from_msg = keep || dense;
-                src[sd].m = from_msg ? msg_j + static_cast<size_t>(sd) * NH : fact_of(sd, L - 1);
+                src[sd].m = dense ? msg_j + static_cast<size_t>(sd) * NH : fact_of(sd, L - 1);
                 src[sd].f0 = L == 2 ? fact_of(sd, 0) : nullptr;
                 src[sd].g_last = gact_of(sd, L - 1);
                 src[sd].g0 = L == 2 ? gact_of(sd, 0) : nullptr;
             }
-            hipLaunchKernelGGL(k_bw_prep, dim3(static_cast<unsigned>((NH + kThreads - 1) / kThreads)),
-                               dim3(kThreads), 0, s, gv, H, L, gw.demb, src[0], src[1], gw.extb, gw.mask4);
+            hipLaunchKernelGGL(k_bw_gates, dim3(static_cast<unsigned>((NH + kThreads - 1) / kThreads)),
+                               dim3(kThreads), 0, s, gv, H, L, src[0], src[1], gw.mask4);
         }
         mark(PL_STAGE_BW_ACTS, false);
         mark(PL_STAGE_BW_CHAIN, true);
         if (wfrag_bw) {
-            launch_sweep_mfma_bw(gv, mv, wfrag_bw, sweep_bias, sweep_ws, fa.cur_node, gw.demb, gw.extb, gw.dagg,
-                                 gw.mask4, gw.dfg, gw.dfg_stride, s);
+            launch_sweep_mfma_bw(gv, mv, wfrag_bw, sweep_bias, sweep_ws, fa.cur_node, gw.demb, gw.dagg, gw.mask4,
+                                 gw.dfg, gw.dfg_stride, s);
         } else {
 #define CALL(R)                                                                                            \
     allow_lds_bw(k_bw_sweep_generic<R>, lds);                                                              \

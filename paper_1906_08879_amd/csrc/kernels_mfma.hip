@@ -87,10 +87,12 @@ struct SweepParams {
     const float4 *featb;    // [2, n_tot] {run time, output size, is-visited, bits(device | is-current << 16)}
     const float *proj;      // [(F + 1), H]: rows of W_in, then b_in; NULL when the input comes from xb
     int D;
-    // reverse pass (BW): ReLU masks of the node's layers in bucket order, one byte per (node,
-    // column): bit 0 gates the gathered sum, bits 1..3 the outputs of layers 0 (L = 2 only),
-    // L - 1 and L (L = 2 only); and the layer deltas, 2L arrays [n_tot, H] in node order
-    const uint8_t *mask4;   // [2, n_tot, H]
+    // ReLU gates of every node's layers, one byte per (sweep direction, node, column), node order:
+    // bit 0 m_v > 0 (gates the gathered sum of the reverse pass), bit 1 output of f's layer 0 > 0
+    // (L = 2), bit 2 output of g's last layer > 0, bit 3 output of g's layer 0 > 0 (L = 2).
+    // Written by a sweep that keeps activations (TR), read by the reverse pass (BW); row 2 n_tot
+    // takes the stores of a chunk's unused rows.
+    uint8_t *mask4;         // [2 n_tot + 1, H]
     float *delta;           // per sweep direction: [2L][n_tot, H] (f's layers, then g's), then H
                             // floats that take the stores of a chunk's unused rows
     size_t delta_stride;    // floats between the two directions' blocks
@@ -249,15 +251,23 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     // the row's far message, which is already in registers (zeros if the row has none); written
     // as A rows of the first layer.  Reverse pass: the sum is gated by bit 0 of the row's mask
     // and kept in gs (it is the delta of f's last layer, stored when the chunk is processed).
+    // A sweep that keeps activations (TR) stores the sum right here (w3 = word 3 of the row's
+    // record: its node id), slot 0 of the kept arrays.
     auto finish_row = [&](int ct, float (&s)[TPW], uint32_t signs, int (&bit)[NT], const int (&mk)[NT][TPW],
-                          float (&gs)[NT][TPW]) __attribute__((always_inline)) {
+                          float (&gs)[NT][TPW], uint32_t w3) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
             if constexpr (BW) {
                 s[t] = (mk[ct][t] & 1) ? s[t] : 0.0f;
                 gs[ct][t] = s[t];
             }
-            if constexpr (TR) gs[ct][t] = s[t];
+            if constexpr (TR) {
+                const uint32_t id = w3 & kRecNoNode;
+                const int m = wc0 + 16 * t + col;
+                float *kept = P.delta + static_cast<size_t>(dir) * P.delta_stride;
+                kept[id == kRecNoNode ? static_cast<uint32_t>(2 * L * gv.n_tot * H + m)
+                                      : static_cast<uint32_t>((n0 + static_cast<int>(id)) * H + m)] = s[t];
+            }
         }
         put_rows(0, 4 * ct + kg, s);
         bit[ct] = static_cast<int>(signs >> 31);
@@ -290,7 +300,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             float s[TPW];
             uint32_t signs = 0;
             sum_slots(kc, rec[ct][0], far[ct], s, signs);
-            finish_row(ct, s, signs, bit, mk, gs);
+            finish_row(ct, s, signs, bit, mk, gs, rec[ct][3]);
         }
     };
     // The same for a chunk in which some row has more sources than its record holds: that row
@@ -372,7 +382,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     }
                 }
             }
-            finish_row(ct, s, signs, bit, mk, gs);
+            finish_row(ct, s, signs, bit, mk, gs, rec[ct][3]);
         }
     };
     // info = word 3 of a record of the chunk (its chunk-wide bits)
@@ -416,8 +426,16 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     int bit0[NT];            // reachability bits of the rows of chunk c
     float farp0[NT][TPW], farp1[NT][TPW];
     float gs0[NT][TPW];      // (BW) gated gathered sums of chunk c: the delta of f's last layer
-    const uint8_t *mask4 = BW ? P.mask4 + (static_cast<size_t>(dir) * gv.n_tot + n0) * H : nullptr;
+    // the reverse pass works on sweep direction 1 - dir: it reads the outside gradient of a node's
+    // state from emb (where it later writes the state's full gradient) and the node's gate bytes,
+    // both by node id; a later forward sweep reads its input from xb in bucket order
+    const uint8_t *gates_in = BW ? P.mask4 + static_cast<size_t>(1 - dir) * gv.n_tot * H : nullptr;
+    uint8_t *gates_out = TR ? P.mask4 + static_cast<size_t>(dir) * gv.n_tot * H : nullptr;
     const float *xin = xb + static_cast<size_t>(n0) * H;
+    auto node_of = [&](const u32x4 &rec) __attribute__((always_inline)) {
+        const uint32_t id = rec[3] & kRecNoNode;
+        return n0 + static_cast<int>(id == kRecNoNode ? 0u : id);
+    };
     float *dlt = BW ? P.delta + static_cast<size_t>(1 - dir) * P.delta_stride
                     : (TR ? P.delta + static_cast<size_t>(dir) * P.delta_stride : nullptr);
     {
@@ -451,8 +469,13 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             } else {
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
-                    xs0[ct][t] = xin[static_cast<size_t>(p0 + rr) * H + wc0 + 16 * t + col];
-                    if constexpr (BW) mks0[ct][t] = mask4[static_cast<size_t>(p0 + rr) * H + wc0 + 16 * t + col];
+                    const int m = wc0 + 16 * t + col;
+                    if constexpr (BW) {
+                        xs0[ct][t] = P.emb[static_cast<uint32_t>(vg0[ct] * 2 * H + (1 - dir) * H + m)];
+                        mks0[ct][t] = gates_in[static_cast<uint32_t>(vg0[ct] * H + m)];
+                    } else {
+                        xs0[ct][t] = xin[static_cast<size_t>(p0 + rr) * H + m];
+                    }
                 }
             }
         }
@@ -479,6 +502,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         // column tiles (and of the co-resident workgroup) interleave, so a dependent matrix
         // instruction never waits for its predecessor.
         f32x4 acc[2][TPW];
+        int gate_bits[NT][TPW];   // (TR) ReLU gates of this chunk's rows, collected layer by layer
 
 #pragma unroll
         for (int n = 0; n < NL; ++n) {
@@ -565,8 +589,14 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     if constexpr (TR) {
                         const uint32_t d_row = live ? static_cast<uint32_t>(vg0[ct] * H + m)
                                                     : static_cast<uint32_t>(2 * L * gv.n_tot * H + m);
-                        if (n == 0) dlt[d_row] = gs0[ct][t];
-                        if (n < NL - 1) dlt[live ? static_cast<uint32_t>((1 + n) * gv.n_tot * H) + d_row : d_row] = y;
+                        // the output of g's last layer is only ever needed as a gate
+                        if (n < NL - 1 && n != L - 1)
+                            dlt[live ? static_cast<uint32_t>((1 + n) * gv.n_tot * H) + d_row : d_row] = y;
+                        const int bit = n == NL - 1 ? 1 : (n == L - 1 ? 4 : (n == 0 ? 8 : 2));
+                        gate_bits[ct][t] = (n == 0 ? 0 : gate_bits[ct][t]) | (y > 0.0f ? bit : 0);
+                        if (n == NL - 1)
+                            gates_out[live ? static_cast<uint32_t>(vg0[ct] * H + m)
+                                           : static_cast<uint32_t>((2 - dir) * gv.n_tot * H + m)] = static_cast<uint8_t>(gate_bits[ct][t]);
                     }
                     if (n == L - 1) {                    // end of g: residual update of s_v
                         y += FF ? x0[ct][t] : xC[ct][t];
@@ -638,9 +668,14 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         } else {
 #pragma unroll
                             for (int t = 0; t < TPW; ++t) {
-                                xN[ct][t] = (xin + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
-                                if constexpr (BW)
-                                    mN[ct][t] = (mask4 + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + wc0 + 16 * t + col)];
+                                const int m = wc0 + 16 * t + col;
+                                if constexpr (BW) {
+                                    const int v = node_of(rcA[ct]);
+                                    xN[ct][t] = P.emb[static_cast<uint32_t>(v * 2 * H + (1 - dir) * H + m)];
+                                    mN[ct][t] = gates_in[static_cast<uint32_t>(v * H + m)];
+                                } else {
+                                    xN[ct][t] = (xin + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + m)];
+                                }
                             }
                         }
                     }
@@ -786,14 +821,16 @@ bool sweep_mfma_supported(int H, int L, int weight_dtype)
 
 void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                        const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
-                       bool first_sweep, bool more_sweeps, float *keep, size_t keep_stride, hipStream_t s)
+                       bool first_sweep, bool more_sweeps, float *keep, size_t keep_stride, uint8_t *gates,
+                       hipStream_t s)
 {
     if (gv.B == 0) return;
-    // keep: where a single sweep also stores a_v and the layer outputs for the reverse pass (TR)
-    const bool tr = keep && first_sweep && !more_sweeps;
+    // keep, gates: where a single sweep also stores a_v, the layer outputs and the ReLU gates for the
+    // reverse pass (TR)
+    const bool tr = keep && gates && first_sweep && !more_sweeps;
     SweepParams P{gv, wfrag, bias, ws.emb, ws.xb, ws.msg, ws.reach, fa.cur_node,
-                  ws.featb, first_sweep ? mv.blob + mv.proj.w : nullptr, mv.D, nullptr, tr ? keep : nullptr,
-                  tr ? keep_stride : 0};
+                  ws.featb, first_sweep ? mv.blob + mv.proj.w : nullptr, mv.D, tr ? gates : nullptr,
+                  tr ? keep : nullptr, tr ? keep_stride : 0};
     if (first_sweep)
         hipLaunchKernelGGL(k_bucket_feats, dim3((gv.n_tot + 255) / 256), dim3(256), 0, s, gv, fa.node_feats,
                            fa.placement, fa.cur_node, mv.D, ws.featb);
@@ -820,14 +857,15 @@ void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace
 }
 
 // The reverse pass of one sweep in both directions (see BW at the kernel).  demb [n_tot + 1, 2H]
-// holds the outside gradient of every state on entry (also given in bucket order in extb) and the
-// gradient of the sweep's input on return; dagg [2 n_tot + 2, H] must have its row 2 n_tot zero.
+// holds the outside gradient of every state on entry and the gradient of the sweep's input on
+// return; mask4 the gate bytes of both sweep directions in node order; dagg [2 n_tot + 2, H] must
+// have its row 2 n_tot zero.
 void launch_sweep_mfma_bw(const GraphView &gv, const ModelView &mv, const uint4 *wfrag, const float *bias,
-                          int WS, const int32_t *cur_node, float *demb, float *extb, float *dagg,
-                          const uint8_t *mask4, float *delta, size_t delta_stride, hipStream_t s)
+                          int WS, const int32_t *cur_node, float *demb, float *dagg, uint8_t *mask4,
+                          float *delta, size_t delta_stride, hipStream_t s)
 {
     if (gv.B == 0) return;
-    SweepParams P{gv, wfrag, bias, demb, extb, dagg, nullptr, cur_node, nullptr, nullptr, mv.D,
+    SweepParams P{gv, wfrag, bias, demb, nullptr, dagg, nullptr, cur_node, nullptr, nullptr, mv.D,
                   mask4, delta, delta_stride};
     const dim3 grid(2 * gv.B);
 #define PL_CASE(HH, WW, LL)                                                                  \
