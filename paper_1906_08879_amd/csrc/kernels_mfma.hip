@@ -126,7 +126,13 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     constexpr int TPW = NTL / NW;              // output column tiles per wave
     constexpr int WC = 16 * TPW;               // columns owned by a wave
     constexpr int NL = 2 * L;                  // layers per chunk: g then f
-    constexpr int LDA = H + 8;                 // bf16 row stride of the activation buffers
+    // bf16 row stride of the activation buffers: H / 2 + 8 words.  Measured with
+    // SQ_LDS_BANK_CONFLICT on this chip: the ds_read_b128 of A rows (lane = row, 16-byte piece)
+    // then runs at its full rate of four cycles (a stride of H / 2 + 4 words takes eight), while
+    // the word stores of a tile's four nodes take four cycles instead of two; no skew of the rows
+    // tried (multiples of four words on rows 4..7 and 8..15) is free of conflicts for both.
+    constexpr int LDA = H + 16;
+    constexpr int kActTile = 16 * LDA;         // one 16-row tile
     constexpr int LDM = H + 16;                // float row stride of the message table (16 mod 64:
                                                // four consecutive rows fall on disjoint banks)
     constexpr int kZeroSlot = kMsgSlots;
@@ -139,7 +145,11 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     // the nodes it was computed from); sums take |x|.  A wave reads and writes only its own
     // columns, so the table needs no barrier.  The last row stays zero.
     __shared__ __attribute__((aligned(16))) float msgtab[(kMsgSlots + 1) * LDM];
-    __shared__ __attribute__((aligned(16))) __bf16 actbuf[2][NT * 16][LDA];
+    __shared__ __attribute__((aligned(16))) __bf16 actbuf[2][NT * kActTile];
+    // element (row r of the chunk's 16 NT rows, column k) of buffer `buf`
+    auto act_at = [&](int buf, int r, int k) __attribute__((always_inline)) {
+        return &actbuf[buf][r * LDA + k];
+    };
     __shared__ float proj_dev[(kMaxD + 1) * H];   // one-hot device rows of W_in, then a zero row
 
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
@@ -220,7 +230,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         return fmaxf(fmaf(ft[2], pw_vis[t], o), 0.0f);
     };
     for (int i = tid; i < (kMsgSlots + 1) * LDM; i += kThreads) msgtab[i] = 0.0f;
-    for (int i = tid; i < 2 * NT * 16 * LDA; i += kThreads) (&actbuf[0][0][0])[i] = static_cast<__bf16>(0.0f);
+    for (int i = tid; i < 2 * NT * kActTile; i += kThreads) (&actbuf[0][0])[i] = static_cast<__bf16>(0.0f);
 
     // Writes this lane's values of node row r, split exactly into three bf16 parts, as rows
     // 4 r .. 4 r + 2 of an A operand.  Two columns per lane travel as one word per part: word
@@ -234,12 +244,12 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             ll[t] = rr[t] - trunc_bf16(rr[t]);
         }
         if constexpr (TPW == 2) {
-            uint32_t *dst = reinterpret_cast<uint32_t *>(&actbuf[buf][4 * r][0]) + 16 * wave + col;
+            uint32_t *dst = reinterpret_cast<uint32_t *>(act_at(buf, 4 * r, 0)) + 16 * wave + col;
             dst[0] = pack_hi16(y[0], y[1]);
             dst[LDA / 2] = pack_hi16(rr[0], rr[1]);
             dst[LDA] = pack_hi16(ll[0], ll[1]);
         } else {
-            unsigned short *dst = reinterpret_cast<unsigned short *>(&actbuf[buf][4 * r][wc0 + col]);
+            unsigned short *dst = reinterpret_cast<unsigned short *>(act_at(buf, 4 * r, wc0 + col));
             dst[0] = static_cast<unsigned short>(__float_as_uint(y[0]) >> 16);
             dst[LDA] = static_cast<unsigned short>(__float_as_uint(rr[0]) >> 16);
             dst[2 * LDA] = static_cast<unsigned short>(__float_as_uint(ll[0]) >> 16);
@@ -513,7 +523,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             auto read_one_tile = [&]() __attribute__((always_inline)) {
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
-                    a1[ks] = *reinterpret_cast<const bf16x8 *>(&actbuf[n & 1][col][32 * ks + 8 * kg]);
+                    a1[ks] = *reinterpret_cast<const bf16x8 *>(act_at(n & 1, col, 32 * ks + 8 * kg));
             };
             auto mfma_one_tile = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -533,7 +543,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
 #pragma unroll
                     for (int ct = 0; ct < 2; ++ct) {
                         const bf16x8 a =
-                            *reinterpret_cast<const bf16x8 *>(&actbuf[n & 1][16 * ct + col][32 * ks + 8 * kg]);
+                            *reinterpret_cast<const bf16x8 *>(act_at(n & 1, 16 * ct + col, 32 * ks + 8 * kg));
 #pragma unroll
                         for (int t = 0; t < TPW; ++t)
 #pragma unroll

@@ -136,7 +136,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_tiles(PoolParams P)
     constexpr int KS1 = K1 / 32, KS2 = H / 32;
     constexpr int NTL = H / 16;                  // output column tiles
     constexpr int TPW = (NTL + 3) / 4;           // column tiles per wave
-    constexpr int LD1 = K1 + 8, LD2 = H + 8;     // bf16 row strides
+    // bf16 row strides: K / 2 + 8 words.  Measured on this chip (SQ_LDS_BANK_CONFLICT): a
+    // ds_read_b128 of A rows then runs at its full rate of four cycles (K / 2 + 4 words: eight).
+    constexpr int LD1 = K1 + 16, LD2 = H + 16;
     constexpr int QPR = K1 / 4;                  // float4 per embedding row
     constexpr int NLD = kBatch * QPR / kThreads; // float4 loads per thread and tile
     static_assert(kBatch * QPR % kThreads == 0, "tile rows must divide over the threads");
@@ -144,7 +146,10 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_tiles(PoolParams P)
 
     // [part][node][k] bf16 parts of the input rows and of the layer-1 outputs
     __shared__ __attribute__((aligned(16))) __bf16 act1[2][3][kBatch][LD1];   // two tiles: one is read while the next is written
-    __shared__ __attribute__((aligned(16))) __bf16 act2[L > 1 ? 3 : 1][kBatch][LD2];
+    __shared__ __attribute__((aligned(16))) __bf16 act2[L > 1 ? 3 : 1][kBatch * LD2];
+    auto act2_at = [&](int part, int node, int k) __attribute__((always_inline)) {
+        return &act2[part][node * LD2 + k];
+    };
     __shared__ int tile_node[8][kBatch];     // node ids of the tiles t - 1 .. t + 4 (slot = tile & 7)
 
     const int set = blockIdx.x, slice = blockIdx.y, b = blockIdx.z;
@@ -371,15 +376,14 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_tiles(PoolParams P)
                     }
                     if constexpr (TPW == 2) {
                         // word 16 wave + col of a row: columns 32 wave + col and 32 wave + 16 + col
-                        uint32_t *w0 = reinterpret_cast<uint32_t *>(&act2[0][node][0]) + 16 * wave + col;
-                        w0[0] = pack_hi16(y[0], y[1]);
-                        w0[kBatch * LD2 / 2] = pack_hi16(r[0], r[1]);
-                        w0[2 * (kBatch * LD2 / 2)] = pack_hi16(l[0], l[1]);
+                        reinterpret_cast<uint32_t *>(act2_at(0, node, 0))[16 * wave + col] = pack_hi16(y[0], y[1]);
+                        reinterpret_cast<uint32_t *>(act2_at(1, node, 0))[16 * wave + col] = pack_hi16(r[0], r[1]);
+                        reinterpret_cast<uint32_t *>(act2_at(2, node, 0))[16 * wave + col] = pack_hi16(l[0], l[1]);
                     } else {
                         const int c = 16 * wave + col;
-                        reinterpret_cast<unsigned short *>(&act2[0][node][c])[0] = static_cast<unsigned short>(__float_as_uint(y[0]) >> 16);
-                        reinterpret_cast<unsigned short *>(&act2[1][node][c])[0] = static_cast<unsigned short>(__float_as_uint(r[0]) >> 16);
-                        reinterpret_cast<unsigned short *>(&act2[2][node][c])[0] = static_cast<unsigned short>(__float_as_uint(l[0]) >> 16);
+                        reinterpret_cast<unsigned short *>(act2_at(0, node, c))[0] = static_cast<unsigned short>(__float_as_uint(y[0]) >> 16);
+                        reinterpret_cast<unsigned short *>(act2_at(1, node, c))[0] = static_cast<unsigned short>(__float_as_uint(r[0]) >> 16);
+                        reinterpret_cast<unsigned short *>(act2_at(2, node, c))[0] = static_cast<unsigned short>(__float_as_uint(l[0]) >> 16);
                     }
                 }
             }
@@ -394,14 +398,14 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_tiles(PoolParams P)
 #pragma unroll
                 for (int ks = 0; ks < kAhead && ks < KS2; ++ks)
 #pragma unroll
-                    for (int p = 0; p < 3; ++p) a[ks][p] = *reinterpret_cast<const bf16x8 *>(&act2[p][col][32 * ks + 8 * kg]);
+                    for (int p = 0; p < 3; ++p) a[ks][p] = *reinterpret_cast<const bf16x8 *>(act2_at(p, col, 32 * ks + 8 * kg));
 #pragma unroll
                 for (int ks = 0; ks < KS2; ++ks) {
                     if (ks + kAhead < KS2) {
 #pragma unroll
                         for (int p = 0; p < 3; ++p)
                             a[(ks + kAhead) % (kAhead + 1)][p] =
-                                *reinterpret_cast<const bf16x8 *>(&act2[p][col][32 * (ks + kAhead) + 8 * kg]);
+                                *reinterpret_cast<const bf16x8 *>(act2_at(p, col, 32 * (ks + kAhead) + 8 * kg));
                     }
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
