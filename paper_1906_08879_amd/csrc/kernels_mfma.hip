@@ -151,6 +151,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         return &actbuf[buf][r * LDA + k];
     };
     __shared__ float proj_dev[(kMaxD + 1) * H];   // one-hot device rows of W_in, then a zero row
+    __shared__ float proj_row[TR ? 5 * H : 1];    // (TR) the other rows of W_in and its bias
 
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -200,16 +201,29 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     // ---- input projection (Section 2.2 step 1), one output column per lane and tile:
     // x = relu(b + time w0 + size w1 + w[2 + device] + is_current w[2 + D] + visited w[3 + D])
     const int D = P.D;
+    // The five rows of W_in that do not depend on the device stay in registers, except in the
+    // variant that keeps activations, which has no registers to spare: it reads them from LDS.
+    constexpr bool kProjLds = TR;
     float pw_time[TPW], pw_size[TPW], pw_cur[TPW], pw_vis[TPW], pw_b[TPW];
     if constexpr (FF) {
+        if constexpr (kProjLds) {
+            for (int i = tid; i < H; i += kThreads) {
+                proj_row[0 * H + i] = P.proj[i];
+                proj_row[1 * H + i] = P.proj[H + i];
+                proj_row[2 * H + i] = P.proj[(2 + D) * H + i];
+                proj_row[3 * H + i] = P.proj[(3 + D) * H + i];
+                proj_row[4 * H + i] = P.proj[(4 + D) * H + i];
+            }
+        } else {
 #pragma unroll
-        for (int t = 0; t < TPW; ++t) {
-            const int m = wc0 + 16 * t + col;
-            pw_time[t] = P.proj[m];
-            pw_size[t] = P.proj[H + m];
-            pw_cur[t] = P.proj[(2 + D) * H + m];
-            pw_vis[t] = P.proj[(3 + D) * H + m];
-            pw_b[t] = P.proj[(4 + D) * H + m];
+            for (int t = 0; t < TPW; ++t) {
+                const int m = wc0 + 16 * t + col;
+                pw_time[t] = P.proj[m];
+                pw_size[t] = P.proj[H + m];
+                pw_cur[t] = P.proj[(2 + D) * H + m];
+                pw_vis[t] = P.proj[(3 + D) * H + m];
+                pw_b[t] = P.proj[(4 + D) * H + m];
+            }
         }
         for (int i = tid; i < (kMaxD + 1) * H; i += kThreads)
             proj_dev[i] = (i < D * H) ? P.proj[2 * H + i] : 0.0f;
@@ -222,12 +236,15 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     };
     auto project = [&](const f32x4 ft, float dev_term, int t) __attribute__((always_inline)) {
         const int bits = __float_as_int(ft[3]);
-        float o = pw_b[t];
-        o = fmaf(ft[0], pw_time[t], o);
-        o = fmaf(ft[1], pw_size[t], o);
+        const int m = wc0 + 16 * t + col;
+        const float w_time = kProjLds ? proj_row[0 * H + m] : pw_time[t], w_size = kProjLds ? proj_row[1 * H + m] : pw_size[t];
+        const float w_cur = kProjLds ? proj_row[2 * H + m] : pw_cur[t], w_vis = kProjLds ? proj_row[3 * H + m] : pw_vis[t];
+        float o = kProjLds ? proj_row[4 * H + m] : pw_b[t];
+        o = fmaf(ft[0], w_time, o);
+        o = fmaf(ft[1], w_size, o);
         o += dev_term;
-        o += (bits >> 16) ? pw_cur[t] : 0.0f;
-        return fmaxf(fmaf(ft[2], pw_vis[t], o), 0.0f);
+        o += (bits >> 16) ? w_cur : 0.0f;
+        return fmaxf(fmaf(ft[2], w_vis, o), 0.0f);
     };
     for (int i = tid; i < (kMsgSlots + 1) * LDM; i += kThreads) msgtab[i] = 0.0f;
     for (int i = tid; i < 2 * NT * kActTile; i += kThreads) (&actbuf[0][0])[i] = static_cast<__bf16>(0.0f);
