@@ -45,7 +45,7 @@ def assert_grad_close(got, ref, w, what):
         n_in, n_out = shapes[name]
         e2 = np.abs(got[ws] - ref[ws]).reshape(n_in, n_out).max(axis=0)
         col = np.abs(ref[ws]).reshape(n_in, n_out).max(axis=0)
-        b2 = GRAD_RTOL * col + GRAD_ATOL_UNIT * gmax
+        b2 = np.maximum(GRAD_RTOL * col + GRAD_ATOL_UNIT * gmax, 1e-300)
         j = int(np.argmax(e2 / b2))
         worst = max(worst, float(e2[j] / b2[j]))
         assert e2[j] <= b2[j], f"{what}: layer {name}, output unit {j}: error {e2[j]:.3g} > {b2[j]:.3g} (column max {col[j]:.3g})"
