@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kThreads) void k_bw_head(GraphView gv, ModelView mv
     __shared__ float dpre[kMaxH];
     __shared__ float logit[kMaxD];
     __shared__ float dlog[kMaxD];
-    const int H = mv.H, D = mv.D, Z = mv.Z, b = blockIdx.x, tid = threadIdx.x;
+    const int H = mv.H, D = mv.D, b = blockIdx.x, tid = threadIdx.x;
     const int n_b = gv.node_off[b + 1] - gv.node_off[b];
     const int cl = cur_node[b];
     const bool cur_ok = cl >= 0 && cl < n_b;
@@ -153,13 +153,48 @@ __global__ __launch_bounds__(kThreads) void k_bw_head(GraphView gv, ModelView mv
         dpre_out[static_cast<size_t>(b) * H + j] = dp;
     }
     if (tid < D) dlogit_out[static_cast<size_t>(b) * D + tid] = dlog[tid];
-    __syncthreads();
-    const float *W1t = blob_t + mv.pol1.w;   // [H][Z]
-    for (int k = tid; k < Z; k += kThreads) {
-        float s = 0.0f;
-        for (int j = 0; j < H; ++j) s = fmaf(W1t[static_cast<size_t>(j) * Z + k], dpre[j], s);
-        dz[static_cast<size_t>(b) * Z + k] = s;
+}
+
+// dz[b][k] = sum_j W1[k][j] dpre[b][j] for kDzGraphs graphs per workgroup and one 256-wide slice of
+// the policy input: a weight is loaded once for all the workgroup's graphs (one workgroup per graph
+// read the whole first policy layer, 1.7 MB at the NASNet-like shape, from L2 every time).
+constexpr int kDzGraphs = 8;
+__global__ __launch_bounds__(kThreads) void k_bw_dz(ModelView mv, int B, const float *__restrict__ blob_t,
+                                                    const float *__restrict__ dpre, float *__restrict__ dz)
+{
+    __shared__ float dp[kDzGraphs][kMaxH];
+    const int H = mv.H, Z = mv.Z, tid = threadIdx.x;
+    const int k = blockIdx.x * kThreads + tid, b0 = blockIdx.y * kDzGraphs;
+    const int nb = min(kDzGraphs, B - b0);
+    for (int i = tid; i < kDzGraphs * H; i += kThreads) {
+        const int g = i / H, j = i - g * H;
+        dp[g][j] = g < nb ? dpre[static_cast<size_t>(b0 + g) * H + j] : 0.0f;
     }
+    __syncthreads();
+    if (k >= Z) return;
+    const float *W1t = blob_t + mv.pol1.w;   // [H][Z]
+    float acc[kDzGraphs];
+#pragma unroll
+    for (int g = 0; g < kDzGraphs; ++g) acc[g] = 0.0f;
+    constexpr int KB = 16;                   // weights per batch of loads
+    int j = 0;
+    for (; j + KB <= H; j += KB) {
+        float w[KB];
+#pragma unroll
+        for (int u = 0; u < KB; ++u) w[u] = W1t[static_cast<size_t>(j + u) * Z + k];
+#pragma unroll
+        for (int u = 0; u < KB; ++u)
+#pragma unroll
+            for (int g = 0; g < kDzGraphs; ++g) acc[g] = fmaf(w[u], dp[g][j + u], acc[g]);
+    }
+    for (; j < H; ++j) {
+        const float w = W1t[static_cast<size_t>(j) * Z + k];
+#pragma unroll
+        for (int g = 0; g < kDzGraphs; ++g) acc[g] = fmaf(w, dp[g][j], acc[g]);
+    }
+#pragma unroll
+    for (int g = 0; g < kDzGraphs; ++g)
+        if (g < nb) dz[static_cast<size_t>(b0 + g) * Z + k] = acc[g];
 }
 
 // Workgroup (set, graph): q[set][d] = h_set(P[set][d]) again for the G device groups, keeping
@@ -1647,6 +1682,8 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
     hipLaunchKernelGGL(k_bw_head, dim3(B), dim3(kThreads), 0, s, gv, mv, blob_t, ws.hidp, n_slices, fa.cur_node,
                        ba.actions, ba.coeff, ba.entropy_coeff, ba.out_entropy, gw.hid, gw.dpre, gw.dlogit, gw.dz,
                        ba.out_logp);
+    hipLaunchKernelGGL(k_bw_dz, dim3((mv.Z + kThreads - 1) / kThreads, (B + kDzGraphs - 1) / kDzGraphs), dim3(kThreads),
+                       0, s, mv, B, blob_t, gw.dpre, gw.dz);
     {
         const size_t lds = sizeof(float) * 3 * kTile * H;
 #define CALL(R)                                                                                          \
