@@ -32,7 +32,7 @@ Readings where the paper is silent:
    rounding per operation: the event order is an integer decision taken in this precision
    on both sides, so the two timelines are identical event by event;
  * peak memory (the paper only says that the start and end timestamps of the operations and the
-   tensor sizes are used to predict it; the model below is this build's reading): the output of
+   tensor sizes are used to predict it; the model below is the reading taken here): the output of
    an operation occupies its own device from the operation's START until the latest of its own
    end, the end of its last consumer on that device and the arrival of its last outgoing
    transfer; on every other device that consumes it, a copy lives from the transfer's arrival
