@@ -139,6 +139,21 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     static_assert(NTL % NW == 0, "column tiles must divide over the waves");
     static_assert(TPW == 1 || TPW == 2, "a lane owns one or two output columns");
     constexpr bool kReadFirst = TPW == 1;
+#ifndef PL_SINK_STORES
+#define PL_SINK_STORES 0
+#endif
+    constexpr bool kSinkStores = PL_SINK_STORES;
+#ifndef PL_UNCOND_T1
+#define PL_UNCOND_T1 0
+#endif
+    // What a later chunk's second row tile needs is loaded whether or not that chunk has one
+    // (its records then name the all-zero rows): no branch splits the code of a layer.  The
+    // reverse pass, which loads four values per row and column tile, keeps the test.
+    constexpr bool kLoadTile1Always = PL_UNCOND_T1;
+#ifndef PL_SPLIT_KINDS
+#define PL_SPLIT_KINDS (!BW)
+#endif
+    constexpr bool kSplitKinds = PL_SPLIT_KINDS;
 
     // Message table: H floats per row.  Messages are ReLU outputs, so their sign bit is free:
     // it carries the reachability flag of the row's node (set if the node is v* or has v* among
@@ -152,6 +167,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     };
     __shared__ float proj_dev[(kMaxD + 1) * H];   // one-hot device rows of W_in, then a zero row
     __shared__ float proj_row[TR ? 5 * H : 1];    // (TR) the other rows of W_in and its bias
+    __shared__ float bias_row[TR ? 2 * L * H : 1];   // (TR) the layers' biases
 
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -179,8 +195,12 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     const int sink_row = spare_row + 1;
 
     // ---- weights of this direction into registers (B operand: lane holds column 16 nt + col)
+    // The variant that keeps activations has no registers for the biases: it reads them from LDS.
+    constexpr bool kBiasLds = TR;
     bf16x8 W[NL][TPW][KS][WS];
     float bias[NL][TPW];
+    if constexpr (kBiasLds)
+        for (int i = tid; i < NL * H; i += kThreads) bias_row[i] = P.bias[static_cast<size_t>(dir) * NL * H + i];
 #pragma unroll
     for (int n = 0; n < NL; ++n)
 #pragma unroll
@@ -195,7 +215,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     const uint4 raw = P.wfrag[at];
                     W[n][t][ks][ws] = *reinterpret_cast<const bf16x8 *>(&raw);
                 }
-            bias[n][t] = P.bias[(static_cast<size_t>(dir) * NL + n) * H + nt * 16 + col];
+            if constexpr (!kBiasLds) bias[n][t] = P.bias[(static_cast<size_t>(dir) * NL + n) * H + nt * 16 + col];
         }
 
     // ---- input projection (Section 2.2 step 1), one output column per lane and tile:
@@ -514,11 +534,13 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     // rB / rC: records of chunk c + 2 / target of chunk c + 3's; fC / fN: feature records of chunk
     // c / target of chunk c + 1's; xC, mC / xN, mN: the same for residual inputs and gate bytes;
     // farA / farB: far messages of chunk c + 1 / target of chunk c + 2's
-    auto step = [&](int c, u32x4 (&rB)[NT], u32x4 (&rC)[NT], f32x4 (&fC)[NT], f32x4 (&fN)[NT],
+    auto step = [&](auto twoc, int c, u32x4 (&rB)[NT], u32x4 (&rC)[NT], f32x4 (&fC)[NT], f32x4 (&fN)[NT],
                     float (&xC)[NT][TPW], float (&xN)[NT][TPW], int (&mC)[NT][TPW], int (&mN)[NT][TPW],
                     float (&farA)[NT][TPW], float (&farB)[NT][TPW]) __attribute__((always_inline)) {
         const int rows = rows0;
-        const bool two = rows > kTileNodes;      // the chunk fills a second row tile
+        // the chunk fills a second row tile: known when the code is compiled (kind 0 / 1), or not (-1)
+        constexpr int kind = decltype(twoc)::value;
+        const bool two = kind < 0 ? rows > kTileNodes : kind > 0;
         const bool has_next = c + 1 < c_end;
         const int ring = (c - c_begin) % RING;   // table rows ring * CH .. of this chunk's messages
         const uint32_t info1 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rcA[0][3])));
@@ -537,6 +559,9 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             // One row tile: the A fragments are read first (a1), the loads and stores of the
             // pipeline ("mid block") are issued while they travel, then the matrix instructions.
             bf16x8 a1[KS];
+            float bias_n[TPW];
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) bias_n[t] = kBiasLds ? bias_row[n * H + wc0 + 16 * t + col] : bias[n][t];
             auto read_one_tile = [&]() __attribute__((always_inline)) {
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
@@ -574,16 +599,20 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             // wc0 + 16 t + col, the three partial products in rows 0..2 of its accumulators.
             // Row tile 0 is handled by code common to both kinds of chunk, so that its stores
             // are on every path (see sink_row).
-            auto epilogue = [&](int ct) __attribute__((always_inline)) {
+            // `dead`: the row tile is beyond the chunk's rows (a chunk of one tile): nothing is
+            // computed for it, but its global stores are issued all the same (to the sink rows),
+            // so that both kinds of chunk leave the same number of stores behind every load.
+            auto epilogue = [&](int ct, auto deadc) __attribute__((always_inline)) {
+                constexpr bool dead = decltype(deadc)::value;
                 const int r = ct * kTileNodes + kg;
-                const bool live = r < rows;
+                const bool live = !dead && r < rows;
                 const int v_emb = live ? vg0[ct] : gv.n_tot;
                 const int v_msg = live ? vg0[ct] : sink_row;
                 float yv[TPW];
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
                     const int m = wc0 + 16 * t + col;
-                    float y = acc[ct][t][0] + acc[ct][t][1] + acc[ct][t][2];
+                    float y = dead ? 0.0f : acc[ct][t][0] + acc[ct][t][1] + acc[ct][t][2];
                     if constexpr (BW) {
                         // delta slot of this layer's gated output: f's layers L-2 .. 0, then g's
                         // layers L-1 .. 0; slot = index into the 2L delta arrays (f first)
@@ -592,27 +621,27 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         auto put_delta = [&](int slot, float val) __attribute__((always_inline)) {
                             dlt[live ? static_cast<uint32_t>(slot * gv.n_tot * H) + d_row : d_row] = val;
                         };
-                        if (n == 0) put_delta(L - 1, gs0[ct][t]);
+                        if (n == 0) put_delta(L - 1, dead ? 0.0f : gs0[ct][t]);
                         if (n == L - 1) {                // end of f^T: ds_v = outside gradient + f path
-                            y += FF ? x0[ct][t] : xC[ct][t];
+                            if constexpr (!dead) y += FF ? x0[ct][t] : xC[ct][t];
                             P.emb[static_cast<uint32_t>(v_emb * 2 * H + (1 - dir) * H + m)] = y;
-                            y = (mC[ct][t] & 4) ? y : 0.0f;
+                            if constexpr (!dead) y = (mC[ct][t] & 4) ? y : 0.0f;
                             put_delta(L + L - 1, y);
                         } else if (n < L - 1) {
-                            y = (mC[ct][t] & 2) ? y : 0.0f;
+                            if constexpr (!dead) y = (mC[ct][t] & 2) ? y : 0.0f;
                             put_delta(L - 2 - n, y);
                         } else if (n < NL - 1) {
-                            y = (mC[ct][t] & 8) ? y : 0.0f;
+                            if constexpr (!dead) y = (mC[ct][t] & 8) ? y : 0.0f;
                             put_delta(L + NL - 2 - n, y);
                         }
                         if (n == NL - 1) {               // end of g^T: da_v
                             msg[static_cast<uint32_t>(v_msg * H + m)] = y;
-                            msgtab[(ring * CH + r) * LDM + m] = y;
+                            if constexpr (!dead) msgtab[(ring * CH + r) * LDM + m] = y;
                         }
                         yv[t] = y;
                         continue;
                     }
-                    y = fmaxf(y + bias[n][t], 0.0f);
+                    if constexpr (!dead) y = fmaxf(y + bias_n[t], 0.0f);
                     if constexpr (TR) {
                         const uint32_t d_row = live ? static_cast<uint32_t>(vg0[ct] * H + m)
                                                     : static_cast<uint32_t>(2 * L * gv.n_tot * H + m);
@@ -620,25 +649,28 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         if (n < NL - 1 && n != L - 1)
                             dlt[live ? static_cast<uint32_t>((1 + n) * gv.n_tot * H) + d_row : d_row] = y;
                         const int bit = n == NL - 1 ? 1 : (n == L - 1 ? 4 : (n == 0 ? 8 : 2));
-                        gate_bits[ct][t] = (n == 0 ? 0 : gate_bits[ct][t]) | (y > 0.0f ? bit : 0);
+                        if constexpr (!dead) gate_bits[ct][t] = (n == 0 ? 0 : gate_bits[ct][t]) | (y > 0.0f ? bit : 0);
                         if (n == NL - 1)
                             gates_out[live ? static_cast<uint32_t>(vg0[ct] * H + m)
-                                           : static_cast<uint32_t>((2 - dir) * gv.n_tot * H + m)] = static_cast<uint8_t>(gate_bits[ct][t]);
+                                           : static_cast<uint32_t>((2 - dir) * gv.n_tot * H + m)] =
+                                dead ? static_cast<uint8_t>(0) : static_cast<uint8_t>(gate_bits[ct][t]);
                     }
                     if (n == L - 1) {                    // end of g: residual update of s_v
-                        y += FF ? x0[ct][t] : xC[ct][t];
+                        if constexpr (!dead) y += FF ? x0[ct][t] : xC[ct][t];
                         P.emb[static_cast<uint32_t>(v_emb * 2 * H + dir * H + m)] = y;
                         if constexpr (WX) xb[static_cast<uint32_t>((live ? n0 + p0 + r : spare_row) * H + m)] = y;
                     }
                     if (n == NL - 1) {                   // end of f: the message of v, flagged
-                        const uint32_t flag = (bit0[ct] | (vg0[ct] == cur)) ? 0x80000000u : 0u;
+                        const uint32_t flag = (!dead && (bit0[ct] | (vg0[ct] == cur))) ? 0x80000000u : 0u;
                         const float flagged = __uint_as_float(__float_as_uint(y) | flag);
                         msg[static_cast<uint32_t>(v_msg * H + m)] = flagged;
-                        msgtab[(ring * CH + r) * LDM + m] = flagged;
+                        if constexpr (!dead) msgtab[(ring * CH + r) * LDM + m] = flagged;
                     }
                     yv[t] = y;
                 }
-                if (n < NL - 1) put_rows((n + 1) & 1, r, yv);
+                if constexpr (!dead) {
+                    if (n < NL - 1) put_rows((n + 1) & 1, r, yv);
+                }
             };
 
             // The loads and stores of the pipeline (the "mid block" below) are issued while the A
@@ -651,7 +683,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     // a far source reads the row of zeros.  The messages were stored by this wave
                     // at least kRing - 1 chunks ago; see the note at the top of the file.
                     const uint32_t info2 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rB[0][3])));
-                    const bool two2 = rows_of(info2) > kTileNodes;
+                    const bool two2 = kLoadTile1Always || rows_of(info2) > kTileNodes;
                     float dterm[NT][TPW];
                     if constexpr (FF) {
 #pragma unroll
@@ -683,7 +715,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 if (n == (NL > 2 ? 1 : 0)) {
                     // second layer: the records of chunk c + 3 and
                     // the inputs of chunk c + 1
-                    const bool two1 = rows1 > kTileNodes;
+                    const bool two1 = kLoadTile1Always || rows1 > kTileNodes;
 #pragma unroll
                     for (int ct = 0; ct < NT; ++ct) {
                         rC[ct] = load_rec(c + 3, ct);
@@ -741,8 +773,11 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 mid_block();
             }
 
-            epilogue(0);
-            if (two) epilogue(1);
+            epilogue(0, std::false_type{});
+            if constexpr (kind == 0 && kSinkStores)
+                epilogue(1, std::true_type{});
+            else if (two)
+                epilogue(1, std::false_type{});
 
             // The table rows that chunk c + 1 sums were all written by this wave (its own
             // columns), so its gather follows without a barrier.
@@ -759,9 +794,30 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             rcA[ct] = rB[ct];       // arrived: its far ids were used behind this chunk's first layer
         }
     };
+    // Both kinds of chunk (one row tile, two) are compiled as straight-line code of their own.
+    // Nothing loaded before the loop is still in flight when it starts: the waits inside the loop
+    // are then counted from the loop's own loads and stores alone (a load issued just before the
+    // loop would otherwise make every iteration wait for all but its newest memory operation).
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    using one_tile = std::integral_constant<int, 0>;
+    using two_tiles = std::integral_constant<int, 1>;
+    using either = std::integral_constant<int, -1>;
     for (int c = c_begin; c < c_end; c += 2) {
-        step(c, rcX0, rcX1, ftp0, ftp1, xs0, xs1, mks0, mks1, farp0, farp1);
-        if (c + 1 < c_end) step(c + 1, rcX1, rcX0, ftp1, ftp0, xs1, xs0, mks1, mks0, farp1, farp0);
+        if constexpr (!kSplitKinds) {
+            step(either{}, c, rcX0, rcX1, ftp0, ftp1, xs0, xs1, mks0, mks1, farp0, farp1);
+            if (c + 1 < c_end) step(either{}, c + 1, rcX1, rcX0, ftp1, ftp0, xs1, xs0, mks1, mks0, farp1, farp0);
+            continue;
+        }
+        if (rows0 > kTileNodes)
+            step(two_tiles{}, c, rcX0, rcX1, ftp0, ftp1, xs0, xs1, mks0, mks1, farp0, farp1);
+        else
+            step(one_tile{}, c, rcX0, rcX1, ftp0, ftp1, xs0, xs1, mks0, mks1, farp0, farp1);
+        if (c + 1 < c_end) {
+            if (rows0 > kTileNodes)
+                step(two_tiles{}, c + 1, rcX1, rcX0, ftp1, ftp0, xs1, xs0, mks1, mks0, farp1, farp0);
+            else
+                step(one_tile{}, c + 1, rcX1, rcX0, ftp1, ftp0, xs1, xs0, mks1, mks0, farp1, farp0);
+        }
     }
 }
 
