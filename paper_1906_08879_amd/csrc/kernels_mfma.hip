@@ -13,10 +13,10 @@
 //     matrix cores without any cross-lane traffic.
 //   * The weight fragments of all layers of one direction live in registers for the whole
 //     kernel (bf16 weights: 128 VGPRs per wave at H = 128); only activations move through LDS.
-//     A lane that owns two output columns writes them as ONE 32-bit word per bf16 part: the
-//     contraction index of the next layer is permuted accordingly (columns c and c + 16 of a
-//     wave are neighbours in A), so an activation row is exchanged with three conflict-free
-//     word stores per lane instead of six half-word stores.
+//     A lane that owns two output columns owns NEIGHBOURS (a wave's two column tiles hold the
+//     even and the odd columns of its 32): it writes them as ONE 32-bit word per bf16 part (three
+//     conflict-free word stores per lane and row instead of six half-word stores), and reads or
+//     writes them in HBM and in the message table with one 8-byte access.
 //   * A wave owns its output columns from end to end: it writes its columns of a message into
 //     an LDS table that holds the last kRing chunks ("near" sources), reads its columns of
 //     older messages ("far" sources) back from HBM straight into the registers that sum them,
@@ -154,6 +154,10 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
 #define PL_SPLIT_KINDS (!BW)
 #endif
     constexpr bool kSplitKinds = PL_SPLIT_KINDS;
+    // A forward sweep writes what the next layer waits for to LDS before it stores to HBM; the
+    // variants that keep activations or feed another sweep have no registers to hold the values
+    // meanwhile.
+    constexpr bool kLdsFirst = !BW && !TR && !WX;
 
     // Message table: H floats per row.  Messages are ReLU outputs, so their sign bit is free:
     // it carries the reachability flag of the row's node (set if the node is v* or has v* among
@@ -167,12 +171,48 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     };
     __shared__ float proj_dev[(kMaxD + 1) * H];   // one-hot device rows of W_in, then a zero row
     __shared__ float proj_row[TR ? 5 * H : 1];    // (TR) the other rows of W_in and its bias
-    __shared__ float bias_row[TR ? 2 * L * H : 1];   // (TR) the layers' biases
+    __shared__ float bias_row[(TR || (FF && WX)) ? 2 * L * H : 1];   // the layers' biases, for the variants short of registers
 
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, kg = lane >> 4;    // MFMA result: column col, node kg of a tile
     const int wc0 = wave * WC;
+    // Output column of this lane in the wave's column tile t.  Where a wave owns two tiles they
+    // interleave (tile 0 the even, tile 1 the odd columns of the wave's 32), so that a lane's two
+    // columns are neighbours: one 8-byte access per lane wherever a row is read or written.
+    auto mcol = [&](int t) __attribute__((always_inline)) { return wc0 + (TPW == 2 ? 2 * col + t : col); };
+    // this lane's columns of a row of floats that starts at element `at`
+    auto load_cols = [&](const float *base, uint32_t at, float (&v)[TPW]) __attribute__((always_inline)) {
+        if constexpr (TPW == 2) {
+            const float2 x = *reinterpret_cast<const float2 *>(base + static_cast<uint32_t>(at + mcol(0)));
+            v[0] = x.x;
+            v[1] = x.y;
+        } else {
+            v[0] = base[static_cast<uint32_t>(at + mcol(0))];
+        }
+    };
+    // the same for rows of gate bytes
+    auto load_gates = [&](const uint8_t *base, uint32_t at, int (&v)[TPW]) __attribute__((always_inline)) {
+        if constexpr (TPW == 2) {
+            const int x = *reinterpret_cast<const uint16_t *>(base + static_cast<uint32_t>(at + mcol(0)));
+            v[0] = x & 0xFF;
+            v[1] = x >> 8;
+        } else {
+            v[0] = base[static_cast<uint32_t>(at + mcol(0))];
+        }
+    };
+    auto store_gates = [&](uint8_t *base, uint32_t at, const int (&v)[TPW]) __attribute__((always_inline)) {
+        if constexpr (TPW == 2)
+            *reinterpret_cast<uint16_t *>(base + static_cast<uint32_t>(at + mcol(0))) = static_cast<uint16_t>(v[0] | (v[1] << 8));
+        else
+            base[static_cast<uint32_t>(at + mcol(0))] = static_cast<uint8_t>(v[0]);
+    };
+    auto store_cols = [&](float *base, uint32_t at, const float (&v)[TPW]) __attribute__((always_inline)) {
+        if constexpr (TPW == 2)
+            *reinterpret_cast<float2 *>(base + static_cast<uint32_t>(at + mcol(0))) = float2{v[0], v[1]};
+        else
+            base[static_cast<uint32_t>(at + mcol(0))] = v[0];
+    };
 
     const GraphView &gv = P.gv;
     const SweepPlanView plan = gv.plan[dir];
@@ -195,8 +235,9 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     const int sink_row = spare_row + 1;
 
     // ---- weights of this direction into registers (B operand: lane holds column 16 nt + col)
-    // The variant that keeps activations has no registers for the biases: it reads them from LDS.
-    constexpr bool kBiasLds = TR;
+    // The variants that keep activations, or compute the projection and feed another sweep, have
+    // no registers for the biases: they read them from LDS.
+    constexpr bool kBiasLds = TR || (FF && WX);
     bf16x8 W[NL][TPW][KS][WS];
     float bias[NL][TPW];
     if constexpr (kBiasLds)
@@ -215,7 +256,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     const uint4 raw = P.wfrag[at];
                     W[n][t][ks][ws] = *reinterpret_cast<const bf16x8 *>(&raw);
                 }
-            if constexpr (!kBiasLds) bias[n][t] = P.bias[(static_cast<size_t>(dir) * NL + n) * H + nt * 16 + col];
+            if constexpr (!kBiasLds) bias[n][t] = P.bias[(static_cast<size_t>(dir) * NL + n) * H + mcol(t)];
         }
 
     // ---- input projection (Section 2.2 step 1), one output column per lane and tile:
@@ -237,7 +278,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         } else {
 #pragma unroll
             for (int t = 0; t < TPW; ++t) {
-                const int m = wc0 + 16 * t + col;
+                const int m = mcol(t);
                 pw_time[t] = P.proj[m];
                 pw_size[t] = P.proj[H + m];
                 pw_cur[t] = P.proj[(2 + D) * H + m];
@@ -252,11 +293,11 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     // the device's row of W_in comes from LDS: read early (device_term), used late (project)
     auto device_term = [&](const f32x4 ft, int t) __attribute__((always_inline)) {
         const int dev = __float_as_int(ft[3]) & 0xFFFF;
-        return proj_dev[(dev < D ? dev : D) * H + wc0 + 16 * t + col];
+        return proj_dev[(dev < D ? dev : D) * H + mcol(t)];
     };
     auto project = [&](const f32x4 ft, float dev_term, int t) __attribute__((always_inline)) {
         const int bits = __float_as_int(ft[3]);
-        const int m = wc0 + 16 * t + col;
+        const int m = mcol(t);
         const float w_time = kProjLds ? proj_row[0 * H + m] : pw_time[t], w_size = kProjLds ? proj_row[1 * H + m] : pw_size[t];
         const float w_cur = kProjLds ? proj_row[2 * H + m] : pw_cur[t], w_vis = kProjLds ? proj_row[3 * H + m] : pw_vis[t];
         float o = kProjLds ? proj_row[4 * H + m] : pw_b[t];
@@ -271,8 +312,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
 
     // Writes this lane's values of node row r, split exactly into three bf16 parts, as rows
     // 4 r .. 4 r + 2 of an A operand.  Two columns per lane travel as one word per part: word
-    // 16 wave + col of a row holds columns wc0 + col (low half) and wc0 + 16 + col (high half),
-    // which is the order in which pack_sweep_weights lays out the contraction index.
+    // 16 wave + col of a row holds columns wc0 + 2 col (low half) and wc0 + 2 col + 1 (high half),
+    // so the rows are in the natural order of the contraction index.
     auto put_rows = [&](int buf, int r, const float (&y)[TPW]) __attribute__((always_inline)) {
         float rr[TPW], ll[TPW];
 #pragma unroll
@@ -308,13 +349,12 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 s[t] = (mk[ct][t] & 1) ? s[t] : 0.0f;
                 gs[ct][t] = s[t];
             }
-            if constexpr (TR) {
-                const uint32_t id = w3 & kRecNoNode;
-                const int m = wc0 + 16 * t + col;
-                float *kept = P.delta + static_cast<size_t>(dir) * P.delta_stride;
-                kept[id == kRecNoNode ? static_cast<uint32_t>(2 * L * gv.n_tot * H + m)
-                                      : static_cast<uint32_t>((n0 + static_cast<int>(id)) * H + m)] = s[t];
-            }
+        }
+        if constexpr (TR) {
+            const uint32_t id = w3 & kRecNoNode;
+            float *kept = P.delta + static_cast<size_t>(dir) * P.delta_stride;
+            store_cols(kept, id == kRecNoNode ? static_cast<uint32_t>(2 * L * gv.n_tot * H)
+                                              : static_cast<uint32_t>((n0 + static_cast<int>(id)) * H), s);
         }
         put_rows(0, 4 * ct + kg, s);
         bit[ct] = static_cast<int>(signs >> 31);
@@ -332,7 +372,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             const float *row = msgtab + slot * LDM;
 #pragma unroll
             for (int t = 0; t < TPW; ++t) {
-                const float x = row[wc0 + 16 * t + col];
+                const float x = row[mcol(t)];
                 s[t] += BW ? x : fabsf(x);
                 if (!BW && t == 0) signs |= __float_as_uint(x);
             }
@@ -415,8 +455,8 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                             const int v = u[k] >= 0 ? n0 + u[k] : spare_row;
 #pragma unroll
                             for (int t = 0; t < TPW; ++t) {
-                                xl[k][t] = row[wc0 + 16 * t + col];
-                                xg[k][t] = msg[static_cast<uint32_t>(v * H + wc0 + 16 * t + col)];
+                                xl[k][t] = row[mcol(t)];
+                                xg[k][t] = msg[static_cast<uint32_t>(v * H + mcol(t))];
                             }
                         }
 #pragma unroll
@@ -514,15 +554,11 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 ftp0[ct] = *reinterpret_cast<const f32x4 *>(featb + p0 + rr);
                 ftp1[ct] = ftp0[ct];
             } else {
-#pragma unroll
-                for (int t = 0; t < TPW; ++t) {
-                    const int m = wc0 + 16 * t + col;
-                    if constexpr (BW) {
-                        xs0[ct][t] = P.emb[static_cast<uint32_t>(vg0[ct] * 2 * H + (1 - dir) * H + m)];
-                        mks0[ct][t] = gates_in[static_cast<uint32_t>(vg0[ct] * H + m)];
-                    } else {
-                        xs0[ct][t] = xin[static_cast<size_t>(p0 + rr) * H + m];
-                    }
+                if constexpr (BW) {
+                    load_cols(P.emb, static_cast<uint32_t>(vg0[ct] * 2 * H + (1 - dir) * H), xs0[ct]);
+                    load_gates(gates_in, static_cast<uint32_t>(vg0[ct] * H), mks0[ct]);
+                } else {
+                    load_cols(xin, static_cast<uint32_t>((p0 + rr) * H), xs0[ct]);
                 }
             }
         }
@@ -561,7 +597,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             bf16x8 a1[KS];
             float bias_n[TPW];
 #pragma unroll
-            for (int t = 0; t < TPW; ++t) bias_n[t] = kBiasLds ? bias_row[n * H + wc0 + 16 * t + col] : bias[n][t];
+            for (int t = 0; t < TPW; ++t) bias_n[t] = kBiasLds ? bias_row[n * H + mcol(t)] : bias[n][t];
             auto read_one_tile = [&]() __attribute__((always_inline)) {
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
@@ -608,69 +644,103 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                 const bool live = !dead && r < rows;
                 const int v_emb = live ? vg0[ct] : gv.n_tot;
                 const int v_msg = live ? vg0[ct] : sink_row;
-                float yv[TPW];
+                // row of this node in the kept / delta array `slot` (unused rows: the spare row)
+                auto delta_at = [&](int slot) __attribute__((always_inline)) {
+                    return live ? static_cast<uint32_t>(slot * gv.n_tot * H) + static_cast<uint32_t>(vg0[ct] * H)
+                                : static_cast<uint32_t>(2 * L * gv.n_tot * H);
+                };
+                float yv[TPW], ypre[TPW];
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) yv[t] = dead ? 0.0f : acc[ct][t][0] + acc[ct][t][1] + acc[ct][t][2];
+                if constexpr (BW) {
+                    // delta slot of this layer's gated output: f's layers L-2 .. 0, then g's
+                    // layers L-1 .. 0; slot = index into the 2L delta arrays (f first)
+                    if (n == 0) {
+                        float g[TPW];
+#pragma unroll
+                        for (int t = 0; t < TPW; ++t) g[t] = dead ? 0.0f : gs0[ct][t];
+                        store_cols(dlt, delta_at(L - 1), g);
+                    }
+                    auto gate = [&](int bit) __attribute__((always_inline)) {
+                        if constexpr (!dead) {
+#pragma unroll
+                            for (int t = 0; t < TPW; ++t) yv[t] = (mC[ct][t] & bit) ? yv[t] : 0.0f;
+                        }
+                    };
+                    if (n == L - 1) {                // end of f^T: ds_v = outside gradient + f path
+                        if constexpr (!dead) {
+#pragma unroll
+                            for (int t = 0; t < TPW; ++t) yv[t] += FF ? x0[ct][t] : xC[ct][t];
+                        }
+                        store_cols(P.emb, static_cast<uint32_t>(v_emb * 2 * H + (1 - dir) * H), yv);
+                        gate(4);
+                        store_cols(dlt, delta_at(L + L - 1), yv);
+                    } else if (n < L - 1) {
+                        gate(2);
+                        store_cols(dlt, delta_at(L - 2 - n), yv);
+                    } else if (n < NL - 1) {
+                        gate(8);
+                        store_cols(dlt, delta_at(L + NL - 2 - n), yv);
+                    }
+                    if (n == NL - 1) {               // end of g^T: da_v
+                        store_cols(msg, static_cast<uint32_t>(v_msg * H), yv);
+                        if constexpr (!dead) store_cols(msgtab, static_cast<uint32_t>((ring * CH + r) * LDM), yv);
+                    }
+                    if constexpr (!dead) {
+                        if (n < NL - 1) put_rows((n + 1) & 1, r, yv);
+                    }
+                    return;
+                }
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) {
-                    const int m = wc0 + 16 * t + col;
-                    float y = dead ? 0.0f : acc[ct][t][0] + acc[ct][t][1] + acc[ct][t][2];
-                    if constexpr (BW) {
-                        // delta slot of this layer's gated output: f's layers L-2 .. 0, then g's
-                        // layers L-1 .. 0; slot = index into the 2L delta arrays (f first)
-                        const uint32_t d_row = live ? static_cast<uint32_t>(vg0[ct] * H + m)
-                                                    : static_cast<uint32_t>(2 * L * gv.n_tot * H + m);
-                        auto put_delta = [&](int slot, float val) __attribute__((always_inline)) {
-                            dlt[live ? static_cast<uint32_t>(slot * gv.n_tot * H) + d_row : d_row] = val;
-                        };
-                        if (n == 0) put_delta(L - 1, dead ? 0.0f : gs0[ct][t]);
-                        if (n == L - 1) {                // end of f^T: ds_v = outside gradient + f path
-                            if constexpr (!dead) y += FF ? x0[ct][t] : xC[ct][t];
-                            P.emb[static_cast<uint32_t>(v_emb * 2 * H + (1 - dir) * H + m)] = y;
-                            if constexpr (!dead) y = (mC[ct][t] & 4) ? y : 0.0f;
-                            put_delta(L + L - 1, y);
-                        } else if (n < L - 1) {
-                            if constexpr (!dead) y = (mC[ct][t] & 2) ? y : 0.0f;
-                            put_delta(L - 2 - n, y);
-                        } else if (n < NL - 1) {
-                            if constexpr (!dead) y = (mC[ct][t] & 8) ? y : 0.0f;
-                            put_delta(L + NL - 2 - n, y);
-                        }
-                        if (n == NL - 1) {               // end of g^T: da_v
-                            msg[static_cast<uint32_t>(v_msg * H + m)] = y;
-                            if constexpr (!dead) msgtab[(ring * CH + r) * LDM + m] = y;
-                        }
-                        yv[t] = y;
-                        continue;
-                    }
+                    float y = yv[t];
                     if constexpr (!dead) y = fmaxf(y + bias_n[t], 0.0f);
-                    if constexpr (TR) {
-                        const uint32_t d_row = live ? static_cast<uint32_t>(vg0[ct] * H + m)
-                                                    : static_cast<uint32_t>(2 * L * gv.n_tot * H + m);
-                        // the output of g's last layer is only ever needed as a gate
-                        if (n < NL - 1 && n != L - 1)
-                            dlt[live ? static_cast<uint32_t>((1 + n) * gv.n_tot * H) + d_row : d_row] = y;
+                    if constexpr (TR && !dead) {
                         const int bit = n == NL - 1 ? 1 : (n == L - 1 ? 4 : (n == 0 ? 8 : 2));
-                        if constexpr (!dead) gate_bits[ct][t] = (n == 0 ? 0 : gate_bits[ct][t]) | (y > 0.0f ? bit : 0);
-                        if (n == NL - 1)
-                            gates_out[live ? static_cast<uint32_t>(vg0[ct] * H + m)
-                                           : static_cast<uint32_t>((2 - dir) * gv.n_tot * H + m)] =
-                                dead ? static_cast<uint8_t>(0) : static_cast<uint8_t>(gate_bits[ct][t]);
+                        gate_bits[ct][t] = (n == 0 ? 0 : gate_bits[ct][t]) | (y > 0.0f ? bit : 0);
                     }
+                    ypre[t] = y;
                     if (n == L - 1) {                    // end of g: residual update of s_v
                         if constexpr (!dead) y += FF ? x0[ct][t] : xC[ct][t];
-                        P.emb[static_cast<uint32_t>(v_emb * 2 * H + dir * H + m)] = y;
-                        if constexpr (WX) xb[static_cast<uint32_t>((live ? n0 + p0 + r : spare_row) * H + m)] = y;
                     }
                     if (n == NL - 1) {                   // end of f: the message of v, flagged
                         const uint32_t flag = (!dead && (bit0[ct] | (vg0[ct] == cur))) ? 0x80000000u : 0u;
-                        const float flagged = __uint_as_float(__float_as_uint(y) | flag);
-                        msg[static_cast<uint32_t>(v_msg * H + m)] = flagged;
-                        if constexpr (!dead) msgtab[(ring * CH + r) * LDM + m] = flagged;
+                        y = __uint_as_float(__float_as_uint(y) | flag);
                     }
                     yv[t] = y;
                 }
+                // a forward sweep's stores to HBM: ypre = the layer's output, yv = what the layer
+                // hands on (the state after the residual, the flagged message)
+                auto hbm_stores = [&]() __attribute__((always_inline)) {
+                    if constexpr (TR) {
+                        // the output of g's last layer is only ever needed as a gate
+                        if (n < NL - 1 && n != L - 1) store_cols(dlt, delta_at(1 + n), ypre);
+                        if (n == NL - 1) {
+                            int gb[TPW];
+#pragma unroll
+                            for (int t = 0; t < TPW; ++t) gb[t] = dead ? 0 : gate_bits[ct][t];
+                            store_gates(gates_out, live ? static_cast<uint32_t>(vg0[ct] * H)
+                                                        : static_cast<uint32_t>((2 - dir) * gv.n_tot * H), gb);
+                        }
+                    }
+                    if (n == L - 1) {
+                        store_cols(P.emb, static_cast<uint32_t>(v_emb * 2 * H + dir * H), yv);
+                        if constexpr (WX) store_cols(xb, static_cast<uint32_t>((live ? n0 + p0 + r : spare_row) * H), yv);
+                    }
+                    if (n == NL - 1) store_cols(msg, static_cast<uint32_t>(v_msg * H), yv);
+                };
+                if constexpr (!kLdsFirst) hbm_stores();
+                // What the next layer (or the next chunk's gather) waits for goes to LDS; where the
+                // registers allow, before the stores to HBM, which then follow while the LDS
+                // writes complete.
                 if constexpr (!dead) {
-                    if (n < NL - 1) put_rows((n + 1) & 1, r, yv);
+                    if (n < NL - 1)
+                        put_rows((n + 1) & 1, r, yv);
+                    else
+                        store_cols(msgtab, static_cast<uint32_t>((ring * CH + r) * LDM), yv);
+                    if constexpr (kLdsFirst) __builtin_amdgcn_sched_barrier(0);
                 }
+                if constexpr (kLdsFirst) hbm_stores();
             };
 
             // The loads and stores of the pipeline (the "mid block" below) are issued while the A
@@ -699,9 +769,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         const uint32_t u = rB[ct][1];
                         const bool wanted = (rB[ct][0] & kRecListed) == 0 && u != kNoFar;
                         const int row = wanted ? n0 + static_cast<int>(u) : spare_row;
-#pragma unroll
-                        for (int t = 0; t < TPW; ++t)
-                            farB[ct][t] = msg[static_cast<uint32_t>(row * H + wc0 + 16 * t + col)];
+                        load_cols(msg, static_cast<uint32_t>(row * H), farB[ct]);
                     }
                     if constexpr (FF) {
 #pragma unroll
@@ -725,16 +793,12 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         if constexpr (FF) {
                             fN[ct] = *reinterpret_cast<const f32x4 *>(featb + p1 + static_cast<uint32_t>(rr));
                         } else {
-#pragma unroll
-                            for (int t = 0; t < TPW; ++t) {
-                                const int m = wc0 + 16 * t + col;
-                                if constexpr (BW) {
-                                    const int v = node_of(rcA[ct]);
-                                    xN[ct][t] = P.emb[static_cast<uint32_t>(v * 2 * H + (1 - dir) * H + m)];
-                                    mN[ct][t] = gates_in[static_cast<uint32_t>(v * H + m)];
-                                } else {
-                                    xN[ct][t] = (xin + static_cast<size_t>(p1) * H)[static_cast<uint32_t>(rr * H + m)];
-                                }
+                            if constexpr (BW) {
+                                const int v = node_of(rcA[ct]);
+                                load_cols(P.emb, static_cast<uint32_t>(v * 2 * H + (1 - dir) * H), xN[ct]);
+                                load_gates(gates_in, static_cast<uint32_t>(v * H), mN[ct]);
+                            } else {
+                                load_cols(xin + static_cast<size_t>(p1) * H, static_cast<uint32_t>(rr * H), xN[ct]);
                             }
                         }
                     }
@@ -844,9 +908,9 @@ __global__ __launch_bounds__(256) void k_bucket_feats(GraphView gv, const float 
 // Index: ((((dir * 2L + n) * MT + mt) * KS + ks) * WS + ws) * 64 + lane, n = g layers then f
 // layers; lane l holds W[k(ks, l / 16, i)][16 mt + l % 16], i = 0..7, as bf16 part ws of the
 // exact three-way split (ws = 0 only when the weights are bf16 already).  k is the position of
-// an input column in the kernel's activation rows: 32 ks + 8 (l / 16) + i where a lane owns one
-// output column, and 32 ks + 16 (i % 2) + 4 (l / 16) + i / 2 where it owns two (H = 128: the
-// columns c and c + 16 of a wave travel as the two halves of one word).
+// an input column in the kernel's activation rows, 32 ks + 8 (l / 16) + i.  Where a wave owns two
+// column tiles (H = 128) they interleave: tile mt holds the columns 32 (mt / 2) + 2 c + mt % 2,
+// c = 0..15, so that a lane's two columns are neighbours (see mcol in the kernel).
 // With `reverse`, the fragments of the reverse pass: index dir is the direction whose chunks are
 // walked, the weights are those of the other direction, transposed, f's layers from the last to
 // the first and then g's (biases are not used there).
@@ -879,9 +943,8 @@ void pack_sweep_weights(const ModelView &mv, const float *blob, int WS, std::vec
                 for (int ks = 0; ks < KS; ++ks)
                     for (int lane = 0; lane < 64; ++lane)
                         for (int i = 0; i < 8; ++i) {
-                            const int k = paired ? 32 * ks + 16 * (i % 2) + 4 * (lane / 16) + i / 2
-                                                 : 32 * ks + 8 * (lane / 16) + i;
-                            const int m = 16 * mt + lane % 16;
+                            const int k = 32 * ks + 8 * (lane / 16) + i;
+                            const int m = paired ? 32 * (mt / 2) + 2 * (lane % 16) + mt % 2 : 16 * mt + lane % 16;
                             float rest = reverse ? blob[lr.w + static_cast<size_t>(m) * H + k]
                                                  : blob[lr.w + static_cast<size_t>(k) * H + m];
                             for (int ws = 0; ws < WS; ++ws) {
