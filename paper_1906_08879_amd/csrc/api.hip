@@ -105,6 +105,7 @@ struct pl_weights {
     uint16_t *d_wfrag_bw = nullptr;  // the same for the reverse pass (transposed, f before g)
     float *d_sweep_bias = nullptr;
     uint16_t *d_pool_frag = nullptr;
+    uint16_t *d_pool_afrag = nullptr;   // the streaming pooling kernel's fragments (null when not covered)
     float *d_pool_bias = nullptr;
     int sweep_ws = 0;               // bf16 parts per weight: 1 (bf16 weights) or 3 (fp32)
     int path = 0;                   // 0 = fastest available kernels, 1 = generic fp32 kernels
@@ -564,18 +565,20 @@ int forward_impl(pl_graph_batch *g, const float *node_feats, const int32_t *plac
     // the node sets as the pooling below reads them: from the reachability bits the sweeps left
     if (out_class) launch_classes(gv, cur_node, ws.reach, out_class, s);
     const bool pool_mfma = w->d_pool_frag && w->path == 0;
+    int pool_slices = ws.n_chunks;
     {
         StageScope scope(timer, PL_STAGE_POOL, s);
         if (pool_mfma)
-            launch_pool_mfma(gv, mv, ws, fa, reinterpret_cast<const uint4 *>(w->d_pool_frag),
-                             w->d_pool_bias, w->sweep_ws, keep_pool, s);
+            pool_slices = launch_pool_mfma(gv, mv, ws, fa, reinterpret_cast<const uint4 *>(w->d_pool_frag),
+                                           reinterpret_cast<const uint4 *>(w->d_pool_afrag), w->d_pool_bias,
+                                           w->sweep_ws, keep_pool, s);
         else
             launch_pool_generic(gv, mv, ws, fa, s);
         if (pool_kept) *pool_kept = pool_mfma && keep_pool;
     }
     {
         StageScope scope(timer, PL_STAGE_HEAD, s);
-        launch_head_generic(gv, mv, ws, fa, pool_mfma ? kPoolSlices : ws.n_chunks, s);
+        launch_head_generic(gv, mv, ws, fa, pool_slices, s);
     }
     if (out_node_emb)
         PL_HIP(hipMemcpyAsync(out_node_emb, ws.emb,
@@ -844,6 +847,13 @@ int pl_weights_create(const pl_model_cfg *cfg, const float *host_blob, size_t n_
             pl_weights_destroy(w);
             return rc;
         }
+        if (pool_stream_supported(cfg->H, cfg->n_layers, cfg->weight_dtype)) {
+            pack_pool_stream_weights(w->view, w->host_blob.data(), &frag);
+            if ((rc = upload(frag, &w->d_pool_afrag))) {
+                pl_weights_destroy(w);
+                return rc;
+            }
+        }
     }
     *out = w;
     return PL_OK;
@@ -866,6 +876,7 @@ int pl_weights_destroy(pl_weights *w)
     (void)hipFree(w->d_wfrag_bw);
     (void)hipFree(w->d_sweep_bias);
     (void)hipFree(w->d_pool_frag);
+    (void)hipFree(w->d_pool_afrag);
     (void)hipFree(w->d_pool_bias);
     delete w;
     return PL_OK;

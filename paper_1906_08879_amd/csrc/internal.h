@@ -186,9 +186,13 @@ constexpr int kPoolSlices = 4;
 bool pool_mfma_supported(int H, int L, int weight_dtype);
 void pack_pool_weights(const ModelView &mv, const float *blob, int WS, std::vector<uint16_t> *frag,
                        std::vector<float> *bias);
-void launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
-                      const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
-                      float *keep, hipStream_t s);
+// fragments of the streaming pooling kernel (weights as A operands); bf16 weights at H = 128
+bool pool_stream_supported(int H, int L, int weight_dtype);
+void pack_pool_stream_weights(const ModelView &mv, const float *blob, std::vector<uint16_t> *frag);
+// returns the number of slices per graph that ws.partial holds afterwards
+int launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
+                     const ForwardArgs &fa, const uint4 *wfrag, const uint4 *afrag, const float *bias, int WS,
+                     float *keep, hipStream_t s);
 
 // ---- policy gradient (kernels_backward.hip): buffers owned by a batch for one (D, H, L)
 struct GradWorkspace {

@@ -6,8 +6,11 @@
 //   k_pool_sort   one workgroup per graph: a counting sort of the graph's nodes by
 //                 key = (set, device group), without atomics (a thread counts and places a
 //                 contiguous block of nodes), so the order is the same on every run;
-//   k_pool_tiles  one workgroup per (set, slice of the set's tiles, graph).  A tile is up to
-//                 sixteen nodes of ONE key, so the sum over a tile's rows needs no per-device
+//   k_pool_stream (H = 128, bf16 weights) one workgroup per graph, or per (set, graph) in small
+//                 batches; every wave walks tiles of its own with the weights in LDS, the rows
+//                 coming straight from HBM and the two layers chained in registers (see there);
+//   k_pool_tiles  (H <= 64) one workgroup per (set, slice of the set's tiles, graph).  A tile is
+//                 up to sixteen nodes of ONE key, so the sum over a tile's rows needs no per-device
 //                 selection: a lane adds its four nodes' outputs to one running sum, which is
 //                 written out when the device changes.
 // In k_pool_tiles:
@@ -20,6 +23,8 @@
 //   * a lane that owns two output columns hands them to the second layer as one word per part
 //     (the second layer's contraction index is permuted to match, see pack_pool_weights);
 //   * all sums are taken in a fixed order, so the result is bitwise reproducible.
+#include <type_traits>
+
 #include "internal.h"
 
 namespace pl {
@@ -455,6 +460,355 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_tiles(PoolParams P)
     }
 }
 
+// ---- k_pool_stream: the same sums with every wave working on tiles of its own.
+// One workgroup of eight waves per (set, graph); wave w is slice w of the set's tiles.  The
+// weights of l_set sit in LDS as MFMA *A* operands (the products are taken transposed:
+// out^T = W^T x^T), the sixteen nodes of a tile are the columns of the B operand:
+//   * lane (n = lane % 16, g = lane / 16) loads eight floats of node n's row per k-step straight
+//     from HBM (two 16-byte loads, issued kLoadAhead k-steps before their use), splits them exactly
+//     into three bf16 parts in registers and uses them as B operands: the input never passes
+//     through LDS, and there is no barrier in the tile loop;
+//   * a weight fragment read from LDS serves the three parts; their products accumulate in one
+//     accumulator, so the parts are summed by the matrix core;
+//   * the transposed result of layer 1 (lane (n, g) holds columns 16 mt + 4 g + j of node n) is, with
+//     two column tiles taken together, exactly a B operand of layer 2 for a permuted contraction
+//     index (the packed weights of layer 2 carry the permutation): the activations go from one
+//     layer to the next in registers;
+//   * a lane adds its node's outputs to running sums; the sixteen lanes of a column are added in a
+//     fixed order when the device group changes.
+constexpr int kStreamWaves = 8;
+constexpr int kStreamOneSetGroups = 256;   // up to this many (set, graph) pairs each gets a workgroup of its own
+constexpr int kStreamThreads = 64 * kStreamWaves;
+
+// position in a row of the i-th of the eight values that lane group g holds in k-step ks
+__host__ __device__ constexpr int stream_k(int ks, int g, int i) { return 32 * ks + 16 * (i / 4) + 4 * g + i % 4; }
+
+template <int H, int L, bool KEEP = false>
+__global__ __launch_bounds__(kStreamThreads, 1) void k_pool_stream(PoolParams P)
+{
+    constexpr int K1 = 2 * H;
+    constexpr int KS1 = K1 / 32, KS2 = H / 32, MT = H / 16;
+#ifndef PL_POOL_AHEAD
+#define PL_POOL_AHEAD 4
+#endif
+    constexpr int kLoadAhead = KS1 < PL_POOL_AHEAD ? KS1 : PL_POOL_AHEAD;     // k-steps of input rows in flight
+    constexpr int MG = MT < 4 ? MT : 4;               // column tiles whose chains interleave
+#ifndef PL_POOL_INTERLEAVE
+#define PL_POOL_INTERLEAVE 1
+#endif
+    constexpr bool kInterleave = PL_POOL_INTERLEAVE;
+    constexpr int kFrags = MT * KS1 + (L > 1 ? MT * KS2 : 0);
+    static_assert(KS1 % kLoadAhead == 0 && MT % MG == 0 && MT % 2 == 0, "shape");
+
+    __shared__ uint4 wlds[kFrags * 64];               // A fragments of l_set: layer 1 [mt][ks], then layer 2
+    __shared__ __attribute__((aligned(16))) float blds[L * H];
+    __shared__ int kofs[kMaxD + 1];                   // first position of each device group of this set
+
+    const int b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: the tile walk stays in scalar registers
+    const int n = lane & 15, g = lane >> 4;
+    const GraphView &gv = P.gv;
+    const int g0 = gv.node_off[b], g_n = gv.node_off[b + 1] - g0;
+    const int G = P.G;
+    int slices = (g_n + kPoolChunk - 1) / kPoolChunk;
+    if (slices > P.max_slices) slices = P.max_slices;
+    // A workgroup takes the sets blockIdx.x, blockIdx.x + gridDim.x, ..: all three of its graph
+    // (grid.x = 1: every workgroup then has the same share of a batch of equal graphs, whatever
+    // the sizes of the sets) or one (grid.x = 3, for batches that would not fill the chip otherwise).
+    for (int set = blockIdx.x; set < 3; set += gridDim.x) {
+    if (set != static_cast<int>(blockIdx.x)) __syncthreads();   // every wave is done with the weights of the previous set
+    const int32_t *kb = P.koff + static_cast<size_t>(b) * (kMaxKeys + 1) + set * G;
+    int n_tiles = 0;
+    for (int d = 0; d < G; ++d) n_tiles += (kb[d + 1] - kb[d] + kBatch - 1) / kBatch;
+    if (tid <= G) kofs[tid] = kb[tid];
+
+    // The set's weights travel to LDS through registers, all loads in flight together; a wave's
+    // first node ids and rows are requested before it waits for them.
+    constexpr int kWPer = kFrags * 64 / kStreamThreads;
+    static_assert(kFrags * 64 % kStreamThreads == 0, "fragments must divide over the threads");
+    uint4 wtmp[kWPer];
+    {
+        const uint4 *src = P.wfrag + static_cast<size_t>(set) * kFrags * 64;
+#pragma unroll
+        for (int k = 0; k < kWPer; ++k) wtmp[k] = src[tid + k * kStreamThreads];
+    }
+    const bool idle = wave >= slices;
+    const int t_lo = idle ? 0 : static_cast<int>(static_cast<long long>(n_tiles) * wave / slices);
+    const int t_hi = idle ? 0 : static_cast<int>(static_cast<long long>(n_tiles) * (wave + 1) / slices);
+    float *dst = P.partial + (((static_cast<size_t>(b) * P.max_slices + wave) * 3 + set) * G) * H;
+
+    // ---- tile walk (uniform over the wave, offsets from LDS so that it never waits for loads from
+    // HBM): device group w_dev, position w_pos of the walk's tile, w_left nodes of the group from there
+    // (before the workgroup's barrier the offsets come from HBM, kof_g; afterwards from LDS, kof)
+    auto kof = [&](int d) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(kofs[d]); };
+    auto kof_g = [&](int d) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(kb[d]); };
+    int w_dev = 0, w_pos = 0, w_left = 0;
+    if (t_lo < t_hi) {                            // the device group of the slice's first tile
+        int before = 0;
+        for (;; ++w_dev) {
+            const int tiles = (kof_g(w_dev + 1) - kof_g(w_dev) + kBatch - 1) / kBatch;
+            if (t_lo < before + tiles) break;
+            before += tiles;
+        }
+        w_pos = kof_g(w_dev) + (t_lo - before) * kBatch;
+        w_left = kof_g(w_dev + 1) - w_pos;
+    }
+    // node of this lane in the walk's tile (rows past the tile's end repeat its first node); the
+    // walk moves on to the next tile
+    auto tile_next = [&](auto offsets, int &cnt, int &dev) __attribute__((always_inline)) {
+        cnt = min(kBatch, w_left);
+        dev = w_dev;
+        const int id = P.klist[g0 + w_pos + (n < cnt ? n : 0)];
+        w_pos += kBatch;
+        w_left -= kBatch;
+        while (w_left <= 0 && w_dev + 1 < G) {
+            ++w_dev;
+            w_pos = offsets(w_dev);
+            w_left = offsets(w_dev + 1) - w_pos;
+        }
+        return id;
+    };
+    auto load_step = [&](int node, int ks, f32x4 (&x)[2]) __attribute__((always_inline)) {
+        const float *row = P.emb + static_cast<size_t>(node) * K1 + 32 * ks + 4 * g;
+        x[0] = *reinterpret_cast<const f32x4 *>(row);
+        x[1] = *reinterpret_cast<const f32x4 *>(row + 16);
+    };
+    // exact three-way split of eight floats into bf16 parts (truncation), as MFMA operands
+    auto split8 = [&](const float (&x)[8], bf16x8 (&part)[3]) __attribute__((always_inline)) {
+        uint32_t w[3][4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float a0 = x[2 * q], a1 = x[2 * q + 1];
+            const float r0 = a0 - trunc_bf16(a0), r1 = a1 - trunc_bf16(a1);
+            const float l0 = r0 - trunc_bf16(r0), l1 = r1 - trunc_bf16(r1);
+            w[0][q] = pack_hi16(a0, a1);
+            w[1][q] = pack_hi16(r0, r1);
+            w[2][q] = pack_hi16(l0, l1);
+        }
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const uint4 v{w[p][0], w[p][1], w[p][2], w[p][3]};
+            part[p] = *reinterpret_cast<const bf16x8 *>(&v);
+        }
+    };
+    auto frag1 = [&](int mt, int ks) __attribute__((always_inline)) {
+        const uint4 v = wlds[(mt * KS1 + ks) * 64 + lane];
+        return *reinterpret_cast<const bf16x8 *>(&v);
+    };
+    auto frag2 = [&](int mt, int ks) __attribute__((always_inline)) {
+        const uint4 v = wlds[(MT * KS1 + mt * KS2 + ks) * 64 + lane];
+        return *reinterpret_cast<const bf16x8 *>(&v);
+    };
+    // The matrix instructions run in groups of MG column tiles x (hi, mid, lo) with one weight
+    // fragment per tile, so that none waits for the one before it on the same accumulator.  Groups
+    // are numbered through both layers: q < NG1: layer 1, k-step q / GPK, tiles MG (q % GPK) ..;
+    // then layer 2 likewise.  The fragments of group q + 1 are read from LDS before the matrix
+    // instructions of group q are issued.
+    constexpr int GPK = MT / MG;                       // groups per k-step
+    constexpr int NG1 = KS1 * GPK, NG = NG1 + (L > 1 ? KS2 * GPK : 0);
+    auto read_group = [&](int q, bf16x8 (&a)[MG]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int m = 0; m < MG; ++m)
+            a[m] = q < NG1 ? frag1(MG * (q % GPK) + m, q / GPK) : frag2(MG * ((q - NG1) % GPK) + m, (q - NG1) / GPK);
+    };
+    auto mfma_group = [&](int m0, const bf16x8 (&a)[MG], const bf16x8 (&part)[3], f32x4 (&acc)[MT]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+#pragma unroll
+            for (int m = 0; m < MG; ++m)
+                acc[m0 + m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], part[p], acc[m0 + m], 0, 0, 0);
+    };
+
+    f32x4 sum[MT];            // running sums of this lane's node slot over the tiles of the current device group
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) sum[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    unsigned written = 0;
+    // Adds the sixteen lanes of a column in a fixed order and writes the device group's sums.
+    auto row_sum = [](float v) __attribute__((always_inline)) {
+        auto step = [](float x, auto ctrl) __attribute__((always_inline)) {
+            return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value, 0xF, 0xF, false));
+        };
+        v = step(v, std::integral_constant<int, 0xB1>{});     // quad_perm [1, 0, 3, 2]
+        v = step(v, std::integral_constant<int, 0x4E>{});     // quad_perm [2, 3, 0, 1]
+        v = step(v, std::integral_constant<int, 0x141>{});    // row_half_mirror
+        v = step(v, std::integral_constant<int, 0x140>{});    // row_mirror
+        return v;
+    };
+    auto flush = [&](int dev_done) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            f32x4 sv;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sv[j] = row_sum(sum[mt][j]);
+            if (n == 0) *reinterpret_cast<f32x4 *>(dst + dev_done * H + 16 * mt + 4 * g) = sv;
+            sum[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        written |= 1u << dev_done;
+    };
+
+    // ---- pipeline: the rows of k-step s + kLoadAhead are in flight while k-step s is computed
+    // The node ids of tile t + 2 are fetched at the start of tile t, before that tile's row loads:
+    // loads return in order, so when an id is handed on at the end of a tile it arrived long ago
+    // and the wait for it leaves the row loads in flight.
+    f32x4 raw[kLoadAhead][2];
+    int cnt = 0, dev = 0, cnt_next = 0, dev_next = 0, cnt_after = 0, dev_after = 0;
+    int node = g0, node_next = g0, node_after = g0;
+    if (t_lo < t_hi) {
+        node = node_next = node_after = tile_next(kof_g, cnt, dev);
+        if (t_lo + 1 < t_hi) node_next = tile_next(kof_g, cnt_next, dev_next);
+#pragma unroll
+        for (int ks = 0; ks < kLoadAhead; ++ks) load_step(node, ks, raw[ks]);
+    }
+    // ---- the weights arrive: every wave writes its share, then the workgroup meets
+#pragma unroll
+    for (int k = 0; k < kWPer; ++k) wlds[tid + k * kStreamThreads] = wtmp[k];
+    for (int i = tid; i < L * H; i += kStreamThreads) blds[i] = P.bias[set * L * H + i];
+    __syncthreads();
+    if (idle) continue;
+    if (t_lo >= t_hi) {
+        for (int i = lane; i < G * H; i += 64) dst[i] = 0.0f;
+        continue;
+    }
+    bf16x8 afr[2][MG];
+    read_group(0, afr[0]);
+    // nothing loaded before the loop is in flight when it starts, so that the waits inside the
+    // loop are counted from the loop's own loads alone
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+
+    int t = t_lo;
+    while (t < t_hi) {
+        const int seg_dev = dev;
+        // the tiles of one device group
+        for (;;) {
+            const bool more = t + 1 < t_hi;
+            if (t + 2 < t_hi) node_after = tile_next(kof, cnt_after, dev_after);
+            f32x4 acc[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            // ---- layer 1.  The split of k-step ks + 1 and the loads of k-step ks + kLoadAhead are
+            // written before the matrix instructions of k-step ks and interleaved with them by the
+            // scheduling groups below: the vector unit works while the matrix core is busy.
+            bf16x8 part[2][3];
+            {
+                float x[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) x[i] = raw[0][i / 4][i % 4];
+                split8(x, part[0]);
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS1; ++ks) {
+                // (after the slice's last tile the same rows once more: every path issues the
+                // same loads, so the waits for them are counted exactly)
+                if (ks + kLoadAhead < KS1)
+                    load_step(node, ks + kLoadAhead, raw[ks % kLoadAhead]);
+                else
+                    load_step(more ? node_next : node, ks + kLoadAhead - KS1, raw[ks % kLoadAhead]);
+                if (ks + 1 < KS1) {
+                    float x[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) x[i] = raw[(ks + 1) % kLoadAhead][i / 4][i % 4];
+                    split8(x, part[(ks + 1) & 1]);
+                }
+#pragma unroll
+                for (int gq = 0; gq < GPK; ++gq) {
+                    const int q = ks * GPK + gq;
+                    read_group((q + 1) % NG, afr[(q + 1) & 1]);
+                    mfma_group(MG * gq, afr[q & 1], part[ks & 1], acc);
+                }
+                if constexpr (kInterleave) {
+                    __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);      // the two row loads
+#pragma unroll
+                    for (int gq = 0; gq < GPK; ++gq) {
+                        __builtin_amdgcn_sched_group_barrier(0x100, MG, 0); // fragments of the next group
+#pragma unroll
+                        for (int i = 0; i < 3 * MG; ++i) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                        }
+                    }
+                }
+            }
+            // ---- bias, ReLU; layer 2 from registers
+            f32x4 out[MT];
+            if constexpr (L > 1) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) out[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                // bias, ReLU and split of the two column tiles that k-step ks of layer 2 contracts
+                auto hand_on = [&](int ks, bf16x8 (&pt)[3]) __attribute__((always_inline)) {
+                    float y[8];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int mt = 2 * ks + h;
+                        const f32x4 bv = *reinterpret_cast<const f32x4 *>(&blds[16 * mt + 4 * g]);
+                        f32x4 yy;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) yy[j] = y[4 * h + j] = fmaxf(acc[mt][j] + bv[j], 0.0f);
+                        if constexpr (KEEP) {
+                            if (n < cnt) *reinterpret_cast<f32x4 *>(P.keep + static_cast<size_t>(node) * H + 16 * mt + 4 * g) = yy;
+                        }
+                    }
+                    split8(y, pt);
+                };
+                hand_on(0, part[0]);
+#pragma unroll
+                for (int ks = 0; ks < KS2; ++ks) {
+                    if (ks + 1 < KS2) hand_on(ks + 1, part[(ks + 1) & 1]);
+#pragma unroll
+                    for (int gq = 0; gq < GPK; ++gq) {
+                        const int q = NG1 + ks * GPK + gq;
+                        read_group((q + 1) % NG, afr[(q + 1) & 1]);
+                        mfma_group(MG * gq, afr[q & 1], part[ks & 1], out);
+                    }
+                    if constexpr (kInterleave && !KEEP) {
+#pragma unroll
+                        for (int gq = 0; gq < GPK; ++gq) {
+                            if (gq == 0) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // the biases
+                            __builtin_amdgcn_sched_group_barrier(0x100, MG, 0);
+#pragma unroll
+                            for (int i = 0; i < 3 * MG; ++i) {
+                                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+                            }
+                        }
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) out[mt] = acc[mt];
+            }
+            // ---- bias, ReLU of the last layer; the node's outputs join the running sums
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const f32x4 bv = *reinterpret_cast<const f32x4 *>(&blds[(L - 1) * H + 16 * mt + 4 * g]);
+                f32x4 yy;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) yy[j] = fmaxf(out[mt][j] + bv[j], 0.0f);
+                if constexpr (KEEP) {
+                    if (n < cnt)
+                        *reinterpret_cast<f32x4 *>(P.keep + (static_cast<size_t>(L - 1) * gv.n_tot + node) * H + 16 * mt + 4 * g) = yy;
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sum[mt][j] += n < cnt ? yy[j] : 0.0f;
+            }
+            node = node_next;
+            cnt = cnt_next;
+            dev = dev_next;
+            node_next = node_after;
+            cnt_next = cnt_after;
+            dev_next = dev_after;
+            ++t;
+            if (t >= t_hi || dev != seg_dev) break;
+        }
+        flush(seg_dev);
+    }
+    for (int d = 0; d < G; ++d) {
+        if ((written >> d) & 1u) continue;
+        for (int i = lane; i < H; i += 64) dst[d * H + i] = 0.0f;
+    }
+    }   // sets
+}
+
 // Appends the MFMA B-operand fragments of one layer: index ((nt * KS + ks) * WS + ws) * 64 + lane,
 // lane l holds W[32 ks + 8 (l / 16) + i][16 nt + l % 16], i = 0..7, as bf16 part ws of the exact
 // three-way split of the weight (ws = 0 only when the weights are bf16 already).
@@ -508,6 +862,36 @@ void pack_pool_weights(const ModelView &mv, const float *blob, int WS, std::vect
         }
 }
 
+// A fragments of the streaming kernel: per set, layer 1 [mt][ks] then layer 2 [mt][ks], 64 lanes
+// of eight bf16: lane l holds W[stream_k(ks, l / 16, i)][16 mt + l % 16], i = 0..7 (bf16 weights).
+void pack_pool_stream_weights(const ModelView &mv, const float *blob, std::vector<uint16_t> *frag)
+{
+    frag->clear();
+    auto to_bf16 = [](float x) {
+        uint32_t u;
+        std::memcpy(&u, &x, 4);
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        return static_cast<uint16_t>(u >> 16);
+    };
+    for (int set = 0; set < 3; ++set)
+        for (int l = 0; l < mv.L; ++l) {
+            const LayerRef &lr = mv.l[set].layer[l];
+            const int MT = lr.n_out / 16, KS = lr.n_in / 32;
+            for (int mt = 0; mt < MT; ++mt)
+                for (int ks = 0; ks < KS; ++ks)
+                    for (int lane = 0; lane < 64; ++lane)
+                        for (int i = 0; i < 8; ++i) {
+                            const int k = stream_k(ks, lane / 16, i), m = 16 * mt + lane % 16;
+                            frag->push_back(to_bf16(blob[lr.w + static_cast<size_t>(k) * lr.n_out + m]));
+                        }
+        }
+}
+
+bool pool_stream_supported(int H, int L, int weight_dtype)
+{
+    return weight_dtype == PL_WEIGHTS_BF16 && H == 128 && (L == 1 || L == 2);
+}
+
 bool pool_mfma_supported(int H, int L, int weight_dtype)
 {
     if (L < 1 || L > 2) return false;
@@ -515,13 +899,30 @@ bool pool_mfma_supported(int H, int L, int weight_dtype)
     return H == 32 || H == 64;
 }
 
-void launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
-                      const ForwardArgs &fa, const uint4 *wfrag, const float *bias, int WS,
-                      float *keep, hipStream_t s)
+int launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
+                     const ForwardArgs &fa, const uint4 *wfrag, const uint4 *afrag, const float *bias, int WS,
+                     float *keep, hipStream_t s)
 {
-    if (gv.B == 0) return;
+    if (gv.B == 0) return kPoolSlices;
     hipLaunchKernelGGL(k_pool_sort, dim3(gv.B), dim3(kThreads), 0, s, gv, ws.reach, fa.placement, fa.cur_node, mv.D,
                        mv.G, mv.single_set, ws.klist, ws.koff);
+    // the shapes that the streaming kernel covers take it (eight slices per set, one per wave)
+    if (afrag && WS == 1 && pool_stream_supported(mv.H, mv.L, PL_WEIGHTS_BF16)) {
+        PoolParams Q{gv, afrag, bias, ws.emb, ws.klist, ws.koff, ws.partial, kStreamWaves, mv.G, keep};
+        const dim3 grid(3 * gv.B <= kStreamOneSetGroups ? 3 : 1, gv.B), block(kStreamThreads);
+        if (mv.L == 2) {
+            if (keep)
+                hipLaunchKernelGGL((k_pool_stream<128, 2, true>), grid, block, 0, s, Q);
+            else
+                hipLaunchKernelGGL((k_pool_stream<128, 2>), grid, block, 0, s, Q);
+        } else {
+            if (keep)
+                hipLaunchKernelGGL((k_pool_stream<128, 1, true>), grid, block, 0, s, Q);
+            else
+                hipLaunchKernelGGL((k_pool_stream<128, 1>), grid, block, 0, s, Q);
+        }
+        return kStreamWaves;
+    }
     PoolParams P{gv, wfrag, bias, ws.emb, ws.klist, ws.koff, ws.partial, kPoolSlices, mv.G, keep};
     const dim3 grid(3, kPoolSlices, gv.B), block(kThreads);
 #define PL_CASE(HH, WW, LL)                                                          \
@@ -530,12 +931,12 @@ void launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace 
             hipLaunchKernelGGL((k_pool_tiles<HH, WW, LL, true>), grid, block, 0, s, P); \
         else                                                                         \
             hipLaunchKernelGGL((k_pool_tiles<HH, WW, LL>), grid, block, 0, s, P);    \
-        return;                                                                      \
+        return kPoolSlices;                                                          \
     }
-    PL_CASE(128, 1, 2) PL_CASE(128, 1, 1)
     PL_CASE(64, 1, 2) PL_CASE(64, 1, 1) PL_CASE(64, 3, 2) PL_CASE(64, 3, 1)
     PL_CASE(32, 1, 2) PL_CASE(32, 1, 1) PL_CASE(32, 3, 2) PL_CASE(32, 3, 1)
 #undef PL_CASE
+    return kPoolSlices;
 }
 
 }  // namespace pl

@@ -168,7 +168,7 @@ def test_node_classes_call_bit_exact():
 def _custom(rng, sizes, D, H, n_layers=2, k_sweeps=1, group=1, weight_dtype="fp32", p_edge=0.3):
     n_nodes, n_edges, srcs, dsts, feats, places, curs = [], [], [], [], [], [], []
     for n in sizes:
-        s, d = tiny_random_dag(rng, n, p_edge)
+        s, d = tiny_random_dag(rng, n, p_edge(n) if callable(p_edge) else p_edge)
         n_nodes.append(n); n_edges.append(len(s)); srcs.append(s); dsts.append(d)
         feats.append(np.stack([rng.lognormal(0, 1, n), rng.lognormal(2, 1, n),
                                (rng.random(n) < 0.5)], axis=1))
@@ -197,6 +197,23 @@ def test_shapes_and_variants(D, H, L, k, group, wd):
     rng = np.random.default_rng(100 * D + H)
     w = _custom(rng, [1, 2, 40, 1, 17, 70, 3], D, H, L, k, group, wd)
     _compare(w, f"D={D} H={H} L={L} k={k} g={group} {wd}", max_fail_frac=0.05)
+
+
+@pytest.mark.parametrize("D,L,group,sizes", [
+    (8, 2, 1, [1300, 1, 2, 17, 140]),              # eight slices beside idle waves and empty sets
+    (16, 2, 1, [300, 700]),                        # the largest device count: most device groups have one tile
+    (1, 1, 0, [1100, 40]),                         # one layer, one device group
+    (3, 2, 0, [5] * 60 + [33] * 30),               # ninety graphs: a workgroup takes all three sets of its graph
+    (4, 2, 1, [16, 32, 48, 15, 17, 31, 33] * 13),  # tiles that end exactly at, just before and just after a device group
+])
+def test_pooling_on_the_widest_shape(D, L, group, sizes):
+    """H = 128 with bf16 weights takes the pooling kernel whose waves walk tiles of their own: both
+    of its launch shapes (a workgroup per (set, graph), a workgroup per graph), ragged tiles, sets
+    and device groups without nodes, waves without tiles."""
+    print(f"[parity] pooling H=128 D={D} L={L} group={group} B={len(sizes)}", flush=True)
+    rng = np.random.default_rng(7000 + 10 * D + L)
+    w = _custom(rng, sizes, D, 128, L, 1, group, "bf16", p_edge=lambda n: min(0.3, 3.0 / n))   # about three edges per node
+    _compare(w, f"pooling H=128 D={D} L={L} g={group}", max_fail_frac=0.05)
 
 
 @pytest.mark.parametrize("name", ["layered200", "nmt", "nasnet"])
