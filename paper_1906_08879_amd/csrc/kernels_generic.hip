@@ -19,8 +19,8 @@ constexpr int kTile = 16;   // rows (nodes) pushed through a network together
 // y[r][j] = act(bias[j] + sum_k x[r][k] * W[k][j]) for r < rows (rows <= kTile).
 // x and y live in LDS.  Thread (grp, j): column j = tid % n_out, row group grp = tid / n_out;
 // it owns rows grp, grp + groups, ... (at most RPT of them), so one weight load feeds up to
-// RPT FMAs.  Requires n_out <= kThreads and min(kThreads / n_out, kTile) * RPT >= kTile.
-template <int RPT, bool WIDE = false>
+// RPT FMAs.  Requires n_out <= kThreads and min(kThreads / n_out, kTile) * RPT >= rows.
+template <int RPT, bool WIDE = false, int KL = 16>
 __device__ __forceinline__ void dense_layer(const float *__restrict__ W,
                                             const float *__restrict__ bias, int n_in, int n_out,
                                             const float *x, int ldx, float *y, int ldy, int rows,
@@ -41,30 +41,58 @@ __device__ __forceinline__ void dense_layer(const float *__restrict__ W,
     int xoff[RPT];   // rows past the tile's end re-read its last row (never stored)
 #pragma unroll
     for (int i = 0; i < RPT; ++i) xoff[i] = min(grp + i * groups, rows - 1) * ldx;
-    // weights sixteen at a time, all loads issued before the first use: the loop is bound by the
-    // latency of one batch instead of one load per step
+    // weights KL at a time, all loads issued before the first use: the loop is bound by the
+    // latency of one batch instead of one load per step.  (WIDE: the float64 blocks stay sixteen
+    // terms long whatever KL is.)
     constexpr int KB = 16;
+    static_assert(KL % KB == 0, "a batch of loads is a whole number of blocks");
     int k = 0;
-    for (; k + KB <= n_in; k += KB) {
-        float w[KB];
+    for (; k + KL <= n_in; k += KL) {
+        float w[KL];
 #pragma unroll
-        for (int u = 0; u < KB; ++u) w[u] = W[static_cast<size_t>(k + u) * n_out + j];
+        for (int u = 0; u < KL; ++u) w[u] = W[static_cast<size_t>(k + u) * n_out + j];
         if constexpr (WIDE) {
-            float part[RPT];
 #pragma unroll
-            for (int i = 0; i < RPT; ++i) part[i] = 0.0f;
+            for (int u0 = 0; u0 < KL; u0 += KB) {
+                float part[RPT];
 #pragma unroll
-            for (int u = 0; u < KB; ++u)
+                for (int i = 0; i < RPT; ++i) part[i] = 0.0f;
 #pragma unroll
-                for (int i = 0; i < RPT; ++i) part[i] = fmaf(x[xoff[i] + k + u], w[u], part[i]);
+                for (int u = u0; u < u0 + KB; ++u)
 #pragma unroll
-            for (int i = 0; i < RPT; ++i) acc[i] += static_cast<double>(part[i]);
+                    for (int i = 0; i < RPT; ++i) part[i] = fmaf(x[xoff[i] + k + u], w[u], part[i]);
+#pragma unroll
+                for (int i = 0; i < RPT; ++i) acc[i] += static_cast<double>(part[i]);
+            }
             continue;
         }
 #pragma unroll
-        for (int u = 0; u < KB; ++u)
+        for (int u = 0; u < KL; ++u)
 #pragma unroll
             for (int i = 0; i < RPT; ++i) acc[i] = fmaf(x[xoff[i] + k + u], w[u], acc[i]);
+    }
+    if constexpr (KL > KB) {          // whole blocks left over
+        for (; k + KB <= n_in; k += KB) {
+            float w[KB];
+#pragma unroll
+            for (int u = 0; u < KB; ++u) w[u] = W[static_cast<size_t>(k + u) * n_out + j];
+            if constexpr (WIDE) {
+                float part[RPT];
+#pragma unroll
+                for (int i = 0; i < RPT; ++i) part[i] = 0.0f;
+#pragma unroll
+                for (int u = 0; u < KB; ++u)
+#pragma unroll
+                    for (int i = 0; i < RPT; ++i) part[i] = fmaf(x[xoff[i] + k + u], w[u], part[i]);
+#pragma unroll
+                for (int i = 0; i < RPT; ++i) acc[i] += static_cast<double>(part[i]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < KB; ++u)
+#pragma unroll
+                    for (int i = 0; i < RPT; ++i) acc[i] = fmaf(x[xoff[i] + k + u], w[u], acc[i]);
+            }
+        }
     }
     for (; k < n_in; ++k) {
         const float w = W[static_cast<size_t>(k) * n_out + j];
@@ -522,23 +550,33 @@ __global__ __launch_bounds__(kThreads) void k_head_policy1(ModelView mv, int B,
     }
     const float *W = mv.blob + mv.pol1.w + static_cast<size_t>(k0) * H;
     const float *xf = &x[0][0];
-    constexpr int KB = 16;      // weights per batch of loads, as in dense_layer
+    constexpr int KB = 16, KL = 64;      // terms per float64 block; weights per batch of loads (in flight together)
     int k = 0;
-    for (; k + KB <= kn; k += KB) {
-        float w[KB];
-#pragma unroll
-        for (int u = 0; u < KB; ++u) w[u] = W[static_cast<size_t>(k + u) * H + j];
-        // sixteen terms in fp32, the blocks in float64: rounding errors stay relative to a
-        // block's own size instead of the running sum's
+    // sixteen terms in fp32, the blocks in float64: rounding errors stay relative to a
+    // block's own size instead of the running sum's
+    auto block = [&](const float *w, int kk) __attribute__((always_inline)) {
         float part[RPT];
 #pragma unroll
         for (int i = 0; i < RPT; ++i) part[i] = 0.0f;
 #pragma unroll
         for (int u = 0; u < KB; ++u)
 #pragma unroll
-            for (int i = 0; i < RPT; ++i) part[i] = fmaf(xf[xoff[i] + k + u], w[u], part[i]);
+            for (int i = 0; i < RPT; ++i) part[i] = fmaf(xf[xoff[i] + kk + u], w[u], part[i]);
 #pragma unroll
         for (int i = 0; i < RPT; ++i) acc[i] += static_cast<double>(part[i]);
+    };
+    for (; k + KL <= kn; k += KL) {
+        float w[KL];
+#pragma unroll
+        for (int u = 0; u < KL; ++u) w[u] = W[static_cast<size_t>(k + u) * H + j];
+#pragma unroll
+        for (int u0 = 0; u0 < KL; u0 += KB) block(w + u0, k + u0);
+    }
+    for (; k + KB <= kn; k += KB) {
+        float w[KB];
+#pragma unroll
+        for (int u = 0; u < KB; ++u) w[u] = W[static_cast<size_t>(k + u) * H + j];
+        block(w, k);
     }
     for (; k < kn; ++k) {
         const double w = static_cast<double>(W[static_cast<size_t>(k) * H + j]);
@@ -684,9 +722,19 @@ void launch_head_generic(const GraphView &gv, const ModelView &mv, const Workspa
     const size_t lds = sizeof(float) * 3 * kTile * mv.H;
     const int n_slices = (mv.Z + kZSlice - 1) / kZSlice;
     const int row_tiles = (gv.B + kTile - 1) / kTile;
+    // h_i works on the G rows of a set, the first policy layer on tiles of kTile graphs: each
+    // thread takes as many rows as that needs
+    int groups = kThreads / mv.H;
+    if (groups > kTile) groups = kTile;
+    if (groups < 1) groups = 1;
+    int rpt_sets = 1;
+    while (groups * rpt_sets < mv.G) rpt_sets *= 2;
 #define CALL(R)                                                                                  \
     hipLaunchKernelGGL(k_head_sets<R>, dim3(3, gv.B), dim3(kThreads), lds, s, gv, mv, ws.emb,    \
-                       ws.partial, fa.cur_node, max_chunks, ws.zbuf, fa.out_pooled);             \
+                       ws.partial, fa.cur_node, max_chunks, ws.zbuf, fa.out_pooled)
+    PL_DISPATCH_RPT(rpt_sets, CALL)
+#undef CALL
+#define CALL(R)                                                                                  \
     hipLaunchKernelGGL(k_head_policy1<R>, dim3(row_tiles, n_slices), dim3(kThreads), 0, s, mv,   \
                        gv.B, ws.zbuf, ws.hidp)
     PL_DISPATCH_RPT(pick_rpt(mv.H), CALL)

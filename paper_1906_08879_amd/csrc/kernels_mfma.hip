@@ -578,7 +578,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         constexpr int kind = decltype(twoc)::value;
         const bool two = kind < 0 ? rows > kTileNodes : kind > 0;
         const bool has_next = c + 1 < c_end;
-        const int ring = (c - c_begin) % RING;   // table rows ring * CH .. of this chunk's messages
+        const int ring = static_cast<int>(static_cast<unsigned>(c - c_begin) % RING);   // table rows ring * CH .. of this chunk's messages
         const uint32_t info1 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(rcA[0][3])));
         const int rows1 = rows_of(info1);
         const int p1 = __builtin_amdgcn_readfirstlane(static_cast<int>(rcA[0][2]));
@@ -809,7 +809,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                     // chunk's nodes go to HBM (for the pooling kernel).
                     if constexpr (!BW) {
 #pragma unroll
-                        for (int ct = 0; ct < NT; ++ct) {
+                        for (int ct = 0; ct < (kind == 0 ? 1 : NT); ++ct) {
                             const int r = ct * kTileNodes + kg;
                             const bool mine = wave == 0 && col == 0 && r < rows;
                             reach[static_cast<uint32_t>(mine ? vg0[ct] : sink_row)] = static_cast<uint8_t>(bit0[ct]);
