@@ -288,7 +288,7 @@ size_t carve_workspace(unsigned char *base, size_t n, size_t B, const ModelView 
     ws->emb = reinterpret_cast<float *>(take(sizeof(float) * ((n + 1) * 2 * H + 4)));
     ws->msg = reinterpret_cast<float *>(take(sizeof(float) * ((2 * n + 2) * H + 4)));
     ws->xb = reinterpret_cast<float *>(take(sizeof(float) * ((2 * n + 1) * H + 4)));
-    ws->featb = reinterpret_cast<float4 *>(take(sizeof(float4) * (2 * n + 1)));
+    ws->featb = reinterpret_cast<float4 *>(take(sizeof(float4) * (n + 1)));
     ws->partial = reinterpret_cast<float *>(take(sizeof(float) * (B * ws->n_chunks * 3 * mv.G * H + 4)));
     ws->zbuf = reinterpret_cast<float *>(take(sizeof(float) * (B * mv.Z + 4)));
     ws->hidp = reinterpret_cast<double *>(take(sizeof(double) * (static_cast<size_t>((mv.Z + 255) / 256) * B * H + 4)));

@@ -123,7 +123,7 @@ struct Workspace {
     float *emb = nullptr;       // [n_tot, 2H]  [td ; bu]
     float *msg = nullptr;       // [2, n_tot, H]
     float *xb = nullptr;        // [2, n_tot, H]  sweep input in bucket order (matrix-core path)
-    float4 *featb = nullptr;    // [2, n_tot] raw features in bucket order (matrix-core path)
+    float4 *featb = nullptr;    // [n_tot] raw-feature records in node order (matrix-core path)
     uint8_t *reach = nullptr;   // [2, n_tot]   0: descendant-of-v* bit, 1: ancestor-of-v* bit
     float *partial = nullptr;   // [B, n_chunks_max, 3G, H] pooling partial sums
     float *zbuf = nullptr;      // [B, Z] policy inputs

@@ -83,8 +83,8 @@ struct SweepParams {
     uint8_t *reach;         // [2, n_tot]
     const int32_t *cur_node;
     // first sweep: the input x_v = relu(W_in^T phi_v + b_in) (Section 2.2 step 1) is computed
-    // here from the node's raw features, kept in bucket order, 16 bytes per node
-    const float4 *featb;    // [2, n_tot] {run time, output size, is-visited, bits(device | is-current << 16)}
+    // here from the node's raw features, 16 bytes per node
+    const float4 *featb;    // [n_tot] {run time, output size, is-visited, bits(device | is-current << 16)}, node order
     const float *proj;      // [(F + 1), H]: rows of W_in, then b_in; NULL when the input comes from xb
     int D;
     // ReLU gates of every node's layers, one byte per (sweep direction, node, column), node order:
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
         for (int i = tid; i < (kMaxD + 1) * H; i += kThreads)
             proj_dev[i] = (i < D * H) ? P.proj[2 * H + i] : 0.0f;
     }
-    const float4 *featb = P.featb + static_cast<size_t>(dir) * gv.n_tot + n0;
+    const float4 *featb = P.featb;   // one 16-byte record per node, node order
     // the device's row of W_in comes from LDS: read early (device_term), used late (project)
     auto device_term = [&](const f32x4 ft, int t) __attribute__((always_inline)) {
         const int dev = __float_as_int(ft[3]) & 0xFFFF;
@@ -551,7 +551,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
             const uint32_t id = rc0[ct][3] & kRecNoNode;
             vg0[ct] = n0 + static_cast<int>(id == kRecNoNode ? 0u : id);
             if constexpr (FF) {
-                ftp0[ct] = *reinterpret_cast<const f32x4 *>(featb + p0 + rr);
+                ftp0[ct] = *reinterpret_cast<const f32x4 *>(featb + static_cast<uint32_t>(vg0[ct]));
                 ftp1[ct] = ftp0[ct];
             } else {
                 if constexpr (BW) {
@@ -791,7 +791,7 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                         const int r = 4 * ct + kg;
                         const int rr = (r < rows1) ? r : 0;
                         if constexpr (FF) {
-                            fN[ct] = *reinterpret_cast<const f32x4 *>(featb + p1 + static_cast<uint32_t>(rr));
+                            fN[ct] = *reinterpret_cast<const f32x4 *>(featb + static_cast<uint32_t>(node_of(rcA[ct])));
                         } else {
                             if constexpr (BW) {
                                 const int v = node_of(rcA[ct]);
@@ -885,9 +885,10 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
     }
 }
 
-// Raw features of every node in the bucket order of both directions (Section 2.1 features;
-// the device and the is-current flag travel as bits).
-__global__ __launch_bounds__(256) void k_bucket_feats(GraphView gv, const float *__restrict__ feats,
+// Raw features of every node as one 16-byte record (Section 2.1 features; the device and the
+// is-current flag travel as bits), in node order: a sweep reads a row's record by the node id that
+// the row's plan record names, one chunk ahead.
+__global__ __launch_bounds__(256) void k_feature_records(GraphView gv, const float *__restrict__ feats,
                                                       const int32_t *__restrict__ placement,
                                                       const int32_t *__restrict__ cur_node, int D,
                                                       float4 *__restrict__ featb)
@@ -898,8 +899,7 @@ __global__ __launch_bounds__(256) void k_bucket_feats(GraphView gv, const float 
     const int dev = placement[v];
     const int bits = ((dev >= 0 && dev < D) ? dev : 0xFFFF) | ((v - gv.node_off[b] == cur_node[b]) ? 0x10000 : 0);
     const float4 rec{feats[v * 3 + 0], feats[v * 3 + 1], feats[v * 3 + 2], __int_as_float(bits)};
-    featb[gv.pos[0][v]] = rec;
-    featb[static_cast<size_t>(gv.n_tot) + gv.pos[1][v]] = rec;
+    featb[v] = rec;
 }
 
 }  // namespace
@@ -978,7 +978,7 @@ void launch_sweep_mfma(const GraphView &gv, const ModelView &mv, const Workspace
                   ws.featb, first_sweep ? mv.blob + mv.proj.w : nullptr, mv.D, tr ? gates : nullptr,
                   tr ? keep : nullptr, tr ? keep_stride : 0};
     if (first_sweep)
-        hipLaunchKernelGGL(k_bucket_feats, dim3((gv.n_tot + 255) / 256), dim3(256), 0, s, gv, fa.node_feats,
+        hipLaunchKernelGGL(k_feature_records, dim3((gv.n_tot + 255) / 256), dim3(256), 0, s, gv, fa.node_feats,
                            fa.placement, fa.cur_node, mv.D, ws.featb);
     const dim3 grid(2 * gv.B);
 #define PL_CASE(HH, WW, LL)                                                      \
