@@ -179,7 +179,7 @@ int pl_embed_forward_ex(pl_graph_batch *g, const float *node_feats, const int32_
  *     of the index data (it allocates; call it once at set-up, with the device current that the
  *     later calls run on), else PL_ERR_STATE.  pl_weights handles are on the device from creation.
  *   - pl_embed_forward_static_bytes(g, w) is the size the call needs, about
- *     N_tot (24 H + 38) bytes; beyond the limit the call returns PL_ERR_SHAPE and launches nothing.
+ *     N_tot (24 H + 22) bytes; beyond the limit the call returns PL_ERR_SHAPE and launches nothing.
  *   - Every call on a device uses that device's one block, which keeps the last call's contents
  *     (what must read as zero is cleared by a small kernel at the start of each call): calls
  *     that overlap in time on one device race, whatever batches they use; calls on one stream,

@@ -83,9 +83,22 @@ __global__ __launch_bounds__(kThreads) void k_pool_sort(GraphView gv, const uint
         return set * G + (G == 1 ? 0 : d);
     };
     for (int k = 0; k < K; ++k) hist[k][tid] = 0;
-    for (int v = lo; v < hi; ++v) {
-        const int k = key_of(v);
-        if (k >= 0) hist[k][tid] += 1;
+    // The keys of a thread's nodes are formed sixteen at a time, all their loads in flight together;
+    // the first sixteen stay in registers for the placing pass.
+    constexpr int KB = 16;
+    int first_keys[KB];
+#pragma unroll
+    for (int u = 0; u < KB; ++u) first_keys[u] = lo + u < hi ? key_of(lo + u) : -1;
+#pragma unroll
+    for (int u = 0; u < KB; ++u)
+        if (first_keys[u] >= 0) hist[first_keys[u]][tid] += 1;
+    for (int base = lo + KB; base < hi; base += KB) {
+        int keys[KB];
+#pragma unroll
+        for (int u = 0; u < KB; ++u) keys[u] = base + u < hi ? key_of(base + u) : -1;
+#pragma unroll
+        for (int u = 0; u < KB; ++u)
+            if (keys[u] >= 0) hist[keys[u]][tid] += 1;
     }
     __syncthreads();
     if (tid < K) {                                   // exclusive prefix over the threads, per key
@@ -110,12 +123,20 @@ __global__ __launch_bounds__(kThreads) void k_pool_sort(GraphView gv, const uint
     __syncthreads();
     int32_t *kb = koff + static_cast<size_t>(b) * (kMaxKeys + 1);
     if (tid <= K) kb[tid] = total[tid];
-    for (int v = lo; v < hi; ++v) {
-        const int k = key_of(v);
-        if (k < 0) continue;
+    auto place = [&](int v, int k) {
+        if (k < 0) return;
         const int at = total[k] + hist[k][tid];
         hist[k][tid] += 1;
         klist[n0 + at] = v;
+    };
+#pragma unroll
+    for (int u = 0; u < KB; ++u) place(lo + u, first_keys[u]);
+    for (int base = lo + KB; base < hi; base += KB) {
+        int keys[KB];
+#pragma unroll
+        for (int u = 0; u < KB; ++u) keys[u] = base + u < hi ? key_of(base + u) : -1;
+#pragma unroll
+        for (int u = 0; u < KB; ++u) place(base + u, keys[u]);
     }
 }
 
