@@ -498,7 +498,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_pool_tiles(PoolParams P)
 //   * a lane adds its node's outputs to running sums; the sixteen lanes of a column are added in a
 //     fixed order when the device group changes.
 constexpr int kStreamWaves = 8;
-constexpr int kStreamOneSetGroups = 256;   // up to this many (set, graph) pairs each gets a workgroup of its own
+constexpr int kStreamGraphsPerChip = 256;  // compute units of the chip: a workgroup of the streaming kernel fills one
 constexpr int kStreamThreads = 64 * kStreamWaves;
 
 // position in a row of the i-th of the eight values that lane group g holds in k-step ks
@@ -930,7 +930,8 @@ int launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace &
     // the shapes that the streaming kernel covers take it (eight slices per set, one per wave)
     if (afrag && WS == 1 && pool_stream_supported(mv.H, mv.L, PL_WEIGHTS_BF16)) {
         PoolParams Q{gv, afrag, bias, ws.emb, ws.klist, ws.koff, ws.partial, kStreamWaves, mv.G, keep};
-        const dim3 grid(3 * gv.B <= kStreamOneSetGroups ? 3 : 1, gv.B), block(kStreamThreads);
+        // one workgroup per graph once that fills the chip; a workgroup per (set, graph) below
+        const dim3 grid(gv.B < kStreamGraphsPerChip ? 3 : 1, gv.B), block(kStreamThreads);
         if (mv.L == 2) {
             if (keep)
                 hipLaunchKernelGGL((k_pool_stream<128, 2, true>), grid, block, 0, s, Q);

@@ -203,7 +203,7 @@ def test_shapes_and_variants(D, H, L, k, group, wd):
     (8, 2, 1, [1300, 1, 2, 17, 140]),              # eight slices beside idle waves and empty sets
     (16, 2, 1, [300, 700]),                        # the largest device count: most device groups have one tile
     (1, 1, 0, [1100, 40]),                         # one layer, one device group
-    (3, 2, 0, [5] * 60 + [33] * 30),               # ninety graphs: a workgroup takes all three sets of its graph
+    (3, 2, 0, [5] * 200 + [33] * 60),              # as many graphs as compute units: a workgroup takes all three sets of its graph
     (4, 2, 1, [16, 32, 48, 15, 17, 31, 33] * 13),  # tiles that end exactly at, just before and just after a device group
 ])
 def test_pooling_on_the_widest_shape(D, L, group, sizes):
