@@ -106,6 +106,7 @@ struct pl_weights {
     float *d_sweep_bias = nullptr;
     uint16_t *d_pool_frag = nullptr;
     uint16_t *d_pool_afrag = nullptr;   // the streaming pooling kernel's fragments (null when not covered)
+    uint16_t *d_pool_bwfrag = nullptr;  // ... and those of its reverse
     float *d_pool_bias = nullptr;
     int sweep_ws = 0;               // bf16 parts per weight: 1 (bf16 weights) or 3 (fp32)
     int path = 0;                   // 0 = fastest available kernels, 1 = generic fp32 kernels
@@ -853,6 +854,13 @@ int pl_weights_create(const pl_model_cfg *cfg, const float *host_blob, size_t n_
                 pl_weights_destroy(w);
                 return rc;
             }
+            if (pool_stream_bw_supported(cfg->H, cfg->n_layers, cfg->weight_dtype)) {
+                pack_pool_stream_bw_weights(w->view, w->host_blob.data(), &frag);
+                if ((rc = upload(frag, &w->d_pool_bwfrag))) {
+                    pl_weights_destroy(w);
+                    return rc;
+                }
+            }
         }
     }
     *out = w;
@@ -877,6 +885,7 @@ int pl_weights_destroy(pl_weights *w)
     (void)hipFree(w->d_sweep_bias);
     (void)hipFree(w->d_pool_frag);
     (void)hipFree(w->d_pool_afrag);
+    (void)hipFree(w->d_pool_bwfrag);
     (void)hipFree(w->d_pool_bias);
     delete w;
     return PL_OK;
@@ -1100,7 +1109,8 @@ static int policy_gradient_impl(pl_graph_batch *g, const float *node_feats, cons
     if (!accumulate) launch_fill_zero(grad, plan_weights(w->cfg, nullptr), s);
     ForwardArgs fa{node_feats, placement, cur_node, out_logits, nullptr, g->gw.pooled};
     const StageMarks marks{&g->timer, stage_mark};
-    const BackwardArgs ba{actions, coeff, entropy_coeff, grad, out_logp, out_entropy, g->gw.snap_emb, g->gw.snap_msg};
+    const BackwardArgs ba{actions, coeff, entropy_coeff, grad, out_logp, out_entropy, g->gw.snap_emb, g->gw.snap_msg,
+                          w->path == 0 ? reinterpret_cast<const uint4 *>(w->d_pool_bwfrag) : nullptr};
     launch_backward(g->view, mv, w->d_blob_t, g->ws, g->gw, fa, ba, w->cfg.k_sweeps, g->ws.n_chunks, w->path,
                     chain_cores ? reinterpret_cast<const uint4 *>(w->d_wfrag_bw) : nullptr, w->d_sweep_bias,
                     w->sweep_ws, keep, pool_kept, &marks, s);

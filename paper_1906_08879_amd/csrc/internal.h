@@ -189,6 +189,13 @@ void pack_pool_weights(const ModelView &mv, const float *blob, int WS, std::vect
 // fragments of the streaming pooling kernel (weights as A operands); bf16 weights at H = 128
 bool pool_stream_supported(int H, int L, int weight_dtype);
 void pack_pool_stream_weights(const ModelView &mv, const float *blob, std::vector<uint16_t> *frag);
+// the reverse of the streaming pooling kernel (two-layer l): deltas of l's layers and d e of every
+// pooled node from the kept layer outputs; reads the sort (ws.klist, ws.koff) of the forward pass
+bool pool_stream_bw_supported(int H, int L, int weight_dtype);
+void pack_pool_stream_bw_weights(const ModelView &mv, const float *blob, std::vector<uint16_t> *frag);
+void launch_pool_stream_bw(const GraphView &gv, const ModelView &mv, const Workspace &ws, const int32_t *placement,
+                           const uint4 *frag, const float *lact, const float *dP, const uint8_t *cls, float *dl,
+                           float *demb, hipStream_t s);
 // returns the number of slices per graph that ws.partial holds afterwards
 int launch_pool_mfma(const GraphView &gv, const ModelView &mv, const Workspace &ws,
                      const ForwardArgs &fa, const uint4 *wfrag, const uint4 *afrag, const float *bias, int WS,
@@ -244,6 +251,8 @@ struct BackwardArgs {
     // states [k - 1][n_tot, 2H] and messages [k - 1][2, n_tot, H] after every sweep but the last
     const float *snap_emb;
     const float *snap_msg;
+    // fragments of the reverse streaming pooling kernel, or null (then the dense-layer kernels do it)
+    const uint4 *pool_bw_frag = nullptr;
 };
 
 void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob_t, const Workspace &ws,

@@ -1713,6 +1713,12 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
                               cnt, n, l == 0 ? 2 * H : H, blob_t + ln.layer[l].w, l == 0 ? 2 * H : H,
                               mv.blob + ln.layer[l].b, 1, nullptr, 0, gw.lact + static_cast<size_t>(l) * NH, H}, H, s);
         }
+        // Where the forward pooling kernel kept l's layer outputs and its reverse is built, one pass
+        // over the same tiles gives the deltas of l's layers and d e; else the dense-layer kernels.
+        const bool stream_bw = pool_kept && ba.pool_bw_frag != nullptr;
+        if (stream_bw) {
+            launch_pool_stream_bw(gv, mv, ws, fa.placement, ba.pool_bw_frag, gw.lact, gw.dP, gw.cls, gw.dl, gw.demb, s);
+        } else {
         hipLaunchKernelGGL(k_bw_pool_seed, dim3(static_cast<unsigned>((NH / 4 + kThreads - 1) / kThreads)),
                            dim3(kThreads), 0, s, gv, H, G, mv.D, gw.cls, fa.placement, gw.dP,
                            gw.lact + static_cast<size_t>(L - 1) * NH, gw.dl + static_cast<size_t>(L - 1) * NH);
@@ -1740,6 +1746,7 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
                 c.w_stride = w_stride;
                 launch_dense(c, H, s);
             }
+        }
         }
     } else {
         const size_t lds = sizeof(float) * kTile * 4 * H;

@@ -830,6 +830,251 @@ __global__ __launch_bounds__(kStreamThreads, 1) void k_pool_stream(PoolParams P)
     }   // sets
 }
 
+// ---- k_pool_stream_bw: the reverse of k_pool_stream for two-layer l networks, one pass over the
+// tiles that the forward pass pooled (same sort, same slices):
+//   delta2 = dP[set][device] gated by l's output, delta1 = (W2 delta2) gated by the first layer's
+//   output, d e = W1 delta1,
+// with the products taken transposed as in the forward kernel: the weights (as stored: row i of a
+// layer holds the outputs fed by input i) are the A operands in LDS, a tile's sixteen nodes the
+// columns of the B operand, deltas split exactly into three bf16 parts, the result of the first
+// product chained into the second in registers.  Both deltas are also written out for the weight
+// gradients.  Nodes that were pooled nowhere (device id out of range) are not visited:
+// k_zero_unpooled clears their rows.
+struct PoolBwParams {
+    GraphView gv;
+    const uint4 *wfrag;        // see pack_pool_stream_bw_weights
+    const float *keep;         // [2][n_tot, H] outputs of l's layers (written by the forward pooling kernel)
+    const float *dP;           // [B, 3, G, H] gradient of the pooled sums
+    const int32_t *klist;
+    const int32_t *koff;
+    float *dl;                 // [2][n_tot, H] deltas of l's layers
+    float *demb;               // [n_tot, 2H]
+    int max_slices;
+    int G;
+};
+
+template <int H>
+__global__ __launch_bounds__(kStreamThreads, 1) void k_pool_stream_bw(PoolBwParams P)
+{
+    constexpr int K1 = 2 * H;
+    constexpr int KS = H / 32, MT2 = H / 16, MT1 = K1 / 16;   // both products contract over H
+    constexpr int MG = 4;
+    constexpr int kFrags = MT2 * KS + MT1 * KS;
+    static_assert(MT2 % MG == 0 && MT1 % MG == 0 && KS == 4, "shape");
+
+    __shared__ uint4 wlds[kFrags * 64];               // A fragments: W2 [mt][ks], then W1 [mt][ks]
+    __shared__ __attribute__((aligned(16))) float dplds[kMaxD * H];   // dP of this (graph, set)
+    __shared__ int kofs[kMaxD + 1];
+
+    const int b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    const GraphView &gv = P.gv;
+    const int g0 = gv.node_off[b], g_n = gv.node_off[b + 1] - g0;
+    const int G = P.G;
+    const size_t NH = static_cast<size_t>(gv.n_tot) * H;
+    int slices = (g_n + kPoolChunk - 1) / kPoolChunk;
+    if (slices > P.max_slices) slices = P.max_slices;
+    for (int set = blockIdx.x; set < 3; set += gridDim.x) {
+    if (set != static_cast<int>(blockIdx.x)) __syncthreads();
+    const int32_t *kb = P.koff + static_cast<size_t>(b) * (kMaxKeys + 1) + set * G;
+    int n_tiles = 0;
+    for (int d = 0; d < G; ++d) n_tiles += (kb[d + 1] - kb[d] + kBatch - 1) / kBatch;
+    if (tid <= G) kofs[tid] = kb[tid];
+    constexpr int kWPer = kFrags * 64 / kStreamThreads;
+    static_assert(kFrags * 64 % kStreamThreads == 0, "fragments must divide over the threads");
+    {
+        uint4 wtmp[kWPer];
+        const uint4 *src = P.wfrag + static_cast<size_t>(set) * kFrags * 64;
+#pragma unroll
+        for (int k = 0; k < kWPer; ++k) wtmp[k] = src[tid + k * kStreamThreads];
+#pragma unroll
+        for (int k = 0; k < kWPer; ++k) wlds[tid + k * kStreamThreads] = wtmp[k];
+    }
+    for (int i = tid; i < G * H; i += kStreamThreads)
+        dplds[i] = P.dP[((static_cast<size_t>(b) * 3 + set) * G) * H + i];
+    __syncthreads();
+    if (wave >= slices) continue;
+    const int t_lo = static_cast<int>(static_cast<long long>(n_tiles) * wave / slices);
+    const int t_hi = static_cast<int>(static_cast<long long>(n_tiles) * (wave + 1) / slices);
+    if (t_lo >= t_hi) continue;
+
+    auto kof = [&](int d) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(kofs[d]); };
+    int w_dev = 0, w_pos = 0, w_left = 0;
+    {
+        int before = 0;
+        for (;; ++w_dev) {
+            const int tiles = (kof(w_dev + 1) - kof(w_dev) + kBatch - 1) / kBatch;
+            if (t_lo < before + tiles) break;
+            before += tiles;
+        }
+        w_pos = kof(w_dev) + (t_lo - before) * kBatch;
+        w_left = kof(w_dev + 1) - w_pos;
+    }
+    auto tile_next = [&](int &cnt, int &dev) __attribute__((always_inline)) {
+        cnt = min(kBatch, w_left);
+        dev = w_dev;
+        const int id = P.klist[g0 + w_pos + (n < cnt ? n : 0)];
+        w_pos += kBatch;
+        w_left -= kBatch;
+        while (w_left <= 0 && w_dev + 1 < G) {
+            ++w_dev;
+            w_pos = kof(w_dev);
+            w_left = kof(w_dev + 1) - w_pos;
+        }
+        return id;
+    };
+    auto split8 = [&](const float (&x)[8], bf16x8 (&part)[3]) __attribute__((always_inline)) {
+        uint32_t w[3][4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float a0 = x[2 * q], a1 = x[2 * q + 1];
+            const float r0 = a0 - trunc_bf16(a0), r1 = a1 - trunc_bf16(a1);
+            const float l0 = r0 - trunc_bf16(r0), l1 = r1 - trunc_bf16(r1);
+            w[0][q] = pack_hi16(a0, a1);
+            w[1][q] = pack_hi16(r0, r1);
+            w[2][q] = pack_hi16(l0, l1);
+        }
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const uint4 v{w[p][0], w[p][1], w[p][2], w[p][3]};
+            part[p] = *reinterpret_cast<const bf16x8 *>(&v);
+        }
+    };
+    // groups of MG row tiles of the result, numbered through both products: q < NG2: W2, k-step
+    // q / GP2; then W1, k-step (q - NG2) / GP1
+    constexpr int GP2 = MT2 / MG, GP1 = MT1 / MG, NG2 = KS * GP2, NG = NG2 + KS * GP1;
+    auto read_group = [&](int q, bf16x8 (&a)[MG]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int m = 0; m < MG; ++m) {
+            const int f = q < NG2 ? (MG * (q % GP2) + m) * KS + q / GP2
+                                  : MT2 * KS + (MG * ((q - NG2) % GP1) + m) * KS + (q - NG2) / GP1;
+            const uint4 v = wlds[f * 64 + lane];
+            a[m] = *reinterpret_cast<const bf16x8 *>(&v);
+        }
+    };
+    // the eight gate values (layer outputs) of this lane for k-step ks of a row of `base`
+    auto load_step = [&](const float *base, int node, int ks, f32x4 (&x)[2]) __attribute__((always_inline)) {
+        const float *row = base + static_cast<size_t>(node) * H + 32 * ks + 4 * g;
+        x[0] = *reinterpret_cast<const f32x4 *>(row);
+        x[1] = *reinterpret_cast<const f32x4 *>(row + 16);
+    };
+
+    const float *keep1 = P.keep, *keep2 = P.keep + NH;
+    float *dl1 = P.dl, *dl2 = P.dl + NH;
+    f32x4 y2[KS][2];           // l's outputs of the tile in flight (gates of delta2), one tile ahead
+    int cnt = 0, dev = 0, cnt_next = 0, dev_next = 0, cnt_after = 0, dev_after = 0;
+    int node = tile_next(cnt, dev);
+    int node_next = node, node_after = node;
+    if (t_lo + 1 < t_hi) node_next = tile_next(cnt_next, dev_next);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) load_step(keep2, node, ks, y2[ks]);
+    bf16x8 afr[2][MG];
+    read_group(0, afr[0]);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the loop's waits are counted from its own loads
+
+    for (int t = t_lo; t < t_hi; ++t) {
+        const bool more = t + 1 < t_hi;
+        const bool live = n < cnt;
+        if (t + 2 < t_hi) node_after = tile_next(cnt_after, dev_after);
+        // the first layer's outputs of this tile (gates of delta1): needed after the first product
+        f32x4 y1[MT2];
+#pragma unroll
+        for (int mt = 0; mt < MT2; ++mt)
+            y1[mt] = *reinterpret_cast<const f32x4 *>(keep1 + static_cast<size_t>(node) * H + 16 * mt + 4 * g);
+        // ---- delta2 and the product with W2
+        f32x4 acc1[MT2];
+#pragma unroll
+        for (int mt = 0; mt < MT2; ++mt) acc1[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            float d2[8];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const f32x4 dp = *reinterpret_cast<const f32x4 *>(&dplds[dev * H + 32 * ks + 16 * h + 4 * g]);
+                f32x4 dv;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) dv[j] = d2[4 * h + j] = y2[ks][h][j] > 0.0f ? dp[j] : 0.0f;
+                if (live) *reinterpret_cast<f32x4 *>(dl2 + static_cast<size_t>(node) * H + 32 * ks + 16 * h + 4 * g) = dv;
+            }
+            // the same rows once more after the slice's last tile: every path issues the same loads
+            load_step(keep2, more ? node_next : node, ks, y2[ks]);
+            bf16x8 part[3];
+            split8(d2, part);
+#pragma unroll
+            for (int gq = 0; gq < GP2; ++gq) {
+                const int q = ks * GP2 + gq;
+                read_group(q + 1, afr[(q + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(6);
+#pragma unroll
+                for (int p = 0; p < 3; ++p)
+#pragma unroll
+                    for (int m = 0; m < MG; ++m)
+                        acc1[MG * gq + m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[q & 1][m], part[p], acc1[MG * gq + m], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(6);
+            }
+        }
+        // ---- delta1 (gated), and the product with W1
+        f32x4 acc0[MT1];
+#pragma unroll
+        for (int mt = 0; mt < MT1; ++mt) acc0[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            float d1[8];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int mt = 2 * ks + h;
+                f32x4 dv;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) dv[j] = d1[4 * h + j] = y1[mt][j] > 0.0f ? acc1[mt][j] : 0.0f;
+                if (live) *reinterpret_cast<f32x4 *>(dl1 + static_cast<size_t>(node) * H + 16 * mt + 4 * g) = dv;
+            }
+            bf16x8 part[3];
+            split8(d1, part);
+#pragma unroll
+            for (int gq = 0; gq < GP1; ++gq) {
+                const int q = NG2 + ks * GP1 + gq;
+                read_group((q + 1) % NG, afr[(q + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(6);
+#pragma unroll
+                for (int p = 0; p < 3; ++p)
+#pragma unroll
+                    for (int m = 0; m < MG; ++m)
+                        acc0[MG * gq + m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[q & 1][m], part[p], acc0[MG * gq + m], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(6);
+            }
+        }
+        if (live) {
+#pragma unroll
+            for (int mt = 0; mt < MT1; ++mt)
+                *reinterpret_cast<f32x4 *>(P.demb + static_cast<size_t>(node) * K1 + 16 * mt + 4 * g) = acc0[mt];
+        }
+        node = node_next;
+        cnt = cnt_next;
+        dev = dev_next;
+        node_next = node_after;
+        cnt_next = cnt_after;
+        dev_next = dev_after;
+    }
+    }   // sets
+}
+
+// Rows of the deltas of l and of d e for nodes that belong to a set but were pooled nowhere (device
+// id out of range): zero.
+__global__ __launch_bounds__(kThreads) void k_zero_unpooled(int n_tot, int H, int L, int D, const uint8_t *__restrict__ cls,
+                                                            const int32_t *__restrict__ placement,
+                                                            float *__restrict__ dl, float *__restrict__ demb)
+{
+    const int v = blockIdx.x * kThreads + threadIdx.x;
+    if (v >= n_tot || cls[v] == 0) return;
+    const int dev = placement[v];
+    if (dev >= 0 && dev < D) return;
+    for (int l = 0; l < L; ++l)
+        for (int i = 0; i < H; ++i) dl[(static_cast<size_t>(l) * n_tot + v) * H + i] = 0.0f;
+    for (int i = 0; i < 2 * H; ++i) demb[static_cast<size_t>(v) * 2 * H + i] = 0.0f;
+}
+
 // Appends the MFMA B-operand fragments of one layer: index ((nt * KS + ks) * WS + ws) * 64 + lane,
 // lane l holds W[32 ks + 8 (l / 16) + i][16 nt + l % 16], i = 0..7, as bf16 part ws of the exact
 // three-way split of the weight (ws = 0 only when the weights are bf16 already).
@@ -906,6 +1151,49 @@ void pack_pool_stream_weights(const ModelView &mv, const float *blob, std::vecto
                             frag->push_back(to_bf16(blob[lr.w + static_cast<size_t>(k) * lr.n_out + m]));
                         }
         }
+}
+
+// A fragments of the reverse streaming kernel (two-layer l): per set, W2 [mt][ks] then W1 [mt][ks];
+// lane l holds W[16 mt + l % 16][stream_k(ks, l / 16, i)], i = 0..7: row = the layer's input index,
+// the contraction runs over its outputs.
+void pack_pool_stream_bw_weights(const ModelView &mv, const float *blob, std::vector<uint16_t> *frag)
+{
+    frag->clear();
+    auto to_bf16 = [](float x) {
+        uint32_t u;
+        std::memcpy(&u, &x, 4);
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        return static_cast<uint16_t>(u >> 16);
+    };
+    for (int set = 0; set < 3; ++set)
+        for (int l = mv.L - 1; l >= 0; --l) {
+            const LayerRef &lr = mv.l[set].layer[l];
+            const int MT = lr.n_in / 16, KS = lr.n_out / 32;
+            for (int mt = 0; mt < MT; ++mt)
+                for (int ks = 0; ks < KS; ++ks)
+                    for (int lane = 0; lane < 64; ++lane)
+                        for (int i = 0; i < 8; ++i) {
+                            const int k = stream_k(ks, lane / 16, i), m = 16 * mt + lane % 16;
+                            frag->push_back(to_bf16(blob[lr.w + static_cast<size_t>(m) * lr.n_out + k]));
+                        }
+        }
+}
+
+bool pool_stream_bw_supported(int H, int L, int weight_dtype)
+{
+    return weight_dtype == PL_WEIGHTS_BF16 && H == 128 && L == 2;
+}
+
+void launch_pool_stream_bw(const GraphView &gv, const ModelView &mv, const Workspace &ws, const int32_t *placement,
+                           const uint4 *frag, const float *lact, const float *dP, const uint8_t *cls, float *dl,
+                           float *demb, hipStream_t s)
+{
+    if (gv.B == 0) return;
+    hipLaunchKernelGGL(k_zero_unpooled, dim3((gv.n_tot + kThreads - 1) / kThreads), dim3(kThreads), 0, s, gv.n_tot, mv.H,
+                       mv.L, mv.D, cls, placement, dl, demb);
+    PoolBwParams P{gv, frag, lact, dP, ws.klist, ws.koff, dl, demb, kStreamWaves, mv.G};
+    const dim3 grid(gv.B < kStreamGraphsPerChip ? 3 : 1, gv.B), block(kStreamThreads);
+    hipLaunchKernelGGL((k_pool_stream_bw<128>), grid, block, 0, s, P);
 }
 
 bool pool_stream_supported(int H, int L, int weight_dtype)

@@ -168,6 +168,29 @@ def test_accumulation_linearity_and_rejected_states():
     assert np.isnan(got["logp"][1]) and np.isnan(got["logp"][2]) and np.isfinite(got["logp"][[0, 3]]).all()
 
 
+def test_nodes_with_a_device_out_of_range_get_no_gradient_on_either_path():
+    """A node whose device id is outside [0, D) is pooled nowhere, so the reverse pooling must leave
+    its rows zero.  The autograd oracle has no such input; the generic kernels and the matrix-core
+    kernels (whose reverse pooling walks the forward pass's tiles and never sees such a node) are
+    two implementations of the same rule and must agree to the gradient bar."""
+    rng = np.random.default_rng(77)
+    w = custom_workload(rng, [40, 70, 17, 33], 8, 128, 2, 1, 1, "bf16")
+    bad = np.array(w.placement, copy=True)
+    for b in range(w.B):
+        lo, hi = int(w.node_off[b]), int(w.node_off[b + 1])
+        pick = [v for v in range(lo, hi) if v - lo != int(w.cur_node[b])][:3]
+        bad[pick[0]] = w.D
+        bad[pick[1]] = -1
+    w.placement = bad
+    actions = rng.integers(0, w.D, w.B).astype(np.int32)
+    coeff = rng.normal(0, 1, w.B).astype(np.float32)
+    fast = run_gradient(w, actions, coeff, path=0)
+    slow = run_gradient(w, actions, coeff, path=1)
+    assert np.isfinite(fast["grad"]).all() and np.isfinite(slow["grad"]).all()
+    worst = assert_grad_close(fast["grad"], slow["grad"].astype(np.float64), w, "device out of range")
+    print(f"[gradient] device out of range: matrix-core vs generic, worst error / bound = {worst:.3g}", flush=True)
+
+
 @pytest.mark.parametrize("case", ["generic", "matrix-core", "nmt"])
 def test_entropy_term(case):
     """Appendix A.7 "Entropy": the loss also carries beta * H(pi); gradient and entropies against the
