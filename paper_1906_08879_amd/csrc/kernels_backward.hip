@@ -36,7 +36,7 @@ constexpr int kPoolSub = 256;  // nodes classified at a time
 
 // y[r][j] = bias[j] + sum_k x[r][k] * W[k * ldw + j] for r < rows (<= kTile), j < n_out, optional
 // ReLU.  x and y in LDS.  Thread (grp, j) owns rows grp, grp + groups, ...  Requires
-// n_out <= kThreads and min(kThreads / n_out, kTile) * RPT >= kTile.  bias may be null.
+// n_out <= kThreads and min(kThreads / n_out, kTile) * RPT >= rows.  bias may be null.
 template <int RPT>
 __device__ __forceinline__ void dense_rows(const float *__restrict__ W, int ldw,
                                            const float *__restrict__ bias, int n_in, int n_out,
@@ -1690,7 +1690,13 @@ void launch_backward(const GraphView &gv, const ModelView &mv, const float *blob
     allow_lds_bw(k_bw_head_sets<R>, lds);                                                                \
     hipLaunchKernelGGL(k_bw_head_sets<R>, dim3(3, B), dim3(kThreads), lds, s, gv, mv, blob_t, gw.pooled, \
                        gw.dz, gw.hin, gw.hact, gw.dh, gw.dP)
-        PL_DISPATCH_RPT(rpt, CALL)
+        // h_i works on the G rows of a set: as many rows per thread as that needs
+        int groups = kThreads / H;
+        if (groups > kTile) groups = kTile;
+        if (groups < 1) groups = 1;
+        int rpt_sets = 1;
+        while (groups * rpt_sets < G) rpt_sets *= 2;
+        PL_DISPATCH_RPT(rpt_sets, CALL)
 #undef CALL
     }
     mark(PL_STAGE_BW_HEAD, false);
