@@ -40,6 +40,7 @@ def path_algorithmic_bytes(n_tot: int, e_tot: int, H: int) -> int:
 
 SWEEP_SOURCES = ("kernels_mfma.hip", "plan.cpp", "sweep_plan.h")
 WGRAD_SOURCES = ("kernels_backward.hip",)
+POOL_SOURCES = ("kernels_pool_mfma.hip",)
 
 
 def csrc_digest(sources=SWEEP_SOURCES) -> str:
@@ -211,6 +212,17 @@ def main() -> int:
                 # what actually bounds the sweep: one dependent step per level of the deepest graph
                 "levels": int(g.max_depth),
                 "us_per_level": round(1e3 * avg_launch_ms / max(1, int(g.max_depth)), 4)}
+
+    # the second stage, pooling: one read of every node's [td ; bu] (8H bytes) and its flags
+    pool_alg = int(w.n_tot) * (8 * w.H + 6)
+    pool_ms = stage_ms.get("pool", 0.0)
+    pool_roofline = {"kernel": "pooling (sort by set and device + l_i of every node, summed per key)",
+                     "bound": "hbm", "achieved": round(pool_alg / (pool_ms * 1e-3) / 1e9, 2) if pool_ms > 0 else 0.0,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(pool_alg / (pool_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 5) if pool_ms > 0 else 0.0,
+                     "traffic": (measured_traffic(args.workload, int(w.B), "pool_traffic_bytes_per_launch", "pool_sha256", POOL_SOURCES)
+                                 if default_variant else None),
+                     "algorithmic_bytes_per_launch": pool_alg, "avg_stage_ms": round(pool_ms, 5)}
 
     # a plain device copy of 1 GiB on the same GPU: what the published peak means in practice here
     cp_a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -419,6 +431,7 @@ def main() -> int:
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
         "layout_build_ms": round(layout_build_ms, 2),
         "roofline": roofline,
+        "pool_roofline": pool_roofline,
         "other_workloads": other,
         "replicated_batch": replicated,
         "episode": episode,
