@@ -780,9 +780,12 @@ __global__ __launch_bounds__(64 * sweep_waves(H), 2) void k_sweep_mfma(SweepPara
                             }
                     }
                 }
-                if (n == (NL > 2 ? 1 : 0)) {
-                    // second layer: the records of chunk c + 3 and
-                    // the inputs of chunk c + 1
+                // The records of chunk c + 3 and the inputs of chunk c + 1: behind the second layer's
+                // matrix instructions; in the reverse pass behind the first layer's, ahead of that
+                // layer's stores: loads and stores retire in order, the reverse pass stores six times
+                // per row and chunk, and a load queued behind a layer's stores returned too late for
+                // the next chunk (2.35 -> 2.22 ms; no change for the forward sweeps).
+                if (n == ((NL > 2 && !BW) ? 1 : 0)) {
                     const bool two1 = kLoadTile1Always || rows1 > kTileNodes;
 #pragma unroll
                     for (int ct = 0; ct < NT; ++ct) {
